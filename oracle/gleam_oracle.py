@@ -1,0 +1,262 @@
+"""CPU oracle for one GLEAM module step of an unrolled PGD network.  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import this file; the
+product (the HIP library and its binding) never does, and this file imports nothing of the
+product.  Everything is float64 / complex128 numpy, written as the plain definitions:
+
+  * F        : orthonormal, uncentred DFT applied as an explicit n x n matrix product per axis
+               (direct O(n^2) definition; `F` of the sensing model, Eq. 1)
+  * A        : A = Omega F S and its Hermitian transpose A^H = S^H F^H Omega (Eq. 1, Eq. 2, PGD section)
+  * DC       : u = x - alpha A^H (A x - y), alpha = 2t   (data-consistency step of PGD, Eq. 3, read with
+               the same iterate on both sides)
+  * prox     : learned proximal CNN f_theta (Eq. 4-5): cross-correlation, zero "same" padding,
+               stride 1, ReLU, residual skips; one tap at a time with a matmul over input channels
+  * loss     : local greedy objective L(f_theta(DC(x_in)), x_ref) (Eq. 10), mean squared or mean
+               absolute complex error
+  * backward : analytic reverse sweep for dL/dtheta of this module only (Alg. 1, gradient step);
+               nothing is propagated to x_in, S or y (decoupled modules).
+
+Pins (tests/test_oracle_*.py): numpy.fft and closed forms for the DFT, the adjoint identity, the
+full-sampling identity A^H A = I, circular-convolution form of a single-coil 1D mask, scipy
+correlate and torch CPU convolutions for the prox, central finite differences and torch autograd
+for the gradient.  No function here is unpinned.
+
+Array layouts: image [B,T,D,H,W], coils [B,C,D,H,W], mask [B,T,D,H,W], k-space [B,C,T,D,H,W],
+activations [B,T,D,H,W,channels] (an image is its own 2-channel activation: re, im).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------- Fourier
+def dft_matrix(n: int, inverse: bool = False) -> np.ndarray:
+    """F[q, j] = n^(-1/2) exp(-+ 2 pi i ((j q) mod n) / n)."""
+    j = np.arange(n, dtype=np.int64)
+    jq = np.outer(j, j) % n
+    sign = 1.0 if inverse else -1.0
+    return np.exp(sign * 2j * np.pi * jq / n) / np.sqrt(n)
+
+
+def dft_axis(a: np.ndarray, axis: int, inverse: bool = False) -> np.ndarray:
+    """X[..., q, ...] = sum_j F[q, j] a[..., j, ...] along one axis."""
+    F = dft_matrix(a.shape[axis], inverse)
+    moved = np.moveaxis(np.asarray(a, np.complex128), axis, -1)
+    return np.moveaxis(moved @ F.T, -1, axis)
+
+
+def dft_nd(a: np.ndarray, ndim_fft: int, inverse: bool = False) -> np.ndarray:
+    """Separable DFT over the last `ndim_fft` axes."""
+    out = np.asarray(a, np.complex128)
+    for ax in range(a.ndim - ndim_fft, a.ndim):
+        out = dft_axis(out, ax, inverse)
+    return out
+
+
+# ----------------------------------------------------------------------------- SENSE operator
+def sense_forward(x, S, M, ndim_fft):
+    """A x = Omega F S x  ->  k-space [B,C,T,D,H,W]."""
+    x = np.asarray(x, np.complex128)
+    S = np.asarray(S, np.complex128)
+    c = S[:, :, None] * x[:, None]
+    k = dft_nd(c, ndim_fft)
+    return np.where((np.asarray(M) != 0)[:, None], k, 0.0)
+
+
+def sense_adjoint(k, S, M, ndim_fft):
+    """A^H k = S^H F^H Omega k  ->  image [B,T,D,H,W]."""
+    S = np.asarray(S, np.complex128)
+    r = np.where((np.asarray(M) != 0)[:, None], np.asarray(k, np.complex128), 0.0)
+    rt = dft_nd(r, ndim_fft, inverse=True)
+    return (np.conj(S)[:, :, None] * rt).sum(axis=1)
+
+
+def sense_normal(x, S, M, ndim_fft):
+    """A^H A x."""
+    return sense_adjoint(sense_forward(x, S, M, ndim_fft), S, M, ndim_fft)
+
+
+def masked_residual(x, S, M, y, ndim_fft):
+    """r = Omega (F S x - y): exactly zero off the mask, whatever y holds there."""
+    x = np.asarray(x, np.complex128)
+    S = np.asarray(S, np.complex128)
+    k = dft_nd(S[:, :, None] * x[:, None], ndim_fft)
+    return np.where((np.asarray(M) != 0)[:, None], k - np.asarray(y, np.complex128), 0.0)
+
+
+def dc_step(x, S, M, y, alpha, ndim_fft):
+    """u = x - alpha A^H (A x - y)."""
+    r = masked_residual(x, S, M, y, ndim_fft)
+    g = sense_adjoint(r, S, np.ones_like(np.asarray(M)), ndim_fft)
+    return np.asarray(x, np.complex128) - alpha * g
+
+
+# ----------------------------------------------------------------------------- convolutions
+def _pad(a, k):
+    """Zero 'same' padding of [B,T,D,H,W,ch] for odd kernel extents k = (kt,kd,kh,kw)."""
+    pads = [(0, 0)] + [(e // 2, e // 2) for e in k] + [(0, 0)]
+    return np.pad(a, pads)
+
+
+def conv_fwd(a, w, b=None):
+    """out[.., p, co] = b[co] + sum_{tap, ci} w[co, tap, ci] a[.., p + tap - floor(k/2), ci],
+    zero outside the grid.  a [B,T,D,H,W,cin], w [cout,kt,kd,kh,kw,cin]."""
+    a = np.asarray(a, np.float64)
+    w = np.asarray(w, np.float64)
+    B, T, D, H, W, _ = a.shape
+    k = w.shape[1:5]
+    ap = _pad(a, k)
+    out = np.zeros((B, T, D, H, W, w.shape[0]))
+    for it in range(k[0]):
+        for i_d in range(k[1]):
+            for ih in range(k[2]):
+                for iw in range(k[3]):
+                    out += ap[:, it:it + T, i_d:i_d + D, ih:ih + H, iw:iw + W, :] @ w[:, it, i_d, ih, iw, :].T
+    if b is not None:
+        out += np.asarray(b, np.float64)
+    return out
+
+
+def conv_dgrad(g, w):
+    """g_in[.., p, ci] = sum_{tap, co} w[co, tap, ci] g[.., p - (tap - floor(k/2)), co]
+    (transpose of conv_fwd with respect to its input)."""
+    g = np.asarray(g, np.float64)
+    w = np.asarray(w, np.float64)
+    B, T, D, H, W, _ = g.shape
+    k = w.shape[1:5]
+    gp = _pad(g, k)
+    out = np.zeros((B, T, D, H, W, w.shape[5]))
+    for it in range(k[0]):
+        for i_d in range(k[1]):
+            for ih in range(k[2]):
+                for iw in range(k[3]):
+                    st, sd, sh, sw = k[0] - 1 - it, k[1] - 1 - i_d, k[2] - 1 - ih, k[3] - 1 - iw
+                    out += gp[:, st:st + T, sd:sd + D, sh:sh + H, sw:sw + W, :] @ w[:, it, i_d, ih, iw, :]
+    return out
+
+
+def conv_wgrad(g, a, k):
+    """dw[co, tap, ci] = sum_{b, p} g[b, p, co] a[b, p + tap - floor(k/2), ci];  db[co] = sum g."""
+    g = np.asarray(g, np.float64)
+    a = np.asarray(a, np.float64)
+    B, T, D, H, W, cout = g.shape
+    cin = a.shape[-1]
+    ap = _pad(a, k)
+    dw = np.zeros((cout,) + tuple(k) + (cin,))
+    g2 = g.reshape(-1, cout)
+    for it in range(k[0]):
+        for i_d in range(k[1]):
+            for ih in range(k[2]):
+                for iw in range(k[3]):
+                    sl = ap[:, it:it + T, i_d:i_d + D, ih:ih + H, iw:iw + W, :].reshape(-1, cin)
+                    dw[:, it, i_d, ih, iw, :] = g2.T @ sl
+    return dw, g2.sum(axis=0)
+
+
+# ----------------------------------------------------------------------------- prox network
+def split_theta(layers, theta):
+    """Views (w, b) per layer out of the flat parameter vector: per layer
+    w[cout][kt][kd][kh][kw][cin] then b[cout] when the layer has a bias."""
+    theta = np.asarray(theta, np.float64)
+    out, o = [], 0
+    for l in layers:
+        nw = l.cout * l.kt * l.kd * l.kh * l.kw * l.cin
+        w = theta[o:o + nw].reshape(l.cout, l.kt, l.kd, l.kh, l.kw, l.cin)
+        o += nw
+        b = None
+        if l.has_bias:
+            b = theta[o:o + l.cout]
+            o += l.cout
+        out.append((w, b))
+    assert o == theta.size, "theta length does not match the prox description"
+    return out
+
+
+def complex_to_channels(x):
+    x = np.asarray(x, np.complex128)
+    return np.stack([x.real, x.imag], axis=-1)
+
+
+def channels_to_complex(a):
+    return a[..., 0] + 1j * a[..., 1]
+
+
+def prox_fwd(layers, theta, u):
+    """Tensors t_0 = u (2 channels) ... t_L = z, and per layer the conv input and the value
+    before the skip add (needed for the ReLU derivatives)."""
+    params = split_theta(layers, theta)
+    t = [complex_to_channels(u)]
+    conv_in, act = [], []
+    for l, (w, b) in zip(layers, params):
+        a = t[-1]
+        if l.relu_in:
+            a = np.maximum(a, 0.0)
+        v = conv_fwd(a, w, b)
+        if l.relu_out:
+            v = np.maximum(v, 0.0)
+        conv_in.append(a)
+        act.append(v)
+        t.append(v + t[l.skip_src] if l.skip_src >= 0 else v)
+    return t, conv_in, act
+
+
+def loss_and_grad(z, x_ref, loss_kind):
+    """L and dL/dz (as 2 real channels).  kind 0: mean |z-x|^2;  kind 1: mean |z-x| with the
+    complex magnitude, sub-gradient 0 where z == x."""
+    d = np.asarray(z, np.complex128) - np.asarray(x_ref, np.complex128)
+    n = d.size
+    if loss_kind == 0:
+        return float((np.abs(d) ** 2).sum() / n), complex_to_channels(2.0 * d / n)
+    mag = np.abs(d)
+    safe = np.where(mag > 0, mag, 1.0)
+    return float(mag.sum() / n), complex_to_channels(np.where(mag > 0, d / safe, 0.0) / n)
+
+
+def prox_bwd(layers, theta, t, conv_in, act, g_z):
+    """dL/dtheta (flat, same layout as theta) from dL/dz.  Gradient reaching t_0 is dropped."""
+    params = split_theta(layers, theta)
+    L = len(layers)
+    G = [None] * (L + 1)
+    G[L] = g_z
+    grads = [None] * L
+    for i in range(L - 1, -1, -1):
+        l = layers[i]
+        w, b = params[i]
+        g = G[i + 1]
+        if g is None:
+            g = np.zeros_like(act[i])
+        if l.skip_src >= 0:
+            s = l.skip_src
+            G[s] = g if G[s] is None else G[s] + g
+        gc = g * (act[i] > 0) if l.relu_out else g
+        dw, db = conv_wgrad(gc, conv_in[i], (l.kt, l.kd, l.kh, l.kw))
+        grads[i] = (dw, db if l.has_bias else None)
+        if i >= 1:
+            gin = conv_dgrad(gc, w)
+            if l.relu_in:
+                gin = gin * (t[i] > 0)
+            G[i] = gin if G[i] is None else G[i] + gin
+    flat = []
+    for dw, db in grads:
+        flat.append(dw.ravel())
+        if db is not None:
+            flat.append(db.ravel())
+    return np.concatenate(flat)
+
+
+# ----------------------------------------------------------------------------- module
+def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None):
+    """x_out = f_theta(DC(x_in)); loss against x_ref when given.  Returns a dict holding
+    everything module_bwd needs."""
+    u = dc_step(x_in, S, M, y, alpha, geom.ndim_fft)
+    t, conv_in, act = prox_fwd(prox.layers, theta, u)
+    z = channels_to_complex(t[-1])
+    out = {"u": u, "x_out": z, "t": t, "conv_in": conv_in, "act": act, "loss": None, "g_z": None}
+    if x_ref is not None:
+        out["loss"], out["g_z"] = loss_and_grad(z, x_ref, prox.loss_kind)
+    return out
+
+
+def module_bwd(prox, theta, fwd):
+    """dL/dtheta_m of the local objective; stops at the module input."""
+    return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"])
