@@ -1,0 +1,123 @@
+/* gleam.h - C ABI of the MI355X (gfx950) hot path of one GLEAM module step.
+ *
+ * One module of an unrolled proximal-gradient network trained greedily (paper: Methods,
+ * "Greedy LEarning for Accelerated MRI Reconstruction", Alg. 1):
+ *
+ *     u     = x_in - alpha * A^H (A x_in - y)        data consistency, Eq. 3 (alpha = 2t)
+ *     x_out = f_theta(u)                             learned proximal CNN, Eq. 4-5
+ *     loss  = L(x_out, x_ref)                        local greedy objective, Eq. 10
+ *     grad  = d loss / d theta   (this module only)  Alg. 1, gradient step
+ *
+ * with the multi-coil forward model A = Omega F S of Eq. 1-2: coil-sensitivity multiply S, orthonormal
+ * uncentred DFT F over the last `ndim_fft` image dimensions, sampling mask Omega.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates and frees no
+ *     device memory, writes no input, and enqueues all work on the caller's stream without synchronising.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Arrays are row-major with the last dimension contiguous; complex numbers are interleaved
+ *     (re, im) float32 pairs (gleam_c64):
+ *         image   x  [B][T][D][H][W]       coils  S [B][C][D][H][W]  (shared by all T frames)
+ *         mask    M  [B][T][D][H][W] uint8 (non-zero = sampled, no coil dimension)
+ *         k-space y  [B][C][T][D][H][W]    (values off the mask are ignored)
+ *     An image is also the prox network's 2-channel real tensor (channels-last: re, im).
+ *   - theta / grad_theta: flat float32, per layer W[cout][kt][kd][kh][kw][cin] then b[cout] if has_bias.
+ *   - Return value: 0 (GLEAM_OK) or a negative gleam_status.  Arguments are validated on the host before
+ *     anything is launched; on error nothing has been enqueued.
+ *   - `ws` is scratch the call may overwrite freely; `saved` carries activations from gleam_module_fwd to
+ *     gleam_module_bwd and may be reused for the next module afterwards (activations of a finished module
+ *     are discarded, as in Alg. 1).  Both must be 256-byte aligned.  Sizes come from gleam_workspace_bytes.
+ *   - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef GLEAM_H
+#define GLEAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct { float re, im; } gleam_c64;
+
+typedef enum {
+    GLEAM_OK = 0,
+    GLEAM_E_NULL = -1,              /* a required pointer is NULL                                      */
+    GLEAM_E_DIMS = -2,              /* non-positive or inconsistent dimension, ndim_fft not 2 or 3     */
+    GLEAM_E_UNSUPPORTED_SIZE = -3,  /* a transformed length has no kernel (see gleam_fft_size_supported) */
+    GLEAM_E_WORKSPACE = -4,         /* ws / saved too small or misaligned                              */
+    GLEAM_E_DESC = -5,              /* prox description is not a valid / supported network             */
+    GLEAM_E_LAUNCH = -6             /* the HIP runtime refused a launch                                */
+} gleam_status;
+
+/* Problem geometry.  ndim_fft = 2 transforms (H, W) and batches over D; ndim_fft = 3 transforms (D, H, W).
+ * T counts temporal frames that are never transformed (2D+t cine); D = 1 and T = 1 for plain 2D. */
+typedef struct {
+    int32_t ndim_fft;
+    int64_t B, C, T, D, H, W;
+} gleam_geom;
+
+/* One convolution layer of the prox: cross-correlation, zero "same" padding, stride 1, odd extents.
+ * With t_0 = u and t_l the output of layer l (1-based):
+ *     a   = relu_in  ? max(t_{l-1}, 0) : t_{l-1}
+ *     v   = conv(a, W_l) + b_l ;  v = relu_out ? max(v, 0) : v
+ *     t_l = skip_src >= 0 ? v + t_{skip_src} : v          (skip_src < l, equal channel counts)
+ * Layer 1 has cin = 2, the last layer cout = 2, and cin of layer l equals cout of layer l-1.
+ * relu_out together with skip_src >= 0 on one layer is rejected (GLEAM_E_DESC). */
+typedef struct {
+    int32_t cin, cout, kt, kd, kh, kw;
+    int32_t relu_in, relu_out, has_bias;
+    int32_t skip_src;               /* -1: none */
+} gleam_conv;
+
+typedef struct {
+    int32_t n_layers;
+    const gleam_conv* layers;       /* host pointer, n_layers entries                                    */
+    int32_t dtype;                  /* 0: float32 convolutions; 1: bfloat16 operands, float32 accumulate */
+    int32_t loss_kind;              /* 0: mean |z-x|^2 over B*P complex pixels; 1: mean |z-x|            */
+} gleam_prox_desc;
+
+/* Bytes of scratch (`ws_bytes`, the maximum any of the three entry points needs for this geometry and
+ * prox) and of saved activations (`saved_bytes`).  prox may be NULL: then only gleam_sense_normal's
+ * scratch is counted and *saved_bytes = 0.  Host-only. */
+int gleam_workspace_bytes(const gleam_geom* geom, const gleam_prox_desc* prox,
+                          size_t* ws_bytes, size_t* saved_bytes);
+
+/* Number of float32 parameters of the prox (length of theta and grad_theta).  Host-only. */
+int gleam_theta_count(const gleam_prox_desc* prox, size_t* n_floats);
+
+/* 1 if a transform of length n has a kernel, else 0.  Host-only. */
+int gleam_fft_size_supported(int64_t n);
+
+/* out = A^H A x : the normal operator of the forward model A = Omega F S (Eq. 1-2; the operator inside
+ * the data-consistency step of Eq. 3).  x, out: image; S: coils; M: mask.  out must not alias x. */
+int gleam_sense_normal(const gleam_geom* geom, const gleam_c64* x, const gleam_c64* S, const uint8_t* M,
+                       gleam_c64* out, void* ws, size_t ws_bytes, void* stream);
+
+/* Forward pass of one module, x_out = f_theta(DC(x_in)) (Eq. 3-5; Alg. 1, forward step).
+ *   x_ref  : fully sampled reference image, or NULL for inference (then `loss` and `saved` may be NULL
+ *            and no backward pass may follow).
+ *   loss   : device float32 scalar, overwritten with L(x_out, x_ref) (Eq. 10).
+ *   x_out  : image, overwritten; must not alias x_in.  Passing it as the next module's x_in is the
+ *            detached hand-off between modules. */
+int gleam_module_fwd(const gleam_geom* geom, const gleam_prox_desc* prox,
+                     const gleam_c64* x_in, const gleam_c64* S, const uint8_t* M, const gleam_c64* y,
+                     float alpha, const float* theta, const gleam_c64* x_ref,
+                     gleam_c64* x_out, float* loss,
+                     void* saved, size_t saved_bytes, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward pass of the same module: grad_theta = d loss / d theta (Alg. 1, gradient step), overwritten.
+ * Consumes `saved` of the matching gleam_module_fwd call (same geom / prox / theta).  No gradient is
+ * produced for x_in, S or y: modules are decoupled and the data-consistency step is not differentiated. */
+int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const float* theta,
+                     const void* saved, size_t saved_bytes, float* grad_theta,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* Static message for a gleam_status value. */
+const char* gleam_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLEAM_H */

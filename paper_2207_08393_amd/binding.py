@@ -1,0 +1,154 @@
+"""Thin ctypes binding of libgleam.so: argument marshalling only.
+
+Every function has the name and argument order of its C declaration in include/gleam.h and
+forwards device pointers of torch tensors (torch is used for device memory and streams only).
+There is no CPU path: if the shared library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgleam.so")
+
+GLEAM_OK = 0
+GLEAM_E_NULL = -1
+GLEAM_E_DIMS = -2
+GLEAM_E_UNSUPPORTED_SIZE = -3
+GLEAM_E_WORKSPACE = -4
+GLEAM_E_DESC = -5
+GLEAM_E_LAUNCH = -6
+
+
+class gleam_geom(C.Structure):
+    _fields_ = [("ndim_fft", C.c_int32), ("B", C.c_int64), ("C", C.c_int64), ("T", C.c_int64),
+                ("D", C.c_int64), ("H", C.c_int64), ("W", C.c_int64)]
+
+
+class gleam_conv(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("cin", "cout", "kt", "kd", "kh", "kw", "relu_in", "relu_out",
+                                         "has_bias", "skip_src")]
+
+
+class gleam_prox_desc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(gleam_conv)), ("dtype", C.c_int32),
+                ("loss_kind", C.c_int32)]
+
+
+class GleamError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libgleam.so (built by paper_2207_08393_amd/csrc/build.sh); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run paper_2207_08393_amd/csrc/build.sh "
+                               "(or __graft_entry__.build()); there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        vp, sz = C.c_void_p, C.c_size_t
+        pg, pp = C.POINTER(gleam_geom), C.POINTER(gleam_prox_desc)
+        L.gleam_strerror.restype = C.c_char_p
+        L.gleam_strerror.argtypes = [C.c_int]
+        L.gleam_fft_size_supported.argtypes = [C.c_int64]
+        L.gleam_theta_count.argtypes = [pp, C.POINTER(sz)]
+        L.gleam_workspace_bytes.argtypes = [pg, pp, C.POINTER(sz), C.POINTER(sz)]
+        L.gleam_sense_normal.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
+        L.gleam_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.gleam_module_bwd.argtypes = [pg, pp, vp, vp, sz, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
+           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd")
+
+
+def strerror(status: int) -> str:
+    return lib().gleam_strerror(int(status)).decode()
+
+
+def make_geom(g) -> gleam_geom:
+    """From any object with ndim_fft, B, C, T, D, H, W attributes."""
+    return gleam_geom(int(g.ndim_fft), int(g.B), int(g.C), int(g.T), int(g.D), int(g.H), int(g.W))
+
+
+def make_prox(p) -> gleam_prox_desc:
+    """From any object with `layers` (cin, cout, kt, kd, kh, kw, relu_in, relu_out, has_bias, skip_src),
+    `dtype` and `loss_kind`.  The returned struct keeps its layer array alive."""
+    arr = (gleam_conv * len(p.layers))()
+    for i, l in enumerate(p.layers):
+        arr[i] = gleam_conv(l.cin, l.cout, l.kt, l.kd, l.kh, l.kw, l.relu_in, l.relu_out, l.has_bias, l.skip_src)
+    d = gleam_prox_desc(len(p.layers), C.cast(arr, C.POINTER(gleam_conv)), int(p.dtype), int(p.loss_kind))
+    d._keep = arr
+    return d
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensors passed to libgleam must be contiguous")
+    return t.data_ptr()
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _check(rc: int, where: str):
+    if rc != GLEAM_OK:
+        raise GleamError(rc, where)
+
+
+def gleam_fft_size_supported(n: int) -> bool:
+    return bool(lib().gleam_fft_size_supported(int(n)))
+
+
+def gleam_theta_count(prox: gleam_prox_desc) -> int:
+    n = C.c_size_t(0)
+    _check(lib().gleam_theta_count(C.byref(prox), C.byref(n)), "gleam_theta_count")
+    return n.value
+
+
+def gleam_workspace_bytes(geom: gleam_geom, prox: Optional[gleam_prox_desc]):
+    ws, saved = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().gleam_workspace_bytes(C.byref(geom), C.byref(prox) if prox is not None else None,
+                                       C.byref(ws), C.byref(saved)), "gleam_workspace_bytes")
+    return ws.value, saved.value
+
+
+def gleam_sense_normal(geom, x, S, M, out, ws, stream=None):
+    _check(lib().gleam_sense_normal(C.byref(geom), _ptr(x), _ptr(S), _ptr(M), _ptr(out), _ptr(ws), _nbytes(ws),
+                                    _stream(stream)), "gleam_sense_normal")
+
+
+def gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref, x_out, loss, saved, ws, stream=None):
+    _check(lib().gleam_module_fwd(C.byref(geom), C.byref(prox), _ptr(x_in), _ptr(S), _ptr(M), _ptr(y),
+                                  C.c_float(alpha), _ptr(theta), _ptr(x_ref), _ptr(x_out), _ptr(loss),
+                                  _ptr(saved), _nbytes(saved), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "gleam_module_fwd")
+
+
+def gleam_module_bwd(geom, prox, theta, saved, grad_theta, ws, stream=None):
+    _check(lib().gleam_module_bwd(C.byref(geom), C.byref(prox), _ptr(theta), _ptr(saved), _nbytes(saved),
+                                  _ptr(grad_theta), _ptr(ws), _nbytes(ws), _stream(stream)), "gleam_module_bwd")

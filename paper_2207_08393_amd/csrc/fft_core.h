@@ -1,0 +1,243 @@
+// In-LDS mixed-radix Stockham FFT building blocks for gfx950 (wave64).
+//
+// A transform of length N is a product of radices chosen at compile time (8, 4, 2 first, then 5, 3
+// and any other odd prime such as the 23 in 368 = 16 * 23).  Each stage reads R points at stride
+// N/R from the LDS buffer, applies the stage twiddles and an R-point DFT held in registers, and
+// writes them back autosorted (in place, with a barrier between the reads and the writes), so the
+// result comes out in natural order with no bit-reversal pass.  Transforms are unnormalised here; callers scale at their global store.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
+
+namespace gleam {
+
+// ------------------------------------------------------------------ compile-time trigonometry
+constexpr double kPi = 3.14159265358979323846264338327950288;
+
+constexpr double ct_sin_small(double x) {  // |x| <= pi
+    double term = x, sum = x, x2 = x * x;
+    for (int n = 1; n < 16; ++n) {
+        term *= -x2 / ((2 * n) * (2 * n + 1));
+        sum += term;
+    }
+    return sum;
+}
+constexpr double ct_cos_small(double x) {
+    double term = 1.0, sum = 1.0, x2 = x * x;
+    for (int n = 1; n < 16; ++n) {
+        term *= -x2 / ((2 * n - 1) * (2 * n));
+        sum += term;
+    }
+    return sum;
+}
+// cos / sin of 2*pi*m/R for integers, reduced to [-pi, pi] first.
+constexpr double ct_cos_frac(int m, int R) {
+    m %= R;
+    if (2 * m > R) m -= R;
+    return ct_cos_small(2.0 * kPi * m / R);
+}
+constexpr double ct_sin_frac(int m, int R) {
+    m %= R;
+    if (2 * m > R) m -= R;
+    return ct_sin_small(2.0 * kPi * m / R);
+}
+
+template <int I> using ic = std::integral_constant<int, I>;
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(ic<Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+// ------------------------------------------------------------------ complex helpers
+__device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
+__device__ __forceinline__ float2 cmul(float2 a, float2 b) {
+    return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+__device__ __forceinline__ float2 cmul_conj(float2 a, float2 b) {  // a * conj(b)
+    return make_float2(a.x * b.x + a.y * b.y, a.y * b.x - a.x * b.y);
+}
+// multiply by -i (forward) or +i (inverse)
+template <bool INV> __device__ __forceinline__ float2 mul_mi(float2 a) {
+    return INV ? make_float2(-a.y, a.x) : make_float2(a.y, -a.x);
+}
+
+// ------------------------------------------------------------------ small DFTs in registers
+template <bool INV> __device__ __forceinline__ void dft2(float2& a, float2& b) {
+    float2 t = csub(a, b);
+    a = cadd(a, b);
+    b = t;
+}
+
+template <bool INV> __device__ __forceinline__ void dft4(float2& b0, float2& b1, float2& b2, float2& b3) {
+    float2 s02 = cadd(b0, b2), d02 = csub(b0, b2);
+    float2 s13 = cadd(b1, b3), d13 = mul_mi<INV>(csub(b1, b3));
+    b0 = cadd(s02, s13);
+    b2 = csub(s02, s13);
+    b1 = cadd(d02, d13);
+    b3 = csub(d02, d13);
+}
+
+template <bool INV> __device__ __forceinline__ void dft8(float2 (&u)[8]) {
+    constexpr float h = 0.70710678118654752440f;
+    float2 a0 = cadd(u[0], u[4]), a4 = csub(u[0], u[4]);
+    float2 a1 = cadd(u[1], u[5]), a5 = csub(u[1], u[5]);
+    float2 a2 = cadd(u[2], u[6]), a6 = csub(u[2], u[6]);
+    float2 a3 = cadd(u[3], u[7]), a7 = csub(u[3], u[7]);
+    // a5 *= w8, a6 *= w8^2, a7 *= w8^3 with w8 = exp(-+ i pi/4)
+    a5 = INV ? make_float2(h * (a5.x - a5.y), h * (a5.x + a5.y)) : make_float2(h * (a5.x + a5.y), h * (a5.y - a5.x));
+    a6 = mul_mi<INV>(a6);
+    a7 = INV ? make_float2(-h * (a7.x + a7.y), h * (a7.x - a7.y)) : make_float2(h * (a7.y - a7.x), -h * (a7.x + a7.y));
+    dft4<INV>(a0, a1, a2, a3);
+    dft4<INV>(a4, a5, a6, a7);
+    u[0] = a0; u[2] = a1; u[4] = a2; u[6] = a3;
+    u[1] = a4; u[3] = a5; u[5] = a6; u[7] = a7;
+}
+
+// Odd prime length R by conjugate-pair folding: with a_r = u_r + u_{R-r}, b_r = u_r - u_{R-r},
+//   X_q     = u_0 + sum_r cos(2 pi q r / R) a_r  -+ i sum_r sin(2 pi q r / R) b_r
+//   X_{R-q} = the same with the opposite sign of the second sum,
+// which halves the multiplications of the direct R x R product; all constants are literals.
+template <int R, bool INV> __device__ __forceinline__ void dft_odd(float2 (&u)[R]) {
+    constexpr int Hn = (R - 1) / 2;
+    float2 a[Hn], b[Hn];
+#pragma unroll
+    for (int r = 1; r <= Hn; ++r) {
+        a[r - 1] = cadd(u[r], u[R - r]);
+        b[r - 1] = csub(u[r], u[R - r]);
+    }
+    const float2 u0 = u[0];
+    float2 s = u0;
+#pragma unroll
+    for (int r = 0; r < Hn; ++r) s = cadd(s, a[r]);
+    u[0] = s;
+    static_for<Hn>([&](auto qi) {
+        constexpr int q = decltype(qi)::value + 1;
+        float2 A = u0, Bv = make_float2(0.f, 0.f);
+        static_for<Hn>([&](auto ri) {
+            constexpr int r = decltype(ri)::value + 1;
+            constexpr float c = (float)ct_cos_frac(q * r, R);
+            constexpr float sn = (float)ct_sin_frac(q * r, R);
+            A.x = fmaf(c, a[r - 1].x, A.x);
+            A.y = fmaf(c, a[r - 1].y, A.y);
+            Bv.x = fmaf(sn, b[r - 1].x, Bv.x);
+            Bv.y = fmaf(sn, b[r - 1].y, Bv.y);
+        });
+        // forward: X_q = A - i Bv ; inverse: X_q = A + i Bv
+        const float2 lo = make_float2(A.x + Bv.y, A.y - Bv.x), hi = make_float2(A.x - Bv.y, A.y + Bv.x);
+        u[q] = INV ? hi : lo;
+        u[R - q] = INV ? lo : hi;
+    });
+}
+
+template <int R, bool INV> __device__ __forceinline__ void dft_r(float2 (&u)[R]) {
+    if constexpr (R == 1) {
+    } else if constexpr (R == 2) {
+        dft2<INV>(u[0], u[1]);
+    } else if constexpr (R == 4) {
+        dft4<INV>(u[0], u[1], u[2], u[3]);
+    } else if constexpr (R == 8) {
+        dft8<INV>(u);
+    } else {
+        static_assert(R % 2 == 1, "radix must be 2, 4, 8 or an odd prime");
+        dft_odd<R, INV>(u);
+    }
+}
+
+// ------------------------------------------------------------------ radix plan
+// Radix of the stage that follows a partial product P (P divides N).
+constexpr int next_radix(int N, int P) {
+    int m = N / P;
+    if (m % 8 == 0) return 8;
+    if (m % 4 == 0) return 4;
+    if (m % 2 == 0) return 2;
+    for (int r = 3; r <= m; r += 2)
+        if (m % r == 0) return r;
+    return 1;
+}
+constexpr int largest_prime_factor(int n) {
+    int best = 1;
+    for (int p = 2; p <= n; ++p)
+        while (n % p == 0) { best = p; n /= p; }
+    return best;
+}
+
+// LDS layouts.  Rows: line-major, element p of line l at l*N + p (threads walk p fastest).
+// Cols: position-major, element p of line l at p*L + l (threads walk l fastest), which matches a
+// tile of L neighbouring columns of a strided axis.
+template <int N, int L, bool COLS> struct Layout {
+    static constexpr int kElems = N * L;
+    __device__ static __forceinline__ int at(int line, int p) { return COLS ? p * L + line : line * N + p; }
+};
+
+// One Stockham stage over L lines held in one LDS buffer, in place: every thread first pulls the
+// inputs of all its butterflies into registers, the workgroup synchronises, then results are written
+// back autosorted.  Ends with a barrier, so the buffer is ready for the next stage or for readers.
+template <int N, int L, bool COLS, bool INV, int P, int NT>
+__device__ __forceinline__ void fft_stage(float2* __restrict__ buf, const float2* __restrict__ tw) {
+    constexpr int R = next_radix(N, P);
+    constexpr int T = N / R;
+    constexpr int PER = (L * T + NT - 1) / NT;
+    using Lay = Layout<N, L, COLS>;
+    float2 u[PER][R];
+#pragma unroll
+    for (int m = 0; m < PER; ++m) {
+        const int idx = threadIdx.x + m * NT;
+        if (PER * NT == L * T || idx < L * T) {
+            int line, i;
+            if (COLS) { line = idx % L; i = idx / L; } else { i = idx % T; line = idx / T; }
+#pragma unroll
+            for (int r = 0; r < R; ++r) u[m][r] = buf[Lay::at(line, i + r * T)];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < PER; ++m) {
+        const int idx = threadIdx.x + m * NT;
+        if (PER * NT == L * T || idx < L * T) {
+            int line, i;
+            if (COLS) { line = idx % L; i = idx / L; } else { i = idx % T; line = idx / T; }
+            const int k = i % P;
+            if constexpr (P > 1) {
+                constexpr int step = N / (P * R);
+#pragma unroll
+                for (int r = 1; r < R; ++r) {
+                    const float2 w = tw[r * k * step];
+                    u[m][r] = INV ? cmul_conj(u[m][r], w) : cmul(u[m][r], w);
+                }
+            }
+            dft_r<R, INV>(u[m]);
+            const int j = (i - k) * R + k;
+#pragma unroll
+            for (int r = 0; r < R; ++r) buf[Lay::at(line, j + r * P)] = u[m][r];
+        }
+    }
+    __syncthreads();
+}
+
+// All stages, in place.  The caller synchronises after filling `buf`; the result is visible to the
+// whole workgroup on return.
+template <int N, int L, bool COLS, bool INV, int NT, int P = 1>
+__device__ __forceinline__ void fft_lines(float2* buf, const float2* tw) {
+    if constexpr (P < N) {
+        fft_stage<N, L, COLS, INV, P, NT>(buf, tw);
+        fft_lines<N, L, COLS, INV, NT, P * next_radix(N, P)>(buf, tw);
+    }
+}
+
+// Forward twiddles w[k] = exp(-2 pi i k / N), k < N, evaluated in double.
+template <int N, int NT> __device__ __forceinline__ void fill_twiddles(float2* tw) {
+    for (int k = threadIdx.x; k < N; k += NT) {
+        double s, c;
+        sincospi(-2.0 * (double)k / (double)N, &s, &c);
+        tw[k] = make_float2((float)c, (float)s);
+    }
+}
+
+}  // namespace gleam

@@ -1,0 +1,168 @@
+// C ABI of the library: host-side validation, workspace carving and kernel sequencing.
+// Nothing here touches device memory directly; every step is a kernel of sense.hip / prox.hip
+// enqueued on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "internal.h"
+
+using namespace gleam;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) % kAlign) == 0; }
+
+int check_geom(const gleam_geom* g) {
+    if (!g) return GLEAM_E_NULL;
+    if (g->ndim_fft != 2 && g->ndim_fft != 3) return GLEAM_E_DIMS;
+    if (g->B < 1 || g->C < 1 || g->T < 1 || g->D < 1 || g->H < 1 || g->W < 1) return GLEAM_E_DIMS;
+    const long long lim = 1LL << 40;  // keeps every byte offset far inside int64
+    long long e = 1;
+    for (long long v : {g->B, g->C, g->T, g->D, g->H, g->W}) {
+        if (v > lim / e) return GLEAM_E_DIMS;
+        e *= v;
+    }
+    if (!fft_size_supported(g->W) || !fft_size_supported(g->H)) return GLEAM_E_UNSUPPORTED_SIZE;
+    if (g->ndim_fft == 3 && !fft_size_supported(g->D)) return GLEAM_E_UNSUPPORTED_SIZE;
+    return GLEAM_OK;
+}
+
+inline size_t n_coil_pixels(const gleam_geom& g) { return (size_t)(g.B * g.C * g.T * g.D * g.H * g.W); }
+inline size_t n_pixels(const gleam_geom& g) { return (size_t)(g.B * g.T * g.D * g.H * g.W); }
+
+int check_prox(const gleam_prox_desc* p) {
+    if (!p) return GLEAM_E_NULL;
+    if (p->n_layers < 1 || p->n_layers > kMaxLayers || !p->layers) return GLEAM_E_DESC;
+    if (p->dtype != 0 && p->dtype != 1) return GLEAM_E_DESC;
+    if (p->loss_kind != 0 && p->loss_kind != 1) return GLEAM_E_DESC;
+    int prev = 2;
+    std::vector<int> ch(p->n_layers + 1);
+    ch[0] = 2;
+    for (int l = 0; l < p->n_layers; ++l) {
+        const gleam_conv& c = p->layers[l];
+        if (c.cin != prev || c.cout < 1 || c.cout > kMaxChannels) return GLEAM_E_DESC;
+        for (int k : {c.kt, c.kd, c.kh, c.kw})
+            if (k < 1 || k > 5 || (k % 2) == 0) return GLEAM_E_DESC;
+        if (c.kt * c.kd * c.kh * c.kw > kMaxTaps) return GLEAM_E_DESC;
+        if (c.skip_src < -1 || c.skip_src > l) return GLEAM_E_DESC;
+        if (c.skip_src >= 0 && ch[c.skip_src] != c.cout) return GLEAM_E_DESC;
+        if (c.skip_src >= 0 && c.relu_out) return GLEAM_E_DESC;
+        for (int m = 0; m < l; ++m)  // one consumer per skip source
+            if (c.skip_src >= 1 && p->layers[m].skip_src == c.skip_src) return GLEAM_E_DESC;
+        if (wgrad_lds_bytes(c) > 150 * 1024) return GLEAM_E_DESC;
+        ch[l + 1] = c.cout;
+        prev = c.cout;
+    }
+    if (prev != 2) return GLEAM_E_DESC;
+    return GLEAM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gleam_strerror(int status) {
+    switch (status) {
+        case GLEAM_OK: return "ok";
+        case GLEAM_E_NULL: return "a required pointer is NULL";
+        case GLEAM_E_DIMS: return "invalid geometry";
+        case GLEAM_E_UNSUPPORTED_SIZE: return "no transform kernel for one of the Fourier lengths";
+        case GLEAM_E_WORKSPACE: return "workspace or saved buffer too small or not 256-byte aligned";
+        case GLEAM_E_DESC: return "invalid or unsupported prox description";
+        case GLEAM_E_LAUNCH: return "HIP launch failed";
+        default: return "unknown gleam status";
+    }
+}
+
+int gleam_fft_size_supported(int64_t n) { return fft_size_supported(n) ? 1 : 0; }
+
+int gleam_theta_count(const gleam_prox_desc* prox, size_t* n_floats) {
+    if (!n_floats) return GLEAM_E_NULL;
+    int rc = check_prox(prox);
+    if (rc) return rc;
+    size_t n = 0;
+    for (int l = 0; l < prox->n_layers; ++l) {
+        const gleam_conv& c = prox->layers[l];
+        n += (size_t)c.cout * c.kt * c.kd * c.kh * c.kw * c.cin + (c.has_bias ? c.cout : 0);
+    }
+    *n_floats = n;
+    return GLEAM_OK;
+}
+
+int gleam_workspace_bytes(const gleam_geom* geom, const gleam_prox_desc* prox, size_t* ws_bytes,
+                          size_t* saved_bytes) {
+    if (!ws_bytes || !saved_bytes) return GLEAM_E_NULL;
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    size_t ws = align_up(n_coil_pixels(*geom) * sizeof(float2));
+    size_t saved = 0;
+    if (prox) {
+        rc = check_prox(prox);
+        if (rc) return rc;
+        ProxPlan plan;
+        plan_prox(*geom, *prox, plan);
+        if (plan.ws_bytes > ws) ws = plan.ws_bytes;
+        saved = plan.saved_bytes;
+    }
+    *ws_bytes = ws;
+    *saved_bytes = saved;
+    return GLEAM_OK;
+}
+
+int gleam_sense_normal(const gleam_geom* geom, const gleam_c64* x, const gleam_c64* S, const uint8_t* M,
+                       gleam_c64* out, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    if (!x || !S || !M || !out || !ws) return GLEAM_E_NULL;
+    if (!aligned(ws) || ws_bytes < n_coil_pixels(*geom) * sizeof(float2)) return GLEAM_E_WORKSPACE;
+    hipError_t e = sense_dc(*geom, (const float2*)x, (const float2*)S, M, nullptr, 0.f, 1.f, (float2*)out,
+                            (float2*)ws, (hipStream_t)stream);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+int gleam_module_fwd(const gleam_geom* geom, const gleam_prox_desc* prox, const gleam_c64* x_in,
+                     const gleam_c64* S, const uint8_t* M, const gleam_c64* y, float alpha, const float* theta,
+                     const gleam_c64* x_ref, gleam_c64* x_out, float* loss, void* saved, size_t saved_bytes,
+                     void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    rc = check_prox(prox);
+    if (rc) return rc;
+    if (!x_in || !S || !M || !y || !theta || !x_out || !ws) return GLEAM_E_NULL;
+    if (x_ref && (!loss || !saved)) return GLEAM_E_NULL;
+    ProxPlan plan;
+    plan_prox(*geom, *prox, plan);
+    if (!aligned(ws) || ws_bytes < plan.ws_bytes) return GLEAM_E_WORKSPACE;
+    if (saved && (!aligned(saved) || saved_bytes < plan.saved_bytes)) return GLEAM_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    // Without a saved buffer (inference) the activations live in the workspace, after the k-space buffer.
+    unsigned char* act_base = saved ? (unsigned char*)saved : (unsigned char*)ws + plan.k_bytes;
+    float2* u = (float2*)(act_base + plan.act_off[0]);
+    hipError_t e = sense_dc(*geom, (const float2*)x_in, (const float2*)S, M, (const float2*)y, 1.f, -alpha, u,
+                            (float2*)ws, st);
+    if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    e = prox_forward(*geom, *prox, plan, theta, act_base, (const float2*)x_ref, (float2*)x_out, loss, ws, st);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const float* theta, const void* saved,
+                     size_t saved_bytes, float* grad_theta, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    rc = check_prox(prox);
+    if (rc) return rc;
+    if (!theta || !saved || !grad_theta || !ws) return GLEAM_E_NULL;
+    ProxPlan plan;
+    plan_prox(*geom, *prox, plan);
+    if (!aligned(ws) || ws_bytes < plan.ws_bytes) return GLEAM_E_WORKSPACE;
+    if (!aligned(saved) || saved_bytes < plan.saved_bytes) return GLEAM_E_WORKSPACE;
+    hipError_t e = prox_backward(*geom, *prox, plan, theta, (const unsigned char*)saved, grad_theta, ws,
+                                 (hipStream_t)stream);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal (non-ABI) declarations shared by the translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+
+#include "../../include/gleam.h"
+
+namespace gleam {
+
+constexpr int kMaxLayers = 32;
+constexpr int kMaxChannels = 256;
+constexpr int kMaxTaps = 32;  // per-pixel tap validity is kept as one 32-bit mask
+
+bool fft_size_supported(long long n);
+
+// out = xs*x + gs * S^H F^H Omega (F S x - y); y may be null (then y = 0).  kbuf holds B*C*T*D*H*W
+// complex values and is overwritten.  Everything is enqueued on `st`.
+hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const unsigned char* M,
+                    const float2* y, float xs, float gs, float2* out, float2* kbuf, hipStream_t st);
+
+// Byte offsets of everything the prox keeps between and during calls.
+//   saved : t_0 (= u, fp32 2 channels), t_1 .. t_{L-1} (fp32), g_z = dL/dz (fp32 2 channels)
+//   ws    : [k-space | activations when the caller gave no saved buffer] for forward;
+//           [G_1 .. G_{L-1} | split-K partials | loss partials] for backward
+struct ProxPlan {
+    int L;
+    long long Q;                      // pixels B*T*D*H*W
+    size_t act_off[kMaxLayers + 1];   // t_l inside saved, l < L
+    size_t gz_off;
+    size_t saved_bytes;
+    size_t grad_off[kMaxLayers + 1];  // G_l inside ws, 1 <= l < L
+    size_t partial_off, partial_bytes;
+    size_t red_off;                   // loss partial sums (doubles)
+    size_t k_bytes;                   // coil k-space buffer at the head of ws (forward)
+    size_t ws_bytes;
+    size_t w_off[kMaxLayers], b_off[kMaxLayers];  // float offsets into theta
+    int n_split;                      // split-K workgroups of the weight-gradient kernels
+};
+
+// LDS bytes the weight-gradient kernel needs for one layer (must stay below the 160 KB of a CU).
+size_t wgrad_lds_bytes(const gleam_conv& c);
+
+void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan);
+
+// z = f_theta(u) with u = t_0 already stored at act_base + act_off[0]; writes t_1..t_{L-1} next to it
+// and z to x_out.  With x_ref: loss (device scalar) and g_z are produced as well.
+hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
+                        unsigned char* act_base, const float2* x_ref, float2* x_out, float* loss, void* ws,
+                        hipStream_t st);
+
+// grad_theta = dL/dtheta from the activations and g_z left by prox_forward.
+hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
+                         const unsigned char* saved, float* grad_theta, void* ws, hipStream_t st);
+
+}  // namespace gleam

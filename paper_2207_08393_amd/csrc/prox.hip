@@ -1,0 +1,574 @@
+// Prox CNN f_theta (Eq. 4-5) forward, local loss (Eq. 10) and the module-confined backward pass
+// (Alg. 1, gradient step) on gfx950, float32 with the 32x32x2 fp32 MFMA.
+//
+// Activations are channels-last [pixels][channels] with pixels flattened over (B,T,D,H,W); a complex
+// image is its own 2-channel activation.  Convolutions are implicit GEMMs:
+//   conv_mfma_kernel : out[q][n] = sum_{tap,k} in[q + off(tap)][k] * w(n, tap, k)
+//                      forward (n = cout, k = cin) and data gradient (n = cin, k = cout, taps flipped)
+//                      share it; bias / ReLU / ReLU-mask / residual add are fused into the store.
+//   wgrad_mfma_kernel: dw[co][tap][ci] = sum_q g[q][co] * a[q + off(tap)][ci], split over pixel chunks,
+//                      partial sums reduced in a fixed order (deterministic).
+// Zero padding is a per-pixel 32-bit tap-validity mask, so pixel tiles are plain runs of the flattened
+// index and never ragged except at the very end of the tensor.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+
+namespace gleam {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kConvThreads = 256;
+
+struct PixDims {
+    int T, D, H, W;
+    int kt, kd, kh, kw;
+    long long Q;
+};
+
+// Bit `tap` is set when pixel q + off(tap) lies inside the grid (same sample, frame, slice, row).
+__device__ __forceinline__ unsigned tap_validity(long long q, const PixDims& d) {
+    if (q >= d.Q) return 0u;
+    const int w = (int)(q % d.W);
+    long long r = q / d.W;
+    const int h = (int)(r % d.H);
+    r /= d.H;
+    const int dd = (int)(r % d.D);
+    r /= d.D;
+    const int t = (int)(r % d.T);
+    unsigned bits = 0u;
+    int tap = 0;
+    for (int it = 0; it < d.kt; ++it)
+        for (int id = 0; id < d.kd; ++id)
+            for (int ih = 0; ih < d.kh; ++ih)
+                for (int iw = 0; iw < d.kw; ++iw, ++tap) {
+                    const int tt = t + it - d.kt / 2, d2 = dd + id - d.kd / 2;
+                    const int hh = h + ih - d.kh / 2, ww = w + iw - d.kw / 2;
+                    const bool ok = tt >= 0 && tt < d.T && d2 >= 0 && d2 < d.D && hh >= 0 && hh < d.H && ww >= 0 && ww < d.W;
+                    bits |= (ok ? 1u : 0u) << tap;
+                }
+    return bits;
+}
+
+// Flattened pixel offset of row-tap rt = (it, id, ih), before the kw taps along W.
+__device__ __forceinline__ long long rowtap_offset(int rt, const PixDims& d) {
+    const int ih = rt % d.kh, id = (rt / d.kh) % d.kd, it = rt / (d.kh * d.kd);
+    return (((long long)(it - d.kt / 2) * d.D + (id - d.kd / 2)) * d.H + (ih - d.kh / 2)) * d.W;
+}
+
+// ------------------------------------------------------------------ forward / data-gradient conv
+struct ConvArgs {
+    const float* in;        // [Q][K]
+    float* out;             // [Q][Nn]
+    const float* w;         // element (n, tap, k) at w[n*w_sn + tapidx*w_st + k*w_sk]
+    const float* bias;      // [Nn] or null
+    const float* mask_ref;  // [Q][Nn] or null: ReLU mask source (value > 0 passes)
+    const float* add;       // [Q][Nn] or null: added to the result
+    long long w_sn, w_st, w_sk;
+    int K, Nn;              // input / output channels of this GEMM
+    int flip;               // 1: tapidx = taps-1-tap (data gradient)
+    int relu_in, relu_out, mask_acc, mask_add;
+    PixDims d;
+};
+
+template <int NB, int CK>
+__global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
+    constexpr int TM = 128, RS = CK + 4, G = CK / 8, NJ = NB / 32;
+    extern __shared__ float smem[];
+    const PixDims d = a.d;
+    const int n_pix = TM + d.kw - 1;
+    float* slab = smem;             // [n_pix][RS]
+    float* wl = smem + n_pix * RS;  // [kw][G][2][NB][4]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, h = lane >> 5;
+    const int n0 = blockIdx.y * NB;
+    const int taps = d.kt * d.kd * d.kh * d.kw, rowtaps = d.kt * d.kd * d.kh;
+    const long long n_tiles = (d.Q + TM - 1) / TM;
+    const bool vec_in = (a.K % 4) == 0, vec_out = (a.Nn % 4) == 0;
+
+    for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const long long q0 = tile * TM;
+        const long long q = q0 + wave * 32 + m;
+        const unsigned vbits = tap_validity(q, d);
+        floatx16 acc[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+        for (int rt = 0; rt < rowtaps; ++rt) {
+            const long long qs = q0 + rowtap_offset(rt, d) - d.kw / 2;
+            for (int c0 = 0; c0 < a.K; c0 += CK) {
+                __syncthreads();
+                // ---- stage the pixel slab (ReLU on load when asked)
+                if (vec_in) {
+                    for (int v = threadIdx.x; v < n_pix * (CK / 4); v += kConvThreads) {
+                        const int pp = v / (CK / 4), c4 = v % (CK / 4);
+                        const long long qq = qs + pp;
+                        const int ch = c0 + 4 * c4;
+                        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (qq >= 0 && qq < d.Q && ch < a.K) val = *reinterpret_cast<const float4*>(a.in + qq * a.K + ch);
+                        if (a.relu_in) {
+                            val.x = fmaxf(val.x, 0.f); val.y = fmaxf(val.y, 0.f);
+                            val.z = fmaxf(val.z, 0.f); val.w = fmaxf(val.w, 0.f);
+                        }
+                        *reinterpret_cast<float4*>(slab + pp * RS + 4 * c4) = val;
+                    }
+                } else {
+                    for (int v = threadIdx.x; v < n_pix * CK; v += kConvThreads) {
+                        const int pp = v / CK, kk = v % CK;
+                        const long long qq = qs + pp;
+                        const int ch = c0 + kk;
+                        float val = 0.f;
+                        if (qq >= 0 && qq < d.Q && ch < a.K) val = a.in[qq * a.K + ch];
+                        if (a.relu_in) val = fmaxf(val, 0.f);
+                        slab[pp * RS + kk] = val;
+                    }
+                }
+                // ---- stage the weights of this row-tap and channel chunk
+                for (int e = threadIdx.x; e < d.kw * CK * NB; e += kConvThreads) {
+                    int n, kk;
+                    if (a.w_sk == 1) { kk = e % CK; n = (e / CK) % NB; } else { n = e % NB; kk = (e / NB) % CK; }
+                    const int dw = e / (CK * NB);
+                    const int tap = rt * d.kw + dw;
+                    const int tapidx = a.flip ? taps - 1 - tap : tap;
+                    const int k = c0 + kk;
+                    float val = 0.f;
+                    if (k < a.K && n0 + n < a.Nn) val = a.w[(n0 + n) * a.w_sn + tapidx * a.w_st + k * a.w_sk];
+                    wl[(((dw * G + kk / 8) * 2 + ((kk >> 2) & 1)) * NB + n) * 4 + (kk & 3)] = val;
+                }
+                __syncthreads();
+                // ---- MFMA: A = weights (rows = output channels), B = pixels (columns)
+                for (int dw = 0; dw < d.kw; ++dw) {
+                    const bool ok = (vbits >> (rt * d.kw + dw)) & 1u;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        float4 pb = *reinterpret_cast<const float4*>(slab + (wave * 32 + m + dw) * RS + 8 * g + 4 * h);
+                        if (!ok) pb = make_float4(0.f, 0.f, 0.f, 0.f);
+                        float4 wa[NJ];
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            wa[j] = *reinterpret_cast<const float4*>(wl + (((dw * G + g) * 2 + h) * NB + 32 * j + m) * 4);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].x, pb.x, acc[j], 0, 0, 0);
+                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].y, pb.y, acc[j], 0, 0, 0);
+                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].z, pb.z, acc[j], 0, 0, 0);
+                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].w, pb.w, acc[j], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+        // ---- epilogue: lane holds pixel q (column m) and 4 consecutive channels per register group
+        if (q < d.Q) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int co0 = n0 + 32 * j + 8 * rg + 4 * h;
+                    if (co0 >= a.Nn) continue;
+                    float v[4] = {acc[j][4 * rg], acc[j][4 * rg + 1], acc[j][4 * rg + 2], acc[j][4 * rg + 3]};
+                    const long long o = q * a.Nn + co0;
+                    if (vec_out) {
+                        if (a.bias) {
+                            const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0);
+                            v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
+                        }
+                        if (a.relu_out) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+                        }
+                        float4 ref = make_float4(1.f, 1.f, 1.f, 1.f);
+                        if (a.mask_ref) ref = *reinterpret_cast<const float4*>(a.mask_ref + o);
+                        const float rr[4] = {ref.x, ref.y, ref.z, ref.w};
+                        if (a.mask_acc) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) v[i] = rr[i] > 0.f ? v[i] : 0.f;
+                        }
+                        if (a.add) {
+                            const float4 av = *reinterpret_cast<const float4*>(a.add + o);
+                            const float aa[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) v[i] += (a.mask_add && !(rr[i] > 0.f)) ? 0.f : aa[i];
+                        }
+                        *reinterpret_cast<float4*>(a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (co0 + i >= a.Nn) break;
+                            float x = v[i];
+                            if (a.bias) x += a.bias[co0 + i];
+                            if (a.relu_out) x = fmaxf(x, 0.f);
+                            const float ref = a.mask_ref ? a.mask_ref[o + i] : 1.f;
+                            if (a.mask_acc) x = ref > 0.f ? x : 0.f;
+                            if (a.add) x += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o + i];
+                            a.out[o + i] = x;
+                        }
+                    }
+                }
+        }
+    }
+}
+
+static int conv_grid_x(long long n_tiles) {
+    const long long cap = 256LL * 6;
+    return (int)(n_tiles < cap ? n_tiles : cap);
+}
+
+template <int NB, int CK>
+static hipError_t launch_conv_t(const ConvArgs& a, hipStream_t st) {
+    const long long n_tiles = (a.d.Q + 127) / 128;
+    const size_t lds = ((size_t)(128 + a.d.kw - 1) * (CK + 4) + (size_t)a.d.kw * CK * NB) * sizeof(float);
+    dim3 grid(conv_grid_x(n_tiles), (a.Nn + NB - 1) / NB);
+    hipLaunchKernelGGL((conv_mfma_kernel<NB, CK>), grid, dim3(kConvThreads), lds, st, a);
+    return hipGetLastError();
+}
+
+static hipError_t launch_conv(const ConvArgs& a, hipStream_t st) {
+    const int ck = a.K <= 8 ? 8 : (a.K <= 16 ? 16 : 32);
+    if (a.Nn <= 32) {
+        if (ck == 8) return launch_conv_t<32, 8>(a, st);
+        if (ck == 16) return launch_conv_t<32, 16>(a, st);
+        return launch_conv_t<32, 32>(a, st);
+    }
+    if (ck == 8) return launch_conv_t<64, 8>(a, st);
+    if (ck == 16) return launch_conv_t<64, 16>(a, st);
+    return launch_conv_t<64, 32>(a, st);
+}
+
+// ------------------------------------------------------------------ weight gradient
+struct WgradArgs {
+    const float* g;    // [Q][Co]  gradient at the conv output (already ReLU-masked)
+    const float* a;    // [Q][Ci]  conv input before its optional ReLU
+    float* partial;    // [n_split][Co][taps][Ci]
+    int Co, Ci, relu_in;
+    PixDims d;
+};
+
+constexpr int kWgTM = 32;  // pixels per staged chunk
+
+template <int JT>
+__global__ __launch_bounds__(kConvThreads) void wgrad_mfma_kernel(WgradArgs a) {
+    extern __shared__ float smem[];
+    const PixDims d = a.d;
+    const int RSg = (a.Co + 3) / 4 * 4 + 1, RSa = (a.Ci + 3) / 4 * 4 + 1;
+    const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
+    const int n_pa = kWgTM + d.kw - 1;
+    float* gs = smem;                          // [kWgTM][RSg]
+    float* as = gs + kWgTM * RSg;              // [rowtaps][n_pa][RSa]
+    unsigned* vmask = reinterpret_cast<unsigned*>(as + rowtaps * n_pa * RSa);  // [kWgTM]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, h = lane >> 5;
+    const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32, tapgroups = (taps + JT - 1) / JT;
+    const int job = blockIdx.y * 4 + wave;
+    const bool active = job < ncb * nib * tapgroups;
+    const int tg = job % tapgroups, pair = job / tapgroups;
+    const int cb = pair / nib, ib = pair % nib;
+    const int tap0 = tg * JT;
+
+    floatx16 acc[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    const long long n_chunks = (d.Q + kWgTM - 1) / kWgTM;
+    for (long long chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
+        const long long q0 = chunk * kWgTM;
+        __syncthreads();
+        for (int v = threadIdx.x; v < kWgTM * a.Co; v += kConvThreads) {
+            const int p = v / a.Co, c = v % a.Co;
+            const long long qq = q0 + p;
+            gs[p * RSg + c] = qq < d.Q ? a.g[qq * a.Co + c] : 0.f;
+        }
+        for (int rt = 0; rt < rowtaps; ++rt) {
+            const long long qs = q0 + rowtap_offset(rt, d) - d.kw / 2;
+            float* dst = as + rt * n_pa * RSa;
+            for (int v = threadIdx.x; v < n_pa * a.Ci; v += kConvThreads) {
+                const int p = v / a.Ci, c = v % a.Ci;
+                const long long qq = qs + p;
+                float val = (qq >= 0 && qq < d.Q) ? a.a[qq * a.Ci + c] : 0.f;
+                if (a.relu_in) val = fmaxf(val, 0.f);
+                dst[p * RSa + c] = val;
+            }
+        }
+        if (threadIdx.x < kWgTM) vmask[threadIdx.x] = tap_validity(q0 + threadIdx.x, d);
+        __syncthreads();
+        if (active) {
+            const int co = cb * 32 + m, ci = ib * 32 + m;
+            const bool co_ok = co < a.Co, ci_ok = ci < a.Ci;
+#pragma unroll 4
+            for (int s = 0; s < kWgTM / 2; ++s) {
+                const int p = 2 * s + h;
+                const float av = co_ok ? gs[p * RSg + co] : 0.f;
+                const unsigned vm = vmask[p];
+#pragma unroll
+                for (int j = 0; j < JT; ++j) {
+                    const int tap = tap0 + j;
+                    if (tap < taps) {
+                        const int rt = tap / d.kw, dw = tap % d.kw;
+                        float bv = ci_ok ? as[(rt * n_pa + p + dw) * RSa + ci] : 0.f;
+                        bv = ((vm >> tap) & 1u) ? bv : 0.f;
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if (active) {
+        float* dst = a.partial + (size_t)blockIdx.x * a.Co * taps * a.Ci;
+        const int ci = ib * 32 + m;
+#pragma unroll
+        for (int j = 0; j < JT; ++j) {
+            const int tap = tap0 + j;
+            if (tap >= taps || ci >= a.Ci) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = cb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (co < a.Co) dst[((size_t)co * taps + tap) * a.Ci + ci] = acc[j][r];
+            }
+        }
+    }
+}
+
+// out[i] = sum_s partial[s][i], s ascending (fixed order => run-to-run identical bits).
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_split, long long n, float* __restrict__ out) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int k = 0; k < n_split; ++k) s += partial[(size_t)k * n + i];
+    out[i] = s;
+}
+
+// partial[blk][c] = sum over this workgroup's pixels of g[q][c]  (bias gradient).
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ g, long long Q, int C, float* __restrict__ partial) {
+    __shared__ float red[256];
+    const int per = 256 / C > 0 ? 256 / C : 1;  // pixel lanes per channel (C <= 256 here)
+    const int c = threadIdx.x % C, lane = threadIdx.x / C;
+    float s = 0.f;
+    if (lane < per) {
+        for (long long q = (long long)blockIdx.x * per + lane; q < Q; q += (long long)gridDim.x * per) s += g[q * C + c];
+    }
+    red[threadIdx.x] = (lane < per) ? s : 0.f;
+    __syncthreads();
+    if (threadIdx.x < C) {
+        float t = 0.f;
+        for (int l = 0; l < per; ++l) t += red[l * C + threadIdx.x];
+        partial[(size_t)blockIdx.x * C + threadIdx.x] = t;
+    }
+}
+
+// ------------------------------------------------------------------ loss
+// part[blk] = sum over this workgroup's pixels of |z-x|^2 (kind 0) or |z-x| (kind 1); gz = dL/dz.
+__global__ __launch_bounds__(256) void loss_kernel(const float2* __restrict__ z, const float2* __restrict__ xr, float2* __restrict__ gz,
+                                                   long long n, int kind, float inv_n, int relu_mask, double* __restrict__ part) {
+    __shared__ double red[256];
+    double s = 0.0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const float2 zv = z[i], xv = xr[i];
+        const float dx = zv.x - xv.x, dy = zv.y - xv.y;
+        float2 g;
+        if (kind == 0) {
+            s += (double)dx * dx + (double)dy * dy;
+            g = make_float2(2.f * dx * inv_n, 2.f * dy * inv_n);
+        } else {
+            const float mag = sqrtf(dx * dx + dy * dy);
+            s += (double)mag;
+            g = mag > 0.f ? make_float2(dx / mag * inv_n, dy / mag * inv_n) : make_float2(0.f, 0.f);
+        }
+        if (relu_mask) {  // last layer ended in a ReLU: gradient passes where its output is positive
+            g.x = zv.x > 0.f ? g.x : 0.f;
+            g.y = zv.y > 0.f ? g.y : 0.f;
+        }
+        gz[i] = g;
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part[blockIdx.x] = red[0];
+}
+
+__global__ void loss_final_kernel(const double* __restrict__ part, int n_part, double inv_n, float* __restrict__ loss) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        double s = 0.0;
+        for (int i = 0; i < n_part; ++i) s += part[i];
+        *loss = (float)(s * inv_n);
+    }
+}
+
+// ------------------------------------------------------------------ host side
+static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+constexpr int kLossBlocks = 512;
+
+static PixDims pix_dims(const gleam_geom& g, const gleam_conv& c) {
+    PixDims d;
+    d.T = (int)g.T; d.D = (int)g.D; d.H = (int)g.H; d.W = (int)g.W;
+    d.kt = c.kt; d.kd = c.kd; d.kh = c.kh; d.kw = c.kw;
+    d.Q = g.B * g.T * g.D * g.H * g.W;
+    return d;
+}
+
+void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
+    const int L = p.n_layers;
+    plan.L = L;
+    plan.Q = g.B * g.T * g.D * g.H * g.W;
+    const size_t Q = (size_t)plan.Q;
+    size_t off = 0, th = 0, max_w = 0;
+    for (int l = 0; l < L; ++l) {
+        const gleam_conv& c = p.layers[l];
+        plan.act_off[l] = off;
+        off += align256(Q * c.cin * sizeof(float));
+        plan.w_off[l] = th;
+        const size_t nw = (size_t)c.cout * c.kt * c.kd * c.kh * c.kw * c.cin;
+        th += nw;
+        plan.b_off[l] = th;
+        if (c.has_bias) th += c.cout;
+        if (nw > max_w) max_w = nw;
+    }
+    plan.gz_off = off;
+    off += align256(Q * 2 * sizeof(float));
+    plan.saved_bytes = off;
+
+    // split-K: enough workgroups to fill the chip, never more than there are pixel chunks
+    const long long chunks = (plan.Q + kWgTM - 1) / kWgTM;
+    plan.n_split = (int)(chunks < 512 ? chunks : 512);
+
+    size_t w = 0;
+    plan.grad_off[0] = 0;
+    for (int l = 1; l < L; ++l) {
+        plan.grad_off[l] = w;
+        w += align256(Q * p.layers[l].cin * sizeof(float));
+    }
+    plan.grad_off[L] = 0;  // G_L = g_z lives in saved
+    plan.partial_off = w;
+    plan.partial_bytes = align256((size_t)plan.n_split * (max_w > (size_t)kMaxChannels ? max_w : (size_t)kMaxChannels) * sizeof(float));
+    w += plan.partial_bytes;
+    const size_t bwd_ws = w;
+
+    plan.red_off = 0;  // loss partials reuse the head of the k-space buffer once DC is done
+    size_t kbytes = align256((size_t)(g.B * g.C * g.T * g.D * g.H * g.W) * sizeof(float2));
+    if (kbytes < align256(kLossBlocks * sizeof(double))) kbytes = align256(kLossBlocks * sizeof(double));
+    plan.k_bytes = kbytes;
+    const size_t fwd_ws = kbytes + plan.saved_bytes;  // room for activations when no saved buffer is given
+    plan.ws_bytes = fwd_ws > bwd_ws ? fwd_ws : bwd_ws;
+}
+
+hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
+                        unsigned char* act_base, const float2* x_ref, float2* x_out, float* loss, void* ws,
+                        hipStream_t st) {
+    const int L = p.n_layers;
+    for (int l = 0; l < L; ++l) {
+        const gleam_conv& c = p.layers[l];
+        const size_t taps = (size_t)c.kt * c.kd * c.kh * c.kw;
+        ConvArgs a{};
+        a.in = reinterpret_cast<const float*>(act_base + plan.act_off[l]);
+        a.out = (l == L - 1) ? reinterpret_cast<float*>(x_out) : reinterpret_cast<float*>(act_base + plan.act_off[l + 1]);
+        a.w = theta + plan.w_off[l];
+        a.w_sn = (long long)(taps * c.cin); a.w_st = c.cin; a.w_sk = 1;
+        a.bias = c.has_bias ? theta + plan.b_off[l] : nullptr;
+        a.add = c.skip_src >= 0 ? reinterpret_cast<const float*>(act_base + plan.act_off[c.skip_src]) : nullptr;
+        a.K = c.cin; a.Nn = c.cout;
+        a.relu_in = c.relu_in; a.relu_out = c.relu_out;
+        a.d = pix_dims(g, c);
+        hipError_t e = launch_conv(a, st);
+        if (e != hipSuccess) return e;
+    }
+    if (x_ref) {
+        const long long n = plan.Q;
+        double* part = reinterpret_cast<double*>((unsigned char*)ws + plan.red_off);
+        float2* gz = reinterpret_cast<float2*>(act_base + plan.gz_off);
+        hipLaunchKernelGGL(loss_kernel, dim3(kLossBlocks), dim3(256), 0, st, (const float2*)x_out, x_ref, gz, n,
+                           p.loss_kind, (float)(1.0 / (double)n), p.layers[L - 1].relu_out, part);
+        hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, kLossBlocks, 1.0 / (double)n, loss);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+static hipError_t launch_wgrad(const WgradArgs& a, int n_split, hipStream_t st) {
+    const PixDims& d = a.d;
+    const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
+    const int RSg = (a.Co + 3) / 4 * 4 + 1, RSa = (a.Ci + 3) / 4 * 4 + 1;
+    const size_t lds = ((size_t)kWgTM * RSg + (size_t)rowtaps * (kWgTM + d.kw - 1) * RSa + kWgTM) * sizeof(float);
+    const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
+    const int jt = taps >= 9 ? 9 : 3;
+    const int tapgroups = (taps + jt - 1) / jt;
+    dim3 grid(n_split, (ncb * nib * tapgroups + 3) / 4);
+    if (jt == 9) {
+        static bool once9 = false;
+        if (!once9) { (void)hipFuncSetAttribute((const void*)wgrad_mfma_kernel<9>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); once9 = true; }
+        hipLaunchKernelGGL(wgrad_mfma_kernel<9>, grid, dim3(kConvThreads), lds, st, a);
+    } else {
+        static bool once3 = false;
+        if (!once3) { (void)hipFuncSetAttribute((const void*)wgrad_mfma_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); once3 = true; }
+        hipLaunchKernelGGL(wgrad_mfma_kernel<3>, grid, dim3(kConvThreads), lds, st, a);
+    }
+    return hipGetLastError();
+}
+
+size_t wgrad_lds_bytes(const gleam_conv& c) {
+    const int rowtaps = c.kt * c.kd * c.kh;
+    const int RSg = (c.cout + 3) / 4 * 4 + 1, RSa = (c.cin + 3) / 4 * 4 + 1;
+    return ((size_t)kWgTM * RSg + (size_t)rowtaps * (kWgTM + c.kw - 1) * RSa + kWgTM) * sizeof(float);
+}
+
+hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
+                         const unsigned char* saved, float* grad_theta, void* ws, hipStream_t st) {
+    const int L = p.n_layers;
+    unsigned char* wsb = (unsigned char*)ws;
+    float* partial = reinterpret_cast<float*>(wsb + plan.partial_off);
+    // Gradient buffer of tensor t_l (1 <= l <= L); G_L is g_z.
+    auto G = [&](int l) -> float* {
+        return l == L ? reinterpret_cast<float*>(const_cast<unsigned char*>(saved) + plan.gz_off)
+                      : reinterpret_cast<float*>(wsb + plan.grad_off[l]);
+    };
+    auto act = [&](int l) -> const float* { return reinterpret_cast<const float*>(saved + plan.act_off[l]); };
+    // pending[s]: layer (1-based) whose output gradient also flows into t_s through its skip, or 0
+    int pending[kMaxLayers + 1] = {0};
+
+    for (int l = L; l >= 1; --l) {  // layer l maps t_{l-1} -> t_l
+        const gleam_conv& c = p.layers[l - 1];
+        const size_t taps = (size_t)c.kt * c.kd * c.kh * c.kw;
+        const PixDims d = pix_dims(g, c);
+        if (c.skip_src >= 1) {
+            if (pending[c.skip_src] != 0) return hipErrorInvalidValue;  // one consumer per skip source (checked at plan time)
+            pending[c.skip_src] = l;
+        }
+        // weight gradient (+ bias gradient)
+        WgradArgs wa{};
+        wa.g = G(l); wa.a = act(l - 1); wa.partial = partial;
+        wa.Co = c.cout; wa.Ci = c.cin; wa.relu_in = c.relu_in; wa.d = d;
+        hipError_t e = launch_wgrad(wa, plan.n_split, st);
+        if (e != hipSuccess) return e;
+        const long long nw = (long long)(c.cout * taps * c.cin);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st,
+                           (const float*)partial, plan.n_split, nw, grad_theta + plan.w_off[l - 1]);
+        if (c.has_bias) {
+            hipLaunchKernelGGL(colsum_kernel, dim3(plan.n_split), dim3(256), 0, st, (const float*)G(l), plan.Q, c.cout, partial);
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((c.cout + 255) / 256), dim3(256), 0, st,
+                               (const float*)partial, plan.n_split, (long long)c.cout, grad_theta + plan.b_off[l - 1]);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (l == 1) break;  // nothing flows into t_0 = u: the module input is detached
+        // data gradient into t_{l-1}, fused with the ReLU masks and the pending skip gradient
+        const gleam_conv& below = p.layers[l - 2];  // layer that produced t_{l-1}
+        ConvArgs a{};
+        a.in = G(l); a.out = G(l - 1);
+        a.w = theta + plan.w_off[l - 1];
+        a.w_sn = 1; a.w_st = c.cin; a.w_sk = (long long)(taps * c.cin); a.flip = 1;
+        a.K = c.cout; a.Nn = c.cin;
+        a.mask_acc = (c.relu_in || below.relu_out) ? 1 : 0;
+        a.mask_add = below.relu_out ? 1 : 0;
+        a.mask_ref = (a.mask_acc || a.mask_add) ? act(l - 1) : nullptr;
+        a.add = pending[l - 1] ? G(pending[l - 1]) : nullptr;
+        a.d = d;
+        e = launch_conv(a, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace gleam

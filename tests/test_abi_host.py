@@ -1,0 +1,115 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments on the host before anything could be launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2207_08393_amd import binding as gb
+from paper_2207_08393_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "gleam.h")).read()
+    declared = set(re.findall(r"\b(gleam_[a-z_0-9]+)\s*\(", header))
+    assert {"gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd"} <= declared
+    lib = gb.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(gb.EXPORTS)
+
+
+def test_strerror_and_counts():
+    assert gb.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert gb.strerror(code) and "unknown" not in gb.strerror(code)
+    assert "unknown" in gb.strerror(-99)
+    c = synth.make_case(0)
+    prox = gb.make_prox(c.prox)
+    assert gb.gleam_theta_count(prox) == c.theta.size == c.prox.n_theta
+    ws, saved = gb.gleam_workspace_bytes(gb.make_geom(c.geom), prox)
+    Q = 64 * 64
+    assert saved >= Q * 4 * (2 + 16 + 16 + 2) and ws >= 8 * c.geom.E and ws % 256 == 0 and saved % 256 == 0
+    ws0, saved0 = gb.gleam_workspace_bytes(gb.make_geom(c.geom), None)
+    assert saved0 == 0 and ws0 >= 8 * c.geom.E
+    for n in (64, 640, 368, 320, 256, 160, 192):
+        assert gb.gleam_fft_size_supported(n)
+    assert not gb.gleam_fft_size_supported(7) and not gb.gleam_fft_size_supported(0)
+
+
+def _status(fn, *a):
+    with pytest.raises(gb.GleamError) as e:
+        fn(*a)
+    return e.value.status
+
+
+def test_bad_geometry_and_sizes_are_rejected():
+    good = synth.Geom(2, 1, 2, 1, 1, 8, 8)
+    for field, val, code in (("ndim_fft", 1, gb.GLEAM_E_DIMS), ("ndim_fft", 4, gb.GLEAM_E_DIMS),
+                             ("B", 0, gb.GLEAM_E_DIMS), ("C", -1, gb.GLEAM_E_DIMS),
+                             ("W", 7, gb.GLEAM_E_UNSUPPORTED_SIZE), ("H", 9, gb.GLEAM_E_UNSUPPORTED_SIZE)):
+        g = synth.Geom(**{**good.__dict__, field: val})
+        assert _status(gb.gleam_workspace_bytes, gb.make_geom(g), None) == code
+    g3 = synth.Geom(3, 1, 2, 1, 7, 8, 8)
+    assert _status(gb.gleam_workspace_bytes, gb.make_geom(g3), None) == gb.GLEAM_E_UNSUPPORTED_SIZE
+    g2 = synth.Geom(2, 1, 2, 1, 7, 8, 8)     # D is only batched for ndim_fft = 2
+    gb.gleam_workspace_bytes(gb.make_geom(g2), None)
+
+
+def test_bad_prox_descriptions_are_rejected():
+    geom = gb.make_geom(synth.Geom(2, 1, 2, 1, 1, 8, 8))
+    k = (1, 1, 3, 3)
+    ok = synth.chain_prox([2, 4, 2], [k, k])
+    gb.gleam_workspace_bytes(geom, gb.make_prox(ok))
+
+    def bad(mut):
+        p = synth.chain_prox([2, 4, 2], [k, k])
+        mut(p)
+        return _status(gb.gleam_workspace_bytes, geom, gb.make_prox(p))
+
+    assert bad(lambda p: setattr(p.layers[0], "cin", 3)) == gb.GLEAM_E_DESC
+    assert bad(lambda p: setattr(p.layers[1], "cout", 3)) == gb.GLEAM_E_DESC
+    assert bad(lambda p: setattr(p.layers[1], "cin", 5)) == gb.GLEAM_E_DESC
+    assert bad(lambda p: setattr(p.layers[0], "kh", 2)) == gb.GLEAM_E_DESC
+    assert bad(lambda p: setattr(p.layers[0], "kw", 9)) == gb.GLEAM_E_DESC
+    assert bad(lambda p: setattr(p.layers[1], "skip_src", 1)) == gb.GLEAM_E_DESC   # 4 channels into 2
+    assert bad(lambda p: setattr(p.layers[1], "skip_src", 5)) == gb.GLEAM_E_DESC
+    assert bad(lambda p: setattr(p.layers[1], "relu_out", 1)) == gb.GLEAM_E_DESC   # relu_out with a skip
+    assert bad(lambda p: setattr(p, "dtype", 7)) == gb.GLEAM_E_DESC
+    assert bad(lambda p: setattr(p, "loss_kind", 2)) == gb.GLEAM_E_DESC
+    empty = synth.ProxDesc([])
+    assert _status(gb.gleam_workspace_bytes, geom, gb.make_prox(empty)) == gb.GLEAM_E_DESC
+
+
+def test_null_pointers_and_short_workspace_are_rejected_before_launch():
+    c = synth.make_case(0)
+    geom, prox = gb.make_geom(c.geom), gb.make_prox(c.prox)
+    ws, saved = gb.gleam_workspace_bytes(geom, prox)
+    fake = 0x1000  # 256-byte aligned, never dereferenced: validation fails first
+    L = gb.lib()
+    assert L.gleam_sense_normal(C.byref(geom), None, fake, fake, fake, fake, ws, None) == gb.GLEAM_E_NULL
+    assert L.gleam_sense_normal(C.byref(geom), fake, fake, fake, None, fake, ws, None) == gb.GLEAM_E_NULL
+    assert L.gleam_sense_normal(C.byref(geom), fake, fake, fake, fake, fake, 16, None) == gb.GLEAM_E_WORKSPACE
+    assert L.gleam_sense_normal(C.byref(geom), fake, fake, fake, fake, fake + 8, ws, None) == gb.GLEAM_E_WORKSPACE
+    assert L.gleam_sense_normal(None, fake, fake, fake, fake, fake, ws, None) == gb.GLEAM_E_NULL
+    args = [C.byref(geom), C.byref(prox), fake, fake, fake, fake, C.c_float(1.0), fake, fake, fake, fake,
+            fake, saved, fake, ws, None]
+    for i in (2, 3, 4, 5, 7, 9, 10, 11, 13):
+        a = list(args)
+        a[i] = None
+        assert L.gleam_module_fwd(*a) == gb.GLEAM_E_NULL, i
+    a = list(args); a[12] = saved - 256
+    assert L.gleam_module_fwd(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(args); a[14] = ws - 256
+    assert L.gleam_module_fwd(*a) == gb.GLEAM_E_WORKSPACE
+    bargs = [C.byref(geom), C.byref(prox), fake, fake, saved, fake, fake, ws, None]
+    for i in (2, 3, 5, 6):
+        a = list(bargs)
+        a[i] = None
+        assert L.gleam_module_bwd(*a) == gb.GLEAM_E_NULL, i
+    a = list(bargs); a[4] = 0
+    assert L.gleam_module_bwd(*a) == gb.GLEAM_E_WORKSPACE
+    assert L.gleam_theta_count(C.byref(prox), None) == gb.GLEAM_E_NULL

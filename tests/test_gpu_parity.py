@@ -1,0 +1,154 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the same
+seeded inputs.  Tolerances: relative L2 <= 1e-4 for float32 results; masks and indexing bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gleam_oracle as og
+from paper_2207_08393_amd import binding as gb
+from paper_2207_08393_amd import synth
+from tests.gpu_util import ModuleRunner, rel_l2, run_sense_normal
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+K2, K3, KS, KT = (1, 1, 3, 3), (1, 3, 3, 3), (1, 1, 3, 3), (3, 1, 1, 1)
+
+
+def _tiny_prox():
+    return synth.chain_prox([2, 4, 2], [K2] * 2)
+
+
+SENSE_SHAPES = [
+    # ndim, B, C, T, D, H, W, mask
+    (2, 2, 3, 2, 1, 8, 12, "uniform"),
+    (2, 1, 4, 1, 1, 64, 64, "uniform"),
+    (2, 1, 2, 1, 1, 46, 20, "vd"),          # radix 23 and 5
+    (2, 1, 2, 1, 3, 10, 6, "random2d"),     # D batched, ragged column tiles
+    (2, 2, 2, 3, 1, 96, 24, "equi"),
+    (3, 1, 2, 1, 8, 12, 10, "random2d"),
+    (3, 1, 3, 2, 16, 20, 6, "random2d"),
+    (2, 1, 2, 1, 1, 160, 192, "vd"),
+    (2, 1, 1, 1, 1, 256, 320, "vd"),
+]
+
+
+@pytest.mark.parametrize("shape", SENSE_SHAPES, ids=lambda s: "x".join(map(str, s[:-1])) + s[-1])
+def test_sense_normal_matches_oracle(shape):
+    nd, B, C_, T, D, H, W, kind = shape
+    geom = synth.Geom(nd, B, C_, T, D, H, W)
+    c = synth.make_custom(100 + H + W, geom, _tiny_prox(), accel=3.0, centre=2, mask_kind=kind)
+    print("case", shape, flush=True)
+    got = run_sense_normal(geom, c.x_true, c.S, c.M)
+    ref = og.sense_normal(c.x_true, c.S, c.M, nd)
+    err = rel_l2(got, ref)
+    assert err <= TOL
+
+
+def test_sense_normal_mask_extremes_are_exact():
+    geom = synth.Geom(2, 1, 3, 1, 1, 16, 24)
+    c = synth.make_custom(5, geom, _tiny_prox(), mask_kind="full")
+    zero = run_sense_normal(geom, c.x_true, c.S, np.zeros_like(c.M))
+    assert np.all(zero.view(np.uint32) == 0)                       # bit-exact +0 with nothing sampled
+    full = run_sense_normal(geom, c.x_true, c.S, c.M)
+    assert rel_l2(full, c.x_true) <= TOL                           # A^H A = I under full sampling
+    # a mask with one sampled k-space point per frame: every index must land where the oracle puts it
+    for (h, w) in ((0, 0), (3, 17), (15, 23)):
+        M = np.zeros_like(c.M)
+        M[..., h, w] = 1
+        got = run_sense_normal(geom, c.x_true, c.S, M)
+        ref = og.sense_normal(c.x_true, c.S, M, 2)
+        err = rel_l2(got, ref)
+    assert err <= TOL
+    # any non-zero byte means sampled
+    M7 = (c.M * 7).astype(np.uint8)
+    assert np.array_equal(run_sense_normal(geom, c.x_true, c.S, M7), full)
+
+
+def module_cases():
+    yield "chain2d", synth.Geom(2, 2, 2, 1, 1, 6, 8), synth.chain_prox([2, 5, 4, 2], [K2] * 3), 0
+    yield "res2d", synth.Geom(2, 1, 2, 1, 1, 6, 10), synth.resblock_prox(4, 2), 0
+    yield "chain3d", synth.Geom(3, 1, 2, 1, 4, 6, 4), synth.chain_prox([2, 3, 3, 2], [K3] * 3), 0
+    yield "cine", synth.Geom(2, 1, 2, 4, 1, 6, 4), synth.chain_prox([2, 4, 4, 4, 2], [KS, KT, KS, KT]), 0
+    yield "nobias_l1", synth.Geom(2, 1, 2, 1, 1, 6, 6), synth.chain_prox([2, 4, 2], [K2] * 2, has_bias=0), 1
+    yield "res2d_l1", synth.Geom(2, 2, 3, 1, 1, 12, 10), synth.resblock_prox(8, 1), 1
+    yield "wide2d", synth.Geom(2, 2, 2, 1, 1, 46, 20), synth.chain_prox([2, 40, 72, 2], [K2] * 3), 0
+    yield "res64", synth.Geom(2, 1, 2, 1, 1, 24, 32), synth.resblock_prox(64, 2), 0
+    yield "vol32", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), 0
+    yield "cine64", synth.Geom(2, 1, 2, 6, 1, 12, 16), synth.chain_prox([2, 64, 64, 64, 2], [KS, KT, KS, KT]), 0
+    yield "k5", synth.Geom(2, 1, 2, 1, 1, 10, 12), synth.chain_prox([2, 6, 2], [(1, 1, 5, 5), (1, 1, 1, 5)]), 0
+
+
+def check_module(c, tol=TOL, alpha=None):
+    alpha = c.alpha if alpha is None else alpha
+    r = ModuleRunner(c, alpha=alpha)
+    r.step()
+    x_out, loss, grad = r.results()
+    f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, c.theta, c.x_true)
+    gref = og.module_bwd(c.prox, c.theta, f)
+    errs = (rel_l2(x_out, f["x_out"]), abs(loss - f["loss"]) / abs(f["loss"]), rel_l2(grad, gref))
+    print("rel errors x_out / loss / grad:", errs, flush=True)
+    assert errs[0] <= tol and errs[1] <= tol and errs[2] <= tol
+    return r, f
+
+
+@pytest.mark.parametrize("name,geom,prox,loss_kind", list(module_cases()), ids=[m[0] for m in module_cases()])
+def test_module_fwd_bwd_matches_oracle(name, geom, prox, loss_kind):
+    prox.loss_kind = loss_kind
+    c = synth.make_custom(31, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.8)
+    print("case", name, flush=True)
+    check_module(c)
+
+
+def test_dc_step_alone_through_zero_weights():
+    # chain prox with all-zero parameters is the identity (outer skip), so x_out = DC(x_in) exactly
+    geom = synth.Geom(2, 2, 3, 2, 1, 20, 12)
+    c = synth.make_custom(8, geom, _tiny_prox(), accel=3.0, centre=2, alpha=0.6)
+    r = ModuleRunner(c, theta=np.zeros_like(c.theta))
+    r.fwd()
+    x_out, _, _ = r.results()
+    assert rel_l2(x_out, og.dc_step(c.x_in, c.S, c.M, c.y, 0.6, 2)) <= TOL
+    # junk in y off the mask must not matter
+    junk = c.y + (c.M == 0)[:, None] * (3 + 4j)
+    c2 = synth.Case(**{**c.__dict__, "y": junk.astype(np.complex64)})
+    r2 = ModuleRunner(c2, theta=np.zeros_like(c.theta))
+    r2.fwd()
+    assert np.array_equal(r2.results()[0], x_out)
+
+
+def test_config0_tiny2d_full():
+    c = synth.make_case(0)
+    print("case cfg0", flush=True)
+    r, f = check_module(c)
+    # inference call (no reference, no saved buffer) gives the same x_out
+    x1 = r.results()[0].copy()
+    r.x_out.fill_(float("nan"))
+    r.fwd(with_ref=False)
+    assert np.array_equal(r.results()[0], x1)
+
+
+def test_backward_is_deterministic_and_decoupled():
+    c = synth.make_custom(3, synth.Geom(2, 2, 2, 1, 1, 46, 20), synth.resblock_prox(32, 1), accel=2.0, centre=2)
+    r = ModuleRunner(c)
+    r.step()
+    g1 = r.results()[2].copy()
+    x_in_before = r.x_in.clone()
+    r.grad.fill_(float("nan"))
+    r.step()
+    assert np.array_equal(r.results()[2], g1)                 # bit-identical split-K reduction
+    assert torch.equal(r.x_in, x_in_before)                   # inputs are never written
+    # hand-off: x_out of module 1 is module 2's x_in; module 1's gradient is unaffected by module 2
+    th2 = synth.init_theta(np.random.default_rng(1), c.prox, 0.1)
+    r2 = ModuleRunner(c, theta=th2, x_in=r.results()[0])
+    r2.step()
+    x2, loss2, g2 = r2.results()
+    f1 = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, c.alpha, c.theta, c.x_true)
+    f2 = og.module_fwd(c.geom, c.prox, f1["x_out"], c.S, c.M, c.y, c.alpha, th2, c.x_true)
+    assert rel_l2(x2, f2["x_out"]) <= TOL and rel_l2(g2, og.module_bwd(c.prox, th2, f2)) <= TOL
+
+
+@pytest.mark.timeout(900)
+def test_config1_knee2d_full_size():
+    """The benchmark workload at full size, every output element against the oracle."""
+    c = synth.make_case(1)
+    print("case cfg1 (oracle takes ~1 min on the host cores)", flush=True)
+    check_module(c)
