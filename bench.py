@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the GLEAM module step on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one gleam_module_fwd + one gleam_module_bwd (data-consistency step, prox forward, local loss,
+module-confined backward) on the knee-shaped 2D workload (640x368, 15 coils, batch 2, fp32, 64-channel
+two-resblock prox), all inputs resident in HBM before the timed region.  Prints ONE JSON line with the
+module steps/s, the roofline of the dominant kernel (HIP-event timed inside the library), the SENSE normal
+operator's bandwidth, and the CPU oracle timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+# HBM traffic per launch (bytes) of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this same command, scaled by the copy-kernel calibration; None until measured for the workload.
+MEASURED_TRAFFIC = {}
+
+
+def aggregate(records):
+    agg = {}
+    for name, flops, nbytes, ms in records:
+        a = agg.setdefault(name, {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
+        a["launches"] += 1
+        a["ms"] += ms
+        a["flops"] += flops
+        a["bytes"] += nbytes
+    return agg
+
+
+def cpu_baseline(case):
+    """Times the oracle (as it stands) on one sample of the batch; returns steps/s scaled to the batch."""
+    import numpy as np
+    from oracle import gleam_oracle as og
+    from paper_2207_08393_amd import synth
+    g = case.geom
+    g1 = synth.Geom(g.ndim_fft, 1, g.C, g.T, g.D, g.H, g.W)
+    t0 = time.perf_counter()
+    f = og.module_fwd(g1, case.prox, case.x_in[:1], case.S[:1], case.M[:1], case.y[:1], case.alpha, case.theta,
+                      case.x_true[:1])
+    og.module_bwd(case.prox, case.theta, f)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": 1.0 / (dt * g.B), "unit": "module steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of {g.B} batch samples (one fwd+bwd of the float64 numpy oracle took {dt:.1f} s), "
+                      f"scaled by 1/{g.B}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2207_08393_amd import binding as gb
+    from paper_2207_08393_amd import synth
+    from paper_2207_08393_amd.runner import ModuleRunner, SenseRunner
+
+    case = synth.make_case(1)
+    g = case.geom
+    r = ModuleRunner(case)
+    sr = SenseRunner(g, case.x_in, case.S, case.M)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        r.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        r.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+
+    # the same steps again with every kernel bracketed by HIP events on the launch stream
+    gb.gleam_profile_begin()
+    for _ in range(args.steps):
+        r.step()
+    agg = aggregate(gb.gleam_profile_end())
+    mfma = {k: v for k, v in agg.items() if k.startswith("conv_")}
+    dom = max(mfma, key=lambda k: mfma[k]["ms"])
+    d = mfma[dom]
+    avg_ms = d["ms"] / d["launches"]
+    achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "avg_launch_ms": avg_ms,
+                "launches_per_step": d["launches"] / args.steps, "traffic": MEASURED_TRAFFIC.get(dom)}
+    conv_ms = sum(v["ms"] for v in mfma.values())
+    conv_tflops = sum(v["flops"] for v in mfma.values()) / (conv_ms * 1e-3) / 1e12
+    kernels = {k: {"avg_ms": v["ms"] / v["launches"], "per_step": v["launches"] / args.steps,
+                   "tflops": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["flops"] else None,
+                   "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9} for k, v in sorted(agg.items())}
+
+    # SENSE normal operator A^H A on its own: algorithmic bytes / event time of its three sweeps
+    for _ in range(args.warmup):
+        sr.run()
+    torch.cuda.synchronize()
+    gb.gleam_profile_begin()
+    for _ in range(args.steps):
+        sr.run()
+    sagg = aggregate(gb.gleam_profile_end())
+    s_ms = sum(v["ms"] for v in sagg.values()) / args.steps
+    s_bytes = sum(v["bytes"] for v in sagg.values()) / args.steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sr.run()
+    torch.cuda.synchronize()
+    s_wall_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    sense = {"bound": "hbm", "achieved": s_bytes / (s_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": s_bytes / (s_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "algorithmic_bytes": s_bytes,
+             "kernel_ms": s_ms, "wall_ms_per_call": s_wall_ms,
+             "sweeps": {k: v["ms"] / v["launches"] for k, v in sagg.items()}}
+
+    out = {"metric": "GLEAM module fwd+bwd steps/s", "value": args.steps / dt, "unit": "module steps/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": case.name, "image": [g.H, g.W], "coils": g.C, "batch": g.B,
+                      "prox": "2 pre-activation resblocks, 64 ch, 3x3, 6 convs", "loss": "l2",
+                      "modules_per_greedy_iteration": case.n_modules},
+           "roofline": roofline,
+           "conv_all": {"tflops": conv_tflops, "frac_of_fp32_mfma_peak": conv_tflops / PEAK_FP32_MFMA_TFLOPS,
+                        "ms_per_step": conv_ms / args.steps},
+           "sense_normal": sense, "kernels": kernels,
+           "greedy_iterations_per_s": args.steps / dt / case.n_modules}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

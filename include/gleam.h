@@ -114,6 +114,20 @@ int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const 
                      const void* saved, size_t saved_bytes, float* grad_theta,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* Measurement aid (not part of the method): between gleam_profile_begin and gleam_profile_end every kernel
+ * this library launches is bracketed by HIP events on the caller's stream.  gleam_profile_end synchronises
+ * the device and copies up to `capacity` per-launch records (launch order) to the HOST array `out`;
+ * *n_records receives the number of launches seen.  `flops` / `bytes` are the algorithmic work of the launch
+ * (padding and re-reads not counted).  Not thread-safe; leave it off in production. */
+typedef struct {
+    char name[56];
+    double flops;
+    double bytes;
+    float ms;
+} gleam_kernel_record;
+int gleam_profile_begin(void);
+int gleam_profile_end(gleam_kernel_record* out, int capacity, int* n_records);
+
 /* Static message for a gleam_status value. */
 const char* gleam_strerror(int status);
 

@@ -37,6 +37,10 @@ class gleam_prox_desc(C.Structure):
                 ("loss_kind", C.c_int32)]
 
 
+class gleam_kernel_record(C.Structure):
+    _fields_ = [("name", C.c_char * 56), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
+
+
 class GleamError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -64,12 +68,15 @@ def lib() -> C.CDLL:
         L.gleam_sense_normal.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
         L.gleam_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_module_bwd.argtypes = [pg, pp, vp, vp, sz, vp, vp, sz, vp]
+        L.gleam_profile_begin.argtypes = []
+        L.gleam_profile_end.argtypes = [C.POINTER(gleam_kernel_record), C.c_int, C.POINTER(C.c_int)]
         _lib = L
     return _lib
 
 
 EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
-           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd")
+           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_profile_begin",
+           "gleam_profile_end")
 
 
 def strerror(status: int) -> str:
@@ -152,3 +159,15 @@ def gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref, x_out, loss
 def gleam_module_bwd(geom, prox, theta, saved, grad_theta, ws, stream=None):
     _check(lib().gleam_module_bwd(C.byref(geom), C.byref(prox), _ptr(theta), _ptr(saved), _nbytes(saved),
                                   _ptr(grad_theta), _ptr(ws), _nbytes(ws), _stream(stream)), "gleam_module_bwd")
+
+
+def gleam_profile_begin():
+    _check(lib().gleam_profile_begin(), "gleam_profile_begin")
+
+
+def gleam_profile_end(capacity: int = 65536):
+    """Returns a list of (name, flops, bytes, ms), one per kernel launch since gleam_profile_begin."""
+    arr = (gleam_kernel_record * capacity)()
+    n = C.c_int(0)
+    _check(lib().gleam_profile_end(arr, capacity, C.byref(n)), "gleam_profile_end")
+    return [(arr[i].name.decode(), arr[i].flops, arr[i].bytes, arr[i].ms) for i in range(min(n.value, capacity))]

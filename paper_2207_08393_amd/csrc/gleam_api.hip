@@ -4,11 +4,38 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
+#include <cstring>
 #include <vector>
 
 #include "internal.h"
 
 using namespace gleam;
+
+namespace gleam {
+namespace {
+struct ProfRec {
+    char name[56];
+    double flops, bytes;
+    hipEvent_t e0, e1;
+};
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+}  // namespace
+bool prof_enabled() { return g_prof_on; }
+void prof_begin(const char* name, double flops, double bytes, hipStream_t st) {
+    ProfRec r{};
+    snprintf(r.name, sizeof(r.name), "%s", name);
+    r.flops = flops;
+    r.bytes = bytes;
+    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+    (void)hipEventRecord(r.e0, st);
+    g_prof.push_back(r);
+}
+void prof_end(hipStream_t st) {
+    if (!g_prof.empty()) (void)hipEventRecord(g_prof.back().e1, st);
+}
+}  // namespace gleam
 
 namespace {
 
@@ -76,6 +103,34 @@ const char* gleam_strerror(int status) {
         case GLEAM_E_LAUNCH: return "HIP launch failed";
         default: return "unknown gleam status";
     }
+}
+
+int gleam_profile_begin(void) {
+    for (auto& r : g_prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+    g_prof.clear();
+    g_prof_on = true;
+    return GLEAM_OK;
+}
+
+int gleam_profile_end(gleam_kernel_record* out, int capacity, int* n_records) {
+    g_prof_on = false;
+    if (!n_records || (capacity > 0 && !out)) return GLEAM_E_NULL;
+    if (hipDeviceSynchronize() != hipSuccess) return GLEAM_E_LAUNCH;
+    *n_records = (int)g_prof.size();
+    for (int i = 0; i < (int)g_prof.size(); ++i) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, g_prof[i].e0, g_prof[i].e1);
+        if (i < capacity) {
+            memcpy(out[i].name, g_prof[i].name, sizeof(out[i].name));
+            out[i].flops = g_prof[i].flops;
+            out[i].bytes = g_prof[i].bytes;
+            out[i].ms = ms;
+        }
+        (void)hipEventDestroy(g_prof[i].e0);
+        (void)hipEventDestroy(g_prof[i].e1);
+    }
+    g_prof.clear();
+    return GLEAM_OK;
 }
 
 int gleam_fft_size_supported(int64_t n) { return fft_size_supported(n) ? 1 : 0; }

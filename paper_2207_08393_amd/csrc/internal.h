@@ -14,6 +14,22 @@ constexpr int kMaxTaps = 32;  // per-pixel tap validity is kept as one 32-bit ma
 
 bool fft_size_supported(long long n);
 
+// Optional per-launch event bracketing (see gleam_profile_begin).  KernelScope records a start event at
+// construction and a stop event at destruction when profiling is on, and does nothing otherwise.
+bool prof_enabled();
+void prof_begin(const char* name, double flops, double bytes, hipStream_t st);
+void prof_end(hipStream_t st);
+struct KernelScope {
+    hipStream_t st;
+    bool on;
+    KernelScope(const char* name, double flops, double bytes, hipStream_t s) : st(s), on(prof_enabled()) {
+        if (on) prof_begin(name, flops, bytes, st);
+    }
+    ~KernelScope() {
+        if (on) prof_end(st);
+    }
+};
+
 // out = xs*x + gs * S^H F^H Omega (F S x - y); y may be null (then y = 0).  kbuf holds B*C*T*D*H*W
 // complex values and is overwritten.  Everything is enqueued on `st`.
 hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const unsigned char* M,

@@ -12,6 +12,8 @@
 // index and never ragged except at the very end of the tensor.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
 #include "internal.h"
 
 namespace gleam {
@@ -225,6 +227,10 @@ static hipError_t launch_conv_t(const ConvArgs& a, hipStream_t st) {
 }
 
 static hipError_t launch_conv(const ConvArgs& a, hipStream_t st) {
+    const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
+    char name[56];
+    snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
+    KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, 4.0 * (double)a.d.Q * (a.K + a.Nn), st);
     const int ck = a.K <= 8 ? 8 : (a.K <= 16 ? 16 : 32);
     if (a.Nn <= 32) {
         if (ck == 8) return launch_conv_t<32, 8>(a, st);
@@ -479,6 +485,7 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
         const long long n = plan.Q;
         double* part = reinterpret_cast<double*>((unsigned char*)ws + plan.red_off);
         float2* gz = reinterpret_cast<float2*>(act_base + plan.gz_off);
+        KernelScope ks("loss", 0.0, 24.0 * (double)n, st);
         hipLaunchKernelGGL(loss_kernel, dim3(kLossBlocks), dim3(256), 0, st, (const float2*)x_out, x_ref, gz, n,
                            p.loss_kind, (float)(1.0 / (double)n), p.layers[L - 1].relu_out, part);
         hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, kLossBlocks, 1.0 / (double)n, loss);
@@ -490,6 +497,9 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
 static hipError_t launch_wgrad(const WgradArgs& a, int n_split, hipStream_t st) {
     const PixDims& d = a.d;
     const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
+    char name[56];
+    snprintf(name, sizeof(name), "conv_wgrad_%dto%d_t%d", a.Ci, a.Co, taps);
+    KernelScope ks(name, 2.0 * (double)d.Q * a.Ci * a.Co * taps, 4.0 * (double)d.Q * (a.Ci + a.Co), st);
     const int RSg = (a.Co + 3) / 4 * 4 + 1, RSa = (a.Ci + 3) / 4 * 4 + 1;
     const size_t lds = ((size_t)kWgTM * RSg + (size_t)rowtaps * (kWgTM + d.kw - 1) * RSa + kWgTM) * sizeof(float);
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
@@ -543,9 +553,13 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         hipError_t e = launch_wgrad(wa, plan.n_split, st);
         if (e != hipSuccess) return e;
         const long long nw = (long long)(c.cout * taps * c.cin);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st,
-                           (const float*)partial, plan.n_split, nw, grad_theta + plan.w_off[l - 1]);
+        {
+            KernelScope ks("wgrad_reduce", 0.0, 4.0 * (double)nw * (plan.n_split + 1), st);
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st,
+                               (const float*)partial, plan.n_split, nw, grad_theta + plan.w_off[l - 1]);
+        }
         if (c.has_bias) {
+            KernelScope ks("bias_grad", 0.0, 4.0 * (double)plan.Q * c.cout, st);
             hipLaunchKernelGGL(colsum_kernel, dim3(plan.n_split), dim3(256), 0, st, (const float*)G(l), plan.Q, c.cout, partial);
             hipLaunchKernelGGL(reduce_partials_kernel, dim3((c.cout + 255) / 256), dim3(256), 0, st,
                                (const float*)partial, plan.n_split, (long long)c.cout, grad_theta + plan.b_off[l - 1]);

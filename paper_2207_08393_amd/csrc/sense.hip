@@ -283,7 +283,14 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
     ra.scale = 1.0f / sqrtf((float)g.W);
     ra.xs = xs; ra.gs = gs;
     ra.n_rows = g.B * g.C * g.T * DH;
-    hipError_t e = launch_rows(false, (int)g.W, ra, st);
+    const double E8 = 8.0 * (double)(g.B * g.C * g.T * g.D * g.H * g.W);   // bytes of one k-space sweep
+    const double P8 = 8.0 * (double)(g.B * g.T * g.D * g.H * g.W);          // bytes of one image
+    const double S8 = E8 / (double)g.T, M1 = P8 / 8.0;
+    hipError_t e;
+    {
+        KernelScope ks("sense_rows_expand", 0.0, S8 + P8 + E8, st);
+        e = launch_rows(false, (int)g.W, ra, st);
+    }
     if (e != hipSuccess) return e;
 
     ColsArgs ca{};
@@ -291,22 +298,35 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
     if (g.ndim_fft == 2) {
         ca.outer = g.B * g.C * g.T * g.D; ca.inner = g.W; ca.Dq = g.D;
         ca.scale = 1.0f / sqrtf((float)g.H);
-        e = launch_cols(2, (int)g.H, ca, st);
+        {
+            KernelScope ks("sense_cols_mid", 0.0, 2.0 * E8 + (y ? E8 : 0.0) + M1, st);
+            e = launch_cols(2, (int)g.H, ca, st);
+        }
         if (e != hipSuccess) return e;
     } else {
         ColsArgs ha = ca;  // H axis: [B*C*T*D][H][W]
         ha.outer = g.B * g.C * g.T * g.D; ha.inner = g.W; ha.Dq = g.D;
         ha.scale = 1.0f / sqrtf((float)g.H);
-        e = launch_cols(0, (int)g.H, ha, st);
+        {
+            KernelScope ks("sense_cols_fwd", 0.0, 2.0 * E8, st);
+            e = launch_cols(0, (int)g.H, ha, st);
+        }
         if (e != hipSuccess) return e;
         ca.outer = g.B * g.C * g.T; ca.inner = g.H * g.W; ca.Dq = 1;  // D axis: [B*C*T][D][H*W]
         ca.scale = 1.0f / sqrtf((float)g.D);
-        e = launch_cols(2, (int)g.D, ca, st);
+        {
+            KernelScope ks("sense_cols_mid", 0.0, 2.0 * E8 + (y ? E8 : 0.0) + M1, st);
+            e = launch_cols(2, (int)g.D, ca, st);
+        }
         if (e != hipSuccess) return e;
-        e = launch_cols(1, (int)g.H, ha, st);
+        {
+            KernelScope ks("sense_cols_inv", 0.0, 2.0 * E8, st);
+            e = launch_cols(1, (int)g.H, ha, st);
+        }
         if (e != hipSuccess) return e;
     }
     ra.n_rows = g.B * g.T * DH;
+    KernelScope ks("sense_rows_reduce", 0.0, E8 + S8 + P8 + (xs != 0.f ? P8 : 0.0), st);
     return launch_rows(true, (int)g.W, ra, st);
 }
 

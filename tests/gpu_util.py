@@ -1,8 +1,7 @@
-"""Helpers for the GPU parity tests: run a synth.Case through the C ABI binding."""
+"""Helpers for the GPU parity tests."""
 import numpy as np
-import torch
 
-from paper_2207_08393_amd import binding as gb
+from paper_2207_08393_amd.runner import ModuleRunner, SenseRunner  # noqa: F401
 
 
 def rel_l2(a, b):
@@ -11,65 +10,7 @@ def rel_l2(a, b):
     return float(np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(b.ravel()), 1e-300))
 
 
-def dev(a):
-    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
-
-
-def cplx(a):
-    """complex64 numpy -> device tensor [..., 2] float32 (interleaved re, im)."""
-    a = np.ascontiguousarray(np.asarray(a, np.complex64))
-    return torch.from_numpy(a.view(np.float32).reshape(a.shape + (2,))).cuda()
-
-
-def to_complex(t):
-    return t.cpu().numpy().view(np.complex64).reshape(t.shape[:-1])
-
-
-def byte_buffer(n):
-    return torch.empty(max(int(n), 256), dtype=torch.uint8, device="cuda")
-
-
 def run_sense_normal(geom, x, S, M):
-    g = gb.make_geom(geom)
-    ws_bytes, _ = gb.gleam_workspace_bytes(g, None)
-    ws = byte_buffer(ws_bytes)
-    out = torch.full(tuple(geom.image_shape) + (2,), float("nan"), device="cuda")
-    gb.gleam_sense_normal(g, cplx(x), cplx(S), dev(M), out, ws)
-    torch.cuda.synchronize()
-    return to_complex(out)
-
-
-class ModuleRunner:
-    """Device-resident copy of a case; `step()` = one gleam_module_fwd + gleam_module_bwd."""
-
-    def __init__(self, case, theta=None, alpha=None, x_in=None):
-        self.case = case
-        self.geom = gb.make_geom(case.geom)
-        self.prox = gb.make_prox(case.prox)
-        self.ws_bytes, self.saved_bytes = gb.gleam_workspace_bytes(self.geom, self.prox)
-        self.ws = byte_buffer(self.ws_bytes)
-        self.saved = byte_buffer(self.saved_bytes)
-        self.x_in = cplx(case.x_in if x_in is None else x_in)
-        self.S, self.M, self.y = cplx(case.S), dev(case.M), cplx(case.y)
-        self.x_ref = cplx(case.x_true)
-        self.theta = dev(np.asarray(case.theta if theta is None else theta, np.float32))
-        self.alpha = float(case.alpha if alpha is None else alpha)
-        self.x_out = torch.full_like(self.x_in, float("nan"))
-        self.loss = torch.full((1,), float("nan"), device="cuda")
-        self.grad = torch.full_like(self.theta, float("nan"))
-
-    def fwd(self, with_ref=True):
-        gb.gleam_module_fwd(self.geom, self.prox, self.x_in, self.S, self.M, self.y, self.alpha, self.theta,
-                            self.x_ref if with_ref else None, self.x_out, self.loss if with_ref else None,
-                            self.saved if with_ref else None, self.ws)
-
-    def bwd(self):
-        gb.gleam_module_bwd(self.geom, self.prox, self.theta, self.saved, self.grad, self.ws)
-
-    def step(self):
-        self.fwd()
-        self.bwd()
-
-    def results(self):
-        torch.cuda.synchronize()
-        return to_complex(self.x_out), float(self.loss.item()), self.grad.cpu().numpy()
+    r = SenseRunner(geom, x, S, M)
+    r.run()
+    return r.result()
