@@ -336,12 +336,315 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_mfma_kernel(WgradArgs a) {
     }
 }
 
+// Pipelined weight gradient for channel counts that are multiples of 4: the next 32-pixel chunk is
+// fetched into registers (float4) while the MFMAs of the current chunk run from LDS, so global latency
+// hides behind the matrix pipe.  Same job layout as wgrad_mfma_kernel.  Optionally accumulates the bias
+// gradient (column sums of g) from the values it stages anyway.
+struct WgradPipeArgs {
+    WgradArgs w;
+    float* bias_partial;  // [n_split][Co] or null
+};
+
+template <int JT, int PG, int PA>
+__global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs pa) {
+    extern __shared__ float smem[];
+    const WgradArgs& a = pa.w;
+    const PixDims d = a.d;
+    const int Co4 = a.Co / 4, Ci4 = a.Ci / 4;
+    const int RSg = a.Co + 4, RSa = a.Ci + 4;
+    const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
+    const int n_pa = kWgTM + d.kw - 1;
+    float* gs = smem;                          // [kWgTM][RSg]
+    float* as = gs + kWgTM * RSg;              // [rowtaps][n_pa][RSa]
+    unsigned* vmask = reinterpret_cast<unsigned*>(as + rowtaps * n_pa * RSa);  // [kWgTM]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, m = lane & 31, h = lane >> 5;
+    const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32, tapgroups = (taps + JT - 1) / JT;
+    const int job = blockIdx.y * 4 + wave;
+    const bool active = job < ncb * nib * tapgroups;
+    const int tg = job % tapgroups, pair = job / tapgroups;
+    const int cb = pair / nib, ib = pair % nib;
+    const int tap0 = tg * JT;
+    const int n_g4 = kWgTM * Co4, n_a4 = rowtaps * n_pa * Ci4;
+
+    // Per-thread staging descriptors: the float4 slots this thread moves are the same for every chunk.
+    int g_lds[PG], g_dq[PG], g_c[PG];
+    int a_lds[PA], a_dq[PA], a_c[PA];
+#pragma unroll
+    for (int i = 0; i < PG; ++i) {
+        const int v = tid + i * kConvThreads;
+        const int p = v / Co4, c4 = v % Co4;
+        g_lds[i] = v < n_g4 ? p * RSg + 4 * c4 : -1;
+        g_dq[i] = p;
+        g_c[i] = 4 * c4;
+    }
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+        const int v = tid + i * kConvThreads;
+        const int rt = v / (n_pa * Ci4), r = v % (n_pa * Ci4);
+        const int p = r / Ci4, c4 = r % Ci4;
+        a_lds[i] = v < n_a4 ? (rt * n_pa + p) * RSa + 4 * c4 : -1;
+        a_dq[i] = v < n_a4 ? (int)rowtap_offset(rt, d) - d.kw / 2 + p : 0;
+        a_c[i] = 4 * c4;
+    }
+    float4 rg[PG], ra[PA], bsum[PG];
+#pragma unroll
+    for (int i = 0; i < PG; ++i) bsum[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    auto fetch = [&](long long q0) {
+#pragma unroll
+        for (int i = 0; i < PG; ++i) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            const long long qq = q0 + g_dq[i];
+            if (g_lds[i] >= 0 && qq < d.Q) v = *reinterpret_cast<const float4*>(a.g + qq * a.Co + g_c[i]);
+            rg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            const long long qq = q0 + a_dq[i];
+            if (a_lds[i] >= 0 && qq >= 0 && qq < d.Q) v = *reinterpret_cast<const float4*>(a.a + qq * a.Ci + a_c[i]);
+            if (a.relu_in) {
+                v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+            }
+            ra[i] = v;
+        }
+    };
+    auto stash = [&](long long q0) {
+#pragma unroll
+        for (int i = 0; i < PG; ++i)
+            if (g_lds[i] >= 0) {
+                *reinterpret_cast<float4*>(gs + g_lds[i]) = rg[i];
+                bsum[i].x += rg[i].x; bsum[i].y += rg[i].y; bsum[i].z += rg[i].z; bsum[i].w += rg[i].w;
+            }
+#pragma unroll
+        for (int i = 0; i < PA; ++i)
+            if (a_lds[i] >= 0) *reinterpret_cast<float4*>(as + a_lds[i]) = ra[i];
+        if (tid < kWgTM) vmask[tid] = tap_validity(q0 + tid, d);
+    };
+
+    floatx16 acc[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    // per-lane LDS read bases
+    const int co = cb * 32 + m, ci = ib * 32 + m;
+    const bool co_ok = active && co < a.Co, ci_ok = active && ci < a.Ci;
+    int b_off[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j) {
+        const int tap = tap0 + j;
+        const int rt = tap / d.kw, dw = tap % d.kw;
+        b_off[j] = (rt * n_pa + dw + h) * RSa + ci;
+    }
+    const int a_off = h * RSg + co;
+
+    const long long n_chunks = (d.Q + kWgTM - 1) / kWgTM;
+    long long chunk = blockIdx.x;
+    if (chunk < n_chunks) {
+        fetch(chunk * kWgTM);
+        stash(chunk * kWgTM);
+    }
+    __syncthreads();
+    for (; chunk < n_chunks; chunk += gridDim.x) {
+        const long long next = chunk + gridDim.x;
+        if (next < n_chunks) fetch(next * kWgTM);
+        if (co_ok || ci_ok) {
+#pragma unroll 2
+            for (int s = 0; s < kWgTM / 2; ++s) {
+                const float av = co_ok ? gs[a_off + 2 * s * RSg] : 0.f;
+                const unsigned vm = vmask[2 * s + h];
+#pragma unroll
+                for (int j = 0; j < JT; ++j) {
+                    if (tap0 + j < taps) {
+                        float bv = ci_ok ? as[b_off[j] + 2 * s * RSa] : 0.f;
+                        bv = ((vm >> (tap0 + j)) & 1u) ? bv : 0.f;
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (next < n_chunks) stash(next * kWgTM);
+        __syncthreads();
+    }
+    if (active) {
+        float* dst = a.partial + (size_t)blockIdx.x * a.Co * taps * a.Ci;
+#pragma unroll
+        for (int j = 0; j < JT; ++j) {
+            const int tap = tap0 + j;
+            if (tap >= taps || ci >= a.Ci) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int cc = cb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (cc < a.Co) dst[((size_t)cc * taps + tap) * a.Ci + ci] = acc[j][r];
+            }
+        }
+    }
+    if (pa.bias_partial != nullptr && blockIdx.y == 0) {
+        // thread (tid, i) summed channels g_c[i]..+3 over its pixels; fold the pixel lanes through LDS
+        __syncthreads();
+        float4* red = reinterpret_cast<float4*>(smem);  // [PG*256] float4 <= staging area
+#pragma unroll
+        for (int i = 0; i < PG; ++i) red[tid + i * kConvThreads] = g_lds[i] >= 0 ? bsum[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        __syncthreads();
+        if (tid < a.Co) {
+            const int c4 = tid / 4, e = tid % 4;
+            float t = 0.f;
+            for (int v = c4; v < PG * kConvThreads; v += Co4) {
+                const float4 x = red[v];
+                t += e == 0 ? x.x : (e == 1 ? x.y : (e == 2 ? x.z : x.w));
+            }
+            pa.bias_partial[(size_t)blockIdx.x * a.Co + tid] = t;
+        }
+    }
+}
+
+// Weight gradient of a layer whose input OR output has very few channels (the 2-channel image side):
+// HBM-bound, so no MFMA.  Lanes index the wide channel dimension; the wide tensor is read once per
+// pixel (coalesced), the thin tensor at the tap-shifted pixel is wave-uniform.
+//   THIN_IN  (cin thin):  dw[co][tap][ci] += g[q][co] * a[q + off(tap)][ci]          lanes = co
+//   !THIN_IN (cout thin): dw[co][tap][ci] += a[q'][ci] * g[q' - off(tap)][co]        lanes = ci
+struct WgradThinArgs {
+    const float* wide;   // [Q][WC]
+    const float* thin;   // [Q][TH]
+    float* partial;      // [n_split][Co][taps][Ci]
+    float* bias_partial; // [n_split][Co] or null
+    int WC;              // wide channels (<= 256, 256 % round64(WC) == 0)
+    int relu_in;
+    PixDims d;
+};
+
+template <int KT, int KD, int KH, int KW, int TH, bool THIN_IN>
+__global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
+    constexpr int TAPS = KT * KD * KH * KW;
+    __shared__ float red[256];
+    const PixDims d = a.d;
+    const int WCr = (a.WC + 63) / 64 * 64;
+    const int groups = 256 / WCr;
+    const int c = threadIdx.x % WCr;
+    const int pg = __builtin_amdgcn_readfirstlane(threadIdx.x / WCr);
+    const bool c_ok = c < a.WC;
+    const long long n_runs = (long long)gridDim.x * groups;
+    const long long run_len = (d.Q + n_runs - 1) / n_runs;
+    const long long qa = ((long long)blockIdx.x * groups + pg) * run_len;
+    const long long qb = qa + run_len < d.Q ? qa + run_len : d.Q;
+
+    float acc[TAPS][TH];
+    float bs[THIN_IN ? 1 : TH];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int e = 0; e < TH; ++e) acc[t][e] = 0.f;
+#pragma unroll
+    for (int e = 0; e < (THIN_IN ? 1 : TH); ++e) bs[e] = 0.f;
+
+    if (qa < qb) {
+        int w = (int)(qa % d.W);
+        long long r = qa / d.W;
+        int hh = (int)(r % d.H);
+        r /= d.H;
+        int dd = (int)(r % d.D);
+        r /= d.D;
+        int tt = (int)(r % d.T);
+        constexpr int sgn = THIN_IN ? 1 : -1;
+        for (long long q = qa; q < qb; ++q) {
+            float wv = c_ok ? a.wide[q * a.WC + c] : 0.f;
+            if (!THIN_IN && a.relu_in) wv = fmaxf(wv, 0.f);
+            if (THIN_IN) bs[0] += wv;
+#pragma unroll
+            for (int it = 0; it < KT; ++it)
+#pragma unroll
+                for (int id = 0; id < KD; ++id)
+#pragma unroll
+                    for (int ih = 0; ih < KH; ++ih)
+#pragma unroll
+                        for (int iw = 0; iw < KW; ++iw) {
+                            const int ot = sgn * (it - KT / 2), od = sgn * (id - KD / 2);
+                            const int oh = sgn * (ih - KH / 2), ow = sgn * (iw - KW / 2);
+                            const bool ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D &&
+                                            hh + oh >= 0 && hh + oh < d.H && w + ow >= 0 && w + ow < d.W;
+                            if (ok) {
+                                const long long qq = q + (((long long)ot * d.D + od) * d.H + oh) * d.W + ow;
+                                const int tap = ((it * KD + id) * KH + ih) * KW + iw;
+#pragma unroll
+                                for (int e = 0; e < TH; ++e) {
+                                    float tv = a.thin[qq * TH + e];
+                                    if (THIN_IN && a.relu_in) tv = fmaxf(tv, 0.f);
+                                    acc[tap][e] = fmaf(wv, tv, acc[tap][e]);
+                                }
+                            }
+                        }
+            if (!THIN_IN) {
+#pragma unroll
+                for (int e = 0; e < TH; ++e) bs[e] += a.thin[q * TH + e];
+            }
+            if (++w == d.W) {
+                w = 0;
+                if (++hh == d.H) {
+                    hh = 0;
+                    if (++dd == d.D) {
+                        dd = 0;
+                        if (++tt == d.T) tt = 0;
+                    }
+                }
+            }
+        }
+    }
+    // fold the pixel groups of this workgroup, then write the partial in dw layout
+    const int Co = THIN_IN ? a.WC : TH, Ci = THIN_IN ? TH : a.WC;
+    float* dst = a.partial + (size_t)blockIdx.x * Co * TAPS * Ci;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int e = 0; e < TH; ++e) {
+            __syncthreads();
+            red[threadIdx.x] = acc[t][e];
+            __syncthreads();
+            if (pg == 0 && c_ok) {
+                float sum = 0.f;
+                for (int g2 = 0; g2 < groups; ++g2) sum += red[g2 * WCr + c];
+                const size_t o = THIN_IN ? ((size_t)c * TAPS + t) * Ci + e : ((size_t)e * TAPS + t) * Ci + c;
+                dst[o] = sum;
+            }
+        }
+    if (a.bias_partial != nullptr) {
+#pragma unroll
+        for (int e = 0; e < (THIN_IN ? 1 : TH); ++e) {
+            __syncthreads();
+            red[threadIdx.x] = bs[e];
+            __syncthreads();
+            if (THIN_IN) {
+                if (pg == 0 && c_ok) {
+                    float sum = 0.f;
+                    for (int g2 = 0; g2 < groups; ++g2) sum += red[g2 * WCr + c];
+                    a.bias_partial[(size_t)blockIdx.x * Co + c] = sum;
+                }
+            } else if (threadIdx.x == 0) {
+                float sum = 0.f;
+                for (int g2 = 0; g2 < groups; ++g2) sum += red[g2 * WCr];
+                a.bias_partial[(size_t)blockIdx.x * Co + e] = sum;
+            }
+        }
+    }
+}
+
 // out[i] = sum_s partial[s][i], s ascending (fixed order => run-to-run identical bits).
 __global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_split, long long n, float* __restrict__ out) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     float s = 0.f;
-    for (int k = 0; k < n_split; ++k) s += partial[(size_t)k * n + i];
+    int k = 0;
+    for (; k + 8 <= n_split; k += 8) {  // 8 independent loads in flight, summed in ascending order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(k + u) * n + i];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; k < n_split; ++k) s += partial[(size_t)k * n + i];
     out[i] = s;
 }
 
@@ -397,10 +700,15 @@ __global__ __launch_bounds__(256) void loss_kernel(const float2* __restrict__ z,
 }
 
 __global__ void loss_final_kernel(const double* __restrict__ part, int n_part, double inv_n, float* __restrict__ loss) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        double s = 0.0;
-        for (int i = 0; i < n_part; ++i) s += part[i];
-        *loss = (float)(s * inv_n);
+    __shared__ double red[64];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n_part; i += 64) s += part[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int i = 0; i < 64; ++i) t += red[i];
+        *loss = (float)(t * inv_n);
     }
 }
 
@@ -449,8 +757,10 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     }
     plan.grad_off[L] = 0;  // G_L = g_z lives in saved
     plan.partial_off = w;
-    plan.partial_bytes = align256((size_t)plan.n_split * (max_w > (size_t)kMaxChannels ? max_w : (size_t)kMaxChannels) * sizeof(float));
+    plan.partial_bytes = align256((size_t)plan.n_split * max_w * sizeof(float));
     w += plan.partial_bytes;
+    plan.bias_partial_off = w;
+    w += align256((size_t)plan.n_split * kMaxChannels * sizeof(float));
     const size_t bwd_ws = w;
 
     plan.red_off = 0;  // loss partials reuse the head of the k-space buffer once DC is done
@@ -494,18 +804,85 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
     return hipSuccess;
 }
 
-static hipError_t launch_wgrad(const WgradArgs& a, int n_split, hipStream_t st) {
+template <int JT, int PG, int PA>
+static void launch_wgrad_pipe_t(const WgradPipeArgs& pa, dim3 grid, size_t lds, hipStream_t st) {
+    static bool once = false;
+    if (!once) {
+        (void)hipFuncSetAttribute((const void*)wgrad_pipe_kernel<JT, PG, PA>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        once = true;
+    }
+    if (lds < (size_t)PG * kConvThreads * sizeof(float4)) lds = (size_t)PG * kConvThreads * sizeof(float4);
+    hipLaunchKernelGGL((wgrad_pipe_kernel<JT, PG, PA>), grid, dim3(kConvThreads), lds, st, pa);
+}
+
+template <int KT, int KD, int KH, int KW>
+static void launch_wgrad_thin_t(const WgradArgs& a, float* bias_partial, int n_split, hipStream_t st) {
+    WgradThinArgs t{};
+    t.partial = a.partial; t.bias_partial = bias_partial; t.relu_in = a.relu_in; t.d = a.d;
+    if (a.Ci == 2) {
+        t.wide = a.g; t.thin = a.a; t.WC = a.Co;
+        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, true>), dim3(n_split), dim3(256), 0, st, t);
+    } else {
+        t.wide = a.a; t.thin = a.g; t.WC = a.Ci;
+        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, false>), dim3(n_split), dim3(256), 0, st, t);
+    }
+}
+
+// Launches the weight-gradient kernel that fits the layer.  *bias_done is set when the kernel also
+// wrote the bias-gradient partials (bias_partial non-null on entry).
+static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bias_done, int n_split, hipStream_t st) {
     const PixDims& d = a.d;
     const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
     char name[56];
     snprintf(name, sizeof(name), "conv_wgrad_%dto%d_t%d", a.Ci, a.Co, taps);
     KernelScope ks(name, 2.0 * (double)d.Q * a.Ci * a.Co * taps, 4.0 * (double)d.Q * (a.Ci + a.Co), st);
-    const int RSg = (a.Co + 3) / 4 * 4 + 1, RSa = (a.Ci + 3) / 4 * 4 + 1;
-    const size_t lds = ((size_t)kWgTM * RSg + (size_t)rowtaps * (kWgTM + d.kw - 1) * RSa + kWgTM) * sizeof(float);
+    *bias_done = false;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
     const int jt = taps >= 9 ? 9 : 3;
     const int tapgroups = (taps + jt - 1) / jt;
     dim3 grid(n_split, (ncb * nib * tapgroups + 3) / 4);
+
+    // (1) one side is the 2-channel image: HBM-bound kernel without MFMA
+    const int wide = a.Ci == 2 ? a.Co : a.Ci;
+    const int wide_r = (wide + 63) / 64 * 64;
+    if ((a.Ci == 2) != (a.Co == 2) && wide >= 8 && wide_r <= 256 && 256 % wide_r == 0) {
+        bool hit = true;
+        if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 1, 3, 3>(a, bias_partial, n_split, st);
+        else if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 3, 3, 3>(a, bias_partial, n_split, st);
+        else if (d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1) launch_wgrad_thin_t<3, 1, 1, 1>(a, bias_partial, n_split, st);
+        else hit = false;
+        if (hit) {
+            *bias_done = bias_partial != nullptr;
+            return hipGetLastError();
+        }
+    }
+    // (2) channel counts that are multiples of 4: register-prefetch pipelined MFMA kernel
+    if (a.Co % 4 == 0 && a.Ci % 4 == 0) {
+        const int n_pa = kWgTM + d.kw - 1;
+        const int need_pg = (kWgTM * (a.Co / 4) + kConvThreads - 1) / kConvThreads;
+        const int need_pa = (rowtaps * n_pa * (a.Ci / 4) + kConvThreads - 1) / kConvThreads;
+        const size_t lds = ((size_t)kWgTM * (a.Co + 4) + (size_t)rowtaps * n_pa * (a.Ci + 4) + kWgTM) * sizeof(float);
+        WgradPipeArgs pa{a, bias_partial};
+        bool hit = true;
+#define GLEAM_WG_TRY(JT_, PG_, PA_)                                             \
+    if (hit_none && jt == JT_ && need_pg <= PG_ && need_pa <= PA_) {            \
+        launch_wgrad_pipe_t<JT_, PG_, PA_>(pa, grid, lds, st);                  \
+        hit_none = false;                                                       \
+    }
+        bool hit_none = true;
+        GLEAM_WG_TRY(9, 1, 4) GLEAM_WG_TRY(9, 2, 8) GLEAM_WG_TRY(9, 1, 16) GLEAM_WG_TRY(9, 4, 16)
+        GLEAM_WG_TRY(3, 1, 4) GLEAM_WG_TRY(3, 2, 8) GLEAM_WG_TRY(3, 1, 16) GLEAM_WG_TRY(3, 4, 16)
+#undef GLEAM_WG_TRY
+        hit = !hit_none;
+        if (hit && lds <= 150 * 1024) {
+            *bias_done = bias_partial != nullptr;
+            return hipGetLastError();
+        }
+        if (hit) return hipErrorInvalidValue;  // cannot happen: the plan bounds LDS use
+    }
+    // (3) generic fallback
+    const int RSg = (a.Co + 3) / 4 * 4 + 1, RSa = (a.Ci + 3) / 4 * 4 + 1;
+    const size_t lds = ((size_t)kWgTM * RSg + (size_t)rowtaps * (kWgTM + d.kw - 1) * RSa + kWgTM) * sizeof(float);
     if (jt == 9) {
         static bool once9 = false;
         if (!once9) { (void)hipFuncSetAttribute((const void*)wgrad_mfma_kernel<9>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); once9 = true; }
@@ -520,7 +897,7 @@ static hipError_t launch_wgrad(const WgradArgs& a, int n_split, hipStream_t st) 
 
 size_t wgrad_lds_bytes(const gleam_conv& c) {
     const int rowtaps = c.kt * c.kd * c.kh;
-    const int RSg = (c.cout + 3) / 4 * 4 + 1, RSa = (c.cin + 3) / 4 * 4 + 1;
+    const int RSg = (c.cout + 3) / 4 * 4 + 4, RSa = (c.cin + 3) / 4 * 4 + 4;  // the wider of the two layouts
     return ((size_t)kWgTM * RSg + (size_t)rowtaps * (kWgTM + c.kw - 1) * RSa + kWgTM) * sizeof(float);
 }
 
@@ -550,7 +927,9 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         WgradArgs wa{};
         wa.g = G(l); wa.a = act(l - 1); wa.partial = partial;
         wa.Co = c.cout; wa.Ci = c.cin; wa.relu_in = c.relu_in; wa.d = d;
-        hipError_t e = launch_wgrad(wa, plan.n_split, st);
+        float* bpart = reinterpret_cast<float*>(wsb + plan.bias_partial_off);
+        bool bias_done = false;
+        hipError_t e = launch_wgrad(wa, c.has_bias ? bpart : nullptr, &bias_done, plan.n_split, st);
         if (e != hipSuccess) return e;
         const long long nw = (long long)(c.cout * taps * c.cin);
         {
@@ -559,10 +938,11 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                                (const float*)partial, plan.n_split, nw, grad_theta + plan.w_off[l - 1]);
         }
         if (c.has_bias) {
-            KernelScope ks("bias_grad", 0.0, 4.0 * (double)plan.Q * c.cout, st);
-            hipLaunchKernelGGL(colsum_kernel, dim3(plan.n_split), dim3(256), 0, st, (const float*)G(l), plan.Q, c.cout, partial);
+            KernelScope ks("bias_grad", 0.0, bias_done ? 0.0 : 4.0 * (double)plan.Q * c.cout, st);
+            if (!bias_done)
+                hipLaunchKernelGGL(colsum_kernel, dim3(plan.n_split), dim3(256), 0, st, (const float*)G(l), plan.Q, c.cout, bpart);
             hipLaunchKernelGGL(reduce_partials_kernel, dim3((c.cout + 255) / 256), dim3(256), 0, st,
-                               (const float*)partial, plan.n_split, (long long)c.cout, grad_theta + plan.b_off[l - 1]);
+                               (const float*)bpart, plan.n_split, (long long)c.cout, grad_theta + plan.b_off[l - 1]);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
