@@ -48,6 +48,7 @@ struct ProxPlan {
     size_t grad_off[kMaxLayers + 1];  // G_l inside ws, 1 <= l < L
     size_t partial_off, partial_bytes;
     size_t bias_partial_off;          // [n_split][kMaxChannels] floats
+    size_t wimg_off_fwd, wimg_off_bwd;  // re-laid weights of the layer being run (inside ws)
     size_t red_off;                   // loss partial sums (doubles)
     size_t k_bytes;                   // coil k-space buffer at the head of ws (forward)
     size_t ws_bytes;

@@ -62,13 +62,12 @@ __device__ __forceinline__ long long rowtap_offset(int rt, const PixDims& d) {
 struct ConvArgs {
     const float* in;        // [Q][K]
     float* out;             // [Q][Nn]
-    const float* w;         // element (n, tap, k) at w[n*w_sn + tapidx*w_st + k*w_sk]
+    const float* wt;        // weights re-laid as LDS images, see weights_image_kernel
     const float* bias;      // [Nn] or null
     const float* mask_ref;  // [Q][Nn] or null: ReLU mask source (value > 0 passes)
     const float* add;       // [Q][Nn] or null: added to the result
-    long long w_sn, w_st, w_sk;
     int K, Nn;              // input / output channels of this GEMM
-    int flip;               // 1: tapidx = taps-1-tap (data gradient)
+    int flip;               // 1: data gradient (only used for naming)
     int relu_in, relu_out, mask_acc, mask_add;
     PixDims d;
 };
@@ -83,7 +82,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
     float* wl = smem + n_pix * RS;  // [kw][G][2][NB][4]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, h = lane >> 5;
     const int n0 = blockIdx.y * NB;
-    const int taps = d.kt * d.kd * d.kh * d.kw, rowtaps = d.kt * d.kd * d.kh;
+    const int rowtaps = d.kt * d.kd * d.kh;
     const long long n_tiles = (d.Q + TM - 1) / TM;
     const bool vec_in = (a.K % 4) == 0, vec_out = (a.Nn % 4) == 0;
 
@@ -126,26 +125,25 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
                         slab[pp * RS + kk] = val;
                     }
                 }
-                // ---- stage the weights of this row-tap and channel chunk
-                for (int e = threadIdx.x; e < d.kw * CK * NB; e += kConvThreads) {
-                    int n, kk;
-                    if (a.w_sk == 1) { kk = e % CK; n = (e / CK) % NB; } else { n = e % NB; kk = (e / NB) % CK; }
-                    const int dw = e / (CK * NB);
-                    const int tap = rt * d.kw + dw;
-                    const int tapidx = a.flip ? taps - 1 - tap : tap;
-                    const int k = c0 + kk;
-                    float val = 0.f;
-                    if (k < a.K && n0 + n < a.Nn) val = a.w[(n0 + n) * a.w_sn + tapidx * a.w_st + k * a.w_sk];
-                    wl[(((dw * G + kk / 8) * 2 + ((kk >> 2) & 1)) * NB + n) * 4 + (kk & 3)] = val;
+                // ---- stage the weights of this row-tap and channel chunk: one contiguous LDS image
+                {
+                    const int n_kc = (a.K + CK - 1) / CK;
+                    const size_t img = ((size_t)(rt * n_kc + c0 / CK) * gridDim.y + blockIdx.y) * (size_t)(d.kw * CK * NB);
+                    const float4* src = reinterpret_cast<const float4*>(a.wt + img);
+                    float4* dst = reinterpret_cast<float4*>(wl);
+                    for (int e = threadIdx.x; e < d.kw * CK * NB / 4; e += kConvThreads) dst[e] = src[e];
                 }
                 __syncthreads();
                 // ---- MFMA: A = weights (rows = output channels), B = pixels (columns)
                 for (int dw = 0; dw < d.kw; ++dw) {
-                    const bool ok = (vbits >> (rt * d.kw + dw)) & 1u;
+                    const unsigned okm = ((vbits >> (rt * d.kw + dw)) & 1u) ? 0xffffffffu : 0u;
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
                         float4 pb = *reinterpret_cast<const float4*>(slab + (wave * 32 + m + dw) * RS + 8 * g + 4 * h);
-                        if (!ok) pb = make_float4(0.f, 0.f, 0.f, 0.f);
+                        pb.x = __uint_as_float(__float_as_uint(pb.x) & okm);  // zero padding: tap outside the grid
+                        pb.y = __uint_as_float(__float_as_uint(pb.y) & okm);
+                        pb.z = __uint_as_float(__float_as_uint(pb.z) & okm);
+                        pb.w = __uint_as_float(__float_as_uint(pb.w) & okm);
                         float4 wa[NJ];
 #pragma unroll
                         for (int j = 0; j < NJ; ++j)
@@ -212,6 +210,36 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
     }
 }
 
+// Re-lays one layer's weights as the LDS images conv_mfma_kernel<NB, CK> copies verbatim.  Image
+// (rt, kc, nb) holds row-tap rt, input-channel chunk kc and output-channel block nb as
+// [kw][CK/8][2][NB][4]: element (dw, k = 8g + 4h + s, n) at (((dw*G + g)*2 + h)*NB + n)*4 + s, zero
+// where k or n runs past the layer.  Source element (n, tap, k) is w[n*sn + tapidx*st + k*sk] with
+// tapidx = flip ? taps-1-tap : tap, which covers the forward pass (n = cout, k = cin) and the data
+// gradient (n = cin, k = cout, taps mirrored).
+struct WimgArgs {
+    const float* w;
+    float* wt;
+    long long sn, st, sk;
+    int K, Nn, flip, taps, kw, CK, NB, n_kc, n_nb;
+    long long total;
+};
+__global__ void weights_image_kernel(WimgArgs a) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.total) return;
+    const int img_elems = a.kw * a.CK * a.NB;
+    const long long img = i / img_elems;
+    const int e = (int)(i % img_elems);
+    const int s = e & 3, n = (e >> 2) % a.NB, hg = (e >> 2) / a.NB;   // hg = (dw*G + g)*2 + h
+    const int h = hg & 1, g = (hg >> 1) % (a.CK / 8), dw = (hg >> 1) / (a.CK / 8);
+    const int nb = (int)(img % a.n_nb), kc = (int)((img / a.n_nb) % a.n_kc), rt = (int)(img / ((long long)a.n_nb * a.n_kc));
+    const int k = kc * a.CK + 8 * g + 4 * h + s, nn = nb * a.NB + n;
+    const int tap = rt * a.kw + dw;
+    const int tapidx = a.flip ? a.taps - 1 - tap : tap;
+    float v = 0.f;
+    if (k < a.K && nn < a.Nn) v = a.w[nn * a.sn + tapidx * a.st + k * a.sk];
+    a.wt[i] = v;
+}
+
 static int conv_grid_x(long long n_tiles) {
     const long long cap = 256LL * 6;
     return (int)(n_tiles < cap ? n_tiles : cap);
@@ -226,13 +254,37 @@ static hipError_t launch_conv_t(const ConvArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-static hipError_t launch_conv(const ConvArgs& a, hipStream_t st) {
+struct ConvWeights {
+    const float* w;
+    long long sn, st, sk;
+};
+
+static inline int conv_ck(int K) { return K <= 8 ? 8 : (K <= 16 ? 16 : 32); }
+static inline int conv_nb(int Nn) { return Nn <= 32 ? 32 : 64; }
+
+// Floats of scratch the re-laid weights of a (K -> Nn, taps) convolution need.
+static size_t conv_wimg_floats(int K, int Nn, int taps) {
+    const int ck = conv_ck(K), nb = conv_nb(Nn);
+    return (size_t)taps * ((K + ck - 1) / ck) * ck * ((Nn + nb - 1) / nb) * nb;
+}
+
+static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scratch, hipStream_t st) {
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
+    const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
+    {
+        WimgArgs t{};
+        t.w = cw.w; t.wt = wt_scratch; t.sn = cw.sn; t.st = cw.st; t.sk = cw.sk;
+        t.K = a.K; t.Nn = a.Nn; t.flip = a.flip; t.taps = taps_; t.kw = a.d.kw; t.CK = ck; t.NB = nb;
+        t.n_kc = (a.K + ck - 1) / ck; t.n_nb = (a.Nn + nb - 1) / nb;
+        t.total = (long long)conv_wimg_floats(a.K, a.Nn, taps_);
+        KernelScope ks("weights_image", 0.0, 8.0 * (double)t.total, st);
+        hipLaunchKernelGGL(weights_image_kernel, dim3((unsigned)((t.total + 255) / 256)), dim3(256), 0, st, t);
+    }
+    a.wt = wt_scratch;
     char name[56];
     snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
     KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, 4.0 * (double)a.d.Q * (a.K + a.Nn), st);
-    const int ck = a.K <= 8 ? 8 : (a.K <= 16 ? 16 : 32);
-    if (a.Nn <= 32) {
+    if (nb == 32) {
         if (ck == 8) return launch_conv_t<32, 8>(a, st);
         if (ck == 16) return launch_conv_t<32, 16>(a, st);
         return launch_conv_t<32, 32>(a, st);
@@ -300,22 +352,26 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_mfma_kernel(WgradArgs a) {
         if (threadIdx.x < kWgTM) vmask[threadIdx.x] = tap_validity(q0 + threadIdx.x, d);
         __syncthreads();
         if (active) {
-            const int co = cb * 32 + m, ci = ib * 32 + m;
-            const bool co_ok = co < a.Co, ci_ok = ci < a.Ci;
+            // channels / taps beyond the layer read a clamped address; their sums are never stored
+            const int co_c = cb * 32 + m < a.Co ? cb * 32 + m : a.Co - 1;
+            const int ci_c = ib * 32 + m < a.Ci ? ib * 32 + m : a.Ci - 1;
 #pragma unroll 4
             for (int s = 0; s < kWgTM / 2; ++s) {
                 const int p = 2 * s + h;
-                const float av = co_ok ? gs[p * RSg + co] : 0.f;
+                const float av = gs[p * RSg + co_c];
                 const unsigned vm = vmask[p];
+                float bv[JT];
 #pragma unroll
                 for (int j = 0; j < JT; ++j) {
-                    const int tap = tap0 + j;
-                    if (tap < taps) {
-                        const int rt = tap / d.kw, dw = tap % d.kw;
-                        float bv = ci_ok ? as[(rt * n_pa + p + dw) * RSa + ci] : 0.f;
-                        bv = ((vm >> tap) & 1u) ? bv : 0.f;
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[j], 0, 0, 0);
-                    }
+                    const int tap = tap0 + j < taps ? tap0 + j : taps - 1;
+                    const int rt = tap / d.kw, dw = tap % d.kw;
+                    bv[j] = as[(rt * n_pa + p + dw) * RSa + ci_c];
+                }
+#pragma unroll
+                for (int j = 0; j < JT; ++j) {
+                    const int tap = tap0 + j < taps ? tap0 + j : taps - 1;
+                    const float b = ((vm >> tap) & 1u) ? bv[j] : 0.f;
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b, acc[j], 0, 0, 0);
                 }
             }
         }
@@ -429,17 +485,21 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
-    // per-lane LDS read bases
+    // Per-lane LDS read bases.  Channels and taps beyond the layer are clamped to a valid address:
+    // what they accumulate lands in rows / columns / taps that are never stored, so no value masking
+    // (and no branch) is needed in the loop.
     const int co = cb * 32 + m, ci = ib * 32 + m;
-    const bool co_ok = active && co < a.Co, ci_ok = active && ci < a.Ci;
+    const int co_c = co < a.Co ? co : a.Co - 1, ci_c = ci < a.Ci ? ci : a.Ci - 1;
     int b_off[JT];
+    unsigned b_bit[JT];
 #pragma unroll
     for (int j = 0; j < JT; ++j) {
-        const int tap = tap0 + j;
+        const int tap = tap0 + j < taps ? tap0 + j : taps - 1;
         const int rt = tap / d.kw, dw = tap % d.kw;
-        b_off[j] = (rt * n_pa + dw + h) * RSa + ci;
+        b_off[j] = (rt * n_pa + dw + h) * RSa + ci_c;
+        b_bit[j] = 1u << tap;
     }
-    const int a_off = h * RSg + co;
+    const int a_off = h * RSg + co_c;
 
     const long long n_chunks = (d.Q + kWgTM - 1) / kWgTM;
     long long chunk = blockIdx.x;
@@ -451,19 +511,31 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
     for (; chunk < n_chunks; chunk += gridDim.x) {
         const long long next = chunk + gridDim.x;
         if (next < n_chunks) fetch(next * kWgTM);
-        if (co_ok || ci_ok) {
+        if (active) {
+            // software pipeline over the 2-pixel K-steps: operands of step s+1 are read from LDS
+            // before the MFMAs of step s are issued
+            float av = gs[a_off];
+            unsigned vm = vmask[h];
+            float bv[JT];
+#pragma unroll
+            for (int j = 0; j < JT; ++j) bv[j] = as[b_off[j]];
 #pragma unroll 2
             for (int s = 0; s < kWgTM / 2; ++s) {
-                const float av = co_ok ? gs[a_off + 2 * s * RSg] : 0.f;
-                const unsigned vm = vmask[2 * s + h];
+                const int sn = s + 1 < kWgTM / 2 ? s + 1 : s;
+                const float av_n = gs[a_off + 2 * sn * RSg];
+                const unsigned vm_n = vmask[2 * sn + h];
+                float bv_n[JT];
+#pragma unroll
+                for (int j = 0; j < JT; ++j) bv_n[j] = as[b_off[j] + 2 * sn * RSa];
 #pragma unroll
                 for (int j = 0; j < JT; ++j) {
-                    if (tap0 + j < taps) {
-                        float bv = ci_ok ? as[b_off[j] + 2 * s * RSa] : 0.f;
-                        bv = ((vm >> (tap0 + j)) & 1u) ? bv : 0.f;
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[j], 0, 0, 0);
-                    }
+                    const float b = (vm & b_bit[j]) ? bv[j] : 0.f;
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b, acc[j], 0, 0, 0);
                 }
+                av = av_n;
+                vm = vm_n;
+#pragma unroll
+                for (int j = 0; j < JT; ++j) bv[j] = bv_n[j];
             }
         }
         __syncthreads();
@@ -761,13 +833,25 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     w += plan.partial_bytes;
     plan.bias_partial_off = w;
     w += align256((size_t)plan.n_split * kMaxChannels * sizeof(float));
+    size_t max_img = 0;
+    for (int l = 0; l < L; ++l) {
+        const gleam_conv& c = p.layers[l];
+        const int taps = c.kt * c.kd * c.kh * c.kw;
+        const size_t f = conv_wimg_floats(c.cin, c.cout, taps), b = conv_wimg_floats(c.cout, c.cin, taps);
+        max_img = f > max_img ? f : max_img;
+        max_img = b > max_img ? b : max_img;
+    }
+    const size_t img_bytes = align256(max_img * sizeof(float));
+    plan.wimg_off_bwd = w;
+    w += img_bytes;
     const size_t bwd_ws = w;
 
     plan.red_off = 0;  // loss partials reuse the head of the k-space buffer once DC is done
     size_t kbytes = align256((size_t)(g.B * g.C * g.T * g.D * g.H * g.W) * sizeof(float2));
     if (kbytes < align256(kLossBlocks * sizeof(double))) kbytes = align256(kLossBlocks * sizeof(double));
     plan.k_bytes = kbytes;
-    const size_t fwd_ws = kbytes + plan.saved_bytes;  // room for activations when no saved buffer is given
+    plan.wimg_off_fwd = kbytes + plan.saved_bytes;
+    const size_t fwd_ws = kbytes + plan.saved_bytes + img_bytes;  // activations live here when no saved buffer is given
     plan.ws_bytes = fwd_ws > bwd_ws ? fwd_ws : bwd_ws;
 }
 
@@ -781,14 +865,13 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
         ConvArgs a{};
         a.in = reinterpret_cast<const float*>(act_base + plan.act_off[l]);
         a.out = (l == L - 1) ? reinterpret_cast<float*>(x_out) : reinterpret_cast<float*>(act_base + plan.act_off[l + 1]);
-        a.w = theta + plan.w_off[l];
-        a.w_sn = (long long)(taps * c.cin); a.w_st = c.cin; a.w_sk = 1;
+        const ConvWeights cw{theta + plan.w_off[l], (long long)(taps * c.cin), (long long)c.cin, 1};
         a.bias = c.has_bias ? theta + plan.b_off[l] : nullptr;
         a.add = c.skip_src >= 0 ? reinterpret_cast<const float*>(act_base + plan.act_off[c.skip_src]) : nullptr;
         a.K = c.cin; a.Nn = c.cout;
         a.relu_in = c.relu_in; a.relu_out = c.relu_out;
         a.d = pix_dims(g, c);
-        hipError_t e = launch_conv(a, st);
+        hipError_t e = launch_conv(a, cw, reinterpret_cast<float*>((unsigned char*)ws + plan.wimg_off_fwd), st);
         if (e != hipSuccess) return e;
     }
     if (x_ref) {
@@ -951,15 +1034,15 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         const gleam_conv& below = p.layers[l - 2];  // layer that produced t_{l-1}
         ConvArgs a{};
         a.in = G(l); a.out = G(l - 1);
-        a.w = theta + plan.w_off[l - 1];
-        a.w_sn = 1; a.w_st = c.cin; a.w_sk = (long long)(taps * c.cin); a.flip = 1;
+        const ConvWeights cw{theta + plan.w_off[l - 1], 1, (long long)c.cin, (long long)(taps * c.cin)};
+        a.flip = 1;
         a.K = c.cout; a.Nn = c.cin;
         a.mask_acc = (c.relu_in || below.relu_out) ? 1 : 0;
         a.mask_add = below.relu_out ? 1 : 0;
         a.mask_ref = (a.mask_acc || a.mask_add) ? act(l - 1) : nullptr;
         a.add = pending[l - 1] ? G(pending[l - 1]) : nullptr;
         a.d = d;
-        e = launch_conv(a, st);
+        e = launch_conv(a, cw, reinterpret_cast<float*>(wsb + plan.wimg_off_bwd), st);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
