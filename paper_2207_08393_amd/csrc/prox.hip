@@ -21,6 +21,7 @@ namespace gleam {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kConvThreads = 256;
+constexpr int kConvTM = 256;  // pixels per workgroup tile of the forward / data-gradient kernel
 
 struct PixDims {
     int T, D, H, W;
@@ -72,140 +73,413 @@ struct ConvArgs {
     PixDims d;
 };
 
-template <int NB, int CK>
+// Software pipeline: while the MFMAs of chunk i (one row-tap x CK input channels) run out of LDS, the
+// pixel slab and the weight image of chunk i+1 - of the next tile when the tile ends - are already in
+// flight into registers; they are written to LDS between two barriers once the MFMAs are issued.
+// Prefetch loads are unconditional: a uniform base pointer plus a per-thread 32-bit offset that never
+// changes; slabs that cross the start or the end of the tensor take a clamped-address path and validity
+// is applied at the LDS store.  A workgroup owns 256 pixels x NB output channels; each of its four
+// waves 64 pixels x NB channels (2 x NB/32 MFMA tiles).
+template <int NB, int CK, int KWMAX, bool VEC>
 __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
-    constexpr int TM = 128, RS = CK + 4, G = CK / 8, NJ = NB / 32;
+    constexpr int TM = kConvTM, RS = CK + 4, G = CK / 8, NJ = NB / 32, PJ = 2, Q4 = CK / 4;
+    constexpr int PS = ((TM + KWMAX - 1) * Q4 + kConvThreads - 1) / kConvThreads;   // slab quads per thread
+    constexpr int PW = (KWMAX * CK * NB / 4 + kConvThreads - 1) / kConvThreads;     // weight float4 per thread
     extern __shared__ float smem[];
     const PixDims d = a.d;
     const int n_pix = TM + d.kw - 1;
     float* slab = smem;             // [n_pix][RS]
     float* wl = smem + n_pix * RS;  // [kw][G][2][NB][4]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, m = lane & 31, h = lane >> 5;
     const int n0 = blockIdx.y * NB;
     const int rowtaps = d.kt * d.kd * d.kh;
+    const int n_kc = (a.K + CK - 1) / CK;
+    const int nck = rowtaps * n_kc;                      // chunks per tile
+    const int w4 = d.kw * CK * NB / 4;                   // float4 per weight image
     const long long n_tiles = (d.Q + TM - 1) / TM;
-    const bool vec_in = (a.K % 4) == 0, vec_out = (a.Nn % 4) == 0;
+    const bool vec_out = (a.Nn % 4) == 0;
+    const bool k_full = (a.K % CK) == 0;                 // no channel padding inside a chunk
 
-    for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const long long q0 = tile * TM;
-        const long long q = q0 + wave * 32 + m;
-        const unsigned vbits = tap_validity(q, d);
-        floatx16 acc[NJ];
+    // slots this thread moves for every chunk: quad (4 channels) s_ch of slab pixel s_pp
+    int s_lds[PS], s_pp[PS], s_ch[PS];
+    unsigned s_off[PS];                                  // element offset of the quad from the slab origin
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+    for (int i = 0; i < PS; ++i) {
+        const int v = tid + i * kConvThreads;
+        const bool used = v < n_pix * Q4;
+        s_pp[i] = used ? v / Q4 : 0;
+        s_ch[i] = used ? 4 * (v % Q4) : 0;
+        s_lds[i] = used ? s_pp[i] * RS + s_ch[i] : -1;
+        s_off[i] = (unsigned)(s_pp[i] * a.K + s_ch[i]);
+    }
+    unsigned w_off[PW];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    for (int i = 0; i < PW; ++i) {
+        const int idx = tid + i * kConvThreads;
+        w_off[i] = idx < w4 ? idx : 0;
+    }
+    float4 rs[PS], rw[PW];
+    unsigned okb = 0u;   // VEC: bit i = quad i valid; scalar: bit 4i+e per element
+    bool interior = true;
 
-        for (int rt = 0; rt < rowtaps; ++rt) {
-            const long long qs = q0 + rowtap_offset(rt, d) - d.kw / 2;
-            for (int c0 = 0; c0 < a.K; c0 += CK) {
-                __syncthreads();
-                // ---- stage the pixel slab (ReLU on load when asked)
-                if (vec_in) {
-                    for (int v = threadIdx.x; v < n_pix * (CK / 4); v += kConvThreads) {
-                        const int pp = v / (CK / 4), c4 = v % (CK / 4);
-                        const long long qq = qs + pp;
-                        const int ch = c0 + 4 * c4;
-                        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (qq >= 0 && qq < d.Q && ch < a.K) val = *reinterpret_cast<const float4*>(a.in + qq * a.K + ch);
-                        if (a.relu_in) {
-                            val.x = fmaxf(val.x, 0.f); val.y = fmaxf(val.y, 0.f);
-                            val.z = fmaxf(val.z, 0.f); val.w = fmaxf(val.w, 0.f);
-                        }
-                        *reinterpret_cast<float4*>(slab + pp * RS + 4 * c4) = val;
-                    }
+    auto fetch = [&](long long tile, int c) {
+        const int rt = c / n_kc, kc = c % n_kc;
+        const long long qs = tile * TM + rowtap_offset(rt, d) - d.kw / 2;
+        interior = k_full && qs >= 0 && qs + n_pix <= d.Q;          // uniform
+        if (interior) {
+            const float* base = a.in + qs * a.K + kc * CK;           // uniform
+            if (VEC) {
+#pragma unroll
+                for (int i = 0; i < PS; ++i) rs[i] = *reinterpret_cast<const float4*>(base + s_off[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < PS; ++i)
+                    rs[i] = make_float4(base[s_off[i]], base[s_off[i] + 1], base[s_off[i] + 2], base[s_off[i] + 3]);
+            }
+        } else {
+            okb = 0u;
+#pragma unroll
+            for (int i = 0; i < PS; ++i) {
+                const long long qq = qs + s_pp[i];
+                const int ch = kc * CK + s_ch[i];
+                const bool okp = qq >= 0 && qq < d.Q;
+                if (VEC) {
+                    const bool ok = okp && ch < a.K;
+                    rs[i] = *reinterpret_cast<const float4*>(a.in + (ok ? qq * a.K + ch : 0));
+                    okb |= (ok ? 1u : 0u) << i;
                 } else {
-                    for (int v = threadIdx.x; v < n_pix * CK; v += kConvThreads) {
-                        const int pp = v / CK, kk = v % CK;
-                        const long long qq = qs + pp;
-                        const int ch = c0 + kk;
-                        float val = 0.f;
-                        if (qq >= 0 && qq < d.Q && ch < a.K) val = a.in[qq * a.K + ch];
-                        if (a.relu_in) val = fmaxf(val, 0.f);
-                        slab[pp * RS + kk] = val;
+                    float e4[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool ok = okp && ch + e < a.K;
+                        e4[e] = a.in[ok ? qq * a.K + ch + e : 0];
+                        okb |= (ok ? 1u : 0u) << (4 * i + e);
                     }
-                }
-                // ---- stage the weights of this row-tap and channel chunk: one contiguous LDS image
-                {
-                    const int n_kc = (a.K + CK - 1) / CK;
-                    const size_t img = ((size_t)(rt * n_kc + c0 / CK) * gridDim.y + blockIdx.y) * (size_t)(d.kw * CK * NB);
-                    const float4* src = reinterpret_cast<const float4*>(a.wt + img);
-                    float4* dst = reinterpret_cast<float4*>(wl);
-                    for (int e = threadIdx.x; e < d.kw * CK * NB / 4; e += kConvThreads) dst[e] = src[e];
-                }
-                __syncthreads();
-                // ---- MFMA: A = weights (rows = output channels), B = pixels (columns)
-                for (int dw = 0; dw < d.kw; ++dw) {
-                    const unsigned okm = ((vbits >> (rt * d.kw + dw)) & 1u) ? 0xffffffffu : 0u;
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        float4 pb = *reinterpret_cast<const float4*>(slab + (wave * 32 + m + dw) * RS + 8 * g + 4 * h);
-                        pb.x = __uint_as_float(__float_as_uint(pb.x) & okm);  // zero padding: tap outside the grid
-                        pb.y = __uint_as_float(__float_as_uint(pb.y) & okm);
-                        pb.z = __uint_as_float(__float_as_uint(pb.z) & okm);
-                        pb.w = __uint_as_float(__float_as_uint(pb.w) & okm);
-                        float4 wa[NJ];
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j)
-                            wa[j] = *reinterpret_cast<const float4*>(wl + (((dw * G + g) * 2 + h) * NB + 32 * j + m) * 4);
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j) {
-                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].x, pb.x, acc[j], 0, 0, 0);
-                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].y, pb.y, acc[j], 0, 0, 0);
-                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].z, pb.z, acc[j], 0, 0, 0);
-                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].w, pb.w, acc[j], 0, 0, 0);
-                        }
-                    }
+                    rs[i] = make_float4(e4[0], e4[1], e4[2], e4[3]);
                 }
             }
         }
-        // ---- epilogue: lane holds pixel q (column m) and 4 consecutive channels per register group
-        if (q < d.Q) {
+        const float4* src = reinterpret_cast<const float4*>(
+            a.wt + ((size_t)(rt * n_kc + kc) * gridDim.y + blockIdx.y) * (size_t)(d.kw * CK * NB));
+#pragma unroll
+        for (int i = 0; i < PW; ++i) rw[i] = src[w_off[i]];
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < PS; ++i) {
+            float4 v = rs[i];
+            if (!interior) {
+                if (VEC) {
+                    const unsigned mk = ((okb >> i) & 1u) ? 0xffffffffu : 0u;
+                    v.x = __uint_as_float(__float_as_uint(v.x) & mk); v.y = __uint_as_float(__float_as_uint(v.y) & mk);
+                    v.z = __uint_as_float(__float_as_uint(v.z) & mk); v.w = __uint_as_float(__float_as_uint(v.w) & mk);
+                } else {
+                    v.x = ((okb >> (4 * i)) & 1u) ? v.x : 0.f; v.y = ((okb >> (4 * i + 1)) & 1u) ? v.y : 0.f;
+                    v.z = ((okb >> (4 * i + 2)) & 1u) ? v.z : 0.f; v.w = ((okb >> (4 * i + 3)) & 1u) ? v.w : 0.f;
+                }
+            }
+            if (a.relu_in) {
+                v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+            }
+            if (s_lds[i] >= 0) *reinterpret_cast<float4*>(slab + s_lds[i]) = v;
+        }
+#pragma unroll
+        for (int i = 0; i < PW; ++i)
+            if (tid + i * kConvThreads < w4) reinterpret_cast<float4*>(wl)[tid + i * kConvThreads] = rw[i];
+    };
+
+    long long tile = blockIdx.x;
+    if (tile < n_tiles) {
+        fetch(tile, 0);
+        stash();
+    }
+    __syncthreads();
+    for (; tile < n_tiles; tile += gridDim.x) {
+        const long long q0 = tile * TM + wave * 64 + m;   // this lane's pixels: q0 and q0 + 32
+        unsigned vbits[PJ];
+#pragma unroll
+        for (int pj = 0; pj < PJ; ++pj) vbits[pj] = tap_validity(q0 + 32 * pj, d);
+        floatx16 acc[PJ][NJ];
+#pragma unroll
+        for (int pj = 0; pj < PJ; ++pj)
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const int co0 = n0 + 32 * j + 8 * rg + 4 * h;
-                    if (co0 >= a.Nn) continue;
-                    float v[4] = {acc[j][4 * rg], acc[j][4 * rg + 1], acc[j][4 * rg + 2], acc[j][4 * rg + 3]};
-                    const long long o = q * a.Nn + co0;
-                    if (vec_out) {
-                        if (a.bias) {
-                            const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0);
-                            v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
-                        }
-                        if (a.relu_out) {
+                for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
+
+        for (int c = 0; c < nck; ++c) {
+            const bool last = c + 1 == nck;
+            const long long ntile = last ? tile + gridDim.x : tile;
+            const bool has_next = ntile < n_tiles;
+            if (has_next) fetch(ntile, last ? 0 : c + 1);
+            // ---- MFMA: A = weights (rows = output channels), B = pixels (columns)
+            const int rt = c / n_kc;
+            for (int dw = 0; dw < d.kw; ++dw) {
+                unsigned okm[PJ];
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
-                        }
-                        float4 ref = make_float4(1.f, 1.f, 1.f, 1.f);
-                        if (a.mask_ref) ref = *reinterpret_cast<const float4*>(a.mask_ref + o);
-                        const float rr[4] = {ref.x, ref.y, ref.z, ref.w};
-                        if (a.mask_acc) {
+                for (int pj = 0; pj < PJ; ++pj) okm[pj] = ((vbits[pj] >> (rt * d.kw + dw)) & 1u) ? 0xffffffffu : 0u;
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) v[i] = rr[i] > 0.f ? v[i] : 0.f;
-                        }
-                        if (a.add) {
-                            const float4 av = *reinterpret_cast<const float4*>(a.add + o);
-                            const float aa[4] = {av.x, av.y, av.z, av.w};
+                for (int g = 0; g < G; ++g) {
+                    float4 pb[PJ], wa[NJ];
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) v[i] += (a.mask_add && !(rr[i] > 0.f)) ? 0.f : aa[i];
-                        }
-                        *reinterpret_cast<float4*>(a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            if (co0 + i >= a.Nn) break;
-                            float x = v[i];
-                            if (a.bias) x += a.bias[co0 + i];
-                            if (a.relu_out) x = fmaxf(x, 0.f);
-                            const float ref = a.mask_ref ? a.mask_ref[o + i] : 1.f;
-                            if (a.mask_acc) x = ref > 0.f ? x : 0.f;
-                            if (a.add) x += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o + i];
-                            a.out[o + i] = x;
-                        }
+                    for (int pj = 0; pj < PJ; ++pj) {
+                        pb[pj] = *reinterpret_cast<const float4*>(slab + (wave * 64 + 32 * pj + m + dw) * RS + 8 * g + 4 * h);
+                        pb[pj].x = __uint_as_float(__float_as_uint(pb[pj].x) & okm[pj]);  // zero padding
+                        pb[pj].y = __uint_as_float(__float_as_uint(pb[pj].y) & okm[pj]);
+                        pb[pj].z = __uint_as_float(__float_as_uint(pb[pj].z) & okm[pj]);
+                        pb[pj].w = __uint_as_float(__float_as_uint(pb[pj].w) & okm[pj]);
                     }
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        wa[j] = *reinterpret_cast<const float4*>(wl + (((dw * G + g) * 2 + h) * NB + 32 * j + m) * 4);
+#pragma unroll
+                    for (int pj = 0; pj < PJ; ++pj)
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].x, pb[pj].x, acc[pj][j], 0, 0, 0);
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].y, pb[pj].y, acc[pj][j], 0, 0, 0);
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].z, pb[pj].z, acc[pj][j], 0, 0, 0);
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].w, pb[pj].w, acc[pj][j], 0, 0, 0);
+                        }
                 }
+            }
+            if (last) {
+                // ---- epilogue: lane holds pixels q0 + 32*pj and 4 consecutive output channels per register group
+#pragma unroll
+                for (int pj = 0; pj < PJ; ++pj) {
+                    const long long q = q0 + 32 * pj;
+                    if (q >= d.Q) continue;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg) {
+                            const int co0 = n0 + 32 * j + 8 * rg + 4 * h;
+                            if (co0 >= a.Nn) continue;
+                            float v[4] = {acc[pj][j][4 * rg], acc[pj][j][4 * rg + 1], acc[pj][j][4 * rg + 2], acc[pj][j][4 * rg + 3]};
+                            const long long o = q * a.Nn + co0;
+                            if (vec_out) {
+                                if (a.bias) {
+                                    const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0);
+                                    v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
+                                }
+                                if (a.relu_out) {
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+                                }
+                                float4 ref = make_float4(1.f, 1.f, 1.f, 1.f);
+                                if (a.mask_ref) ref = *reinterpret_cast<const float4*>(a.mask_ref + o);
+                                const float rr[4] = {ref.x, ref.y, ref.z, ref.w};
+                                if (a.mask_acc) {
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) v[i] = rr[i] > 0.f ? v[i] : 0.f;
+                                }
+                                if (a.add) {
+                                    const float4 av = *reinterpret_cast<const float4*>(a.add + o);
+                                    const float aa[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) v[i] += (a.mask_add && !(rr[i] > 0.f)) ? 0.f : aa[i];
+                                }
+                                *reinterpret_cast<float4*>(a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                            } else {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    if (co0 + i >= a.Nn) break;
+                                    float x = v[i];
+                                    if (a.bias) x += a.bias[co0 + i];
+                                    if (a.relu_out) x = fmaxf(x, 0.f);
+                                    const float ref = a.mask_ref ? a.mask_ref[o + i] : 1.f;
+                                    if (a.mask_acc) x = ref > 0.f ? x : 0.f;
+                                    if (a.add) x += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o + i];
+                                    a.out[o + i] = x;
+                                }
+                            }
+                        }
+                }
+            }
+            __syncthreads();
+            if (has_next) stash();
+            __syncthreads();
+        }
+    }
+}
+
+// Forward / data-gradient convolution with global -> LDS direct loads (no register staging, so few
+// VGPRs and three workgroups per CU).  Chunks (row-tap x CK input channels) alternate between two LDS
+// buffers: the direct loads of the next chunk - next tile at a tile end - are issued before the MFMAs
+// of the current one, one barrier per chunk.  The compiler still waits for a wave's own outstanding
+// direct loads before that wave's LDS reads, so most of the overlap comes from the co-resident
+// workgroups rather than from within a wave.
+// A direct load writes lane l's 16 bytes at (uniform LDS base) + 16*l, so a wave fills 64 consecutive
+// quad slots (quad = 4 channels of one slab pixel).  Rows cannot be padded in that scheme; instead the
+// quad position inside a pixel row is XOR-swizzled with the pixel index, chosen by picking each lane's
+// GLOBAL address, which keeps the 128-bit operand reads bank-conflict free.  Pixels or channels past
+// the tensor are read from a clamped address: they only ever meet masked taps or zero weights.
+// Requires K % 4 == 0 (16-byte alignment of every quad).
+template <int NB, int CK, int PJ>
+__global__ __launch_bounds__(kConvThreads) void conv_dlds_kernel(ConvArgs a) {
+    constexpr int TM = 128 * PJ, G = CK / 8, NJ = NB / 32, Q4 = CK / 4;
+    constexpr int RP = Q4 >= 8 ? 1 : 8 / Q4;   // pixel rows per 128 bytes of LDS
+    extern __shared__ float smem[];
+    const PixDims d = a.d;
+    const int n_pix = TM + d.kw - 1;
+    const int slab_ops = (n_pix * Q4 + 63) / 64;          // wave-wide loads per slab
+    const int w4 = d.kw * CK * NB / 4;
+    const int w_ops = (w4 + 63) / 64;
+    const int buf_floats = (slab_ops + w_ops) * 256;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 31, h = lane >> 5;
+    const int n0 = blockIdx.y * NB;
+    const int rowtaps = d.kt * d.kd * d.kh;
+    const int n_kc = (a.K + CK - 1) / CK;
+    const int nck = rowtaps * n_kc;
+    const long long n_tiles = (d.Q + TM - 1) / TM;
+    const bool vec_out = (a.Nn % 4) == 0;
+    const long long last_quad = d.Q * a.K - 4;            // highest legal quad start
+
+    auto issue = [&](long long tile, int c, int buf) {
+        const int rt = c / n_kc, kc = c % n_kc;
+        const long long qs = tile * TM + rowtap_offset(rt, d) - d.kw / 2;
+        float* dst = smem + buf * buf_floats;
+        for (int o = wave; o < slab_ops; o += 4) {
+            const int v = o * 64 + lane;
+            const int pp = v / Q4, pos = v % Q4;
+            const int c4 = pos ^ ((pp / RP) % Q4);
+            long long off = (qs + pp) * a.K + kc * CK + 4 * c4;
+            off = off < 0 ? 0 : (off > last_quad ? last_quad : off);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.in + off),
+                                             (__attribute__((address_space(3))) void*)(dst + o * 256), 16, 0, 0);
+        }
+        const float* src = a.wt + ((size_t)(rt * n_kc + kc) * gridDim.y + blockIdx.y) * (size_t)(d.kw * CK * NB);
+        float* wdst = dst + slab_ops * 256;
+        for (int o = wave; o < w_ops; o += 4) {
+            int v = o * 64 + lane;
+            v = v < w4 ? v : 0;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + 4 * v),
+                                             (__attribute__((address_space(3))) void*)(wdst + o * 256), 16, 0, 0);
+        }
+    };
+
+    long long tile = blockIdx.x;
+    int cur = 0;
+    if (tile < n_tiles) issue(tile, 0, 0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (; tile < n_tiles; tile += gridDim.x) {
+        const long long q0 = tile * TM + wave * (32 * PJ) + m;
+        unsigned vbits[PJ];
+#pragma unroll
+        for (int pj = 0; pj < PJ; ++pj) vbits[pj] = tap_validity(q0 + 32 * pj, d);
+        floatx16 acc[PJ][NJ];
+#pragma unroll
+        for (int pj = 0; pj < PJ; ++pj)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
+
+        for (int c = 0; c < nck; ++c) {
+            const bool last = c + 1 == nck;
+            const long long ntile = last ? tile + gridDim.x : tile;
+            if (ntile < n_tiles) issue(ntile, last ? 0 : c + 1, cur ^ 1);
+            const float* slab = smem + cur * buf_floats;
+            const float* wl = slab + slab_ops * 256;
+            const int rt = c / n_kc;
+            for (int dw = 0; dw < d.kw; ++dw) {
+                unsigned okm[PJ];
+                const float* prow[PJ];
+                int key[PJ];
+#pragma unroll
+                for (int pj = 0; pj < PJ; ++pj) {
+                    okm[pj] = ((vbits[pj] >> (rt * d.kw + dw)) & 1u) ? 0xffffffffu : 0u;
+                    const int pix = wave * (32 * PJ) + 32 * pj + m + dw;
+                    prow[pj] = slab + pix * CK;
+                    key[pj] = (pix / RP) % Q4;
+                }
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float4 pb[PJ], wa[NJ];
+#pragma unroll
+                    for (int pj = 0; pj < PJ; ++pj) {
+                        pb[pj] = *reinterpret_cast<const float4*>(prow[pj] + 4 * ((2 * g + h) ^ key[pj]));
+                        if (a.relu_in) {
+                            pb[pj].x = fmaxf(pb[pj].x, 0.f); pb[pj].y = fmaxf(pb[pj].y, 0.f);
+                            pb[pj].z = fmaxf(pb[pj].z, 0.f); pb[pj].w = fmaxf(pb[pj].w, 0.f);
+                        }
+                        pb[pj].x = __uint_as_float(__float_as_uint(pb[pj].x) & okm[pj]);  // zero padding
+                        pb[pj].y = __uint_as_float(__float_as_uint(pb[pj].y) & okm[pj]);
+                        pb[pj].z = __uint_as_float(__float_as_uint(pb[pj].z) & okm[pj]);
+                        pb[pj].w = __uint_as_float(__float_as_uint(pb[pj].w) & okm[pj]);
+                    }
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        wa[j] = *reinterpret_cast<const float4*>(wl + (((dw * G + g) * 2 + h) * NB + 32 * j + m) * 4);
+#pragma unroll
+                    for (int pj = 0; pj < PJ; ++pj)
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].x, pb[pj].x, acc[pj][j], 0, 0, 0);
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].y, pb[pj].y, acc[pj][j], 0, 0, 0);
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].z, pb[pj].z, acc[pj][j], 0, 0, 0);
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].w, pb[pj].w, acc[pj][j], 0, 0, 0);
+                        }
+                }
+            }
+            if (last) {
+#pragma unroll
+                for (int pj = 0; pj < PJ; ++pj) {
+                    const long long q = q0 + 32 * pj;
+                    if (q >= d.Q) continue;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg) {
+                            const int co0 = n0 + 32 * j + 8 * rg + 4 * h;
+                            if (co0 >= a.Nn) continue;
+                            float v[4] = {acc[pj][j][4 * rg], acc[pj][j][4 * rg + 1], acc[pj][j][4 * rg + 2], acc[pj][j][4 * rg + 3]};
+                            const long long o = q * a.Nn + co0;
+                            if (vec_out) {
+                                if (a.bias) {
+                                    const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0);
+                                    v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
+                                }
+                                if (a.relu_out) {
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+                                }
+                                float4 ref = make_float4(1.f, 1.f, 1.f, 1.f);
+                                if (a.mask_ref) ref = *reinterpret_cast<const float4*>(a.mask_ref + o);
+                                const float rr[4] = {ref.x, ref.y, ref.z, ref.w};
+                                if (a.mask_acc) {
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) v[i] = rr[i] > 0.f ? v[i] : 0.f;
+                                }
+                                if (a.add) {
+                                    const float4 av = *reinterpret_cast<const float4*>(a.add + o);
+                                    const float aa[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) v[i] += (a.mask_add && !(rr[i] > 0.f)) ? 0.f : aa[i];
+                                }
+                                *reinterpret_cast<float4*>(a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                            } else {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    if (co0 + i >= a.Nn) break;
+                                    float x = v[i];
+                                    if (a.bias) x += a.bias[co0 + i];
+                                    if (a.relu_out) x = fmaxf(x, 0.f);
+                                    const float ref = a.mask_ref ? a.mask_ref[o + i] : 1.f;
+                                    if (a.mask_acc) x = ref > 0.f ? x : 0.f;
+                                    if (a.add) x += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o + i];
+                                    a.out[o + i] = x;
+                                }
+                            }
+                        }
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0);   // the next chunk's direct loads have landed in LDS
+            __syncthreads();                 // ... and every wave is done reading the current buffer
+            cur ^= 1;
         }
     }
 }
@@ -241,16 +515,48 @@ __global__ void weights_image_kernel(WimgArgs a) {
 }
 
 static int conv_grid_x(long long n_tiles) {
-    const long long cap = 256LL * 6;
+    const long long cap = 256LL * 2;   // persistent: two workgroups per CU fit (LDS), each loops over tiles
     return (int)(n_tiles < cap ? n_tiles : cap);
+}
+
+template <int NB, int CK, int KWMAX, bool VEC>
+static void launch_conv_k(const ConvArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    static bool once = false;
+    if (!once) {
+        (void)hipFuncSetAttribute((const void*)conv_mfma_kernel<NB, CK, KWMAX, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        once = true;
+    }
+    hipLaunchKernelGGL((conv_mfma_kernel<NB, CK, KWMAX, VEC>), grid, dim3(kConvThreads), lds, st, a);
+}
+
+template <int NB, int CK, int PJ>
+static void launch_conv_dlds(const ConvArgs& a, hipStream_t st) {
+    static bool once = false;
+    if (!once) {
+        (void)hipFuncSetAttribute((const void*)conv_dlds_kernel<NB, CK, PJ>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        once = true;
+    }
+    constexpr int TM = 128 * PJ, Q4 = CK / 4;
+    const int slab_ops = ((TM + a.d.kw - 1) * Q4 + 63) / 64, w_ops = (a.d.kw * CK * NB / 4 + 63) / 64;
+    const size_t lds = (size_t)2 * (slab_ops + w_ops) * 1024;
+    const long long n_tiles = (a.d.Q + TM - 1) / TM;
+    const int per_cu = (int)(160 * 1024 / lds) > 0 ? (int)(160 * 1024 / lds) : 1;
+    const long long cap = 256LL * (per_cu > 4 ? 4 : per_cu);
+    dim3 grid((unsigned)(n_tiles < cap ? n_tiles : cap), (a.Nn + NB - 1) / NB);
+    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ>), grid, dim3(kConvThreads), lds, st, a);
 }
 
 template <int NB, int CK>
 static hipError_t launch_conv_t(const ConvArgs& a, hipStream_t st) {
-    const long long n_tiles = (a.d.Q + 127) / 128;
-    const size_t lds = ((size_t)(128 + a.d.kw - 1) * (CK + 4) + (size_t)a.d.kw * CK * NB) * sizeof(float);
+    if ((a.K % 4) == 0) {
+        launch_conv_dlds<NB, CK, 1>(a, st);
+        return hipGetLastError();
+    }
+    const long long n_tiles = (a.d.Q + kConvTM - 1) / kConvTM;
+    const size_t lds = ((size_t)(kConvTM + a.d.kw - 1) * (CK + 4) + (size_t)a.d.kw * CK * NB) * sizeof(float);
     dim3 grid(conv_grid_x(n_tiles), (a.Nn + NB - 1) / NB);
-    hipLaunchKernelGGL((conv_mfma_kernel<NB, CK>), grid, dim3(kConvThreads), lds, st, a);
+    if (a.d.kw > 3) launch_conv_k<NB, CK, 5, false>(a, grid, lds, st);
+    else launch_conv_k<NB, CK, 3, false>(a, grid, lds, st);
     return hipGetLastError();
 }
 
@@ -259,7 +565,9 @@ struct ConvWeights {
     long long sn, st, sk;
 };
 
-static inline int conv_ck(int K) { return K <= 8 ? 8 : (K <= 16 ? 16 : 32); }
+// Input channels per staged chunk: 16 keeps a double-buffered workgroup near 42 KB of LDS, so three
+// workgroups share a CU (measured faster than 32-channel chunks at one workgroup per CU).
+static inline int conv_ck(int K) { return K <= 8 ? 8 : 16; }
 static inline int conv_nb(int Nn) { return Nn <= 32 ? 32 : 64; }
 
 // Floats of scratch the re-laid weights of a (K -> Nn, taps) convolution need.
@@ -284,14 +592,8 @@ static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scrat
     char name[56];
     snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
     KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, 4.0 * (double)a.d.Q * (a.K + a.Nn), st);
-    if (nb == 32) {
-        if (ck == 8) return launch_conv_t<32, 8>(a, st);
-        if (ck == 16) return launch_conv_t<32, 16>(a, st);
-        return launch_conv_t<32, 32>(a, st);
-    }
-    if (ck == 8) return launch_conv_t<64, 8>(a, st);
-    if (ck == 16) return launch_conv_t<64, 16>(a, st);
-    return launch_conv_t<64, 32>(a, st);
+    if (nb == 32) return ck == 8 ? launch_conv_t<32, 8>(a, st) : launch_conv_t<32, 16>(a, st);
+    return ck == 8 ? launch_conv_t<64, 8>(a, st) : launch_conv_t<64, 16>(a, st);
 }
 
 // ------------------------------------------------------------------ weight gradient
@@ -447,35 +749,48 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
 #pragma unroll
     for (int i = 0; i < PG; ++i) bsum[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 
+    // Prefetch loads are unconditional (clamped addresses); validity and ReLU are applied at the LDS
+    // store, so nothing between the loads waits on memory.
+    unsigned g_okb = 0u, a_okb = 0u;
     auto fetch = [&](long long q0) {
+        g_okb = 0u;
+        a_okb = 0u;
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             const long long qq = q0 + g_dq[i];
-            if (g_lds[i] >= 0 && qq < d.Q) v = *reinterpret_cast<const float4*>(a.g + qq * a.Co + g_c[i]);
-            rg[i] = v;
+            const bool ok = g_lds[i] >= 0 && qq < d.Q;
+            rg[i] = *reinterpret_cast<const float4*>(a.g + (ok ? qq * a.Co + g_c[i] : 0));
+            g_okb |= (ok ? 1u : 0u) << i;
         }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             const long long qq = q0 + a_dq[i];
-            if (a_lds[i] >= 0 && qq >= 0 && qq < d.Q) v = *reinterpret_cast<const float4*>(a.a + qq * a.Ci + a_c[i]);
-            if (a.relu_in) {
-                v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-            }
-            ra[i] = v;
+            const bool ok = a_lds[i] >= 0 && qq >= 0 && qq < d.Q;
+            ra[i] = *reinterpret_cast<const float4*>(a.a + (ok ? qq * a.Ci + a_c[i] : 0));
+            a_okb |= (ok ? 1u : 0u) << i;
         }
     };
     auto stash = [&](long long q0) {
 #pragma unroll
-        for (int i = 0; i < PG; ++i)
-            if (g_lds[i] >= 0) {
-                *reinterpret_cast<float4*>(gs + g_lds[i]) = rg[i];
-                bsum[i].x += rg[i].x; bsum[i].y += rg[i].y; bsum[i].z += rg[i].z; bsum[i].w += rg[i].w;
-            }
+        for (int i = 0; i < PG; ++i) {
+            const unsigned mk = ((g_okb >> i) & 1u) ? 0xffffffffu : 0u;
+            float4 v = rg[i];
+            v.x = __uint_as_float(__float_as_uint(v.x) & mk); v.y = __uint_as_float(__float_as_uint(v.y) & mk);
+            v.z = __uint_as_float(__float_as_uint(v.z) & mk); v.w = __uint_as_float(__float_as_uint(v.w) & mk);
+            if (g_lds[i] >= 0) *reinterpret_cast<float4*>(gs + g_lds[i]) = v;
+            bsum[i].x += v.x; bsum[i].y += v.y; bsum[i].z += v.z; bsum[i].w += v.w;
+        }
 #pragma unroll
-        for (int i = 0; i < PA; ++i)
-            if (a_lds[i] >= 0) *reinterpret_cast<float4*>(as + a_lds[i]) = ra[i];
+        for (int i = 0; i < PA; ++i) {
+            const unsigned mk = ((a_okb >> i) & 1u) ? 0xffffffffu : 0u;
+            float4 v = ra[i];
+            v.x = __uint_as_float(__float_as_uint(v.x) & mk); v.y = __uint_as_float(__float_as_uint(v.y) & mk);
+            v.z = __uint_as_float(__float_as_uint(v.z) & mk); v.w = __uint_as_float(__float_as_uint(v.w) & mk);
+            if (a.relu_in) {
+                v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+            }
+            if (a_lds[i] >= 0) *reinterpret_cast<float4*>(as + a_lds[i]) = v;
+        }
         if (tid < kWgTM) vmask[tid] = tap_validity(q0 + tid, d);
     };
 
