@@ -1,7 +1,7 @@
 // In-LDS mixed-radix Stockham FFT building blocks for gfx950 (wave64).
 //
-// A transform of length N is a product of radices chosen at compile time (8, 4, 2 first, then 5, 3
-// and any other odd prime such as the 23 in 368 = 16 * 23).  Each stage reads R points at stride
+// A transform of length N is a product of radices chosen at compile time (16 or whatever
+// remains once it fits in registers, e.g. 368 = 16 * 23, 320 = 16 * 20, 640 = 16 * 8 * 5).  Each stage reads R points at stride
 // N/R from the LDS buffer, applies the stage twiddles and an R-point DFT held in registers, and
 // writes them back autosorted (in place, with a barrier between the reads and the writes), so the
 // result comes out in natural order with no bit-reversal pass.  Transforms are unnormalised here; callers scale at their global store.
@@ -136,24 +136,64 @@ template <int R, bool INV> __device__ __forceinline__ void dft_odd(float2 (&u)[R
     });
 }
 
+// First factor of an in-register DFT of length R: R itself for the base cases (2, 4, 8, odd primes).
+constexpr int first_factor(int R) {
+    if (R == 2 || R == 4 || R == 8) return R;
+    if (R % 8 == 0) return 8;
+    if (R % 4 == 0) return 4;
+    if (R % 2 == 0) return 2;
+    for (int p = 3; p * p <= R; p += 2)
+        if (R % p == 0) return p;
+    return R;
+}
+
+// DFT of any small length held in registers.  Composite R = R1*R2 is one Cooley-Tukey step with
+// literal twiddles: X[q1 + R1*q2] = sum_r2 w_R2^(r2 q2) * w_R^(r2 q1) * (sum_r1 w_R1^(r1 q1) u[r1*R2 + r2]).
 template <int R, bool INV> __device__ __forceinline__ void dft_r(float2 (&u)[R]) {
+    constexpr int R1 = first_factor(R);
     if constexpr (R == 1) {
-    } else if constexpr (R == 2) {
-        dft2<INV>(u[0], u[1]);
-    } else if constexpr (R == 4) {
-        dft4<INV>(u[0], u[1], u[2], u[3]);
-    } else if constexpr (R == 8) {
-        dft8<INV>(u);
+    } else if constexpr (R1 == R) {
+        if constexpr (R == 2) dft2<INV>(u[0], u[1]);
+        else if constexpr (R == 4) dft4<INV>(u[0], u[1], u[2], u[3]);
+        else if constexpr (R == 8) dft8<INV>(u);
+        else dft_odd<R, INV>(u);
     } else {
-        static_assert(R % 2 == 1, "radix must be 2, 4, 8 or an odd prime");
-        dft_odd<R, INV>(u);
+        constexpr int R2 = R / R1;
+        float2 y[R];
+        static_for<R2>([&](auto r2c) {
+            constexpr int r2 = decltype(r2c)::value;
+            float2 v[R1];
+            static_for<R1>([&](auto r1c) { v[decltype(r1c)::value] = u[decltype(r1c)::value * R2 + r2]; });
+            dft_r<R1, INV>(v);
+            static_for<R1>([&](auto q1c) {
+                constexpr int q1 = decltype(q1c)::value;
+                if constexpr (q1 * r2 == 0) {
+                    y[q1 * R2 + r2] = v[q1];
+                } else {
+                    constexpr float c = (float)ct_cos_frac(q1 * r2, R);
+                    constexpr float sn = (float)ct_sin_frac(q1 * r2, R);   // forward twiddle = c - i sn
+                    const float2 w = make_float2(c, INV ? sn : -sn);
+                    y[q1 * R2 + r2] = cmul(v[q1], w);
+                }
+            });
+        });
+        static_for<R1>([&](auto q1c) {
+            constexpr int q1 = decltype(q1c)::value;
+            float2 v[R2];
+            static_for<R2>([&](auto r2c) { v[decltype(r2c)::value] = y[q1 * R2 + decltype(r2c)::value]; });
+            dft_r<R2, INV>(v);
+            static_for<R2>([&](auto q2c) { u[q1 + R1 * decltype(q2c)::value] = v[decltype(q2c)::value]; });
+        });
     }
 }
 
 // ------------------------------------------------------------------ radix plan
-// Radix of the stage that follows a partial product P (P divides N).
+// Radix of the stage that follows a partial product P (P divides N): whatever is left once it fits in
+// registers (<= 24 points), otherwise the largest power of two up to 16, otherwise a small prime.
 constexpr int next_radix(int N, int P) {
     int m = N / P;
+    if (m <= 24) return m;
+    if (m % 16 == 0) return 16;
     if (m % 8 == 0) return 8;
     if (m % 4 == 0) return 4;
     if (m % 2 == 0) return 2;
@@ -161,37 +201,32 @@ constexpr int next_radix(int N, int P) {
         if (m % r == 0) return r;
     return 1;
 }
-constexpr int largest_prime_factor(int n) {
-    int best = 1;
-    for (int p = 2; p <= n; ++p)
-        while (n % p == 0) { best = p; n /= p; }
-    return best;
-}
 
-// LDS layouts.  Rows: line-major, element p of line l at l*N + p (threads walk p fastest).
-// Cols: position-major, element p of line l at p*L + l (threads walk l fastest), which matches a
-// tile of L neighbouring columns of a strided axis.
-template <int N, int L, bool COLS> struct Layout {
-    static constexpr int kElems = N * L;
-    __device__ static __forceinline__ int at(int line, int p) { return COLS ? p * L + line : line * N + p; }
+// LDS layout of a tile of L lines: position-major, element p of line l at p*(L + PAD) + l, and threads
+// walk l fastest.  With L a multiple of 16 every butterfly access of a wave covers whole 128-byte rows,
+// so the stages are bank-conflict free.  PAD = 1 lets a kernel whose GLOBAL rows run along p (threads
+// walking p fastest while loading and storing) transpose into this layout without conflicts either.
+template <int N, int L, int PAD> struct Layout {
+    static constexpr int kStride = L + PAD;
+    static constexpr int kElems = N * kStride;
+    __device__ static __forceinline__ int at(int line, int p) { return p * kStride + line; }
 };
 
 // One Stockham stage over L lines held in one LDS buffer, in place: every thread first pulls the
 // inputs of all its butterflies into registers, the workgroup synchronises, then results are written
 // back autosorted.  Ends with a barrier, so the buffer is ready for the next stage or for readers.
-template <int N, int L, bool COLS, bool INV, int P, int NT>
+template <int N, int L, int PAD, bool INV, int P, int NT>
 __device__ __forceinline__ void fft_stage(float2* __restrict__ buf, const float2* __restrict__ tw) {
     constexpr int R = next_radix(N, P);
     constexpr int T = N / R;
     constexpr int PER = (L * T + NT - 1) / NT;
-    using Lay = Layout<N, L, COLS>;
+    using Lay = Layout<N, L, PAD>;
     float2 u[PER][R];
 #pragma unroll
     for (int m = 0; m < PER; ++m) {
         const int idx = threadIdx.x + m * NT;
         if (PER * NT == L * T || idx < L * T) {
-            int line, i;
-            if (COLS) { line = idx % L; i = idx / L; } else { i = idx % T; line = idx / T; }
+            const int line = idx % L, i = idx / L;
 #pragma unroll
             for (int r = 0; r < R; ++r) u[m][r] = buf[Lay::at(line, i + r * T)];
         }
@@ -201,8 +236,7 @@ __device__ __forceinline__ void fft_stage(float2* __restrict__ buf, const float2
     for (int m = 0; m < PER; ++m) {
         const int idx = threadIdx.x + m * NT;
         if (PER * NT == L * T || idx < L * T) {
-            int line, i;
-            if (COLS) { line = idx % L; i = idx / L; } else { i = idx % T; line = idx / T; }
+            const int line = idx % L, i = idx / L;
             const int k = i % P;
             if constexpr (P > 1) {
                 constexpr int step = N / (P * R);
@@ -223,11 +257,11 @@ __device__ __forceinline__ void fft_stage(float2* __restrict__ buf, const float2
 
 // All stages, in place.  The caller synchronises after filling `buf`; the result is visible to the
 // whole workgroup on return.
-template <int N, int L, bool COLS, bool INV, int NT, int P = 1>
+template <int N, int L, int PAD, bool INV, int NT, int P = 1>
 __device__ __forceinline__ void fft_lines(float2* buf, const float2* tw) {
     if constexpr (P < N) {
-        fft_stage<N, L, COLS, INV, P, NT>(buf, tw);
-        fft_lines<N, L, COLS, INV, NT, P * next_radix(N, P)>(buf, tw);
+        fft_stage<N, L, PAD, INV, P, NT>(buf, tw);
+        fft_lines<N, L, PAD, INV, NT, P * next_radix(N, P)>(buf, tw);
     }
 }
 

@@ -14,14 +14,15 @@
 
 namespace gleam {
 
-constexpr int kNT = 256;  // threads per workgroup of every transform kernel
-
-template <int N> constexpr int rows_lines() {
-    int l = 1;
-    while (l * 2 * N <= 4096 && l < 64) l *= 2;
-    return l;
-}
-template <int N> constexpr int cols_lines() { return N > 320 ? 8 : 16; }
+// Lines (rows or columns) per workgroup tile and threads per workgroup, by transform length.  Tiles hold
+// 16 or more lines so that every LDS access of a butterfly stage is conflict free (see Layout).
+template <int N> constexpr int rows_lines() { return N > 384 ? 8 : (N >= 192 ? 16 : (N >= 96 ? 32 : 64)); }
+template <int N> constexpr int rows_threads() { return N * rows_lines<N>() >= 4096 ? 512 : 256; }
+// The coil-reduction kernel transforms fewer lines at a time: smaller tiles, more workgroups per CU.
+template <int N> constexpr int reduce_lines() { return N >= 192 ? 8 : rows_lines<N>(); }
+template <int N> constexpr int reduce_threads() { return N >= 192 ? 256 : rows_threads<N>(); }
+template <int N> constexpr int cols_lines() { return N >= 512 ? 8 : 16; }
+template <int N> constexpr int cols_threads() { return N >= 192 ? 512 : 256; }
 
 struct RowsArgs {
     const float2* x;      // image [B][T][DH][W]
@@ -29,18 +30,20 @@ struct RowsArgs {
     float2* k;            // k-space [B][C][T][DH][W]
     float2* out;          // image (reduce only)
     long long C, T, DH;   // DH = D*H rows per frame
-    long long n_rows;     // expand: B*C*T*DH ; reduce: B*T*DH
+    long long n_rows;     // expand: B*C*T*DH k-space rows ; reduce: B*T*DH image rows
     float scale;          // N^-1/2
     float xs, gs;         // reduce: out = xs*x + gs*g
 };
 
-// Forward transform along W of S*x, one k-space row per line.
+// Forward transform along W of S*x: L consecutive k-space rows per tile, coil multiply fused into the
+// load, two complex values (16 bytes) per global access.
 template <int N>
-__global__ __launch_bounds__(kNT) void rows_expand_kernel(RowsArgs a) {
-    constexpr int L = rows_lines<N>();
-    __shared__ float2 buf[N * L], tw[N];
+__global__ __launch_bounds__(rows_threads<N>()) void rows_expand_kernel(RowsArgs a) {
+    constexpr int L = rows_lines<N>(), NT = rows_threads<N>(), H2 = N / 2;
+    using Lay = Layout<N, L, 1>;
+    __shared__ float2 buf[Lay::kElems], tw[N];
     __shared__ long long xoff[L], soff[L];
-    fill_twiddles<N, kNT>(tw);
+    fill_twiddles<N, NT>(tw);
     const long long n_tiles = (a.n_rows + L - 1) / L;
     for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         __syncthreads();
@@ -58,38 +61,50 @@ __global__ __launch_bounds__(kNT) void rows_expand_kernel(RowsArgs a) {
             soff[threadIdx.x] = so;
         }
         __syncthreads();
-        for (int idx = threadIdx.x; idx < N * L; idx += kNT) {
-            const int line = idx / N, p = idx % N;
-            float2 v = make_float2(0.f, 0.f);
-            if (xoff[line] >= 0) v = cmul(a.S[soff[line] + p], a.x[xoff[line] + p]);
-            buf[idx] = v;
+        for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
+            const int line = idx / H2, p = 2 * (idx % H2);
+            float2 v0 = make_float2(0.f, 0.f), v1 = v0;
+            if (xoff[line] >= 0) {
+                const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[line] + p);
+                const float4 xv = *reinterpret_cast<const float4*>(a.x + xoff[line] + p);
+                v0 = cmul(make_float2(sv.x, sv.y), make_float2(xv.x, xv.y));
+                v1 = cmul(make_float2(sv.z, sv.w), make_float2(xv.z, xv.w));
+            }
+            buf[Lay::at(line, p)] = v0;
+            buf[Lay::at(line, p + 1)] = v1;
         }
         __syncthreads();
-        fft_lines<N, L, false, false, kNT>(buf, tw);
-        for (int idx = threadIdx.x; idx < N * L; idx += kNT) {
-            const int line = idx / N;
+        fft_lines<N, L, 1, false, NT>(buf, tw);
+        for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
+            const int line = idx / H2, p = 2 * (idx % H2);
             if (xoff[line] >= 0) {
-                const float2 v = buf[idx];
-                a.k[(tile * L + line) * N + idx % N] = make_float2(v.x * a.scale, v.y * a.scale);
+                const float2 v0 = buf[Lay::at(line, p)], v1 = buf[Lay::at(line, p + 1)];
+                *reinterpret_cast<float4*>(a.k + (tile * L + line) * N + p) =
+                    make_float4(v0.x * a.scale, v0.y * a.scale, v1.x * a.scale, v1.y * a.scale);
             }
         }
     }
 }
 
-// Inverse transform along W of every coil's row, then out = xs*x + gs*sum_c conj(S_c) * row_c.
+// Inverse transform along W and coil reduction.  A tile is LR image rows x CG coils (LR*CG <= L lines)
+// transformed together; then out = xs*x + gs * sum_c conj(S_c) * row_c is accumulated in registers,
+// looping over coil groups when C > CG.  The per-coil images never leave LDS.
 template <int N>
-__global__ __launch_bounds__(kNT) void rows_reduce_kernel(RowsArgs a) {
-    constexpr int L = rows_lines<N>();
-    constexpr int PER = (N * L + kNT - 1) / kNT;
-    __shared__ float2 buf[N * L], tw[N];
-    __shared__ long long koff[L], soff[L];   // offsets of coil 0; coil strides below
-    fill_twiddles<N, kNT>(tw);
-    const long long n_tiles = (a.n_rows + L - 1) / L;
+__global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsArgs a) {
+    constexpr int L = reduce_lines<N>(), NT = reduce_threads<N>(), H2 = N / 2;
+    constexpr int PER = (H2 * L + NT - 1) / NT;   // output pairs per thread (upper bound: CG = 1)
+    using Lay = Layout<N, L, 1>;
+    __shared__ float2 buf[Lay::kElems], tw[N];
+    __shared__ long long koff[L], soff[L];        // per image row of the tile, coil 0
+    fill_twiddles<N, NT>(tw);
+    const int CG = a.C < L ? (int)a.C : L;        // coils transformed together
+    const int LR = L / CG;                        // image rows per tile
+    const long long n_tiles = (a.n_rows + LR - 1) / LR;
     const long long kstride = a.T * a.DH * N, sstride = a.DH * N;
     for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         __syncthreads();
-        if (threadIdx.x < L) {
-            const long long row = tile * L + threadIdx.x;   // image row (b, t, dh)
+        if (threadIdx.x < LR) {
+            const long long row = tile * LR + threadIdx.x;   // image row (b, t, dh)
             long long ko = -1, so = -1;
             if (row < a.n_rows) {
                 const long long dh = row % a.DH;
@@ -102,47 +117,56 @@ __global__ __launch_bounds__(kNT) void rows_reduce_kernel(RowsArgs a) {
             soff[threadIdx.x] = so;
         }
         __syncthreads();
-        float2 acc[PER];
+        float4 acc[PER];
 #pragma unroll
-        for (int m = 0; m < PER; ++m) acc[m] = make_float2(0.f, 0.f);
-        for (long long c = 0; c < a.C; ++c) {
-            for (int idx = threadIdx.x; idx < N * L; idx += kNT) {
-                const int line = idx / N, p = idx % N;
-                float2 v = make_float2(0.f, 0.f);
-                if (koff[line] >= 0) v = a.k[koff[line] + c * kstride + p];
-                buf[idx] = v;
+        for (int m = 0; m < PER; ++m) acc[m] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int c0 = 0; c0 < a.C; c0 += CG) {
+            const int ncg = a.C - c0 < CG ? (int)(a.C - c0) : CG;
+            // line l = r*CG + c holds coil c0 + c of image row r; unused lines are zero
+            for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
+                const int line = idx / H2, p = 2 * (idx % H2);
+                const int r = line / CG, c = line % CG;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (r < LR && c < ncg && koff[r] >= 0)
+                    v = *reinterpret_cast<const float4*>(a.k + koff[r] + (c0 + c) * kstride + p);
+                buf[Lay::at(line, p)] = make_float2(v.x, v.y);
+                buf[Lay::at(line, p + 1)] = make_float2(v.z, v.w);
             }
             __syncthreads();
-            fft_lines<N, L, false, true, kNT>(buf, tw);
+            fft_lines<N, L, 1, true, NT>(buf, tw);
 #pragma unroll
             for (int m = 0; m < PER; ++m) {
-                const int idx = threadIdx.x + m * kNT;
-                if (idx < N * L) {
-                    const int line = idx / N;
-                    if (koff[line] >= 0) {
-                        const float2 sv = a.S[soff[line] + c * sstride + idx % N];
-                        const float2 pr = cmul_conj(buf[idx], sv);
-                        acc[m].x += pr.x;
-                        acc[m].y += pr.y;
+                const int e = threadIdx.x + m * NT;      // pair index over LR rows
+                if (e < H2 * LR) {
+                    const int r = e / H2, p = 2 * (e % H2);
+                    if (koff[r] >= 0) {
+                        for (int c = 0; c < ncg; ++c) {
+                            const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[r] + (c0 + c) * sstride + p);
+                            const float2 v0 = buf[Lay::at(r * CG + c, p)], v1 = buf[Lay::at(r * CG + c, p + 1)];
+                            const float2 p0 = cmul_conj(v0, make_float2(sv.x, sv.y));
+                            const float2 p1 = cmul_conj(v1, make_float2(sv.z, sv.w));
+                            acc[m].x += p0.x; acc[m].y += p0.y; acc[m].z += p1.x; acc[m].w += p1.y;
+                        }
                     }
                 }
             }
             __syncthreads();
         }
+        const float gsc = a.gs * a.scale;
 #pragma unroll
         for (int m = 0; m < PER; ++m) {
-            const int idx = threadIdx.x + m * kNT;
-            if (idx < N * L) {
-                const int line = idx / N;
-                if (koff[line] >= 0) {
-                    const long long o = (tile * L + line) * N + idx % N;
-                    float2 r = make_float2(a.gs * a.scale * acc[m].x, a.gs * a.scale * acc[m].y);
+            const int e = threadIdx.x + m * NT;
+            if (e < H2 * LR) {
+                const int r = e / H2, p = 2 * (e % H2);
+                if (koff[r] >= 0) {
+                    const long long o = (tile * LR + r) * N + p;
+                    float4 res = make_float4(gsc * acc[m].x, gsc * acc[m].y, gsc * acc[m].z, gsc * acc[m].w);
                     if (a.xs != 0.f) {
-                        const float2 xv = a.x[o];
-                        r.x = fmaf(a.xs, xv.x, r.x);
-                        r.y = fmaf(a.xs, xv.y, r.y);
+                        const float4 xv = *reinterpret_cast<const float4*>(a.x + o);
+                        res.x = fmaf(a.xs, xv.x, res.x); res.y = fmaf(a.xs, xv.y, res.y);
+                        res.z = fmaf(a.xs, xv.z, res.z); res.w = fmaf(a.xs, xv.w, res.w);
                     }
-                    a.out[o] = r;
+                    *reinterpret_cast<float4*>(a.out + o) = res;
                 }
             }
         }
@@ -153,69 +177,93 @@ struct ColsArgs {
     float2* k;             // k-space viewed as [outer][N][inner], transformed in place along N
     const float2* y;       // measured k-space, same view (mid only; may be null)
     const unsigned char* M;  // mask (mid only)
-    long long outer, inner;
+    long long outer, inner;  // inner is even (it is a product of transform lengths, all even)
     long long C, T, Dq;    // outer = ((b*C + c)*T + t)*Dq + dq ; mask row = (b*T + t)*Dq + dq
     float scale;           // N^-1/2, applied at the store (mid applies its forward N^-1/2 in LDS)
 };
 
-// MODE 0: forward, 1: inverse, 2: forward -> (mask ? k - y : 0) -> inverse.
+// Strided axis: a tile is 16 neighbouring columns (128 contiguous bytes per row) of one [N][inner] plane.
+// MODE 0: forward, 1: inverse, 2: forward -> (mask ? k - y : 0) -> inverse.  In MODE 2 the measured
+// k-space and the mask bytes of the tile are fetched into registers before the forward transform.
 template <int N, int MODE>
-__global__ __launch_bounds__(kNT) void cols_kernel(ColsArgs a) {
-    constexpr int L = cols_lines<N>();
-    __shared__ float2 buf[N * L], tw[N];
-    fill_twiddles<N, kNT>(tw);
+__global__ __launch_bounds__(cols_threads<N>()) void cols_kernel(ColsArgs a) {
+    constexpr int L = cols_lines<N>(), NT = cols_threads<N>(), L2 = L / 2;
+    constexpr int PER = (N * L2 + NT - 1) / NT;
+    using Lay = Layout<N, L, 0>;
+    __shared__ float2 buf[Lay::kElems], tw[N];
+    fill_twiddles<N, NT>(tw);
     const long long tiles_per = (a.inner + L - 1) / L;
     const long long n_tiles = a.outer * tiles_per;
     for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const long long o = tile / tiles_per;
         const long long i0 = (tile % tiles_per) * L;
         const long long base = o * N * a.inner + i0;
-        const int valid = (int)((a.inner - i0) < L ? (a.inner - i0) : L);
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < N * L; idx += kNT) {
-            const int l = idx % L, p = idx / L;
-            float2 v = make_float2(0.f, 0.f);
-            if (l < valid) v = a.k[base + (long long)p * a.inner + l];
-            buf[idx] = v;
-        }
-        __syncthreads();
-        if constexpr (MODE == 1) {
-            fft_lines<N, L, true, true, kNT>(buf, tw);
-        } else {
-            fft_lines<N, L, true, false, kNT>(buf, tw);
-        }
+        const int valid = (int)((a.inner - i0) < L ? (a.inner - i0) : L);   // even
+        long long mbase = 0;
         if constexpr (MODE == 2) {
             const long long dq = o % a.Dq;
             const long long t = (o / a.Dq) % a.T;
             const long long b = o / (a.Dq * a.T * a.C);
-            const long long mbase = ((b * a.T + t) * a.Dq + dq) * N * a.inner + i0;
-            // the forward transform of this axis carries N^-1/2; apply it before subtracting y
-            const float fs = rsqrtf((float)N);
-            for (int idx = threadIdx.x; idx < N * L; idx += kNT) {
-                const int l = idx % L, p = idx / L;
-                float2 r = make_float2(0.f, 0.f);
-                if (l < valid) {
-                    const long long off = (long long)p * a.inner + l;
-                    if (a.M[mbase + off] != 0) {
-                        const float2 v = buf[idx];
-                        r = make_float2(v.x * fs, v.y * fs);
-                        if (a.y != nullptr) {
-                            const float2 yv = a.y[base + off];
-                            r.x -= yv.x;
-                            r.y -= yv.y;
-                        }
+            mbase = ((b * a.T + t) * a.Dq + dq) * N * a.inner + i0;
+        }
+        __syncthreads();
+        float4 yv[MODE == 2 ? PER : 1];
+        unsigned mk[MODE == 2 ? PER : 1];
+#pragma unroll
+        for (int m = 0; m < PER; ++m) {
+            const int idx = threadIdx.x + m * NT;
+            if (idx < N * L2) {
+                const int l = 2 * (idx % L2), p = idx / L2;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                const long long off = (long long)p * a.inner + l;
+                if (l < valid) v = *reinterpret_cast<const float4*>(a.k + base + off);
+                buf[Lay::at(l, p)] = make_float2(v.x, v.y);
+                buf[Lay::at(l + 1, p)] = make_float2(v.z, v.w);
+                if constexpr (MODE == 2) {
+                    yv[m] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    mk[m] = 0u;
+                    if (l < valid) {
+                        mk[m] = *reinterpret_cast<const unsigned short*>(a.M + mbase + off);
+                        if (a.y != nullptr) yv[m] = *reinterpret_cast<const float4*>(a.y + base + off);
                     }
                 }
-                buf[idx] = r;
+            }
+        }
+        __syncthreads();
+        if constexpr (MODE == 1) {
+            fft_lines<N, L, 0, true, NT>(buf, tw);
+        } else {
+            fft_lines<N, L, 0, false, NT>(buf, tw);
+        }
+        if constexpr (MODE == 2) {
+            // the forward transform of this axis carries N^-1/2; apply it before subtracting y
+            const float fs = rsqrtf((float)N);
+#pragma unroll
+            for (int m = 0; m < PER; ++m) {
+                const int idx = threadIdx.x + m * NT;
+                if (idx < N * L2) {
+                    const int l = 2 * (idx % L2), p = idx / L2;
+                    const float2 v0 = buf[Lay::at(l, p)], v1 = buf[Lay::at(l + 1, p)];
+                    float2 r0 = make_float2(0.f, 0.f), r1 = r0;
+                    if (mk[m] & 0x00ffu) r0 = make_float2(v0.x * fs - yv[m].x, v0.y * fs - yv[m].y);
+                    if (mk[m] & 0xff00u) r1 = make_float2(v1.x * fs - yv[m].z, v1.y * fs - yv[m].w);
+                    buf[Lay::at(l, p)] = r0;
+                    buf[Lay::at(l + 1, p)] = r1;
+                }
             }
             __syncthreads();
-            fft_lines<N, L, true, true, kNT>(buf, tw);
+            fft_lines<N, L, 0, true, NT>(buf, tw);
         }
-        for (int idx = threadIdx.x; idx < N * L; idx += kNT) {
-            const int l = idx % L, p = idx / L;
-            if (l < valid) {
-                const float2 v = buf[idx];
-                a.k[base + (long long)p * a.inner + l] = make_float2(v.x * a.scale, v.y * a.scale);
+#pragma unroll
+        for (int m = 0; m < PER; ++m) {
+            const int idx = threadIdx.x + m * NT;
+            if (idx < N * L2) {
+                const int l = 2 * (idx % L2), p = idx / L2;
+                if (l < valid) {
+                    const float2 v0 = buf[Lay::at(l, p)], v1 = buf[Lay::at(l + 1, p)];
+                    *reinterpret_cast<float4*>(a.k + base + (long long)p * a.inner + l) =
+                        make_float4(v0.x * a.scale, v0.y * a.scale, v1.x * a.scale, v1.y * a.scale);
+                }
             }
         }
     }
@@ -244,9 +292,12 @@ static hipError_t launch_rows(bool reduce, int N, const RowsArgs& a, hipStream_t
     switch (N) {
 #define X(NN)                                                                                          \
     case NN: {                                                                                         \
-        const long long tiles = (a.n_rows + rows_lines<NN>() - 1) / rows_lines<NN>();                  \
-        if (reduce) hipLaunchKernelGGL(rows_reduce_kernel<NN>, dim3(grid_for(tiles)), dim3(kNT), 0, st, a); \
-        else hipLaunchKernelGGL(rows_expand_kernel<NN>, dim3(grid_for(tiles)), dim3(kNT), 0, st, a);   \
+        constexpr int L_ = rows_lines<NN>(), LR_ = reduce_lines<NN>();                                 \
+        const int cg = a.C < LR_ ? (int)a.C : LR_;                                                     \
+        const long long per = reduce ? LR_ / cg : L_;                                                  \
+        const long long tiles = (a.n_rows + per - 1) / per;                                            \
+        if (reduce) hipLaunchKernelGGL(rows_reduce_kernel<NN>, dim3(grid_for(tiles)), dim3(reduce_threads<NN>()), 0, st, a); \
+        else hipLaunchKernelGGL(rows_expand_kernel<NN>, dim3(grid_for(tiles)), dim3(rows_threads<NN>()), 0, st, a);   \
         break;                                                                                         \
     }
         GLEAM_FFT_SIZES(X)
@@ -261,7 +312,7 @@ static hipError_t launch_cols(int mode, int N, const ColsArgs& a, hipStream_t st
 #define X(NN)                                                                                          \
     case NN: {                                                                                         \
         const long long tiles = a.outer * ((a.inner + cols_lines<NN>() - 1) / cols_lines<NN>());       \
-        const dim3 g(grid_for(tiles)), b(kNT);                                                         \
+        const dim3 g(grid_for(tiles)), b(cols_threads<NN>());                                                         \
         if (mode == 0) hipLaunchKernelGGL((cols_kernel<NN, 0>), g, b, 0, st, a);                       \
         else if (mode == 1) hipLaunchKernelGGL((cols_kernel<NN, 1>), g, b, 0, st, a);                  \
         else hipLaunchKernelGGL((cols_kernel<NN, 2>), g, b, 0, st, a);                                 \
