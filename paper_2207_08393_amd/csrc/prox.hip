@@ -484,6 +484,85 @@ __global__ __launch_bounds__(kConvThreads) void conv_dlds_kernel(ConvArgs a) {
     }
 }
 
+// Convolution whose INPUT has two channels (first layer forward; data gradient of a layer whose output
+// is the 2-channel image): K = 2 -> Nn wide.  HBM-bound on the output, so no MFMA: lanes index the
+// output channel and keep their 2*taps weights in registers; the 2-channel input rows around the current
+// image row sit in LDS, zero-filled outside the grid, and are read as wave-wide broadcasts.  Same fused
+// epilogue as conv_dlds_kernel.  Source weight (n, tap, e) at w[n*sn + tapidx*st + e*sk].
+struct ConvThinInArgs {
+    ConvArgs c;          // in = [Q][2]; wt unused
+    const float* w;
+    long long sn, st, sk;
+};
+
+template <int KT, int KD, int KH, int KW>
+__global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
+    constexpr int RT = KT * KD * KH, TAPS = RT * KW, TH = 2;
+    extern __shared__ float smem[];
+    const ConvArgs& a = ta.c;
+    const PixDims d = a.d;
+    const int WS = d.W + KW - 1;
+    float* slab = smem;   // [RT][WS][2]
+    const int WCr = (a.Nn + 63) / 64 * 64;
+    const int groups = 256 / WCr;
+    const int n = threadIdx.x % WCr;
+    const int pg = __builtin_amdgcn_readfirstlane(threadIdx.x / WCr);
+    const bool n_ok = n < a.Nn;
+    const int nc = n_ok ? n : 0;
+    float wreg[TAPS][TH];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) {
+        const int tapidx = a.flip ? TAPS - 1 - t : t;
+#pragma unroll
+        for (int e = 0; e < TH; ++e) wreg[t][e] = ta.w[nc * ta.sn + tapidx * ta.st + e * ta.sk];
+    }
+    const float bias = (a.bias && n_ok) ? a.bias[n] : 0.f;
+    const long long n_rows = d.Q / d.W;
+    for (long long row = blockIdx.x; row < n_rows; row += gridDim.x) {
+        long long r = row;
+        const int hh = (int)(r % d.H);
+        r /= d.H;
+        const int dd = (int)(r % d.D);
+        r /= d.D;
+        const int tt = (int)(r % d.T);
+        __syncthreads();
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int ih = rt % KH, id = (rt / KH) % KD, it = rt / (KH * KD);
+            const int ot = it - KT / 2, od = id - KD / 2, oh = ih - KH / 2;
+            const bool row_ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D && hh + oh >= 0 && hh + oh < d.H;
+            const long long src_row = row + ((long long)ot * d.D + od) * d.H + oh;
+            for (int idx = threadIdx.x; idx < WS * TH; idx += 256) {
+                const int col = idx / TH - KW / 2, e = idx % TH;
+                float v = 0.f;
+                if (row_ok && col >= 0 && col < d.W) v = a.in[(src_row * d.W + col) * TH + e];
+                if (a.relu_in) v = fmaxf(v, 0.f);
+                slab[rt * WS * TH + idx] = v;
+            }
+        }
+        __syncthreads();
+        for (int w = pg; w < d.W; w += groups) {
+            float acc = bias;
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int iw = 0; iw < KW; ++iw) {
+                    const float* tp = slab + (rt * WS + w + iw) * TH;
+                    acc = fmaf(wreg[rt * KW + iw][0], tp[0], acc);
+                    acc = fmaf(wreg[rt * KW + iw][1], tp[1], acc);
+                }
+            if (n_ok) {
+                const long long o = (row * d.W + w) * a.Nn + n;
+                if (a.relu_out) acc = fmaxf(acc, 0.f);
+                const float ref = a.mask_ref ? a.mask_ref[o] : 1.f;
+                if (a.mask_acc) acc = ref > 0.f ? acc : 0.f;
+                if (a.add) acc += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o];
+                a.out[o] = acc;
+            }
+        }
+    }
+}
+
 // Re-lays one layer's weights as the LDS images conv_mfma_kernel<NB, CK> copies verbatim.  Image
 // (rt, kc, nb) holds row-tap rt, input-channel chunk kc and output-channel block nb as
 // [kw][CK/8][2][NB][4]: element (dw, k = 8g + 4h + s, n) at (((dw*G + g)*2 + h)*NB + n)*4 + s, zero
@@ -576,8 +655,32 @@ static size_t conv_wimg_floats(int K, int Nn, int taps) {
     return (size_t)taps * ((K + ck - 1) / ck) * ck * ((Nn + nb - 1) / nb) * nb;
 }
 
+template <int KT, int KD, int KH, int KW>
+static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, hipStream_t st) {
+    ConvThinInArgs t{a, cw.w, cw.sn, cw.st, cw.sk};
+    const long long n_rows = a.d.Q / a.d.W;
+    const size_t lds = (size_t)KT * KD * KH * (a.d.W + KW - 1) * 2 * sizeof(float);
+    const long long cap = 256LL * 8;
+    hipLaunchKernelGGL((conv_thin_in_kernel<KT, KD, KH, KW>), dim3((unsigned)(n_rows < cap ? n_rows : cap)), dim3(256), lds, st, t);
+}
+
 static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scratch, hipStream_t st) {
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
+    {   // two input channels and a wide output: HBM-bound kernel without MFMA
+        const int wr = (a.Nn + 63) / 64 * 64;
+        if (a.K == 2 && a.Nn >= 8 && wr <= 256 && 256 % wr == 0) {
+            char name[56];
+            snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
+            KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, 4.0 * (double)a.d.Q * (a.K + a.Nn), st);
+            const PixDims& d = a.d;
+            bool hit = true;
+            if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) launch_conv_thin_in_t<1, 1, 3, 3>(a, cw, st);
+            else if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) launch_conv_thin_in_t<1, 3, 3, 3>(a, cw, st);
+            else if (d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1) launch_conv_thin_in_t<3, 1, 1, 1>(a, cw, st);
+            else hit = false;
+            if (hit) return hipGetLastError();
+        }
+    }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
     {
         WimgArgs t{};
@@ -891,14 +994,15 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
 
 // Weight gradient of a layer whose input OR output has very few channels (the 2-channel image side):
 // HBM-bound, so no MFMA.  Lanes index the wide channel dimension; the wide tensor is read once per
-// pixel (coalesced), the thin tensor at the tap-shifted pixel is wave-uniform.
+// pixel (coalesced); the thin tensor's rows around the current image row sit in LDS, zero-filled where
+// a tap falls outside the grid, and are read as wave-wide broadcasts - no validity test in the loop.
 //   THIN_IN  (cin thin):  dw[co][tap][ci] += g[q][co] * a[q + off(tap)][ci]          lanes = co
 //   !THIN_IN (cout thin): dw[co][tap][ci] += a[q'][ci] * g[q' - off(tap)][co]        lanes = ci
 struct WgradThinArgs {
     const float* wide;   // [Q][WC]
     const float* thin;   // [Q][TH]
-    float* partial;      // [n_split][Co][taps][Ci]
-    float* bias_partial; // [n_split][Co] or null
+    float* partial;      // [gridDim.x][Co][taps][Ci]
+    float* bias_partial; // [gridDim.x][Co] or null
     int WC;              // wide channels (<= 256, 256 % round64(WC) == 0)
     int relu_in;
     PixDims d;
@@ -906,18 +1010,19 @@ struct WgradThinArgs {
 
 template <int KT, int KD, int KH, int KW, int TH, bool THIN_IN>
 __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
-    constexpr int TAPS = KT * KD * KH * KW;
-    __shared__ float red[256];
+    constexpr int RT = KT * KD * KH, TAPS = RT * KW;
+    constexpr int sgn = THIN_IN ? 1 : -1;
+    extern __shared__ float smem[];
     const PixDims d = a.d;
+    const int WS = d.W + KW - 1;            // slab columns: image columns -KW/2 .. W-1+KW/2
+    float* slab = smem;                     // [RT][WS][TH]
+    float* red = smem + RT * WS * TH;       // [256]
     const int WCr = (a.WC + 63) / 64 * 64;
     const int groups = 256 / WCr;
     const int c = threadIdx.x % WCr;
     const int pg = __builtin_amdgcn_readfirstlane(threadIdx.x / WCr);
     const bool c_ok = c < a.WC;
-    const long long n_runs = (long long)gridDim.x * groups;
-    const long long run_len = (d.Q + n_runs - 1) / n_runs;
-    const long long qa = ((long long)blockIdx.x * groups + pg) * run_len;
-    const long long qb = qa + run_len < d.Q ? qa + run_len : d.Q;
+    const long long n_rows = d.Q / d.W;
 
     float acc[TAPS][TH];
     float bs[THIN_IN ? 1 : TH];
@@ -928,55 +1033,45 @@ __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
 #pragma unroll
     for (int e = 0; e < (THIN_IN ? 1 : TH); ++e) bs[e] = 0.f;
 
-    if (qa < qb) {
-        int w = (int)(qa % d.W);
-        long long r = qa / d.W;
-        int hh = (int)(r % d.H);
+    for (long long row = blockIdx.x; row < n_rows; row += gridDim.x) {
+        long long r = row;
+        const int hh = (int)(r % d.H);
         r /= d.H;
-        int dd = (int)(r % d.D);
+        const int dd = (int)(r % d.D);
         r /= d.D;
-        int tt = (int)(r % d.T);
-        constexpr int sgn = THIN_IN ? 1 : -1;
-        for (long long q = qa; q < qb; ++q) {
-            float wv = c_ok ? a.wide[q * a.WC + c] : 0.f;
+        const int tt = (int)(r % d.T);
+        __syncthreads();
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int ih = rt % KH, id = (rt / KH) % KD, it = rt / (KH * KD);
+            const int ot = sgn * (it - KT / 2), od = sgn * (id - KD / 2), oh = sgn * (ih - KH / 2);
+            const bool row_ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D && hh + oh >= 0 && hh + oh < d.H;
+            const long long src_row = row + ((long long)ot * d.D + od) * d.H + oh;
+            for (int idx = threadIdx.x; idx < WS * TH; idx += 256) {
+                const int col = idx / TH - KW / 2, e = idx % TH;
+                float v = 0.f;
+                if (row_ok && col >= 0 && col < d.W) v = a.thin[(src_row * d.W + col) * TH + e];
+                if (THIN_IN && a.relu_in) v = fmaxf(v, 0.f);
+                slab[rt * WS * TH + idx] = v;
+            }
+        }
+        __syncthreads();
+        for (int w = pg; w < d.W; w += groups) {
+            float wv = c_ok ? a.wide[(row * d.W + w) * a.WC + c] : 0.f;
             if (!THIN_IN && a.relu_in) wv = fmaxf(wv, 0.f);
             if (THIN_IN) bs[0] += wv;
 #pragma unroll
-            for (int it = 0; it < KT; ++it)
+            for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-                for (int id = 0; id < KD; ++id)
+                for (int iw = 0; iw < KW; ++iw) {
+                    const float* tp = slab + (rt * WS + w + (THIN_IN ? iw : KW - 1 - iw)) * TH;
 #pragma unroll
-                    for (int ih = 0; ih < KH; ++ih)
-#pragma unroll
-                        for (int iw = 0; iw < KW; ++iw) {
-                            const int ot = sgn * (it - KT / 2), od = sgn * (id - KD / 2);
-                            const int oh = sgn * (ih - KH / 2), ow = sgn * (iw - KW / 2);
-                            const bool ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D &&
-                                            hh + oh >= 0 && hh + oh < d.H && w + ow >= 0 && w + ow < d.W;
-                            if (ok) {
-                                const long long qq = q + (((long long)ot * d.D + od) * d.H + oh) * d.W + ow;
-                                const int tap = ((it * KD + id) * KH + ih) * KW + iw;
-#pragma unroll
-                                for (int e = 0; e < TH; ++e) {
-                                    float tv = a.thin[qq * TH + e];
-                                    if (THIN_IN && a.relu_in) tv = fmaxf(tv, 0.f);
-                                    acc[tap][e] = fmaf(wv, tv, acc[tap][e]);
-                                }
-                            }
-                        }
-            if (!THIN_IN) {
-#pragma unroll
-                for (int e = 0; e < TH; ++e) bs[e] += a.thin[q * TH + e];
-            }
-            if (++w == d.W) {
-                w = 0;
-                if (++hh == d.H) {
-                    hh = 0;
-                    if (++dd == d.D) {
-                        dd = 0;
-                        if (++tt == d.T) tt = 0;
-                    }
+                    for (int e = 0; e < TH; ++e) acc[rt * KW + iw][e] = fmaf(wv, tp[e], acc[rt * KW + iw][e]);
                 }
+            if (!THIN_IN) {
+                const float* tp = slab + ((RT / 2) * WS + w + KW / 2) * TH;   // centre tap = the pixel itself
+#pragma unroll
+                for (int e = 0; e < TH; ++e) bs[e] += tp[e];
             }
         }
     }
@@ -1217,12 +1312,13 @@ template <int KT, int KD, int KH, int KW>
 static void launch_wgrad_thin_t(const WgradArgs& a, float* bias_partial, int n_split, hipStream_t st) {
     WgradThinArgs t{};
     t.partial = a.partial; t.bias_partial = bias_partial; t.relu_in = a.relu_in; t.d = a.d;
+    const size_t lds = ((size_t)KT * KD * KH * (a.d.W + KW - 1) * 2 + 256) * sizeof(float);
     if (a.Ci == 2) {
         t.wide = a.g; t.thin = a.a; t.WC = a.Co;
-        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, true>), dim3(n_split), dim3(256), 0, st, t);
+        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, true>), dim3(n_split), dim3(256), lds, st, t);
     } else {
         t.wide = a.a; t.thin = a.g; t.WC = a.Ci;
-        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, false>), dim3(n_split), dim3(256), 0, st, t);
+        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, false>), dim3(n_split), dim3(256), lds, st, t);
     }
 }
 
