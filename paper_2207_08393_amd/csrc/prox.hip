@@ -709,6 +709,7 @@ struct WgradArgs {
 };
 
 constexpr int kWgTM = 32;  // pixels per staged chunk
+constexpr int kThinSplit = 1024;  // most partial sums the thin weight-gradient kernel writes
 
 template <int JT>
 __global__ __launch_bounds__(kConvThreads) void wgrad_mfma_kernel(WgradArgs a) {
@@ -806,8 +807,9 @@ struct WgradPipeArgs {
     float* bias_partial;  // [n_split][Co] or null
 };
 
-template <int JT, int PG, int PA>
-__global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs pa) {
+template <int JT, int PG, int PA, int NW>
+__global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
+    constexpr int NT = NW * 64;
     extern __shared__ float smem[];
     const WgradArgs& a = pa.w;
     const PixDims d = a.d;
@@ -821,7 +823,7 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, m = lane & 31, h = lane >> 5;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32, tapgroups = (taps + JT - 1) / JT;
-    const int job = blockIdx.y * 4 + wave;
+    const int job = blockIdx.y * NW + wave;
     const bool active = job < ncb * nib * tapgroups;
     const int tg = job % tapgroups, pair = job / tapgroups;
     const int cb = pair / nib, ib = pair % nib;
@@ -833,7 +835,7 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
     int a_lds[PA], a_dq[PA], a_c[PA];
 #pragma unroll
     for (int i = 0; i < PG; ++i) {
-        const int v = tid + i * kConvThreads;
+        const int v = tid + i * NT;
         const int p = v / Co4, c4 = v % Co4;
         g_lds[i] = v < n_g4 ? p * RSg + 4 * c4 : -1;
         g_dq[i] = p;
@@ -841,7 +843,7 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
     }
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
-        const int v = tid + i * kConvThreads;
+        const int v = tid + i * NT;
         const int rt = v / (n_pa * Ci4), r = v % (n_pa * Ci4);
         const int p = r / Ci4, c4 = r % Ci4;
         a_lds[i] = v < n_a4 ? (rt * n_pa + p) * RSa + 4 * c4 : -1;
@@ -978,12 +980,12 @@ __global__ __launch_bounds__(kConvThreads) void wgrad_pipe_kernel(WgradPipeArgs 
         __syncthreads();
         float4* red = reinterpret_cast<float4*>(smem);  // [PG*256] float4 <= staging area
 #pragma unroll
-        for (int i = 0; i < PG; ++i) red[tid + i * kConvThreads] = g_lds[i] >= 0 ? bsum[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < PG; ++i) red[tid + i * NT] = g_lds[i] >= 0 ? bsum[i] : make_float4(0.f, 0.f, 0.f, 0.f);
         __syncthreads();
         if (tid < a.Co) {
             const int c4 = tid / 4, e = tid % 4;
             float t = 0.f;
-            for (int v = c4; v < PG * kConvThreads; v += Co4) {
+            for (int v = c4; v < PG * NT; v += Co4) {
                 const float4 x = red[v];
                 t += e == 0 ? x.x : (e == 1 ? x.y : (e == 2 ? x.z : x.w));
             }
@@ -1113,21 +1115,27 @@ __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
     }
 }
 
-// out[i] = sum_s partial[s][i], s ascending (fixed order => run-to-run identical bits).
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_split, long long n, float* __restrict__ out) {
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+// out[i] = sum_s partial[s][i], s ascending (fixed order => run-to-run identical bits).  Two segments in
+// one launch: the weight-gradient partials (n elements) and, when n2 > 0, the bias-gradient partials.
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_split, long long n, float* __restrict__ out,
+                                       const float* __restrict__ partial2, long long n2, float* __restrict__ out2) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n + n2) return;
+    const float* src = partial;
+    float* dst = out;
+    long long stride = n;
+    if (i >= n) { i -= n; src = partial2; dst = out2; stride = n2; }
     float s = 0.f;
     int k = 0;
     for (; k + 8 <= n_split; k += 8) {  // 8 independent loads in flight, summed in ascending order
         float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(k + u) * n + i];
+        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(k + u) * stride + i];
 #pragma unroll
         for (int u = 0; u < 8; ++u) s += v[u];
     }
-    for (; k < n_split; ++k) s += partial[(size_t)k * n + i];
-    out[i] = s;
+    for (; k < n_split; ++k) s += src[(size_t)k * stride + i];
+    dst[i] = s;
 }
 
 // partial[blk][c] = sum over this workgroup's pixels of g[q][c]  (bias gradient).
@@ -1229,7 +1237,7 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
 
     // split-K: enough workgroups to fill the chip, never more than there are pixel chunks
     const long long chunks = (plan.Q + kWgTM - 1) / kWgTM;
-    plan.n_split = (int)(chunks < 512 ? chunks : 512);
+    plan.n_split = (int)(chunks < 256 ? chunks : 256);
 
     size_t w = 0;
     plan.grad_off[0] = 0;
@@ -1242,7 +1250,7 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     plan.partial_bytes = align256((size_t)plan.n_split * max_w * sizeof(float));
     w += plan.partial_bytes;
     plan.bias_partial_off = w;
-    w += align256((size_t)plan.n_split * kMaxChannels * sizeof(float));
+    w += align256((size_t)kThinSplit * kMaxChannels * sizeof(float));
     size_t max_img = 0;
     for (int l = 0; l < L; ++l) {
         const gleam_conv& c = p.layers[l];
@@ -1297,15 +1305,15 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
     return hipSuccess;
 }
 
-template <int JT, int PG, int PA>
+template <int JT, int PG, int PA, int NW>
 static void launch_wgrad_pipe_t(const WgradPipeArgs& pa, dim3 grid, size_t lds, hipStream_t st) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)wgrad_pipe_kernel<JT, PG, PA>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        (void)hipFuncSetAttribute((const void*)wgrad_pipe_kernel<JT, PG, PA, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         once = true;
     }
-    if (lds < (size_t)PG * kConvThreads * sizeof(float4)) lds = (size_t)PG * kConvThreads * sizeof(float4);
-    hipLaunchKernelGGL((wgrad_pipe_kernel<JT, PG, PA>), grid, dim3(kConvThreads), lds, st, pa);
+    if (lds < (size_t)PG * NW * 64 * sizeof(float4)) lds = (size_t)PG * NW * 64 * sizeof(float4);
+    hipLaunchKernelGGL((wgrad_pipe_kernel<JT, PG, PA, NW>), grid, dim3(NW * 64), lds, st, pa);
 }
 
 template <int KT, int KD, int KH, int KW>
@@ -1324,13 +1332,15 @@ static void launch_wgrad_thin_t(const WgradArgs& a, float* bias_partial, int n_s
 
 // Launches the weight-gradient kernel that fits the layer.  *bias_done is set when the kernel also
 // wrote the bias-gradient partials (bias_partial non-null on entry).
-static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bias_done, int n_split, hipStream_t st) {
+static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bias_done, int n_split, size_t partial_floats,
+                               int* used_split, hipStream_t st) {
     const PixDims& d = a.d;
     const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
     char name[56];
     snprintf(name, sizeof(name), "conv_wgrad_%dto%d_t%d", a.Ci, a.Co, taps);
     KernelScope ks(name, 2.0 * (double)d.Q * a.Ci * a.Co * taps, 4.0 * (double)d.Q * (a.Ci + a.Co), st);
     *bias_done = false;
+    *used_split = n_split;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
     const int jt = taps >= 9 ? 9 : 3;
     const int tapgroups = (taps + jt - 1) / jt;
@@ -1340,12 +1350,19 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
     const int wide = a.Ci == 2 ? a.Co : a.Ci;
     const int wide_r = (wide + 63) / 64 * 64;
     if ((a.Ci == 2) != (a.Co == 2) && wide >= 8 && wide_r <= 256 && 256 % wide_r == 0) {
+        // HBM-bound: one workgroup per image row up to kThinSplit partials (as many as the scratch holds)
+        long long ts = d.Q / d.W;
+        if (ts > kThinSplit) ts = kThinSplit;
+        const long long fit = (long long)(partial_floats / ((size_t)a.Co * taps * a.Ci));
+        if (ts > fit) ts = fit;
+        const int tsplit = (int)(ts < 1 ? 1 : ts);
         bool hit = true;
-        if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 1, 3, 3>(a, bias_partial, n_split, st);
-        else if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 3, 3, 3>(a, bias_partial, n_split, st);
-        else if (d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1) launch_wgrad_thin_t<3, 1, 1, 1>(a, bias_partial, n_split, st);
+        if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 1, 3, 3>(a, bias_partial, tsplit, st);
+        else if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 3, 3, 3>(a, bias_partial, tsplit, st);
+        else if (d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1) launch_wgrad_thin_t<3, 1, 1, 1>(a, bias_partial, tsplit, st);
         else hit = false;
         if (hit) {
+            *used_split = tsplit;
             *bias_done = bias_partial != nullptr;
             return hipGetLastError();
         }
@@ -1358,12 +1375,22 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
         const size_t lds = ((size_t)kWgTM * (a.Co + 4) + (size_t)rowtaps * n_pa * (a.Ci + 4) + kWgTM) * sizeof(float);
         WgradPipeArgs pa{a, bias_partial};
         bool hit = true;
+        bool hit_none = true;
+        // 9 taps on a 2x2 grid of 32x32 channel blocks: eight waves, each one block and 5 (or 4) taps, so
+        // that two waves share a SIMD and cover each other's LDS and issue latencies
+        if (taps == 9 && ncb * nib == 4) {
+            const int pg8 = (kWgTM * (a.Co / 4) + 511) / 512, pa8 = (rowtaps * n_pa * (a.Ci / 4) + 511) / 512;
+            if (pg8 <= 1 && pa8 <= 4) {
+                dim3 g8(n_split, 1);
+                launch_wgrad_pipe_t<5, 1, 4, 8>(pa, g8, lds, st);
+                hit_none = false;
+            }
+        }
 #define GLEAM_WG_TRY(JT_, PG_, PA_)                                             \
     if (hit_none && jt == JT_ && need_pg <= PG_ && need_pa <= PA_) {            \
-        launch_wgrad_pipe_t<JT_, PG_, PA_>(pa, grid, lds, st);                  \
+        launch_wgrad_pipe_t<JT_, PG_, PA_, 4>(pa, grid, lds, st);               \
         hit_none = false;                                                       \
     }
-        bool hit_none = true;
         GLEAM_WG_TRY(9, 1, 4) GLEAM_WG_TRY(9, 2, 8) GLEAM_WG_TRY(9, 1, 16) GLEAM_WG_TRY(9, 4, 16)
         GLEAM_WG_TRY(3, 1, 4) GLEAM_WG_TRY(3, 2, 8) GLEAM_WG_TRY(3, 1, 16) GLEAM_WG_TRY(3, 4, 16)
 #undef GLEAM_WG_TRY
@@ -1423,20 +1450,21 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         wa.Co = c.cout; wa.Ci = c.cin; wa.relu_in = c.relu_in; wa.d = d;
         float* bpart = reinterpret_cast<float*>(wsb + plan.bias_partial_off);
         bool bias_done = false;
-        hipError_t e = launch_wgrad(wa, c.has_bias ? bpart : nullptr, &bias_done, plan.n_split, st);
+        int used_split = plan.n_split;
+        hipError_t e = launch_wgrad(wa, c.has_bias ? bpart : nullptr, &bias_done, plan.n_split,
+                                    plan.partial_bytes / sizeof(float), &used_split, st);
         if (e != hipSuccess) return e;
         const long long nw = (long long)(c.cout * taps * c.cin);
-        {
-            KernelScope ks("wgrad_reduce", 0.0, 4.0 * (double)nw * (plan.n_split + 1), st);
-            hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st,
-                               (const float*)partial, plan.n_split, nw, grad_theta + plan.w_off[l - 1]);
+        if (c.has_bias && !bias_done) {
+            KernelScope ks("bias_grad", 0.0, 4.0 * (double)plan.Q * c.cout, st);
+            hipLaunchKernelGGL(colsum_kernel, dim3(used_split), dim3(256), 0, st, (const float*)G(l), plan.Q, c.cout, bpart);
         }
-        if (c.has_bias) {
-            KernelScope ks("bias_grad", 0.0, bias_done ? 0.0 : 4.0 * (double)plan.Q * c.cout, st);
-            if (!bias_done)
-                hipLaunchKernelGGL(colsum_kernel, dim3(plan.n_split), dim3(256), 0, st, (const float*)G(l), plan.Q, c.cout, bpart);
-            hipLaunchKernelGGL(reduce_partials_kernel, dim3((c.cout + 255) / 256), dim3(256), 0, st,
-                               (const float*)bpart, plan.n_split, (long long)c.cout, grad_theta + plan.b_off[l - 1]);
+        {
+            const long long nb = c.has_bias ? c.cout : 0;
+            KernelScope ks("wgrad_reduce", 0.0, 4.0 * (double)(nw + nb) * (used_split + 1), st);
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((nw + nb + 255) / 256)), dim3(256), 0, st,
+                               (const float*)partial, used_split, nw, grad_theta + plan.w_off[l - 1],
+                               (const float*)bpart, nb, c.has_bias ? grad_theta + plan.b_off[l - 1] : nullptr);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
