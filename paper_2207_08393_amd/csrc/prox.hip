@@ -29,6 +29,24 @@ struct PixDims {
     long long Q;
 };
 
+// XCD-aware work split.  Workgroups are dealt to the 8 XCDs round-robin by their linear id, and each XCD
+// has its own L2.  Work items (pixel tiles or chunks) that re-read each other's rows - the row taps of a
+// convolution - should therefore run on the same XCD at about the same time: XCD x owns one contiguous
+// eighth of the items and its workgroups walk that range with stride = workgroups per XCD.
+// gridDim.x must be a multiple of 8 (launchers round up; surplus workgroups get an empty range).
+struct XcdRange {
+    long long first, end, stride;
+};
+__device__ __forceinline__ XcdRange xcd_range(long long n_items) {
+    const long long per_xcd = (n_items + 7) / 8;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    XcdRange r;
+    r.first = xcd * per_xcd + slot;
+    r.end = (xcd + 1) * per_xcd < n_items ? (xcd + 1) * per_xcd : n_items;
+    r.stride = gridDim.x >> 3;
+    return r;
+}
+
 // Bit `tap` is set when pixel q + off(tap) lies inside the grid (same sample, frame, slice, row).
 __device__ __forceinline__ unsigned tap_validity(long long q, const PixDims& d) {
     if (q >= d.Q) return 0u;
@@ -316,9 +334,9 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
 // GLOBAL address, which keeps the 128-bit operand reads bank-conflict free.  Pixels or channels past
 // the tensor are read from a clamped address: they only ever meet masked taps or zero weights.
 // Requires K % 4 == 0 (16-byte alignment of every quad).
-template <int NB, int CK, int PJ>
-__global__ __launch_bounds__(kConvThreads) void conv_dlds_kernel(ConvArgs a) {
-    constexpr int TM = 128 * PJ, G = CK / 8, NJ = NB / 32, Q4 = CK / 4;
+template <int NB, int CK, int PJ, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
+    constexpr int TM = NW * 32 * PJ, G = CK / 8, NJ = NB / 32, Q4 = CK / 4;
     constexpr int RP = Q4 >= 8 ? 1 : 8 / Q4;   // pixel rows per 128 bytes of LDS
     extern __shared__ float smem[];
     const PixDims d = a.d;
@@ -341,7 +359,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_dlds_kernel(ConvArgs a) {
         const int rt = c / n_kc, kc = c % n_kc;
         const long long qs = tile * TM + rowtap_offset(rt, d) - d.kw / 2;
         float* dst = smem + buf * buf_floats;
-        for (int o = wave; o < slab_ops; o += 4) {
+        for (int o = wave; o < slab_ops; o += NW) {
             const int v = o * 64 + lane;
             const int pp = v / Q4, pos = v % Q4;
             const int c4 = pos ^ ((pp / RP) % Q4);
@@ -352,7 +370,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_dlds_kernel(ConvArgs a) {
         }
         const float* src = a.wt + ((size_t)(rt * n_kc + kc) * gridDim.y + blockIdx.y) * (size_t)(d.kw * CK * NB);
         float* wdst = dst + slab_ops * 256;
-        for (int o = wave; o < w_ops; o += 4) {
+        for (int o = wave; o < w_ops; o += NW) {
             int v = o * 64 + lane;
             v = v < w4 ? v : 0;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + 4 * v),
@@ -360,12 +378,13 @@ __global__ __launch_bounds__(kConvThreads) void conv_dlds_kernel(ConvArgs a) {
         }
     };
 
-    long long tile = blockIdx.x;
+    const XcdRange xr = xcd_range(n_tiles);
+    long long tile = xr.first;
     int cur = 0;
-    if (tile < n_tiles) issue(tile, 0, 0);
+    if (tile < xr.end) issue(tile, 0, 0);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    for (; tile < n_tiles; tile += gridDim.x) {
+    for (; tile < xr.end; tile += xr.stride) {
         const long long q0 = tile * TM + wave * (32 * PJ) + m;
         unsigned vbits[PJ];
 #pragma unroll
@@ -380,8 +399,8 @@ __global__ __launch_bounds__(kConvThreads) void conv_dlds_kernel(ConvArgs a) {
 
         for (int c = 0; c < nck; ++c) {
             const bool last = c + 1 == nck;
-            const long long ntile = last ? tile + gridDim.x : tile;
-            if (ntile < n_tiles) issue(ntile, last ? 0 : c + 1, cur ^ 1);
+            const long long ntile = last ? tile + xr.stride : tile;
+            if (ntile < xr.end) issue(ntile, last ? 0 : c + 1, cur ^ 1);
             const float* slab = smem + cur * buf_floats;
             const float* wl = slab + slab_ops * 256;
             const int rt = c / n_kc;
@@ -608,27 +627,30 @@ static void launch_conv_k(const ConvArgs& a, dim3 grid, size_t lds, hipStream_t 
     hipLaunchKernelGGL((conv_mfma_kernel<NB, CK, KWMAX, VEC>), grid, dim3(kConvThreads), lds, st, a);
 }
 
-template <int NB, int CK, int PJ>
+template <int NB, int CK, int PJ, int NW>
 static void launch_conv_dlds(const ConvArgs& a, hipStream_t st) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)conv_dlds_kernel<NB, CK, PJ>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        (void)hipFuncSetAttribute((const void*)conv_dlds_kernel<NB, CK, PJ, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         once = true;
     }
-    constexpr int TM = 128 * PJ, Q4 = CK / 4;
+    constexpr int TM = NW * 32 * PJ, Q4 = CK / 4;
     const int slab_ops = ((TM + a.d.kw - 1) * Q4 + 63) / 64, w_ops = (a.d.kw * CK * NB / 4 + 63) / 64;
     const size_t lds = (size_t)2 * (slab_ops + w_ops) * 1024;
     const long long n_tiles = (a.d.Q + TM - 1) / TM;
-    const int per_cu = (int)(160 * 1024 / lds) > 0 ? (int)(160 * 1024 / lds) : 1;
-    const long long cap = 256LL * (per_cu > 4 ? 4 : per_cu);
-    dim3 grid((unsigned)(n_tiles < cap ? n_tiles : cap), (a.Nn + NB - 1) / NB);
-    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ>), grid, dim3(kConvThreads), lds, st, a);
+    int per_cu = (int)(160 * 1024 / lds);
+    if (per_cu * NW > 16) per_cu = 16 / NW;
+    if (per_cu < 1) per_cu = 1;
+    const long long cap = 256LL * per_cu;
+    const long long gx = ((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8;   // XCD-aware split needs a multiple of 8
+    dim3 grid((unsigned)gx, (a.Nn + NB - 1) / NB);
+    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW>), grid, dim3(NW * 64), lds, st, a);
 }
 
 template <int NB, int CK>
 static hipError_t launch_conv_t(const ConvArgs& a, hipStream_t st) {
     if ((a.K % 4) == 0) {
-        launch_conv_dlds<NB, CK, 1>(a, st);
+        launch_conv_dlds<NB, CK, 1, 4>(a, st);
         return hipGetLastError();
     }
     const long long n_tiles = (a.d.Q + kConvTM - 1) / kConvTM;
@@ -922,15 +944,16 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     const int a_off = h * RSg + co_c;
 
     const long long n_chunks = (d.Q + kWgTM - 1) / kWgTM;
-    long long chunk = blockIdx.x;
-    if (chunk < n_chunks) {
+    const XcdRange xr = xcd_range(n_chunks);
+    long long chunk = xr.first;
+    if (chunk < xr.end) {
         fetch(chunk * kWgTM);
         stash(chunk * kWgTM);
     }
     __syncthreads();
-    for (; chunk < n_chunks; chunk += gridDim.x) {
-        const long long next = chunk + gridDim.x;
-        if (next < n_chunks) fetch(next * kWgTM);
+    for (; chunk < xr.end; chunk += xr.stride) {
+        const long long next = chunk + xr.stride;
+        if (next < xr.end) fetch(next * kWgTM);
         if (active) {
             // software pipeline over the 2-pixel K-steps: operands of step s+1 are read from LDS
             // before the MFMAs of step s are issued
@@ -959,7 +982,7 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
             }
         }
         __syncthreads();
-        if (next < n_chunks) stash(next * kWgTM);
+        if (next < xr.end) stash(next * kWgTM);
         __syncthreads();
     }
     if (active) {
@@ -1237,7 +1260,7 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
 
     // split-K: enough workgroups to fill the chip, never more than there are pixel chunks
     const long long chunks = (plan.Q + kWgTM - 1) / kWgTM;
-    plan.n_split = (int)(chunks < 256 ? chunks : 256);
+    plan.n_split = (int)(chunks < 256 ? (chunks + 7) / 8 * 8 : 256);   // multiple of 8: XCD-aware split
 
     size_t w = 0;
     plan.grad_off[0] = 0;
