@@ -11,6 +11,7 @@
 
 #include "fft_core.h"
 #include "internal.h"
+#include "xcd.h"
 
 namespace gleam {
 
@@ -194,7 +195,9 @@ __global__ __launch_bounds__(cols_threads<N>()) void cols_kernel(ColsArgs a) {
     fill_twiddles<N, NT>(tw);
     const long long tiles_per = (a.inner + L - 1) / L;
     const long long n_tiles = a.outer * tiles_per;
-    for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    // neighbouring column tiles share 128-byte lines: keep them on one XCD (one L2)
+    const XcdRange xr = xcd_range(n_tiles);
+    for (long long tile = xr.first; tile < xr.end; tile += xr.stride) {
         const long long o = tile / tiles_per;
         const long long i0 = (tile % tiles_per) * L;
         const long long base = o * N * a.inner + i0;
@@ -285,7 +288,8 @@ bool fft_size_supported(long long n) {
 
 static int grid_for(long long n_tiles) {
     const long long cap = 256LL * 8;
-    return (int)(n_tiles < cap ? (n_tiles > 0 ? n_tiles : 1) : cap);
+    const long long g = n_tiles < cap ? (n_tiles > 0 ? n_tiles : 1) : cap;
+    return (int)((g + 7) / 8 * 8);   // multiple of 8 for the XCD-aware split of the column kernels
 }
 
 static hipError_t launch_rows(bool reduce, int N, const RowsArgs& a, hipStream_t st) {

@@ -152,3 +152,37 @@ def test_config1_knee2d_full_size():
     c = synth.make_case(1)
     print("case cfg1 (oracle takes ~1 min on the host cores)", flush=True)
     check_module(c)
+
+
+@pytest.mark.timeout(600)
+def test_config4_cine2dt_full_size():
+    """Dynamic 2D+t workload at full size ((2+1)D prox: 3x3x1 spatial and 1x1x3 temporal layers)."""
+    c = synth.make_case(4)
+    print("case cfg4 cine", flush=True)
+    check_module(c)
+
+
+@pytest.mark.timeout(900)
+def test_config2_brain2d_full_size_fp32_convs():
+    """Brain-shaped workload (128-channel chain, batch 4) at full size.  Its bf16 operand mode has no
+    kernels yet, so the float32 convolutions run here, against the float32 tolerance."""
+    c = synth.make_case(2)
+    c.prox.dtype = 0
+    print("case cfg2 brain, fp32 convs", flush=True)
+    check_module(c)
+
+
+@pytest.mark.timeout(1200)
+def test_config3_vol3d_full_size():
+    """3D volume (256x160x160, 3D FFT, 3x3x3 prox) at full size; the oracle needs about two minutes."""
+    c = synth.make_case(3)
+    print("case cfg3 vol3d", flush=True)
+    check_module(c)
+
+
+def test_bf16_operand_mode_is_rejected_not_silently_run_in_fp32():
+    c = synth.make_case(0)
+    c.prox.dtype = 1
+    with pytest.raises(gb.GleamError) as e:
+        gb.gleam_workspace_bytes(gb.make_geom(c.geom), gb.make_prox(c.prox))
+    assert e.value.status == gb.GLEAM_E_DESC
