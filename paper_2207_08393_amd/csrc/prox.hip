@@ -317,15 +317,21 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
 // GLOBAL address, which keeps the 128-bit operand reads bank-conflict free.  Pixels or channels past
 // the tensor are read from a clamped address: they only ever meet masked taps or zero weights.
 // Requires K % 4 == 0 (16-byte alignment of every quad).
-template <int NB, int CK, int PJ, int NW>
+// KW > 0 fixes the kernel extent along W at compile time (all LDS operand offsets become immediates);
+// KW == 0 reads it from the arguments.
+template <int NB, int CK, int PJ, int NW, int KW>
 __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
     constexpr int TM = NW * 32 * PJ, G = CK / 8, NJ = NB / 32, Q4 = CK / 4;
     constexpr int RP = Q4 >= 8 ? 1 : 8 / Q4;   // pixel rows per 128 bytes of LDS
+    constexpr int KWM = KW > 0 ? KW : 5;       // most taps along W
+    constexpr int MAXS = ((TM + KWM - 1) * Q4 + 63) / 64 / NW + 1;   // slab loads per wave and chunk
+    constexpr int MAXW = (KWM * CK * NB / 4 + 63) / 64 / NW + 1;     // weight loads per wave and chunk
     extern __shared__ float smem[];
     const PixDims d = a.d;
-    const int n_pix = TM + d.kw - 1;
+    const int kw = KW > 0 ? KW : d.kw;
+    const int n_pix = TM + kw - 1;
     const int slab_ops = (n_pix * Q4 + 63) / 64;          // wave-wide loads per slab
-    const int w4 = d.kw * CK * NB / 4;
+    const int w4 = kw * CK * NB / 4;
     const int w_ops = (w4 + 63) / 64;
     const int buf_floats = (slab_ops + w_ops) * 256;
     const int tid = threadIdx.x;
@@ -336,30 +342,75 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
     const int nck = rowtaps * n_kc;
     const long long n_tiles = (d.Q + TM - 1) / TM;
     const bool vec_out = (a.Nn % 4) == 0;
+    const bool k_full = (a.K % CK) == 0;
     const long long last_quad = d.Q * a.K - 4;            // highest legal quad start
+
+    // Per-lane constants of the direct loads: element offset of this lane's quad from the slab origin
+    // (pixel qs, channel kc*CK) and float offset of its weight quad inside an image.
+    unsigned s_off[MAXS], w_off[MAXW];
+    int s_pp[MAXS], s_c4[MAXS];
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+        const int v = (wave + i * NW) * 64 + lane;
+        s_pp[i] = v / Q4;
+        s_c4[i] = (v % Q4) ^ ((s_pp[i] / RP) % Q4);
+        s_off[i] = (unsigned)(s_pp[i] * a.K + 4 * s_c4[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < MAXW; ++i) {
+        const int v = (wave + i * NW) * 64 + lane;
+        w_off[i] = 4u * (unsigned)(v < w4 ? v : 0);
+    }
 
     auto issue = [&](long long tile, int c, int buf) {
         const int rt = c / n_kc, kc = c % n_kc;
-        const long long qs = tile * TM + rowtap_offset(rt, d) - d.kw / 2;
+        const long long qs = tile * TM + rowtap_offset(rt, d) - kw / 2;
         float* dst = smem + buf * buf_floats;
-        for (int o = wave; o < slab_ops; o += NW) {
-            const int v = o * 64 + lane;
-            const int pp = v / Q4, pos = v % Q4;
-            const int c4 = pos ^ ((pp / RP) % Q4);
-            long long off = (qs + pp) * a.K + kc * CK + 4 * c4;
-            off = off < 0 ? 0 : (off > last_quad ? last_quad : off);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.in + off),
-                                             (__attribute__((address_space(3))) void*)(dst + o * 256), 16, 0, 0);
+        const bool interior = k_full && qs >= 0 && qs + (long long)slab_ops * 64 / Q4 <= d.Q;   // uniform
+        if (interior) {
+            const float* base = a.in + qs * a.K + kc * CK;                                       // uniform
+#pragma unroll
+            for (int i = 0; i < MAXS; ++i) {
+                const int o = wave + i * NW;
+                if (o < slab_ops)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + s_off[i]),
+                                                     (__attribute__((address_space(3))) void*)(dst + o * 256), 16, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < MAXS; ++i) {
+                const int o = wave + i * NW;
+                if (o < slab_ops) {
+                    long long off = (qs + s_pp[i]) * a.K + kc * CK + 4 * s_c4[i];
+                    off = off < 0 ? 0 : (off > last_quad ? last_quad : off);
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.in + off),
+                                                     (__attribute__((address_space(3))) void*)(dst + o * 256), 16, 0, 0);
+                }
+            }
         }
-        const float* src = a.wt + ((size_t)(rt * n_kc + kc) * gridDim.y + blockIdx.y) * (size_t)(d.kw * CK * NB);
+        const float* src = a.wt + ((size_t)(rt * n_kc + kc) * gridDim.y + blockIdx.y) * (size_t)(kw * CK * NB);
         float* wdst = dst + slab_ops * 256;
-        for (int o = wave; o < w_ops; o += NW) {
-            int v = o * 64 + lane;
-            v = v < w4 ? v : 0;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + 4 * v),
-                                             (__attribute__((address_space(3))) void*)(wdst + o * 256), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < MAXW; ++i) {
+            const int o = wave + i * NW;
+            if (o < w_ops)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + w_off[i]),
+                                                 (__attribute__((address_space(3))) void*)(wdst + o * 256), 16, 0, 0);
         }
     };
+
+    // LDS float offsets of this lane's pixel operand for every (pixel block, tap along W, 8-channel group)
+    int p_off[PJ][KWM][G];
+#pragma unroll
+    for (int pj = 0; pj < PJ; ++pj)
+#pragma unroll
+        for (int dw = 0; dw < KWM; ++dw) {
+            const int pix = wave * (32 * PJ) + 32 * pj + m + dw;
+            const int key = (pix / RP) % Q4;
+#pragma unroll
+            for (int g = 0; g < G; ++g) p_off[pj][dw][g] = pix * CK + 4 * ((2 * g + h) ^ key);
+        }
+    const int wa_lane = (h * NB + m) * 4;
 
     const XcdRange xr = xcd_range(n_tiles);
     long long tile = xr.first;
@@ -385,25 +436,20 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
             const long long ntile = last ? tile + xr.stride : tile;
             if (ntile < xr.end) issue(ntile, last ? 0 : c + 1, cur ^ 1);
             const float* slab = smem + cur * buf_floats;
-            const float* wl = slab + slab_ops * 256;
+            const float* wl = slab + slab_ops * 256 + wa_lane;
             const int rt = c / n_kc;
-            for (int dw = 0; dw < d.kw; ++dw) {
-                unsigned okm[PJ];
-                const float* prow[PJ];
-                int key[PJ];
 #pragma unroll
-                for (int pj = 0; pj < PJ; ++pj) {
-                    okm[pj] = ((vbits[pj] >> (rt * d.kw + dw)) & 1u) ? 0xffffffffu : 0u;
-                    const int pix = wave * (32 * PJ) + 32 * pj + m + dw;
-                    prow[pj] = slab + pix * CK;
-                    key[pj] = (pix / RP) % Q4;
-                }
+            for (int dw = 0; dw < KWM; ++dw) {
+                if (KW == 0 && dw >= kw) break;
+                unsigned okm[PJ];
+#pragma unroll
+                for (int pj = 0; pj < PJ; ++pj) okm[pj] = ((vbits[pj] >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     float4 pb[PJ], wa[NJ];
 #pragma unroll
                     for (int pj = 0; pj < PJ; ++pj) {
-                        pb[pj] = *reinterpret_cast<const float4*>(prow[pj] + 4 * ((2 * g + h) ^ key[pj]));
+                        pb[pj] = *reinterpret_cast<const float4*>(slab + p_off[pj][dw][g]);
                         if (a.relu_in) {
                             pb[pj].x = fmaxf(pb[pj].x, 0.f); pb[pj].y = fmaxf(pb[pj].y, 0.f);
                             pb[pj].z = fmaxf(pb[pj].z, 0.f); pb[pj].w = fmaxf(pb[pj].w, 0.f);
@@ -415,7 +461,7 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
                     }
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
-                        wa[j] = *reinterpret_cast<const float4*>(wl + (((dw * G + g) * 2 + h) * NB + 32 * j + m) * 4);
+                        wa[j] = *reinterpret_cast<const float4*>(wl + ((dw * G + g) * 2 * NB + 32 * j) * 4);
 #pragma unroll
                     for (int pj = 0; pj < PJ; ++pj)
 #pragma unroll
@@ -610,11 +656,11 @@ static void launch_conv_k(const ConvArgs& a, dim3 grid, size_t lds, hipStream_t 
     hipLaunchKernelGGL((conv_mfma_kernel<NB, CK, KWMAX, VEC>), grid, dim3(kConvThreads), lds, st, a);
 }
 
-template <int NB, int CK, int PJ, int NW>
-static void launch_conv_dlds(const ConvArgs& a, hipStream_t st) {
+template <int NB, int CK, int PJ, int NW, int KW>
+static void launch_conv_dlds_k(const ConvArgs& a, hipStream_t st) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)conv_dlds_kernel<NB, CK, PJ, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        (void)hipFuncSetAttribute((const void*)conv_dlds_kernel<NB, CK, PJ, NW, KW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         once = true;
     }
     constexpr int TM = NW * 32 * PJ, Q4 = CK / 4;
@@ -627,7 +673,14 @@ static void launch_conv_dlds(const ConvArgs& a, hipStream_t st) {
     const long long cap = 256LL * per_cu;
     const long long gx = ((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8;   // XCD-aware split needs a multiple of 8
     dim3 grid((unsigned)gx, (a.Nn + NB - 1) / NB);
-    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW>), grid, dim3(NW * 64), lds, st, a);
+    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW, KW>), grid, dim3(NW * 64), lds, st, a);
+}
+
+template <int NB, int CK, int PJ, int NW>
+static void launch_conv_dlds(const ConvArgs& a, hipStream_t st) {
+    if (a.d.kw == 3) launch_conv_dlds_k<NB, CK, PJ, NW, 3>(a, st);
+    else if (a.d.kw == 1) launch_conv_dlds_k<NB, CK, PJ, NW, 1>(a, st);
+    else launch_conv_dlds_k<NB, CK, PJ, NW, 0>(a, st);
 }
 
 template <int NB, int CK>
