@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <type_traits>
 
 #include "internal.h"
 #include "xcd.h"
@@ -326,14 +327,18 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
     constexpr int KWM = KW > 0 ? KW : 5;       // most taps along W
     constexpr int MAXS = ((TM + KWM - 1) * Q4 + 63) / 64 / NW + 1;   // slab loads per wave and chunk
     constexpr int MAXW = (KWM * CK * NB / 4 + 63) / 64 / NW + 1;     // weight loads per wave and chunk
-    extern __shared__ float smem[];
+    // The two chunk buffers are separate LDS objects on purpose: the compiler can then tell that an LDS
+    // read of one buffer does not depend on direct loads still in flight into the other, and does not
+    // make a wave wait for its own prefetch before its MFMAs.
+    constexpr int kBufFloats = (((TM + KWM - 1) * Q4 + 63) / 64 + (KWM * CK * NB / 4 + 63) / 64) * 256;
+    __shared__ float bufA[kBufFloats];
+    __shared__ float bufB[kBufFloats];
     const PixDims d = a.d;
     const int kw = KW > 0 ? KW : d.kw;
     const int n_pix = TM + kw - 1;
     const int slab_ops = (n_pix * Q4 + 63) / 64;          // wave-wide loads per slab
     const int w4 = kw * CK * NB / 4;
     const int w_ops = (w4 + 63) / 64;
-    const int buf_floats = (slab_ops + w_ops) * 256;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 31, h = lane >> 5;
     const int n0 = blockIdx.y * NB;
@@ -362,10 +367,9 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
         w_off[i] = 4u * (unsigned)(v < w4 ? v : 0);
     }
 
-    auto issue = [&](long long tile, int c, int buf) {
+    auto issue = [&](long long tile, int c, float* dst) {
         const int rt = c / n_kc, kc = c % n_kc;
         const long long qs = tile * TM + rowtap_offset(rt, d) - kw / 2;
-        float* dst = smem + buf * buf_floats;
         const bool interior = k_full && qs >= 0 && qs + (long long)slab_ops * 64 / Q4 <= d.Q;   // uniform
         if (interior) {
             const float* base = a.in + qs * a.K + kc * CK;                                       // uniform
@@ -414,33 +418,38 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
 
     const XcdRange xr = xcd_range(n_tiles);
     long long tile = xr.first;
-    int cur = 0;
-    if (tile < xr.end) issue(tile, 0, 0);
+    int c = 0;
+    if (tile < xr.end) issue(tile, 0, bufA);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    for (; tile < xr.end; tile += xr.stride) {
-        const long long q0 = tile * TM + wave * (32 * PJ) + m;
-        unsigned vbits[PJ];
-#pragma unroll
-        for (int pj = 0; pj < PJ; ++pj) vbits[pj] = tap_validity(q0 + 32 * pj, d);
-        floatx16 acc[PJ][NJ];
-#pragma unroll
-        for (int pj = 0; pj < PJ; ++pj)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
 
-        for (int c = 0; c < nck; ++c) {
-            const bool last = c + 1 == nck;
-            const long long ntile = last ? tile + xr.stride : tile;
-            if (ntile < xr.end) issue(ntile, last ? 0 : c + 1, cur ^ 1);
-            const float* slab = smem + cur * buf_floats;
+    long long q0 = 0;
+    unsigned vbits[PJ];
+    floatx16 acc[PJ][NJ];
+    // One chunk: prefetch the following chunk into `nxt`, run the MFMAs of the current one out of `slab`.
+    // Called alternately with (bufA, bufB) and (bufB, bufA) so that each call site names its buffers.
+    auto step = [&](const float* slab, float* nxt) {
+        if (c == 0) {
+            q0 = tile * TM + wave * (32 * PJ) + m;
+#pragma unroll
+            for (int pj = 0; pj < PJ; ++pj) vbits[pj] = tap_validity(q0 + 32 * pj, d);
+#pragma unroll
+            for (int pj = 0; pj < PJ; ++pj)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
+        }
+        const bool last = c + 1 == nck;
+        const long long ntile = last ? tile + xr.stride : tile;
+        const int nc = last ? 0 : c + 1;
+        if (ntile < xr.end) issue(ntile, nc, nxt);
+        {
             const float* wl = slab + slab_ops * 256 + wa_lane;
             const int rt = c / n_kc;
 #pragma unroll
             for (int dw = 0; dw < KWM; ++dw) {
-                if (KW == 0 && dw >= kw) break;
+                if (KW == 0 && dw >= kw) continue;
                 unsigned okm[PJ];
 #pragma unroll
                 for (int pj = 0; pj < PJ; ++pj) okm[pj] = ((vbits[pj] >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
@@ -525,10 +534,16 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
                         }
                 }
             }
-            __builtin_amdgcn_s_waitcnt(0);   // the next chunk's direct loads have landed in LDS
-            __syncthreads();                 // ... and every wave is done reading the current buffer
-            cur ^= 1;
         }
+        __builtin_amdgcn_s_waitcnt(0);   // the next chunk's direct loads have landed in LDS
+        __syncthreads();                 // ... and every wave is done reading the current buffer
+        tile = ntile;
+        c = nc;
+    };
+    while (tile < xr.end) {
+        step(bufA, bufB);
+        if (tile >= xr.end) break;
+        step(bufB, bufA);
     }
 }
 
@@ -658,14 +673,8 @@ static void launch_conv_k(const ConvArgs& a, dim3 grid, size_t lds, hipStream_t 
 
 template <int NB, int CK, int PJ, int NW, int KW>
 static void launch_conv_dlds_k(const ConvArgs& a, hipStream_t st) {
-    static bool once = false;
-    if (!once) {
-        (void)hipFuncSetAttribute((const void*)conv_dlds_kernel<NB, CK, PJ, NW, KW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        once = true;
-    }
-    constexpr int TM = NW * 32 * PJ, Q4 = CK / 4;
-    const int slab_ops = ((TM + a.d.kw - 1) * Q4 + 63) / 64, w_ops = (a.d.kw * CK * NB / 4 + 63) / 64;
-    const size_t lds = (size_t)2 * (slab_ops + w_ops) * 1024;
+    constexpr int TM = NW * 32 * PJ, Q4 = CK / 4, KWM = KW > 0 ? KW : 5;
+    constexpr size_t lds = (size_t)2 * (((TM + KWM - 1) * Q4 + 63) / 64 + (KWM * CK * NB / 4 + 63) / 64) * 1024;   // static in the kernel
     const long long n_tiles = (a.d.Q + TM - 1) / TM;
     int per_cu = (int)(160 * 1024 / lds);
     if (per_cu * NW > 16) per_cu = 16 / NW;
@@ -673,7 +682,7 @@ static void launch_conv_dlds_k(const ConvArgs& a, hipStream_t st) {
     const long long cap = 256LL * per_cu;
     const long long gx = ((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8;   // XCD-aware split needs a multiple of 8
     dim3 grid((unsigned)gx, (a.Nn + NB - 1) / NB);
-    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW, KW>), grid, dim3(NW * 64), lds, st, a);
+    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW, KW>), grid, dim3(NW * 64), 0, st, a);
 }
 
 template <int NB, int CK, int PJ, int NW>
