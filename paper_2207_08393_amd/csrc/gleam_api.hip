@@ -64,7 +64,7 @@ inline size_t n_pixels(const gleam_geom& g) { return (size_t)(g.B * g.T * g.D * 
 int check_prox(const gleam_prox_desc* p) {
     if (!p) return GLEAM_E_NULL;
     if (p->n_layers < 1 || p->n_layers > kMaxLayers || !p->layers) return GLEAM_E_DESC;
-    if (p->dtype != 0) return GLEAM_E_DESC;  // bf16 operands (dtype 1) have no kernels yet
+    if (p->dtype != 0 && p->dtype != 1) return GLEAM_E_DESC;
     if (p->loss_kind != 0 && p->loss_kind != 1) return GLEAM_E_DESC;
     int prev = 2;
     std::vector<int> ch(p->n_layers + 1);
@@ -85,6 +85,7 @@ int check_prox(const gleam_prox_desc* p) {
         prev = c.cout;
     }
     if (prev != 2) return GLEAM_E_DESC;
+    if (p->dtype == 1 && !prox_bf16_supported(*p)) return GLEAM_E_DESC;
     return GLEAM_OK;
 }
 

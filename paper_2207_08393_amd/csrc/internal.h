@@ -59,6 +59,9 @@ struct ProxPlan {
 // LDS bytes the weight-gradient kernel needs for one layer (must stay below the 160 KB of a CU).
 size_t wgrad_lds_bytes(const gleam_conv& c);
 
+// Whether prox dtype 1 (bfloat16 operands) has kernels for this network.
+bool prox_bf16_supported(const gleam_prox_desc& p);
+
 void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan);
 
 // z = f_theta(u) with u = t_0 already stored at act_base + act_off[0]; writes t_1..t_{L-1} next to it

@@ -15,51 +15,9 @@
 #include <cstdio>
 #include <type_traits>
 
-#include "internal.h"
-#include "xcd.h"
+#include "prox_common.h"
 
 namespace gleam {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-constexpr int kConvThreads = 256;
-constexpr int kConvTM = 256;  // pixels per workgroup tile of the forward / data-gradient kernel
-
-struct PixDims {
-    int T, D, H, W;
-    int kt, kd, kh, kw;
-    long long Q;
-};
-
-// Bit `tap` is set when pixel q + off(tap) lies inside the grid (same sample, frame, slice, row).
-__device__ __forceinline__ unsigned tap_validity(long long q, const PixDims& d) {
-    if (q >= d.Q) return 0u;
-    const int w = (int)(q % d.W);
-    long long r = q / d.W;
-    const int h = (int)(r % d.H);
-    r /= d.H;
-    const int dd = (int)(r % d.D);
-    r /= d.D;
-    const int t = (int)(r % d.T);
-    unsigned bits = 0u;
-    int tap = 0;
-    for (int it = 0; it < d.kt; ++it)
-        for (int id = 0; id < d.kd; ++id)
-            for (int ih = 0; ih < d.kh; ++ih)
-                for (int iw = 0; iw < d.kw; ++iw, ++tap) {
-                    const int tt = t + it - d.kt / 2, d2 = dd + id - d.kd / 2;
-                    const int hh = h + ih - d.kh / 2, ww = w + iw - d.kw / 2;
-                    const bool ok = tt >= 0 && tt < d.T && d2 >= 0 && d2 < d.D && hh >= 0 && hh < d.H && ww >= 0 && ww < d.W;
-                    bits |= (ok ? 1u : 0u) << tap;
-                }
-    return bits;
-}
-
-// Flattened pixel offset of row-tap rt = (it, id, ih), before the kw taps along W.
-__device__ __forceinline__ long long rowtap_offset(int rt, const PixDims& d) {
-    const int ih = rt % d.kh, id = (rt / d.kh) % d.kd, it = rt / (d.kh * d.kd);
-    return (((long long)(it - d.kt / 2) * d.D + (id - d.kd / 2)) * d.H + (ih - d.kh / 2)) * d.W;
-}
 
 // ------------------------------------------------------------------ forward / data-gradient conv
 struct ConvArgs {
@@ -558,7 +516,7 @@ struct ConvThinInArgs {
     long long sn, st, sk;
 };
 
-template <int KT, int KD, int KH, int KW>
+template <int KT, int KD, int KH, int KW, bool BF>
 __global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
     constexpr int RT = KT * KD * KH, TAPS = RT * KW, TH = 2;
     extern __shared__ float smem[];
@@ -617,10 +575,19 @@ __global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
             if (n_ok) {
                 const long long o = (row * d.W + w) * a.Nn + n;
                 if (a.relu_out) acc = fmaxf(acc, 0.f);
-                const float ref = a.mask_ref ? a.mask_ref[o] : 1.f;
-                if (a.mask_acc) acc = ref > 0.f ? acc : 0.f;
-                if (a.add) acc += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o];
-                a.out[o] = acc;
+                if (BF) {   // wide tensors (out, mask_ref, add) are bfloat16
+                    const unsigned short* mr = reinterpret_cast<const unsigned short*>(a.mask_ref);
+                    const unsigned short* ad = reinterpret_cast<const unsigned short*>(a.add);
+                    const float ref = mr ? bf16_to_f32(mr[o]) : 1.f;
+                    if (a.mask_acc) acc = ref > 0.f ? acc : 0.f;
+                    if (ad) acc += (a.mask_add && !(ref > 0.f)) ? 0.f : bf16_to_f32(ad[o]);
+                    reinterpret_cast<unsigned short*>(a.out)[o] = f32_to_bf16(acc);
+                } else {
+                    const float ref = a.mask_ref ? a.mask_ref[o] : 1.f;
+                    if (a.mask_acc) acc = ref > 0.f ? acc : 0.f;
+                    if (a.add) acc += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o];
+                    a.out[o] = acc;
+                }
             }
         }
     }
@@ -723,30 +690,42 @@ static size_t conv_wimg_floats(int K, int Nn, int taps) {
 }
 
 template <int KT, int KD, int KH, int KW>
-static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, hipStream_t st) {
+static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, bool bf, hipStream_t st) {
     ConvThinInArgs t{a, cw.w, cw.sn, cw.st, cw.sk};
     const long long n_rows = a.d.Q / a.d.W;
     const size_t lds = (size_t)KT * KD * KH * (a.d.W + KW - 1) * 2 * sizeof(float);
     const long long cap = 256LL * 8;
-    hipLaunchKernelGGL((conv_thin_in_kernel<KT, KD, KH, KW>), dim3((unsigned)(n_rows < cap ? n_rows : cap)), dim3(256), lds, st, t);
+    const dim3 grid((unsigned)(n_rows < cap ? n_rows : cap));
+    if (bf) hipLaunchKernelGGL((conv_thin_in_kernel<KT, KD, KH, KW, true>), grid, dim3(256), lds, st, t);
+    else hipLaunchKernelGGL((conv_thin_in_kernel<KT, KD, KH, KW, false>), grid, dim3(256), lds, st, t);
+}
+
+// Launches the two-channel-input kernel when the layer fits it; *hit tells whether it did.
+static hipError_t launch_conv_thin_in(const ConvArgs& a, const ConvWeights& cw, bool bf, bool* hit, hipStream_t st) {
+    *hit = false;
+    const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
+    const int wr = (a.Nn + 63) / 64 * 64;
+    if (!(a.K == 2 && a.Nn >= 8 && wr <= 256 && 256 % wr == 0)) return hipSuccess;
+    const PixDims& d = a.d;
+    const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
+    const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
+    if (!k2 && !k3 && !kt3) return hipSuccess;
+    char name[56];
+    snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
+    KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, (bf ? 2.0 : 4.0) * (double)a.d.Q * a.Nn + 8.0 * (double)a.d.Q, st);
+    if (k2) launch_conv_thin_in_t<1, 1, 3, 3>(a, cw, bf, st);
+    else if (k3) launch_conv_thin_in_t<1, 3, 3, 3>(a, cw, bf, st);
+    else launch_conv_thin_in_t<3, 1, 1, 1>(a, cw, bf, st);
+    *hit = true;
+    return hipGetLastError();
 }
 
 static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scratch, hipStream_t st) {
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
     {   // two input channels and a wide output: HBM-bound kernel without MFMA
-        const int wr = (a.Nn + 63) / 64 * 64;
-        if (a.K == 2 && a.Nn >= 8 && wr <= 256 && 256 % wr == 0) {
-            char name[56];
-            snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
-            KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, 4.0 * (double)a.d.Q * (a.K + a.Nn), st);
-            const PixDims& d = a.d;
-            bool hit = true;
-            if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) launch_conv_thin_in_t<1, 1, 3, 3>(a, cw, st);
-            else if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) launch_conv_thin_in_t<1, 3, 3, 3>(a, cw, st);
-            else if (d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1) launch_conv_thin_in_t<3, 1, 1, 1>(a, cw, st);
-            else hit = false;
-            if (hit) return hipGetLastError();
-        }
+        bool hit = false;
+        const hipError_t e = launch_conv_thin_in(a, cw, false, &hit, st);
+        if (hit || e != hipSuccess) return e;
     }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
     {
@@ -1078,7 +1057,7 @@ struct WgradThinArgs {
     PixDims d;
 };
 
-template <int KT, int KD, int KH, int KW, int TH, bool THIN_IN>
+template <int KT, int KD, int KH, int KW, int TH, bool THIN_IN, bool BF>
 __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
     constexpr int RT = KT * KD * KH, TAPS = RT * KW;
     constexpr int sgn = THIN_IN ? 1 : -1;
@@ -1127,7 +1106,9 @@ __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
         }
         __syncthreads();
         for (int w = pg; w < d.W; w += groups) {
-            float wv = c_ok ? a.wide[(row * d.W + w) * a.WC + c] : 0.f;
+            float wv = 0.f;
+            if (c_ok) wv = BF ? bf16_to_f32(reinterpret_cast<const unsigned short*>(a.wide)[(row * d.W + w) * a.WC + c])
+                              : a.wide[(row * d.W + w) * a.WC + c];
             if (!THIN_IN && a.relu_in) wv = fmaxf(wv, 0.f);
             if (THIN_IN) bs[0] += wv;
 #pragma unroll
@@ -1282,16 +1263,48 @@ static PixDims pix_dims(const gleam_geom& g, const gleam_conv& c) {
     return d;
 }
 
+// Whether the bfloat16 operand mode has kernels for this network: 2-channel first input and last output
+// handled by the thin kernels, every interior channel count a multiple of 8, kernel extent 1 or 3 along W.
+bool prox_bf16_supported(const gleam_prox_desc& p) {
+    const int L = p.n_layers;
+    if (L < 2) return false;
+    auto thin_shape = [](const gleam_conv& c) {
+        return (c.kt == 1 && c.kd == 1 && c.kh == 3 && c.kw == 3) || (c.kt == 1 && c.kd == 3 && c.kh == 3 && c.kw == 3) ||
+               (c.kt == 3 && c.kd == 1 && c.kh == 1 && c.kw == 1);
+    };
+    auto wide_ok = [](int ch) {
+        const int r = (ch + 63) / 64 * 64;
+        return ch >= 8 && ch % 8 == 0 && r <= 256 && 256 % r == 0;
+    };
+    for (int l = 0; l < L; ++l) {
+        const gleam_conv& c = p.layers[l];
+        if (c.kw != 1 && c.kw != 3) return false;
+        if (l == 0) {
+            if (c.cin != 2 || !wide_ok(c.cout) || !thin_shape(c)) return false;
+        } else if (l == L - 1) {
+            if (c.cout != 2 || !wide_ok(c.cin) || !thin_shape(c)) return false;
+            if (c.skip_src > 0) return false;
+        } else {
+            if (c.cin % 8 || c.cout % 8) return false;
+            if (wgrad_bf16_lds_bytes(c.cout, c.cin, c.kt, c.kd, c.kh, c.kw) > 150 * 1024) return false;
+            const int rowtaps = c.kt * c.kd * c.kh;
+            if (32 * (c.cout / 8) > 2 * 512 || rowtaps * (32 + c.kw - 1) * (c.cin / 8) > 8 * 512) return false;
+        }
+    }
+    return true;
+}
+
 void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     const int L = p.n_layers;
     plan.L = L;
     plan.Q = g.B * g.T * g.D * g.H * g.W;
     const size_t Q = (size_t)plan.Q;
+    const size_t es = p.dtype == 1 ? 2 : 4;   // bytes per element of the interior activations / gradients
     size_t off = 0, th = 0, max_w = 0;
     for (int l = 0; l < L; ++l) {
         const gleam_conv& c = p.layers[l];
         plan.act_off[l] = off;
-        off += align256(Q * c.cin * sizeof(float));
+        off += align256(Q * c.cin * (l == 0 ? sizeof(float) : es));   // t_0 = u is always float32
         plan.w_off[l] = th;
         const size_t nw = (size_t)c.cout * c.kt * c.kd * c.kh * c.kw * c.cin;
         th += nw;
@@ -1311,7 +1324,7 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     plan.grad_off[0] = 0;
     for (int l = 1; l < L; ++l) {
         plan.grad_off[l] = w;
-        w += align256(Q * p.layers[l].cin * sizeof(float));
+        w += align256(Q * p.layers[l].cin * es);
     }
     plan.grad_off[L] = 0;  // G_L = g_z lives in saved
     plan.partial_off = w;
@@ -1326,6 +1339,11 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
         const size_t f = conv_wimg_floats(c.cin, c.cout, taps), b = conv_wimg_floats(c.cout, c.cin, taps);
         max_img = f > max_img ? f : max_img;
         max_img = b > max_img ? b : max_img;
+        if (p.dtype == 1) {   // bf16 images are half the bytes per element, but chunked by 32 channels
+            const size_t fb = (conv_bf16_wimg_elems(c.cin, c.cout, taps) + 1) / 2, bb = (conv_bf16_wimg_elems(c.cout, c.cin, taps) + 1) / 2;
+            max_img = fb > max_img ? fb : max_img;
+            max_img = bb > max_img ? bb : max_img;
+        }
     }
     const size_t img_bytes = align256(max_img * sizeof(float));
     plan.wimg_off_bwd = w;
@@ -1357,7 +1375,28 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
         a.K = c.cin; a.Nn = c.cout;
         a.relu_in = c.relu_in; a.relu_out = c.relu_out;
         a.d = pix_dims(g, c);
-        hipError_t e = launch_conv(a, cw, reinterpret_cast<float*>((unsigned char*)ws + plan.wimg_off_fwd), st);
+        hipError_t e;
+        if (p.dtype == 1) {
+            if (l == 0) {           // float32 image in, bfloat16 features out
+                bool hit = false;
+                e = launch_conv_thin_in(a, cw, true, &hit, st);
+                if (e == hipSuccess && !hit) e = hipErrorInvalidValue;
+            } else {                // bfloat16 in; the last layer writes the float32 image
+                ConvBf16Args b{};
+                b.in = reinterpret_cast<const unsigned short*>(a.in);
+                b.out = a.out;
+                b.bias = a.bias;
+                b.add = a.add;
+                b.K = c.cin; b.Nn = c.cout;
+                b.out_f32 = (l == L - 1) ? 1 : 0;
+                b.relu_in = c.relu_in; b.relu_out = c.relu_out;
+                b.d = a.d;
+                e = launch_conv_bf16(b, cw.w, cw.sn, cw.st, cw.sk, 0,
+                                     reinterpret_cast<unsigned short*>((unsigned char*)ws + plan.wimg_off_fwd), st);
+            }
+        } else {
+            e = launch_conv(a, cw, reinterpret_cast<float*>((unsigned char*)ws + plan.wimg_off_fwd), st);
+        }
         if (e != hipSuccess) return e;
     }
     if (x_ref) {
@@ -1385,17 +1424,46 @@ static void launch_wgrad_pipe_t(const WgradPipeArgs& pa, dim3 grid, size_t lds, 
 }
 
 template <int KT, int KD, int KH, int KW>
-static void launch_wgrad_thin_t(const WgradArgs& a, float* bias_partial, int n_split, hipStream_t st) {
+static void launch_wgrad_thin_t(const WgradArgs& a, float* bias_partial, int n_split, bool bf, hipStream_t st) {
     WgradThinArgs t{};
     t.partial = a.partial; t.bias_partial = bias_partial; t.relu_in = a.relu_in; t.d = a.d;
     const size_t lds = ((size_t)KT * KD * KH * (a.d.W + KW - 1) * 2 + 256) * sizeof(float);
-    if (a.Ci == 2) {
+    const dim3 grid(n_split), blk(256);
+    if (a.Ci == 2) {   // thin input a (float32), wide output gradient g
         t.wide = a.g; t.thin = a.a; t.WC = a.Co;
-        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, true>), dim3(n_split), dim3(256), lds, st, t);
-    } else {
+        if (bf) hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, true, true>), grid, blk, lds, st, t);
+        else hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, true, false>), grid, blk, lds, st, t);
+    } else {           // thin output gradient g (float32), wide input a
         t.wide = a.a; t.thin = a.g; t.WC = a.Ci;
-        hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, false>), dim3(n_split), dim3(256), lds, st, t);
+        if (bf) hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, false, true>), grid, blk, lds, st, t);
+        else hipLaunchKernelGGL((wgrad_thin_kernel<KT, KD, KH, KW, 2, false, false>), grid, blk, lds, st, t);
     }
+}
+
+// Thin-layer weight gradient if the layer fits it (*hit).  `bf`: the wide tensor is bfloat16.
+static hipError_t launch_wgrad_thin(const WgradArgs& a, float* bias_partial, bool bf, size_t partial_floats, int* used_split,
+                                    bool* hit, hipStream_t st) {
+    *hit = false;
+    const PixDims& d = a.d;
+    const int taps = d.kt * d.kd * d.kh * d.kw;
+    const int wide = a.Ci == 2 ? a.Co : a.Ci;
+    const int wide_r = (wide + 63) / 64 * 64;
+    if (!((a.Ci == 2) != (a.Co == 2) && wide >= 8 && wide_r <= 256 && 256 % wide_r == 0)) return hipSuccess;
+    const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
+    const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
+    if (!k2 && !k3 && !kt3) return hipSuccess;
+    // HBM-bound: one workgroup per image row up to kThinSplit partials (as many as the scratch holds)
+    long long ts = d.Q / d.W;
+    if (ts > kThinSplit) ts = kThinSplit;
+    const long long fit = (long long)(partial_floats / ((size_t)a.Co * taps * a.Ci));
+    if (ts > fit) ts = fit;
+    const int tsplit = (int)(ts < 1 ? 1 : ts);
+    if (k2) launch_wgrad_thin_t<1, 1, 3, 3>(a, bias_partial, tsplit, bf, st);
+    else if (k3) launch_wgrad_thin_t<1, 3, 3, 3>(a, bias_partial, tsplit, bf, st);
+    else launch_wgrad_thin_t<3, 1, 1, 1>(a, bias_partial, tsplit, bf, st);
+    *used_split = tsplit;
+    *hit = true;
+    return hipGetLastError();
 }
 
 // Launches the weight-gradient kernel that fits the layer.  *bias_done is set when the kernel also
@@ -1415,24 +1483,13 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
     dim3 grid(n_split, (ncb * nib * tapgroups + 3) / 4);
 
     // (1) one side is the 2-channel image: HBM-bound kernel without MFMA
-    const int wide = a.Ci == 2 ? a.Co : a.Ci;
-    const int wide_r = (wide + 63) / 64 * 64;
-    if ((a.Ci == 2) != (a.Co == 2) && wide >= 8 && wide_r <= 256 && 256 % wide_r == 0) {
-        // HBM-bound: one workgroup per image row up to kThinSplit partials (as many as the scratch holds)
-        long long ts = d.Q / d.W;
-        if (ts > kThinSplit) ts = kThinSplit;
-        const long long fit = (long long)(partial_floats / ((size_t)a.Co * taps * a.Ci));
-        if (ts > fit) ts = fit;
-        const int tsplit = (int)(ts < 1 ? 1 : ts);
-        bool hit = true;
-        if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 1, 3, 3>(a, bias_partial, tsplit, st);
-        else if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) launch_wgrad_thin_t<1, 3, 3, 3>(a, bias_partial, tsplit, st);
-        else if (d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1) launch_wgrad_thin_t<3, 1, 1, 1>(a, bias_partial, tsplit, st);
-        else hit = false;
+    {
+        bool hit = false;
+        const hipError_t e = launch_wgrad_thin(a, bias_partial, false, partial_floats, used_split, &hit, st);
+        if (e != hipSuccess) return e;
         if (hit) {
-            *used_split = tsplit;
             *bias_done = bias_partial != nullptr;
-            return hipGetLastError();
+            return hipSuccess;
         }
     }
     // (2) channel counts that are multiples of 4: register-prefetch pipelined MFMA kernel
@@ -1519,8 +1576,29 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         float* bpart = reinterpret_cast<float*>(wsb + plan.bias_partial_off);
         bool bias_done = false;
         int used_split = plan.n_split;
-        hipError_t e = launch_wgrad(wa, c.has_bias ? bpart : nullptr, &bias_done, plan.n_split,
-                                    plan.partial_bytes / sizeof(float), &used_split, st);
+        hipError_t e;
+        if (p.dtype == 1) {
+            if (l == 1 || l == L) {   // one side is the float32 2-channel image, the wide side is bfloat16
+                bool hit = false;
+                KernelScope ks(l == 1 ? "conv_bf16_wgrad_thin_in" : "conv_bf16_wgrad_thin_out", 2.0 * (double)d.Q * c.cin * c.cout * taps,
+                               2.0 * (double)d.Q * (c.cin + c.cout), st);
+                e = launch_wgrad_thin(wa, c.has_bias ? bpart : nullptr, true, plan.partial_bytes / sizeof(float), &used_split, &hit, st);
+                if (e == hipSuccess && !hit) e = hipErrorInvalidValue;
+                bias_done = c.has_bias;
+            } else {
+                WgradBf16Args wb{};
+                wb.g = reinterpret_cast<const unsigned short*>(wa.g);
+                wb.a = reinterpret_cast<const unsigned short*>(wa.a);
+                wb.partial = partial;
+                wb.bias_partial = c.has_bias ? bpart : nullptr;
+                wb.Co = c.cout; wb.Ci = c.cin; wb.relu_in = c.relu_in; wb.d = d;
+                e = launch_wgrad_bf16(wb, plan.n_split, st);
+                bias_done = c.has_bias;
+            }
+        } else {
+            e = launch_wgrad(wa, c.has_bias ? bpart : nullptr, &bias_done, plan.n_split,
+                             plan.partial_bytes / sizeof(float), &used_split, st);
+        }
         if (e != hipSuccess) return e;
         const long long nw = (long long)(c.cout * taps * c.cin);
         if (c.has_bias && !bias_done) {
@@ -1549,7 +1627,25 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         a.mask_ref = (a.mask_acc || a.mask_add) ? act(l - 1) : nullptr;
         a.add = pending[l - 1] ? G(pending[l - 1]) : nullptr;
         a.d = d;
-        e = launch_conv(a, cw, reinterpret_cast<float*>(wsb + plan.wimg_off_bwd), st);
+        if (p.dtype == 1) {
+            if (l == L) {           // float32 loss gradient in, bfloat16 gradient out
+                bool hit = false;
+                e = launch_conv_thin_in(a, cw, true, &hit, st);
+                if (e == hipSuccess && !hit) e = hipErrorInvalidValue;
+            } else {
+                ConvBf16Args b{};
+                b.in = reinterpret_cast<const unsigned short*>(a.in);
+                b.out = a.out;
+                b.mask_ref = reinterpret_cast<const unsigned short*>(a.mask_ref);
+                b.add = a.add;
+                b.K = a.K; b.Nn = a.Nn;
+                b.mask_acc = a.mask_acc; b.mask_add = a.mask_add;
+                b.d = d;
+                e = launch_conv_bf16(b, cw.w, cw.sn, cw.st, cw.sk, 1, reinterpret_cast<unsigned short*>(wsb + plan.wimg_off_bwd), st);
+            }
+        } else {
+            e = launch_conv(a, cw, reinterpret_cast<float*>(wsb + plan.wimg_off_bwd), st);
+        }
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -1,0 +1,542 @@
+// Prox convolutions with bfloat16 operands and float32 accumulation on the gfx950 32x32x16 bf16 MFMA
+// (prox dtype 1).  Activations and inter-layer gradients are bfloat16 [pixels][channels]; weights are
+// rounded from the float32 master copy once per layer and call; bias, loss, residual add into the image
+// and every weight gradient stay float32.
+//
+//   conv_bf16_kernel  : forward and data gradient, same scheme as the float32 direct-to-LDS kernel - two
+//                       LDS chunk buffers filled by global->LDS direct loads, XOR-swizzled 16-byte quads
+//                       (8 channels), 32 input channels per chunk (two MFMA K-blocks per tap).
+//   wgrad_bf16_kernel : weight gradient; the contraction runs over pixels, so g and a are transposed into
+//                       LDS ([channel][pixel]) while they are staged and each lane reads its 8 pixels as
+//                       one 16-byte word; the three taps along W come from one 20-byte window by shifts.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+
+#include "prox_common.h"
+
+namespace gleam {
+
+constexpr int kBfCK = 32;   // input channels per staged chunk of the forward / data-gradient kernel
+
+// ------------------------------------------------------------------ weights -> bf16 LDS images
+// Image (rt, kc, nb) = [kw][kBfCK/16][2][NB][8]: element (dw, k = 16g + 8h + s, n) at
+// ((((dw*G + g)*2 + h)*NB + n)*8 + s, zero past the layer; source (n, tap, k) at w[n*sn + tapidx*st + k*sk].
+struct WimgBf16Args {
+    const float* w;
+    unsigned short* wt;
+    long long sn, st, sk;
+    int K, Nn, flip, taps, kw, NB, n_kc, n_nb;
+    long long total;
+};
+__global__ void weights_image_bf16_kernel(WimgBf16Args a) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.total) return;
+    constexpr int G = kBfCK / 16;
+    const int img_elems = a.kw * kBfCK * a.NB;
+    const long long img = i / img_elems;
+    const int e = (int)(i % img_elems);
+    const int s = e & 7, n = (e >> 3) % a.NB, hg = (e >> 3) / a.NB;
+    const int h = hg & 1, g = (hg >> 1) % G, dw = (hg >> 1) / G;
+    const int nb = (int)(img % a.n_nb), kc = (int)((img / a.n_nb) % a.n_kc), rt = (int)(img / ((long long)a.n_nb * a.n_kc));
+    const int k = kc * kBfCK + 16 * g + 8 * h + s, nn = nb * a.NB + n;
+    const int tap = rt * a.kw + dw;
+    const int tapidx = a.flip ? a.taps - 1 - tap : tap;
+    float v = 0.f;
+    if (k < a.K && nn < a.Nn) v = a.w[nn * a.sn + tapidx * a.st + k * a.sk];
+    a.wt[i] = f32_to_bf16(v);
+}
+
+static inline int bf_nb(int Nn) { return Nn <= 32 ? 32 : 64; }
+size_t conv_bf16_wimg_elems(int K, int Nn, int taps) {
+    const int nb = bf_nb(Nn);
+    return (size_t)taps * ((K + kBfCK - 1) / kBfCK) * kBfCK * ((Nn + nb - 1) / nb) * nb;
+}
+
+// ------------------------------------------------------------------ forward / data gradient
+template <int NB, int KW>
+__global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args a) {
+    constexpr int NW = 4, TM = 128, G = kBfCK / 16, NJ = NB / 32, QP = kBfCK / 8;   // QP quads per pixel row
+    constexpr int RP = 8 / QP;                 // pixel rows per 128 bytes of LDS (QP = 4 -> 2)
+    constexpr int KWM = KW > 0 ? KW : 5;
+    constexpr int kSlabOpsMax = ((TM + KWM - 1) * QP + 63) / 64, kWOpsMax = (KWM * kBfCK * NB / 8 + 63) / 64;
+    constexpr int MAXS = kSlabOpsMax / NW + 1, MAXW = kWOpsMax / NW + 1;
+    constexpr int kBufQuads = (kSlabOpsMax + kWOpsMax) * 64;
+    __shared__ uint4 bufA[kBufQuads];
+    __shared__ uint4 bufB[kBufQuads];
+    const PixDims d = a.d;
+    const int kw = KW > 0 ? KW : d.kw;
+    const int n_pix = TM + kw - 1;
+    const int slab_ops = (n_pix * QP + 63) / 64;
+    const int w8 = kw * kBfCK * NB / 8;        // quads per weight image
+    const int w_ops = (w8 + 63) / 64;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 31, h = lane >> 5;
+    const int n0 = blockIdx.y * NB;
+    const int rowtaps = d.kt * d.kd * d.kh;
+    const int n_kc = (a.K + kBfCK - 1) / kBfCK;
+    const int nck = rowtaps * n_kc;
+    const long long n_tiles = (d.Q + TM - 1) / TM;
+    const bool k_full = (a.K % kBfCK) == 0;
+    const long long last_quad = d.Q * a.K - 8;   // highest legal quad start (elements)
+
+    unsigned s_off[MAXS], w_off[MAXW];
+    int s_pp[MAXS], s_c8[MAXS];
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+        const int v = (wave + i * NW) * 64 + lane;
+        s_pp[i] = v / QP;
+        s_c8[i] = (v % QP) ^ ((s_pp[i] / RP) % QP);
+        s_off[i] = (unsigned)(s_pp[i] * a.K + 8 * s_c8[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < MAXW; ++i) {
+        const int v = (wave + i * NW) * 64 + lane;
+        w_off[i] = 8u * (unsigned)(v < w8 ? v : 0);
+    }
+    auto issue = [&](long long tile, int c, uint4* dst) {
+        const int rt = c / n_kc, kc = c % n_kc;
+        const long long qs = tile * TM + rowtap_offset(rt, d) - kw / 2;
+        const bool interior = k_full && qs >= 0 && qs + (long long)slab_ops * 64 / QP <= d.Q;   // uniform
+        if (interior) {
+            const unsigned short* base = a.in + qs * a.K + kc * kBfCK;
+#pragma unroll
+            for (int i = 0; i < MAXS; ++i) {
+                const int o = wave + i * NW;
+                if (o < slab_ops)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + s_off[i]),
+                                                     (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < MAXS; ++i) {
+                const int o = wave + i * NW;
+                if (o < slab_ops) {
+                    long long off = (qs + s_pp[i]) * a.K + kc * kBfCK + 8 * s_c8[i];
+                    off = off < 0 ? 0 : (off > last_quad ? last_quad : off);
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.in + off),
+                                                     (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
+                }
+            }
+        }
+        const unsigned short* src = a.wt + ((size_t)(rt * n_kc + kc) * gridDim.y + blockIdx.y) * (size_t)(kw * kBfCK * NB);
+        uint4* wdst = dst + slab_ops * 64;
+#pragma unroll
+        for (int i = 0; i < MAXW; ++i) {
+            const int o = wave + i * NW;
+            if (o < w_ops)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + w_off[i]),
+                                                 (__attribute__((address_space(3))) void*)(wdst + o * 64), 16, 0, 0);
+        }
+    };
+
+    // quad index of this lane's pixel operand for every (tap along W, 16-channel K-block)
+    int p_off[KWM][G];
+#pragma unroll
+    for (int dw = 0; dw < KWM; ++dw) {
+        const int pix = wave * 32 + m + dw;
+        const int key = (pix / RP) % QP;
+#pragma unroll
+        for (int g = 0; g < G; ++g) p_off[dw][g] = pix * QP + ((2 * g + h) ^ key);
+    }
+    const int wa_lane = h * NB + m;
+
+    const XcdRange xr = xcd_range(n_tiles);
+    long long tile = xr.first;
+    int c = 0;
+    if (tile < xr.end) issue(tile, 0, bufA);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    long long q = 0;
+    unsigned vbits = 0u;
+    floatx16 acc[NJ];
+    auto step = [&](const uint4* slab, uint4* nxt) {
+        if (c == 0) {
+            q = tile * TM + wave * 32 + m;
+            vbits = tap_validity(q, d);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+        }
+        const bool last = c + 1 == nck;
+        const long long ntile = last ? tile + xr.stride : tile;
+        const int nc = last ? 0 : c + 1;
+        if (ntile < xr.end) issue(ntile, nc, nxt);
+        const uint4* wl = slab + slab_ops * 64 + wa_lane;
+        const int rt = c / n_kc;
+#pragma unroll
+        for (int dw = 0; dw < KWM; ++dw) {
+            if (KW == 0 && dw >= kw) continue;
+            const unsigned okm = ((vbits >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                uint4 pb = slab[p_off[dw][g]];
+                if (a.relu_in) {
+                    pb.x = relu_bf16x2(pb.x); pb.y = relu_bf16x2(pb.y); pb.z = relu_bf16x2(pb.z); pb.w = relu_bf16x2(pb.w);
+                }
+                pb.x &= okm; pb.y &= okm; pb.z &= okm; pb.w &= okm;   // zero padding: tap outside the grid
+                const bf16x8 pv = __builtin_bit_cast(bf16x8, pb);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const uint4 wa = wl[(dw * G + g) * 2 * NB + 32 * j];
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa), pv, acc[j], 0, 0, 0);
+                }
+            }
+        }
+        if (last && q < d.Q) {
+            // lane holds pixel q and, per register group, 4 consecutive output channels
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int co0 = n0 + 32 * j + 8 * rg + 4 * h;
+                    if (co0 >= a.Nn) continue;
+                    const long long o = q * a.Nn + co0;
+                    if (!a.out_f32 && (a.Nn % 4) == 0) {
+                        // four consecutive bf16 channels = one 8-byte access
+                        float x[4] = {acc[j][4 * rg], acc[j][4 * rg + 1], acc[j][4 * rg + 2], acc[j][4 * rg + 3]};
+                        if (a.bias) {
+                            const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0);
+                            x[0] += bv.x; x[1] += bv.y; x[2] += bv.z; x[3] += bv.w;
+                        }
+                        if (a.relu_out) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) x[i] = fmaxf(x[i], 0.f);
+                        }
+                        uint2 rf = make_uint2(0x3f803f80u, 0x3f803f80u);   // 1.0 in every half
+                        if (a.mask_ref) rf = *reinterpret_cast<const uint2*>(a.mask_ref + o);
+                        const float ref[4] = {bf16_to_f32((unsigned short)rf.x), bf16_to_f32((unsigned short)(rf.x >> 16)),
+                                              bf16_to_f32((unsigned short)rf.y), bf16_to_f32((unsigned short)(rf.y >> 16))};
+                        if (a.mask_acc) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) x[i] = ref[i] > 0.f ? x[i] : 0.f;
+                        }
+                        if (a.add) {
+                            const uint2 av = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned short*>(a.add) + o);
+                            const float ad[4] = {bf16_to_f32((unsigned short)av.x), bf16_to_f32((unsigned short)(av.x >> 16)),
+                                                 bf16_to_f32((unsigned short)av.y), bf16_to_f32((unsigned short)(av.y >> 16))};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) x[i] += (a.mask_add && !(ref[i] > 0.f)) ? 0.f : ad[i];
+                        }
+                        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.out) + o) =
+                            make_uint2(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]));
+                        continue;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (co0 + i >= a.Nn) break;
+                        float x = acc[j][4 * rg + i];
+                        if (a.bias) x += a.bias[co0 + i];
+                        if (a.relu_out) x = fmaxf(x, 0.f);
+                        const float ref = a.mask_ref ? bf16_to_f32(a.mask_ref[o + i]) : 1.f;
+                        if (a.mask_acc) x = ref > 0.f ? x : 0.f;
+                        if (a.add) {
+                            const float av = a.out_f32 ? reinterpret_cast<const float*>(a.add)[o + i]
+                                                       : bf16_to_f32(reinterpret_cast<const unsigned short*>(a.add)[o + i]);
+                            x += (a.mask_add && !(ref > 0.f)) ? 0.f : av;
+                        }
+                        if (a.out_f32) reinterpret_cast<float*>(a.out)[o + i] = x;
+                        else reinterpret_cast<unsigned short*>(a.out)[o + i] = f32_to_bf16(x);
+                    }
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        tile = ntile;
+        c = nc;
+    };
+    while (tile < xr.end) {
+        step(bufA, bufB);
+        if (tile >= xr.end) break;
+        step(bufB, bufA);
+    }
+}
+
+template <int NB, int KW>
+static void launch_conv_bf16_k(const ConvBf16Args& a, hipStream_t st) {
+    constexpr int TM = 128, QP = kBfCK / 8, KWM = KW > 0 ? KW : 5;
+    constexpr size_t lds = (size_t)2 * (((TM + KWM - 1) * QP + 63) / 64 + (KWM * kBfCK * NB / 8 + 63) / 64) * 1024;
+    const long long n_tiles = (a.d.Q + TM - 1) / TM;
+    int per_cu = (int)(160 * 1024 / lds);
+    if (per_cu > 4) per_cu = 4;
+    if (per_cu < 1) per_cu = 1;
+    const long long cap = 256LL * per_cu;
+    const long long gx = ((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8;
+    dim3 grid((unsigned)gx, (a.Nn + NB - 1) / NB);
+    hipLaunchKernelGGL((conv_bf16_kernel<NB, KW>), grid, dim3(256), 0, st, a);
+}
+
+hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long sn, long long st_, long long sk, int flip,
+                            unsigned short* wt_scratch, hipStream_t stream) {
+    ConvBf16Args a = a_in;
+    const int taps = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
+    const int nb = bf_nb(a.Nn);
+    {
+        WimgBf16Args t{};
+        t.w = w; t.wt = wt_scratch; t.sn = sn; t.st = st_; t.sk = sk;
+        t.K = a.K; t.Nn = a.Nn; t.flip = flip; t.taps = taps; t.kw = a.d.kw; t.NB = nb;
+        t.n_kc = (a.K + kBfCK - 1) / kBfCK; t.n_nb = (a.Nn + nb - 1) / nb;
+        t.total = (long long)conv_bf16_wimg_elems(a.K, a.Nn, taps);
+        KernelScope ks("weights_image_bf16", 0.0, 6.0 * (double)t.total, stream);
+        hipLaunchKernelGGL(weights_image_bf16_kernel, dim3((unsigned)((t.total + 255) / 256)), dim3(256), 0, stream, t);
+    }
+    a.wt = wt_scratch;
+    char name[56];
+    snprintf(name, sizeof(name), "conv_bf16_%s_%dto%d_t%d", flip ? "dgrad" : "fwd", a.K, a.Nn, taps);
+    KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps, 2.0 * (double)a.d.Q * (a.K + a.Nn), stream);
+    if (nb == 32) {
+        if (a.d.kw == 3) launch_conv_bf16_k<32, 3>(a, stream);
+        else if (a.d.kw == 1) launch_conv_bf16_k<32, 1>(a, stream);
+        else launch_conv_bf16_k<32, 0>(a, stream);
+    } else {
+        if (a.d.kw == 3) launch_conv_bf16_k<64, 3>(a, stream);
+        else if (a.d.kw == 1) launch_conv_bf16_k<64, 1>(a, stream);
+        else launch_conv_bf16_k<64, 0>(a, stream);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ weight gradient
+constexpr int kBwTM = 32;     // pixels per staged chunk = two MFMA K-blocks of 16
+constexpr int kBwRow = 48;    // LDS row length in pixels (32 + up to 4 halo, padded so rows stay 16-byte aligned)
+
+size_t wgrad_bf16_lds_bytes(int Co, int Ci, int kt, int kd, int kh, int kw) {
+    const int rowtaps = kt * kd * kh, taps = rowtaps * kw;
+    return ((size_t)Co * kBwRow + (size_t)rowtaps * Ci * kBwRow + (size_t)taps * kBwTM) * sizeof(unsigned short) + 16;
+}
+
+// Each wave owns one (32 cout x 32 cin) block and JT consecutive taps starting at a multiple of KW.
+template <int JT, int KW, int NW>
+__global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
+    constexpr int NT = NW * 64;
+    extern __shared__ unsigned short smem16[];
+    const PixDims d = a.d;
+    const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * KW;
+    const int n_pa = kBwTM + KW - 1;
+    unsigned short* gsT = smem16;                               // [Co][kBwRow]      pixel p at column p
+    unsigned short* asT = gsT + a.Co * kBwRow;                  // [rowtaps][Ci][kBwRow]  slab pixel pp at column pp
+    unsigned short* vmT = asT + rowtaps * a.Ci * kBwRow;        // [taps][kBwTM] 0xffff where (pixel, tap) is inside the grid
+    __shared__ int all_valid;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 31, h = lane >> 5;
+    const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
+    const int tapgroups = (taps + JT - 1) / JT;
+    const int job = blockIdx.y * NW + wave;
+    const bool active = job < ncb * nib * tapgroups;
+    const int tg = job % tapgroups, pair = job / tapgroups;
+    const int cb = pair / nib, ib = pair % nib;
+    const int tap0 = tg * JT;                                   // multiple of KW by construction (JT % KW == 0)
+    const int Co8 = a.Co / 8, Ci8 = a.Ci / 8;
+    const int n_g8 = kBwTM * Co8, n_a8 = rowtaps * n_pa * Ci8;
+    constexpr int PG = 2, PA = 8;                               // 16-byte staging slots per thread (upper bounds)
+
+    uint4 rg[PG], ra[PA];
+    float bsum[PG][8];
+#pragma unroll
+    for (int i = 0; i < PG; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bsum[i][e] = 0.f;
+
+    // prefetch loads are unconditional (clamped address); validity is applied when they are stashed
+    unsigned g_ok = 0u, a_ok = 0u;
+    auto fetch = [&](long long q0) {
+        g_ok = 0u;
+        a_ok = 0u;
+#pragma unroll
+        for (int i = 0; i < PG; ++i) {
+            const int v = tid + i * NT;
+            const int p = v / Co8, c8 = v % Co8;
+            const long long qq = q0 + p;
+            const bool ok = v < n_g8 && qq < d.Q;
+            rg[i] = *reinterpret_cast<const uint4*>(a.g + (ok ? qq * a.Co + 8 * c8 : 0));
+            g_ok |= (ok ? 1u : 0u) << i;
+        }
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            const int v = tid + i * NT;
+            const int rt = v / (n_pa * Ci8), r = v % (n_pa * Ci8);
+            const int p = r / Ci8, c8 = r % Ci8;
+            const long long qq = q0 + (v < n_a8 ? rowtap_offset(rt, d) : 0) - KW / 2 + p;
+            const bool ok = v < n_a8 && qq >= 0 && qq < d.Q;
+            ra[i] = *reinterpret_cast<const uint4*>(a.a + (ok ? qq * a.Ci + 8 * c8 : 0));
+            a_ok |= (ok ? 1u : 0u) << i;
+        }
+    };
+    auto stash = [&](long long q0) {
+#pragma unroll
+        for (int i = 0; i < PG; ++i) {
+            const int v = tid + i * NT;
+            if (v < n_g8) {
+                const int p = v / Co8, c8 = v % Co8;
+                const unsigned mk = ((g_ok >> i) & 1u) ? 0xffffffffu : 0u;
+                const unsigned w4[4] = {rg[i].x & mk, rg[i].y & mk, rg[i].z & mk, rg[i].w & mk};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned short hv = (unsigned short)(w4[e >> 1] >> (16 * (e & 1)));
+                    gsT[(8 * c8 + e) * kBwRow + p] = hv;
+                    bsum[i][e] += bf16_to_f32(hv);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            const int v = tid + i * NT;
+            if (v < n_a8) {
+                const int rt = v / (n_pa * Ci8), r = v % (n_pa * Ci8);
+                const int p = r / Ci8, c8 = r % Ci8;
+                const unsigned mk = ((a_ok >> i) & 1u) ? 0xffffffffu : 0u;
+                unsigned w4[4] = {ra[i].x & mk, ra[i].y & mk, ra[i].z & mk, ra[i].w & mk};
+                if (a.relu_in) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w4[e] = relu_bf16x2(w4[e]);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    asT[(rt * a.Ci + 8 * c8 + e) * kBwRow + p] = (unsigned short)(w4[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        if (tid < kBwTM) {
+            const unsigned vb = tap_validity(q0 + tid, d);
+            for (int t = 0; t < taps; ++t) vmT[t * kBwTM + tid] = ((vb >> t) & 1u) ? 0xffffu : 0u;
+            const unsigned full = taps >= 32 ? 0xffffffffu : ((1u << taps) - 1u);
+            const bool okall = vb == full;
+            // wave 0 holds threads 0..63 >= kBwTM: ballot over the first 32 lanes
+            const unsigned long long bal = __ballot(okall);
+            if (tid == 0) all_valid = (bal & 0xffffffffull) == 0xffffffffull;
+        }
+    };
+
+    floatx16 acc[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    const int co = cb * 32 + m, ci = ib * 32 + m;
+    const int co_c = co < a.Co ? co : a.Co - 1, ci_c = ci < a.Ci ? ci : a.Ci - 1;
+    const int rt0 = tap0 / KW;
+
+    const long long n_chunks = (d.Q + kBwTM - 1) / kBwTM;
+    const XcdRange xr = xcd_range(n_chunks);
+    long long chunk = xr.first;
+    if (chunk < xr.end) {
+        fetch(chunk * kBwTM);
+        stash(chunk * kBwTM);
+    }
+    __syncthreads();
+    for (; chunk < xr.end; chunk += xr.stride) {
+        const long long next = chunk + xr.stride;
+        if (next < xr.end) fetch(next * kBwTM);
+        if (active) {
+            const bool fast = all_valid != 0;
+#pragma unroll
+            for (int kb = 0; kb < kBwTM / 16; ++kb) {
+                const int px = 16 * kb + 8 * h;   // this lane's first pixel of the K-block
+                const uint4 ga = *reinterpret_cast<const uint4*>(gsT + co_c * kBwRow + px);
+                const bf16x8 gv = __builtin_bit_cast(bf16x8, ga);
+#pragma unroll
+                for (int jr = 0; jr < JT / KW; ++jr) {
+                    const int rt = rt0 + jr < rowtaps ? rt0 + jr : rowtaps - 1;
+                    const unsigned short* row = asT + (rt * a.Ci + ci_c) * kBwRow + px;
+                    // window of slab pixels px .. px+9 as five 32-bit words (+ one more for KW = 5)
+                    const uint4 lo = *reinterpret_cast<const uint4*>(row);
+                    const uint2 hi = *reinterpret_cast<const uint2*>(row + 8);
+                    const unsigned dws[6] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y};
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw) {
+                        const int j = jr * KW + dw;
+                        uint4 b;
+                        if (dw % 2 == 0) {
+                            b = make_uint4(dws[dw / 2], dws[dw / 2 + 1], dws[dw / 2 + 2], dws[dw / 2 + 3]);
+                        } else {
+                            b.x = __builtin_amdgcn_alignbit(dws[dw / 2 + 1], dws[dw / 2], 16);
+                            b.y = __builtin_amdgcn_alignbit(dws[dw / 2 + 2], dws[dw / 2 + 1], 16);
+                            b.z = __builtin_amdgcn_alignbit(dws[dw / 2 + 3], dws[dw / 2 + 2], 16);
+                            b.w = __builtin_amdgcn_alignbit(dws[dw / 2 + 4], dws[dw / 2 + 3], 16);
+                        }
+                        if (!fast) {
+                            const int tap = tap0 + j < taps ? tap0 + j : taps - 1;
+                            const uint4 mk = *reinterpret_cast<const uint4*>(vmT + tap * kBwTM + px);
+                            b.x &= mk.x; b.y &= mk.y; b.z &= mk.z; b.w &= mk.w;
+                        }
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b), acc[j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (next < xr.end) stash(next * kBwTM);
+        __syncthreads();
+    }
+    if (active) {
+        float* dst = a.partial + (size_t)blockIdx.x * a.Co * taps * a.Ci;
+#pragma unroll
+        for (int j = 0; j < JT; ++j) {
+            const int tap = tap0 + j;
+            if (tap >= taps || ci >= a.Ci) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int cc = cb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (cc < a.Co) dst[((size_t)cc * taps + tap) * a.Ci + ci] = acc[j][r];
+            }
+        }
+    }
+    if (a.bias_partial != nullptr && blockIdx.y == 0) {
+        __syncthreads();
+        float* red = reinterpret_cast<float*>(smem16);   // [PG*NT][8] floats; fits: checked by the launcher
+#pragma unroll
+        for (int i = 0; i < PG; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[(tid + i * NT) * 8 + e] = (tid + i * NT) < n_g8 ? bsum[i][e] : 0.f;
+        __syncthreads();
+        if (tid < a.Co) {
+            const int c8 = tid / 8, e = tid % 8;
+            float t = 0.f;
+            for (int v = c8; v < PG * NT; v += Co8) t += red[v * 8 + e];
+            a.bias_partial[(size_t)blockIdx.x * a.Co + tid] = t;
+        }
+    }
+}
+
+template <int JT, int KW, int NW>
+static void launch_wgrad_bf16_k(const WgradBf16Args& a, dim3 grid, size_t lds, hipStream_t st) {
+    static bool once = false;
+    if (!once) {
+        (void)hipFuncSetAttribute((const void*)wgrad_bf16_kernel<JT, KW, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        once = true;
+    }
+    hipLaunchKernelGGL((wgrad_bf16_kernel<JT, KW, NW>), grid, dim3(NW * 64), lds, st, a);
+}
+
+// Supported: Co, Ci multiples of 8 (16-byte rows), kw in {1, 3}; the caller checks and falls back otherwise.
+hipError_t launch_wgrad_bf16(const WgradBf16Args& a, int n_split, hipStream_t stream) {
+    const PixDims& d = a.d;
+    const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
+    char name[56];
+    snprintf(name, sizeof(name), "conv_bf16_wgrad_%dto%d_t%d", a.Ci, a.Co, taps);
+    KernelScope ks(name, 2.0 * (double)d.Q * a.Ci * a.Co * taps, 2.0 * (double)d.Q * (a.Ci + a.Co), stream);
+    constexpr int NW = 8, NT = NW * 64;
+    size_t lds = wgrad_bf16_lds_bytes(a.Co, a.Ci, d.kt, d.kd, d.kh, d.kw);
+    const size_t red = (size_t)2 * NT * 8 * sizeof(float);
+    if (lds < red) lds = red;
+    const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
+    const int n_pa = kBwTM + d.kw - 1;
+    // staging slots per thread must fit the compile-time bounds (2 for g, 8 for a)
+    if (kBwTM * (a.Co / 8) > 2 * NT || rowtaps * n_pa * (a.Ci / 8) > 8 * NT || lds > 150 * 1024) return hipErrorInvalidValue;
+    if (d.kw == 3) {
+        const int jt = 9, tapgroups = (taps + jt - 1) / jt;
+        dim3 grid(n_split, (ncb * nib * tapgroups + NW - 1) / NW);
+        launch_wgrad_bf16_k<9, 3, NW>(a, grid, lds, stream);
+    } else if (d.kw == 1) {
+        const int jt = 3, tapgroups = (taps + jt - 1) / jt;
+        dim3 grid(n_split, (ncb * nib * tapgroups + NW - 1) / NW);
+        launch_wgrad_bf16_k<3, 1, NW>(a, grid, lds, stream);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace gleam

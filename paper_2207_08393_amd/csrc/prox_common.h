@@ -1,0 +1,100 @@
+// Declarations shared by the float32 (prox.hip) and bfloat16 (prox_bf16.hip) prox kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+#include "xcd.h"
+
+namespace gleam {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kConvThreads = 256;
+constexpr int kConvTM = 256;  // pixels per workgroup tile of the forward / data-gradient kernel
+
+struct PixDims {
+    int T, D, H, W;
+    int kt, kd, kh, kw;
+    long long Q;
+};
+
+// Bit `tap` is set when pixel q + off(tap) lies inside the grid (same sample, frame, slice, row).
+__device__ __forceinline__ unsigned tap_validity(long long q, const PixDims& d) {
+    if (q >= d.Q) return 0u;
+    const int w = (int)(q % d.W);
+    long long r = q / d.W;
+    const int h = (int)(r % d.H);
+    r /= d.H;
+    const int dd = (int)(r % d.D);
+    r /= d.D;
+    const int t = (int)(r % d.T);
+    unsigned bits = 0u;
+    int tap = 0;
+    for (int it = 0; it < d.kt; ++it)
+        for (int id = 0; id < d.kd; ++id)
+            for (int ih = 0; ih < d.kh; ++ih)
+                for (int iw = 0; iw < d.kw; ++iw, ++tap) {
+                    const int tt = t + it - d.kt / 2, d2 = dd + id - d.kd / 2;
+                    const int hh = h + ih - d.kh / 2, ww = w + iw - d.kw / 2;
+                    const bool ok = tt >= 0 && tt < d.T && d2 >= 0 && d2 < d.D && hh >= 0 && hh < d.H && ww >= 0 && ww < d.W;
+                    bits |= (ok ? 1u : 0u) << tap;
+                }
+    return bits;
+}
+
+// Flattened pixel offset of row-tap rt = (it, id, ih), before the kw taps along W.
+__device__ __forceinline__ long long rowtap_offset(int rt, const PixDims& d) {
+    const int ih = rt % d.kh, id = (rt / d.kh) % d.kd, it = rt / (d.kh * d.kd);
+    return (((long long)(it - d.kt / 2) * d.D + (id - d.kd / 2)) * d.H + (ih - d.kh / 2)) * d.W;
+}
+
+
+// ------------------------------------------------------------------ bfloat16 helpers
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ unsigned short f32_to_bf16(float f) {   // round to nearest even
+    unsigned u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+}
+// max(x, 0) on two packed bf16 values: clear every half whose sign bit is set
+__device__ __forceinline__ unsigned relu_bf16x2(unsigned x) {
+    const unsigned neg = ((x >> 15) & 0x00010001u) * 0xffffu;
+    return x & ~neg;
+}
+
+// Launch arguments of the bf16 MFMA convolution (forward and data gradient): in/out/mask_ref/add are
+// bfloat16 [Q][channels] unless out_f32 (then out and add are float32).  wt: bf16 LDS images.
+struct ConvBf16Args {
+    const unsigned short* in;
+    void* out;
+    const unsigned short* wt;
+    const float* bias;
+    const unsigned short* mask_ref;
+    const void* add;
+    int K, Nn;
+    int out_f32;
+    int relu_in, relu_out, mask_acc, mask_add;
+    PixDims d;
+};
+hipError_t launch_conv_bf16(const ConvBf16Args& a, const float* w, long long sn, long long st, long long sk, int flip,
+                            unsigned short* wt_scratch, hipStream_t stream);
+size_t conv_bf16_wimg_elems(int K, int Nn, int taps);
+
+// Weight gradient with bf16 operands: g [Q][Co], a [Q][Ci] bfloat16; partial sums float32.
+struct WgradBf16Args {
+    const unsigned short* g;
+    const unsigned short* a;
+    float* partial;        // [gridDim.x][Co][taps][Ci]
+    float* bias_partial;   // [gridDim.x][Co] or null
+    int Co, Ci, relu_in;
+    PixDims d;
+};
+hipError_t launch_wgrad_bf16(const WgradBf16Args& a, int n_split, hipStream_t stream);
+size_t wgrad_bf16_lds_bytes(int Co, int Ci, int kt, int kd, int kh, int kw);
+
+}  // namespace gleam

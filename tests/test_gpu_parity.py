@@ -164,8 +164,8 @@ def test_config4_cine2dt_full_size():
 
 @pytest.mark.timeout(900)
 def test_config2_brain2d_full_size_fp32_convs():
-    """Brain-shaped workload (128-channel chain, batch 4) at full size.  Its bf16 operand mode has no
-    kernels yet, so the float32 convolutions run here, against the float32 tolerance."""
+    """Brain-shaped workload (128-channel chain, batch 4) at full size with float32 convolutions, against
+    the float32 tolerance (its bfloat16 mode is test_config2_brain2d_full_size_bf16)."""
     c = synth.make_case(2)
     c.prox.dtype = 0
     print("case cfg2 brain, fp32 convs", flush=True)
@@ -180,9 +180,41 @@ def test_config3_vol3d_full_size():
     check_module(c)
 
 
-def test_bf16_operand_mode_is_rejected_not_silently_run_in_fp32():
-    c = synth.make_case(0)
-    c.prox.dtype = 1
+BF16_TOL = 2e-2   # bfloat16 operands (8 mantissa bits), float32 accumulation; oracle stays float64
+
+
+def bf16_cases():
+    yield "chain16", synth.Geom(2, 1, 2, 1, 1, 12, 20), synth.chain_prox([2, 16, 16, 2], [K2] * 3, dtype=1), 0
+    yield "chain40", synth.Geom(2, 2, 2, 1, 1, 46, 20), synth.chain_prox([2, 40, 72, 40, 2], [K2] * 4, dtype=1), 0
+    yield "res64", synth.Geom(2, 1, 2, 1, 1, 24, 32), synth.resblock_prox(64, 2, dtype=1), 0
+    yield "chain128_l1", synth.Geom(2, 1, 2, 1, 1, 20, 24), synth.chain_prox([2, 128, 128, 128, 2], [K2] * 4, dtype=1), 1
+    yield "vol32", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3, dtype=1), 0
+    yield "cine64", synth.Geom(2, 1, 2, 6, 1, 12, 16), synth.chain_prox([2, 64, 64, 64, 2], [KS, KT, KS, KT], dtype=1), 0
+
+
+@pytest.mark.parametrize("name,geom,prox,loss_kind", list(bf16_cases()), ids=[m[0] for m in bf16_cases()])
+def test_module_bf16_operands_match_oracle(name, geom, prox, loss_kind):
+    prox.loss_kind = loss_kind
+    c = synth.make_custom(41, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.8)
+    print("case bf16", name, flush=True)
+    check_module(c, tol=BF16_TOL)
+
+
+def test_bf16_mode_rejects_networks_without_kernels():
+    geom = gb.make_geom(synth.Geom(2, 1, 2, 1, 1, 8, 8))
+    odd = synth.chain_prox([2, 12, 20, 2], [K2] * 3, dtype=1)       # 12 and 20 are multiples of 4, not of 8
     with pytest.raises(gb.GleamError) as e:
-        gb.gleam_workspace_bytes(gb.make_geom(c.geom), gb.make_prox(c.prox))
+        gb.gleam_workspace_bytes(geom, gb.make_prox(odd))
     assert e.value.status == gb.GLEAM_E_DESC
+    k5 = synth.chain_prox([2, 16, 2], [(1, 1, 5, 5)] * 2, dtype=1)
+    with pytest.raises(gb.GleamError):
+        gb.gleam_workspace_bytes(geom, gb.make_prox(k5))
+
+
+@pytest.mark.timeout(900)
+def test_config2_brain2d_full_size_bf16():
+    """Brain-shaped workload as configured: bfloat16 conv operands, float32 accumulation, complex64 SENSE."""
+    c = synth.make_case(2)
+    assert c.prox.dtype == 1
+    print("case cfg2 brain, bf16 convs", flush=True)
+    check_module(c, tol=BF16_TOL)
