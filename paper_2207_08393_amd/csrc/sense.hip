@@ -94,6 +94,7 @@ template <int N>
 __global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsArgs a) {
     constexpr int L = reduce_lines<N>(), NT = reduce_threads<N>(), H2 = N / 2;
     constexpr int PER = (H2 * L + NT - 1) / NT;   // output pairs per thread (upper bound: CG = 1)
+    constexpr int kSPre = 8;                      // coil-map values per thread fetched ahead of the transform
     using Lay = Layout<N, L, 1>;
     __shared__ float2 buf[Lay::kElems], tw[N];
     __shared__ long long koff[L], soff[L];        // per image row of the tile, coil 0
@@ -133,6 +134,18 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsAr
                 buf[Lay::at(line, p)] = make_float2(v.x, v.y);
                 buf[Lay::at(line, p + 1)] = make_float2(v.z, v.w);
             }
+            // the coil maps of this thread's first output pair are fetched before the transform, so their
+            // latency is hidden behind it (tiles of one image row, the common case, have one pair per thread)
+            float4 s0[kSPre];
+            {
+                const int e = threadIdx.x;
+                const int r = e / H2, p = 2 * (e % H2);
+                const bool ok = e < H2 * LR && koff[r < LR ? r : 0] >= 0;
+                const float2* sp = a.S + (ok ? soff[r] + (long long)c0 * sstride + p : 0);
+#pragma unroll
+                for (int c = 0; c < kSPre; ++c)
+                    s0[c] = *reinterpret_cast<const float4*>(sp + (ok && c < ncg ? c * sstride : 0));
+            }
             __syncthreads();
             fft_lines<N, L, 1, true, NT>(buf, tw);
 #pragma unroll
@@ -141,6 +154,17 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsAr
                 if (e < H2 * LR) {
                     const int r = e / H2, p = 2 * (e % H2);
                     if (koff[r] >= 0) {
+                        if (m == 0 && CG <= kSPre) {
+#pragma unroll
+                            for (int c = 0; c < kSPre; ++c) {
+                                if (c < ncg) {
+                                    const float2 v0 = buf[Lay::at(r * CG + c, p)], v1 = buf[Lay::at(r * CG + c, p + 1)];
+                                    const float2 p0 = cmul_conj(v0, make_float2(s0[c].x, s0[c].y));
+                                    const float2 p1 = cmul_conj(v1, make_float2(s0[c].z, s0[c].w));
+                                    acc[m].x += p0.x; acc[m].y += p0.y; acc[m].z += p1.x; acc[m].w += p1.y;
+                                }
+                            }
+                        } else
                         for (int c = 0; c < ncg; ++c) {
                             const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[r] + (c0 + c) * sstride + p);
                             const float2 v0 = buf[Lay::at(r * CG + c, p)], v1 = buf[Lay::at(r * CG + c, p + 1)];
