@@ -211,7 +211,7 @@ struct ColsArgs {
 // MODE 0: forward, 1: inverse, 2: forward -> (mask ? k - y : 0) -> inverse.  In MODE 2 the measured
 // k-space and the mask bytes of the tile are fetched into registers before the forward transform.
 template <int N, int MODE>
-__global__ __launch_bounds__(cols_threads<N>()) void cols_kernel(ColsArgs a) {
+__global__ __launch_bounds__(cols_threads<N>(), (N >= 512 ? 2 : 1) * cols_threads<N>() / 256) void cols_kernel(ColsArgs a) {
     constexpr int L = cols_lines<N>(), NT = cols_threads<N>(), L2 = L / 2;
     constexpr int PER = (N * L2 + NT - 1) / NT;
     using Lay = Layout<N, L, 0>;
@@ -234,8 +234,11 @@ __global__ __launch_bounds__(cols_threads<N>()) void cols_kernel(ColsArgs a) {
             mbase = ((b * a.T + t) * a.Dq + dq) * N * a.inner + i0;
         }
         __syncthreads();
-        float4 yv[MODE == 2 ? PER : 1];
-        unsigned mk[MODE == 2 ? PER : 1];
+        // Long transforms keep two workgroups per CU resident instead (register budget), and fetch the
+        // measured k-space at the mask stage while the other workgroup computes.
+        constexpr bool kPre = MODE == 2 && N < 512;
+        float4 yv[kPre ? PER : 1];
+        unsigned mk[kPre ? PER : 1];
 #pragma unroll
         for (int m = 0; m < PER; ++m) {
             const int idx = threadIdx.x + m * NT;
@@ -246,7 +249,7 @@ __global__ __launch_bounds__(cols_threads<N>()) void cols_kernel(ColsArgs a) {
                 if (l < valid) v = *reinterpret_cast<const float4*>(a.k + base + off);
                 buf[Lay::at(l, p)] = make_float2(v.x, v.y);
                 buf[Lay::at(l + 1, p)] = make_float2(v.z, v.w);
-                if constexpr (MODE == 2) {
+                if constexpr (kPre) {
                     yv[m] = make_float4(0.f, 0.f, 0.f, 0.f);
                     mk[m] = 0u;
                     if (l < valid) {
@@ -272,8 +275,18 @@ __global__ __launch_bounds__(cols_threads<N>()) void cols_kernel(ColsArgs a) {
                     const int l = 2 * (idx % L2), p = idx / L2;
                     const float2 v0 = buf[Lay::at(l, p)], v1 = buf[Lay::at(l + 1, p)];
                     float2 r0 = make_float2(0.f, 0.f), r1 = r0;
-                    if (mk[m] & 0x00ffu) r0 = make_float2(v0.x * fs - yv[m].x, v0.y * fs - yv[m].y);
-                    if (mk[m] & 0xff00u) r1 = make_float2(v1.x * fs - yv[m].z, v1.y * fs - yv[m].w);
+                    float4 yy = make_float4(0.f, 0.f, 0.f, 0.f);
+                    unsigned mm = 0u;
+                    if constexpr (kPre) {
+                        yy = yv[m];
+                        mm = mk[m];
+                    } else if (l < valid) {
+                        const long long off = (long long)p * a.inner + l;
+                        mm = *reinterpret_cast<const unsigned short*>(a.M + mbase + off);
+                        if (a.y != nullptr) yy = *reinterpret_cast<const float4*>(a.y + base + off);
+                    }
+                    if (mm & 0x00ffu) r0 = make_float2(v0.x * fs - yy.x, v0.y * fs - yy.y);
+                    if (mm & 0xff00u) r1 = make_float2(v1.x * fs - yy.z, v1.y * fs - yy.w);
                     buf[Lay::at(l, p)] = r0;
                     buf[Lay::at(l + 1, p)] = r1;
                 }
