@@ -593,6 +593,178 @@ __global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
     }
 }
 
+// Convolution whose OUTPUT has two channels (last layer forward): K wide -> 2.  HBM-bound on its input,
+// so no MFMA.  A tile is 64 neighbouring pixels of one image row, one lane each.  The input rows of every
+// row tap are staged in LDS (KC channels per round, zero outside the grid, ReLU applied), pixel stride
+// KC + 4 floats so that 16-byte reads of neighbouring lanes do not collide.  Work items (row tap,
+// 16-channel chunk) are dealt to the four waves; the two output channels' weights of an item are
+// wave-uniform, read straight from theta (a restrict kernel argument, so they come as scalar loads).  Partial sums of the waves meet in LDS, where bias and the
+// skip tensor are added.  Input is float32 or (BF) bfloat16; output, skip and weights are float32.
+struct ConvThinOutArgs {
+    const void* in;       // [Q][K]
+    const float* bias;    // [2] or null
+    const float* add;     // [Q][2] or null
+    float* out;           // [Q][2]
+    int K, KC, relu_in, relu_out;
+    PixDims d;
+};
+
+constexpr int kThinOutPx = 64;
+
+__device__ __forceinline__ float4 zero_unless(bool ok, float4 v) {
+    return make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
+}
+
+template <int KT, int KD, int KH, int KW, bool BF, int KC>
+__global__ __launch_bounds__(256) void conv_thin_out_kernel(ConvThinOutArgs a, const float* __restrict__ wts) {
+    constexpr int RT = KT * KD * KH, TAPS = RT * KW, PXS = kThinOutPx + KW - 1, EPG = BF ? 8 : 4;
+    constexpr int RS = KC + 4, GPN = KC / EPG;   // pixel stride in floats; 16-byte groups per pixel and round
+    constexpr int PER_ROW = PXS * GPN, TOTAL = RT * PER_ROW, ITER = (TOTAL + 255) / 256;
+    constexpr int NCH = KC / 16;
+    static_assert(ITER <= 32, "validity bits of one staging round must fit a 32-bit mask");
+    extern __shared__ float smem[];
+    const PixDims d = a.d;
+    float* slab = smem;                        // [RT][PXS][RS]
+    float* red = smem + RT * PXS * RS;         // [4][64][2]
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
+    const int n_rounds = a.K / KC;
+    const int segs = (d.W + kThinOutPx - 1) / kThinOutPx;
+    const long long n_tiles = (d.Q / d.W) * segs;
+    const XcdRange xr = xcd_range(n_tiles);
+
+    // Per-thread staging slots, the same for every tile: slot `it` moves one 16-byte group from element
+    // offset rel[it] (relative to the tile's first pixel, channel 0 of the round) to LDS offset dst[it].
+    int rel[ITER], dst[ITER], pxo[ITER];
+    unsigned rtm[ITER];
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int idx = threadIdx.x + it * 256;
+        const int rt = idx / PER_ROW, rem = idx % PER_ROW, px = rem / GPN, gi = rem % GPN;
+        const int ih = rt % KH, id = (rt / KH) % KD, itp = rt / (KH * KD);
+        const int ot = itp - KT / 2, od = id - KD / 2, oh = ih - KH / 2;
+        rel[it] = ((((ot * d.D + od) * d.H + oh) * d.W) + px - KW / 2) * a.K + gi * EPG;
+        dst[it] = (rt * PXS + px) * RS + gi * EPG;
+        pxo[it] = px - KW / 2;
+        rtm[it] = idx < TOTAL ? 1u << rt : 0u;
+    }
+    // Staging registers of the NEXT (tile, round): fetched while the current one is being computed.
+    uint4 stg[ITER];
+    unsigned okm = 0u;
+    auto fetch = [&](long long tile, int rd) {
+        const long long row = tile / segs;
+        const int w0 = (int)(tile % segs) * kThinOutPx;
+        long long r = row;
+        const int hh = (int)(r % d.H);
+        r /= d.H;
+        const int dd = (int)(r % d.D);
+        r /= d.D;
+        const int tt = (int)(r % d.T);
+        unsigned rows_ok = 0u;   // bit rt: the input row of row tap rt lies inside the grid
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int ih = rt % KH, id = (rt / KH) % KD, itp = rt / (KH * KD);
+            const bool v = (unsigned)(tt + itp - KT / 2) < (unsigned)d.T && (unsigned)(dd + id - KD / 2) < (unsigned)d.D &&
+                           (unsigned)(hh + ih - KH / 2) < (unsigned)d.H;
+            rows_ok |= (v ? 1u : 0u) << rt;
+        }
+        const char* base = reinterpret_cast<const char*>(a.in) + ((row * d.W + w0) * a.K + rd * KC) * (BF ? 2 : 4);
+        okm = 0u;
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const bool ok = (rows_ok & rtm[it]) != 0u && (unsigned)(w0 + pxo[it]) < (unsigned)d.W;
+            const char* src = ok ? base + (long long)rel[it] * (BF ? 2 : 4) : reinterpret_cast<const char*>(a.in);
+            stg[it] = *reinterpret_cast<const uint4*>(src);   // clamped, always readable
+            okm |= (ok ? 1u : 0u) << it;
+        }
+    };
+
+    const float biasv = a.bias ? a.bias[threadIdx.x & 1] : 0.f;
+    long long tile = xr.first;
+    int rd = 0;
+    if (tile < xr.end) fetch(tile, 0);
+    float acc0 = 0.f, acc1 = 0.f;
+    while (tile < xr.end) {
+        __syncthreads();   // the previous round's readers are done with the slab
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            if (rtm[it] != 0u) {
+                const bool ok = (okm >> it) & 1u;
+                float* dp = slab + dst[it];
+                const uint4 u = stg[it];
+                if constexpr (BF) {
+                    float4 lo = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+                                            __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+                    float4 hi = make_float4(__uint_as_float(u.z << 16), __uint_as_float(u.z & 0xffff0000u),
+                                            __uint_as_float(u.w << 16), __uint_as_float(u.w & 0xffff0000u));
+                    if (a.relu_in) {
+                        lo = make_float4(fmaxf(lo.x, 0.f), fmaxf(lo.y, 0.f), fmaxf(lo.z, 0.f), fmaxf(lo.w, 0.f));
+                        hi = make_float4(fmaxf(hi.x, 0.f), fmaxf(hi.y, 0.f), fmaxf(hi.z, 0.f), fmaxf(hi.w, 0.f));
+                    }
+                    *reinterpret_cast<float4*>(dp) = zero_unless(ok, lo);
+                    *reinterpret_cast<float4*>(dp + 4) = zero_unless(ok, hi);
+                } else {
+                    float4 v = make_float4(__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w));
+                    if (a.relu_in) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+                    *reinterpret_cast<float4*>(dp) = zero_unless(ok, v);
+                }
+            }
+        }
+        __syncthreads();
+        const int k0 = rd * KC;
+        const bool last_round = rd + 1 == n_rounds;
+        const long long ntile = last_round ? tile + xr.stride : tile;
+        const int nrd = last_round ? 0 : rd + 1;
+        // the skip value of this thread's output is requested ahead of the next tile's fetch, so that
+        // waiting for it later does not wait for that fetch as well (loads complete in order)
+        float addv = 0.f;
+        if (last_round && a.add && threadIdx.x < 2 * kThinOutPx) {
+            const int w0 = (int)(tile % segs) * kThinOutPx, px = threadIdx.x >> 1;
+            if (w0 + px < d.W) addv = a.add[((tile / segs) * d.W + w0 + px) * 2 + (threadIdx.x & 1)];
+        }
+        if (ntile < xr.end) fetch(ntile, nrd);
+#pragma unroll
+        for (int i = 0; i < (RT * NCH + 3) / 4; ++i) {
+            const int item = wave + 4 * i;
+            if ((RT * NCH) % 4 != 0 && item >= RT * NCH) break;
+            const int rt = item / NCH, ch = item % NCH;
+#pragma unroll
+            for (int dw = 0; dw < KW; ++dw) {
+                const float* __restrict__ wp0 = wts + (long long)(rt * KW + dw) * a.K + k0 + ch * 16;
+                const float* __restrict__ wp1 = wp0 + (long long)TAPS * a.K;
+                const float* sp = slab + (rt * PXS + lane + dw) * RS + ch * 16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float4 x = *reinterpret_cast<const float4*>(sp + 4 * j);
+                    acc0 = fmaf(x.x, wp0[4 * j + 0], acc0); acc1 = fmaf(x.x, wp1[4 * j + 0], acc1);
+                    acc0 = fmaf(x.y, wp0[4 * j + 1], acc0); acc1 = fmaf(x.y, wp1[4 * j + 1], acc1);
+                    acc0 = fmaf(x.z, wp0[4 * j + 2], acc0); acc1 = fmaf(x.z, wp1[4 * j + 2], acc1);
+                    acc0 = fmaf(x.w, wp0[4 * j + 3], acc0); acc1 = fmaf(x.w, wp1[4 * j + 3], acc1);
+                }
+            }
+        }
+        if (last_round) {
+            const long long row = tile / segs;
+            const int w0 = (int)(tile % segs) * kThinOutPx;
+            *reinterpret_cast<float2*>(red + (wave * kThinOutPx + lane) * 2) = make_float2(acc0, acc1);
+            acc0 = 0.f;
+            acc1 = 0.f;
+            __syncthreads();
+            if (threadIdx.x < 2 * kThinOutPx) {
+                const int px = threadIdx.x >> 1, co = threadIdx.x & 1;
+                if (w0 + px < d.W) {
+                    float v = red[threadIdx.x] + red[2 * kThinOutPx + threadIdx.x] + red[4 * kThinOutPx + threadIdx.x] +
+                              red[6 * kThinOutPx + threadIdx.x];
+                    v += biasv;
+                    if (a.relu_out) v = fmaxf(v, 0.f);
+                    a.out[(row * d.W + w0 + px) * 2 + co] = v + addv;
+                }
+            }
+        }
+        tile = ntile;
+        rd = nrd;
+    }
+}
+
 // Re-lays one layer's weights as the LDS images conv_mfma_kernel<NB, CK> copies verbatim.  Image
 // (rt, kc, nb) holds row-tap rt, input-channel chunk kc and output-channel block nb as
 // [kw][CK/8][2][NB][4]: element (dw, k = 8g + 4h + s, n) at (((dw*G + g)*2 + h)*NB + n)*4 + s, zero
@@ -720,11 +892,64 @@ static hipError_t launch_conv_thin_in(const ConvArgs& a, const ConvWeights& cw, 
     return hipGetLastError();
 }
 
+template <int KT, int KD, int KH, int KW, int KC>
+static void launch_conv_thin_out_k(const ConvThinOutArgs& t, const float* w, bool bf, hipStream_t st) {
+    constexpr int RT = KT * KD * KH, PXS = kThinOutPx + KW - 1;
+    constexpr size_t lds = ((size_t)RT * PXS * (KC + 4) + 4 * kThinOutPx * 2) * sizeof(float);
+    const long long n_tiles = (t.d.Q / t.d.W) * ((t.d.W + kThinOutPx - 1) / kThinOutPx);
+    const long long cap = 256LL * (lds > 53 * 1024 ? 2 : 3);
+    const dim3 grid((unsigned)(((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8));
+    if (bf) hipLaunchKernelGGL((conv_thin_out_kernel<KT, KD, KH, KW, true, KC>), grid, dim3(256), lds, st, t, w);
+    else hipLaunchKernelGGL((conv_thin_out_kernel<KT, KD, KH, KW, false, KC>), grid, dim3(256), lds, st, t, w);
+}
+template <int KT, int KD, int KH, int KW>
+static void launch_conv_thin_out_t(const ConvThinOutArgs& t, const float* w, bool bf, hipStream_t st) {
+    constexpr int RT = KT * KD * KH;
+    if constexpr (RT <= 3) {   // slab of at most 56 KB: 64, 32 or 16 channels per round
+        if (t.KC == 64) return launch_conv_thin_out_k<KT, KD, KH, KW, 64>(t, w, bf, st);
+        if (t.KC == 32) return launch_conv_thin_out_k<KT, KD, KH, KW, 32>(t, w, bf, st);
+    }
+    launch_conv_thin_out_k<KT, KD, KH, KW, 16>(t, w, bf, st);
+}
+
+// Launches the two-channel-output kernel when the layer fits it (forward pass only: weights are read in
+// theta's own layout); *hit tells whether it did.  `in` is bfloat16 when bf.
+static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw, bool bf, bool* hit, hipStream_t st) {
+    *hit = false;
+    const PixDims& d = a.d;
+    const int taps_ = d.kt * d.kd * d.kh * d.kw;
+    if (!(a.Nn == 2 && a.K >= 16 && a.K % 16 == 0 && !a.flip && !a.mask_ref && cw.sk == 1 && cw.st == a.K &&
+          cw.sn == (long long)taps_ * a.K))
+        return hipSuccess;
+    const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
+    const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
+    if (!k2 && !k3 && !kt3) return hipSuccess;
+    const int rt = taps_ / d.kw;
+    if ((double)(d.kt / 2 + 1) * d.D * d.H * d.W * a.K * 4.0 >= 2147483648.0) return hipSuccess;   // 32-bit tap offsets
+    const int kc = rt > 3 ? 16 : (a.K % 64 == 0 ? 64 : (a.K % 32 == 0 ? 32 : 16));   // channels per round
+    ConvThinOutArgs t{};
+    t.in = a.in; t.bias = a.bias; t.add = a.add; t.out = a.out;
+    t.K = a.K; t.KC = kc; t.relu_in = a.relu_in; t.relu_out = a.relu_out; t.d = d;
+    char name[56];
+    snprintf(name, sizeof(name), "conv_fwd_%dto%d_t%d", a.K, a.Nn, taps_);
+    KernelScope ks(name, 2.0 * (double)d.Q * a.K * a.Nn * taps_, (bf ? 2.0 : 4.0) * (double)d.Q * a.K + 8.0 * (double)d.Q, st);
+    if (k2) launch_conv_thin_out_t<1, 1, 3, 3>(t, cw.w, bf, st);
+    else if (k3) launch_conv_thin_out_t<1, 3, 3, 3>(t, cw.w, bf, st);
+    else launch_conv_thin_out_t<3, 1, 1, 1>(t, cw.w, bf, st);
+    *hit = true;
+    return hipGetLastError();
+}
+
 static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scratch, hipStream_t st) {
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
     {   // two input channels and a wide output: HBM-bound kernel without MFMA
         bool hit = false;
         const hipError_t e = launch_conv_thin_in(a, cw, false, &hit, st);
+        if (hit || e != hipSuccess) return e;
+    }
+    {   // two output channels and a wide input (forward): HBM-bound kernel without MFMA
+        bool hit = false;
+        const hipError_t e = launch_conv_thin_out(a, cw, false, &hit, st);
         if (hit || e != hipSuccess) return e;
     }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
@@ -1382,6 +1607,12 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
                 e = launch_conv_thin_in(a, cw, true, &hit, st);
                 if (e == hipSuccess && !hit) e = hipErrorInvalidValue;
             } else {                // bfloat16 in; the last layer writes the float32 image
+                if (l == L - 1) {
+                    bool hit = false;
+                    e = launch_conv_thin_out(a, cw, true, &hit, st);
+                    if (e != hipSuccess) return e;
+                    if (hit) continue;
+                }
                 ConvBf16Args b{};
                 b.in = reinterpret_cast<const unsigned short*>(a.in);
                 b.out = a.out;
