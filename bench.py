@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the GLEAM module step on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..4]
 
 One step = one gleam_module_fwd + one gleam_module_bwd (data-consistency step, prox forward, local loss,
-module-confined backward) on the knee-shaped 2D workload (640x368, 15 coils, batch 2, fp32, 64-channel
-two-resblock prox), all inputs resident in HBM before the timed region.  Prints ONE JSON line with the
-module steps/s, the roofline of the dominant kernel (HIP-event timed inside the library), the SENSE normal
-operator's bandwidth, and the CPU oracle timed on the host cores as a reported baseline.
+module-confined backward), all inputs resident in HBM before the timed region.  The default workload (1) is
+the knee-shaped 2D one (640x368, 15 coils, batch 2, fp32, 64-channel two-resblock prox); --workload picks
+another of the five synthetic configurations (0 tiny 2D, 2 brain-shaped bf16, 3 3D volume, 4 2D+t cine).
+Prints ONE JSON line with the module steps/s, the roofline of the dominant kernel (HIP-event timed inside
+the library), the SENSE normal operator's bandwidth, and the CPU oracle timed on the host cores as a
+reported baseline (default workload and the small ones only: the oracle needs minutes on the others).
 """
 import argparse
 import json
@@ -20,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 # HBM traffic per launch (bytes) from the two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per
@@ -48,6 +51,14 @@ def aggregate(records):
         a["flops"] += flops
         a["bytes"] += nbytes
     return agg
+
+
+def prox_text(prox):
+    ls = prox.layers
+    taps = sorted({f"{l.kt}x{l.kd}x{l.kh}x{l.kw}" for l in ls})
+    skips = sum(1 for l in ls if l.skip_src >= 0)
+    return (f"{len(ls)} convs, {max(l.cout for l in ls[:-1])} ch, kernels (t,d,h,w) {'/'.join(taps)}, "
+            f"{skips} skip adds, {'bf16 operands + fp32 accumulate' if prox.dtype == 1 else 'fp32'}")
 
 
 def cpu_baseline(case):
@@ -81,6 +92,8 @@ def main():
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain 256 MiB device copy (known size) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
+    ap.add_argument("--workload", type=int, default=1, choices=range(5),
+                    help="synthetic configuration: 0 tiny2d, 1 knee2d (default), 2 brain2d bf16, 3 vol3d, 4 cine2dt")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -98,7 +111,8 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-    case = synth.make_case(1)
+    case = synth.make_case(args.workload)
+    peak = PEAK_BF16_MFMA_TFLOPS if case.prox.dtype == 1 else PEAK_FP32_MFMA_TFLOPS
     g = case.geom
     r = ModuleRunner(case)
     sr = SenseRunner(g, case.x_in, case.S, case.M)
@@ -129,8 +143,8 @@ def main():
     d = by_kernel[dom]
     avg_ms = d["ms"] / d["launches"]
     achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
-    roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "avg_launch_ms": avg_ms,
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak,
+                "unit": "TFLOP/s", "frac": achieved / peak, "avg_launch_ms": avg_ms,
                 "launches_per_step": d["launches"] / args.steps, "traffic": MEASURED_TRAFFIC.get(dom)}
     conv_ms = sum(v["ms"] for v in mfma.values())
     conv_tflops = sum(v["flops"] for v in mfma.values()) / (conv_ms * 1e-3) / 1e12
@@ -161,17 +175,18 @@ def main():
 
     out = {"metric": "GLEAM module fwd+bwd steps/s", "value": args.steps / dt, "unit": "module steps/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-           "data": "synthetic",
-           "config": {"workload": case.name, "image": [g.H, g.W], "coils": g.C, "batch": g.B,
-                      "prox": "2 pre-activation resblocks, 64 ch, 3x3, 6 convs", "loss": "l2",
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if case.prox.dtype == 1 else "f32", "data": "synthetic",
+           "config": {"workload": case.name, "image": [d_ for d_ in (g.T, g.D, g.H, g.W) if d_ > 1],
+                      "fft_dims": g.ndim_fft, "coils": g.C, "batch": g.B, "prox": prox_text(case.prox),
+                      "loss": "l1" if case.prox.loss_kind == 1 else "l2",
                       "modules_per_greedy_iteration": case.n_modules},
            "roofline": roofline,
-           "conv_all": {"tflops": conv_tflops, "frac_of_fp32_mfma_peak": conv_tflops / PEAK_FP32_MFMA_TFLOPS,
+           "conv_all": {"tflops": conv_tflops, "frac_of_mfma_peak": conv_tflops / peak,
                         "ms_per_step": conv_ms / args.steps},
            "sense_normal": sense, "kernels": kernels,
            "greedy_iterations_per_s": args.steps / dt / case.n_modules}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload in (0, 1, 4):
         out["cpu_baseline"] = cpu_baseline(case)
     print(json.dumps(out))
 
