@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
     constexpr int TM = kConvTM, RS = CK + 4, G = CK / 8, NJ = NB / 32, PJ = 2, Q4 = CK / 4;
     constexpr int PS = ((TM + KWMAX - 1) * Q4 + kConvThreads - 1) / kConvThreads;   // slab quads per thread
     constexpr int PW = (KWMAX * CK * NB / 4 + kConvThreads - 1) / kConvThreads;     // weight float4 per thread
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const PixDims d = a.d;
     const int n_pix = TM + d.kw - 1;
     float* slab = smem;             // [n_pix][RS]
@@ -519,7 +519,7 @@ struct ConvThinInArgs {
 template <int KT, int KD, int KH, int KW, bool BF>
 __global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
     constexpr int RT = KT * KD * KH, TAPS = RT * KW, TH = 2;
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const ConvArgs& a = ta.c;
     const PixDims d = a.d;
     const int WS = d.W + KW - 1;
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(256) void conv_thin_out_kernel(ConvThinOutArgs a, c
     constexpr int PER_ROW = PXS * GPN, TOTAL = RT * PER_ROW, ITER = (TOTAL + 255) / 256;
     constexpr int NCH = KC / 16;
     static_assert(ITER <= 32, "validity bits of one staging round must fit a 32-bit mask");
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const PixDims d = a.d;
     float* slab = smem;                        // [RT][PXS][RS]
     float* red = smem + RT * PXS * RS;         // [4][64][2]
@@ -984,7 +984,7 @@ constexpr int kThinSplit = 1024;  // most partial sums the thin weight-gradient 
 
 template <int JT>
 __global__ __launch_bounds__(kConvThreads) void wgrad_mfma_kernel(WgradArgs a) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const PixDims d = a.d;
     const int RSg = (a.Co + 3) / 4 * 4 + 1, RSa = (a.Ci + 3) / 4 * 4 + 1;
     const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
@@ -1081,7 +1081,7 @@ struct WgradPipeArgs {
 template <int JT, int PG, int PA, int NW>
 __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     constexpr int NT = NW * 64;
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const WgradArgs& a = pa.w;
     const PixDims d = a.d;
     const int Co4 = a.Co / 4, Ci4 = a.Ci / 4;
@@ -1286,7 +1286,7 @@ template <int KT, int KD, int KH, int KW, int TH, bool THIN_IN, bool BF>
 __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
     constexpr int RT = KT * KD * KH, TAPS = RT * KW;
     constexpr int sgn = THIN_IN ? 1 : -1;
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const PixDims d = a.d;
     const int WS = d.W + KW - 1;            // slab columns: image columns -KW/2 .. W-1+KW/2
     float* slab = smem;                     // [RT][WS][TH]

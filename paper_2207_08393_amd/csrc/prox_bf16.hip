@@ -300,25 +300,44 @@ hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long 
 
 // ------------------------------------------------------------------ weight gradient
 constexpr int kBwTM = 32;     // pixels per staged chunk = two MFMA K-blocks of 16
-constexpr int kBwRow = 48;    // LDS row length in pixels (32 + up to 4 halo, padded so rows stay 16-byte aligned)
+constexpr int kBwSlab = 36;   // slab rows per row tap: 32 + 2 halo, rounded up to the 12-pixel read windows
+constexpr size_t kBwLdsMax = 150 * 1024;
+
+// LDS rows are pixels, [pixel][channels rounded up to 32, + 16]: the 32-byte pad puts the four pixel rows
+// a 16-lane group touches in one transposing read into different banks.
+__host__ __device__ inline int bw_row(int ch) { return (ch + 31) / 32 * 32 + 16; }
 
 size_t wgrad_bf16_lds_bytes(int Co, int Ci, int kt, int kd, int kh, int kw) {
     const int rowtaps = kt * kd * kh, taps = rowtaps * kw;
-    return ((size_t)Co * kBwRow + (size_t)rowtaps * Ci * kBwRow + (size_t)taps * kBwTM) * sizeof(unsigned short) + 16;
+    const size_t buf = ((size_t)kBwTM * bw_row(Co) + (size_t)rowtaps * kBwSlab * bw_row(Ci) + (size_t)taps * kBwTM + 7) / 8 * 8;
+    const size_t two = 2 * buf * sizeof(unsigned short);
+    return two <= kBwLdsMax ? two : two / 2;   // double-buffered when it fits
+}
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+// gfx950 LDS transposing read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s passes the
+// address of 4 consecutive 16-bit values of row s/4, columns 4*(s%4)..+3 of a 4 x 16 block; lane j gets
+// column j of the block, rows 0..3.  (Checked with an index pattern on the device.)
+__device__ __forceinline__ uint2 lds_read_tr16(const unsigned short* p) {
+    const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(p));
+    return __builtin_bit_cast(uint2, v);
 }
 
 // Each wave owns one (32 cout x 32 cin) block and JT consecutive taps starting at a multiple of KW.
-template <int JT, int KW, int NW>
+// PG / PA: 16-byte staging slots per thread for the gradient chunk and the input slab.
+template <int JT, int KW, int NW, int PG, int PA>
 __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
     constexpr int NT = NW * 64;
-    extern __shared__ unsigned short smem16[];
+    extern __shared__ __attribute__((aligned(16))) unsigned short smem16[];
     const PixDims d = a.d;
     const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * KW;
     const int n_pa = kBwTM + KW - 1;
-    unsigned short* gsT = smem16;                               // [Co][kBwRow]      pixel p at column p
-    unsigned short* asT = gsT + a.Co * kBwRow;                  // [rowtaps][Ci][kBwRow]  slab pixel pp at column pp
-    unsigned short* vmT = asT + rowtaps * a.Ci * kBwRow;        // [taps][kBwTM] 0xffff where (pixel, tap) is inside the grid
-    __shared__ int all_valid;
+    const int CoP = bw_row(a.Co), CiP = bw_row(a.Ci);
+    // two staging buffers, each: gs [kBwTM][CoP] (chunk pixel p, channel c), as [rowtaps][kBwSlab][CiP]
+    // (slab pixel pp = p + dw, channel c), vm [taps][kBwTM] (0xffff where (pixel, tap) is inside the grid)
+    const int as_off = kBwTM * CoP, vm_off = as_off + rowtaps * kBwSlab * CiP;
+    const int buf_elems = (vm_off + taps * kBwTM + 7) / 8 * 8;
+    __shared__ int all_valid[2];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 31, h = lane >> 5;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
@@ -330,7 +349,28 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
     const int tap0 = tg * JT;                                   // multiple of KW by construction (JT % KW == 0)
     const int Co8 = a.Co / 8, Ci8 = a.Ci / 8;
     const int n_g8 = kBwTM * Co8, n_a8 = rowtaps * n_pa * Ci8;
-    constexpr int PG = 2, PA = 8;                               // 16-byte staging slots per thread (upper bounds)
+
+    // Staging slots, the same for every chunk: slot i moves 16 bytes (8 channels of one pixel) from pixel
+    // q0 + dq[i], channel col[i], to LDS offset lds[i].  Unused slots have lds < 0.
+    int g_dq[PG], g_col[PG], g_lds[PG];
+    int a_dq[PA], a_col[PA], a_lds[PA];
+#pragma unroll
+    for (int i = 0; i < PG; ++i) {
+        const int v = tid + i * NT;
+        const int p = v / Co8, c8 = v % Co8;
+        g_dq[i] = p;
+        g_col[i] = 8 * c8;
+        g_lds[i] = v < n_g8 ? p * CoP + 8 * c8 : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+        const int v = tid + i * NT;
+        const int rt = v / (n_pa * Ci8), r = v % (n_pa * Ci8);
+        const int p = r / Ci8, c8 = r % Ci8;
+        a_dq[i] = v < n_a8 ? (int)rowtap_offset(rt, d) - KW / 2 + p : 0;
+        a_col[i] = 8 * c8;
+        a_lds[i] = v < n_a8 ? (rt * kBwSlab + p) * CiP + 8 * c8 : -1;
+    }
 
     uint4 rg[PG], ra[PA];
     float bsum[PG][8];
@@ -346,65 +386,59 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
         a_ok = 0u;
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
-            const int v = tid + i * NT;
-            const int p = v / Co8, c8 = v % Co8;
-            const long long qq = q0 + p;
-            const bool ok = v < n_g8 && qq < d.Q;
-            rg[i] = *reinterpret_cast<const uint4*>(a.g + (ok ? qq * a.Co + 8 * c8 : 0));
+            const long long qq = q0 + g_dq[i];
+            const bool ok = g_lds[i] >= 0 && qq < d.Q;
+            rg[i] = *reinterpret_cast<const uint4*>(a.g + (ok ? qq * a.Co + g_col[i] : 0));
             g_ok |= (ok ? 1u : 0u) << i;
         }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            const int v = tid + i * NT;
-            const int rt = v / (n_pa * Ci8), r = v % (n_pa * Ci8);
-            const int p = r / Ci8, c8 = r % Ci8;
-            const long long qq = q0 + (v < n_a8 ? rowtap_offset(rt, d) : 0) - KW / 2 + p;
-            const bool ok = v < n_a8 && qq >= 0 && qq < d.Q;
-            ra[i] = *reinterpret_cast<const uint4*>(a.a + (ok ? qq * a.Ci + 8 * c8 : 0));
+            const long long qq = q0 + a_dq[i];
+            const bool ok = a_lds[i] >= 0 && qq >= 0 && qq < d.Q;
+            ra[i] = *reinterpret_cast<const uint4*>(a.a + (ok ? qq * a.Ci + a_col[i] : 0));
             a_ok |= (ok ? 1u : 0u) << i;
         }
     };
-    auto stash = [&](long long q0) {
+    // pixel coordinates of this thread's validity pixel (threads below kBwTM), advanced chunk by chunk
+    PixCoord vc{0, 0, 0, 0}, vstep{0, 0, 0, 0};
+    auto stash = [&](long long q0, int buf) {
+        unsigned short* gsT = smem16 + buf * buf_elems;
+        unsigned short* asT = gsT + as_off;
+        unsigned short* vmT = gsT + vm_off;
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
-            const int v = tid + i * NT;
-            if (v < n_g8) {
-                const int p = v / Co8, c8 = v % Co8;
+            if (g_lds[i] >= 0) {
                 const unsigned mk = ((g_ok >> i) & 1u) ? 0xffffffffu : 0u;
                 const unsigned w4[4] = {rg[i].x & mk, rg[i].y & mk, rg[i].z & mk, rg[i].w & mk};
+                *reinterpret_cast<uint4*>(gsT + g_lds[i]) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+                if (a.bias_partial != nullptr) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const unsigned short hv = (unsigned short)(w4[e >> 1] >> (16 * (e & 1)));
-                    gsT[(8 * c8 + e) * kBwRow + p] = hv;
-                    bsum[i][e] += bf16_to_f32(hv);
+                    for (int e = 0; e < 8; ++e)
+                        bsum[i][e] += (e & 1) ? __uint_as_float(w4[e >> 1] & 0xffff0000u) : __uint_as_float(w4[e >> 1] << 16);
                 }
             }
         }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            const int v = tid + i * NT;
-            if (v < n_a8) {
-                const int rt = v / (n_pa * Ci8), r = v % (n_pa * Ci8);
-                const int p = r / Ci8, c8 = r % Ci8;
+            if (a_lds[i] >= 0) {
                 const unsigned mk = ((a_ok >> i) & 1u) ? 0xffffffffu : 0u;
                 unsigned w4[4] = {ra[i].x & mk, ra[i].y & mk, ra[i].z & mk, ra[i].w & mk};
                 if (a.relu_in) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) w4[e] = relu_bf16x2(w4[e]);
                 }
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    asT[(rt * a.Ci + 8 * c8 + e) * kBwRow + p] = (unsigned short)(w4[e >> 1] >> (16 * (e & 1)));
+                *reinterpret_cast<uint4*>(asT + a_lds[i]) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
             }
         }
         if (tid < kBwTM) {
-            const unsigned vb = tap_validity(q0 + tid, d);
+            const unsigned vb = q0 + tid < d.Q ? tap_validity_at(vc, d) : 0u;
+            pix_advance(vc, vstep, d);
             for (int t = 0; t < taps; ++t) vmT[t * kBwTM + tid] = ((vb >> t) & 1u) ? 0xffffu : 0u;
             const unsigned full = taps >= 32 ? 0xffffffffu : ((1u << taps) - 1u);
             const bool okall = vb == full;
             // wave 0 holds threads 0..63 >= kBwTM: ballot over the first 32 lanes
             const unsigned long long bal = __ballot(okall);
-            if (tid == 0) all_valid = (bal & 0xffffffffull) == 0xffffffffull;
+            if (tid == 0) all_valid[buf] = (bal & 0xffffffffull) == 0xffffffffull;
         }
     };
 
@@ -414,36 +448,42 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
-    const int co = cb * 32 + m, ci = ib * 32 + m;
-    const int co_c = co < a.Co ? co : a.Co - 1, ci_c = ci < a.Ci ? ci : a.Ci - 1;
+    const int ci = ib * 32 + m;
     const int rt0 = tap0 / KW;
+    // per-lane offsets of the transposing reads: row s/4 and columns 16*(group%2) + 4*(s%4) inside the
+    // wave's 32-channel block, pixels 8h.. of the K-block (group = lane/16, s = lane%16, h = group/2)
+    const int tr_row = 8 * h + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int g_rd = tr_row * CoP + cb * 32 + tr_col;
+    const int a_rd = as_off + tr_row * CiP + ib * 32 + tr_col;
 
+    // Pipeline over this workgroup's chunks c0, c1, ...: while the MFMAs of chunk i read LDS buffer i%2,
+    // chunk i+1 (fetched one step earlier) is written to the other buffer and chunk i+2 is requested from
+    // HBM; one barrier per chunk.  Layers whose two buffers do not fit LDS use one buffer and two barriers.
     const long long n_chunks = (d.Q + kBwTM - 1) / kBwTM;
     const XcdRange xr = xcd_range(n_chunks);
     long long chunk = xr.first;
-    if (chunk < xr.end) {
-        fetch(chunk * kBwTM);
-        stash(chunk * kBwTM);
+    if (tid < kBwTM) {
+        vc = pix_coord((chunk < xr.end ? chunk : 0) * kBwTM + tid, d);
+        vstep = pix_coord(xr.stride * kBwTM, d);
     }
-    __syncthreads();
-    for (; chunk < xr.end; chunk += xr.stride) {
-        const long long next = chunk + xr.stride;
-        if (next < xr.end) fetch(next * kBwTM);
+    auto compute = [&](int buf) {
         if (active) {
-            const bool fast = all_valid != 0;
+            const unsigned short* base = smem16 + buf * buf_elems;
+            const bool fast = all_valid[buf] != 0;
 #pragma unroll
             for (int kb = 0; kb < kBwTM / 16; ++kb) {
                 const int px = 16 * kb + 8 * h;   // this lane's first pixel of the K-block
-                const uint4 ga = *reinterpret_cast<const uint4*>(gsT + co_c * kBwRow + px);
-                const bf16x8 gv = __builtin_bit_cast(bf16x8, ga);
+                const uint2 g0 = lds_read_tr16(base + g_rd + (16 * kb) * CoP), g1 = lds_read_tr16(base + g_rd + (16 * kb + 4) * CoP);
+                const bf16x8 gv = __builtin_bit_cast(bf16x8, make_uint4(g0.x, g0.y, g1.x, g1.y));
 #pragma unroll
                 for (int jr = 0; jr < JT / KW; ++jr) {
                     const int rt = rt0 + jr < rowtaps ? rt0 + jr : rowtaps - 1;
-                    const unsigned short* row = asT + (rt * a.Ci + ci_c) * kBwRow + px;
-                    // window of slab pixels px .. px+9 as five 32-bit words (+ one more for KW = 5)
-                    const uint4 lo = *reinterpret_cast<const uint4*>(row);
-                    const uint2 hi = *reinterpret_cast<const uint2*>(row + 8);
-                    const unsigned dws[6] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y};
+                    // window of slab pixels px .. px+11 of this lane's input channel as six 32-bit words
+                    const unsigned short* row = base + a_rd + (rt * kBwSlab + 16 * kb) * CiP;
+                    const uint2 w0 = lds_read_tr16(row), w1 = lds_read_tr16(row + 4 * CiP);
+                    uint2 w2 = make_uint2(0u, 0u);
+                    if (KW > 1) w2 = lds_read_tr16(row + 8 * CiP);
+                    const unsigned dws[6] = {w0.x, w0.y, w1.x, w1.y, w2.x, w2.y};
 #pragma unroll
                     for (int dw = 0; dw < KW; ++dw) {
                         const int j = jr * KW + dw;
@@ -458,7 +498,7 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
                         }
                         if (!fast) {
                             const int tap = tap0 + j < taps ? tap0 + j : taps - 1;
-                            const uint4 mk = *reinterpret_cast<const uint4*>(vmT + tap * kBwTM + px);
+                            const uint4 mk = *reinterpret_cast<const uint4*>(base + vm_off + tap * kBwTM + px);
                             b.x &= mk.x; b.y &= mk.y; b.z &= mk.z; b.w &= mk.w;
                         }
                         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b), acc[j], 0, 0, 0);
@@ -466,9 +506,37 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
                 }
             }
         }
+    };
+    if (a.two_buf) {
+        if (chunk < xr.end) {
+            fetch(chunk * kBwTM);
+            stash(chunk * kBwTM, 0);
+            if (chunk + xr.stride < xr.end) fetch((chunk + xr.stride) * kBwTM);
+        }
         __syncthreads();
-        if (next < xr.end) stash(next * kBwTM);
+        int buf = 0;
+        for (; chunk < xr.end; chunk += xr.stride) {
+            const long long next = chunk + xr.stride, next2 = next + xr.stride;
+            if (next < xr.end) stash(next * kBwTM, buf ^ 1);
+            if (next2 < xr.end) fetch(next2 * kBwTM);
+            compute(buf);
+            __syncthreads();
+            buf ^= 1;
+        }
+    } else {   // one buffer (large layers): write the next chunk between two barriers
+        if (chunk < xr.end) {
+            fetch(chunk * kBwTM);
+            stash(chunk * kBwTM, 0);
+        }
         __syncthreads();
+        for (; chunk < xr.end; chunk += xr.stride) {
+            const long long next = chunk + xr.stride;
+            if (next < xr.end) fetch(next * kBwTM);
+            compute(0);
+            __syncthreads();
+            if (next < xr.end) stash(next * kBwTM, 0);
+            __syncthreads();
+        }
     }
     if (active) {
         float* dst = a.partial + (size_t)blockIdx.x * a.Co * taps * a.Ci;
@@ -500,39 +568,49 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
     }
 }
 
-template <int JT, int KW, int NW>
+template <int JT, int KW, int NW, int PG, int PA>
 static void launch_wgrad_bf16_k(const WgradBf16Args& a, dim3 grid, size_t lds, hipStream_t st) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)wgrad_bf16_kernel<JT, KW, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        (void)hipFuncSetAttribute((const void*)wgrad_bf16_kernel<JT, KW, NW, PG, PA>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         once = true;
     }
-    hipLaunchKernelGGL((wgrad_bf16_kernel<JT, KW, NW>), grid, dim3(NW * 64), lds, st, a);
+    hipLaunchKernelGGL((wgrad_bf16_kernel<JT, KW, NW, PG, PA>), grid, dim3(NW * 64), lds, st, a);
 }
 
 // Supported: Co, Ci multiples of 8 (16-byte rows), kw in {1, 3}; the caller checks and falls back otherwise.
-hipError_t launch_wgrad_bf16(const WgradBf16Args& a, int n_split, hipStream_t stream) {
-    const PixDims& d = a.d;
+hipError_t launch_wgrad_bf16(const WgradBf16Args& a_in, int n_split, hipStream_t stream) {
+    WgradBf16Args a = a_in;
+    const PixDims& d = a_in.d;
     const int rowtaps = d.kt * d.kd * d.kh, taps = rowtaps * d.kw;
     char name[56];
     snprintf(name, sizeof(name), "conv_bf16_wgrad_%dto%d_t%d", a.Ci, a.Co, taps);
     KernelScope ks(name, 2.0 * (double)d.Q * a.Ci * a.Co * taps, 2.0 * (double)d.Q * (a.Ci + a.Co), stream);
     constexpr int NW = 8, NT = NW * 64;
     size_t lds = wgrad_bf16_lds_bytes(a.Co, a.Ci, d.kt, d.kd, d.kh, d.kw);
+    {
+        const size_t one = ((size_t)kBwTM * bw_row(a.Co) + (size_t)(d.kt * d.kd * d.kh) * kBwSlab * bw_row(a.Ci) +
+                            (size_t)(d.kt * d.kd * d.kh * d.kw) * kBwTM + 7) / 8 * 8 * sizeof(unsigned short);
+        a.two_buf = 2 * one <= kBwLdsMax ? 1 : 0;
+    }
     const size_t red = (size_t)2 * NT * 8 * sizeof(float);
     if (lds < red) lds = red;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
     const int n_pa = kBwTM + d.kw - 1;
     // staging slots per thread must fit the compile-time bounds (2 for g, 8 for a)
     if (kBwTM * (a.Co / 8) > 2 * NT || rowtaps * n_pa * (a.Ci / 8) > 8 * NT || lds > 150 * 1024) return hipErrorInvalidValue;
+    // few staging slots (channel counts up to 128 with 3 row taps) keep the kernel free of register spills
+    const bool small = kBwTM * (a.Co / 8) <= NT && rowtaps * n_pa * (a.Ci / 8) <= 4 * NT;
     if (d.kw == 3) {
         const int jt = 9, tapgroups = (taps + jt - 1) / jt;
         dim3 grid(n_split, (ncb * nib * tapgroups + NW - 1) / NW);
-        launch_wgrad_bf16_k<9, 3, NW>(a, grid, lds, stream);
+        if (small) launch_wgrad_bf16_k<9, 3, NW, 1, 4>(a, grid, lds, stream);
+        else launch_wgrad_bf16_k<9, 3, NW, 2, 8>(a, grid, lds, stream);
     } else if (d.kw == 1) {
         const int jt = 3, tapgroups = (taps + jt - 1) / jt;
         dim3 grid(n_split, (ncb * nib * tapgroups + NW - 1) / NW);
-        launch_wgrad_bf16_k<3, 1, NW>(a, grid, lds, stream);
+        if (small) launch_wgrad_bf16_k<3, 1, NW, 1, 4>(a, grid, lds, stream);
+        else launch_wgrad_bf16_k<3, 1, NW, 2, 8>(a, grid, lds, stream);
     } else {
         return hipErrorInvalidValue;
     }

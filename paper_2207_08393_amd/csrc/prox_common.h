@@ -42,6 +42,52 @@ __device__ __forceinline__ unsigned tap_validity(long long q, const PixDims& d) 
     return bits;
 }
 
+// The same bits for a pixel tracked by its coordinates, for kernels that walk the pixel index in equal
+// steps and cannot afford the divisions of tap_validity per step.
+struct PixCoord {
+    int w, h, dd, t;
+};
+__device__ __forceinline__ PixCoord pix_coord(long long q, const PixDims& d) {
+    PixCoord c;
+    c.w = (int)(q % d.W);
+    long long r = q / d.W;
+    c.h = (int)(r % d.H);
+    r /= d.H;
+    c.dd = (int)(r % d.D);
+    r /= d.D;
+    c.t = (int)(r % d.T);
+    return c;
+}
+// c += step, where step holds the coordinates of the step length (pix_coord(step_pixels)).
+__device__ __forceinline__ void pix_advance(PixCoord& c, const PixCoord& step, const PixDims& d) {
+    c.w += step.w;
+    int carry = c.w >= d.W ? 1 : 0;
+    c.w -= carry ? d.W : 0;
+    c.h += step.h + carry;
+    carry = c.h >= d.H ? 1 : 0;
+    c.h -= carry ? d.H : 0;
+    c.dd += step.dd + carry;
+    carry = c.dd >= d.D ? 1 : 0;
+    c.dd -= carry ? d.D : 0;
+    c.t += step.t + carry;
+    c.t -= c.t >= d.T ? d.T : 0;
+}
+__device__ __forceinline__ unsigned tap_validity_at(const PixCoord& c, const PixDims& d) {
+    unsigned bits = 0u;
+    int tap = 0;
+    for (int it = 0; it < d.kt; ++it)
+        for (int id = 0; id < d.kd; ++id)
+            for (int ih = 0; ih < d.kh; ++ih)
+                for (int iw = 0; iw < d.kw; ++iw, ++tap) {
+                    const int tt = c.t + it - d.kt / 2, d2 = c.dd + id - d.kd / 2;
+                    const int hh = c.h + ih - d.kh / 2, ww = c.w + iw - d.kw / 2;
+                    const bool ok = (unsigned)tt < (unsigned)d.T && (unsigned)d2 < (unsigned)d.D && (unsigned)hh < (unsigned)d.H &&
+                                    (unsigned)ww < (unsigned)d.W;
+                    bits |= (ok ? 1u : 0u) << tap;
+                }
+    return bits;
+}
+
 // Flattened pixel offset of row-tap rt = (it, id, ih), before the kw taps along W.
 __device__ __forceinline__ long long rowtap_offset(int rt, const PixDims& d) {
     const int ih = rt % d.kh, id = (rt / d.kh) % d.kd, it = rt / (d.kh * d.kd);
@@ -92,6 +138,7 @@ struct WgradBf16Args {
     float* partial;        // [gridDim.x][Co][taps][Ci]
     float* bias_partial;   // [gridDim.x][Co] or null
     int Co, Ci, relu_in;
+    int two_buf;           // set by the launcher: LDS holds two staging buffers
     PixDims d;
 };
 hipError_t launch_wgrad_bf16(const WgradBf16Args& a, int n_split, hipStream_t stream);
