@@ -405,41 +405,89 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
         {
             const float* wl = slab + slab_ops * 256 + wa_lane;
             const int rt = c / n_kc;
+            if constexpr (KW > 0) {
+                // Operands of unit u + 1 (one tap along W x 8 input channels) are read from LDS before the
+                // MFMAs of unit u are issued, and consecutive MFMAs alternate between accumulators.
+                constexpr int U = KW * G;
+                float4 pb[2][PJ], wa[2][NJ];
+                auto load_unit = [&](int u, int slot) {
+                    const int dw = u / G, g = u % G;
 #pragma unroll
-            for (int dw = 0; dw < KWM; ++dw) {
-                if (KW == 0 && dw >= kw) continue;
-                unsigned okm[PJ];
-#pragma unroll
-                for (int pj = 0; pj < PJ; ++pj) okm[pj] = ((vbits[pj] >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float4 pb[PJ], wa[NJ];
-#pragma unroll
-                    for (int pj = 0; pj < PJ; ++pj) {
-                        pb[pj] = *reinterpret_cast<const float4*>(slab + p_off[pj][dw][g]);
-                        if (a.relu_in) {
-                            pb[pj].x = fmaxf(pb[pj].x, 0.f); pb[pj].y = fmaxf(pb[pj].y, 0.f);
-                            pb[pj].z = fmaxf(pb[pj].z, 0.f); pb[pj].w = fmaxf(pb[pj].w, 0.f);
-                        }
-                        pb[pj].x = __uint_as_float(__float_as_uint(pb[pj].x) & okm[pj]);  // zero padding
-                        pb[pj].y = __uint_as_float(__float_as_uint(pb[pj].y) & okm[pj]);
-                        pb[pj].z = __uint_as_float(__float_as_uint(pb[pj].z) & okm[pj]);
-                        pb[pj].w = __uint_as_float(__float_as_uint(pb[pj].w) & okm[pj]);
-                    }
+                    for (int pj = 0; pj < PJ; ++pj) pb[slot][pj] = *reinterpret_cast<const float4*>(slab + p_off[pj][dw][g]);
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
-                        wa[j] = *reinterpret_cast<const float4*>(wl + ((dw * G + g) * 2 * NB + 32 * j) * 4);
+                        wa[slot][j] = *reinterpret_cast<const float4*>(wl + ((dw * G + g) * 2 * NB + 32 * j) * 4);
+                };
+                load_unit(0, 0);
 #pragma unroll
-                    for (int pj = 0; pj < PJ; ++pj)
+                for (int u = 0; u < U; ++u) {
+                    const int cur = u & 1, dw = u / G;
+                    if (u + 1 < U) load_unit(u + 1, cur ^ 1);
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) {
-                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].x, pb[pj].x, acc[pj][j], 0, 0, 0);
-                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].y, pb[pj].y, acc[pj][j], 0, 0, 0);
-                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].z, pb[pj].z, acc[pj][j], 0, 0, 0);
-                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].w, pb[pj].w, acc[pj][j], 0, 0, 0);
+                    for (int pj = 0; pj < PJ; ++pj) {
+                        const unsigned okm = ((vbits[pj] >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
+                        float4& v = pb[cur][pj];
+                        if (a.relu_in) {
+                            v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
                         }
+                        v.x = __uint_as_float(__float_as_uint(v.x) & okm);  // zero padding
+                        v.y = __uint_as_float(__float_as_uint(v.y) & okm);
+                        v.z = __uint_as_float(__float_as_uint(v.z) & okm);
+                        v.w = __uint_as_float(__float_as_uint(v.w) & okm);
+                    }
+#pragma unroll
+                    for (int pj = 0; pj < PJ; ++pj) {
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[cur][j].x, pb[cur][pj].x, acc[pj][j], 0, 0, 0);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[cur][j].y, pb[cur][pj].y, acc[pj][j], 0, 0, 0);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[cur][j].z, pb[cur][pj].z, acc[pj][j], 0, 0, 0);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[cur][j].w, pb[cur][pj].w, acc[pj][j], 0, 0, 0);
+                    }
                 }
-            }
+            } else {
+#pragma unroll
+                for (int dw = 0; dw < KWM; ++dw) {
+                    if (KW == 0 && dw >= kw) continue;
+                    unsigned okm[PJ];
+    #pragma unroll
+                    for (int pj = 0; pj < PJ; ++pj) okm[pj] = ((vbits[pj] >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
+    #pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        float4 pb[PJ], wa[NJ];
+    #pragma unroll
+                        for (int pj = 0; pj < PJ; ++pj) {
+                            pb[pj] = *reinterpret_cast<const float4*>(slab + p_off[pj][dw][g]);
+                            if (a.relu_in) {
+                                pb[pj].x = fmaxf(pb[pj].x, 0.f); pb[pj].y = fmaxf(pb[pj].y, 0.f);
+                                pb[pj].z = fmaxf(pb[pj].z, 0.f); pb[pj].w = fmaxf(pb[pj].w, 0.f);
+                            }
+                            pb[pj].x = __uint_as_float(__float_as_uint(pb[pj].x) & okm[pj]);  // zero padding
+                            pb[pj].y = __uint_as_float(__float_as_uint(pb[pj].y) & okm[pj]);
+                            pb[pj].z = __uint_as_float(__float_as_uint(pb[pj].z) & okm[pj]);
+                            pb[pj].w = __uint_as_float(__float_as_uint(pb[pj].w) & okm[pj]);
+                        }
+    #pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            wa[j] = *reinterpret_cast<const float4*>(wl + ((dw * G + g) * 2 * NB + 32 * j) * 4);
+    #pragma unroll
+                        for (int pj = 0; pj < PJ; ++pj)
+    #pragma unroll
+                            for (int j = 0; j < NJ; ++j) {
+                                acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].x, pb[pj].x, acc[pj][j], 0, 0, 0);
+                                acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].y, pb[pj].y, acc[pj][j], 0, 0, 0);
+                                acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].z, pb[pj].z, acc[pj][j], 0, 0, 0);
+                                acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[j].w, pb[pj].w, acc[pj][j], 0, 0, 0);
+                            }
+                    }
+                }
+}
             if (last) {
 #pragma unroll
                 for (int pj = 0; pj < PJ; ++pj) {

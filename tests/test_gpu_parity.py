@@ -190,6 +190,8 @@ def bf16_cases():
     yield "chain128_l1", synth.Geom(2, 1, 2, 1, 1, 20, 24), synth.chain_prox([2, 128, 128, 128, 2], [K2] * 4, dtype=1), 1
     yield "vol32", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3, dtype=1), 0
     yield "cine64", synth.Geom(2, 1, 2, 6, 1, 12, 16), synth.chain_prox([2, 64, 64, 64, 2], [KS, KT, KS, KT], dtype=1), 0
+    # 96 channels x 27 taps: the weight gradient's two staging buffers exceed LDS, so it runs single-buffered
+    yield "vol96_one_buffer", synth.Geom(3, 1, 2, 1, 6, 8, 12), synth.chain_prox([2, 96, 96, 2], [K3] * 3, dtype=1), 0
 
 
 @pytest.mark.parametrize("name,geom,prox,loss_kind", list(bf16_cases()), ids=[m[0] for m in bf16_cases()])
