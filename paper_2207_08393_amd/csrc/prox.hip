@@ -1138,7 +1138,6 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     const int n_pa = kWgTM + d.kw - 1;
     float* gs = smem;                          // [kWgTM][RSg]
     float* as = gs + kWgTM * RSg;              // [rowtaps][n_pa][RSa]
-    unsigned* vmask = reinterpret_cast<unsigned*>(as + rowtaps * n_pa * RSa);  // [kWgTM]
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, m = lane & 31, h = lane >> 5;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32, tapgroups = (taps + JT - 1) / JT;
@@ -1151,7 +1150,8 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
 
     // Per-thread staging descriptors: the float4 slots this thread moves are the same for every chunk.
     int g_lds[PG], g_dq[PG], g_c[PG];
-    int a_lds[PA], a_dq[PA], a_c[PA];
+    int a_lds[PA], a_dq[PA], a_c[PA], a_px[PA];
+    unsigned a_rt[PA];
 #pragma unroll
     for (int i = 0; i < PG; ++i) {
         const int v = tid + i * NT;
@@ -1168,6 +1168,8 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
         a_lds[i] = v < n_a4 ? (rt * n_pa + p) * RSa + 4 * c4 : -1;
         a_dq[i] = v < n_a4 ? (int)rowtap_offset(rt, d) - d.kw / 2 + p : 0;
         a_c[i] = 4 * c4;
+        a_px[i] = p - d.kw / 2;
+        a_rt[i] = v < n_a4 ? 1u << rt : 0u;
     }
     float4 rg[PG], ra[PA], bsum[PG];
 #pragma unroll
@@ -1176,25 +1178,47 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     // Prefetch loads are unconditional (clamped addresses); validity and ReLU are applied at the LDS
     // store, so nothing between the loads waits on memory.
     unsigned g_okb = 0u, a_okb = 0u;
-    auto fetch = [&](long long q0) {
+    // A chunk is a 32-pixel segment of one image row (the last segment of a row may be ragged).  Pixels
+    // past the end of the row get g = 0, and slab entries outside the grid (row taps above / below the
+    // image, the halo columns left / right of it) are stored as 0, so the MFMA loop needs no masks.
+    const int segs = (d.W + kWgTM - 1) / kWgTM;
+    auto fetch = [&](long long chunk) {
+        const long long row = chunk / segs;
+        const int w0 = (int)(chunk % segs) * kWgTM;
+        long long r = row;
+        const int hh = (int)(r % d.H);
+        r /= d.H;
+        const int dd = (int)(r % d.D);
+        r /= d.D;
+        const int tt = (int)(r % d.T);
+        unsigned rows_ok = 0u;
+        {
+            int rt = 0;
+            for (int it = 0; it < d.kt; ++it)
+                for (int id = 0; id < d.kd; ++id)
+                    for (int ih = 0; ih < d.kh; ++ih, ++rt) {
+                        const bool v = (unsigned)(tt + it - d.kt / 2) < (unsigned)d.T && (unsigned)(dd + id - d.kd / 2) < (unsigned)d.D &&
+                                       (unsigned)(hh + ih - d.kh / 2) < (unsigned)d.H;
+                        rows_ok |= (v ? 1u : 0u) << rt;
+                    }
+        }
+        const long long q0 = row * d.W + w0;
         g_okb = 0u;
         a_okb = 0u;
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
-            const long long qq = q0 + g_dq[i];
-            const bool ok = g_lds[i] >= 0 && qq < d.Q;
-            rg[i] = *reinterpret_cast<const float4*>(a.g + (ok ? qq * a.Co + g_c[i] : 0));
+            const bool ok = g_lds[i] >= 0 && w0 + g_dq[i] < d.W;
+            rg[i] = *reinterpret_cast<const float4*>(a.g + (ok ? (q0 + g_dq[i]) * a.Co + g_c[i] : 0));
             g_okb |= (ok ? 1u : 0u) << i;
         }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            const long long qq = q0 + a_dq[i];
-            const bool ok = a_lds[i] >= 0 && qq >= 0 && qq < d.Q;
-            ra[i] = *reinterpret_cast<const float4*>(a.a + (ok ? qq * a.Ci + a_c[i] : 0));
+            const bool ok = (rows_ok & a_rt[i]) != 0u && (unsigned)(w0 + a_px[i]) < (unsigned)d.W;
+            ra[i] = *reinterpret_cast<const float4*>(a.a + (ok ? (q0 + a_dq[i]) * a.Ci + a_c[i] : 0));
             a_okb |= (ok ? 1u : 0u) << i;
         }
     };
-    auto stash = [&](long long q0) {
+    auto stash = [&]() {
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
             const unsigned mk = ((g_okb >> i) & 1u) ? 0xffffffffu : 0u;
@@ -1215,7 +1239,6 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
             }
             if (a_lds[i] >= 0) *reinterpret_cast<float4*>(as + a_lds[i]) = v;
         }
-        if (tid < kWgTM) vmask[tid] = tap_validity(q0 + tid, d);
     };
 
     floatx16 acc[JT];
@@ -1230,32 +1253,29 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     const int co = cb * 32 + m, ci = ib * 32 + m;
     const int co_c = co < a.Co ? co : a.Co - 1, ci_c = ci < a.Ci ? ci : a.Ci - 1;
     int b_off[JT];
-    unsigned b_bit[JT];
 #pragma unroll
     for (int j = 0; j < JT; ++j) {
         const int tap = tap0 + j < taps ? tap0 + j : taps - 1;
         const int rt = tap / d.kw, dw = tap % d.kw;
         b_off[j] = (rt * n_pa + dw + h) * RSa + ci_c;
-        b_bit[j] = 1u << tap;
     }
     const int a_off = h * RSg + co_c;
 
-    const long long n_chunks = (d.Q + kWgTM - 1) / kWgTM;
+    const long long n_chunks = (d.Q / d.W) * segs;
     const XcdRange xr = xcd_range(n_chunks);
     long long chunk = xr.first;
     if (chunk < xr.end) {
-        fetch(chunk * kWgTM);
-        stash(chunk * kWgTM);
+        fetch(chunk);
+        stash();
     }
     __syncthreads();
     for (; chunk < xr.end; chunk += xr.stride) {
         const long long next = chunk + xr.stride;
-        if (next < xr.end) fetch(next * kWgTM);
+        if (next < xr.end) fetch(next);
         if (active) {
             // software pipeline over the 2-pixel K-steps: operands of step s+1 are read from LDS
             // before the MFMAs of step s are issued
             float av = gs[a_off];
-            unsigned vm = vmask[h];
             float bv[JT];
 #pragma unroll
             for (int j = 0; j < JT; ++j) bv[j] = as[b_off[j]];
@@ -1263,23 +1283,18 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
             for (int s = 0; s < kWgTM / 2; ++s) {
                 const int sn = s + 1 < kWgTM / 2 ? s + 1 : s;
                 const float av_n = gs[a_off + 2 * sn * RSg];
-                const unsigned vm_n = vmask[2 * sn + h];
                 float bv_n[JT];
 #pragma unroll
                 for (int j = 0; j < JT; ++j) bv_n[j] = as[b_off[j] + 2 * sn * RSa];
 #pragma unroll
-                for (int j = 0; j < JT; ++j) {
-                    const float b = (vm & b_bit[j]) ? bv[j] : 0.f;
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b, acc[j], 0, 0, 0);
-                }
+                for (int j = 0; j < JT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[j], acc[j], 0, 0, 0);
                 av = av_n;
-                vm = vm_n;
 #pragma unroll
                 for (int j = 0; j < JT; ++j) bv[j] = bv_n[j];
             }
         }
         __syncthreads();
-        if (next < xr.end) stash(next * kWgTM);
+        if (next < xr.end) stash();
         __syncthreads();
     }
     if (active) {
