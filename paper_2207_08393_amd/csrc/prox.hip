@@ -1799,7 +1799,12 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
         // that two waves share a SIMD and cover each other's LDS and issue latencies
         if (taps == 9 && ncb * nib == 4) {
             const int pg8 = (kWgTM * (a.Co / 4) + 511) / 512, pa8 = (rowtaps * n_pa * (a.Ci / 4) + 511) / 512;
-            if (pg8 <= 1 && pa8 <= 4) {
+            const int pg12 = (kWgTM * (a.Co / 4) + 767) / 768, pa12 = (rowtaps * n_pa * (a.Ci / 4) + 767) / 768;
+            if (pg12 <= 1 && pa12 <= 3) {
+                dim3 g12(n_split, 1);
+                launch_wgrad_pipe_t<3, 1, 3, 12>(pa, g12, lds, st);
+                hit_none = false;
+            } else if (pg8 <= 1 && pa8 <= 4) {
                 dim3 g8(n_split, 1);
                 launch_wgrad_pipe_t<5, 1, 4, 8>(pa, g8, lds, st);
                 hit_none = false;
