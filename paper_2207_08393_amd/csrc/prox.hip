@@ -1795,19 +1795,28 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
         WgradPipeArgs pa{a, bias_partial};
         bool hit = true;
         bool hit_none = true;
-        // 9 taps on a 2x2 grid of 32x32 channel blocks: eight waves, each one block and 5 (or 4) taps, so
-        // that two waves share a SIMD and cover each other's LDS and issue latencies
-        if (taps == 9 && ncb * nib == 4) {
-            const int pg8 = (kWgTM * (a.Co / 4) + 511) / 512, pa8 = (rowtaps * n_pa * (a.Ci / 4) + 511) / 512;
+        // Twelve waves when the layer splits into 7..12 jobs of one 32x32 channel block x 3 taps (9 taps on
+        // 2x2 blocks, 27 taps on one block) or x 1 tap (3 taps on 2x2 blocks): three waves share a SIMD
+        // and cover each other's LDS and issue latencies, and no wave carries a padded tap.
+        {
+            const int blocks = ncb * nib;
+            const int jobs3 = blocks * ((taps + 2) / 3), jobs1 = blocks * taps;
             const int pg12 = (kWgTM * (a.Co / 4) + 767) / 768, pa12 = (rowtaps * n_pa * (a.Ci / 4) + 767) / 768;
-            if (pg12 <= 1 && pa12 <= 3) {
-                dim3 g12(n_split, 1);
-                launch_wgrad_pipe_t<3, 1, 3, 12>(pa, g12, lds, st);
+            const dim3 g12(n_split, 1);
+            if (taps % 3 == 0 && jobs3 >= 7 && jobs3 <= 12 && pg12 <= 1 && pa12 <= 4) {
+                if (pa12 <= 3) launch_wgrad_pipe_t<3, 1, 3, 12>(pa, g12, lds, st);
+                else launch_wgrad_pipe_t<3, 1, 4, 12>(pa, g12, lds, st);
                 hit_none = false;
-            } else if (pg8 <= 1 && pa8 <= 4) {
-                dim3 g8(n_split, 1);
-                launch_wgrad_pipe_t<5, 1, 4, 8>(pa, g8, lds, st);
+            } else if (jobs1 >= 7 && jobs1 <= 12 && pg12 <= 1 && pa12 <= 3) {
+                launch_wgrad_pipe_t<1, 1, 3, 12>(pa, g12, lds, st);
                 hit_none = false;
+            } else if (taps == 9 && blocks == 4) {   // wider layers: eight waves, 5 + 4 taps per wave pair
+                const int pg8 = (kWgTM * (a.Co / 4) + 511) / 512, pa8 = (rowtaps * n_pa * (a.Ci / 4) + 511) / 512;
+                if (pg8 <= 1 && pa8 <= 4) {
+                    dim3 g8(n_split, 1);
+                    launch_wgrad_pipe_t<5, 1, 4, 8>(pa, g8, lds, st);
+                    hit_none = false;
+                }
             }
         }
 #define GLEAM_WG_TRY(JT_, PG_, PA_)                                             \
