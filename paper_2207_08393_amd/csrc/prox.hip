@@ -566,16 +566,17 @@ struct ConvThinInArgs {
 
 template <int KT, int KD, int KH, int KW, bool BF>
 __global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
-    constexpr int RT = KT * KD * KH, TAPS = RT * KW, TH = 2;
+    constexpr int RT = KT * KD * KH, TAPS = RT * KW, TH = 2, PX = 4;   // PX pixels per lane and step
+    constexpr int NC4 = (PX + KW - 1 + 1) / 2;                          // float4 (2 pixels x 2 channels) per row tap
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const ConvArgs& a = ta.c;
     const PixDims d = a.d;
-    const int WS = d.W + KW - 1;
+    const int WS = (d.W + PX - 1) / PX * PX + 2 * NC4 - PX;   // slab row: columns -KW/2 .. , zero past the row
     float* slab = smem;   // [RT][WS][2]
-    const int WCr = (a.Nn + 63) / 64 * 64;
+    const int WCr = a.Nn <= 32 ? 32 : (a.Nn <= 64 ? 64 : (a.Nn <= 128 ? 128 : 256));
     const int groups = 256 / WCr;
     const int n = threadIdx.x % WCr;
-    const int pg = __builtin_amdgcn_readfirstlane(threadIdx.x / WCr);
+    const int pg = threadIdx.x / WCr;
     const bool n_ok = n < a.Nn;
     const int nc = n_ok ? n : 0;
     float wreg[TAPS][TH];
@@ -595,46 +596,80 @@ __global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
         r /= d.D;
         const int tt = (int)(r % d.T);
         __syncthreads();
+        // stage the RT input rows: all loads of a pass are issued (clamped addresses) before any LDS store
+        for (int j0 = 0; j0 < WS; j0 += 256) {
+            const int j = j0 + threadIdx.x, col = j - KW / 2;
+            float2 v[RT];
+            bool ok[RT];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const int ih = rt % KH, id = (rt / KH) % KD, it = rt / (KH * KD);
-            const int ot = it - KT / 2, od = id - KD / 2, oh = ih - KH / 2;
-            const bool row_ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D && hh + oh >= 0 && hh + oh < d.H;
-            const long long src_row = row + ((long long)ot * d.D + od) * d.H + oh;
-            for (int idx = threadIdx.x; idx < WS * TH; idx += 256) {
-                const int col = idx / TH - KW / 2, e = idx % TH;
-                float v = 0.f;
-                if (row_ok && col >= 0 && col < d.W) v = a.in[(src_row * d.W + col) * TH + e];
-                if (a.relu_in) v = fmaxf(v, 0.f);
-                slab[rt * WS * TH + idx] = v;
+            for (int rt = 0; rt < RT; ++rt) {
+                const int ih = rt % KH, id = (rt / KH) % KD, it = rt / (KH * KD);
+                const int ot = it - KT / 2, od = id - KD / 2, oh = ih - KH / 2;
+                const bool row_ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D && hh + oh >= 0 && hh + oh < d.H;
+                const long long src_row = row + ((long long)ot * d.D + od) * d.H + oh;
+                ok[rt] = row_ok && col >= 0 && col < d.W;
+                v[rt] = *reinterpret_cast<const float2*>(a.in + (ok[rt] ? (src_row * d.W + col) * TH : 0));
+            }
+            if (j < WS) {
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    float2 x = make_float2(ok[rt] ? v[rt].x : 0.f, ok[rt] ? v[rt].y : 0.f);
+                    if (a.relu_in) x = make_float2(fmaxf(x.x, 0.f), fmaxf(x.y, 0.f));
+                    *reinterpret_cast<float2*>(slab + (rt * WS + j) * TH) = x;
+                }
             }
         }
         __syncthreads();
-        for (int w = pg; w < d.W; w += groups) {
-            float acc = bias;
+        // each lane: one output channel, PX consecutive pixels; the input columns of a row tap come as
+        // 16-byte reads (two pixels x two channels), the same address for all lanes of a channel group
+        for (int w = pg * PX; w < d.W; w += groups * PX) {
+            float acc[PX];
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
+            for (int p = 0; p < PX; ++p) acc[p] = bias;
 #pragma unroll
-                for (int iw = 0; iw < KW; ++iw) {
-                    const float* tp = slab + (rt * WS + w + iw) * TH;
-                    acc = fmaf(wreg[rt * KW + iw][0], tp[0], acc);
-                    acc = fmaf(wreg[rt * KW + iw][1], tp[1], acc);
+            for (int rt = 0; rt < RT; ++rt) {
+                float col[2 * NC4][TH];
+#pragma unroll
+                for (int c4 = 0; c4 < NC4; ++c4) {
+                    const float4 v = *reinterpret_cast<const float4*>(slab + (rt * WS + w + 2 * c4) * TH);
+                    col[2 * c4][0] = v.x; col[2 * c4][1] = v.y; col[2 * c4 + 1][0] = v.z; col[2 * c4 + 1][1] = v.w;
                 }
+#pragma unroll
+                for (int iw = 0; iw < KW; ++iw)
+#pragma unroll
+                    for (int p = 0; p < PX; ++p) {
+                        acc[p] = fmaf(wreg[rt * KW + iw][0], col[p + iw][0], acc[p]);
+                        acc[p] = fmaf(wreg[rt * KW + iw][1], col[p + iw][1], acc[p]);
+                    }
+            }
             if (n_ok) {
-                const long long o = (row * d.W + w) * a.Nn + n;
-                if (a.relu_out) acc = fmaxf(acc, 0.f);
-                if (BF) {   // wide tensors (out, mask_ref, add) are bfloat16
-                    const unsigned short* mr = reinterpret_cast<const unsigned short*>(a.mask_ref);
-                    const unsigned short* ad = reinterpret_cast<const unsigned short*>(a.add);
-                    const float ref = mr ? bf16_to_f32(mr[o]) : 1.f;
-                    if (a.mask_acc) acc = ref > 0.f ? acc : 0.f;
-                    if (ad) acc += (a.mask_add && !(ref > 0.f)) ? 0.f : bf16_to_f32(ad[o]);
-                    reinterpret_cast<unsigned short*>(a.out)[o] = f32_to_bf16(acc);
-                } else {
-                    const float ref = a.mask_ref ? a.mask_ref[o] : 1.f;
-                    if (a.mask_acc) acc = ref > 0.f ? acc : 0.f;
-                    if (a.add) acc += (a.mask_add && !(ref > 0.f)) ? 0.f : a.add[o];
-                    a.out[o] = acc;
+                // reference / skip values of the PX outputs are requested together, then combined and stored
+                const long long o0 = (row * d.W + w) * a.Nn + n;
+                float ref[PX], add[PX];
+#pragma unroll
+                for (int p = 0; p < PX; ++p) {
+                    const long long o = w + p < d.W ? o0 + (long long)p * a.Nn : o0;
+                    ref[p] = 1.f;
+                    add[p] = 0.f;
+                    if (BF) {   // wide tensors (out, mask_ref, add) are bfloat16
+                        if (a.mask_ref) ref[p] = bf16_to_f32(reinterpret_cast<const unsigned short*>(a.mask_ref)[o]);
+                        if (a.add) add[p] = bf16_to_f32(reinterpret_cast<const unsigned short*>(a.add)[o]);
+                    } else {
+                        if (a.mask_ref) ref[p] = a.mask_ref[o];
+                        if (a.add) add[p] = a.add[o];
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < PX; ++p) {
+                    float x = acc[p];
+                    if (a.relu_out) x = fmaxf(x, 0.f);
+                    if (a.mask_acc) x = ref[p] > 0.f ? x : 0.f;
+                    x += (a.mask_add && !(ref[p] > 0.f)) ? 0.f : add[p];
+                    if (w + p < d.W) {
+                        const long long o = o0 + (long long)p * a.Nn;
+                        if (BF) reinterpret_cast<unsigned short*>(a.out)[o] = f32_to_bf16(x);
+                        else a.out[o] = x;
+                    }
                 }
             }
         }
@@ -913,7 +948,8 @@ template <int KT, int KD, int KH, int KW>
 static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, bool bf, hipStream_t st) {
     ConvThinInArgs t{a, cw.w, cw.sn, cw.st, cw.sk};
     const long long n_rows = a.d.Q / a.d.W;
-    const size_t lds = (size_t)KT * KD * KH * (a.d.W + KW - 1) * 2 * sizeof(float);
+    constexpr int PX = 4, NC4 = (PX + KW - 1 + 1) / 2;
+    const size_t lds = (size_t)KT * KD * KH * ((a.d.W + PX - 1) / PX * PX + 2 * NC4 - PX) * 2 * sizeof(float);
     const long long cap = 256LL * 8;
     const dim3 grid((unsigned)(n_rows < cap ? n_rows : cap));
     if (bf) hipLaunchKernelGGL((conv_thin_in_kernel<KT, KD, KH, KW, true>), grid, dim3(256), lds, st, t);
@@ -924,8 +960,7 @@ static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, bool
 static hipError_t launch_conv_thin_in(const ConvArgs& a, const ConvWeights& cw, bool bf, bool* hit, hipStream_t st) {
     *hit = false;
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
-    const int wr = (a.Nn + 63) / 64 * 64;
-    if (!(a.K == 2 && a.Nn >= 8 && wr <= 256 && 256 % wr == 0)) return hipSuccess;
+    if (!(a.K == 2 && a.Nn >= 8 && a.Nn <= 256)) return hipSuccess;
     const PixDims& d = a.d;
     const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
     const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
