@@ -1375,24 +1375,26 @@ struct WgradThinArgs {
     const float* thin;   // [Q][TH]
     float* partial;      // [gridDim.x][Co][taps][Ci]
     float* bias_partial; // [gridDim.x][Co] or null
-    int WC;              // wide channels (<= 256, 256 % round64(WC) == 0)
+    int WC;              // wide channels (<= 256)
     int relu_in;
     PixDims d;
 };
 
 template <int KT, int KD, int KH, int KW, int TH, bool THIN_IN, bool BF>
 __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
-    constexpr int RT = KT * KD * KH, TAPS = RT * KW;
+    static_assert(TH == 2, "the thin side is the 2-channel image");
+    constexpr int RT = KT * KD * KH, TAPS = RT * KW, PX = 4;   // PX pixels per lane and step
+    constexpr int NC4 = (PX + KW - 1 + 1) / 2;                  // float4 (2 pixels x 2 channels) per row tap
     constexpr int sgn = THIN_IN ? 1 : -1;
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const PixDims d = a.d;
-    const int WS = d.W + KW - 1;            // slab columns: image columns -KW/2 .. W-1+KW/2
+    const int WS = (d.W + PX - 1) / PX * PX + 2 * NC4 - PX;   // slab columns: image columns -KW/2 .., zero past the row
     float* slab = smem;                     // [RT][WS][TH]
     float* red = smem + RT * WS * TH;       // [256]
-    const int WCr = (a.WC + 63) / 64 * 64;
+    const int WCr = a.WC <= 32 ? 32 : (a.WC <= 64 ? 64 : (a.WC <= 128 ? 128 : 256));
     const int groups = 256 / WCr;
     const int c = threadIdx.x % WCr;
-    const int pg = __builtin_amdgcn_readfirstlane(threadIdx.x / WCr);
+    const int pg = threadIdx.x / WCr;
     const bool c_ok = c < a.WC;
     const long long n_rows = d.Q / d.W;
 
@@ -1413,39 +1415,69 @@ __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
         r /= d.D;
         const int tt = (int)(r % d.T);
         __syncthreads();
+        // stage the RT thin rows: all loads of a pass are issued (clamped addresses) before any LDS store
+        for (int j0 = 0; j0 < WS; j0 += 256) {
+            const int j = j0 + threadIdx.x, col = j - KW / 2;
+            float2 v[RT];
+            bool ok[RT];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const int ih = rt % KH, id = (rt / KH) % KD, it = rt / (KH * KD);
-            const int ot = sgn * (it - KT / 2), od = sgn * (id - KD / 2), oh = sgn * (ih - KH / 2);
-            const bool row_ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D && hh + oh >= 0 && hh + oh < d.H;
-            const long long src_row = row + ((long long)ot * d.D + od) * d.H + oh;
-            for (int idx = threadIdx.x; idx < WS * TH; idx += 256) {
-                const int col = idx / TH - KW / 2, e = idx % TH;
-                float v = 0.f;
-                if (row_ok && col >= 0 && col < d.W) v = a.thin[(src_row * d.W + col) * TH + e];
-                if (THIN_IN && a.relu_in) v = fmaxf(v, 0.f);
-                slab[rt * WS * TH + idx] = v;
+            for (int rt = 0; rt < RT; ++rt) {
+                const int ih = rt % KH, id = (rt / KH) % KD, it = rt / (KH * KD);
+                const int ot = sgn * (it - KT / 2), od = sgn * (id - KD / 2), oh = sgn * (ih - KH / 2);
+                const bool row_ok = tt + ot >= 0 && tt + ot < d.T && dd + od >= 0 && dd + od < d.D && hh + oh >= 0 && hh + oh < d.H;
+                const long long src_row = row + ((long long)ot * d.D + od) * d.H + oh;
+                ok[rt] = row_ok && col >= 0 && col < d.W;
+                v[rt] = *reinterpret_cast<const float2*>(a.thin + (ok[rt] ? (src_row * d.W + col) * TH : 0));
+            }
+            if (j < WS) {
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    float2 x = make_float2(ok[rt] ? v[rt].x : 0.f, ok[rt] ? v[rt].y : 0.f);
+                    if (THIN_IN && a.relu_in) x = make_float2(fmaxf(x.x, 0.f), fmaxf(x.y, 0.f));
+                    *reinterpret_cast<float2*>(slab + (rt * WS + j) * TH) = x;
+                }
             }
         }
         __syncthreads();
-        for (int w = pg; w < d.W; w += groups) {
-            float wv = 0.f;
-            if (c_ok) wv = BF ? bf16_to_f32(reinterpret_cast<const unsigned short*>(a.wide)[(row * d.W + w) * a.WC + c])
-                              : a.wide[(row * d.W + w) * a.WC + c];
-            if (!THIN_IN && a.relu_in) wv = fmaxf(wv, 0.f);
-            if (THIN_IN) bs[0] += wv;
+        // each lane: one wide channel, PX consecutive pixels per step (their loads are issued together)
+        for (int w = pg * PX; w < d.W; w += groups * PX) {
+            float wv[PX];
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
+            for (int p = 0; p < PX; ++p) {
+                const bool ok = c_ok && w + p < d.W;
+                const long long o = ok ? (row * d.W + w + p) * a.WC + c : 0;
+                const float x = BF ? bf16_to_f32(reinterpret_cast<const unsigned short*>(a.wide)[o]) : a.wide[o];
+                wv[p] = ok ? x : 0.f;
+            }
+            if (!THIN_IN && a.relu_in) {
 #pragma unroll
-                for (int iw = 0; iw < KW; ++iw) {
-                    const float* tp = slab + (rt * WS + w + (THIN_IN ? iw : KW - 1 - iw)) * TH;
+                for (int p = 0; p < PX; ++p) wv[p] = fmaxf(wv[p], 0.f);
+            }
+            if (THIN_IN) {
 #pragma unroll
-                    for (int e = 0; e < TH; ++e) acc[rt * KW + iw][e] = fmaf(wv, tp[e], acc[rt * KW + iw][e]);
+                for (int p = 0; p < PX; ++p) bs[0] += wv[p];
+            }
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                float col[2 * NC4][TH];
+#pragma unroll
+                for (int c4 = 0; c4 < NC4; ++c4) {
+                    const float4 v = *reinterpret_cast<const float4*>(slab + (rt * WS + w + 2 * c4) * TH);
+                    col[2 * c4][0] = v.x; col[2 * c4][1] = v.y; col[2 * c4 + 1][0] = v.z; col[2 * c4 + 1][1] = v.w;
                 }
-            if (!THIN_IN) {
-                const float* tp = slab + ((RT / 2) * WS + w + KW / 2) * TH;   // centre tap = the pixel itself
 #pragma unroll
-                for (int e = 0; e < TH; ++e) bs[e] += tp[e];
+                for (int iw = 0; iw < KW; ++iw)
+#pragma unroll
+                    for (int p = 0; p < PX; ++p)
+#pragma unroll
+                        for (int e = 0; e < TH; ++e)
+                            acc[rt * KW + iw][e] = fmaf(wv[p], col[p + (THIN_IN ? iw : KW - 1 - iw)][e], acc[rt * KW + iw][e]);
+                if (!THIN_IN && rt == RT / 2) {   // centre tap = the pixel itself: bias gradient of the thin side
+#pragma unroll
+                    for (int p = 0; p < PX; ++p)
+#pragma unroll
+                        for (int e = 0; e < TH; ++e) bs[e] += col[p + KW / 2][e];
+                }
             }
         }
     }
@@ -1595,10 +1627,7 @@ bool prox_bf16_supported(const gleam_prox_desc& p) {
         return (c.kt == 1 && c.kd == 1 && c.kh == 3 && c.kw == 3) || (c.kt == 1 && c.kd == 3 && c.kh == 3 && c.kw == 3) ||
                (c.kt == 3 && c.kd == 1 && c.kh == 1 && c.kw == 1);
     };
-    auto wide_ok = [](int ch) {
-        const int r = (ch + 63) / 64 * 64;
-        return ch >= 8 && ch % 8 == 0 && r <= 256 && 256 % r == 0;
-    };
+    auto wide_ok = [](int ch) { return ch >= 8 && ch % 8 == 0 && ch <= 256; };
     for (int l = 0; l < L; ++l) {
         const gleam_conv& c = p.layers[l];
         if (c.kw != 1 && c.kw != 3) return false;
@@ -1756,7 +1785,8 @@ template <int KT, int KD, int KH, int KW>
 static void launch_wgrad_thin_t(const WgradArgs& a, float* bias_partial, int n_split, bool bf, hipStream_t st) {
     WgradThinArgs t{};
     t.partial = a.partial; t.bias_partial = bias_partial; t.relu_in = a.relu_in; t.d = a.d;
-    const size_t lds = ((size_t)KT * KD * KH * (a.d.W + KW - 1) * 2 + 256) * sizeof(float);
+    constexpr int PX = 4, NC4 = (PX + KW - 1 + 1) / 2;
+    const size_t lds = ((size_t)KT * KD * KH * ((a.d.W + PX - 1) / PX * PX + 2 * NC4 - PX) * 2 + 256) * sizeof(float);
     const dim3 grid(n_split), blk(256);
     if (a.Ci == 2) {   // thin input a (float32), wide output gradient g
         t.wide = a.g; t.thin = a.a; t.WC = a.Co;
@@ -1776,8 +1806,7 @@ static hipError_t launch_wgrad_thin(const WgradArgs& a, float* bias_partial, boo
     const PixDims& d = a.d;
     const int taps = d.kt * d.kd * d.kh * d.kw;
     const int wide = a.Ci == 2 ? a.Co : a.Ci;
-    const int wide_r = (wide + 63) / 64 * 64;
-    if (!((a.Ci == 2) != (a.Co == 2) && wide >= 8 && wide_r <= 256 && 256 % wide_r == 0)) return hipSuccess;
+    if (!((a.Ci == 2) != (a.Co == 2) && wide >= 8 && wide <= 256)) return hipSuccess;
     const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
     const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
     if (!k2 && !k3 && !kt3) return hipSuccess;
