@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
 // Requires K % 4 == 0 (16-byte alignment of every quad).
 // KW > 0 fixes the kernel extent along W at compile time (all LDS operand offsets become immediates);
 // KW == 0 reads it from the arguments.
-template <int NB, int CK, int PJ, int NW, int KW>
+template <int NB, int CK, int PJ, int NW, int KW, bool RELU>
 __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
     constexpr int TM = NW * 32 * PJ, G = CK / 8, NJ = NB / 32, Q4 = CK / 4;
     constexpr int RP = Q4 >= 8 ? 1 : 8 / Q4;   // pixel rows per 128 bytes of LDS
@@ -423,17 +423,19 @@ __global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
                 for (int u = 0; u < U; ++u) {
                     const int cur = u & 1, dw = u / G;
                     if (u + 1 < U) load_unit(u + 1, cur ^ 1);
+                    // Ordinary vector instructions take issue slots from the MFMAs, so ReLU and the zero
+                    // padding are done on the bit patterns: max with 0 as a signed integer is ReLU (negative
+                    // floats have the sign bit set), and the padding mask is one AND.
 #pragma unroll
                     for (int pj = 0; pj < PJ; ++pj) {
-                        const unsigned okm = ((vbits[pj] >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
+                        const int okm = -(int)((vbits[pj] >> (rt * kw + dw)) & 1u);   // all ones: tap inside the grid
                         float4& v = pb[cur][pj];
-                        if (a.relu_in) {
-                            v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+                        int x0 = __float_as_int(v.x), x1 = __float_as_int(v.y), x2 = __float_as_int(v.z), x3 = __float_as_int(v.w);
+                        if (RELU) {
+                            x0 = x0 > 0 ? x0 : 0; x1 = x1 > 0 ? x1 : 0; x2 = x2 > 0 ? x2 : 0; x3 = x3 > 0 ? x3 : 0;
                         }
-                        v.x = __uint_as_float(__float_as_uint(v.x) & okm);  // zero padding
-                        v.y = __uint_as_float(__float_as_uint(v.y) & okm);
-                        v.z = __uint_as_float(__float_as_uint(v.z) & okm);
-                        v.w = __uint_as_float(__float_as_uint(v.w) & okm);
+                        v.x = __int_as_float(x0 & okm); v.y = __int_as_float(x1 & okm);
+                        v.z = __int_as_float(x2 & okm); v.w = __int_as_float(x3 & okm);
                     }
 #pragma unroll
                     for (int pj = 0; pj < PJ; ++pj) {
@@ -904,7 +906,8 @@ static void launch_conv_dlds_k(const ConvArgs& a, hipStream_t st) {
     const long long cap = 256LL * per_cu;
     const long long gx = ((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8;   // XCD-aware split needs a multiple of 8
     dim3 grid((unsigned)gx, (a.Nn + NB - 1) / NB);
-    hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW, KW>), grid, dim3(NW * 64), 0, st, a);
+    if (a.relu_in) hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW, KW, true>), grid, dim3(NW * 64), 0, st, a);
+    else hipLaunchKernelGGL((conv_dlds_kernel<NB, CK, PJ, NW, KW, false>), grid, dim3(NW * 64), 0, st, a);
 }
 
 template <int NB, int CK, int PJ, int NW>
