@@ -12,6 +12,7 @@
 // index and never ragged except at the very end of the tensor.
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
 #include <cstdio>
 #include <type_traits>
 
@@ -1522,27 +1523,65 @@ __global__ __launch_bounds__(256) void wgrad_thin_kernel(WgradThinArgs a) {
     }
 }
 
-// out[i] = sum_s partial[s][i], s ascending (fixed order => run-to-run identical bits).  Two segments in
-// one launch: the weight-gradient partials (n elements) and, when n2 > 0, the bias-gradient partials.
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_split, long long n, float* __restrict__ out,
-                                       const float* __restrict__ partial2, long long n2, float* __restrict__ out2) {
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n + n2) return;
-    const float* src = partial;
-    float* dst = out;
-    long long stride = n;
-    if (i >= n) { i -= n; src = partial2; dst = out2; stride = n2; }
-    float s = 0.f;
-    int k = 0;
-    for (; k + 8 <= n_split; k += 8) {  // 8 independent loads in flight, summed in ascending order
-        float v[8];
+// out[i] = sum_s partial[s][i] in a fixed order (run-to-run identical bits).  Two segments in one launch:
+// the weight-gradient partials (n elements, blocks [0, nbw)) and, when n2 > 0, the bias-gradient partials.
+// A block of 256 threads is 16 split groups x 16 lanes: group g sums its contiguous sixteenth of the
+// partials (several loads in flight per thread), the 16 group sums are then added in ascending order.
+// VEC = 4 (weights only, when n % 4 == 0 and `out` is 16-byte aligned) moves float4 per lane.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int n_split, long long n,
+                                                              float* __restrict__ out, int vec, int nbw,
+                                                              const float* __restrict__ partial2, long long n2,
+                                                              float* __restrict__ out2) {
+    __shared__ float4 red[16][16];
+    const int lane = threadIdx.x & 15, sg = threadIdx.x >> 4;
+    const int per = (n_split + 15) / 16;
+    const int k0 = sg * per, k1 = k0 + per < n_split ? k0 + per : n_split;
+    const bool first = (int)blockIdx.x < nbw;
+    const float* src = first ? partial : partial2;
+    float* dst = first ? out : out2;
+    const long long stride = first ? n : n2;
+    const int width = (first && vec) ? 4 : 1;
+    const long long i = ((long long)(first ? blockIdx.x : blockIdx.x - nbw) * 16 + lane) * width;
+    const bool ok = i < stride;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ok) {
+        if (width == 4) {
+            int k = k0;
+            for (; k + 4 <= k1; k += 4) {
+                float4 v[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(k + u) * stride + i];
+                for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(src + (size_t)(k + u) * stride + i);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += v[u];
+                for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+            }
+            for (; k < k1; ++k) {
+                const float4 v = *reinterpret_cast<const float4*>(src + (size_t)k * stride + i);
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            }
+        } else {
+            int k = k0;
+            for (; k + 4 <= k1; k += 4) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = src[(size_t)(k + u) * stride + i];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) s.x += v[u];
+            }
+            for (; k < k1; ++k) s.x += src[(size_t)k * stride + i];
+        }
     }
-    for (; k < n_split; ++k) s += src[(size_t)k * stride + i];
-    dst[i] = s;
+    red[sg][lane] = s;
+    __syncthreads();
+    if (sg == 0 && ok) {
+        float4 t = red[0][lane];
+#pragma unroll
+        for (int g2 = 1; g2 < 16; ++g2) {
+            const float4 v = red[g2][lane];
+            t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+        }
+        if (width == 4) *reinterpret_cast<float4*>(dst + i) = t;
+        else dst[i] = t.x;
+    }
 }
 
 // partial[blk][c] = sum over this workgroup's pixels of g[q][c]  (bias gradient).
@@ -1983,8 +2022,11 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         {
             const long long nb = c.has_bias ? c.cout : 0;
             KernelScope ks("wgrad_reduce", 0.0, 4.0 * (double)(nw + nb) * (used_split + 1), st);
-            hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((nw + nb + 255) / 256)), dim3(256), 0, st,
-                               (const float*)partial, used_split, nw, grad_theta + plan.w_off[l - 1],
+            float* gw = grad_theta + plan.w_off[l - 1];
+            const int vec = (nw % 4 == 0 && (reinterpret_cast<uintptr_t>(gw) & 15) == 0) ? 1 : 0;
+            const int nbw = (int)((nw + 16 * (vec ? 4 : 1) - 1) / (16 * (vec ? 4 : 1))), nbb = (int)((nb + 15) / 16);
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)(nbw + nbb)), dim3(256), 0, st,
+                               (const float*)partial, used_split, nw, gw, vec, nbw,
                                (const float*)bpart, nb, c.has_bias ? grad_theta + plan.b_off[l - 1] : nullptr);
         }
         e = hipGetLastError();
