@@ -280,7 +280,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
 // KW > 0 fixes the kernel extent along W at compile time (all LDS operand offsets become immediates);
 // KW == 0 reads it from the arguments.
 template <int NB, int CK, int PJ, int NW, int KW, bool RELU>
-__global__ __launch_bounds__(NW * 64) void conv_dlds_kernel(ConvArgs a) {
+__global__ __launch_bounds__(NW * 64, 2) void conv_dlds_kernel(ConvArgs a) {
     constexpr int TM = NW * 32 * PJ, G = CK / 8, NJ = NB / 32, Q4 = CK / 4;
     constexpr int RP = Q4 >= 8 ? 1 : 8 / Q4;   // pixel rows per 128 bytes of LDS
     constexpr int KWM = KW > 0 ? KW : 5;       // most taps along W

@@ -54,8 +54,8 @@ size_t conv_bf16_wimg_elems(int K, int Nn, int taps) {
 }
 
 // ------------------------------------------------------------------ forward / data gradient
-template <int NB, int KW>
-__global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args a) {
+template <int NB, int KW, bool RELU>
+__global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
     constexpr int NW = 4, TM = 128, G = kBfCK / 16, NJ = NB / 32, QP = kBfCK / 8;   // QP quads per pixel row
     constexpr int RP = 8 / QP;                 // pixel rows per 128 bytes of LDS (QP = 4 -> 2)
     constexpr int KWM = KW > 0 ? KW : 5;
@@ -94,9 +94,9 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args a) {
         const int v = (wave + i * NW) * 64 + lane;
         w_off[i] = 8u * (unsigned)(v < w8 ? v : 0);
     }
-    auto issue = [&](long long tile, int c, uint4* dst) {
-        const int rt = c / n_kc, kc = c % n_kc;
-        const long long qs = tile * TM + rowtap_offset(rt, d) - kw / 2;
+    auto issue = [&](long long tile, const ChunkIter& ci, uint4* dst) {
+        const int rt = ci.rt, kc = ci.kc;
+        const long long qs = tile * TM + ci.off - kw / 2;
         const bool interior = k_full && qs >= 0 && qs + (long long)slab_ops * 64 / QP <= d.Q;   // uniform
         if (interior) {
             const unsigned short* base = a.in + qs * a.K + kc * kBfCK;
@@ -143,29 +143,31 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args a) {
 
     const XcdRange xr = xcd_range(n_tiles);
     long long tile = xr.first;
-    int c = 0;
-    if (tile < xr.end) issue(tile, 0, bufA);
+    ChunkIter ci = chunk_first(d);
+    if (tile < xr.end) issue(tile, ci, bufA);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    long long q = 0;
+    // this lane's pixel of the current tile, tracked by coordinates (no divisions per tile)
+    long long q = (tile < xr.end ? tile : 0) * TM + wave * 32 + m;
+    PixCoord qc = pix_coord(q < d.Q ? q : 0, d);
+    const PixCoord qstep = pix_coord(xr.stride * TM, d);
     unsigned vbits = 0u;
     floatx16 acc[NJ];
     auto step = [&](const uint4* slab, uint4* nxt) {
-        if (c == 0) {
-            q = tile * TM + wave * 32 + m;
-            vbits = tap_validity(q, d);
+        if (ci.c == 0) {
+            vbits = q < d.Q ? tap_validity_at(qc, d) : 0u;
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
         }
-        const bool last = c + 1 == nck;
+        const bool last = ci.c + 1 == nck;
         const long long ntile = last ? tile + xr.stride : tile;
-        const int nc = last ? 0 : c + 1;
-        if (ntile < xr.end) issue(ntile, nc, nxt);
+        const ChunkIter nci = chunk_next(ci, n_kc, nck, d);
+        if (ntile < xr.end) issue(ntile, nci, nxt);
         const uint4* wl = slab + slab_ops * 64 + wa_lane;
-        const int rt = c / n_kc;
+        const int rt = ci.rt;
 #pragma unroll
         for (int dw = 0; dw < KWM; ++dw) {
             if (KW == 0 && dw >= kw) continue;
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args a) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 uint4 pb = slab[p_off[dw][g]];
-                if (a.relu_in) {
+                if (RELU) {
                     pb.x = relu_bf16x2(pb.x); pb.y = relu_bf16x2(pb.y); pb.z = relu_bf16x2(pb.z); pb.w = relu_bf16x2(pb.w);
                 }
                 pb.x &= okm; pb.y &= okm; pb.z &= okm; pb.w &= okm;   // zero padding: tap outside the grid
@@ -244,8 +246,12 @@ __global__ __launch_bounds__(256) void conv_bf16_kernel(ConvBf16Args a) {
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        if (last) {
+            q += xr.stride * TM;
+            pix_advance(qc, qstep, d);
+        }
         tile = ntile;
-        c = nc;
+        ci = nci;
     };
     while (tile < xr.end) {
         step(bufA, bufB);
@@ -265,7 +271,8 @@ static void launch_conv_bf16_k(const ConvBf16Args& a, hipStream_t st) {
     const long long cap = 256LL * per_cu;
     const long long gx = ((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8;
     dim3 grid((unsigned)gx, (a.Nn + NB - 1) / NB);
-    hipLaunchKernelGGL((conv_bf16_kernel<NB, KW>), grid, dim3(256), 0, st, a);
+    if (a.relu_in) hipLaunchKernelGGL((conv_bf16_kernel<NB, KW, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((conv_bf16_kernel<NB, KW, false>), grid, dim3(256), 0, st, a);
 }
 
 hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long sn, long long st_, long long sk, int flip,

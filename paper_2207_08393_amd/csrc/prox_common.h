@@ -107,10 +107,44 @@ __device__ __forceinline__ float bf16_to_f32(unsigned short h) { return __uint_a
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
     return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
 }
-// max(x, 0) on two packed bf16 values: clear every half whose sign bit is set
+// max(x, 0) on two packed bf16 values: a negative bf16 has the sign bit of its 16-bit pattern set, so a
+// packed signed 16-bit max with 0 is ReLU (one instruction)
+typedef short short2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned relu_bf16x2(unsigned x) {
-    const unsigned neg = ((x >> 15) & 0x00010001u) * 0xffffu;
-    return x & ~neg;
+    const short2v zero = {0, 0};
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(short2v, x), zero));
+}
+
+// Walks the chunks of one pixel tile in order (row tap major, input-channel chunk minor) and keeps the
+// flattened pixel offset of the row tap, without divisions.
+struct ChunkIter {
+    int c, rt, kc, ih, id, it;
+    long long off;   // rowtap_offset(rt)
+};
+__device__ __forceinline__ ChunkIter chunk_first(const PixDims& d) {
+    ChunkIter x;
+    x.c = x.rt = x.kc = x.ih = x.id = x.it = 0;
+    x.off = (((long long)(0 - d.kt / 2) * d.D + (0 - d.kd / 2)) * d.H + (0 - d.kh / 2)) * d.W;
+    return x;
+}
+__device__ __forceinline__ ChunkIter chunk_next(ChunkIter x, int n_kc, int nck, const PixDims& d) {
+    if (x.c + 1 == nck) return chunk_first(d);
+    ++x.c;
+    if (++x.kc == n_kc) {
+        x.kc = 0;
+        ++x.rt;
+        x.off += d.W;                                        // next row
+        if (++x.ih == d.kh) {
+            x.ih = 0;
+            x.off += (long long)(d.H - d.kh) * d.W;           // next slice, first row tap
+            if (++x.id == d.kd) {
+                x.id = 0;
+                x.off += (long long)(d.D - d.kd) * d.H * d.W;   // next frame, first slice tap
+                ++x.it;
+            }
+        }
+    }
+    return x;
 }
 
 // Launch arguments of the bf16 MFMA convolution (forward and data gradient): in/out/mask_ref/add are
