@@ -326,9 +326,9 @@ __global__ __launch_bounds__(NW * 64, 2) void conv_dlds_kernel(ConvArgs a) {
         w_off[i] = 4u * (unsigned)(v < w4 ? v : 0);
     }
 
-    auto issue = [&](long long tile, int c, float* dst) {
-        const int rt = c / n_kc, kc = c % n_kc;
-        const long long qs = tile * TM + rowtap_offset(rt, d) - kw / 2;
+    auto issue = [&](long long tile, const ChunkIter& ci, float* dst) {
+        const int rt = ci.rt, kc = ci.kc;
+        const long long qs = tile * TM + ci.off - kw / 2;
         const bool interior = k_full && qs >= 0 && qs + (long long)slab_ops * 64 / Q4 <= d.Q;   // uniform
         if (interior) {
             const float* base = a.in + qs * a.K + kc * CK;                                       // uniform
@@ -377,21 +377,25 @@ __global__ __launch_bounds__(NW * 64, 2) void conv_dlds_kernel(ConvArgs a) {
 
     const XcdRange xr = xcd_range(n_tiles);
     long long tile = xr.first;
-    int c = 0;
-    if (tile < xr.end) issue(tile, 0, bufA);
+    ChunkIter ci = chunk_first(d);
+    if (tile < xr.end) issue(tile, ci, bufA);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    long long q0 = 0;
+    // this lane's pixels of the current tile, tracked by coordinates (no divisions per tile)
+    long long q0 = (tile < xr.end ? tile : 0) * TM + wave * (32 * PJ) + m;
+    PixCoord qc[PJ];
+#pragma unroll
+    for (int pj = 0; pj < PJ; ++pj) qc[pj] = pix_coord(q0 + 32 * pj < d.Q ? q0 + 32 * pj : 0, d);
+    const PixCoord qstep = pix_coord(xr.stride * TM, d);
     unsigned vbits[PJ];
     floatx16 acc[PJ][NJ];
     // One chunk: prefetch the following chunk into `nxt`, run the MFMAs of the current one out of `slab`.
     // Called alternately with (bufA, bufB) and (bufB, bufA) so that each call site names its buffers.
     auto step = [&](const float* slab, float* nxt) {
-        if (c == 0) {
-            q0 = tile * TM + wave * (32 * PJ) + m;
+        if (ci.c == 0) {
 #pragma unroll
-            for (int pj = 0; pj < PJ; ++pj) vbits[pj] = tap_validity(q0 + 32 * pj, d);
+            for (int pj = 0; pj < PJ; ++pj) vbits[pj] = q0 + 32 * pj < d.Q ? tap_validity_at(qc[pj], d) : 0u;
 #pragma unroll
             for (int pj = 0; pj < PJ; ++pj)
 #pragma unroll
@@ -399,13 +403,13 @@ __global__ __launch_bounds__(NW * 64, 2) void conv_dlds_kernel(ConvArgs a) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
         }
-        const bool last = c + 1 == nck;
+        const bool last = ci.c + 1 == nck;
         const long long ntile = last ? tile + xr.stride : tile;
-        const int nc = last ? 0 : c + 1;
-        if (ntile < xr.end) issue(ntile, nc, nxt);
+        const ChunkIter nci = chunk_next(ci, n_kc, nck, d);
+        if (ntile < xr.end) issue(ntile, nci, nxt);
         {
             const float* wl = slab + slab_ops * 256 + wa_lane;
-            const int rt = c / n_kc;
+            const int rt = ci.rt;
             if constexpr (KW > 0) {
                 // Operands of unit u + 1 (one tap along W x 8 input channels) are read from LDS before the
                 // MFMAs of unit u are issued, and consecutive MFMAs alternate between accumulators.
@@ -546,8 +550,13 @@ __global__ __launch_bounds__(NW * 64, 2) void conv_dlds_kernel(ConvArgs a) {
         }
         __builtin_amdgcn_s_waitcnt(0);   // the next chunk's direct loads have landed in LDS
         __syncthreads();                 // ... and every wave is done reading the current buffer
+        if (last) {
+            q0 += xr.stride * TM;
+#pragma unroll
+            for (int pj = 0; pj < PJ; ++pj) pix_advance(qc[pj], qstep, d);
+        }
         tile = ntile;
-        c = nc;
+        ci = nci;
     };
     while (tile < xr.end) {
         step(bufA, bufB);
