@@ -1230,15 +1230,15 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     // past the end of the row get g = 0, and slab entries outside the grid (row taps above / below the
     // image, the halo columns left / right of it) are stored as 0, so the MFMA loop needs no masks.
     const int segs = (d.W + kWgTM - 1) / kWgTM;
-    auto fetch = [&](long long chunk) {
-        const long long row = chunk / segs;
-        const int w0 = (int)(chunk % segs) * kWgTM;
-        long long r = row;
-        const int hh = (int)(r % d.H);
-        r /= d.H;
-        const int dd = (int)(r % d.D);
-        r /= d.D;
-        const int tt = (int)(r % d.T);
+    // (segment, row, slice, frame) of the chunk to fetch, advanced chunk by chunk without divisions
+    PixDims cd = d;
+    cd.W = segs;
+    PixCoord cc{0, 0, 0, 0}, cstep{0, 0, 0, 0};
+    long long crow = 0, rstep = 0;   // image row of that chunk, whole rows per step
+    auto fetch = [&]() {
+        const long long row = crow;
+        const int w0 = cc.w * kWgTM;
+        const int hh = cc.h, dd = cc.dd, tt = cc.t;
         unsigned rows_ok = 0u;
         {
             int rt = 0;
@@ -1250,6 +1250,8 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
                         rows_ok |= (v ? 1u : 0u) << rt;
                     }
         }
+        crow += rstep + (cc.w + cstep.w >= segs ? 1 : 0);
+        pix_advance(cc, cstep, cd);
         const long long q0 = row * d.W + w0;
         g_okb = 0u;
         a_okb = 0u;
@@ -1313,13 +1315,17 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     const XcdRange xr = xcd_range(n_chunks);
     long long chunk = xr.first;
     if (chunk < xr.end) {
-        fetch(chunk);
+        cc = pix_coord(chunk, cd);
+        cstep = pix_coord(xr.stride, cd);
+        crow = chunk / segs;
+        rstep = xr.stride / segs;
+        fetch();
         stash();
     }
     __syncthreads();
     for (; chunk < xr.end; chunk += xr.stride) {
         const long long next = chunk + xr.stride;
-        if (next < xr.end) fetch(next);
+        if (next < xr.end) fetch();
         if (active) {
             // software pipeline over the 2-pixel K-steps: operands of step s+1 are read from LDS
             // before the MFMAs of step s are issued
