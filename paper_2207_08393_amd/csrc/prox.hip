@@ -1206,7 +1206,7 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
         const int p = v / Co4, c4 = v % Co4;
         g_lds[i] = v < n_g4 ? p * RSg + 4 * c4 : -1;
         g_dq[i] = p;
-        g_c[i] = 4 * c4;
+        g_c[i] = p * a.Co + 4 * c4;   // element offset from the chunk's first pixel
     }
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
@@ -1215,7 +1215,7 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
         const int p = r / Ci4, c4 = r % Ci4;
         a_lds[i] = v < n_a4 ? (rt * n_pa + p) * RSa + 4 * c4 : -1;
         a_dq[i] = v < n_a4 ? (int)rowtap_offset(rt, d) - d.kw / 2 + p : 0;
-        a_c[i] = 4 * c4;
+        a_c[i] = a_dq[i] * a.Ci + 4 * c4;   // element offset from the chunk's first pixel (may be negative)
         a_px[i] = p - d.kw / 2;
         a_rt[i] = v < n_a4 ? 1u << rt : 0u;
     }
@@ -1253,41 +1253,47 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
         crow += rstep + (cc.w + cstep.w >= segs ? 1 : 0);
         pix_advance(cc, cstep, cd);
         const long long q0 = row * d.W + w0;
+        const float* gbase = a.g + q0 * a.Co;   // uniform; per-slot offsets are 32-bit constants
+        const float* abase = a.a + q0 * a.Ci;
         g_okb = 0u;
         a_okb = 0u;
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
             const bool ok = g_lds[i] >= 0 && w0 + g_dq[i] < d.W;
-            rg[i] = *reinterpret_cast<const float4*>(a.g + (ok ? (q0 + g_dq[i]) * a.Co + g_c[i] : 0));
+            rg[i] = *reinterpret_cast<const float4*>(ok ? gbase + g_c[i] : a.g);
             g_okb |= (ok ? 1u : 0u) << i;
         }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
             const bool ok = (rows_ok & a_rt[i]) != 0u && (unsigned)(w0 + a_px[i]) < (unsigned)d.W;
-            ra[i] = *reinterpret_cast<const float4*>(a.a + (ok ? (q0 + a_dq[i]) * a.Ci + a_c[i] : 0));
+            ra[i] = *reinterpret_cast<const float4*>(ok ? abase + a_c[i] : a.a);
             a_okb |= (ok ? 1u : 0u) << i;
         }
     };
+    // masks and ReLU work on the bit patterns (integer max with 0 is ReLU): every ordinary vector
+    // instruction saved here is an issue slot returned to the MFMAs
     auto stash = [&]() {
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
-            const unsigned mk = ((g_okb >> i) & 1u) ? 0xffffffffu : 0u;
+            const int mk = -(int)((g_okb >> i) & 1u);
             float4 v = rg[i];
-            v.x = __uint_as_float(__float_as_uint(v.x) & mk); v.y = __uint_as_float(__float_as_uint(v.y) & mk);
-            v.z = __uint_as_float(__float_as_uint(v.z) & mk); v.w = __uint_as_float(__float_as_uint(v.w) & mk);
+            v.x = __int_as_float(__float_as_int(v.x) & mk); v.y = __int_as_float(__float_as_int(v.y) & mk);
+            v.z = __int_as_float(__float_as_int(v.z) & mk); v.w = __int_as_float(__float_as_int(v.w) & mk);
             if (g_lds[i] >= 0) *reinterpret_cast<float4*>(gs + g_lds[i]) = v;
-            bsum[i].x += v.x; bsum[i].y += v.y; bsum[i].z += v.z; bsum[i].w += v.w;
+            if (pa.bias_partial != nullptr) {
+                bsum[i].x += v.x; bsum[i].y += v.y; bsum[i].z += v.z; bsum[i].w += v.w;
+            }
         }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            const unsigned mk = ((a_okb >> i) & 1u) ? 0xffffffffu : 0u;
-            float4 v = ra[i];
-            v.x = __uint_as_float(__float_as_uint(v.x) & mk); v.y = __uint_as_float(__float_as_uint(v.y) & mk);
-            v.z = __uint_as_float(__float_as_uint(v.z) & mk); v.w = __uint_as_float(__float_as_uint(v.w) & mk);
+            const int mk = -(int)((a_okb >> i) & 1u);
+            int x0 = __float_as_int(ra[i].x), x1 = __float_as_int(ra[i].y), x2 = __float_as_int(ra[i].z), x3 = __float_as_int(ra[i].w);
             if (a.relu_in) {
-                v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+                x0 = x0 > 0 ? x0 : 0; x1 = x1 > 0 ? x1 : 0; x2 = x2 > 0 ? x2 : 0; x3 = x3 > 0 ? x3 : 0;
             }
-            if (a_lds[i] >= 0) *reinterpret_cast<float4*>(as + a_lds[i]) = v;
+            if (a_lds[i] >= 0)
+                *reinterpret_cast<float4*>(as + a_lds[i]) = make_float4(__int_as_float(x0 & mk), __int_as_float(x1 & mk),
+                                                                        __int_as_float(x2 & mk), __int_as_float(x3 & mk));
         }
     };
 
@@ -1908,7 +1914,8 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
         }
     }
     // (2) channel counts that are multiples of 4: register-prefetch pipelined MFMA kernel
-    if (a.Co % 4 == 0 && a.Ci % 4 == 0) {
+    const double max_off = (double)(d.kt / 2 + 1) * d.D * d.H * d.W * (a.Ci > a.Co ? a.Ci : a.Co);   // 32-bit slot offsets
+    if (a.Co % 4 == 0 && a.Ci % 4 == 0 && max_off < 2147483648.0) {
         const int n_pa = kWgTM + d.kw - 1;
         const int need_pg = (kWgTM * (a.Co / 4) + kConvThreads - 1) / kConvThreads;
         const int need_pa = (rowtaps * n_pa * (a.Ci / 4) + kConvThreads - 1) / kConvThreads;
