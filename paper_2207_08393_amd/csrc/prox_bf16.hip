@@ -316,7 +316,7 @@ __host__ __device__ inline int bw_row(int ch) { return (ch + 31) / 32 * 32 + 16;
 
 size_t wgrad_bf16_lds_bytes(int Co, int Ci, int kt, int kd, int kh, int kw) {
     const int rowtaps = kt * kd * kh, taps = rowtaps * kw;
-    const size_t buf = ((size_t)kBwTM * bw_row(Co) + (size_t)rowtaps * kBwSlab * bw_row(Ci) + (size_t)taps * kBwTM + 7) / 8 * 8;
+    const size_t buf = ((size_t)kBwTM * bw_row(Co) + (size_t)rowtaps * kBwSlab * bw_row(Ci) + 7) / 8 * 8;
     const size_t two = 2 * buf * sizeof(unsigned short);
     return two <= kBwLdsMax ? two : two / 2;   // double-buffered when it fits
 }
@@ -341,10 +341,10 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
     const int n_pa = kBwTM + KW - 1;
     const int CoP = bw_row(a.Co), CiP = bw_row(a.Ci);
     // two staging buffers, each: gs [kBwTM][CoP] (chunk pixel p, channel c), as [rowtaps][kBwSlab][CiP]
-    // (slab pixel pp = p + dw, channel c), vm [taps][kBwTM] (0xffff where (pixel, tap) is inside the grid)
-    const int as_off = kBwTM * CoP, vm_off = as_off + rowtaps * kBwSlab * CiP;
-    const int buf_elems = (vm_off + taps * kBwTM + 7) / 8 * 8;
-    __shared__ int all_valid[2];
+    // (slab pixel pp = p + dw, channel c).  A chunk is a 32-pixel segment of one image row; pixels past
+    // the row end get g = 0 and slab entries outside the grid are stored as 0, so the MFMA loop needs no masks.
+    const int as_off = kBwTM * CoP;
+    const int buf_elems = (as_off + rowtaps * kBwSlab * CiP + 7) / 8 * 8;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 31, h = lane >> 5;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32;
@@ -359,14 +359,15 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
 
     // Staging slots, the same for every chunk: slot i moves 16 bytes (8 channels of one pixel) from pixel
     // q0 + dq[i], channel col[i], to LDS offset lds[i].  Unused slots have lds < 0.
-    int g_dq[PG], g_col[PG], g_lds[PG];
-    int a_dq[PA], a_col[PA], a_lds[PA];
+    int g_dq[PG], g_off[PG], g_lds[PG];
+    int a_px[PA], a_off[PA], a_lds[PA];
+    unsigned a_rt[PA];
 #pragma unroll
     for (int i = 0; i < PG; ++i) {
         const int v = tid + i * NT;
         const int p = v / Co8, c8 = v % Co8;
         g_dq[i] = p;
-        g_col[i] = 8 * c8;
+        g_off[i] = p * a.Co + 8 * c8;   // element offset from the chunk's first pixel
         g_lds[i] = v < n_g8 ? p * CoP + 8 * c8 : -1;
     }
 #pragma unroll
@@ -374,8 +375,9 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
         const int v = tid + i * NT;
         const int rt = v / (n_pa * Ci8), r = v % (n_pa * Ci8);
         const int p = r / Ci8, c8 = r % Ci8;
-        a_dq[i] = v < n_a8 ? (int)rowtap_offset(rt, d) - KW / 2 + p : 0;
-        a_col[i] = 8 * c8;
+        a_px[i] = p - KW / 2;
+        a_off[i] = v < n_a8 ? ((int)rowtap_offset(rt, d) - KW / 2 + p) * a.Ci + 8 * c8 : 0;   // may be negative
+        a_rt[i] = v < n_a8 ? 1u << rt : 0u;
         a_lds[i] = v < n_a8 ? (rt * kBwSlab + p) * CiP + 8 * c8 : -1;
     }
 
@@ -388,30 +390,48 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
 
     // prefetch loads are unconditional (clamped address); validity is applied when they are stashed
     unsigned g_ok = 0u, a_ok = 0u;
-    auto fetch = [&](long long q0) {
+    // (segment, row, slice, frame) of the chunk to fetch, advanced chunk by chunk without divisions
+    const int segs = (d.W + kBwTM - 1) / kBwTM;
+    PixDims cd = d;
+    cd.W = segs;
+    PixCoord cc{0, 0, 0, 0}, cstep{0, 0, 0, 0};
+    long long crow = 0, rstep = 0;
+    auto fetch = [&]() {
+        const int w0 = cc.w * kBwTM;
+        unsigned rows_ok = 0u;
+        {
+            int rt = 0;
+            for (int it = 0; it < d.kt; ++it)
+                for (int id = 0; id < d.kd; ++id)
+                    for (int ih = 0; ih < d.kh; ++ih, ++rt) {
+                        const bool v = (unsigned)(cc.t + it - d.kt / 2) < (unsigned)d.T && (unsigned)(cc.dd + id - d.kd / 2) < (unsigned)d.D &&
+                                       (unsigned)(cc.h + ih - d.kh / 2) < (unsigned)d.H;
+                        rows_ok |= (v ? 1u : 0u) << rt;
+                    }
+        }
+        const long long q0 = crow * d.W + w0;
+        const unsigned short* gbase = a.g + q0 * a.Co;   // uniform; per-slot offsets are 32-bit constants
+        const unsigned short* abase = a.a + q0 * a.Ci;
+        crow += rstep + (cc.w + cstep.w >= segs ? 1 : 0);
+        pix_advance(cc, cstep, cd);
         g_ok = 0u;
         a_ok = 0u;
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
-            const long long qq = q0 + g_dq[i];
-            const bool ok = g_lds[i] >= 0 && qq < d.Q;
-            rg[i] = *reinterpret_cast<const uint4*>(a.g + (ok ? qq * a.Co + g_col[i] : 0));
+            const bool ok = g_lds[i] >= 0 && w0 + g_dq[i] < d.W;
+            rg[i] = *reinterpret_cast<const uint4*>(ok ? gbase + g_off[i] : a.g);
             g_ok |= (ok ? 1u : 0u) << i;
         }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            const long long qq = q0 + a_dq[i];
-            const bool ok = a_lds[i] >= 0 && qq >= 0 && qq < d.Q;
-            ra[i] = *reinterpret_cast<const uint4*>(a.a + (ok ? qq * a.Ci + a_col[i] : 0));
+            const bool ok = (rows_ok & a_rt[i]) != 0u && (unsigned)(w0 + a_px[i]) < (unsigned)d.W;
+            ra[i] = *reinterpret_cast<const uint4*>(ok ? abase + a_off[i] : a.a);
             a_ok |= (ok ? 1u : 0u) << i;
         }
     };
-    // pixel coordinates of this thread's validity pixel (threads below kBwTM), advanced chunk by chunk
-    PixCoord vc{0, 0, 0, 0}, vstep{0, 0, 0, 0};
-    auto stash = [&](long long q0, int buf) {
+    auto stash = [&](int buf) {
         unsigned short* gsT = smem16 + buf * buf_elems;
         unsigned short* asT = gsT + as_off;
-        unsigned short* vmT = gsT + vm_off;
 #pragma unroll
         for (int i = 0; i < PG; ++i) {
             if (g_lds[i] >= 0) {
@@ -437,16 +457,6 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
                 *reinterpret_cast<uint4*>(asT + a_lds[i]) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
             }
         }
-        if (tid < kBwTM) {
-            const unsigned vb = q0 + tid < d.Q ? tap_validity_at(vc, d) : 0u;
-            pix_advance(vc, vstep, d);
-            for (int t = 0; t < taps; ++t) vmT[t * kBwTM + tid] = ((vb >> t) & 1u) ? 0xffffu : 0u;
-            const unsigned full = taps >= 32 ? 0xffffffffu : ((1u << taps) - 1u);
-            const bool okall = vb == full;
-            // wave 0 holds threads 0..63 >= kBwTM: ballot over the first 32 lanes
-            const unsigned long long bal = __ballot(okall);
-            if (tid == 0) all_valid[buf] = (bal & 0xffffffffull) == 0xffffffffull;
-        }
     };
 
     floatx16 acc[JT];
@@ -466,20 +476,20 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
     // Pipeline over this workgroup's chunks c0, c1, ...: while the MFMAs of chunk i read LDS buffer i%2,
     // chunk i+1 (fetched one step earlier) is written to the other buffer and chunk i+2 is requested from
     // HBM; one barrier per chunk.  Layers whose two buffers do not fit LDS use one buffer and two barriers.
-    const long long n_chunks = (d.Q + kBwTM - 1) / kBwTM;
+    const long long n_chunks = (d.Q / d.W) * segs;
     const XcdRange xr = xcd_range(n_chunks);
     long long chunk = xr.first;
-    if (tid < kBwTM) {
-        vc = pix_coord((chunk < xr.end ? chunk : 0) * kBwTM + tid, d);
-        vstep = pix_coord(xr.stride * kBwTM, d);
+    if (chunk < xr.end) {
+        cc = pix_coord(chunk, cd);
+        cstep = pix_coord(xr.stride, cd);
+        crow = chunk / segs;
+        rstep = xr.stride / segs;
     }
     auto compute = [&](int buf) {
         if (active) {
             const unsigned short* base = smem16 + buf * buf_elems;
-            const bool fast = all_valid[buf] != 0;
 #pragma unroll
             for (int kb = 0; kb < kBwTM / 16; ++kb) {
-                const int px = 16 * kb + 8 * h;   // this lane's first pixel of the K-block
                 const uint2 g0 = lds_read_tr16(base + g_rd + (16 * kb) * CoP), g1 = lds_read_tr16(base + g_rd + (16 * kb + 4) * CoP);
                 const bf16x8 gv = __builtin_bit_cast(bf16x8, make_uint4(g0.x, g0.y, g1.x, g1.y));
 #pragma unroll
@@ -503,11 +513,6 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
                             b.z = __builtin_amdgcn_alignbit(dws[dw / 2 + 3], dws[dw / 2 + 2], 16);
                             b.w = __builtin_amdgcn_alignbit(dws[dw / 2 + 4], dws[dw / 2 + 3], 16);
                         }
-                        if (!fast) {
-                            const int tap = tap0 + j < taps ? tap0 + j : taps - 1;
-                            const uint4 mk = *reinterpret_cast<const uint4*>(base + vm_off + tap * kBwTM + px);
-                            b.x &= mk.x; b.y &= mk.y; b.z &= mk.z; b.w &= mk.w;
-                        }
                         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b), acc[j], 0, 0, 0);
                     }
                 }
@@ -516,32 +521,32 @@ __global__ __launch_bounds__(NW * 64) void wgrad_bf16_kernel(WgradBf16Args a) {
     };
     if (a.two_buf) {
         if (chunk < xr.end) {
-            fetch(chunk * kBwTM);
-            stash(chunk * kBwTM, 0);
-            if (chunk + xr.stride < xr.end) fetch((chunk + xr.stride) * kBwTM);
+            fetch();
+            stash(0);
+            if (chunk + xr.stride < xr.end) fetch();
         }
         __syncthreads();
         int buf = 0;
         for (; chunk < xr.end; chunk += xr.stride) {
             const long long next = chunk + xr.stride, next2 = next + xr.stride;
-            if (next < xr.end) stash(next * kBwTM, buf ^ 1);
-            if (next2 < xr.end) fetch(next2 * kBwTM);
+            if (next < xr.end) stash(buf ^ 1);
+            if (next2 < xr.end) fetch();
             compute(buf);
             __syncthreads();
             buf ^= 1;
         }
     } else {   // one buffer (large layers): write the next chunk between two barriers
         if (chunk < xr.end) {
-            fetch(chunk * kBwTM);
-            stash(chunk * kBwTM, 0);
+            fetch();
+            stash(0);
         }
         __syncthreads();
         for (; chunk < xr.end; chunk += xr.stride) {
             const long long next = chunk + xr.stride;
-            if (next < xr.end) fetch(next * kBwTM);
+            if (next < xr.end) fetch();
             compute(0);
             __syncthreads();
-            if (next < xr.end) stash(next * kBwTM, 0);
+            if (next < xr.end) stash(0);
             __syncthreads();
         }
     }
@@ -596,8 +601,8 @@ hipError_t launch_wgrad_bf16(const WgradBf16Args& a_in, int n_split, hipStream_t
     constexpr int NW = 8, NT = NW * 64;
     size_t lds = wgrad_bf16_lds_bytes(a.Co, a.Ci, d.kt, d.kd, d.kh, d.kw);
     {
-        const size_t one = ((size_t)kBwTM * bw_row(a.Co) + (size_t)(d.kt * d.kd * d.kh) * kBwSlab * bw_row(a.Ci) +
-                            (size_t)(d.kt * d.kd * d.kh * d.kw) * kBwTM + 7) / 8 * 8 * sizeof(unsigned short);
+        const size_t one = ((size_t)kBwTM * bw_row(a.Co) + (size_t)(d.kt * d.kd * d.kh) * kBwSlab * bw_row(a.Ci) + 7) / 8 * 8 *
+                           sizeof(unsigned short);
         a.two_buf = 2 * one <= kBwLdsMax ? 1 : 0;
     }
     const size_t red = (size_t)2 * NT * 8 * sizeof(float);
