@@ -54,6 +54,10 @@ struct ProxPlan {
     size_t ws_bytes;
     size_t w_off[kMaxLayers], b_off[kMaxLayers];  // float offsets into theta
     int n_split;                      // split-K workgroups of the weight-gradient kernels
+    // t_j is stored after the ReLU of its only consumer (layer j+1 has relu_in, no layer takes t_j as a
+    // skip source, and the producing layer adds no skip): the consumer then needs no ReLU on its operand,
+    // and "stored value > 0" is the same ReLU mask for the backward pass.
+    bool post_relu[kMaxLayers + 1];
 };
 
 // LDS bytes the weight-gradient kernel needs for one layer (must stay below the 160 KB of a CU).

@@ -1710,6 +1710,12 @@ bool prox_bf16_supported(const gleam_prox_desc& p) {
 }
 
 void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
+    for (int t = 0; t <= kMaxLayers; ++t) plan.post_relu[t] = false;
+    for (int t = 1; t < p.n_layers; ++t) {
+        bool ok = p.layers[t].relu_in != 0 && p.layers[t - 1].skip_src < 0;
+        for (int l = 0; l < p.n_layers; ++l) ok = ok && p.layers[l].skip_src != t;
+        plan.post_relu[t] = ok;
+    }
     const int L = p.n_layers;
     plan.L = L;
     plan.Q = g.B * g.T * g.D * g.H * g.W;
@@ -1788,7 +1794,8 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
         a.bias = c.has_bias ? theta + plan.b_off[l] : nullptr;
         a.add = c.skip_src >= 0 ? reinterpret_cast<const float*>(act_base + plan.act_off[c.skip_src]) : nullptr;
         a.K = c.cin; a.Nn = c.cout;
-        a.relu_in = c.relu_in; a.relu_out = c.relu_out;
+        a.relu_in = (c.relu_in && !plan.post_relu[l]) ? 1 : 0;
+        a.relu_out = (c.relu_out || (l + 1 < L && plan.post_relu[l + 1])) ? 1 : 0;
         a.d = pix_dims(g, c);
         hipError_t e;
         if (p.dtype == 1) {
@@ -1810,7 +1817,7 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
                 b.add = a.add;
                 b.K = c.cin; b.Nn = c.cout;
                 b.out_f32 = (l == L - 1) ? 1 : 0;
-                b.relu_in = c.relu_in; b.relu_out = c.relu_out;
+                b.relu_in = a.relu_in; b.relu_out = a.relu_out;
                 b.d = a.d;
                 e = launch_conv_bf16(b, cw.w, cw.sn, cw.st, cw.sk, 0,
                                      reinterpret_cast<unsigned short*>((unsigned char*)ws + plan.wimg_off_fwd), st);
@@ -2008,7 +2015,7 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         // weight gradient (+ bias gradient)
         WgradArgs wa{};
         wa.g = G(l); wa.a = act(l - 1); wa.partial = partial;
-        wa.Co = c.cout; wa.Ci = c.cin; wa.relu_in = c.relu_in; wa.d = d;
+        wa.Co = c.cout; wa.Ci = c.cin; wa.relu_in = (c.relu_in && !plan.post_relu[l - 1]) ? 1 : 0; wa.d = d;
         float* bpart = reinterpret_cast<float*>(wsb + plan.bias_partial_off);
         bool bias_done = false;
         int used_split = plan.n_split;
@@ -2027,7 +2034,7 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                 wb.a = reinterpret_cast<const unsigned short*>(wa.a);
                 wb.partial = partial;
                 wb.bias_partial = c.has_bias ? bpart : nullptr;
-                wb.Co = c.cout; wb.Ci = c.cin; wb.relu_in = c.relu_in; wb.d = d;
+                wb.Co = c.cout; wb.Ci = c.cin; wb.relu_in = wa.relu_in; wb.d = d;
                 e = launch_wgrad_bf16(wb, plan.n_split, st);
                 bias_done = c.has_bias;
             }
