@@ -13,6 +13,8 @@
 
 #include <cstdio>
 
+#include <type_traits>
+
 #include "prox_common.h"
 
 namespace gleam {
@@ -153,10 +155,14 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
     PixCoord qc = pix_coord(q < d.Q ? q : 0, d);
     const PixCoord qstep = pix_coord(xr.stride * TM, d);
     unsigned vbits = 0u;
+    bool tile_masked = true;
+    const int n_taps = rowtaps * kw;
+    const unsigned all_taps = n_taps >= 32 ? 0xffffffffu : (1u << n_taps) - 1u;
     floatx16 acc[NJ];
     auto step = [&](const uint4* slab, uint4* nxt) {
         if (ci.c == 0) {
             vbits = q < d.Q ? tap_validity_at(qc, d) : 0u;
+            tile_masked = __builtin_amdgcn_ballot_w64(vbits != all_taps) != 0ull;   // wave-uniform
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -168,25 +174,34 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
         if (ntile < xr.end) issue(ntile, nci, nxt);
         const uint4* wl = slab + slab_ops * 64 + wa_lane;
         const int rt = ci.rt;
+        // MASKED: some lane of this wave has a tap outside the grid in this tile (zero padding); interior
+        // tiles take the path without the per-operand AND (ordinary vector instructions cost MFMA issue slots)
+        auto units = [&](auto masked) {
+            constexpr bool MASKED = decltype(masked)::value;
 #pragma unroll
-        for (int dw = 0; dw < KWM; ++dw) {
-            if (KW == 0 && dw >= kw) continue;
-            const unsigned okm = ((vbits >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
+            for (int dw = 0; dw < KWM; ++dw) {
+                if (KW == 0 && dw >= kw) continue;
+                const unsigned okm = ((vbits >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                uint4 pb = slab[p_off[dw][g]];
-                if (RELU) {
-                    pb.x = relu_bf16x2(pb.x); pb.y = relu_bf16x2(pb.y); pb.z = relu_bf16x2(pb.z); pb.w = relu_bf16x2(pb.w);
-                }
-                pb.x &= okm; pb.y &= okm; pb.z &= okm; pb.w &= okm;   // zero padding: tap outside the grid
-                const bf16x8 pv = __builtin_bit_cast(bf16x8, pb);
+                for (int g = 0; g < G; ++g) {
+                    uint4 pb = slab[p_off[dw][g]];
+                    if (RELU) {
+                        pb.x = relu_bf16x2(pb.x); pb.y = relu_bf16x2(pb.y); pb.z = relu_bf16x2(pb.z); pb.w = relu_bf16x2(pb.w);
+                    }
+                    if (MASKED) {
+                        pb.x &= okm; pb.y &= okm; pb.z &= okm; pb.w &= okm;
+                    }
+                    const bf16x8 pv = __builtin_bit_cast(bf16x8, pb);
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) {
-                    const uint4 wa = wl[(dw * G + g) * 2 * NB + 32 * j];
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa), pv, acc[j], 0, 0, 0);
+                    for (int j = 0; j < NJ; ++j) {
+                        const uint4 wa = wl[(dw * G + g) * 2 * NB + 32 * j];
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa), pv, acc[j], 0, 0, 0);
+                    }
                 }
             }
-        }
+        };
+        if (tile_masked) units(std::true_type{});
+        else units(std::false_type{});
         if (last && q < d.Q) {
             // lane holds pixel q and, per register group, 4 consecutive output channels
 #pragma unroll
