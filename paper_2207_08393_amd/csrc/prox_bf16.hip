@@ -56,9 +56,11 @@ size_t conv_bf16_wimg_elems(int K, int Nn, int taps) {
 }
 
 // ------------------------------------------------------------------ forward / data gradient
-template <int NB, int KW, bool RELU>
+// A wave owns 32*PJ pixels x NB output channels: every weight operand read from LDS feeds PJ MFMAs and
+// every pixel operand NB/32 of them (the kernel is bound by LDS operand bandwidth, not by the MFMA rate).
+template <int NB, int KW, bool RELU, int PJ>
 __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
-    constexpr int NW = 4, TM = 128, G = kBfCK / 16, NJ = NB / 32, QP = kBfCK / 8;   // QP quads per pixel row
+    constexpr int NW = 4, TM = NW * 32 * PJ, G = kBfCK / 16, NJ = NB / 32, QP = kBfCK / 8;   // QP quads per pixel row
     constexpr int RP = 8 / QP;                 // pixel rows per 128 bytes of LDS (QP = 4 -> 2)
     constexpr int KWM = KW > 0 ? KW : 5;
     constexpr int kSlabOpsMax = ((TM + KWM - 1) * QP + 63) / 64, kWOpsMax = (KWM * kBfCK * NB / 8 + 63) / 64;
@@ -133,14 +135,16 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
     };
 
     // quad index of this lane's pixel operand for every (tap along W, 16-channel K-block)
-    int p_off[KWM][G];
+    int p_off[PJ][KWM][G];
 #pragma unroll
-    for (int dw = 0; dw < KWM; ++dw) {
-        const int pix = wave * 32 + m + dw;
-        const int key = (pix / RP) % QP;
+    for (int pj = 0; pj < PJ; ++pj)
 #pragma unroll
-        for (int g = 0; g < G; ++g) p_off[dw][g] = pix * QP + ((2 * g + h) ^ key);
-    }
+        for (int dw = 0; dw < KWM; ++dw) {
+            const int pix = wave * (32 * PJ) + 32 * pj + m + dw;
+            const int key = (pix / RP) % QP;
+#pragma unroll
+            for (int g = 0; g < G; ++g) p_off[pj][dw][g] = pix * QP + ((2 * g + h) ^ key);
+        }
     const int wa_lane = h * NB + m;
 
     const XcdRange xr = xcd_range(n_tiles);
@@ -151,22 +155,31 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
     __syncthreads();
 
     // this lane's pixel of the current tile, tracked by coordinates (no divisions per tile)
-    long long q = (tile < xr.end ? tile : 0) * TM + wave * 32 + m;
-    PixCoord qc = pix_coord(q < d.Q ? q : 0, d);
+    long long q0 = (tile < xr.end ? tile : 0) * TM + wave * (32 * PJ) + m;   // pixel of pj = 0; pj adds 32
+    PixCoord qc[PJ];
+#pragma unroll
+    for (int pj = 0; pj < PJ; ++pj) qc[pj] = pix_coord(q0 + 32 * pj < d.Q ? q0 + 32 * pj : 0, d);
     const PixCoord qstep = pix_coord(xr.stride * TM, d);
-    unsigned vbits = 0u;
+    unsigned vbits[PJ];
     bool tile_masked = true;
     const int n_taps = rowtaps * kw;
     const unsigned all_taps = n_taps >= 32 ? 0xffffffffu : (1u << n_taps) - 1u;
-    floatx16 acc[NJ];
+    floatx16 acc[PJ][NJ];
     auto step = [&](const uint4* slab, uint4* nxt) {
         if (ci.c == 0) {
-            vbits = q < d.Q ? tap_validity_at(qc, d) : 0u;
-            tile_masked = __builtin_amdgcn_ballot_w64(vbits != all_taps) != 0ull;   // wave-uniform
+            bool any = false;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
+            for (int pj = 0; pj < PJ; ++pj) {
+                vbits[pj] = q0 + 32 * pj < d.Q ? tap_validity_at(qc[pj], d) : 0u;
+                any = any || vbits[pj] != all_taps;
+            }
+            tile_masked = __builtin_amdgcn_ballot_w64(any) != 0ull;   // wave-uniform
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+            for (int pj = 0; pj < PJ; ++pj)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
         }
         const bool last = ci.c + 1 == nck;
         const long long ntile = last ? tile + xr.stride : tile;
@@ -181,29 +194,39 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
 #pragma unroll
             for (int dw = 0; dw < KWM; ++dw) {
                 if (KW == 0 && dw >= kw) continue;
-                const unsigned okm = ((vbits >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    uint4 pb = slab[p_off[dw][g]];
-                    if (RELU) {
-                        pb.x = relu_bf16x2(pb.x); pb.y = relu_bf16x2(pb.y); pb.z = relu_bf16x2(pb.z); pb.w = relu_bf16x2(pb.w);
+                    bf16x8 pv[PJ];
+#pragma unroll
+                    for (int pj = 0; pj < PJ; ++pj) {
+                        uint4 pb = slab[p_off[pj][dw][g]];
+                        if (RELU) {
+                            pb.x = relu_bf16x2(pb.x); pb.y = relu_bf16x2(pb.y); pb.z = relu_bf16x2(pb.z); pb.w = relu_bf16x2(pb.w);
+                        }
+                        if (MASKED) {
+                            const unsigned okm = ((vbits[pj] >> (rt * kw + dw)) & 1u) ? 0xffffffffu : 0u;
+                            pb.x &= okm; pb.y &= okm; pb.z &= okm; pb.w &= okm;
+                        }
+                        pv[pj] = __builtin_bit_cast(bf16x8, pb);
                     }
-                    if (MASKED) {
-                        pb.x &= okm; pb.y &= okm; pb.z &= okm; pb.w &= okm;
-                    }
-                    const bf16x8 pv = __builtin_bit_cast(bf16x8, pb);
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) {
-                        const uint4 wa = wl[(dw * G + g) * 2 * NB + 32 * j];
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa), pv, acc[j], 0, 0, 0);
+                        const bf16x8 wv = __builtin_bit_cast(bf16x8, wl[(dw * G + g) * 2 * NB + 32 * j]);
+#pragma unroll
+                        for (int pj = 0; pj < PJ; ++pj)
+                            acc[pj][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, pv[pj], acc[pj][j], 0, 0, 0);
                     }
                 }
             }
         };
         if (tile_masked) units(std::true_type{});
         else units(std::false_type{});
-        if (last && q < d.Q) {
+        if (last) {
             // lane holds pixel q and, per register group, 4 consecutive output channels
+#pragma unroll
+            for (int pj = 0; pj < PJ; ++pj) {
+            const long long q = q0 + 32 * pj;
+            if (q >= d.Q) continue;
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -213,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
                     const long long o = q * a.Nn + co0;
                     if (!a.out_f32 && (a.Nn % 4) == 0) {
                         // four consecutive bf16 channels = one 8-byte access
-                        float x[4] = {acc[j][4 * rg], acc[j][4 * rg + 1], acc[j][4 * rg + 2], acc[j][4 * rg + 3]};
+                        float x[4] = {acc[pj][j][4 * rg], acc[pj][j][4 * rg + 1], acc[pj][j][4 * rg + 2], acc[pj][j][4 * rg + 3]};
                         if (a.bias) {
                             const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0);
                             x[0] += bv.x; x[1] += bv.y; x[2] += bv.z; x[3] += bv.w;
@@ -244,7 +267,7 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         if (co0 + i >= a.Nn) break;
-                        float x = acc[j][4 * rg + i];
+                        float x = acc[pj][j][4 * rg + i];
                         if (a.bias) x += a.bias[co0 + i];
                         if (a.relu_out) x = fmaxf(x, 0.f);
                         const float ref = a.mask_ref ? bf16_to_f32(a.mask_ref[o + i]) : 1.f;
@@ -258,12 +281,14 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
                         else reinterpret_cast<unsigned short*>(a.out)[o + i] = f32_to_bf16(x);
                     }
                 }
+            }
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (last) {
-            q += xr.stride * TM;
-            pix_advance(qc, qstep, d);
+            q0 += xr.stride * TM;
+#pragma unroll
+            for (int pj = 0; pj < PJ; ++pj) pix_advance(qc[pj], qstep, d);
         }
         tile = ntile;
         ci = nci;
@@ -275,9 +300,9 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
     }
 }
 
-template <int NB, int KW>
+template <int NB, int KW, int PJ>
 static void launch_conv_bf16_k(const ConvBf16Args& a, hipStream_t st) {
-    constexpr int TM = 128, QP = kBfCK / 8, KWM = KW > 0 ? KW : 5;
+    constexpr int TM = 128 * PJ, QP = kBfCK / 8, KWM = KW > 0 ? KW : 5;
     constexpr size_t lds = (size_t)2 * (((TM + KWM - 1) * QP + 63) / 64 + (KWM * kBfCK * NB / 8 + 63) / 64) * 1024;
     const long long n_tiles = (a.d.Q + TM - 1) / TM;
     int per_cu = (int)(160 * 1024 / lds);
@@ -286,8 +311,8 @@ static void launch_conv_bf16_k(const ConvBf16Args& a, hipStream_t st) {
     const long long cap = 256LL * per_cu;
     const long long gx = ((n_tiles < cap ? n_tiles : cap) + 7) / 8 * 8;
     dim3 grid((unsigned)gx, (a.Nn + NB - 1) / NB);
-    if (a.relu_in) hipLaunchKernelGGL((conv_bf16_kernel<NB, KW, true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((conv_bf16_kernel<NB, KW, false>), grid, dim3(256), 0, st, a);
+    if (a.relu_in) hipLaunchKernelGGL((conv_bf16_kernel<NB, KW, true, PJ>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((conv_bf16_kernel<NB, KW, false, PJ>), grid, dim3(256), 0, st, a);
 }
 
 hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long sn, long long st_, long long sk, int flip,
@@ -309,13 +334,13 @@ hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long 
     snprintf(name, sizeof(name), "conv_bf16_%s_%dto%d_t%d", flip ? "dgrad" : "fwd", a.K, a.Nn, taps);
     KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps, 2.0 * (double)a.d.Q * (a.K + a.Nn), stream);
     if (nb == 32) {
-        if (a.d.kw == 3) launch_conv_bf16_k<32, 3>(a, stream);
-        else if (a.d.kw == 1) launch_conv_bf16_k<32, 1>(a, stream);
-        else launch_conv_bf16_k<32, 0>(a, stream);
+        if (a.d.kw == 3) launch_conv_bf16_k<32, 3, 1>(a, stream);
+        else if (a.d.kw == 1) launch_conv_bf16_k<32, 1, 1>(a, stream);
+        else launch_conv_bf16_k<32, 0, 1>(a, stream);
     } else {
-        if (a.d.kw == 3) launch_conv_bf16_k<64, 3>(a, stream);
-        else if (a.d.kw == 1) launch_conv_bf16_k<64, 1>(a, stream);
-        else launch_conv_bf16_k<64, 0>(a, stream);
+        if (a.d.kw == 3) launch_conv_bf16_k<64, 3, 1>(a, stream);
+        else if (a.d.kw == 1) launch_conv_bf16_k<64, 1, 1>(a, stream);
+        else launch_conv_bf16_k<64, 0, 1>(a, stream);
     }
     return hipGetLastError();
 }
