@@ -30,14 +30,14 @@ PEAK_HBM_GBS = 8000.0
 # profiles/module_step_knee2d_hbm_traffic.txt.  Scaling: the 256 MiB calibration copy reads 131 100 KiB on
 # FETCH_SIZE (factor 2.0: the counter under-reports 128-byte requests) and 262 144 KiB on WRITE_SIZE (1.0).
 MEASURED_TRAFFIC = {
-    "conv_dlds_kernel<64,16,1,4,3> fwd+dgrad 64->64 3x3": 1.706e5 * 1024 * 2.0 + 1.339e5 * 1024 * 1.0,
-    "wgrad_pipe_kernel<3,1,3,12> wgrad 64->64 3x3": 1.185e5 * 1024 * 2.0 + 3.693e4 * 1024 * 1.0,
+    "conv_dlds_kernel<64,16,1,4,3,RELU> fwd+dgrad 64->64 3x3": 1.694e5 * 1024 * 2.0 + 1.413e5 * 1024 * 1.0,
+    "wgrad_pipe_kernel<3,1,3,12> wgrad 64->64 3x3": 1.184e5 * 1024 * 2.0 + 3.693e4 * 1024 * 1.0,
 }
 
 # library launch label -> GPU kernel it runs (forward and data gradient of a 64->64 layer are one kernel)
 KERNEL_OF = {
-    "conv_fwd_64to64_t9": "conv_dlds_kernel<64,16,1,4,3> fwd+dgrad 64->64 3x3",
-    "conv_dgrad_64to64_t9": "conv_dlds_kernel<64,16,1,4,3> fwd+dgrad 64->64 3x3",
+    "conv_fwd_64to64_t9": "conv_dlds_kernel<64,16,1,4,3,RELU> fwd+dgrad 64->64 3x3",
+    "conv_dgrad_64to64_t9": "conv_dlds_kernel<64,16,1,4,3,RELU> fwd+dgrad 64->64 3x3",
     "conv_wgrad_64to64_t9": "wgrad_pipe_kernel<3,1,3,12> wgrad 64->64 3x3",
 }
 
