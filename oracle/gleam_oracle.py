@@ -16,10 +16,16 @@ product.  Everything is float64 / complex128 numpy, written as the plain definit
   * backward : analytic reverse sweep for dL/dtheta of this module only (Alg. 1, gradient step);
                nothing is propagated to x_in, S or y (decoupled modules).
 
+  * greedy   : Alg. 1 for one mini-batch: modules in order, each with its own parameters, local loss,
+               local gradient and Adam update (beta1 = 0.9, beta2 = 0.999, Implementation Details); the
+               detached output of module m is the input of module m + 1
+  * Adam     : Kingma & Ba's update with bias correction (the optimizer the paper names)
+
 Pins (tests/test_oracle_*.py): numpy.fft and closed forms for the DFT, the adjoint identity, the
 full-sampling identity A^H A = I, circular-convolution form of a single-coil 1D mask, scipy
 correlate and torch CPU convolutions for the prox, central finite differences and torch autograd
-for the gradient.  No function here is unpinned.
+for the gradient; torch.optim.Adam, the closed-form first step and a two-module torch autograd model
+with a detached hand-off for the greedy iteration.  No function here is unpinned.
 
 Array layouts: image [B,T,D,H,W], coils [B,C,D,H,W], mask [B,T,D,H,W], k-space [B,C,T,D,H,W],
 activations [B,T,D,H,W,channels] (an image is its own 2-channel activation: re, im).
@@ -260,3 +266,44 @@ def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None):
 def module_bwd(prox, theta, fwd):
     """dL/dtheta_m of the local objective; stops at the module input."""
     return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"])
+
+
+# ----------------------------------------------------------------------------- greedy training (Alg. 1)
+def adam_step(theta, grad, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam update (the optimizer named in Implementation Details), step count t >= 1:
+        m <- beta1 m + (1 - beta1) g ;  v <- beta2 v + (1 - beta2) g^2
+        theta <- theta - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+    Returns (theta, m, v) as new float64 arrays."""
+    theta = np.asarray(theta, np.float64)
+    g = np.asarray(grad, np.float64)
+    m = beta1 * np.asarray(m, np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, np.float64) + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    return theta - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
+
+
+def greedy_iteration(geom, prox, x0, S, M, y, alpha, thetas, ms, vs, t, lr, x_ref, beta1=0.9, beta2=0.999, eps=1e-8):
+    """Alg. 1 for one mini-batch: for module i = 1..len(thetas): forward x_i = f_theta_i(DC(x_{i-1})), local
+    loss against x_ref, gradient of that loss with respect to theta_i only, Adam update of theta_i; the
+    activations of the module are dropped and x_i is handed on as a constant.
+    Returns (x_final, losses, thetas, ms, vs) with the updated per-module lists."""
+    x = np.asarray(x0, np.complex128)
+    losses, new_t, new_m, new_v = [], [], [], []
+    for th, m, v in zip(thetas, ms, vs):
+        f = module_fwd(geom, prox, x, S, M, y, alpha, th, x_ref)
+        g = module_bwd(prox, th, f)
+        th2, m2, v2 = adam_step(th, g, m, v, t, lr, beta1, beta2, eps)
+        losses.append(f["loss"])
+        new_t.append(th2); new_m.append(m2); new_v.append(v2)
+        x = f["x_out"]          # computed with the parameters before the update; detached hand-off
+    return x, losses, new_t, new_m, new_v
+
+
+def unrolled_inference(geom, prox, x0, S, M, y, alpha, thetas):
+    """x_i = f_theta_i(DC(x_{i-1})) through the given modules (all of them, or the first N_inf: Alg. 1's
+    modules can be evaluated up to any depth)."""
+    x = np.asarray(x0, np.complex128)
+    for th in thetas:
+        x = module_fwd(geom, prox, x, S, M, y, alpha, th)["x_out"]
+    return x
