@@ -114,6 +114,48 @@ int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const 
                      const void* saved, size_t saved_bytes, float* grad_theta,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* Adam hyper-parameters (Implementation Details: beta1 = 0.9, beta2 = 0.999; the paper does not state the
+ * learning rate or epsilon). */
+typedef struct {
+    float lr, beta1, beta2, eps;
+} gleam_adam;
+
+/* One Adam update of n parameters in place ("Update Parameters" of Alg. 1), step count t >= 1:
+ *     m <- beta1 m + (1-beta1) g ;  v <- beta2 v + (1-beta2) g^2
+ *     theta <- theta - lr * (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps)
+ * theta, grad, m, v: device float32 arrays of n elements; m and v are the optimizer state (zero before the
+ * first step).  The bias corrections are evaluated on the host in double. */
+int gleam_adam_step(const gleam_adam* hyper, int64_t t, size_t n, float* theta, const float* grad,
+                    float* m, float* v, void* stream);
+
+/* One greedy training iteration over a mini-batch (Alg. 1): for module i = 1..n_modules, forward
+ * x_i = f_theta_i(DC(x_{i-1})), local loss against x_ref (Eq. 10), gradient of that loss with respect to
+ * theta_i only, Adam update of theta_i; the module's activations are then dropped (`saved` and `ws` are
+ * reused by the next module) and x_i is handed on without gradient.
+ *   x0        : input image of module 1 (e.g. the zero-filled reconstruction A^H y); not written.
+ *   theta     : [n_modules][n_theta] float32, updated in place (n_theta = gleam_theta_count).
+ *   adam_m/_v : optimizer state, same shape as theta.
+ *   t         : Adam step count of this iteration (>= 1), the same for every module.
+ *   x_out     : x_{n_modules}, overwritten.  x_tmp: one more image of scratch (the modules alternate between
+ *               the two).  Neither may alias x0.
+ *   losses    : device float32 [n_modules], loss of every module before its update.
+ *   grad      : device scratch of n_theta floats.
+ * Every module's output is computed with its parameters BEFORE the update.  All modules share the
+ * architecture `prox`.  Other arguments as in gleam_module_fwd. */
+int gleam_greedy_iteration(const gleam_geom* geom, const gleam_prox_desc* prox, int n_modules,
+                           const gleam_c64* x0, const gleam_c64* S, const uint8_t* M, const gleam_c64* y,
+                           float alpha, float* theta, float* adam_m, float* adam_v, const gleam_adam* hyper,
+                           int64_t t, const gleam_c64* x_ref, gleam_c64* x_out, gleam_c64* x_tmp,
+                           float* losses, float* grad, void* saved, size_t saved_bytes, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/* Inference through the first n_modules modules (all of them, or fewer: early exit at depth N_inf),
+ * x_i = f_theta_i(DC(x_{i-1})); nothing is saved.  theta: [n_modules][n_theta]; x_out, x_tmp as above. */
+int gleam_unrolled_infer(const gleam_geom* geom, const gleam_prox_desc* prox, int n_modules,
+                         const gleam_c64* x0, const gleam_c64* S, const uint8_t* M, const gleam_c64* y,
+                         float alpha, const float* theta, gleam_c64* x_out, gleam_c64* x_tmp,
+                         void* ws, size_t ws_bytes, void* stream);
+
 /* Measurement aid (not part of the method): between gleam_profile_begin and gleam_profile_end every kernel
  * this library launches is bracketed by HIP events on the caller's stream.  gleam_profile_end synchronises
  * the device and copies up to `capacity` per-launch records (launch order) to the HOST array `out`;

@@ -41,6 +41,10 @@ class gleam_kernel_record(C.Structure):
     _fields_ = [("name", C.c_char * 56), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
 
 
+class gleam_adam(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+
+
 class GleamError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -68,6 +72,10 @@ def lib() -> C.CDLL:
         L.gleam_sense_normal.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
         L.gleam_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_module_bwd.argtypes = [pg, pp, vp, vp, sz, vp, vp, sz, vp]
+        L.gleam_adam_step.argtypes = [C.POINTER(gleam_adam), C.c_int64, sz, vp, vp, vp, vp, vp]
+        L.gleam_greedy_iteration.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, C.POINTER(gleam_adam),
+                                             C.c_int64, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.gleam_unrolled_infer.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, sz, vp]
         L.gleam_profile_begin.argtypes = []
         L.gleam_profile_end.argtypes = [C.POINTER(gleam_kernel_record), C.c_int, C.POINTER(C.c_int)]
         _lib = L
@@ -75,8 +83,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
-           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_profile_begin",
-           "gleam_profile_end")
+           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_adam_step",
+           "gleam_greedy_iteration", "gleam_unrolled_infer", "gleam_profile_begin", "gleam_profile_end")
 
 
 def strerror(status: int) -> str:
@@ -159,6 +167,29 @@ def gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref, x_out, loss
 def gleam_module_bwd(geom, prox, theta, saved, grad_theta, ws, stream=None):
     _check(lib().gleam_module_bwd(C.byref(geom), C.byref(prox), _ptr(theta), _ptr(saved), _nbytes(saved),
                                   _ptr(grad_theta), _ptr(ws), _nbytes(ws), _stream(stream)), "gleam_module_bwd")
+
+
+def make_adam(lr, beta1=0.9, beta2=0.999, eps=1e-8) -> gleam_adam:
+    return gleam_adam(float(lr), float(beta1), float(beta2), float(eps))
+
+
+def gleam_adam_step(hyper, t, theta, grad, m, v, stream=None):
+    _check(lib().gleam_adam_step(C.byref(hyper), int(t), theta.numel(), _ptr(theta), _ptr(grad), _ptr(m), _ptr(v),
+                                 _stream(stream)), "gleam_adam_step")
+
+
+def gleam_greedy_iteration(geom, prox, n_modules, x0, S, M, y, alpha, theta, adam_m, adam_v, hyper, t, x_ref, x_out,
+                           x_tmp, losses, grad, saved, ws, stream=None):
+    _check(lib().gleam_greedy_iteration(C.byref(geom), C.byref(prox), int(n_modules), _ptr(x0), _ptr(S), _ptr(M), _ptr(y),
+                                        C.c_float(alpha), _ptr(theta), _ptr(adam_m), _ptr(adam_v), C.byref(hyper), int(t),
+                                        _ptr(x_ref), _ptr(x_out), _ptr(x_tmp), _ptr(losses), _ptr(grad), _ptr(saved),
+                                        _nbytes(saved), _ptr(ws), _nbytes(ws), _stream(stream)), "gleam_greedy_iteration")
+
+
+def gleam_unrolled_infer(geom, prox, n_modules, x0, S, M, y, alpha, theta, x_out, x_tmp, ws, stream=None):
+    _check(lib().gleam_unrolled_infer(C.byref(geom), C.byref(prox), int(n_modules), _ptr(x0), _ptr(S), _ptr(M), _ptr(y),
+                                      C.c_float(alpha), _ptr(theta), _ptr(x_out), _ptr(x_tmp), _ptr(ws), _nbytes(ws),
+                                      _stream(stream)), "gleam_unrolled_infer")
 
 
 def gleam_profile_begin():

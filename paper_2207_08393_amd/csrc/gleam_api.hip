@@ -221,4 +221,63 @@ int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const 
     return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
 }
 
+int gleam_adam_step(const gleam_adam* hyper, int64_t t, size_t n, float* theta, const float* grad, float* m, float* v,
+                    void* stream) {
+    if (!hyper || !theta || !grad || !m || !v) return GLEAM_E_NULL;
+    if (t < 1 || !(hyper->beta1 >= 0.f && hyper->beta1 < 1.f) || !(hyper->beta2 >= 0.f && hyper->beta2 < 1.f) ||
+        !(hyper->eps >= 0.f))
+        return GLEAM_E_DESC;
+    if (n == 0) return GLEAM_OK;
+    const hipError_t e = adam_update(*hyper, (long long)t, n, theta, grad, m, v, (hipStream_t)stream);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+int gleam_greedy_iteration(const gleam_geom* geom, const gleam_prox_desc* prox, int n_modules, const gleam_c64* x0,
+                           const gleam_c64* S, const uint8_t* M, const gleam_c64* y, float alpha, float* theta,
+                           float* adam_m, float* adam_v, const gleam_adam* hyper, int64_t t, const gleam_c64* x_ref,
+                           gleam_c64* x_out, gleam_c64* x_tmp, float* losses, float* grad, void* saved,
+                           size_t saved_bytes, void* ws, size_t ws_bytes, void* stream) {
+    if (n_modules < 1) return GLEAM_E_DIMS;
+    if (!x0 || !theta || !adam_m || !adam_v || !hyper || !x_ref || !x_out || !x_tmp || !losses || !grad) return GLEAM_E_NULL;
+    if (x_out == x0 || x_tmp == x0 || x_out == x_tmp) return GLEAM_E_DIMS;
+    size_t n_theta = 0;
+    int rc = gleam_theta_count(prox, &n_theta);
+    if (rc) return rc;
+    const gleam_c64* x_in = x0;
+    for (int i = 0; i < n_modules; ++i) {
+        // alternate the two image buffers so that the last module writes x_out
+        gleam_c64* xo = ((n_modules - 1 - i) % 2 == 0) ? x_out : x_tmp;
+        float* th = theta + (size_t)i * n_theta;
+        rc = gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, th, x_ref, xo, losses + i, saved, saved_bytes, ws, ws_bytes,
+                              stream);
+        if (rc) return rc;
+        rc = gleam_module_bwd(geom, prox, th, saved, saved_bytes, grad, ws, ws_bytes, stream);
+        if (rc) return rc;
+        rc = gleam_adam_step(hyper, t, n_theta, th, grad, adam_m + (size_t)i * n_theta, adam_v + (size_t)i * n_theta, stream);
+        if (rc) return rc;
+        x_in = xo;
+    }
+    return GLEAM_OK;
+}
+
+int gleam_unrolled_infer(const gleam_geom* geom, const gleam_prox_desc* prox, int n_modules, const gleam_c64* x0,
+                         const gleam_c64* S, const uint8_t* M, const gleam_c64* y, float alpha, const float* theta,
+                         gleam_c64* x_out, gleam_c64* x_tmp, void* ws, size_t ws_bytes, void* stream) {
+    if (n_modules < 1) return GLEAM_E_DIMS;
+    if (!x0 || !theta || !x_out || !x_tmp) return GLEAM_E_NULL;
+    if (x_out == x0 || x_tmp == x0 || x_out == x_tmp) return GLEAM_E_DIMS;
+    size_t n_theta = 0;
+    int rc = gleam_theta_count(prox, &n_theta);
+    if (rc) return rc;
+    const gleam_c64* x_in = x0;
+    for (int i = 0; i < n_modules; ++i) {
+        gleam_c64* xo = ((n_modules - 1 - i) % 2 == 0) ? x_out : x_tmp;
+        rc = gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, theta + (size_t)i * n_theta, nullptr, xo, nullptr, nullptr, 0,
+                              ws, ws_bytes, stream);
+        if (rc) return rc;
+        x_in = xo;
+    }
+    return GLEAM_OK;
+}
+
 }  // extern "C"

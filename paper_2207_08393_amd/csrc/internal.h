@@ -78,4 +78,8 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
 hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
                          const unsigned char* saved, float* grad_theta, void* ws, hipStream_t st);
 
+// theta <- Adam(theta, grad) in place with state m, v; bias corrections evaluated on the host in double.
+hipError_t adam_update(const gleam_adam& h, long long t, size_t n, float* theta, const float* grad, float* m, float* v,
+                       hipStream_t st);
+
 }  // namespace gleam

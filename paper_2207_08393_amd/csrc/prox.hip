@@ -12,6 +12,7 @@
 // index and never ragged except at the very end of the tensor.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdint>
 #include <cstdio>
 #include <type_traits>
@@ -2095,6 +2096,30 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// ------------------------------------------------------------------ Adam ("Update Parameters", Alg. 1)
+__global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, const float* __restrict__ grad,
+                                                   float* __restrict__ m, float* __restrict__ v, size_t n, float beta1,
+                                                   float beta2, float step, float inv_c2, float eps) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float g = grad[i];
+    const float mi = beta1 * m[i] + (1.f - beta1) * g;
+    const float vi = beta2 * v[i] + (1.f - beta2) * g * g;
+    m[i] = mi;
+    v[i] = vi;
+    // step = lr / (1 - beta1^t), inv_c2 = 1 / (1 - beta2^t)
+    theta[i] -= step * mi / (sqrtf(vi * inv_c2) + eps);
+}
+
+hipError_t adam_update(const gleam_adam& h, long long t, size_t n, float* theta, const float* grad, float* m, float* v,
+                       hipStream_t st) {
+    const double c1 = 1.0 - pow((double)h.beta1, (double)t), c2 = 1.0 - pow((double)h.beta2, (double)t);
+    KernelScope ks("adam", 0.0, 28.0 * (double)n, st);
+    hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, theta, grad, m, v, n, h.beta1, h.beta2,
+                       (float)((double)h.lr / c1), (float)(1.0 / c2), h.eps);
+    return hipGetLastError();
 }
 
 }  // namespace gleam

@@ -78,3 +78,46 @@ class ModuleRunner:
     def results(self):
         torch.cuda.synchronize()
         return to_complex(self.x_out), float(self.loss.item()), self.grad.cpu().numpy()
+
+
+class GreedyRunner:
+    """Device-resident state of greedy training (Alg. 1): per-module parameters and Adam moments;
+    `iteration()` = one gleam_greedy_iteration over the case's mini-batch."""
+
+    def __init__(self, case, thetas, lr, alpha=None, beta1=0.9, beta2=0.999, eps=1e-8, adam_m=None, adam_v=None):
+        self.case = case
+        self.geom = gb.make_geom(case.geom)
+        self.prox = gb.make_prox(case.prox)
+        self.n_modules = len(thetas)
+        self.ws_bytes, self.saved_bytes = gb.gleam_workspace_bytes(self.geom, self.prox)
+        self.ws = byte_buffer(self.ws_bytes)
+        self.saved = byte_buffer(self.saved_bytes)
+        self.x0 = cplx(case.x_in)
+        self.S, self.M, self.y = cplx(case.S), dev(case.M), cplx(case.y)
+        self.x_ref = cplx(case.x_true)
+        self.theta = dev(np.stack([np.asarray(t, np.float32) for t in thetas]))
+        zeros = np.zeros(self.theta.shape, np.float32)
+        self.m = dev(zeros if adam_m is None else np.stack([np.asarray(a, np.float32) for a in adam_m]))
+        self.v = dev(zeros if adam_v is None else np.stack([np.asarray(a, np.float32) for a in adam_v]))
+        self.hyper = gb.make_adam(lr, beta1, beta2, eps)
+        self.alpha = float(case.alpha if alpha is None else alpha)
+        self.x_out = torch.full_like(self.x0, float("nan"))
+        self.x_tmp = torch.full_like(self.x0, float("nan"))
+        self.losses = torch.full((self.n_modules,), float("nan"), device="cuda")
+        self.grad = torch.empty(self.theta.shape[1], device="cuda")
+
+    def iteration(self, t):
+        gb.gleam_greedy_iteration(self.geom, self.prox, self.n_modules, self.x0, self.S, self.M, self.y, self.alpha,
+                                  self.theta, self.m, self.v, self.hyper, t, self.x_ref, self.x_out, self.x_tmp,
+                                  self.losses, self.grad, self.saved, self.ws)
+
+    def infer(self, n_modules=None):
+        gb.gleam_unrolled_infer(self.geom, self.prox, self.n_modules if n_modules is None else n_modules, self.x0,
+                                self.S, self.M, self.y, self.alpha, self.theta, self.x_out, self.x_tmp, self.ws)
+        torch.cuda.synchronize()
+        return to_complex(self.x_out)
+
+    def results(self):
+        torch.cuda.synchronize()
+        return (to_complex(self.x_out), self.losses.cpu().numpy(), self.theta.cpu().numpy(), self.m.cpu().numpy(),
+                self.v.cpu().numpy())

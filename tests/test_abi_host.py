@@ -113,3 +113,39 @@ def test_null_pointers_and_short_workspace_are_rejected_before_launch():
     a = list(bargs); a[4] = 0
     assert L.gleam_module_bwd(*a) == gb.GLEAM_E_WORKSPACE
     assert L.gleam_theta_count(C.byref(prox), None) == gb.GLEAM_E_NULL
+
+
+def test_greedy_entry_points_reject_bad_arguments_before_launch():
+    c = synth.make_case(0)
+    geom, prox = gb.make_geom(c.geom), gb.make_prox(c.prox)
+    ws, saved = gb.gleam_workspace_bytes(geom, prox)
+    fake = 0x1000
+    L = gb.lib()
+    h = gb.make_adam(1e-3)
+    assert L.gleam_adam_step(None, 1, 4, fake, fake, fake, fake, None) == gb.GLEAM_E_NULL
+    assert L.gleam_adam_step(C.byref(h), 1, 4, fake, None, fake, fake, None) == gb.GLEAM_E_NULL
+    assert L.gleam_adam_step(C.byref(h), 0, 4, fake, fake, fake, fake, None) == gb.GLEAM_E_DESC     # t starts at 1
+    bad = gb.make_adam(1e-3, beta1=1.0)
+    assert L.gleam_adam_step(C.byref(bad), 1, 4, fake, fake, fake, fake, None) == gb.GLEAM_E_DESC
+    assert L.gleam_adam_step(C.byref(h), 1, 0, fake, fake, fake, fake, None) == gb.GLEAM_OK          # nothing to do
+    x0, xo, xt = 0x1000, 0x2000, 0x3000
+    args = [C.byref(geom), C.byref(prox), 2, x0, fake, fake, fake, C.c_float(1.0), fake, fake, fake, C.byref(h), 1,
+            fake, xo, xt, fake, fake, fake, saved, fake, ws, None]
+    a = list(args); a[2] = 0
+    assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_DIMS
+    for i in (3, 8, 9, 10, 13, 14, 15, 16, 17):
+        a = list(args); a[i] = None
+        assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_NULL, i
+    a = list(args); a[14] = x0          # output aliases the input image
+    assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_DIMS
+    a = list(args); a[15] = xo          # scratch image aliases the output
+    assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_DIMS
+    a = list(args); a[21] = ws - 256    # short workspace is caught by the first module before any launch
+    assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_WORKSPACE
+    iargs = [C.byref(geom), C.byref(prox), 2, x0, fake, fake, fake, C.c_float(1.0), fake, xo, xt, fake, ws, None]
+    a = list(iargs); a[2] = -1
+    assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_DIMS
+    a = list(iargs); a[8] = None
+    assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_NULL
+    a = list(iargs); a[9] = x0
+    assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_DIMS

@@ -220,3 +220,53 @@ def test_config2_brain2d_full_size_bf16():
     assert c.prox.dtype == 1
     print("case cfg2 brain, bf16 convs", flush=True)
     check_module(c, tol=BF16_TOL)
+
+
+# ----------------------------------------------------------------------------- greedy training (Alg. 1)
+def test_adam_step_matches_oracle():
+    import torch
+    rng = np.random.default_rng(5)
+    n = 1000 + 37                                   # several blocks and a ragged tail
+    theta = rng.standard_normal(n).astype(np.float32)
+    m = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    v = (0.01 * rng.random(n)).astype(np.float32)
+    dt, dm, dv = (torch.from_numpy(a.copy()).cuda() for a in (theta, m, v))
+    h = gb.make_adam(2e-3)
+    rt, rm, rv = theta.astype(np.float64), m.astype(np.float64), v.astype(np.float64)
+    for t in range(3, 6):
+        g = rng.standard_normal(n).astype(np.float32)
+        gb.gleam_adam_step(h, t, dt, torch.from_numpy(g).cuda(), dm, dv)
+        rt, rm, rv = og.adam_step(rt, g, rm, rv, t, 2e-3)
+    torch.cuda.synchronize()
+    assert rel_l2(dt.cpu().numpy(), rt) <= TOL and rel_l2(dm.cpu().numpy(), rm) <= TOL and rel_l2(dv.cpu().numpy(), rv) <= TOL
+
+
+@pytest.mark.parametrize("n_modules", [1, 2, 3])
+def test_greedy_iteration_and_inference_match_oracle(n_modules):
+    from paper_2207_08393_amd.runner import GreedyRunner
+    geom = synth.Geom(2, 2, 3, 1, 1, 12, 10)
+    prox = synth.resblock_prox(8, 1)
+    c = synth.make_custom(21, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.8)
+    rng = np.random.default_rng(n_modules)
+    thetas = [c.theta + np.float32(0.03 * k) * rng.standard_normal(c.theta.size).astype(np.float32) for k in range(n_modules)]
+    lr = 1e-3
+    r = GreedyRunner(c, thetas, lr, alpha=0.8)
+    ref_t = [t.astype(np.float64) for t in thetas]
+    ref_m = [np.zeros(c.theta.size) for _ in thetas]
+    ref_v = [np.zeros(c.theta.size) for _ in thetas]
+    for t in (1, 2):                                 # two iterations: the second starts from updated state
+        r.iteration(t)
+        x_ref, losses, ref_t, ref_m, ref_v = og.greedy_iteration(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, ref_t, ref_m,
+                                                                 ref_v, t, lr, c.x_true)
+        x, ls, th, m, v = r.results()
+        assert rel_l2(x, x_ref) <= TOL
+        assert np.allclose(ls, losses, rtol=TOL)
+        # parameters move by ~lr per step: compare the accumulated update as well as the parameters
+        assert rel_l2(th, np.stack(ref_t)) <= TOL
+        assert rel_l2(m, np.stack(ref_m)) <= 10 * TOL and rel_l2(v, np.stack(ref_v)) <= 10 * TOL
+        upd = th - np.stack(thetas)
+        ref_upd = np.stack(ref_t) - np.stack([a.astype(np.float64) for a in thetas])
+        assert rel_l2(upd, ref_upd) <= 2e-3          # first steps are ~lr*sign(g): tiny gradients may flip
+    for depth in range(1, n_modules + 1):            # early exit at any depth
+        xi = r.infer(depth)
+        assert rel_l2(xi, og.unrolled_inference(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, ref_t[:depth])) <= TOL
