@@ -16,6 +16,8 @@ product.  Everything is float64 / complex128 numpy, written as the plain definit
   * backward : analytic reverse sweep for dL/dtheta of this module only (Alg. 1, gradient step);
                nothing is propagated to x_in, S or y (decoupled modules).
 
+  * deep     : a module of K = N/M unrolled iterations (GLEAM section): backpropagation inside the module,
+               through its prox networks and data-consistency steps, none beyond its input
   * greedy   : Alg. 1 for one mini-batch: modules in order, each with its own parameters, local loss,
                local gradient and Adam update (beta1 = 0.9, beta2 = 0.999, Implementation Details); the
                detached output of module m is the input of module m + 1
@@ -218,8 +220,10 @@ def loss_and_grad(z, x_ref, loss_kind):
     return float(mag.sum() / n), complex_to_channels(np.where(mag > 0, d / safe, 0.0) / n)
 
 
-def prox_bwd(layers, theta, t, conv_in, act, g_z):
-    """dL/dtheta (flat, same layout as theta) from dL/dz.  Gradient reaching t_0 is dropped."""
+def prox_bwd(layers, theta, t, conv_in, act, g_z, want_input_grad=False):
+    """dL/dtheta (flat, same layout as theta) from dL/dz.  The gradient reaching t_0 = u is dropped (modules
+    are decoupled) unless want_input_grad, which returns (dL/dtheta, dL/du as 2 real channels): a module
+    that holds several unrolled iterations backpropagates through its own iterations."""
     params = split_theta(layers, theta)
     L = len(layers)
     G = [None] * (L + 1)
@@ -237,7 +241,7 @@ def prox_bwd(layers, theta, t, conv_in, act, g_z):
         gc = g * (act[i] > 0) if l.relu_out else g
         dw, db = conv_wgrad(gc, conv_in[i], (l.kt, l.kd, l.kh, l.kw))
         grads[i] = (dw, db if l.has_bias else None)
-        if i >= 1:
+        if i >= 1 or want_input_grad:
             gin = conv_dgrad(gc, w)
             if l.relu_in:
                 gin = gin * (t[i] > 0)
@@ -247,6 +251,8 @@ def prox_bwd(layers, theta, t, conv_in, act, g_z):
         flat.append(dw.ravel())
         if db is not None:
             flat.append(db.ravel())
+    if want_input_grad:
+        return np.concatenate(flat), G[0]
     return np.concatenate(flat)
 
 
@@ -266,6 +272,38 @@ def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None):
 def module_bwd(prox, theta, fwd):
     """dL/dtheta_m of the local objective; stops at the module input."""
     return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"])
+
+
+# ----------------------------------------------------------------------------- module of several iterations
+def deep_module_fwd(geom, prox, x_in, S, M, y, alpha, thetas, x_ref=None):
+    """A module that holds K = N/M unrolled iterations (GLEAM section, N > M): x_j = f_theta_j(DC(x_{j-1})),
+    j = 1..K, with the local loss on x_K only.  Returns the per-iteration forward records."""
+    x = np.asarray(x_in, np.complex128)
+    recs = []
+    for j, th in enumerate(thetas):
+        last = j == len(thetas) - 1
+        recs.append(module_fwd(geom, prox, x, S, M, y, alpha, th, x_ref if last else None))
+        x = recs[-1]["x_out"]
+    return {"x_out": x, "loss": recs[-1]["loss"], "iters": recs}
+
+
+def deep_module_bwd(geom, prox, S, M, alpha, thetas, fwd):
+    """Gradients of the module's loss with respect to theta_1..theta_K (list): backpropagation inside the
+    module, through every prox and every data-consistency step.  DC is affine in x with the Hermitian
+    linear part I - alpha A^H A, so dL/dx_{j-1} = g_u - alpha A^H A g_u with g_u = dL/du_j (complex view of
+    the two real channels).  Nothing is propagated to the module's input."""
+    K = len(thetas)
+    grads = [None] * K
+    g_out = fwd["iters"][-1]["g_z"]
+    for j in range(K - 1, -1, -1):
+        r = fwd["iters"][j]
+        if j == 0:
+            grads[j] = prox_bwd(prox.layers, thetas[j], r["t"], r["conv_in"], r["act"], g_out)
+        else:
+            grads[j], g_u = prox_bwd(prox.layers, thetas[j], r["t"], r["conv_in"], r["act"], g_out, want_input_grad=True)
+            gc = channels_to_complex(g_u)
+            g_out = complex_to_channels(gc - alpha * sense_normal(gc, S, M, geom.ndim_fft))
+    return grads
 
 
 # ----------------------------------------------------------------------------- greedy training (Alg. 1)

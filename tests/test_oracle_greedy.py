@@ -99,3 +99,54 @@ def test_greedy_iteration_is_local_and_inference_reuses_modules():
     x2 = og.unrolled_inference(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 1.0, thetas[:2])
     f = og.module_fwd(c.geom, c.prox, x2, c.S, c.M, c.y, 1.0, thetas[2])
     assert np.allclose(f["x_out"], base[0], atol=1e-14)
+
+
+def test_deep_module_gradients_vs_torch_autograd_through_dc_and_finite_differences():
+    """A module of K = 3 unrolled iterations: torch differentiates through torch.fft's DC and the convs."""
+    geom = synth.Geom(2, 2, 3, 1, 1, 6, 8)
+    for prox in (synth.resblock_prox(3, 1), synth.chain_prox([2, 4, 2], [(1, 1, 3, 3)] * 2)):
+        for loss_kind in (0, 1):
+            prox.loss_kind = loss_kind
+            c = synth.make_custom(14, geom, prox, accel=2.0, centre=2, bias_std=0.1)
+            n = c.theta.size
+            thetas = [(c.theta + 0.05 * k * RNG.standard_normal(n)).astype(np.float64) for k in range(3)]
+            alpha = 0.6
+            fwd = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, thetas, c.x_true)
+            grads = og.deep_module_bwd(c.geom, c.prox, c.S, c.M, alpha, thetas, fwd)
+            S = torch.from_numpy(c.S.astype(np.complex128))
+            M = torch.from_numpy(c.M)
+            y = torch.from_numpy(c.y.astype(np.complex128))
+            ref = torch.from_numpy(og.complex_to_channels(c.x_true.astype(np.complex128)))
+            ps = [torch.tensor(t.copy(), requires_grad=True) for t in thetas]
+            x = torch.from_numpy(c.x_in.astype(np.complex128))
+            for p in ps:
+                u = torch_dc(x, S, M, y, alpha, 2)
+                z = torch_prox(c.prox.layers, p, torch.view_as_real(u), c.geom.image_shape)
+                x = torch.view_as_complex(z.contiguous())
+            d2 = ((z - ref) ** 2).sum(-1)
+            loss = d2.mean() if loss_kind == 0 else torch.sqrt(d2).mean()
+            loss.backward()
+            assert np.isclose(fwd["loss"], loss.item(), rtol=1e-11)
+            assert np.allclose(fwd["x_out"], x.detach().numpy(), atol=1e-12)
+            for g, p in zip(grads, ps):
+                assert np.allclose(g, p.grad.numpy(), rtol=1e-8, atol=1e-13)
+    # central differences on the first iteration's parameters (their gradient crosses two DC steps)
+    eps = 1e-6
+    d = RNG.standard_normal(n)
+
+    def loss_at(t0):
+        return og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, [t0] + thetas[1:], c.x_true)["loss"]
+
+    num = (loss_at(thetas[0] + eps * d) - loss_at(thetas[0] - eps * d)) / (2 * eps)
+    assert np.isclose(num, grads[0] @ d, rtol=1e-5)
+
+
+def test_deep_module_of_one_iteration_is_the_plain_module():
+    geom = synth.Geom(2, 1, 2, 1, 1, 6, 6)
+    prox = synth.chain_prox([2, 3, 2], [(1, 1, 3, 3)] * 2)
+    c = synth.make_custom(4, geom, prox, accel=2.0, centre=2)
+    th = c.theta.astype(np.float64)
+    f1 = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.9, th, c.x_true)
+    fd = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.9, [th], c.x_true)
+    assert np.array_equal(f1["x_out"], fd["x_out"]) and f1["loss"] == fd["loss"]
+    assert np.array_equal(og.module_bwd(c.prox, th, f1), og.deep_module_bwd(c.geom, c.prox, c.S, c.M, 0.9, [th], fd)[0])
