@@ -187,6 +187,18 @@ def main():
     greedy_ms = 1e3 * (time.perf_counter() - t0) / n_it
     del gr
 
+    # a module of two unrolled iterations (N/M = 2): fwd + bwd through both prox networks and the DC step between
+    from paper_2207_08393_amd.runner import DeepModuleRunner
+    dr = DeepModuleRunner(case, [case.theta, case.theta])
+    dr.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_it):
+        dr.step()
+    torch.cuda.synchronize()
+    deep_ms = 1e3 * (time.perf_counter() - t0) / n_it
+    del dr
+
     out = {"metric": "GLEAM module fwd+bwd steps/s", "value": args.steps / dt, "unit": "module steps/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -201,6 +213,8 @@ def main():
            "sense_normal": sense, "kernels": kernels,
            "greedy_iteration": {"modules": case.n_modules, "ms": greedy_ms, "iterations_per_s": 1e3 / greedy_ms,
                                 "includes": "fwd + bwd + Adam update of every module, detached hand-off"}}
+    out["deep_module"] = {"iterations_per_module": 2, "ms": deep_ms,
+                          "includes": "fwd + bwd of one module holding two unrolled iterations"}
     if not args.no_cpu_baseline and args.workload in (0, 1, 4):
         out["cpu_baseline"] = cpu_baseline(case)
     print(json.dumps(out))

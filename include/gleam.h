@@ -114,6 +114,27 @@ int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const 
                      const void* saved, size_t saved_bytes, float* grad_theta,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* A module that holds n_iter = N/M unrolled iterations (GLEAM section, N > M), each with its own parameters:
+ *     x_j = f_theta_j(DC(x_{j-1})),  j = 1..n_iter,   loss = L(x_{n_iter}, x_ref)
+ * The local loss is backpropagated inside the module, through its prox networks and data-consistency steps
+ * (dL/dx_{j-1} = g - alpha A^H A g with g = dL/du_j), and not beyond the module input.
+ *   theta / grad_theta : [n_iter][n_theta] float32.
+ *   saved              : n_iter blocks, sized by gleam_deep_workspace_bytes; written by both calls.
+ *   x_out, x_tmp       : final image and one image of scratch (must not alias x_in or each other).
+ * Requires a prox whose first layer has relu_in = 0 and at most one layer taking its skip from the input
+ * when n_iter > 1 (else GLEAM_E_DESC).  n_iter = 1 is gleam_module_fwd / gleam_module_bwd. */
+int gleam_deep_workspace_bytes(const gleam_geom* geom, const gleam_prox_desc* prox, int n_iter,
+                               size_t* ws_bytes, size_t* saved_bytes);
+int gleam_deep_module_fwd(const gleam_geom* geom, const gleam_prox_desc* prox, int n_iter,
+                          const gleam_c64* x_in, const gleam_c64* S, const uint8_t* M, const gleam_c64* y,
+                          float alpha, const float* theta, const gleam_c64* x_ref, gleam_c64* x_out,
+                          gleam_c64* x_tmp, float* loss, void* saved, size_t saved_bytes, void* ws,
+                          size_t ws_bytes, void* stream);
+int gleam_deep_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, int n_iter,
+                          const gleam_c64* S, const uint8_t* M, float alpha, const float* theta,
+                          void* saved, size_t saved_bytes, float* grad_theta, void* ws, size_t ws_bytes,
+                          void* stream);
+
 /* Adam hyper-parameters (Implementation Details: beta1 = 0.9, beta2 = 0.999; the paper does not state the
  * learning rate or epsilon). */
 typedef struct {

@@ -72,6 +72,9 @@ def lib() -> C.CDLL:
         L.gleam_sense_normal.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
         L.gleam_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_module_bwd.argtypes = [pg, pp, vp, vp, sz, vp, vp, sz, vp]
+        L.gleam_deep_workspace_bytes.argtypes = [pg, pp, C.c_int, C.POINTER(sz), C.POINTER(sz)]
+        L.gleam_deep_module_fwd.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.gleam_deep_module_bwd.argtypes = [pg, pp, C.c_int, vp, vp, C.c_float, vp, vp, sz, vp, vp, sz, vp]
         L.gleam_adam_step.argtypes = [C.POINTER(gleam_adam), C.c_int64, sz, vp, vp, vp, vp, vp]
         L.gleam_greedy_iteration.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, C.POINTER(gleam_adam),
                                              C.c_int64, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
@@ -83,7 +86,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
-           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_adam_step",
+           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_deep_workspace_bytes",
+           "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_adam_step",
            "gleam_greedy_iteration", "gleam_unrolled_infer", "gleam_profile_begin", "gleam_profile_end")
 
 
@@ -167,6 +171,26 @@ def gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref, x_out, loss
 def gleam_module_bwd(geom, prox, theta, saved, grad_theta, ws, stream=None):
     _check(lib().gleam_module_bwd(C.byref(geom), C.byref(prox), _ptr(theta), _ptr(saved), _nbytes(saved),
                                   _ptr(grad_theta), _ptr(ws), _nbytes(ws), _stream(stream)), "gleam_module_bwd")
+
+
+def gleam_deep_workspace_bytes(geom, prox, n_iter):
+    ws, saved = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().gleam_deep_workspace_bytes(C.byref(geom), C.byref(prox), int(n_iter), C.byref(ws), C.byref(saved)),
+           "gleam_deep_workspace_bytes")
+    return ws.value, saved.value
+
+
+def gleam_deep_module_fwd(geom, prox, n_iter, x_in, S, M, y, alpha, theta, x_ref, x_out, x_tmp, loss, saved, ws, stream=None):
+    _check(lib().gleam_deep_module_fwd(C.byref(geom), C.byref(prox), int(n_iter), _ptr(x_in), _ptr(S), _ptr(M), _ptr(y),
+                                       C.c_float(alpha), _ptr(theta), _ptr(x_ref), _ptr(x_out), _ptr(x_tmp), _ptr(loss),
+                                       _ptr(saved), _nbytes(saved), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "gleam_deep_module_fwd")
+
+
+def gleam_deep_module_bwd(geom, prox, n_iter, S, M, alpha, theta, saved, grad_theta, ws, stream=None):
+    _check(lib().gleam_deep_module_bwd(C.byref(geom), C.byref(prox), int(n_iter), _ptr(S), _ptr(M), C.c_float(alpha),
+                                       _ptr(theta), _ptr(saved), _nbytes(saved), _ptr(grad_theta), _ptr(ws), _nbytes(ws),
+                                       _stream(stream)), "gleam_deep_module_bwd")
 
 
 def make_adam(lr, beta1=0.9, beta2=0.999, eps=1e-8) -> gleam_adam:

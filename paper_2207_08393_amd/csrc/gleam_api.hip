@@ -216,9 +216,86 @@ int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const 
     plan_prox(*geom, *prox, plan);
     if (!aligned(ws) || ws_bytes < plan.ws_bytes) return GLEAM_E_WORKSPACE;
     if (!aligned(saved) || saved_bytes < plan.saved_bytes) return GLEAM_E_WORKSPACE;
-    hipError_t e = prox_backward(*geom, *prox, plan, theta, (const unsigned char*)saved, grad_theta, ws,
+    hipError_t e = prox_backward(*geom, *prox, plan, theta, (const unsigned char*)saved, grad_theta, nullptr, ws,
                                  (hipStream_t)stream);
     return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+static int check_deep(const gleam_prox_desc* prox, int n_iter) {
+    if (n_iter < 1) return GLEAM_E_DIMS;
+    if (n_iter == 1) return GLEAM_OK;
+    if (prox->layers[0].relu_in) return GLEAM_E_DESC;
+    int from_input = 0;
+    for (int l = 0; l < prox->n_layers; ++l) from_input += prox->layers[l].skip_src == 0 ? 1 : 0;
+    return from_input <= 1 ? GLEAM_OK : GLEAM_E_DESC;
+}
+
+int gleam_deep_workspace_bytes(const gleam_geom* geom, const gleam_prox_desc* prox, int n_iter, size_t* ws_bytes,
+                               size_t* saved_bytes) {
+    if (!prox) return GLEAM_E_NULL;
+    int rc = gleam_workspace_bytes(geom, prox, ws_bytes, saved_bytes);
+    if (rc) return rc;
+    rc = check_deep(prox, n_iter);
+    if (rc) return rc;
+    *saved_bytes = align_up(*saved_bytes) * (size_t)n_iter;
+    return GLEAM_OK;
+}
+
+int gleam_deep_module_fwd(const gleam_geom* geom, const gleam_prox_desc* prox, int n_iter, const gleam_c64* x_in,
+                          const gleam_c64* S, const uint8_t* M, const gleam_c64* y, float alpha, const float* theta,
+                          const gleam_c64* x_ref, gleam_c64* x_out, gleam_c64* x_tmp, float* loss, void* saved,
+                          size_t saved_bytes, void* ws, size_t ws_bytes, void* stream) {
+    size_t ws_need = 0, saved_need = 0, n_theta = 0;
+    int rc = gleam_deep_workspace_bytes(geom, prox, n_iter, &ws_need, &saved_need);
+    if (rc) return rc;
+    if (!x_in || !theta || !x_ref || !x_out || !x_tmp || !loss || !saved) return GLEAM_E_NULL;
+    if (x_out == x_in || x_tmp == x_in || x_out == x_tmp) return GLEAM_E_DIMS;
+    if (!aligned(saved) || saved_bytes < saved_need) return GLEAM_E_WORKSPACE;
+    rc = gleam_theta_count(prox, &n_theta);
+    if (rc) return rc;
+    const size_t block = saved_need / (size_t)n_iter;
+    const gleam_c64* xi = x_in;
+    for (int j = 0; j < n_iter; ++j) {
+        const bool last = j == n_iter - 1;
+        gleam_c64* xo = ((n_iter - 1 - j) % 2 == 0) ? x_out : x_tmp;   // the last iteration writes x_out
+        rc = gleam_module_fwd(geom, prox, xi, S, M, y, alpha, theta + (size_t)j * n_theta, last ? x_ref : nullptr, xo,
+                              last ? loss : nullptr, (unsigned char*)saved + (size_t)j * block, block, ws, ws_bytes, stream);
+        if (rc) return rc;
+        xi = xo;
+    }
+    return GLEAM_OK;
+}
+
+int gleam_deep_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, int n_iter, const gleam_c64* S,
+                          const uint8_t* M, float alpha, const float* theta, void* saved, size_t saved_bytes,
+                          float* grad_theta, void* ws, size_t ws_bytes, void* stream) {
+    size_t ws_need = 0, saved_need = 0, n_theta = 0;
+    int rc = gleam_deep_workspace_bytes(geom, prox, n_iter, &ws_need, &saved_need);
+    if (rc) return rc;
+    if (!S || !M || !theta || !saved || !grad_theta || !ws) return GLEAM_E_NULL;
+    if (!aligned(ws) || ws_bytes < ws_need) return GLEAM_E_WORKSPACE;
+    if (!aligned(saved) || saved_bytes < saved_need) return GLEAM_E_WORKSPACE;
+    rc = gleam_theta_count(prox, &n_theta);
+    if (rc) return rc;
+    ProxPlan plan;
+    plan_prox(*geom, *prox, plan);
+    const size_t block = saved_need / (size_t)n_iter;
+    hipStream_t st = (hipStream_t)stream;
+    for (int j = n_iter - 1; j >= 0; --j) {
+        unsigned char* sj = (unsigned char*)saved + (size_t)j * block;
+        // dL/du_j overwrites u_j = t_0 of this iteration, which is dead once its first layer's weight gradient is done
+        float2* g_u = j > 0 ? (float2*)(sj + plan.act_off[0]) : nullptr;
+        hipError_t e = prox_backward(*geom, *prox, plan, theta + (size_t)j * n_theta, sj, grad_theta + (size_t)j * n_theta, g_u,
+                                     ws, st);
+        if (e != hipSuccess) return GLEAM_E_LAUNCH;
+        if (j > 0) {
+            // through the data-consistency step: dL/dx_{j-1} = g_u - alpha A^H A g_u, the incoming gradient of iteration j-1
+            float2* g_prev = (float2*)((unsigned char*)saved + (size_t)(j - 1) * block + plan.gz_off);
+            e = sense_dc(*geom, g_u, (const float2*)S, M, nullptr, 1.f, -alpha, g_prev, (float2*)ws, st);
+            if (e != hipSuccess) return GLEAM_E_LAUNCH;
+        }
+    }
+    return GLEAM_OK;
 }
 
 int gleam_adam_step(const gleam_adam* hyper, int64_t t, size_t n, float* theta, const float* grad, float* m, float* v,

@@ -74,9 +74,12 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
                         unsigned char* act_base, const float2* x_ref, float2* x_out, float* loss, void* ws,
                         hipStream_t st);
 
-// grad_theta = dL/dtheta from the activations and g_z left by prox_forward.
+// grad_theta = dL/dtheta from the activations and g_z left by prox_forward.  g_in (may be null): receives
+// dL/du, the gradient with respect to the prox input, float32 2 channels; it may alias t_0 inside `saved`
+// (t_0 is dead once the first layer's weight gradient is done).  Requires layers[0].relu_in == 0 and at
+// most one layer taking its skip from t_0.
 hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
-                         const unsigned char* saved, float* grad_theta, void* ws, hipStream_t st);
+                         const unsigned char* saved, float* grad_theta, float2* g_in, void* ws, hipStream_t st);
 
 // theta <- Adam(theta, grad) in place with state m, v; bias corrections evaluated on the host in double.
 hipError_t adam_update(const gleam_adam& h, long long t, size_t n, float* theta, const float* grad, float* m, float* v,

@@ -1009,15 +1009,28 @@ static void launch_conv_thin_out_t(const ConvThinOutArgs& t, const float* w, boo
     launch_conv_thin_out_k<KT, KD, KH, KW, 16>(t, w, bf, st);
 }
 
-// Launches the two-channel-output kernel when the layer fits it (forward pass only: weights are read in
-// theta's own layout); *hit tells whether it did.  `in` is bfloat16 when bf.
-static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw, bool bf, bool* hit, hipStream_t st) {
+// wt[n][tap][k] = w[n*sn + tapidx*st + k*sk] (tapidx mirrored when flip), n < 2: the layout the
+// two-channel-output kernel reads, for the data gradient of a layer whose INPUT is the 2-channel image.
+__global__ void thin_out_weights_kernel(const float* __restrict__ w, long long sn, long long st_, long long sk, int flip,
+                                        int taps, int K, float* __restrict__ wt) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 2 * taps * K) return;
+    const int k = i % K, tap = (i / K) % taps, n = i / (K * taps);
+    const int tapidx = flip ? taps - 1 - tap : tap;
+    wt[i] = w[n * sn + tapidx * st_ + k * sk];
+}
+
+// Launches the two-channel-output kernel when the layer fits it; *hit tells whether it did.  The forward
+// pass reads theta's own layout; other weight layouts (the data gradient into the image) are re-laid into
+// wt_scratch first.  `in` is bfloat16 when bf.
+static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw, bool bf, float* wt_scratch, bool* hit,
+                                       hipStream_t st) {
     *hit = false;
     const PixDims& d = a.d;
     const int taps_ = d.kt * d.kd * d.kh * d.kw;
-    if (!(a.Nn == 2 && a.K >= 16 && a.K % 16 == 0 && !a.flip && !a.mask_ref && cw.sk == 1 && cw.st == a.K &&
-          cw.sn == (long long)taps_ * a.K))
-        return hipSuccess;
+    if (!(a.Nn == 2 && a.K >= 16 && a.K % 16 == 0 && !a.mask_ref)) return hipSuccess;
+    const bool direct = !a.flip && cw.sk == 1 && cw.st == a.K && cw.sn == (long long)taps_ * a.K;
+    if (!direct && wt_scratch == nullptr) return hipSuccess;
     const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
     const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
     if (!k2 && !k3 && !kt3) return hipSuccess;
@@ -1027,12 +1040,19 @@ static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw,
     ConvThinOutArgs t{};
     t.in = a.in; t.bias = a.bias; t.add = a.add; t.out = a.out;
     t.K = a.K; t.KC = kc; t.relu_in = a.relu_in; t.relu_out = a.relu_out; t.d = d;
+    const float* wts = cw.w;
+    if (!direct) {
+        const int n = 2 * taps_ * a.K;
+        hipLaunchKernelGGL(thin_out_weights_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cw.w, cw.sn, cw.st, cw.sk, a.flip,
+                           taps_, a.K, wt_scratch);
+        wts = wt_scratch;
+    }
     char name[56];
-    snprintf(name, sizeof(name), "conv_fwd_%dto%d_t%d", a.K, a.Nn, taps_);
+    snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
     KernelScope ks(name, 2.0 * (double)d.Q * a.K * a.Nn * taps_, (bf ? 2.0 : 4.0) * (double)d.Q * a.K + 8.0 * (double)d.Q, st);
-    if (k2) launch_conv_thin_out_t<1, 1, 3, 3>(t, cw.w, bf, st);
-    else if (k3) launch_conv_thin_out_t<1, 3, 3, 3>(t, cw.w, bf, st);
-    else launch_conv_thin_out_t<3, 1, 1, 1>(t, cw.w, bf, st);
+    if (k2) launch_conv_thin_out_t<1, 1, 3, 3>(t, wts, bf, st);
+    else if (k3) launch_conv_thin_out_t<1, 3, 3, 3>(t, wts, bf, st);
+    else launch_conv_thin_out_t<3, 1, 1, 1>(t, wts, bf, st);
     *hit = true;
     return hipGetLastError();
 }
@@ -1046,7 +1066,7 @@ static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scrat
     }
     {   // two output channels and a wide input (forward): HBM-bound kernel without MFMA
         bool hit = false;
-        const hipError_t e = launch_conv_thin_out(a, cw, false, &hit, st);
+        const hipError_t e = launch_conv_thin_out(a, cw, false, wt_scratch, &hit, st);
         if (hit || e != hipSuccess) return e;
     }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
@@ -1807,7 +1827,7 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
             } else {                // bfloat16 in; the last layer writes the float32 image
                 if (l == L - 1) {
                     bool hit = false;
-                    e = launch_conv_thin_out(a, cw, true, &hit, st);
+                    e = launch_conv_thin_out(a, cw, true, nullptr, &hit, st);
                     if (e != hipSuccess) return e;
                     if (hit) continue;
                 }
@@ -1992,8 +2012,9 @@ size_t wgrad_lds_bytes(const gleam_conv& c) {
 }
 
 hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
-                         const unsigned char* saved, float* grad_theta, void* ws, hipStream_t st) {
+                         const unsigned char* saved, float* grad_theta, float2* g_in, void* ws, hipStream_t st) {
     const int L = p.n_layers;
+    int skip_from_input = 0;   // layer (1-based) whose output gradient also flows into t_0 = u through its skip
     unsigned char* wsb = (unsigned char*)ws;
     float* partial = reinterpret_cast<float*>(wsb + plan.partial_off);
     // Gradient buffer of tensor t_l (1 <= l <= L); G_L is g_z.
@@ -2012,6 +2033,10 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         if (c.skip_src >= 1) {
             if (pending[c.skip_src] != 0) return hipErrorInvalidValue;  // one consumer per skip source (checked at plan time)
             pending[c.skip_src] = l;
+        }
+        if (c.skip_src == 0) {
+            if (g_in && skip_from_input != 0) return hipErrorInvalidValue;   // checked by the caller
+            skip_from_input = l;
         }
         // weight gradient (+ bias gradient)
         WgradArgs wa{};
@@ -2061,7 +2086,34 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if (l == 1) break;  // nothing flows into t_0 = u: the module input is detached
+        if (l == 1) {
+            if (!g_in) break;   // nothing flows into t_0 = u: the module input is detached
+            // a module of several unrolled iterations: gradient with respect to this iteration's input u,
+            // dL/du = conv_1^T(G_1) + (gradient of a skip taken from u), float32 2 channels
+            ConvArgs a{};
+            a.in = G(1); a.out = reinterpret_cast<float*>(g_in);
+            const ConvWeights cw{theta + plan.w_off[0], 1, (long long)c.cin, (long long)(taps * c.cin)};
+            a.flip = 1;
+            a.K = c.cout; a.Nn = c.cin;
+            a.add = skip_from_input ? G(skip_from_input) : nullptr;
+            a.d = d;
+            float* scratch = reinterpret_cast<float*>(wsb + plan.wimg_off_bwd);
+            if (p.dtype == 1) {
+                bool hit = false;
+                e = launch_conv_thin_out(a, cw, true, scratch, &hit, st);
+                if (e == hipSuccess && !hit) {
+                    ConvBf16Args b{};
+                    b.in = reinterpret_cast<const unsigned short*>(a.in);
+                    b.out = a.out; b.add = a.add; b.out_f32 = 1;
+                    b.K = a.K; b.Nn = a.Nn; b.d = d;
+                    e = launch_conv_bf16(b, cw.w, cw.sn, cw.st, cw.sk, 1, reinterpret_cast<unsigned short*>(scratch), st);
+                }
+            } else {
+                e = launch_conv(a, cw, scratch, st);
+            }
+            if (e != hipSuccess) return e;
+            break;
+        }
         // data gradient into t_{l-1}, fused with the ReLU masks and the pending skip gradient
         const gleam_conv& below = p.layers[l - 2];  // layer that produced t_{l-1}
         ConvArgs a{};

@@ -121,3 +121,35 @@ class GreedyRunner:
         torch.cuda.synchronize()
         return (to_complex(self.x_out), self.losses.cpu().numpy(), self.theta.cpu().numpy(), self.m.cpu().numpy(),
                 self.v.cpu().numpy())
+
+
+class DeepModuleRunner:
+    """A module of n_iter unrolled iterations (own parameters each): `step()` = gleam_deep_module_fwd + _bwd."""
+
+    def __init__(self, case, thetas, alpha=None):
+        self.case = case
+        self.geom = gb.make_geom(case.geom)
+        self.prox = gb.make_prox(case.prox)
+        self.n_iter = len(thetas)
+        self.ws_bytes, self.saved_bytes = gb.gleam_deep_workspace_bytes(self.geom, self.prox, self.n_iter)
+        self.ws = byte_buffer(self.ws_bytes)
+        self.saved = byte_buffer(self.saved_bytes)
+        self.x_in = cplx(case.x_in)
+        self.S, self.M, self.y = cplx(case.S), dev(case.M), cplx(case.y)
+        self.x_ref = cplx(case.x_true)
+        self.theta = dev(np.stack([np.asarray(t, np.float32) for t in thetas]))
+        self.alpha = float(case.alpha if alpha is None else alpha)
+        self.x_out = torch.full_like(self.x_in, float("nan"))
+        self.x_tmp = torch.full_like(self.x_in, float("nan"))
+        self.loss = torch.full((1,), float("nan"), device="cuda")
+        self.grad = torch.full_like(self.theta, float("nan"))
+
+    def step(self):
+        gb.gleam_deep_module_fwd(self.geom, self.prox, self.n_iter, self.x_in, self.S, self.M, self.y, self.alpha,
+                                 self.theta, self.x_ref, self.x_out, self.x_tmp, self.loss, self.saved, self.ws)
+        gb.gleam_deep_module_bwd(self.geom, self.prox, self.n_iter, self.S, self.M, self.alpha, self.theta, self.saved,
+                                 self.grad, self.ws)
+
+    def results(self):
+        torch.cuda.synchronize()
+        return to_complex(self.x_out), float(self.loss.item()), self.grad.cpu().numpy()

@@ -149,3 +149,49 @@ def test_greedy_entry_points_reject_bad_arguments_before_launch():
     assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_NULL
     a = list(iargs); a[9] = x0
     assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_DIMS
+
+
+def test_deep_module_entry_points_reject_bad_arguments_before_launch():
+    c = synth.make_case(0)
+    geom, prox = gb.make_geom(c.geom), gb.make_prox(c.prox)
+    ws1, saved1 = gb.gleam_workspace_bytes(geom, prox)
+    ws, saved = gb.gleam_deep_workspace_bytes(geom, prox, 3)
+    assert ws == ws1 and saved >= 3 * saved1 and saved % 256 == 0
+    assert gb.gleam_deep_workspace_bytes(geom, prox, 1) == (ws1, (saved1 + 255) // 256 * 256)
+    L = gb.lib()
+    w, s = C.c_size_t(0), C.c_size_t(0)
+    assert L.gleam_deep_workspace_bytes(C.byref(geom), C.byref(prox), 0, C.byref(w), C.byref(s)) == gb.GLEAM_E_DIMS
+    # several iterations need the gradient with respect to the prox input: no ReLU on the input, one skip from it at most
+    relu_first = synth.chain_prox([2, 8, 2], [(1, 1, 3, 3)] * 2)
+    relu_first.layers[0].relu_in = 1
+    p = gb.make_prox(relu_first)
+    assert L.gleam_deep_workspace_bytes(C.byref(geom), C.byref(p), 2, C.byref(w), C.byref(s)) == gb.GLEAM_E_DESC
+    assert L.gleam_deep_workspace_bytes(C.byref(geom), C.byref(p), 1, C.byref(w), C.byref(s)) == gb.GLEAM_OK
+    two_skips = synth.chain_prox([2, 2, 2], [(1, 1, 3, 3)] * 2)
+    two_skips.layers[0].skip_src = 0
+    two_skips.layers[1].skip_src = 0
+    p = gb.make_prox(two_skips)
+    assert L.gleam_deep_workspace_bytes(C.byref(geom), C.byref(p), 2, C.byref(w), C.byref(s)) == gb.GLEAM_E_DESC
+    ws, saved = gb.gleam_deep_workspace_bytes(geom, prox, 2)
+    fake, x0, xo, xt = 0x1000, 0x1000, 0x2000, 0x3000
+    fargs = [C.byref(geom), C.byref(prox), 2, x0, fake, fake, fake, C.c_float(1.0), fake, fake, xo, xt, fake, fake, saved,
+             fake, ws, None]
+    for i in (3, 8, 9, 10, 11, 12, 13):
+        a = list(fargs); a[i] = None
+        assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_NULL, i
+    a = list(fargs); a[10] = x0
+    assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_DIMS
+    a = list(fargs); a[11] = xo
+    assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_DIMS
+    a = list(fargs); a[14] = saved - 256
+    assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_WORKSPACE
+    bargs = [C.byref(geom), C.byref(prox), 2, fake, fake, C.c_float(1.0), fake, fake, saved, fake, fake, ws, None]
+    for i in (3, 4, 6, 7, 9, 10):
+        a = list(bargs); a[i] = None
+        assert L.gleam_deep_module_bwd(*a) == gb.GLEAM_E_NULL, i
+    a = list(bargs); a[8] = saved - 256
+    assert L.gleam_deep_module_bwd(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(bargs); a[11] = ws - 256
+    assert L.gleam_deep_module_bwd(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(bargs); a[2] = 0
+    assert L.gleam_deep_module_bwd(*a) == gb.GLEAM_E_DIMS

@@ -270,3 +270,38 @@ def test_greedy_iteration_and_inference_match_oracle(n_modules):
     for depth in range(1, n_modules + 1):            # early exit at any depth
         xi = r.infer(depth)
         assert rel_l2(xi, og.unrolled_inference(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, ref_t[:depth])) <= TOL
+
+
+# ----------------------------------------------------------------------------- modules of several iterations
+def deep_cases():
+    yield "res8_k3", synth.Geom(2, 2, 3, 1, 1, 12, 10), synth.resblock_prox(8, 1), 3, 0, 0
+    yield "chain16_k2", synth.Geom(2, 1, 2, 1, 1, 20, 12), synth.chain_prox([2, 16, 16, 2], [K2] * 3), 2, 0, 1
+    yield "res64_k2", synth.Geom(2, 1, 2, 1, 1, 24, 32), synth.resblock_prox(64, 1), 2, 0, 0
+    yield "vol32_k2", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), 2, 0, 0
+    yield "cine16_k2", synth.Geom(2, 1, 2, 4, 1, 6, 8), synth.chain_prox([2, 16, 16, 2], [KS, KT, KT]), 2, 0, 0
+    yield "chain16_k2_bf16", synth.Geom(2, 1, 2, 1, 1, 20, 12), synth.chain_prox([2, 16, 16, 2], [K2] * 3, dtype=1), 2, 1, 0
+    yield "chain40_k2_bf16", synth.Geom(2, 1, 2, 1, 1, 12, 20), synth.chain_prox([2, 40, 40, 2], [K2] * 3, dtype=1), 2, 1, 0
+
+
+@pytest.mark.parametrize("name,geom,prox,n_iter,bf,loss_kind", list(deep_cases()), ids=[m[0] for m in deep_cases()])
+def test_deep_module_matches_oracle(name, geom, prox, n_iter, bf, loss_kind):
+    from paper_2207_08393_amd.runner import DeepModuleRunner
+    prox.loss_kind = loss_kind
+    c = synth.make_custom(51, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.7)
+    rng = np.random.default_rng(n_iter)
+    thetas = [c.theta + np.float32(0.03 * k) * rng.standard_normal(c.theta.size).astype(np.float32) for k in range(n_iter)]
+    r = DeepModuleRunner(c, thetas, alpha=0.7)
+    r.step()
+    x, loss, grad = r.results()
+    f = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.7, thetas, c.x_true)
+    g = og.deep_module_bwd(c.geom, c.prox, c.S, c.M, 0.7, thetas, f)
+    tol = BF16_TOL if bf else TOL
+    errs = (rel_l2(x, f["x_out"]), abs(loss - f["loss"]) / abs(f["loss"]), [rel_l2(grad[j], g[j]) for j in range(n_iter)])
+    print("case deep", name, "rel errors x_out / loss / grads per iteration:", errs, flush=True)
+    assert errs[0] <= tol and errs[1] <= tol
+    # The gradient of iteration j crosses n_iter-1-j data-consistency steps on its way back.  Each applies
+    # I - alpha A^H A, whose eigenvalues lie in [1-alpha, 1] (normalised maps, orthonormal DFT), so it can raise a
+    # relative error by at most its condition number 1/(1-alpha): rounding noise is spread over all of k-space while
+    # the sampled part of the signal shrinks.  fp32 keeps the plain tolerance; bf16 gets the bound.
+    for j in range(n_iter):
+        assert errs[2][j] <= (tol / (1.0 - 0.7) ** (n_iter - 1 - j) if bf else tol)

@@ -150,3 +150,21 @@ def test_deep_module_of_one_iteration_is_the_plain_module():
     fd = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.9, [th], c.x_true)
     assert np.array_equal(f1["x_out"], fd["x_out"]) and f1["loss"] == fd["loss"]
     assert np.array_equal(og.module_bwd(c.prox, th, f1), og.deep_module_bwd(c.geom, c.prox, c.S, c.M, 0.9, [th], fd)[0])
+
+
+def test_dc_gradient_operator_is_conditioned_by_one_over_one_minus_alpha():
+    """With maps normalised to sum_c |S_c|^2 = 1 and the orthonormal DFT, A^H A has its spectrum in [0, 1]; so
+    I - alpha A^H A (the backward of the data-consistency step) maps any g to a norm in [(1-alpha)|g|, |g|].
+    The bf16 tolerance of modules of several iterations rests on this bound."""
+    c = synth.make_custom(9, synth.Geom(2, 1, 4, 1, 1, 10, 12), synth.resblock_prox(4, 1), accel=3.0, centre=2)
+    rng = np.random.default_rng(2)
+    alpha, nd = 0.7, c.geom.ndim_fft
+    lo, hi = np.inf, 0.0
+    for k in range(20):
+        g = rng.standard_normal(c.geom.image_shape) + 1j * rng.standard_normal(c.geom.image_shape)
+        if k % 2:                                   # half of the probes live in the sampled subspace
+            g = og.sense_normal(g, c.S, c.M, nd)
+        r = np.linalg.norm(g - alpha * og.sense_normal(g, c.S, c.M, nd)) / np.linalg.norm(g)
+        lo, hi = min(lo, r), max(hi, r)
+    assert 1 - alpha - 1e-12 <= lo and hi <= 1 + 1e-12
+    assert lo < 0.6                                 # the contraction is real: sampled components do shrink
