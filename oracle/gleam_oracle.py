@@ -18,6 +18,10 @@ product.  Everything is float64 / complex128 numpy, written as the plain definit
 
   * deep     : a module of K = N/M unrolled iterations (GLEAM section): backpropagation inside the module,
                through its prox networks and data-consistency steps, none beyond its input
+  * MoDL     : the half-quadratic-splitting module (MoDL section, Eq. 6-8): z = f_theta(x), then
+               x+ = (A^H A + mu I)^-1 (A^H y + mu z) by a fixed number of conjugate-gradient steps from zero,
+               one system per batch sample; the backward pass applies the same truncated solve to the loss
+               gradient (the inverse is Hermitian) and stops at the module input
   * greedy   : Alg. 1 for one mini-batch: modules in order, each with its own parameters, local loss,
                local gradient and Adam update (beta1 = 0.9, beta2 = 0.999, Implementation Details); the
                detached output of module m is the input of module m + 1
@@ -27,7 +31,8 @@ Pins (tests/test_oracle_*.py): numpy.fft and closed forms for the DFT, the adjoi
 full-sampling identity A^H A = I, circular-convolution form of a single-coil 1D mask, scipy
 correlate and torch CPU convolutions for the prox, central finite differences and torch autograd
 for the gradient; torch.optim.Adam, the closed-form first step and a two-module torch autograd model
-with a detached hand-off for the greedy iteration.  No function here is unpinned.
+with a detached hand-off for the greedy iteration; a dense solve, the Krylov-subspace optimality of the
+truncated iterate and torch autograd through torch.linalg.solve for the MoDL module.  No function here is unpinned.
 
 Array layouts: image [B,T,D,H,W], coils [B,C,D,H,W], mask [B,T,D,H,W], k-space [B,C,T,D,H,W],
 activations [B,T,D,H,W,channels] (an image is its own 2-channel activation: re, im).
@@ -304,6 +309,55 @@ def deep_module_bwd(geom, prox, S, M, alpha, thetas, fwd):
             gc = channels_to_complex(g_u)
             g_out = complex_to_channels(gc - alpha * sense_normal(gc, S, M, geom.ndim_fft))
     return grads
+
+
+# ----------------------------------------------------------------------------- MoDL module (Eq. 6-8)
+def cg_solve(x_shape, S, M, mu, b, n_cg, ndim_fft):
+    """n_cg conjugate-gradient steps from x = 0 on (A^H A + mu I) x = b, one system per batch sample
+    (leading axis): the textbook recurrence
+        a = <r,r> / <p, Q p> ; x += a p ; r -= a Q p ; beta = <r,r>_new / <r,r>_old ; p = r + beta p.
+    A sample whose residual is exactly zero stops moving (a = beta = 0) instead of dividing by zero."""
+    b = np.asarray(b, np.complex128)
+    x = np.zeros(x_shape, np.complex128)
+    r = b.copy()
+    p = b.copy()
+    B = b.shape[0]
+    axes = tuple(range(1, b.ndim))
+    bc = (slice(None),) + (None,) * (b.ndim - 1)
+    rr = np.sum(np.abs(r) ** 2, axis=axes)
+    for _ in range(n_cg):
+        Qp = sense_normal(p, S, M, ndim_fft) + mu * p
+        pQp = np.sum((np.conj(p) * Qp).real, axis=axes)
+        a = np.where(pQp > 0, rr / np.where(pQp > 0, pQp, 1.0), 0.0)
+        x = x + a[bc] * p
+        r = r - a[bc] * Qp
+        rr_new = np.sum(np.abs(r) ** 2, axis=axes)
+        beta = np.where(rr > 0, rr_new / np.where(rr > 0, rr, 1.0), 0.0)
+        p = r + beta[bc] * p
+        rr = rr_new
+    assert x.shape[0] == B
+    return x
+
+
+def modl_module_fwd(geom, prox, x_in, S, M, aty, mu, n_cg, theta, x_ref=None):
+    """One MoDL module: z = f_theta(x_in) (Eq. 8), x_out = (A^H A + mu I)^-1 (A^H y + mu z) by n_cg CG steps
+    (Eq. 7); aty is A^H y.  Loss against x_ref when given."""
+    t, conv_in, act = prox_fwd(prox.layers, theta, np.asarray(x_in, np.complex128))
+    z = channels_to_complex(t[-1])
+    x_out = cg_solve(z.shape, S, M, mu, np.asarray(aty, np.complex128) + mu * z, n_cg, geom.ndim_fft)
+    out = {"z": z, "x_out": x_out, "t": t, "conv_in": conv_in, "act": act, "loss": None, "g_x": None}
+    if x_ref is not None:
+        out["loss"], out["g_x"] = loss_and_grad(x_out, x_ref, prox.loss_kind)
+    return out
+
+
+def modl_module_bwd(geom, prox, S, M, mu, n_cg, theta, fwd):
+    """dL/dtheta of the MoDL module.  x_out = Q^-1 (A^H y + mu z) with Q = A^H A + mu I Hermitian, so
+    dL/dz = mu Q^-1 dL/dx_out; the inverse is again applied by n_cg CG steps (the same truncated solve as
+    the forward pass), then the prox is swept backwards.  Nothing goes to the module input."""
+    gx = channels_to_complex(fwd["g_x"])
+    g_z = complex_to_channels(mu * cg_solve(gx.shape, S, M, mu, gx, n_cg, geom.ndim_fft))
+    return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], g_z)
 
 
 # ----------------------------------------------------------------------------- greedy training (Alg. 1)
