@@ -199,6 +199,18 @@ def main():
     deep_ms = 1e3 * (time.perf_counter() - t0) / n_it
     del dr
 
+    # one MoDL module (Eq. 6-8) on the same data: prox, 10 CG steps forward, 10 CG steps backward, prox backward
+    from paper_2207_08393_amd.runner import ModlRunner
+    mr = ModlRunner(case, 0.05, 10)
+    mr.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_it):
+        mr.step()
+    torch.cuda.synchronize()
+    modl_ms = 1e3 * (time.perf_counter() - t0) / n_it
+    del mr
+
     out = {"metric": "GLEAM module fwd+bwd steps/s", "value": args.steps / dt, "unit": "module steps/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -215,6 +227,8 @@ def main():
                                 "includes": "fwd + bwd + Adam update of every module, detached hand-off"}}
     out["deep_module"] = {"iterations_per_module": 2, "ms": deep_ms,
                           "includes": "fwd + bwd of one module holding two unrolled iterations"}
+    out["modl_module"] = {"mu": 0.05, "cg_steps": 10, "ms": modl_ms,
+                          "includes": "fwd + bwd of one MoDL module: prox, 10 CG steps each way (20 A^H A sweeps)"}
     if not args.no_cpu_baseline and args.workload in (0, 1, 4):
         out["cpu_baseline"] = cpu_baseline(case)
     print(json.dumps(out))

@@ -135,6 +135,33 @@ int gleam_deep_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, i
                           void* saved, size_t saved_bytes, float* grad_theta, void* ws, size_t ws_bytes,
                           void* stream);
 
+/* out = A^H y = S^H F^H Omega y (Eq. 2's adjoint; the zero-filled SENSE image the networks start from and the
+ * constant term of the MoDL update).  ws as sized by gleam_workspace_bytes(geom, NULL or prox) plus one image
+ * (B*T*D*H*W complex64), or simply by gleam_modl_workspace_bytes.  out must not alias y. */
+int gleam_sense_adjoint(const gleam_geom* geom, const gleam_c64* S, const uint8_t* M, const gleam_c64* y,
+                        gleam_c64* out, void* ws, size_t ws_bytes, void* stream);
+
+/* One MoDL module (MoDL section, Eq. 6-8):
+ *     z = f_theta(x_in)                                   (Eq. 8)
+ *     x_out = (A^H A + mu I)^-1 (aty + mu z),  aty = A^H y (Eq. 7)
+ * solved by exactly n_cg conjugate-gradient steps from zero, one system per batch sample (all scalars of the
+ * recurrence stay on the device; a sample whose residual is exactly zero stops moving).  With x_ref the local
+ * loss (device scalar) is produced and `saved` keeps what the backward pass needs.
+ * gleam_modl_module_bwd: dL/dtheta; dL/dz = mu (A^H A + mu I)^-1 dL/dx_out is formed by the same n_cg-step
+ * solve, then the prox is swept backwards; nothing is propagated to x_in.
+ *   mu >= 0, n_cg >= 1 (else GLEAM_E_DIMS).  The last prox layer must not end in a ReLU (GLEAM_E_DESC).
+ *   saved : as gleam_workspace_bytes reports (written by the backward pass as well).
+ *   ws    : gleam_modl_workspace_bytes; x_out must not alias x_in, aty or x_ref. */
+int gleam_modl_workspace_bytes(const gleam_geom* geom, const gleam_prox_desc* prox, size_t* ws_bytes,
+                               size_t* saved_bytes);
+int gleam_modl_module_fwd(const gleam_geom* geom, const gleam_prox_desc* prox, const gleam_c64* x_in,
+                          const gleam_c64* S, const uint8_t* M, const gleam_c64* aty, float mu, int n_cg,
+                          const float* theta, const gleam_c64* x_ref, gleam_c64* x_out, float* loss,
+                          void* saved, size_t saved_bytes, void* ws, size_t ws_bytes, void* stream);
+int gleam_modl_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const gleam_c64* S,
+                          const uint8_t* M, float mu, int n_cg, const float* theta, void* saved,
+                          size_t saved_bytes, float* grad_theta, void* ws, size_t ws_bytes, void* stream);
+
 /* Adam hyper-parameters (Implementation Details: beta1 = 0.9, beta2 = 0.999; the paper does not state the
  * learning rate or epsilon). */
 typedef struct {

@@ -75,6 +75,10 @@ def lib() -> C.CDLL:
         L.gleam_deep_workspace_bytes.argtypes = [pg, pp, C.c_int, C.POINTER(sz), C.POINTER(sz)]
         L.gleam_deep_module_fwd.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_deep_module_bwd.argtypes = [pg, pp, C.c_int, vp, vp, C.c_float, vp, vp, sz, vp, vp, sz, vp]
+        L.gleam_sense_adjoint.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
+        L.gleam_modl_workspace_bytes.argtypes = [pg, pp, C.POINTER(sz), C.POINTER(sz)]
+        L.gleam_modl_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.gleam_modl_module_bwd.argtypes = [pg, pp, vp, vp, C.c_float, C.c_int, vp, vp, sz, vp, vp, sz, vp]
         L.gleam_adam_step.argtypes = [C.POINTER(gleam_adam), C.c_int64, sz, vp, vp, vp, vp, vp]
         L.gleam_greedy_iteration.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, C.POINTER(gleam_adam),
                                              C.c_int64, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
@@ -87,7 +91,8 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
            "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_deep_workspace_bytes",
-           "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_adam_step",
+           "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_sense_adjoint", "gleam_modl_workspace_bytes",
+           "gleam_modl_module_fwd", "gleam_modl_module_bwd", "gleam_adam_step",
            "gleam_greedy_iteration", "gleam_unrolled_infer", "gleam_profile_begin", "gleam_profile_end")
 
 
@@ -191,6 +196,30 @@ def gleam_deep_module_bwd(geom, prox, n_iter, S, M, alpha, theta, saved, grad_th
     _check(lib().gleam_deep_module_bwd(C.byref(geom), C.byref(prox), int(n_iter), _ptr(S), _ptr(M), C.c_float(alpha),
                                        _ptr(theta), _ptr(saved), _nbytes(saved), _ptr(grad_theta), _ptr(ws), _nbytes(ws),
                                        _stream(stream)), "gleam_deep_module_bwd")
+
+
+def gleam_sense_adjoint(geom, S, M, y, out, ws, stream=None):
+    _check(lib().gleam_sense_adjoint(C.byref(geom), _ptr(S), _ptr(M), _ptr(y), _ptr(out), _ptr(ws), _nbytes(ws),
+                                     _stream(stream)), "gleam_sense_adjoint")
+
+
+def gleam_modl_workspace_bytes(geom, prox):
+    ws, saved = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().gleam_modl_workspace_bytes(C.byref(geom), C.byref(prox), C.byref(ws), C.byref(saved)),
+           "gleam_modl_workspace_bytes")
+    return ws.value, saved.value
+
+
+def gleam_modl_module_fwd(geom, prox, x_in, S, M, aty, mu, n_cg, theta, x_ref, x_out, loss, saved, ws, stream=None):
+    _check(lib().gleam_modl_module_fwd(C.byref(geom), C.byref(prox), _ptr(x_in), _ptr(S), _ptr(M), _ptr(aty), C.c_float(mu),
+                                       int(n_cg), _ptr(theta), _ptr(x_ref), _ptr(x_out), _ptr(loss), _ptr(saved),
+                                       _nbytes(saved), _ptr(ws), _nbytes(ws), _stream(stream)), "gleam_modl_module_fwd")
+
+
+def gleam_modl_module_bwd(geom, prox, S, M, mu, n_cg, theta, saved, grad_theta, ws, stream=None):
+    _check(lib().gleam_modl_module_bwd(C.byref(geom), C.byref(prox), _ptr(S), _ptr(M), C.c_float(mu), int(n_cg),
+                                       _ptr(theta), _ptr(saved), _nbytes(saved), _ptr(grad_theta), _ptr(ws), _nbytes(ws),
+                                       _stream(stream)), "gleam_modl_module_bwd")
 
 
 def make_adam(lr, beta1=0.9, beta2=0.999, eps=1e-8) -> gleam_adam:

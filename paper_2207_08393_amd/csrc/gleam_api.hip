@@ -298,6 +298,104 @@ int gleam_deep_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, i
     return GLEAM_OK;
 }
 
+int gleam_sense_adjoint(const gleam_geom* geom, const gleam_c64* S, const uint8_t* M, const gleam_c64* y, gleam_c64* out,
+                        void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    if (!S || !M || !y || !out || !ws) return GLEAM_E_NULL;
+    if (out == y) return GLEAM_E_DIMS;
+    const size_t kb = align_up(n_coil_pixels(*geom) * sizeof(float2));
+    const long long n = geom->B * geom->T * geom->D * geom->H * geom->W;
+    if (!aligned(ws) || ws_bytes < kb + (size_t)n * sizeof(float2)) return GLEAM_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    // A^H y = -(A^H (A 0 - y)): the fused sweep on a zero image
+    float2* zero = (float2*)((unsigned char*)ws + kb);
+    hipError_t e = fill_zero(zero, n, st);
+    if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    e = sense_dc(*geom, zero, (const float2*)S, M, (const float2*)y, 0.f, -1.f, (float2*)out, (float2*)ws, st);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+static int check_modl(const gleam_geom* geom, const gleam_prox_desc* prox, float mu, int n_cg) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    rc = check_prox(prox);
+    if (rc) return rc;
+    if (prox->layers[prox->n_layers - 1].relu_out) return GLEAM_E_DESC;
+    if (!(mu >= 0.f) || !(mu < 3.0e38f) || n_cg < 1) return GLEAM_E_DIMS;
+    return GLEAM_OK;
+}
+
+int gleam_modl_workspace_bytes(const gleam_geom* geom, const gleam_prox_desc* prox, size_t* ws_bytes, size_t* saved_bytes) {
+    if (!prox) return GLEAM_E_NULL;
+    int rc = gleam_workspace_bytes(geom, prox, ws_bytes, saved_bytes);
+    if (rc) return rc;
+    if (prox->layers[prox->n_layers - 1].relu_out) return GLEAM_E_DESC;
+    *ws_bytes = align_up(*ws_bytes) + cg_scratch_bytes(*geom);
+    return GLEAM_OK;
+}
+
+int gleam_modl_module_fwd(const gleam_geom* geom, const gleam_prox_desc* prox, const gleam_c64* x_in, const gleam_c64* S,
+                          const uint8_t* M, const gleam_c64* aty, float mu, int n_cg, const float* theta,
+                          const gleam_c64* x_ref, gleam_c64* x_out, float* loss, void* saved, size_t saved_bytes, void* ws,
+                          size_t ws_bytes, void* stream) {
+    int rc = check_modl(geom, prox, mu, n_cg);
+    if (rc) return rc;
+    if (!x_in || !S || !M || !aty || !theta || !x_out || !ws) return GLEAM_E_NULL;
+    if (x_ref && (!loss || !saved)) return GLEAM_E_NULL;
+    if (x_out == x_in || x_out == aty || (x_ref && x_out == x_ref)) return GLEAM_E_DIMS;
+    size_t ws_need = 0, saved_need = 0;
+    rc = gleam_modl_workspace_bytes(geom, prox, &ws_need, &saved_need);
+    if (rc) return rc;
+    if (!aligned(ws) || ws_bytes < ws_need) return GLEAM_E_WORKSPACE;
+    if (saved && (!aligned(saved) || saved_bytes < saved_need)) return GLEAM_E_WORKSPACE;
+    ProxPlan plan;
+    plan_prox(*geom, *prox, plan);
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char* act_base = saved ? (unsigned char*)saved : (unsigned char*)ws + plan.k_bytes;
+    unsigned char* scratch = (unsigned char*)ws + (ws_need - cg_scratch_bytes(*geom));
+    const size_t img = (size_t)plan.Q * sizeof(float2);
+    // the prox input t_0 is the module input itself
+    if (hipMemcpyAsync(act_base + plan.act_off[0], x_in, img, hipMemcpyDeviceToDevice, st) != hipSuccess) return GLEAM_E_LAUNCH;
+    // z lands in the solver's third vector, which the first operator application overwrites only after the
+    // right-hand side aty + mu z has been formed
+    float2* z = (float2*)(scratch + 2 * align_up(img));
+    hipError_t e = prox_forward(*geom, *prox, plan, theta, act_base, nullptr, z, nullptr, ws, st);
+    if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    e = cg_solve(*geom, (const float2*)S, M, mu, n_cg, (const float2*)aty, z, 1.f, mu, (float2*)x_out, (float2*)ws, scratch, st);
+    if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    if (x_ref) {
+        e = loss_and_grad((const float2*)x_out, (const float2*)x_ref, (float2*)(act_base + plan.gz_off), plan.Q, prox->loss_kind,
+                          0, (double*)((unsigned char*)ws + plan.red_off), loss, st);
+        if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    }
+    return GLEAM_OK;
+}
+
+int gleam_modl_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const gleam_c64* S, const uint8_t* M, float mu,
+                          int n_cg, const float* theta, void* saved, size_t saved_bytes, float* grad_theta, void* ws,
+                          size_t ws_bytes, void* stream) {
+    int rc = check_modl(geom, prox, mu, n_cg);
+    if (rc) return rc;
+    if (!S || !M || !theta || !saved || !grad_theta || !ws) return GLEAM_E_NULL;
+    size_t ws_need = 0, saved_need = 0;
+    rc = gleam_modl_workspace_bytes(geom, prox, &ws_need, &saved_need);
+    if (rc) return rc;
+    if (!aligned(ws) || ws_bytes < ws_need) return GLEAM_E_WORKSPACE;
+    if (!aligned(saved) || saved_bytes < saved_need) return GLEAM_E_WORKSPACE;
+    ProxPlan plan;
+    plan_prox(*geom, *prox, plan);
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char* scratch = (unsigned char*)ws + (ws_need - cg_scratch_bytes(*geom));
+    // dL/dz = mu Q^-1 dL/dx_out, solved in place: the solve is linear in its right-hand side, so the factor mu
+    // goes into the right-hand side and the solution replaces the loss gradient where the prox sweep expects it
+    float2* g = (float2*)((unsigned char*)saved + plan.gz_off);
+    hipError_t e = cg_solve(*geom, (const float2*)S, M, mu, n_cg, g, nullptr, mu, 0.f, g, (float2*)ws, scratch, st);
+    if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    e = prox_backward(*geom, *prox, plan, theta, (const unsigned char*)saved, grad_theta, nullptr, ws, st);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
 int gleam_adam_step(const gleam_adam* hyper, int64_t t, size_t n, float* theta, const float* grad, float* m, float* v,
                     void* stream) {
     if (!hyper || !theta || !grad || !m || !v) return GLEAM_E_NULL;

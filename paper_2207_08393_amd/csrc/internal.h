@@ -81,6 +81,20 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
 hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const ProxPlan& plan, const float* theta,
                          const unsigned char* saved, float* grad_theta, float2* g_in, void* ws, hipStream_t st);
 
+// loss (device scalar) of x against x_ref and g = dL/dx (2 real channels); `part` holds kLossPartials doubles.
+// relu_mask: zero the gradient where x <= 0 (x is the output of a layer that ends in a ReLU).
+constexpr int kLossPartials = 512;
+hipError_t loss_and_grad(const float2* x, const float2* x_ref, float2* g, long long n, int loss_kind, int relu_mask,
+                         double* part, float* loss, hipStream_t st);
+
+// n_cg conjugate-gradient steps from zero on (A^H A + mu I) x = c1*u + c2*v (v may be null), one system per
+// batch sample.  x may alias u.  kbuf: coil k-space buffer of sense_dc; scratch: cg_scratch_bytes(g) bytes.
+constexpr int kCgBlocksMax = 64;   // workgroups (= partial sums) per batch sample
+size_t cg_scratch_bytes(const gleam_geom& g);
+hipError_t cg_solve(const gleam_geom& g, const float2* S, const unsigned char* M, float mu, int n_cg, const float2* u,
+                    const float2* v, float c1, float c2, float2* x, float2* kbuf, void* scratch, hipStream_t st);
+hipError_t fill_zero(float2* x, long long n, hipStream_t st);
+
 // theta <- Adam(theta, grad) in place with state m, v; bias corrections evaluated on the host in double.
 hipError_t adam_update(const gleam_adam& h, long long t, size_t n, float* theta, const float* grad, float* m, float* v,
                        hipStream_t st);

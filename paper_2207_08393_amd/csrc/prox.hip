@@ -1692,7 +1692,16 @@ __global__ void loss_final_kernel(const double* __restrict__ part, int n_part, d
 
 // ------------------------------------------------------------------ host side
 static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
-constexpr int kLossBlocks = 512;
+constexpr int kLossBlocks = kLossPartials;
+
+hipError_t loss_and_grad(const float2* x, const float2* x_ref, float2* g, long long n, int loss_kind, int relu_mask,
+                         double* part, float* loss, hipStream_t st) {
+    KernelScope ks("loss", 0.0, 24.0 * (double)n, st);
+    hipLaunchKernelGGL(loss_kernel, dim3(kLossBlocks), dim3(256), 0, st, x, x_ref, g, n, loss_kind, (float)(1.0 / (double)n),
+                       relu_mask, part);
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, kLossBlocks, 1.0 / (double)n, loss);
+    return hipGetLastError();
+}
 
 static PixDims pix_dims(const gleam_geom& g, const gleam_conv& c) {
     PixDims d;
@@ -1852,11 +1861,7 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
         const long long n = plan.Q;
         double* part = reinterpret_cast<double*>((unsigned char*)ws + plan.red_off);
         float2* gz = reinterpret_cast<float2*>(act_base + plan.gz_off);
-        KernelScope ks("loss", 0.0, 24.0 * (double)n, st);
-        hipLaunchKernelGGL(loss_kernel, dim3(kLossBlocks), dim3(256), 0, st, (const float2*)x_out, x_ref, gz, n,
-                           p.loss_kind, (float)(1.0 / (double)n), p.layers[L - 1].relu_out, part);
-        hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, kLossBlocks, 1.0 / (double)n, loss);
-        return hipGetLastError();
+        return loss_and_grad((const float2*)x_out, x_ref, gz, n, p.loss_kind, p.layers[L - 1].relu_out, part, loss, st);
     }
     return hipSuccess;
 }

@@ -153,3 +153,36 @@ class DeepModuleRunner:
     def results(self):
         torch.cuda.synchronize()
         return to_complex(self.x_out), float(self.loss.item()), self.grad.cpu().numpy()
+
+
+class ModlRunner:
+    """One MoDL module (prox, then n_cg conjugate-gradient steps on A^H A + mu I): `step()` = fwd + bwd.
+    A^H y is formed once at construction with gleam_sense_adjoint."""
+
+    def __init__(self, case, mu, n_cg, theta=None):
+        self.case = case
+        self.geom = gb.make_geom(case.geom)
+        self.prox = gb.make_prox(case.prox)
+        self.mu, self.n_cg = float(mu), int(n_cg)
+        self.ws_bytes, self.saved_bytes = gb.gleam_modl_workspace_bytes(self.geom, self.prox)
+        self.ws = byte_buffer(self.ws_bytes)
+        self.saved = byte_buffer(self.saved_bytes)
+        self.x_in = cplx(case.x_in)
+        self.S, self.M, self.y = cplx(case.S), dev(case.M), cplx(case.y)
+        self.x_ref = cplx(case.x_true)
+        self.theta = dev(np.asarray(case.theta if theta is None else theta, np.float32))
+        self.aty = torch.full_like(self.x_in, float("nan"))
+        gb.gleam_sense_adjoint(self.geom, self.S, self.M, self.y, self.aty, self.ws)
+        self.x_out = torch.full_like(self.x_in, float("nan"))
+        self.loss = torch.full((1,), float("nan"), device="cuda")
+        self.grad = torch.full_like(self.theta, float("nan"))
+
+    def step(self):
+        gb.gleam_modl_module_fwd(self.geom, self.prox, self.x_in, self.S, self.M, self.aty, self.mu, self.n_cg, self.theta,
+                                 self.x_ref, self.x_out, self.loss, self.saved, self.ws)
+        gb.gleam_modl_module_bwd(self.geom, self.prox, self.S, self.M, self.mu, self.n_cg, self.theta, self.saved, self.grad,
+                                 self.ws)
+
+    def results(self):
+        torch.cuda.synchronize()
+        return to_complex(self.x_out), float(self.loss.item()), self.grad.cpu().numpy(), to_complex(self.aty)

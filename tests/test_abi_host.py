@@ -195,3 +195,56 @@ def test_deep_module_entry_points_reject_bad_arguments_before_launch():
     assert L.gleam_deep_module_bwd(*a) == gb.GLEAM_E_WORKSPACE
     a = list(bargs); a[2] = 0
     assert L.gleam_deep_module_bwd(*a) == gb.GLEAM_E_DIMS
+
+
+def test_modl_entry_points_reject_bad_arguments_before_launch():
+    c = synth.make_case(0)
+    geom, prox = gb.make_geom(c.geom), gb.make_prox(c.prox)
+    ws1, saved1 = gb.gleam_workspace_bytes(geom, prox)
+    ws, saved = gb.gleam_modl_workspace_bytes(geom, prox)
+    n_img = c.geom.B * c.geom.T * c.geom.D * c.geom.H * c.geom.W * 8
+    assert saved == saved1 and ws >= ws1 + 3 * n_img      # residual, direction and operator output
+    L = gb.lib()
+    fake, x0, xo, aty = 0x1000, 0x2000, 0x3000, 0x4000
+    mu = C.c_float(0.5)
+    fargs = [C.byref(geom), C.byref(prox), x0, fake, fake, aty, mu, 10, fake, fake, xo, fake, fake, saved, fake, ws, None]
+    for i in (2, 3, 4, 5, 8, 10, 11, 12, 14):
+        a = list(fargs); a[i] = None
+        assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_NULL, i
+    a = list(fargs); a[10] = x0
+    assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_DIMS
+    a = list(fargs); a[10] = aty
+    assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_DIMS
+    a = list(fargs); a[7] = 0
+    assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_DIMS
+    a = list(fargs); a[6] = C.c_float(-1.0)
+    assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_DIMS
+    a = list(fargs); a[6] = C.c_float(float("nan"))
+    assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_DIMS
+    a = list(fargs); a[15] = ws1                          # a plain module workspace is too small for the solver
+    assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(fargs); a[13] = saved - 256
+    assert L.gleam_modl_module_fwd(*a) == gb.GLEAM_E_WORKSPACE
+    bargs = [C.byref(geom), C.byref(prox), fake, fake, mu, 10, fake, fake, saved, fake, fake, ws, None]
+    for i in (2, 3, 6, 7, 9, 10):
+        a = list(bargs); a[i] = None
+        assert L.gleam_modl_module_bwd(*a) == gb.GLEAM_E_NULL, i
+    a = list(bargs); a[5] = -3
+    assert L.gleam_modl_module_bwd(*a) == gb.GLEAM_E_DIMS
+    a = list(bargs); a[11] = ws - 256
+    assert L.gleam_modl_module_bwd(*a) == gb.GLEAM_E_WORKSPACE
+    # a prox that ends in a ReLU would need the mask of z behind the solve: not supported
+    relu_last = synth.chain_prox([2, 8, 2], [(1, 1, 3, 3)] * 2)
+    relu_last.layers[-1].relu_out = 1
+    p = gb.make_prox(relu_last)
+    w, s = C.c_size_t(0), C.c_size_t(0)
+    assert L.gleam_modl_workspace_bytes(C.byref(geom), C.byref(p), C.byref(w), C.byref(s)) == gb.GLEAM_E_DESC
+    # adjoint
+    aargs = [C.byref(geom), fake, fake, x0, xo, fake, ws, None]
+    for i in (1, 2, 3, 4, 5):
+        a = list(aargs); a[i] = None
+        assert L.gleam_sense_adjoint(*a) == gb.GLEAM_E_NULL, i
+    a = list(aargs); a[4] = x0
+    assert L.gleam_sense_adjoint(*a) == gb.GLEAM_E_DIMS
+    a = list(aargs); a[6] = 1024
+    assert L.gleam_sense_adjoint(*a) == gb.GLEAM_E_WORKSPACE

@@ -305,3 +305,49 @@ def test_deep_module_matches_oracle(name, geom, prox, n_iter, bf, loss_kind):
     # the sampled part of the signal shrinks.  fp32 keeps the plain tolerance; bf16 gets the bound.
     for j in range(n_iter):
         assert errs[2][j] <= (tol / (1.0 - 0.7) ** (n_iter - 1 - j) if bf else tol)
+
+
+# ----------------------------------------------------------------------------- MoDL module (Eq. 6-8)
+def modl_cases():
+    yield "res8_mu0.4_cg10", synth.Geom(2, 2, 3, 1, 1, 12, 10), synth.resblock_prox(8, 1), 0.4, 10, 0
+    yield "res64_mu0.05_cg10_l1", synth.Geom(2, 1, 4, 1, 1, 24, 32), synth.resblock_prox(64, 1), 0.05, 10, 1
+    yield "chain16_mu4_cg3", synth.Geom(2, 3, 2, 1, 1, 20, 12), synth.chain_prox([2, 16, 16, 2], [K2] * 3), 4.0, 3, 0
+    yield "vol32_mu0.05_cg10", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), 0.05, 10, 0
+    yield "cine16_mu0.5_cg1", synth.Geom(2, 1, 2, 4, 1, 6, 8), synth.chain_prox([2, 16, 16, 2], [KS, KT, KT]), 0.5, 1, 0
+    yield "chain16_bf16_mu0.4_cg10", synth.Geom(2, 1, 2, 1, 1, 20, 12), synth.chain_prox([2, 16, 16, 2], [K2] * 3, dtype=1), 0.4, 10, 0
+
+
+@pytest.mark.parametrize("name,geom,prox,mu,n_cg,loss_kind", list(modl_cases()), ids=[m[0] for m in modl_cases()])
+def test_modl_module_matches_oracle(name, geom, prox, mu, n_cg, loss_kind):
+    from paper_2207_08393_amd.runner import ModlRunner
+    prox.loss_kind = loss_kind
+    c = synth.make_custom(61, geom, prox, accel=3.0, centre=2, bias_std=0.1)
+    r = ModlRunner(c, mu, n_cg)
+    r.step()
+    x, loss, grad, aty = r.results()
+    nd = c.geom.ndim_fft
+    aty_o = og.sense_adjoint(c.y.astype(np.complex128), c.S, c.M, nd)
+    f = og.modl_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, aty_o, mu, n_cg, c.theta, c.x_true)
+    g = og.modl_module_bwd(c.geom, c.prox, c.S, c.M, mu, n_cg, c.theta, f)
+    errs = (rel_l2(aty, aty_o), rel_l2(x, f["x_out"]), abs(loss - f["loss"]) / abs(f["loss"]), rel_l2(grad, g))
+    print("case modl", name, "rel errors A^H y / x_out / loss / grad:", errs, flush=True)
+    tol = BF16_TOL if c.prox.dtype == 1 else TOL
+    assert errs[0] <= TOL and max(errs[1:]) <= tol
+
+
+def test_modl_module_survives_an_exactly_converged_solve():
+    """One coil of unit magnitude and full sampling make A^H A the identity: CG converges in its first step, the
+    residual is exactly zero afterwards and the remaining steps must leave the solution alone (no 0/0)."""
+    from paper_2207_08393_amd.runner import ModlRunner
+    geom = synth.Geom(2, 2, 1, 1, 1, 8, 8)
+    c = synth.make_custom(62, geom, synth.resblock_prox(8, 1), mask_kind="full", bias_std=0.1)
+    c.S[...] = 1.0
+    c.y[...] = og.sense_forward(c.x_true.astype(np.complex128), c.S, c.M, 2).astype(np.complex64)
+    r = ModlRunner(c, 0.5, 6)
+    r.step()
+    x, loss, grad, aty = r.results()
+    aty_o = og.sense_adjoint(c.y.astype(np.complex128), c.S, c.M, 2)
+    f = og.modl_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, aty_o, 0.5, 6, c.theta, c.x_true)
+    g = og.modl_module_bwd(c.geom, c.prox, c.S, c.M, 0.5, 6, c.theta, f)
+    assert np.all(np.isfinite(x)) and np.all(np.isfinite(grad))
+    assert rel_l2(x, f["x_out"]) <= TOL and rel_l2(grad, g) <= TOL
