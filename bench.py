@@ -185,6 +185,12 @@ def main():
         gr.iteration(2 + k)
     torch.cuda.synchronize()
     greedy_ms = 1e3 * (time.perf_counter() - t0) / n_it
+    # activation memory: greedy training keeps one module's activations at a time; end-to-end backpropagation
+    # through the same N = M modules would keep all of them (estimate, not built)
+    mem = {"activations_one_module_bytes": gr.saved_bytes, "workspace_bytes": gr.ws_bytes,
+           "greedy_peak_bytes": gr.saved_bytes + gr.ws_bytes,
+           "end_to_end_estimate_bytes": case.n_modules * gr.saved_bytes + gr.ws_bytes,
+           "ratio": (case.n_modules * gr.saved_bytes + gr.ws_bytes) / (gr.saved_bytes + gr.ws_bytes)}
     del gr
 
     # a module of two unrolled iterations (N/M = 2): fwd + bwd through both prox networks and the DC step between
@@ -224,7 +230,8 @@ def main():
                         "ms_per_step": conv_ms / args.steps},
            "sense_normal": sense, "kernels": kernels,
            "greedy_iteration": {"modules": case.n_modules, "ms": greedy_ms, "iterations_per_s": 1e3 / greedy_ms,
-                                "includes": "fwd + bwd + Adam update of every module, detached hand-off"}}
+                                "includes": "fwd + bwd + Adam update of every module, detached hand-off",
+                                "memory": mem}}
     out["deep_module"] = {"iterations_per_module": 2, "ms": deep_ms,
                           "includes": "fwd + bwd of one module holding two unrolled iterations"}
     out["modl_module"] = {"mu": 0.05, "cg_steps": 10, "ms": modl_ms,

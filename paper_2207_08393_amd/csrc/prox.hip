@@ -958,6 +958,15 @@ static size_t conv_wimg_floats(int K, int Nn, int taps) {
     return (size_t)taps * ((K + ck - 1) / ck) * ck * ((Nn + nb - 1) / nb) * nb;
 }
 
+// The Winograd path can be switched off (GLEAM_NO_WINOGRAD=1 in the environment) to time the direct kernels.
+static bool wino_enabled() {
+    static const bool on = [] {
+        const char* e = getenv("GLEAM_NO_WINOGRAD");
+        return !(e && e[0] == '1');
+    }();
+    return on;
+}
+
 template <int KT, int KD, int KH, int KW>
 static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, bool bf, hipStream_t st) {
     ConvThinInArgs t{a, cw.w, cw.sn, cw.st, cw.sk};
@@ -1068,6 +1077,15 @@ static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scrat
         bool hit = false;
         const hipError_t e = launch_conv_thin_out(a, cw, false, wt_scratch, &hit, st);
         if (hit || e != hipSuccess) return e;
+    }
+    if (wino_enabled() && conv_wino_applies(a.d, a.K, a.Nn)) {   // 3x3 in the plane: Winograd F(2x2, 3x3)
+        WinoArgs wa{};
+        wa.in = a.in; wa.out = a.out; wa.bias = a.bias; wa.mask_ref = a.mask_ref; wa.add = a.add;
+        wa.K = a.K; wa.Nn = a.Nn; wa.relu_out = a.relu_out; wa.mask_acc = a.mask_acc; wa.mask_add = a.mask_add;
+        wa.H = a.d.H; wa.W = a.d.W; wa.NI = a.d.Q / ((long long)a.d.H * a.d.W);
+        char name[56];
+        snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
+        return launch_conv_wino(wa, cw.w, cw.sn, cw.st, cw.sk, a.flip, a.relu_in, wt_scratch, name, st);
     }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
     {
@@ -1790,6 +1808,10 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
         const size_t f = conv_wimg_floats(c.cin, c.cout, taps), b = conv_wimg_floats(c.cout, c.cin, taps);
         max_img = f > max_img ? f : max_img;
         max_img = b > max_img ? b : max_img;
+        if (taps == 9) {      // transformed weights of the Winograd path (16 values per channel pair)
+            const size_t wn = conv_wino_weight_floats(c.cin, c.cout);
+            max_img = wn > max_img ? wn : max_img;
+        }
         if (p.dtype == 1) {   // bf16 images are half the bytes per element, but chunked by 32 channels
             const size_t fb = (conv_bf16_wimg_elems(c.cin, c.cout, taps) + 1) / 2, bb = (conv_bf16_wimg_elems(c.cout, c.cin, taps) + 1) / 2;
             max_img = fb > max_img ? fb : max_img;

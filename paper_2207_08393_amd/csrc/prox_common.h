@@ -149,6 +149,25 @@ __device__ __forceinline__ ChunkIter chunk_next(ChunkIter x, int n_kc, int nck, 
 
 // Launch arguments of the bf16 MFMA convolution (forward and data gradient): in/out/mask_ref/add are
 // bfloat16 [Q][channels] unless out_f32 (then out and add are float32).  wt: bf16 LDS images.
+// Winograd F(2x2, 3x3) convolution, float32 (prox_wino.hip).  Same fused epilogue as the direct kernels.
+struct WinoArgs {
+    const float* in;        // [NI][H][W][K]
+    float* out;             // [NI][H][W][Nn]
+    const float* u;         // transformed weights (set by the launcher)
+    const float* zero;      // one quad of zeros in global memory (set by the launcher)
+    const float* bias;      // [Nn] or null
+    const float* mask_ref;  // [Q][Nn] or null: ReLU mask source (value > 0 passes)
+    const float* add;       // [Q][Nn] or null
+    int K, Nn, relu_out, mask_acc, mask_add;
+    long long NI;           // images (B*T*D)
+    int H, W, bx_n, by_n;
+    long long n_blocks;
+};
+bool conv_wino_applies(const PixDims& d, int K, int Nn);
+size_t conv_wino_weight_floats(int K, int Nn);
+hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st, long long sk, int flip, int relu_in,
+                            float* u_scratch, const char* name, hipStream_t stream);
+
 struct ConvBf16Args {
     const unsigned short* in;
     void* out;

@@ -1,0 +1,289 @@
+// 3x3 convolution (forward and data gradient, float32) by the Winograd minimal-filtering algorithm
+// F(2x2, 3x3) of Lavin & Gray on gfx950: every 2x2 block of outputs comes from 16 multiplications per
+// (input channel, output channel) pair instead of 36, and the 16 element-wise products over all channels
+// are 16 independent matrix products that run on the matrix cores:
+//     Y = A^T [ sum_k (G g_k G^T) .* (B^T d_k B) ] A
+// with d the 4x4 input patch around the 2x2 output block, g the 3x3 kernel, and the constant matrices
+//     B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1],  G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1],
+//     A^T = [1 1 1 0; 0 1 -1 -1].
+// Everything is fused: the transformed input never exists in memory.
+//
+// Work split.  A workgroup of 8 waves owns 8 x 32 output pixels (4 x 16 blocks of 2x2, "tiles") and 64
+// output channels.  Wave w = xi + 4*blk owns row xi of the 4x4 product grid (positions (xi, nu), nu = 0..3)
+// for the two tile rows blk: 4 positions x (32 tiles x 64 channels) = 8 MFMA accumulators of 32x32.  A wave
+// thus needs only row xi of B^T d: two of the four input rows, which it reads from the LDS copy of the
+// raw input region (10 x 34 pixels x 8 channels per chunk, filled by direct global->LDS loads, zero outside
+// the image), turns into its four B operands with 8 additions per channel, and multiplies with the
+// transformed weights U (also staged by direct loads).  After the last channel chunk the 16 products of a
+// tile are spread over four waves; they are combined through LDS (A^T . A) and stored with the usual fused
+// epilogue (bias, ReLU, ReLU mask, skip / gradient add).
+#include "prox_common.h"
+
+namespace gleam {
+
+namespace {
+
+constexpr int kWRawSlots = 704;    // 10 rows x 2 channel quads x 34 columns = 680 quads, rounded up to whole wave loads
+constexpr int kWUSlots = 2048;     // 16 positions x 64 output channels x 2 channel quads
+constexpr int kWBufFloats = (kWRawSlots + kWUSlots) * 4;
+constexpr int kWExQuads = 9;       // 8 output-channel quads per tile and pass, padded to 9 (bank spread)
+constexpr int kWExFloats = 8 * 2 * 32 * kWExQuads * 4;
+
+__device__ __forceinline__ void dma16(const float* g, float* l) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)l, 16, 0, 0);
+}
+
+__device__ __forceinline__ float4 relu4(float4 v) {   // on the bit patterns: negative floats are negative integers
+    int x0 = __float_as_int(v.x), x1 = __float_as_int(v.y), x2 = __float_as_int(v.z), x3 = __float_as_int(v.w);
+    x0 = x0 > 0 ? x0 : 0; x1 = x1 > 0 ? x1 : 0; x2 = x2 > 0 ? x2 : 0; x3 = x3 > 0 ? x3 : 0;
+    return make_float4(__int_as_float(x0), __int_as_float(x1), __int_as_float(x2), __int_as_float(x3));
+}
+__device__ __forceinline__ float4 fma4(float s, float4 a, float4 b) {   // s*a + b
+    return make_float4(fmaf(s, a.x, b.x), fmaf(s, a.y, b.y), fmaf(s, a.z, b.z), fmaf(s, a.w, b.w));
+}
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
+
+template <bool RELU>
+__global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
+    // Separate LDS objects: reads of one chunk buffer then do not wait for direct loads into the other.
+    __shared__ __attribute__((aligned(16))) float bufA[kWBufFloats];
+    __shared__ __attribute__((aligned(16))) float bufB[kWBufFloats];
+    __shared__ __attribute__((aligned(16))) float ex[kWExFloats];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, h = lane >> 5, xi = wave & 3, blk = wave >> 2;
+    const int trl = m >> 4, tc = m & 15;
+
+    // XCD-aware order: the eight XCDs each take a contiguous eighth of the blocks (neighbours share halo rows)
+    const long long per_xcd = (a.n_blocks + 7) / 8;
+    const long long item = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((long long)(blockIdx.x >> 3) >= per_xcd || item >= a.n_blocks) return;   // uniform for the workgroup
+    const int bx = (int)(item % a.bx_n);
+    const long long rest = item / a.bx_n;
+    const int by = (int)(rest % a.by_n);
+    const long long img = rest / a.by_n;
+    const int x0 = bx * 32, y0 = by * 8, ny = blockIdx.y, n0 = ny * 64;
+    const int n_kc = a.K / 8;
+
+    // direct-load sources of this lane: two quads of the raw region (zero quad outside the image), four of U
+    const float* gp[2];
+    int gstep[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int s = tid + i * 512;
+        const int rq = s / 34, col = s - rq * 34, row = rq >> 1, quad = rq & 1;
+        const int yy = y0 - 1 + row, xx = x0 - 1 + col;
+        const bool ok = s < 680 && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
+        gp[i] = ok ? a.in + ((img * a.H + yy) * a.W + xx) * a.K + quad * 4 : a.zero;
+        gstep[i] = ok ? 8 : 0;
+    }
+    const float* up = a.u + (size_t)ny * n_kc * (kWUSlots * 4) + tid * 4;
+
+    auto issue = [&](int kc, float* dst) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int o = wave + i * 8;
+            if (o < kWRawSlots / 64) dma16(gp[i] + kc * gstep[i], dst + o * 256);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int o = wave + i * 8;
+            dma16(up + (size_t)kc * (kWUSlots * 4) + i * 2048, dst + kWRawSlots * 4 + o * 256);
+        }
+    };
+
+    // row xi of B^T: d[ra] + sg * d[rb]
+    const int ra = xi == 0 ? 0 : (xi == 2 ? 2 : 1);
+    const int rb = xi == 3 ? 3 : (xi == 2 ? 1 : 2);
+    const float sg = xi == 1 ? 1.f : -1.f;
+    const int offA = (((4 * blk + 2 * trl + ra) * 2 + h) * 34 + 2 * tc) * 4;
+    const int offB = (((4 * blk + 2 * trl + rb) * 2 + h) * 34 + 2 * tc) * 4;
+    const int offU = kWRawSlots * 4 + ((xi * 4 * 64 + m) * 2 + h) * 4;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int nu = 0; nu < 4; ++nu)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nu][j][r] = 0.f;
+
+    auto compute = [&](const float* buf) {
+        float4 t[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float4 da = *reinterpret_cast<const float4*>(buf + offA + c * 4);
+            float4 db = *reinterpret_cast<const float4*>(buf + offB + c * 4);
+            if (RELU) {
+                da = relu4(da);
+                db = relu4(db);
+            }
+            t[c] = fma4(sg, db, da);
+        }
+        float4 v[4];
+        v[0] = sub4(t[0], t[2]);
+        v[1] = add4(t[1], t[2]);
+        v[2] = sub4(t[2], t[1]);
+        v[3] = sub4(t[1], t[3]);
+#pragma unroll
+        for (int nu = 0; nu < 4; ++nu) {
+            const float4 u0 = *reinterpret_cast<const float4*>(buf + offU + ((nu * 64) * 2) * 4);
+            const float4 u1 = *reinterpret_cast<const float4*>(buf + offU + ((nu * 64 + 32) * 2) * 4);
+            acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.x, v[nu].x, acc[nu][0], 0, 0, 0);
+            acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.x, v[nu].x, acc[nu][1], 0, 0, 0);
+            acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.y, v[nu].y, acc[nu][0], 0, 0, 0);
+            acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.y, v[nu].y, acc[nu][1], 0, 0, 0);
+            acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.z, v[nu].z, acc[nu][0], 0, 0, 0);
+            acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.z, v[nu].z, acc[nu][1], 0, 0, 0);
+            acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.w, v[nu].w, acc[nu][0], 0, 0, 0);
+            acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.w, v[nu].w, acc[nu][1], 0, 0, 0);
+        }
+    };
+
+    issue(0, bufA);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int kc = 0; kc < n_kc; kc += 2) {   // n_kc is even (K is a multiple of 16)
+        issue(kc + 1, bufB);
+        compute(bufA);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (kc + 2 < n_kc) issue(kc + 2, bufA);
+        compute(bufB);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    }
+
+    // Output transform.  In registers over nu: R_0 = M_0 + M_1 + M_2, R_1 = M_1 - M_2 - M_3; across the four
+    // waves of a tile-row pair through LDS: Y_0 = R[xi=0] + R[1] + R[2], Y_1 = R[1] - R[2] - R[3].
+    // One pass per 32 output channels.
+    const int tid_b = tid & 255;
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp) {
+        if (jp) __syncthreads();
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            float r0[4], r1[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float m0 = acc[0][jp][4 * rg + i], m1 = acc[1][jp][4 * rg + i];
+                const float m2 = acc[2][jp][4 * rg + i], m3 = acc[3][jp][4 * rg + i];
+                r0[i] = m0 + m1 + m2;
+                r1[i] = m1 - m2 - m3;
+            }
+            const int cq = 2 * rg + h;
+            *reinterpret_cast<float4*>(ex + (((wave * 2 + 0) * 32 + m) * kWExQuads + cq) * 4) = make_float4(r0[0], r0[1], r0[2], r0[3]);
+            *reinterpret_cast<float4*>(ex + (((wave * 2 + 1) * 32 + m) * kWExQuads + cq) * 4) = make_float4(r1[0], r1[1], r1[2], r1[3]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {          // output row inside the tile
+            const int itm = tid_b + 256 * i;
+            const int cq = itm & 7, tile = (itm >> 3) & 31;
+            const int y = y0 + 4 * blk + 2 * (tile >> 4) + i;
+            const int co = n0 + 32 * jp + 4 * cq;
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {   // output column inside the tile
+                const int x = x0 + 2 * (tile & 15) + jj;
+                auto rd = [&](int x_i) {
+                    return *reinterpret_cast<const float4*>(ex + ((((x_i + 4 * blk) * 2 + jj) * 32 + tile) * kWExQuads + cq) * 4);
+                };
+                float4 yv;
+                if (i == 0) yv = add4(add4(rd(0), rd(1)), rd(2));
+                else yv = sub4(sub4(rd(1), rd(2)), rd(3));
+                if (y < a.H && x < a.W) {
+                    float v[4] = {yv.x, yv.y, yv.z, yv.w};
+                    const long long o = ((img * a.H + y) * a.W + x) * a.Nn + co;
+                    if (a.bias) {
+                        const float4 bv = *reinterpret_cast<const float4*>(a.bias + co);
+                        v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
+                    }
+                    if (a.relu_out) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                    }
+                    float4 ref = make_float4(1.f, 1.f, 1.f, 1.f);
+                    if (a.mask_ref) ref = *reinterpret_cast<const float4*>(a.mask_ref + o);
+                    const float rr[4] = {ref.x, ref.y, ref.z, ref.w};
+                    if (a.mask_acc) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = rr[e] > 0.f ? v[e] : 0.f;
+                    }
+                    if (a.add) {
+                        const float4 av = *reinterpret_cast<const float4*>(a.add + o);
+                        const float aa[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
+                    }
+                    *reinterpret_cast<float4*>(a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            }
+        }
+    }
+}
+
+// U = G g G^T for every (output channel n, input channel k), laid out as the kernel's LDS image:
+// u[(((ny*n_kc + kc)*16 + pos)*64 + nn)*8 + kk], n = 64*ny + nn, k = 8*kc + kk, pos = 4*xi + nu; one zero
+// quad follows.  Source weight (n, tap, k) at w[n*sn + tapidx*st + k*sk], taps mirrored for the data gradient.
+__global__ __launch_bounds__(256) void wino_weights_kernel(const float* __restrict__ w, long long sn, long long st_, long long sk,
+                                                           int flip, int K, int Nn, float* __restrict__ u) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx == 0) {
+        float* z = u + (size_t)16 * K * Nn;
+        z[0] = z[1] = z[2] = z[3] = 0.f;
+    }
+    if (idx >= K * Nn) return;
+    const int k = idx % K, n = idx / K;
+    float g[3][3];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) g[t / 3][t % 3] = w[n * sn + (flip ? 8 - t : t) * st_ + k * sk];
+    float gg[4][3];   // G g
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        gg[0][b] = g[0][b];
+        gg[1][b] = 0.5f * (g[0][b] + g[1][b] + g[2][b]);
+        gg[2][b] = 0.5f * (g[0][b] - g[1][b] + g[2][b]);
+        gg[3][b] = g[2][b];
+    }
+    const int ny = n / 64, nn = n % 64, kc = k / 8, kk = k % 8, n_kc = K / 8;
+    float* dst = u + (((size_t)(ny * n_kc + kc) * 16) * 64 + nn) * 8 + kk;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const float uu[4] = {gg[x][0], 0.5f * (gg[x][0] + gg[x][1] + gg[x][2]), 0.5f * (gg[x][0] - gg[x][1] + gg[x][2]), gg[x][2]};
+#pragma unroll
+        for (int nu = 0; nu < 4; ++nu) dst[(size_t)(4 * x + nu) * 64 * 8] = uu[nu];
+    }
+}
+
+}  // namespace
+
+bool conv_wino_applies(const PixDims& d, int K, int Nn) {
+    return d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3 && K % 16 == 0 && Nn % 64 == 0;
+}
+
+size_t conv_wino_weight_floats(int K, int Nn) { return (size_t)16 * K * Nn + 4; }
+
+hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st_, long long sk, int flip, int relu_in,
+                            float* u_scratch, const char* name, hipStream_t st) {
+    {
+        KernelScope ks("weights_image", 0.0, 4.0 * (double)(9 + 16) * a.K * a.Nn, st);
+        hipLaunchKernelGGL(wino_weights_kernel, dim3((unsigned)((a.K * a.Nn + 255) / 256)), dim3(256), 0, st, w, sn, st_, sk, flip,
+                           a.K, a.Nn, u_scratch);
+    }
+    a.u = u_scratch;
+    a.zero = u_scratch + (size_t)16 * a.K * a.Nn;
+    a.bx_n = (a.W + 31) / 32;
+    a.by_n = (a.H + 7) / 8;
+    a.n_blocks = a.NI * (long long)a.bx_n * a.by_n;
+    const long long per_xcd = (a.n_blocks + 7) / 8;
+    dim3 grid((unsigned)(8 * per_xcd), (unsigned)(a.Nn / 64));
+    const double Q = (double)a.NI * a.H * a.W;
+    KernelScope ks(name, 2.0 * Q * a.K * a.Nn * 9, 4.0 * Q * (a.K + a.Nn), st);
+    if (relu_in) hipLaunchKernelGGL((conv_wino_kernel<true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((conv_wino_kernel<false>), grid, dim3(512), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace gleam
