@@ -26,8 +26,13 @@ namespace {
 constexpr int kWRawSlots = 704;    // 10 rows x 2 channel quads x 34 columns = 680 quads, rounded up to whole wave loads
 constexpr int kWUSlots = 2048;     // 16 positions x 64 output channels x 2 channel quads
 constexpr int kWBufFloats = (kWRawSlots + kWUSlots) * 4;
-constexpr int kWExQuads = 9;       // 8 output-channel quads per tile and pass, padded to 9 (bank spread)
-constexpr int kWExFloats = 8 * 2 * 32 * kWExQuads * 4;
+constexpr int kWExFloats = 8 * 2 * 32 * 8 * 4;   // per pass: 8 waves x 2 output columns x 32 tiles x 8 channel quads
+// Exchange element (wave, column jj, tile, quad cq): the quad index is XOR-ed with bits of the tile index so that
+// both the writers (16 lanes = 16 tiles, one quad) and the readers (16 lanes = 2 tiles x 8 quads) touch 16
+// different 16-byte bank groups: LDS serves 128-bit accesses 16 lanes at a time out of 64 banks.
+__device__ __forceinline__ int ex_off(int wave, int jj, int tile, int cq) {
+    return ((((wave * 2 + jj) * 32 + tile) * 8) + (cq ^ ((tile >> 1) & 7))) * 4;
+}
 
 __device__ __forceinline__ void dma16(const float* g, float* l) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
@@ -56,36 +61,53 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
     const int m = lane & 31, h = lane >> 5, xi = wave & 3, blk = wave >> 2;
     const int trl = m >> 4, tc = m & 15;
 
-    // XCD-aware order: the eight XCDs each take a contiguous eighth of the blocks (neighbours share halo rows)
-    const long long per_xcd = (a.n_blocks + 7) / 8;
-    const long long item = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((long long)(blockIdx.x >> 3) >= per_xcd || item >= a.n_blocks) return;   // uniform for the workgroup
-    const int bx = (int)(item % a.bx_n);
-    const long long rest = item / a.bx_n;
-    const int by = (int)(rest % a.by_n);
-    const long long img = rest / a.by_n;
-    const int x0 = bx * 32, y0 = by * 8, ny = blockIdx.y, n0 = ny * 64;
+    // Persistent workgroups, XCD-aware order: each XCD owns a contiguous eighth of the blocks (neighbours share
+    // halo rows in its L2) and its workgroups walk that range with a fixed stride.
+    const XcdRange xr = xcd_range(a.n_blocks);
+    const int ny = blockIdx.y, n0 = ny * 64;
     const int n_kc = a.K / 8;
 
-    // direct-load sources of this lane: two quads of the raw region (zero quad outside the image), four of U
-    const float* gp[2];
-    int gstep[2];
+    // Direct-load sources of this lane: two quads of the raw region (a zero quad outside the image) and four
+    // of U.  The position of a quad inside the region does not depend on the block.
+    int s_row[2], s_col[2], s_quad[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int s = tid + i * 512;
-        const int rq = s / 34, col = s - rq * 34, row = rq >> 1, quad = rq & 1;
-        const int yy = y0 - 1 + row, xx = x0 - 1 + col;
-        const bool ok = s < 680 && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
-        gp[i] = ok ? a.in + ((img * a.H + yy) * a.W + xx) * a.K + quad * 4 : a.zero;
-        gstep[i] = ok ? 8 : 0;
+        const int rq = s / 34, rem = s - rq * 34;
+        s_col[i] = rem < 17 ? 2 * rem : 2 * (rem - 17) + 1;   // even columns first, then odd ones
+        s_row[i] = s < 680 ? (rq >> 1) : -100000;            // slots past the region always read the zero quad
+        s_quad[i] = rq & 1;
     }
+    struct Block {
+        int x0, y0;
+        long long img;
+        const float* gp[2];
+        int gstep[2];
+    };
+    auto setup = [&](long long item) {
+        Block b;
+        const int bx = (int)(item % a.bx_n);
+        const long long rest = item / a.bx_n;
+        const int by = (int)(rest % a.by_n);
+        b.img = rest / a.by_n;
+        b.x0 = bx * 32;
+        b.y0 = by * 8;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int yy = b.y0 - 1 + s_row[i], xx = b.x0 - 1 + s_col[i];
+            const bool ok = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
+            b.gp[i] = ok ? a.in + ((b.img * a.H + yy) * a.W + xx) * a.K + s_quad[i] * 4 : a.zero;
+            b.gstep[i] = ok ? 8 : 0;
+        }
+        return b;
+    };
     const float* up = a.u + (size_t)ny * n_kc * (kWUSlots * 4) + tid * 4;
 
-    auto issue = [&](int kc, float* dst) {
+    auto issue = [&](const Block& b, int kc, float* dst) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int o = wave + i * 8;
-            if (o < kWRawSlots / 64) dma16(gp[i] + kc * gstep[i], dst + o * 256);
+            if (o < kWRawSlots / 64) dma16(b.gp[i] + kc * b.gstep[i], dst + o * 256);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -98,24 +120,21 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
     const int ra = xi == 0 ? 0 : (xi == 2 ? 2 : 1);
     const int rb = xi == 3 ? 3 : (xi == 2 ? 1 : 2);
     const float sg = xi == 1 ? 1.f : -1.f;
-    const int offA = (((4 * blk + 2 * trl + ra) * 2 + h) * 34 + 2 * tc) * 4;
-    const int offB = (((4 * blk + 2 * trl + rb) * 2 + h) * 34 + 2 * tc) * 4;
-    const int offU = kWRawSlots * 4 + ((xi * 4 * 64 + m) * 2 + h) * 4;
+    // Region quad (row, channel quad, column) sits at slot (row*2 + quad)*34 + (column & 1)*17 + column/2: the 16
+    // tiles of a row then read 16 neighbouring slots for each of their four columns (no bank conflicts).
+    const int offA = (((4 * blk + 2 * trl + ra) * 2 + h) * 34 + tc) * 4;
+    const int offB = (((4 * blk + 2 * trl + rb) * 2 + h) * 34 + tc) * 4;
+    // U quad (position, channel quad hq, output channel n) at slot ((pos*2 + hq)*64 + n)
+    const int offU = kWRawSlots * 4 + (((xi * 4) * 2 + h) * 64 + m) * 4;
 
     floatx16 acc[4][2];
-#pragma unroll
-    for (int nu = 0; nu < 4; ++nu)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[nu][j][r] = 0.f;
 
     auto compute = [&](const float* buf) {
         float4 t[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            float4 da = *reinterpret_cast<const float4*>(buf + offA + c * 4);
-            float4 db = *reinterpret_cast<const float4*>(buf + offB + c * 4);
+            float4 da = *reinterpret_cast<const float4*>(buf + offA + ((c & 1) * 17 + (c >> 1)) * 4);
+            float4 db = *reinterpret_cast<const float4*>(buf + offB + ((c & 1) * 17 + (c >> 1)) * 4);
             if (RELU) {
                 da = relu4(da);
                 db = relu4(db);
@@ -129,8 +148,8 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
         v[3] = sub4(t[1], t[3]);
 #pragma unroll
         for (int nu = 0; nu < 4; ++nu) {
-            const float4 u0 = *reinterpret_cast<const float4*>(buf + offU + ((nu * 64) * 2) * 4);
-            const float4 u1 = *reinterpret_cast<const float4*>(buf + offU + ((nu * 64 + 32) * 2) * 4);
+            const float4 u0 = *reinterpret_cast<const float4*>(buf + offU + (nu * 2 * 64) * 4);
+            const float4 u1 = *reinterpret_cast<const float4*>(buf + offU + (nu * 2 * 64 + 32) * 4);
             acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.x, v[nu].x, acc[nu][0], 0, 0, 0);
             acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.x, v[nu].x, acc[nu][1], 0, 0, 0);
             acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.y, v[nu].y, acc[nu][0], 0, 0, 0);
@@ -142,15 +161,37 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
         }
     };
 
-    issue(0, bufA);
+    if (xr.first >= xr.end) return;   // uniform for the workgroup
+    Block cur = setup(xr.first);
+    issue(cur, 0, bufA);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    const int tid_b = tid & 255;
+    float4 bias_r[2];
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp)
+        bias_r[jp] = a.bias ? *reinterpret_cast<const float4*>(a.bias + n0 + 32 * jp + 4 * (tid_b & 7)) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (long long item = xr.first; item < xr.end; item += xr.stride) {
+    const bool has_next = item + xr.stride < xr.end;
+    const Block nxt = setup(has_next ? item + xr.stride : item);
+    const int x0 = cur.x0, y0 = cur.y0;
+    const long long img = cur.img;
+#pragma unroll
+    for (int nu = 0; nu < 4; ++nu)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nu][j][r] = 0.f;
     for (int kc = 0; kc < n_kc; kc += 2) {   // n_kc is even (K is a multiple of 16)
-        issue(kc + 1, bufB);
+        issue(cur, kc + 1, bufB);
+        __builtin_amdgcn_sched_barrier(0);   // keep the direct loads ahead of the MFMAs they overlap with
         compute(bufA);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (kc + 2 < n_kc) issue(kc + 2, bufA);
+        // the first chunk of the next block is fetched under the last MFMAs of this one
+        if (kc + 2 < n_kc) issue(cur, kc + 2, bufA);
+        else if (has_next) issue(nxt, 0, bufA);
+        __builtin_amdgcn_sched_barrier(0);
         compute(bufB);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -158,11 +199,33 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
 
     // Output transform.  In registers over nu: R_0 = M_0 + M_1 + M_2, R_1 = M_1 - M_2 - M_3; across the four
     // waves of a tile-row pair through LDS: Y_0 = R[xi=0] + R[1] + R[2], Y_1 = R[1] - R[2] - R[3].
-    // One pass per 32 output channels.
-    const int tid_b = tid & 255;
+    // One pass per 32 output channels.  A thread finishes the 2x2 pixels of one tile for one channel quad; what
+    // the fused epilogue reads from memory (ReLU mask source, tensor to add) is requested for all four pixels
+    // before the exchange, from a clamped address where the pixel is outside the image.
+    const int e_cq = tid_b & 7, e_tile = (tid_b >> 3) & 31;
+    const int ey = y0 + 4 * blk + 2 * (e_tile >> 4), ex_ = x0 + 2 * (e_tile & 15);
+    bool okp[2][2];
+    long long op[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            okp[i][jj] = ey + i < a.H && ex_ + jj < a.W;
+            op[i][jj] = okp[i][jj] ? ((img * a.H + ey + i) * a.W + ex_ + jj) * a.Nn + n0 + 4 * e_cq : (long long)(n0 + 4 * e_cq);
+        }
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) {
         if (jp) __syncthreads();
+        float4 refv[2][2], addv[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                refv[i][jj] = make_float4(1.f, 1.f, 1.f, 1.f);
+                addv[i][jj] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (a.mask_ref) refv[i][jj] = *reinterpret_cast<const float4*>(a.mask_ref + op[i][jj] + 32 * jp);
+                if (a.add) addv[i][jj] = *reinterpret_cast<const float4*>(a.add + op[i][jj] + 32 * jp);
+            }
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
             float r0[4], r1[4];
@@ -174,58 +237,41 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
                 r1[i] = m1 - m2 - m3;
             }
             const int cq = 2 * rg + h;
-            *reinterpret_cast<float4*>(ex + (((wave * 2 + 0) * 32 + m) * kWExQuads + cq) * 4) = make_float4(r0[0], r0[1], r0[2], r0[3]);
-            *reinterpret_cast<float4*>(ex + (((wave * 2 + 1) * 32 + m) * kWExQuads + cq) * 4) = make_float4(r1[0], r1[1], r1[2], r1[3]);
+            *reinterpret_cast<float4*>(ex + ex_off(wave, 0, m, cq)) = make_float4(r0[0], r0[1], r0[2], r0[3]);
+            *reinterpret_cast<float4*>(ex + ex_off(wave, 1, m, cq)) = make_float4(r1[0], r1[1], r1[2], r1[3]);
         }
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 2; ++i) {          // output row inside the tile
-            const int itm = tid_b + 256 * i;
-            const int cq = itm & 7, tile = (itm >> 3) & 31;
-            const int y = y0 + 4 * blk + 2 * (tile >> 4) + i;
-            const int co = n0 + 32 * jp + 4 * cq;
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj) {   // output column inside the tile
-                const int x = x0 + 2 * (tile & 15) + jj;
-                auto rd = [&](int x_i) {
-                    return *reinterpret_cast<const float4*>(ex + ((((x_i + 4 * blk) * 2 + jj) * 32 + tile) * kWExQuads + cq) * 4);
-                };
+                auto rd = [&](int x_i) { return *reinterpret_cast<const float4*>(ex + ex_off(x_i + 4 * blk, jj, e_tile, e_cq)); };
                 float4 yv;
                 if (i == 0) yv = add4(add4(rd(0), rd(1)), rd(2));
                 else yv = sub4(sub4(rd(1), rd(2)), rd(3));
-                if (y < a.H && x < a.W) {
-                    float v[4] = {yv.x, yv.y, yv.z, yv.w};
-                    const long long o = ((img * a.H + y) * a.W + x) * a.Nn + co;
-                    if (a.bias) {
-                        const float4 bv = *reinterpret_cast<const float4*>(a.bias + co);
-                        v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
-                    }
-                    if (a.relu_out) {
+                float v[4] = {yv.x + bias_r[jp].x, yv.y + bias_r[jp].y, yv.z + bias_r[jp].z, yv.w + bias_r[jp].w};
+                if (a.relu_out) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-                    }
-                    float4 ref = make_float4(1.f, 1.f, 1.f, 1.f);
-                    if (a.mask_ref) ref = *reinterpret_cast<const float4*>(a.mask_ref + o);
-                    const float rr[4] = {ref.x, ref.y, ref.z, ref.w};
-                    if (a.mask_acc) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = rr[e] > 0.f ? v[e] : 0.f;
-                    }
-                    if (a.add) {
-                        const float4 av = *reinterpret_cast<const float4*>(a.add + o);
-                        const float aa[4] = {av.x, av.y, av.z, av.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
-                    }
-                    *reinterpret_cast<float4*>(a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
                 }
+                const float rr[4] = {refv[i][jj].x, refv[i][jj].y, refv[i][jj].z, refv[i][jj].w};
+                const float aa[4] = {addv[i][jj].x, addv[i][jj].y, addv[i][jj].z, addv[i][jj].w};
+                if (a.mask_acc) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = rr[e] > 0.f ? v[e] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
+                if (okp[i][jj]) *reinterpret_cast<float4*>(a.out + op[i][jj] + 32 * jp) = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
+    }
+    cur = nxt;   // the barriers of the next block's chunk loop separate its exchange writes from these reads
     }
 }
 
 // U = G g G^T for every (output channel n, input channel k), laid out as the kernel's LDS image:
-// u[(((ny*n_kc + kc)*16 + pos)*64 + nn)*8 + kk], n = 64*ny + nn, k = 8*kc + kk, pos = 4*xi + nu; one zero
+// u[((((ny*n_kc + kc)*16 + pos)*2 + hq)*64 + nn)*4 + kk], n = 64*ny + nn, k = 8*kc + 4*hq + kk, pos = 4*xi + nu; one zero
 // quad follows.  Source weight (n, tap, k) at w[n*sn + tapidx*st + k*sk], taps mirrored for the data gradient.
 __global__ __launch_bounds__(256) void wino_weights_kernel(const float* __restrict__ w, long long sn, long long st_, long long sk,
                                                            int flip, int K, int Nn, float* __restrict__ u) {
@@ -247,13 +293,13 @@ __global__ __launch_bounds__(256) void wino_weights_kernel(const float* __restri
         gg[2][b] = 0.5f * (g[0][b] - g[1][b] + g[2][b]);
         gg[3][b] = g[2][b];
     }
-    const int ny = n / 64, nn = n % 64, kc = k / 8, kk = k % 8, n_kc = K / 8;
-    float* dst = u + (((size_t)(ny * n_kc + kc) * 16) * 64 + nn) * 8 + kk;
+    const int ny = n / 64, nn = n % 64, kc = k / 8, hq = (k % 8) / 4, kk = k % 4, n_kc = K / 8;
+    float* dst = u + ((((size_t)(ny * n_kc + kc) * 16) * 2 + hq) * 64 + nn) * 4 + kk;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const float uu[4] = {gg[x][0], 0.5f * (gg[x][0] + gg[x][1] + gg[x][2]), 0.5f * (gg[x][0] - gg[x][1] + gg[x][2]), gg[x][2]};
 #pragma unroll
-        for (int nu = 0; nu < 4; ++nu) dst[(size_t)(4 * x + nu) * 64 * 8] = uu[nu];
+        for (int nu = 0; nu < 4; ++nu) dst[(size_t)(4 * x + nu) * 2 * 64 * 4] = uu[nu];
     }
 }
 
@@ -277,8 +323,9 @@ hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long 
     a.bx_n = (a.W + 31) / 32;
     a.by_n = (a.H + 7) / 8;
     a.n_blocks = a.NI * (long long)a.bx_n * a.by_n;
-    const long long per_xcd = (a.n_blocks + 7) / 8;
-    dim3 grid((unsigned)(8 * per_xcd), (unsigned)(a.Nn / 64));
+    const long long cap = 256 / (a.Nn / 64) > 8 ? 256 / (a.Nn / 64) : 8;   // one workgroup per CU in total
+    const long long gx = ((a.n_blocks < cap ? a.n_blocks : cap) + 7) / 8 * 8;
+    dim3 grid((unsigned)gx, (unsigned)(a.Nn / 64));
     const double Q = (double)a.NI * a.H * a.W;
     KernelScope ks(name, 2.0 * Q * a.K * a.Nn * 9, 4.0 * Q * (a.K + a.Nn), st);
     if (relu_in) hipLaunchKernelGGL((conv_wino_kernel<true>), grid, dim3(512), 0, st, a);
