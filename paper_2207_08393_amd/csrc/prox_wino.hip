@@ -17,16 +17,19 @@
 // transformed weights U (also staged by direct loads).  After the last channel chunk the 16 products of a
 // tile are spread over four waves; they are combined through LDS (A^T . A) and stored with the usual fused
 // epilogue (bias, ReLU, ReLU mask, skip / gradient add).
+#include <type_traits>
+
 #include "prox_common.h"
 
 namespace gleam {
 
 namespace {
 
-constexpr int kWRawSlots = 704;    // 10 rows x 2 channel quads x 34 columns = 680 quads, rounded up to whole wave loads
+constexpr int kWRawSlots = 448;    // 6 rows x 2 channel quads x 34 columns = 408 quads, rounded up to whole wave loads
 constexpr int kWUSlots = 2048;     // 16 positions x 64 output channels x 2 channel quads
 constexpr int kWBufFloats = (kWRawSlots + kWUSlots) * 4;
-constexpr int kWExFloats = 8 * 2 * 32 * 8 * 4;   // per pass: 8 waves x 2 output columns x 32 tiles x 8 channel quads
+constexpr int kWExFloats = 4 * 2 * 32 * 8 * 4;   // per pass: 4 waves x 2 output columns x 32 tiles x 8 channel quads
+static_assert(kWExFloats <= kWBufFloats, "the exchange reuses a chunk buffer");
 // Exchange element (wave, column jj, tile, quad cq): the quad index is XOR-ed with bits of the tile index so that
 // both the writers (16 lanes = 16 tiles, one quad) and the readers (16 lanes = 2 tiles x 8 quads) touch 16
 // different 16-byte bank groups: LDS serves 128-bit accesses 16 lanes at a time out of 64 banks.
@@ -51,14 +54,14 @@ __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(
 __device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
 
 template <bool RELU>
-__global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
+__global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
     // Separate LDS objects: reads of one chunk buffer then do not wait for direct loads into the other.
     __shared__ __attribute__((aligned(16))) float bufA[kWBufFloats];
     __shared__ __attribute__((aligned(16))) float bufB[kWBufFloats];
-    __shared__ __attribute__((aligned(16))) float ex[kWExFloats];
+    float* const ex = bufB;   // the exchange of the output transform reuses the second chunk buffer
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m = lane & 31, h = lane >> 5, xi = wave & 3, blk = wave >> 2;
+    const int m = lane & 31, h = lane >> 5, xi = wave;
     const int trl = m >> 4, tc = m & 15;
 
     // Persistent workgroups, XCD-aware order: each XCD owns a contiguous eighth of the blocks (neighbours share
@@ -72,10 +75,10 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
     int s_row[2], s_col[2], s_quad[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const int s = tid + i * 512;
+        const int s = tid + i * 256;
         const int rq = s / 34, rem = s - rq * 34;
         s_col[i] = rem < 17 ? 2 * rem : 2 * (rem - 17) + 1;   // even columns first, then odd ones
-        s_row[i] = s < 680 ? (rq >> 1) : -100000;            // slots past the region always read the zero quad
+        s_row[i] = s < 408 ? (rq >> 1) : -100000;            // slots past the region always read the zero quad
         s_quad[i] = rq & 1;
     }
     struct Block {
@@ -91,7 +94,7 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
         const int by = (int)(rest % a.by_n);
         b.img = rest / a.by_n;
         b.x0 = bx * 32;
-        b.y0 = by * 8;
+        b.y0 = by * 4;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int yy = b.y0 - 1 + s_row[i], xx = b.x0 - 1 + s_col[i];
@@ -101,18 +104,20 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
         }
         return b;
     };
-    const float* up = a.u + (size_t)ny * n_kc * (kWUSlots * 4) + tid * 4;
+    const float* ubase = a.u + (size_t)ny * n_kc * (kWUSlots * 4);   // uniform; lanes add a 32-bit offset
+    const unsigned uoff = 4u * (unsigned)tid;
 
     auto issue = [&](const Block& b, int kc, float* dst) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int o = wave + i * 8;
+            const int o = wave + i * 4;
             if (o < kWRawSlots / 64) dma16(b.gp[i] + kc * b.gstep[i], dst + o * 256);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int o = wave + i * 8;
-            dma16(up + (size_t)kc * (kWUSlots * 4) + i * 2048, dst + kWRawSlots * 4 + o * 256);
+        for (int i = 0; i < 8; ++i) {
+            const int o = wave + i * 4;
+            const float* ub = ubase + ((size_t)kc * (kWUSlots * 4) + 1024 * i);   // scalar address
+            dma16(ub + uoff, dst + kWRawSlots * 4 + o * 256);
         }
     };
 
@@ -122,14 +127,15 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
     const float sg = xi == 1 ? 1.f : -1.f;
     // Region quad (row, channel quad, column) sits at slot (row*2 + quad)*34 + (column & 1)*17 + column/2: the 16
     // tiles of a row then read 16 neighbouring slots for each of their four columns (no bank conflicts).
-    const int offA = (((4 * blk + 2 * trl + ra) * 2 + h) * 34 + tc) * 4;
-    const int offB = (((4 * blk + 2 * trl + rb) * 2 + h) * 34 + tc) * 4;
+    const int offA = (((2 * trl + ra) * 2 + h) * 34 + tc) * 4;
+    const int offB = (((2 * trl + rb) * 2 + h) * 34 + tc) * 4;
     // U quad (position, channel quad hq, output channel n) at slot ((pos*2 + hq)*64 + n)
     const int offU = kWRawSlots * 4 + (((xi * 4) * 2 + h) * 64 + m) * 4;
 
     floatx16 acc[4][2];
 
-    auto compute = [&](const float* buf) {
+    auto compute = [&](const float* buf, auto first_c) {
+        constexpr bool FIRST = decltype(first_c)::value;   // first chunk of a block: accumulators start from zero
         float4 t[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -150,8 +156,16 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
         for (int nu = 0; nu < 4; ++nu) {
             const float4 u0 = *reinterpret_cast<const float4*>(buf + offU + (nu * 2 * 64) * 4);
             const float4 u1 = *reinterpret_cast<const float4*>(buf + offU + (nu * 2 * 64 + 32) * 4);
-            acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.x, v[nu].x, acc[nu][0], 0, 0, 0);
-            acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.x, v[nu].x, acc[nu][1], 0, 0, 0);
+            if (FIRST) {
+                floatx16 z;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.x, v[nu].x, z, 0, 0, 0);
+                acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.x, v[nu].x, z, 0, 0, 0);
+            } else {
+                acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.x, v[nu].x, acc[nu][0], 0, 0, 0);
+                acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.x, v[nu].x, acc[nu][1], 0, 0, 0);
+            }
             acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.y, v[nu].y, acc[nu][0], 0, 0, 0);
             acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u1.y, v[nu].y, acc[nu][1], 0, 0, 0);
             acc[nu][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(u0.z, v[nu].z, acc[nu][0], 0, 0, 0);
@@ -166,7 +180,7 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
     issue(cur, 0, bufA);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    const int tid_b = tid & 255;
+    const int tid_b = tid;
     float4 bias_r[2];
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp)
@@ -176,23 +190,24 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
     const Block nxt = setup(has_next ? item + xr.stride : item);
     const int x0 = cur.x0, y0 = cur.y0;
     const long long img = cur.img;
-#pragma unroll
-    for (int nu = 0; nu < 4; ++nu)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[nu][j][r] = 0.f;
-    for (int kc = 0; kc < n_kc; kc += 2) {   // n_kc is even (K is a multiple of 16)
-        issue(cur, kc + 1, bufB);
-        __builtin_amdgcn_sched_barrier(0);   // keep the direct loads ahead of the MFMAs they overlap with
-        compute(bufA);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
+    // n_kc is even (K is a multiple of 16): chunks alternate between the two buffers
+    issue(cur, 1, bufB);
+    __builtin_amdgcn_sched_barrier(0);   // keep the direct loads ahead of the MFMAs they overlap with
+    compute(bufA, std::true_type{});
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int kc = 1; kc < n_kc; kc += 2) {
         // the first chunk of the next block is fetched under the last MFMAs of this one
-        if (kc + 2 < n_kc) issue(cur, kc + 2, bufA);
+        if (kc + 1 < n_kc) issue(cur, kc + 1, bufA);
         else if (has_next) issue(nxt, 0, bufA);
         __builtin_amdgcn_sched_barrier(0);
-        compute(bufB);
+        compute(bufB, std::false_type{});
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (kc + 1 >= n_kc) break;
+        issue(cur, kc + 2, bufB);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(bufA, std::false_type{});
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
@@ -203,7 +218,7 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
     // the fused epilogue reads from memory (ReLU mask source, tensor to add) is requested for all four pixels
     // before the exchange, from a clamped address where the pixel is outside the image.
     const int e_cq = tid_b & 7, e_tile = (tid_b >> 3) & 31;
-    const int ey = y0 + 4 * blk + 2 * (e_tile >> 4), ex_ = x0 + 2 * (e_tile & 15);
+    const int ey = y0 + 2 * (e_tile >> 4), ex_ = x0 + 2 * (e_tile & 15);
     bool okp[2][2];
     long long op[2][2];
 #pragma unroll
@@ -245,7 +260,7 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
         for (int i = 0; i < 2; ++i) {          // output row inside the tile
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj) {   // output column inside the tile
-                auto rd = [&](int x_i) { return *reinterpret_cast<const float4*>(ex + ex_off(x_i + 4 * blk, jj, e_tile, e_cq)); };
+                auto rd = [&](int x_i) { return *reinterpret_cast<const float4*>(ex + ex_off(x_i, jj, e_tile, e_cq)); };
                 float4 yv;
                 if (i == 0) yv = add4(add4(rd(0), rd(1)), rd(2));
                 else yv = sub4(sub4(rd(1), rd(2)), rd(3));
@@ -266,7 +281,8 @@ __global__ __launch_bounds__(512) void conv_wino_kernel(WinoArgs a) {
             }
         }
     }
-    cur = nxt;   // the barriers of the next block's chunk loop separate its exchange writes from these reads
+    __syncthreads();   // the exchange lived in the second chunk buffer, which the next block loads into first
+    cur = nxt;
     }
 }
 
@@ -321,15 +337,15 @@ hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long 
     a.u = u_scratch;
     a.zero = u_scratch + (size_t)16 * a.K * a.Nn;
     a.bx_n = (a.W + 31) / 32;
-    a.by_n = (a.H + 7) / 8;
+    a.by_n = (a.H + 3) / 4;
     a.n_blocks = a.NI * (long long)a.bx_n * a.by_n;
-    const long long cap = 256 / (a.Nn / 64) > 8 ? 256 / (a.Nn / 64) : 8;   // one workgroup per CU in total
+    const long long cap = 512 / (a.Nn / 64) > 8 ? 512 / (a.Nn / 64) : 8;   // two workgroups per CU in total
     const long long gx = ((a.n_blocks < cap ? a.n_blocks : cap) + 7) / 8 * 8;
     dim3 grid((unsigned)gx, (unsigned)(a.Nn / 64));
     const double Q = (double)a.NI * a.H * a.W;
     KernelScope ks(name, 2.0 * Q * a.K * a.Nn * 9, 4.0 * Q * (a.K + a.Nn), st);
-    if (relu_in) hipLaunchKernelGGL((conv_wino_kernel<true>), grid, dim3(512), 0, st, a);
-    else hipLaunchKernelGGL((conv_wino_kernel<false>), grid, dim3(512), 0, st, a);
+    if (relu_in) hipLaunchKernelGGL((conv_wino_kernel<true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((conv_wino_kernel<false>), grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
