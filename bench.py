@@ -36,8 +36,8 @@ MEASURED_TRAFFIC = {
 
 # library launch label -> GPU kernel it runs (forward and data gradient of a 64->64 layer are one kernel)
 KERNEL_OF = {
-    "conv_fwd_64to64_t9": "conv_dlds_kernel<64,16,1,4,3,RELU> fwd+dgrad 64->64 3x3",
-    "conv_dgrad_64to64_t9": "conv_dlds_kernel<64,16,1,4,3,RELU> fwd+dgrad 64->64 3x3",
+    "conv_fwd_64to64_t9": "conv_wino_kernel<RELU> fwd+dgrad 64->64 3x3 (Winograd F(2x2,3x3))",
+    "conv_dgrad_64to64_t9": "conv_wino_kernel<RELU> fwd+dgrad 64->64 3x3 (Winograd F(2x2,3x3))",
     "conv_wgrad_64to64_t9": "wgrad_pipe_kernel<3,1,3,12> wgrad 64->64 3x3",
 }
 

@@ -8,15 +8,17 @@
 //     A^T = [1 1 1 0; 0 1 -1 -1].
 // Everything is fused: the transformed input never exists in memory.
 //
-// Work split.  A workgroup of 8 waves owns 8 x 32 output pixels (4 x 16 blocks of 2x2, "tiles") and 64
-// output channels.  Wave w = xi + 4*blk owns row xi of the 4x4 product grid (positions (xi, nu), nu = 0..3)
-// for the two tile rows blk: 4 positions x (32 tiles x 64 channels) = 8 MFMA accumulators of 32x32.  A wave
-// thus needs only row xi of B^T d: two of the four input rows, which it reads from the LDS copy of the
-// raw input region (10 x 34 pixels x 8 channels per chunk, filled by direct global->LDS loads, zero outside
-// the image), turns into its four B operands with 8 additions per channel, and multiplies with the
-// transformed weights U (also staged by direct loads).  After the last channel chunk the 16 products of a
-// tile are spread over four waves; they are combined through LDS (A^T . A) and stored with the usual fused
-// epilogue (bias, ReLU, ReLU mask, skip / gradient add).
+// Work split.  A workgroup of 4 waves owns 4 x 32 output pixels (2 x 16 blocks of 2x2, "tiles") and 64 output
+// channels; two workgroups share a CU (LDS and registers allow exactly that), so the output transform of one
+// overlaps the matrix work of the other.  Wave xi owns row xi of the 4x4 product grid (positions (xi, nu),
+// nu = 0..3): 4 positions x (32 tiles x 64 channels) = 8 MFMA accumulators of 32x32.  A wave thus needs only
+// row xi of B^T d: two of the four input rows, which it reads from the LDS copy of the raw input region
+// (6 x 34 pixels x 8 channels per chunk, filled by direct global->LDS loads, zero outside the image), turns
+// into its four B operands with 8 additions per channel, and multiplies with the transformed weights U (also
+// staged by direct loads).  After the last channel chunk the 16 products of a tile are spread over the four
+// waves; they are combined through LDS (A^T . A) and stored with the usual fused epilogue (bias, ReLU, ReLU
+// mask, skip / gradient add).  Workgroups are persistent and fetch the first chunk of their next block under
+// the last MFMAs of the current one.
 #include <type_traits>
 
 #include "prox_common.h"
@@ -52,6 +54,8 @@ __device__ __forceinline__ float4 fma4(float s, float4 a, float4 b) {   // s*a +
 }
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 __device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
+
+}  // namespace
 
 template <bool RELU>
 __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
@@ -318,8 +322,6 @@ __global__ __launch_bounds__(256) void wino_weights_kernel(const float* __restri
         for (int nu = 0; nu < 4; ++nu) dst[(size_t)(4 * x + nu) * 2 * 64 * 4] = uu[nu];
     }
 }
-
-}  // namespace
 
 bool conv_wino_applies(const PixDims& d, int K, int Nn) {
     return d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3 && K % 16 == 0 && Nn % 64 == 0;
