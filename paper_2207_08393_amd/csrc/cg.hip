@@ -8,9 +8,9 @@
 
 namespace gleam {
 
-namespace {
-
 constexpr int kCgThreads = 256;
+
+namespace {
 
 __device__ inline double block_sum(double v, double* red) {
     red[threadIdx.x] = v;
@@ -27,6 +27,8 @@ __device__ inline double sum_partials(const double* __restrict__ part, int nb) {
     for (int i = 0; i < nb; ++i) s += part[i];
     return s;
 }
+
+}  // namespace
 
 // grid (nb, B).  r = c1*u + c2*v (v may be null), p = r, x = 0, rr[b][blk] = partial <r, r>.
 // x may alias u (each element is read before it is overwritten by the same lane).
@@ -114,9 +116,7 @@ __global__ __launch_bounds__(kCgThreads) void fill_zero_kernel(float2* __restric
         x[i] = make_float2(0.f, 0.f);
 }
 
-inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
-
-}  // namespace
+static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 static int cg_blocks(long long n) {
     long long nb = (n + 4 * kCgThreads - 1) / (4 * kCgThreads);   // at least four elements per lane
