@@ -1798,6 +1798,16 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     plan.grad_off[L] = 0;  // G_L = g_z lives in saved
     plan.partial_off = w;
     plan.partial_bytes = align256((size_t)plan.n_split * max_w * sizeof(float));
+    for (int l = 0; l < L; ++l) {   // Winograd weight gradient: 16 products per channel pair, per split, plus their sum
+        const gleam_conv& c = p.layers[l];
+        PixDims dd{};
+        dd.T = (int)g.T; dd.D = (int)g.D; dd.H = (int)g.H; dd.W = (int)g.W;
+        dd.kt = c.kt; dd.kd = c.kd; dd.kh = c.kh; dd.kw = c.kw;
+        if (p.dtype == 0 && wgrad_wino_applies(dd, c.cin, c.cout)) {
+            const size_t need = align256(wgrad_wino_partial_floats(c.cin, c.cout, plan.n_split) * sizeof(float));
+            if (need > plan.partial_bytes) plan.partial_bytes = need;
+        }
+    }
     w += plan.partial_bytes;
     plan.bias_partial_off = w;
     w += align256((size_t)kThinSplit * kMaxChannels * sizeof(float));
@@ -2070,7 +2080,7 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         wa.g = G(l); wa.a = act(l - 1); wa.partial = partial;
         wa.Co = c.cout; wa.Ci = c.cin; wa.relu_in = (c.relu_in && !plan.post_relu[l - 1]) ? 1 : 0; wa.d = d;
         float* bpart = reinterpret_cast<float*>(wsb + plan.bias_partial_off);
-        bool bias_done = false;
+        bool bias_done = false, wino_wgrad_done = false;
         int used_split = plan.n_split;
         hipError_t e;
         if (p.dtype == 1) {
@@ -2091,17 +2101,41 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                 e = launch_wgrad_bf16(wb, plan.n_split, st);
                 bias_done = c.has_bias;
             }
+        } else if (wino_enabled() && wgrad_wino_applies(d, c.cin, c.cout)) {
+            // Winograd F(2x2, 3x3): partial sums of the 16 transformed products, fixed-order reduction, back-transform
+            WinoWgradArgs ww{};
+            ww.g = wa.g; ww.a = wa.a; ww.partial = partial; ww.bias_partial = c.has_bias ? bpart : nullptr;
+            ww.Co = c.cout; ww.Ci = c.cin; ww.H = d.H; ww.W = d.W; ww.NI = d.Q / ((long long)d.H * d.W);
+            const long long np = 16LL * c.cout * c.cin, nb = c.has_bias ? c.cout : 0;
+            {
+                char name[56];
+                snprintf(name, sizeof(name), "conv_wgrad_%dto%d_t%d", c.cin, c.cout, taps);
+                KernelScope ks(name, 2.0 * (double)d.Q * c.cin * c.cout * taps, 4.0 * (double)d.Q * (c.cin + c.cout), st);
+                e = launch_wgrad_wino(ww, wa.relu_in, plan.n_split, st);
+                if (e != hipSuccess) return e;
+            }
+            float* psum = partial + (size_t)plan.n_split * np;
+            {
+                KernelScope ks("wgrad_reduce", 0.0, 4.0 * (double)(np + nb) * (plan.n_split + 1), st);
+                const int nbw = (int)((np + 63) / 64), nbb = (int)((nb + 15) / 16);
+                hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)(nbw + nbb)), dim3(256), 0, st, (const float*)partial,
+                                   plan.n_split, np, psum, 1, nbw, (const float*)bpart, nb,
+                                   c.has_bias ? grad_theta + plan.b_off[l - 1] : nullptr);
+                e = wgrad_wino_finish(psum, c.cout, c.cin, grad_theta + plan.w_off[l - 1], st);
+                if (e != hipSuccess) return e;
+            }
+            wino_wgrad_done = true;
         } else {
             e = launch_wgrad(wa, c.has_bias ? bpart : nullptr, &bias_done, plan.n_split,
                              plan.partial_bytes / sizeof(float), &used_split, st);
         }
         if (e != hipSuccess) return e;
         const long long nw = (long long)(c.cout * taps * c.cin);
-        if (c.has_bias && !bias_done) {
+        if (c.has_bias && !bias_done && !wino_wgrad_done) {
             KernelScope ks("bias_grad", 0.0, 4.0 * (double)plan.Q * c.cout, st);
             hipLaunchKernelGGL(colsum_kernel, dim3(used_split), dim3(256), 0, st, (const float*)G(l), plan.Q, c.cout, bpart);
         }
-        {
+        if (!wino_wgrad_done) {
             const long long nb = c.has_bias ? c.cout : 0;
             KernelScope ks("wgrad_reduce", 0.0, 4.0 * (double)(nw + nb) * (used_split + 1), st);
             float* gw = grad_theta + plan.w_off[l - 1];

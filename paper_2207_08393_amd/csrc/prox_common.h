@@ -168,6 +168,27 @@ size_t conv_wino_weight_floats(int K, int Nn);
 hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st, long long sk, int flip, int relu_in,
                             float* u_scratch, const char* name, hipStream_t stream);
 
+// Winograd weight gradient of a 3x3 layer, float32 (prox_wino.hip): partial sums of the 16 transformed
+// products per workgroup, then a fixed-order reduction and the back-transform to the nine taps.
+struct WinoWgradArgs {
+    const float* g;         // [NI][H][W][Co]  gradient at the conv output (already ReLU-masked)
+    const float* a;         // [NI][H][W][Ci]  conv input before its optional ReLU
+    const float* zero;      // one quad of zeros in global memory
+    float* partial;         // [gridDim.x][16][Co][Ci], followed by [16][Co][Ci] for the reduced sums
+    float* bias_partial;    // [gridDim.x][Co] or null
+    int Co, Ci;
+    long long NI;
+    int H, W, bx_n, by_n;
+    long long n_chunks;
+};
+bool wgrad_wino_applies(const PixDims& d, int Ci, int Co);
+size_t wgrad_wino_partial_floats(int Ci, int Co, int n_split);   // partials, reduced sums and the zero quad
+// Runs the kernel with n_split workgroups; the partials then need wgrad_wino_finish.
+hipError_t launch_wgrad_wino(WinoWgradArgs a, int relu_in, int n_split, hipStream_t stream);
+// grad_w[co][tap][ci] = G^T (sum of partials) G  (call after the partials have been reduced into
+// partial + n_split*16*Co*Ci by reduce_partials_kernel)
+hipError_t wgrad_wino_finish(const float* psum, int Co, int Ci, float* grad_w, hipStream_t stream);
+
 struct ConvBf16Args {
     const unsigned short* in;
     void* out;

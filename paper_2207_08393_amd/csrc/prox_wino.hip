@@ -44,6 +44,11 @@ __device__ __forceinline__ void dma16(const float* g, float* l) {
                                      (__attribute__((address_space(3))) void*)l, 16, 0, 0);
 }
 
+// uniform base + per-lane unsigned byte offset: the form the compiler turns into a scalar-base direct load
+__device__ __forceinline__ void dma16_off(const float* base, unsigned byte_off, float* l) {
+    dma16(reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off), l);
+}
+
 __device__ __forceinline__ float4 relu4(float4 v) {   // on the bit patterns: negative floats are negative integers
     int x0 = __float_as_int(v.x), x1 = __float_as_int(v.y), x2 = __float_as_int(v.z), x3 = __float_as_int(v.w);
     x0 = x0 > 0 ? x0 : 0; x1 = x1 > 0 ? x1 : 0; x2 = x2 > 0 ? x2 : 0; x3 = x3 > 0 ? x3 : 0;
@@ -109,7 +114,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
         return b;
     };
     const float* ubase = a.u + (size_t)ny * n_kc * (kWUSlots * 4);   // uniform; lanes add a 32-bit offset
-    const unsigned uoff = 4u * (unsigned)tid;
+    const unsigned uoff = 16u * (unsigned)tid;   // bytes
 
     auto issue = [&](const Block& b, int kc, float* dst) {
 #pragma unroll
@@ -121,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
         for (int i = 0; i < 8; ++i) {
             const int o = wave + i * 4;
             const float* ub = ubase + ((size_t)kc * (kWUSlots * 4) + 1024 * i);   // scalar address
-            dma16(ub + uoff, dst + kWRawSlots * 4 + o * 256);
+            dma16_off(ub, uoff, dst + kWRawSlots * 4 + o * 256);
         }
     };
 
@@ -321,6 +326,259 @@ __global__ __launch_bounds__(256) void wino_weights_kernel(const float* __restri
 #pragma unroll
         for (int nu = 0; nu < 4; ++nu) dst[(size_t)(4 * x + nu) * 2 * 64 * 4] = uu[nu];
     }
+}
+
+// ------------------------------------------------------------------ weight gradient
+// dL/dg = G^T [ sum over tiles of (A dY A^T) .* (B^T d B) ] G: per position of the 4x4 grid a
+// [cout x tiles] . [tiles x cin] matrix product.  A workgroup of 8 waves keeps all 16 products of a 64 x 64
+// channel block in registers (wave = row xi of the grid x one of the two 32-channel input blocks: 4 positions
+// x 64 x 32 = 8 accumulators of 32x32), walks chunks of 16 tiles (2 x 32
+// output pixels: the raw gradient rows and the raw input rows with halo are staged in LDS by direct loads,
+// all channels, double-buffered) and forms both MFMA operands on the fly: a lane holds one channel and one
+// of the two tiles of an MFMA's contraction step, reads the few pixels its position needs (4-byte LDS reads,
+// lanes = consecutive channels; the two lane halves are kept on different banks by an XOR of the channel
+// index with a pixel bit) and combines them with 2-3 additions.  Persistent split over the image: every
+// workgroup writes its partial sums once; a fixed-order reduction and G^T . G follow.
+constexpr int kGDPix = 4 * 34, kGGPix = 2 * 32;          // staged pixels per chunk: input rows with halo, gradient rows
+constexpr int kGBufFloats = (kGDPix + kGGPix) * 64;
+constexpr int kGWaveLoads = (kGDPix + kGGPix) * 16 / 64;   // 50 wave-wide direct loads per chunk
+
+template <bool RELU>
+__global__ __launch_bounds__(512) void wgrad_wino_kernel(WinoWgradArgs a) {
+    __shared__ __attribute__((aligned(16))) float bufs[2 * kGBufFloats];   // two chunk buffers
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int xi = wave >> 1, ji = wave & 1;   // wave = row of the product grid x 32-channel input block
+    const int m = lane & 31, h = lane >> 5;
+    const int nci = a.Ci / 64;
+    const int co0 = 64 * ((int)blockIdx.y / nci), ci0 = 64 * ((int)blockIdx.y % nci);
+    const XcdRange xr = xcd_range(a.n_chunks);
+    if (xr.first >= xr.end) {   // nothing to do: the partial of this workgroup is zero
+        for (int i = tid; i < 16 * 64 * 64; i += 512) {
+            const int pos = i >> 12, co = (i >> 6) & 63, ci = i & 63;
+            a.partial[(((size_t)blockIdx.x * 16 + pos) * a.Co + co0 + co) * a.Ci + ci0 + ci] = 0.f;
+        }
+        if (a.bias_partial && ci0 == 0 && tid < 64) a.bias_partial[(size_t)blockIdx.x * a.Co + co0 + tid] = 0.f;
+        return;
+    }
+
+    // direct-load slots of this lane (7 x 512 >= 3200 quads): byte offset from the chunk origin and position
+    constexpr int NS = 7;
+    unsigned s_off[NS];
+    int s_rc[NS];   // (row + 1) << 8 | (column + 1), relative to the first output pixel of the chunk
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int s = tid + 512 * i;
+        if (s < kGDPix * 16) {
+            const int px = s >> 4, qd = (s & 15) ^ (8 * ((px >> 1) & 1));
+            const int row = px / 34, col = px - row * 34;
+            s_rc[i] = (row << 8) | col;
+            s_off[i] = 4u * (unsigned)((row * a.W + col) * a.Ci + 4 * qd);
+        } else {
+            const int s2 = s - kGDPix * 16;
+            const int px = s2 >> 4, qd = (s2 & 15) ^ (8 * ((px >> 1) & 1));
+            const int row = px >> 5, col = px & 31;
+            s_rc[i] = ((row + 1) << 8) | (col + 1);
+            s_off[i] = 4u * (unsigned)((row * a.W + col) * a.Co + 4 * qd);
+        }
+    }
+    // slots 0..2175 belong to the input region, the rest to the gradient region: slot = tid + 512*i
+    auto is_g = [&](int i) { return i > 4 || (i == 4 && tid >= kGDPix * 16 - 4 * 512); };
+    auto issue = [&](long long item, float* dst) {
+        const int bx = (int)(item % a.bx_n);
+        const long long rest = item / a.bx_n;
+        const int by = (int)(rest % a.by_n);
+        const long long img = rest / a.by_n;
+        const int x0 = 32 * bx, y0 = 2 * by;
+        const float* od = a.a + ((img * a.H + y0 - 1) * a.W + x0 - 1) * a.Ci + ci0;   // uniform; never read outside the tensor
+        const float* og = a.g + ((img * a.H + y0) * a.W + x0) * a.Co + co0;
+        const bool interior = y0 >= 1 && y0 + 2 < a.H && x0 >= 1 && x0 + 32 < a.W;    // uniform
+        if (interior) {
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int o = wave + 8 * i;
+                if (o < kGWaveLoads) {
+                    if (i < 4) dma16_off(od, s_off[i], dst + o * 256);
+                    else if (i > 4) dma16_off(og, s_off[i], dst + o * 256);
+                    else dma16(reinterpret_cast<const float*>(reinterpret_cast<const char*>(is_g(i) ? og : od) + s_off[i]), dst + o * 256);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int o = wave + 8 * i;
+                if (o < kGWaveLoads) {
+                    const int yy = y0 - 1 + (s_rc[i] >> 8), xx = x0 - 1 + (s_rc[i] & 255);
+                    const bool ok = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
+                    dma16(ok ? reinterpret_cast<const float*>(reinterpret_cast<const char*>(is_g(i) ? og : od) + s_off[i]) : a.zero,
+                          dst + o * 256);
+                }
+            }
+        }
+    };
+
+    // row xi of A dY (coefficients of the two gradient rows) and of B^T d (two of the four input rows)
+    const float ca = xi == 3 ? 0.f : 1.f, cb = xi == 0 ? 0.f : (xi == 1 ? 1.f : -1.f);
+    const int ra = xi == 0 ? 0 : (xi == 2 ? 2 : 1), rb = xi == 3 ? 3 : (xi == 2 ? 1 : 2);
+    const float sg = xi == 1 ? 1.f : -1.f;
+    // LDS float offsets of this lane inside a chunk buffer: element (pixel, channel) sits at
+    // pixel*64 + (channel ^ 32*((pixel>>1)&1))
+    int db[2][2];   // input channel 32*ji + m: [row a/b][(column>>1)&1]
+#pragma unroll
+    for (int rs = 0; rs < 2; ++rs)
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp) {
+            const int r = rs ? rb : ra;
+            db[rs][cp] = (r * 34 + 2 * h) * 64 + m + 32 * (ji ^ ((r + h + cp) & 1));
+        }
+    int gb[2];      // output channels m and 32 + m
+#pragma unroll
+    for (int jo = 0; jo < 2; ++jo) gb[jo] = kGDPix * 64 + (2 * h) * 64 + m + 32 * (jo ^ h);
+
+    floatx16 acc[4][2];   // [column nu of the product grid][cout block]
+#pragma unroll
+    for (int nu = 0; nu < 4; ++nu)
+#pragma unroll
+        for (int jo = 0; jo < 2; ++jo)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nu][jo][r] = 0.f;
+    float bsum[2] = {0.f, 0.f};
+
+    // One chunk: 8 contraction steps (tiles 2q and 2q+1 on the two lane halves), 8 MFMAs each.  One copy of the
+    // code serves both chunk buffers (the buffer is a uniform offset added to six lane addresses per chunk); a
+    // scheduling fence per step bounds how far the compiler may pull LDS reads forward.
+    auto run = [&](int boff) {
+        const float* const pd00 = bufs + boff + db[0][0];
+        const float* const pd01 = bufs + boff + db[0][1];
+        const float* const pd10 = bufs + boff + db[1][0];
+        const float* const pd11 = bufs + boff + db[1][1];
+        const float* const pg0 = bufs + boff + gb[0];
+        const float* const pg1 = bufs + boff + gb[1];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float z[4][2], v[4];
+#pragma unroll
+            for (int jo = 0; jo < 2; ++jo) {
+                const float* pg = jo ? pg1 : pg0;
+                const float g00 = pg[(4 * q) * 64], g01 = pg[(4 * q + 1) * 64];
+                const float g10 = pg[(32 + 4 * q) * 64], g11 = pg[(32 + 4 * q + 1) * 64];
+                const float r0 = fmaf(cb, g10, ca * g00), r1 = fmaf(cb, g11, ca * g01);   // row xi of A dY
+                z[0][jo] = r0;                // (A dY A^T)[xi][nu]: r0, r0 + r1, r0 - r1, -r1
+                z[1][jo] = r0 + r1;
+                z[2][jo] = r0 - r1;
+                z[3][jo] = -r1;
+            }
+            {
+                float t[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float da = ((c >> 1) & 1 ? pd01 : pd00)[(4 * q + c) * 64];
+                    float dbv = ((c >> 1) & 1 ? pd11 : pd10)[(4 * q + c) * 64];
+                    if (RELU) {
+                        da = __int_as_float(__float_as_int(da) > 0 ? __float_as_int(da) : 0);
+                        dbv = __int_as_float(__float_as_int(dbv) > 0 ? __float_as_int(dbv) : 0);
+                    }
+                    t[c] = fmaf(sg, dbv, da);   // row xi of B^T d
+                }
+                v[0] = t[0] - t[2];
+                v[1] = t[1] + t[2];
+                v[2] = t[2] - t[1];
+                v[3] = t[1] - t[3];
+            }
+            if (xi == 1) { bsum[0] += z[1][0]; bsum[1] += z[1][1]; }   // position (1,1) of A dY A^T = sum of the 2x2 block
+#pragma unroll
+            for (int nu = 0; nu < 4; ++nu)
+#pragma unroll
+                for (int jo = 0; jo < 2; ++jo)
+                    acc[nu][jo] = __builtin_amdgcn_mfma_f32_32x32x2f32(z[nu][jo], v[nu], acc[nu][jo], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    issue(xr.first, bufs);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    int cur = 0;
+    for (long long item = xr.first; item < xr.end; item += xr.stride) {
+        if (item + xr.stride < xr.end) issue(item + xr.stride, bufs + (cur ^ 1) * kGBufFloats);
+        __builtin_amdgcn_sched_barrier(0);
+        run(cur * kGBufFloats);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        cur ^= 1;
+    }
+
+#pragma unroll
+    for (int nu = 0; nu < 4; ++nu) {
+        const int pos = 4 * xi + nu;
+#pragma unroll
+        for (int jo = 0; jo < 2; ++jo)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = co0 + 32 * jo + 8 * (r >> 2) + 4 * h + (r & 3), ci = ci0 + 32 * ji + m;
+                a.partial[(((size_t)blockIdx.x * 16 + pos) * a.Co + co) * a.Ci + ci] = acc[nu][jo][r];
+            }
+    }
+    if (a.bias_partial && ci0 == 0 && xi == 1 && ji == 0) {
+#pragma unroll
+        for (int jo = 0; jo < 2; ++jo) {
+            const float tot = bsum[jo] + __shfl_xor(bsum[jo], 32);
+            if (h == 0) a.bias_partial[(size_t)blockIdx.x * a.Co + co0 + 32 * jo + m] = tot;
+        }
+    }
+}
+
+// grad_w[co][tap][ci] = G^T P G from the reduced sums P[pos][co][ci]
+__global__ __launch_bounds__(256) void wgrad_wino_finish_kernel(const float* __restrict__ psum, int Co, int Ci, float* __restrict__ gw) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= Co * Ci) return;
+    const int ci = idx % Ci, co = idx / Ci;
+    float P[4][4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int n = 0; n < 4; ++n) P[x][n] = psum[((size_t)(4 * x + n) * Co + co) * Ci + ci];
+    float gp[3][4];   // G^T P
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        gp[0][n] = P[0][n] + 0.5f * (P[1][n] + P[2][n]);
+        gp[1][n] = 0.5f * (P[1][n] - P[2][n]);
+        gp[2][n] = 0.5f * (P[1][n] + P[2][n]) + P[3][n];
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        float* o = gw + ((size_t)co * 9 + t * 3) * Ci + ci;
+        o[0] = gp[t][0] + 0.5f * (gp[t][1] + gp[t][2]);
+        o[Ci] = 0.5f * (gp[t][1] - gp[t][2]);
+        o[2 * Ci] = 0.5f * (gp[t][1] + gp[t][2]) + gp[t][3];
+    }
+}
+
+bool wgrad_wino_applies(const PixDims& d, int Ci, int Co) {
+    return d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3 && Ci % 64 == 0 && Co % 64 == 0 &&
+           4.0 * d.W * (Ci > Co ? Ci : Co) < 5.0e8;   // 32-bit lane byte offsets within four image rows
+}
+
+size_t wgrad_wino_partial_floats(int Ci, int Co, int n_split) { return (size_t)(n_split + 1) * 16 * Ci * Co + 4; }
+
+hipError_t launch_wgrad_wino(WinoWgradArgs a, int relu_in, int n_split, hipStream_t st) {
+    a.bx_n = (a.W + 31) / 32;
+    a.by_n = (a.H + 1) / 2;
+    a.n_chunks = a.NI * (long long)a.bx_n * a.by_n;
+    a.zero = a.partial + (size_t)(n_split + 1) * 16 * a.Co * a.Ci;
+    {   // a fill kernel rather than a memset node, so that callers may capture the launch sequence
+        const hipError_t e = fill_zero(reinterpret_cast<float2*>(const_cast<float*>(a.zero)), 2, st);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)n_split, (unsigned)((a.Co / 64) * (a.Ci / 64)));
+    if (relu_in) hipLaunchKernelGGL((wgrad_wino_kernel<true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_wino_kernel<false>), grid, dim3(512), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t wgrad_wino_finish(const float* psum, int Co, int Ci, float* grad_w, hipStream_t st) {
+    hipLaunchKernelGGL(wgrad_wino_finish_kernel, dim3((unsigned)((Co * Ci + 255) / 256)), dim3(256), 0, st, psum, Co, Ci, grad_w);
+    return hipGetLastError();
 }
 
 bool conv_wino_applies(const PixDims& d, int K, int Nn) {
