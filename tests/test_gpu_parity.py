@@ -76,6 +76,12 @@ def module_cases():
     yield "vol32", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), 0
     yield "cine64", synth.Geom(2, 1, 2, 6, 1, 12, 16), synth.chain_prox([2, 64, 64, 64, 2], [KS, KT, KS, KT]), 0
     yield "k5", synth.Geom(2, 1, 2, 1, 1, 10, 12), synth.chain_prox([2, 6, 2], [(1, 1, 5, 5), (1, 1, 1, 5)]), 0
+    # 3x3 layers with 64-multiples of channels take the Winograd kernels: image sizes that the 4 x 32 and 2 x 32
+    # pixel blocks do not divide (transform lengths are even, so odd sizes cannot occur), several images, two
+    # channel blocks on either side, no bias
+    yield "wino_ragged", synth.Geom(2, 2, 2, 1, 1, 10, 46), synth.resblock_prox(64, 1), 0
+    yield "wino_128", synth.Geom(2, 1, 2, 1, 1, 6, 96), synth.chain_prox([2, 64, 128, 64, 2], [K2] * 4), 0
+    yield "wino_nobias_l1", synth.Geom(2, 1, 2, 3, 1, 6, 46), synth.chain_prox([2, 64, 64, 2], [K2] * 3, has_bias=0), 1
 
 
 def check_module(c, tol=TOL, alpha=None):
@@ -136,6 +142,16 @@ def test_backward_is_deterministic_and_decoupled():
     r.step()
     assert np.array_equal(r.results()[2], g1)                 # bit-identical split-K reduction
     assert torch.equal(r.x_in, x_in_before)                   # inputs are never written
+    # the same for the Winograd kernels (64-channel 3x3 layers): partial sums are reduced in a fixed order
+    cw = synth.make_custom(4, synth.Geom(2, 2, 2, 1, 1, 20, 46), synth.resblock_prox(64, 1), accel=2.0, centre=2)
+    rw = ModuleRunner(cw)
+    rw.step()
+    xw, _, gw = rw.results()
+    xw, gw = xw.copy(), gw.copy()
+    rw.grad.fill_(float("nan"))
+    rw.x_out.fill_(float("nan"))
+    rw.step()
+    assert np.array_equal(rw.results()[2], gw) and np.array_equal(rw.results()[0], xw)
     # hand-off: x_out of module 1 is module 2's x_in; module 1's gradient is unaffected by module 2
     th2 = synth.init_theta(np.random.default_rng(1), c.prox, 0.1)
     r2 = ModuleRunner(c, theta=th2, x_in=r.results()[0])
