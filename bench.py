@@ -31,14 +31,14 @@ PEAK_HBM_GBS = 8000.0
 # FETCH_SIZE (factor 2.0: the counter under-reports 128-byte requests) and 262 144 KiB on WRITE_SIZE (1.0).
 MEASURED_TRAFFIC = {
     "conv_wino_kernel<RELU> fwd+dgrad 64->64 3x3 (Winograd F(2x2,3x3))": 1.3876e5 * 1024 * 2.0 + 1.1776e5 * 1024 * 1.0,
-    "wgrad_pipe_kernel<3,1,3,12> wgrad 64->64 3x3": 1.184e5 * 1024 * 2.0 + 3.693e4 * 1024 * 1.0,
+    "wgrad_wino_kernel<RELU> wgrad 64->64 3x3 (Winograd F(2x2,3x3))": None,
 }
 
 # library launch label -> GPU kernel it runs (forward and data gradient of a 64->64 layer are one kernel)
 KERNEL_OF = {
     "conv_fwd_64to64_t9": "conv_wino_kernel<RELU> fwd+dgrad 64->64 3x3 (Winograd F(2x2,3x3))",
     "conv_dgrad_64to64_t9": "conv_wino_kernel<RELU> fwd+dgrad 64->64 3x3 (Winograd F(2x2,3x3))",
-    "conv_wgrad_64to64_t9": "wgrad_pipe_kernel<3,1,3,12> wgrad 64->64 3x3",
+    "conv_wgrad_64to64_t9": "wgrad_wino_kernel<RELU> wgrad 64->64 3x3 (Winograd F(2x2,3x3))",
 }
 
 

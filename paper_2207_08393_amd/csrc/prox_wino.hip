@@ -454,15 +454,29 @@ __global__ __launch_bounds__(512) void wgrad_wino_kernel(WinoWgradArgs a) {
         const float* const pd11 = bufs + boff + db[1][1];
         const float* const pg0 = bufs + boff + gb[0];
         const float* const pg1 = bufs + boff + gb[1];
+        float rg[2][4], rd[2][4];   // raw pixels of one step: gradient [cout block][row*2 + column], input [row a/b][column]
+        auto load = [&](int q) {
+#pragma unroll
+            for (int jo = 0; jo < 2; ++jo) {
+                const float* pg = jo ? pg1 : pg0;
+                rg[jo][0] = pg[(4 * q) * 64];
+                rg[jo][1] = pg[(4 * q + 1) * 64];
+                rg[jo][2] = pg[(32 + 4 * q) * 64];
+                rg[jo][3] = pg[(32 + 4 * q + 1) * 64];
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                rd[0][c] = ((c >> 1) & 1 ? pd01 : pd00)[(4 * q + c) * 64];
+                rd[1][c] = ((c >> 1) & 1 ? pd11 : pd10)[(4 * q + c) * 64];
+            }
+        };
+        load(0);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             float z[4][2], v[4];
 #pragma unroll
             for (int jo = 0; jo < 2; ++jo) {
-                const float* pg = jo ? pg1 : pg0;
-                const float g00 = pg[(4 * q) * 64], g01 = pg[(4 * q + 1) * 64];
-                const float g10 = pg[(32 + 4 * q) * 64], g11 = pg[(32 + 4 * q + 1) * 64];
-                const float r0 = fmaf(cb, g10, ca * g00), r1 = fmaf(cb, g11, ca * g01);   // row xi of A dY
+                const float r0 = fmaf(cb, rg[jo][2], ca * rg[jo][0]), r1 = fmaf(cb, rg[jo][3], ca * rg[jo][1]);   // row xi of A dY
                 z[0][jo] = r0;                // (A dY A^T)[xi][nu]: r0, r0 + r1, r0 - r1, -r1
                 z[1][jo] = r0 + r1;
                 z[2][jo] = r0 - r1;
@@ -472,8 +486,7 @@ __global__ __launch_bounds__(512) void wgrad_wino_kernel(WinoWgradArgs a) {
                 float t[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    float da = ((c >> 1) & 1 ? pd01 : pd00)[(4 * q + c) * 64];
-                    float dbv = ((c >> 1) & 1 ? pd11 : pd10)[(4 * q + c) * 64];
+                    float da = rd[0][c], dbv = rd[1][c];
                     if (RELU) {
                         da = __int_as_float(__float_as_int(da) > 0 ? __float_as_int(da) : 0);
                         dbv = __int_as_float(__float_as_int(dbv) > 0 ? __float_as_int(dbv) : 0);
@@ -486,6 +499,7 @@ __global__ __launch_bounds__(512) void wgrad_wino_kernel(WinoWgradArgs a) {
                 v[3] = t[1] - t[3];
             }
             if (xi == 1) { bsum[0] += z[1][0]; bsum[1] += z[1][1]; }   // position (1,1) of A dY A^T = sum of the 2x2 block
+            if (q + 1 < 8) load(q + 1);      // the next step's pixels are on their way while this step's MFMAs issue
 #pragma unroll
             for (int nu = 0; nu < 4; ++nu)
 #pragma unroll
