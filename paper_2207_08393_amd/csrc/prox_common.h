@@ -173,7 +173,6 @@ hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long 
 struct WinoWgradArgs {
     const float* g;         // [NI][H][W][Co]  gradient at the conv output (already ReLU-masked)
     const float* a;         // [NI][H][W][Ci]  conv input before its optional ReLU
-    const float* zero;      // one quad of zeros in global memory
     float* partial;         // [gridDim.x][16][Co][Ci], followed by [16][Co][Ci] for the reduced sums
     float* bias_partial;    // [gridDim.x][Co] or null
     int Co, Ci;
@@ -182,7 +181,7 @@ struct WinoWgradArgs {
     long long n_chunks;
 };
 bool wgrad_wino_applies(const PixDims& d, int Ci, int Co);
-size_t wgrad_wino_partial_floats(int Ci, int Co, int n_split);   // partials, reduced sums and the zero quad
+size_t wgrad_wino_partial_floats(int Ci, int Co, int n_split);   // partials and reduced sums
 // Runs the kernel with n_split workgroups; the partials then need wgrad_wino_finish.
 hipError_t launch_wgrad_wino(WinoWgradArgs a, int relu_in, int n_split, hipStream_t stream);
 // grad_w[co][tap][ci] = G^T (sum of partials) G  (call after the partials have been reduced into

@@ -410,8 +410,10 @@ __global__ __launch_bounds__(512) void wgrad_wino_kernel(WinoWgradArgs a) {
                 if (o < kGWaveLoads) {
                     const int yy = y0 - 1 + (s_rc[i] >> 8), xx = x0 - 1 + (s_rc[i] & 255);
                     const bool ok = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
-                    dma16(ok ? reinterpret_cast<const float*>(reinterpret_cast<const char*>(is_g(i) ? og : od) + s_off[i]) : a.zero,
-                          dst + o * 256);
+                    // lanes whose pixel lies outside the image store zeros themselves (a direct load writes lane l's
+                    // 16 bytes at the wave's base + 16*l, masked-off lanes write nothing)
+                    if (ok) dma16(reinterpret_cast<const float*>(reinterpret_cast<const char*>(is_g(i) ? og : od) + s_off[i]), dst + o * 256);
+                    else *reinterpret_cast<float4*>(dst + o * 256 + lane * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
         }
@@ -573,17 +575,12 @@ bool wgrad_wino_applies(const PixDims& d, int Ci, int Co) {
            4.0 * d.W * (Ci > Co ? Ci : Co) < 5.0e8;   // 32-bit lane byte offsets within four image rows
 }
 
-size_t wgrad_wino_partial_floats(int Ci, int Co, int n_split) { return (size_t)(n_split + 1) * 16 * Ci * Co + 4; }
+size_t wgrad_wino_partial_floats(int Ci, int Co, int n_split) { return (size_t)(n_split + 1) * 16 * Ci * Co; }
 
 hipError_t launch_wgrad_wino(WinoWgradArgs a, int relu_in, int n_split, hipStream_t st) {
     a.bx_n = (a.W + 31) / 32;
     a.by_n = (a.H + 1) / 2;
     a.n_chunks = a.NI * (long long)a.bx_n * a.by_n;
-    a.zero = a.partial + (size_t)(n_split + 1) * 16 * a.Co * a.Ci;
-    {   // a fill kernel rather than a memset node, so that callers may capture the launch sequence
-        const hipError_t e = fill_zero(reinterpret_cast<float2*>(const_cast<float*>(a.zero)), 2, st);
-        if (e != hipSuccess) return e;
-    }
     dim3 grid((unsigned)n_split, (unsigned)((a.Co / 64) * (a.Ci / 64)));
     if (relu_in) hipLaunchKernelGGL((wgrad_wino_kernel<true>), grid, dim3(512), 0, st, a);
     else hipLaunchKernelGGL((wgrad_wino_kernel<false>), grid, dim3(512), 0, st, a);
