@@ -16,6 +16,7 @@ product.  Everything is float64 / complex128 numpy, written as the plain definit
   * backward : analytic reverse sweep for dL/dtheta of this module only (Alg. 1, gradient step);
                nothing is propagated to x_in, S or y (decoupled modules).
 
+  * alpha    : gradient of the local loss with respect to the step size of the data-consistency step
   * deep     : a module of K = N/M unrolled iterations (GLEAM section): backpropagation inside the module,
                through its prox networks and data-consistency steps, none beyond its input
   * MoDL     : the half-quadratic-splitting module (MoDL section, Eq. 6-8): z = f_theta(x), then
@@ -277,6 +278,15 @@ def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None):
 def module_bwd(prox, theta, fwd):
     """dL/dtheta_m of the local objective; stops at the module input."""
     return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"])
+
+
+def module_bwd_alpha(geom, prox, x_in, S, M, y, theta, fwd):
+    """Gradients of the local loss with respect to theta and to the step size alpha = 2t of the module's
+    data-consistency step (Eq. 3), for a learnable step size.  u = x - alpha r with r = A^H (A x - y), so
+    dL/dalpha = -<dL/du, r> over the real and imaginary parts; still nothing goes to x_in."""
+    g_theta, g_u = prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"], want_input_grad=True)
+    r = sense_adjoint(masked_residual(x_in, S, M, y, geom.ndim_fft), S, M, geom.ndim_fft)
+    return g_theta, float(-(g_u * complex_to_channels(r)).sum())
 
 
 # ----------------------------------------------------------------------------- module of several iterations

@@ -168,3 +168,33 @@ def test_dc_gradient_operator_is_conditioned_by_one_over_one_minus_alpha():
         lo, hi = min(lo, r), max(hi, r)
     assert 1 - alpha - 1e-12 <= lo and hi <= 1 + 1e-12
     assert lo < 0.6                                 # the contraction is real: sampled components do shrink
+
+
+def test_step_size_gradient_vs_torch_autograd_and_finite_differences():
+    """dL/dalpha of the local loss, with alpha a differentiable scalar of the torch model (torch.fft DC step,
+    conv3d prox) and by central differences of the oracle's own forward pass."""
+    for loss_kind, prox in ((0, synth.resblock_prox(3, 1)), (1, synth.chain_prox([2, 4, 2], [(1, 1, 3, 3)] * 2))):
+        prox.loss_kind = loss_kind
+        c = synth.make_custom(21 + loss_kind, synth.Geom(2, 2, 3, 1, 1, 6, 8), prox, accel=2.0, centre=2, bias_std=0.1)
+        alpha = 0.6
+        theta = c.theta.astype(np.float64)
+        f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, theta, c.x_true)
+        g_theta, g_alpha = og.module_bwd_alpha(c.geom, c.prox, c.x_in, c.S, c.M, c.y, theta, f)
+        assert np.allclose(g_theta, og.module_bwd(c.prox, theta, f), rtol=0, atol=0)      # same parameter gradient
+
+        S = torch.from_numpy(c.S.astype(np.complex128)); M = torch.from_numpy(c.M)
+        y = torch.from_numpy(c.y.astype(np.complex128)); x = torch.from_numpy(c.x_in.astype(np.complex128))
+        a_t = torch.tensor(alpha, dtype=torch.float64, requires_grad=True)
+        p = torch.tensor(theta.copy(), requires_grad=True)
+        u = torch_dc(x, S, M, y, a_t, 2)
+        z = torch_prox(c.prox.layers, p, torch.view_as_real(u), c.geom.image_shape)
+        d = torch.view_as_complex(z.contiguous()) - torch.from_numpy(c.x_true.astype(np.complex128))
+        loss = (d.abs() ** 2).mean() if loss_kind == 0 else d.abs().mean()
+        loss.backward()
+        assert np.isclose(g_alpha, a_t.grad.item(), rtol=1e-9)
+        assert np.allclose(g_theta, p.grad.numpy(), rtol=1e-8, atol=1e-12)
+
+        h = 1e-5
+        lp = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha + h, theta, c.x_true)["loss"]
+        lm = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha - h, theta, c.x_true)["loss"]
+        assert np.isclose(g_alpha, (lp - lm) / (2 * h), rtol=1e-5)
