@@ -114,6 +114,17 @@ int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const 
                      const void* saved, size_t saved_bytes, float* grad_theta,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* gleam_module_bwd for a learnable step size (Eq. 3, alpha = 2t as a parameter of the module): grad_theta as
+ * gleam_module_bwd, and grad_alpha (one float32 on the device) = dL/dalpha = -<dL/du, A^H (A x_in - y)>, the
+ * inner product taken over real and imaginary parts.  dL/du is the gradient with respect to the prox input,
+ * so the prox must have relu_in = 0 on its first layer and at most one layer taking its skip from the input
+ * (else GLEAM_E_DESC); the residual image is recomputed with one more SENSE sweep.  x_in, S, M, y are the
+ * arguments the forward call had; `saved` is written (the prox input is replaced by its gradient). */
+int gleam_module_bwd_alpha(const gleam_geom* geom, const gleam_prox_desc* prox, const gleam_c64* x_in,
+                           const gleam_c64* S, const uint8_t* M, const gleam_c64* y, const float* theta,
+                           void* saved, size_t saved_bytes, float* grad_theta, float* grad_alpha, void* ws,
+                           size_t ws_bytes, void* stream);
+
 /* A module that holds n_iter = N/M unrolled iterations (GLEAM section, N > M), each with its own parameters:
  *     x_j = f_theta_j(DC(x_{j-1})),  j = 1..n_iter,   loss = L(x_{n_iter}, x_ref)
  * The local loss is backpropagated inside the module, through its prox networks and data-consistency steps

@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
         L.gleam_sense_normal.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
         L.gleam_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_module_bwd.argtypes = [pg, pp, vp, vp, sz, vp, vp, sz, vp]
+        L.gleam_module_bwd_alpha.argtypes = [pg, pp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, sz, vp]
         L.gleam_deep_workspace_bytes.argtypes = [pg, pp, C.c_int, C.POINTER(sz), C.POINTER(sz)]
         L.gleam_deep_module_fwd.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_deep_module_bwd.argtypes = [pg, pp, C.c_int, vp, vp, C.c_float, vp, vp, sz, vp, vp, sz, vp]
@@ -90,7 +91,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
-           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_deep_workspace_bytes",
+           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_module_bwd_alpha", "gleam_deep_workspace_bytes",
            "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_sense_adjoint", "gleam_modl_workspace_bytes",
            "gleam_modl_module_fwd", "gleam_modl_module_bwd", "gleam_adam_step",
            "gleam_greedy_iteration", "gleam_unrolled_infer", "gleam_profile_begin", "gleam_profile_end")
@@ -176,6 +177,12 @@ def gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref, x_out, loss
 def gleam_module_bwd(geom, prox, theta, saved, grad_theta, ws, stream=None):
     _check(lib().gleam_module_bwd(C.byref(geom), C.byref(prox), _ptr(theta), _ptr(saved), _nbytes(saved),
                                   _ptr(grad_theta), _ptr(ws), _nbytes(ws), _stream(stream)), "gleam_module_bwd")
+
+
+def gleam_module_bwd_alpha(geom, prox, x_in, S, M, y, theta, saved, grad_theta, grad_alpha, ws, stream=None):
+    _check(lib().gleam_module_bwd_alpha(C.byref(geom), C.byref(prox), _ptr(x_in), _ptr(S), _ptr(M), _ptr(y), _ptr(theta),
+                                        _ptr(saved), _nbytes(saved), _ptr(grad_theta), _ptr(grad_alpha), _ptr(ws),
+                                        _nbytes(ws), _stream(stream)), "gleam_module_bwd_alpha")
 
 
 def gleam_deep_workspace_bytes(geom, prox, n_iter):

@@ -221,6 +221,36 @@ int gleam_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, const 
     return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
 }
 
+static int check_deep(const gleam_prox_desc* prox, int n_iter);
+
+int gleam_module_bwd_alpha(const gleam_geom* geom, const gleam_prox_desc* prox, const gleam_c64* x_in, const gleam_c64* S,
+                           const uint8_t* M, const gleam_c64* y, const float* theta, void* saved, size_t saved_bytes,
+                           float* grad_theta, float* grad_alpha, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    rc = check_prox(prox);
+    if (rc) return rc;
+    rc = check_deep(prox, 2);   // the same conditions as a gradient that crosses the prox input
+    if (rc) return rc;
+    if (!x_in || !S || !M || !y || !theta || !saved || !grad_theta || !grad_alpha || !ws) return GLEAM_E_NULL;
+    ProxPlan plan;
+    plan_prox(*geom, *prox, plan);
+    if (!aligned(ws) || ws_bytes < plan.ws_bytes) return GLEAM_E_WORKSPACE;
+    if (!aligned(saved) || saved_bytes < plan.saved_bytes) return GLEAM_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float2* g_u = (float2*)((unsigned char*)saved + plan.act_off[0]);   // dL/du replaces u, which is dead by then
+    hipError_t e = prox_backward(*geom, *prox, plan, theta, (const unsigned char*)saved, grad_theta, g_u, ws, st);
+    if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    // r = A^H (A x_in - y) into the image slot behind the k-space buffer, then dL/dalpha = -<dL/du, r>
+    float2* r = (float2*)((unsigned char*)ws + plan.k_bytes);
+    e = sense_dc(*geom, (const float2*)x_in, (const float2*)S, M, (const float2*)y, 0.f, 1.f, r, (float2*)ws, st);
+    if (e != hipSuccess) return GLEAM_E_LAUNCH;
+    // the partial sums go behind the residual image (the head of the workspace is the k-space buffer)
+    double* part = (double*)((unsigned char*)ws + plan.k_bytes + align_up((size_t)plan.Q * sizeof(float2)));
+    e = real_dot(g_u, r, plan.Q, -1.0, part, grad_alpha, st);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
 static int check_deep(const gleam_prox_desc* prox, int n_iter) {
     if (n_iter < 1) return GLEAM_E_DIMS;
     if (n_iter == 1) return GLEAM_OK;

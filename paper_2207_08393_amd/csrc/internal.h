@@ -95,6 +95,9 @@ hipError_t cg_solve(const gleam_geom& g, const float2* S, const unsigned char* M
                     const float2* v, float c1, float c2, float2* x, float2* kbuf, void* scratch, hipStream_t st);
 hipError_t fill_zero(float2* x, long long n, hipStream_t st);
 
+// out (device scalar) = scale * sum over all samples of Re <u, v>; n complex values in total; part: kLossPartials doubles
+hipError_t real_dot(const float2* u, const float2* v, long long n, double scale, double* part, float* out, hipStream_t st);
+
 // theta <- Adam(theta, grad) in place with state m, v; bias corrections evaluated on the host in double.
 hipError_t adam_update(const gleam_adam& h, long long t, size_t n, float* theta, const float* grad, float* m, float* v,
                        hipStream_t st);

@@ -1708,6 +1708,24 @@ __global__ void loss_final_kernel(const double* __restrict__ part, int n_part, d
     }
 }
 
+// part[blk] = partial sum of Re <u, v> (complex values as two reals)
+__global__ __launch_bounds__(256) void real_dot_kernel(const float2* __restrict__ u, const float2* __restrict__ v, long long n,
+                                                       double* __restrict__ part) {
+    __shared__ double red[256];
+    double s = 0.0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const float2 a = u[i], b = v[i];
+        s += (double)a.x * b.x + (double)a.y * b.y;
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part[blockIdx.x] = red[0];
+}
+
 // ------------------------------------------------------------------ host side
 static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 constexpr int kLossBlocks = kLossPartials;
@@ -1718,6 +1736,13 @@ hipError_t loss_and_grad(const float2* x, const float2* x_ref, float2* g, long l
     hipLaunchKernelGGL(loss_kernel, dim3(kLossBlocks), dim3(256), 0, st, x, x_ref, g, n, loss_kind, (float)(1.0 / (double)n),
                        relu_mask, part);
     hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, kLossBlocks, 1.0 / (double)n, loss);
+    return hipGetLastError();
+}
+
+hipError_t real_dot(const float2* u, const float2* v, long long n, double scale, double* part, float* out, hipStream_t st) {
+    KernelScope ks("real_dot", 0.0, 16.0 * (double)n, st);
+    hipLaunchKernelGGL(real_dot_kernel, dim3(kLossBlocks), dim3(256), 0, st, u, v, n, part);
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, (const double*)part, kLossBlocks, scale, out);
     return hipGetLastError();
 }
 

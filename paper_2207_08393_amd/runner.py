@@ -71,6 +71,14 @@ class ModuleRunner:
     def bwd(self):
         gb.gleam_module_bwd(self.geom, self.prox, self.theta, self.saved, self.grad, self.ws)
 
+    def bwd_alpha(self):
+        """Backward pass that also forms dL/dalpha (returned as a float after a synchronisation)."""
+        g_alpha = torch.full((1,), float("nan"), device="cuda")
+        gb.gleam_module_bwd_alpha(self.geom, self.prox, self.x_in, self.S, self.M, self.y, self.theta, self.saved, self.grad,
+                                  g_alpha, self.ws)
+        torch.cuda.synchronize()
+        return float(g_alpha.item())
+
     def step(self):
         self.fwd()
         self.bwd()

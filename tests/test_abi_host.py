@@ -248,3 +248,24 @@ def test_modl_entry_points_reject_bad_arguments_before_launch():
     assert L.gleam_sense_adjoint(*a) == gb.GLEAM_E_DIMS
     a = list(aargs); a[6] = 1024
     assert L.gleam_sense_adjoint(*a) == gb.GLEAM_E_WORKSPACE
+
+
+def test_step_size_gradient_entry_point_rejects_bad_arguments_before_launch():
+    c = synth.make_case(0)
+    geom, prox = gb.make_geom(c.geom), gb.make_prox(c.prox)
+    ws, saved = gb.gleam_workspace_bytes(geom, prox)
+    L = gb.lib()
+    fake = 0x1000
+    args = [C.byref(geom), C.byref(prox), fake, fake, fake, fake, fake, fake, saved, fake, fake, fake, ws, None]
+    for i in (2, 3, 4, 5, 6, 7, 9, 10, 11):
+        a = list(args); a[i] = None
+        assert L.gleam_module_bwd_alpha(*a) == gb.GLEAM_E_NULL, i
+    a = list(args); a[8] = saved - 256
+    assert L.gleam_module_bwd_alpha(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(args); a[12] = ws - 256
+    assert L.gleam_module_bwd_alpha(*a) == gb.GLEAM_E_WORKSPACE
+    relu_first = synth.chain_prox([2, 8, 2], [(1, 1, 3, 3)] * 2)
+    relu_first.layers[0].relu_in = 1
+    p = gb.make_prox(relu_first)
+    a = list(args); a[1] = C.byref(p)
+    assert L.gleam_module_bwd_alpha(*a) == gb.GLEAM_E_DESC

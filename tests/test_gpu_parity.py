@@ -367,3 +367,25 @@ def test_modl_module_survives_an_exactly_converged_solve():
     g = og.modl_module_bwd(c.geom, c.prox, c.S, c.M, 0.5, 6, c.theta, f)
     assert np.all(np.isfinite(x)) and np.all(np.isfinite(grad))
     assert rel_l2(x, f["x_out"]) <= TOL and rel_l2(grad, g) <= TOL
+
+
+# ----------------------------------------------------------------------------- learnable step size
+@pytest.mark.parametrize("name,geom,prox,loss_kind", [
+    ("res8", synth.Geom(2, 2, 3, 1, 1, 12, 10), synth.resblock_prox(8, 1), 0),
+    ("res64_l1", synth.Geom(2, 1, 2, 1, 1, 24, 46), synth.resblock_prox(64, 1), 1),
+    ("vol32", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), 0),
+    ("chain16_bf16", synth.Geom(2, 1, 2, 1, 1, 20, 12), synth.chain_prox([2, 16, 16, 2], [K2] * 3, dtype=1), 0),
+], ids=["res8", "res64_l1", "vol32", "chain16_bf16"])
+def test_step_size_gradient_matches_oracle(name, geom, prox, loss_kind):
+    prox.loss_kind = loss_kind
+    c = synth.make_custom(71, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.6)
+    r = ModuleRunner(c, alpha=0.6)
+    r.fwd()
+    g_alpha = r.bwd_alpha()
+    _, _, grad = r.results()
+    f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.6, c.theta, c.x_true)
+    g_ref, ga_ref = og.module_bwd_alpha(c.geom, c.prox, c.x_in, c.S, c.M, c.y, c.theta, f)
+    tol = BF16_TOL if c.prox.dtype == 1 else TOL
+    errs = (rel_l2(grad, g_ref), abs(g_alpha - ga_ref) / abs(ga_ref))
+    print("case alpha", name, "rel errors grad_theta / grad_alpha:", errs, "grad_alpha", ga_ref, flush=True)
+    assert errs[0] <= tol and errs[1] <= tol
