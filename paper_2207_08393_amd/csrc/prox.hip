@@ -283,7 +283,9 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ConvArgs a) {
 template <int NB, int CK, int PJ, int NW, int KW, bool RELU>
 __global__ __launch_bounds__(NW * 64, 2) void conv_dlds_kernel(ConvArgs a) {
     constexpr int TM = NW * 32 * PJ, G = CK / 8, NJ = NB / 32, Q4 = CK / 4;
-    constexpr int RP = Q4 >= 8 ? 1 : 8 / Q4;   // pixel rows per 128 bytes of LDS
+    // Swizzle period: LDS serves 128-bit accesses 16 lanes at a time out of 64 banks (256 bytes), so 16 consecutive
+    // pixels must land on 16 different 16-byte slots: pixel rows per 256 bytes of LDS.
+    constexpr int RP = Q4 >= 16 ? 1 : 16 / Q4;
     constexpr int KWM = KW > 0 ? KW : 5;       // most taps along W
     constexpr int MAXS = ((TM + KWM - 1) * Q4 + 63) / 64 / NW + 1;   // slab loads per wave and chunk
     constexpr int MAXW = (KWM * CK * NB / 4 + 63) / 64 / NW + 1;     // weight loads per wave and chunk

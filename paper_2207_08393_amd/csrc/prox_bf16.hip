@@ -61,7 +61,8 @@ size_t conv_bf16_wimg_elems(int K, int Nn, int taps) {
 template <int NB, int KW, bool RELU, int PJ>
 __global__ __launch_bounds__(256, 2) void conv_bf16_kernel(ConvBf16Args a) {
     constexpr int NW = 4, TM = NW * 32 * PJ, G = kBfCK / 16, NJ = NB / 32, QP = kBfCK / 8;   // QP quads per pixel row
-    constexpr int RP = 8 / QP;                 // pixel rows per 128 bytes of LDS (QP = 4 -> 2)
+    constexpr int RP = 16 / QP;                // pixel rows per 256 bytes of LDS: 16 consecutive pixels (the lanes one
+                                               // 128-bit LDS access serves together) land on 16 different 16-byte slots
     constexpr int KWM = KW > 0 ? KW : 5;
     constexpr int kSlabOpsMax = ((TM + KWM - 1) * QP + 63) / 64, kWOpsMax = (KWM * kBfCK * NB / 8 + 63) / 64;
     constexpr int MAXS = kSlabOpsMax / NW + 1, MAXW = kWOpsMax / NW + 1;
