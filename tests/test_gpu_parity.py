@@ -389,3 +389,28 @@ def test_step_size_gradient_matches_oracle(name, geom, prox, loss_kind):
     errs = (rel_l2(grad, g_ref), abs(g_alpha - ga_ref) / abs(ga_ref))
     print("case alpha", name, "rel errors grad_theta / grad_alpha:", errs, "grad_alpha", ga_ref, flush=True)
     assert errs[0] <= tol and errs[1] <= tol
+
+
+def test_direct_kernels_still_cover_the_winograd_shapes():
+    """GLEAM_NO_WINOGRAD=1 (read once per process) routes the 64-channel 3x3 layers through the direct MFMA
+    kernels; a fresh interpreter runs one module step that way and checks it against the oracle."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import numpy as np\n"
+        "from oracle import gleam_oracle as og\n"
+        "from paper_2207_08393_amd import synth\n"
+        "from paper_2207_08393_amd.runner import ModuleRunner\n"
+        "c = synth.make_custom(31, synth.Geom(2, 1, 2, 1, 1, 24, 46), synth.resblock_prox(64, 1), accel=2.0, centre=2, bias_std=0.1, alpha=0.8)\n"
+        "r = ModuleRunner(c, alpha=0.8); r.step(); x, loss, grad = r.results()\n"
+        "f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, c.theta, c.x_true); g = og.module_bwd(c.prox, c.theta, f)\n"
+        "rel = lambda a, b: float(np.linalg.norm(np.asarray(a, np.complex128) - b) / np.linalg.norm(b))\n"
+        "e = (rel(x, f['x_out']), abs(loss - f['loss']) / abs(f['loss']), rel(grad, g))\n"
+        "print('direct-kernel rel errors', e)\n"
+        "assert max(e) <= 1e-4, e\n")
+    env = dict(os.environ, GLEAM_NO_WINOGRAD="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
+    print(out.stdout, out.stderr[-2000:], flush=True)
+    assert out.returncode == 0
