@@ -85,10 +85,12 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int s = tid + i * 256;
-        const int rq = s / 34, rem = s - rq * 34;
-        s_col[i] = rem < 17 ? 2 * rem : 2 * (rem - 17) + 1;   // even columns first, then odd ones
-        s_row[i] = s < 408 ? (rq >> 1) : -100000;            // slots past the region always read the zero quad
-        s_quad[i] = rq & 1;
+        // slot = ((row*2 + column parity)*17 + column/2)*2 + quad: the two quads of a pixel are neighbouring lanes
+        // (one 32-byte request), even columns before odd ones
+        const int rp = s / 34, rem = s - rp * 34;
+        s_col[i] = 2 * (rem >> 1) + (rp & 1);
+        s_row[i] = s < 408 ? (rp >> 1) : -100000;            // slots past the region always read the zero quad
+        s_quad[i] = rem & 1;
     }
     struct Block {
         int x0, y0;
@@ -136,8 +138,8 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
     const float sg = xi == 1 ? 1.f : -1.f;
     // Region quad (row, channel quad, column) sits at slot (row*2 + quad)*34 + (column & 1)*17 + column/2: the 16
     // tiles of a row then read 16 neighbouring slots for each of their four columns (no bank conflicts).
-    const int offA = (((2 * trl + ra) * 2 + h) * 34 + tc) * 4;
-    const int offB = (((2 * trl + rb) * 2 + h) * 34 + tc) * 4;
+    const int offA = (((2 * trl + ra) * 2) * 17 + tc) * 8 + 4 * h;
+    const int offB = (((2 * trl + rb) * 2) * 17 + tc) * 8 + 4 * h;
     // U quad (position, channel quad hq, output channel n) at slot ((pos*2 + hq)*64 + n)
     const int offU = kWRawSlots * 4 + (((xi * 4) * 2 + h) * 64 + m) * 4;
 
@@ -148,8 +150,8 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
         float4 t[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            float4 da = *reinterpret_cast<const float4*>(buf + offA + ((c & 1) * 17 + (c >> 1)) * 4);
-            float4 db = *reinterpret_cast<const float4*>(buf + offB + ((c & 1) * 17 + (c >> 1)) * 4);
+            float4 da = *reinterpret_cast<const float4*>(buf + offA + ((c & 1) * 17 + (c >> 1)) * 8);
+            float4 db = *reinterpret_cast<const float4*>(buf + offB + ((c & 1) * 17 + (c >> 1)) * 8);
             if (RELU) {
                 da = relu4(da);
                 db = relu4(db);
