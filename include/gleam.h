@@ -44,7 +44,7 @@ typedef struct { float re, im; } gleam_c64;
 typedef enum {
     GLEAM_OK = 0,
     GLEAM_E_NULL = -1,              /* a required pointer is NULL                                      */
-    GLEAM_E_DIMS = -2,              /* non-positive or inconsistent dimension, ndim_fft not 2 or 3     */
+    GLEAM_E_DIMS = -2,              /* non-positive or inconsistent dimension, ndim_fft not 1, 2 or 3  */
     GLEAM_E_UNSUPPORTED_SIZE = -3,  /* a transformed length has no kernel (see gleam_fft_size_supported) */
     GLEAM_E_WORKSPACE = -4,         /* ws / saved too small or misaligned                              */
     GLEAM_E_DESC = -5,              /* prox description is not a valid / supported network             */
@@ -52,7 +52,11 @@ typedef enum {
 } gleam_status;
 
 /* Problem geometry.  ndim_fft = 2 transforms (H, W) and batches over D; ndim_fft = 3 transforms (D, H, W).
- * T counts temporal frames that are never transformed (2D+t cine); D = 1 and T = 1 for plain 2D. */
+ * T counts temporal frames that are never transformed (2D+t cine); D = 1 and T = 1 for plain 2D.
+ * ndim_fft = 1 transforms W only and batches over D and H: the form a problem takes when its mask does not
+ * depend on an axis (line masks of 2D Cartesian sampling, a fully sampled read-out), after the caller has
+ * inverse-transformed the measured k-space along that axis once; the whole operator then runs in a single
+ * sweep without the k-space buffer.  Every entry point accepts it. */
 typedef struct {
     int32_t ndim_fft;
     int64_t B, C, T, D, H, W;

@@ -45,7 +45,7 @@ inline bool aligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) % kA
 
 int check_geom(const gleam_geom* g) {
     if (!g) return GLEAM_E_NULL;
-    if (g->ndim_fft != 2 && g->ndim_fft != 3) return GLEAM_E_DIMS;
+    if (g->ndim_fft < 1 || g->ndim_fft > 3) return GLEAM_E_DIMS;
     if (g->B < 1 || g->C < 1 || g->T < 1 || g->D < 1 || g->H < 1 || g->W < 1) return GLEAM_E_DIMS;
     const long long lim = 1LL << 40;  // keeps every byte offset far inside int64
     long long e = 1;
@@ -53,7 +53,8 @@ int check_geom(const gleam_geom* g) {
         if (v > lim / e) return GLEAM_E_DIMS;
         e *= v;
     }
-    if (!fft_size_supported(g->W) || !fft_size_supported(g->H)) return GLEAM_E_UNSUPPORTED_SIZE;
+    if (!fft_size_supported(g->W)) return GLEAM_E_UNSUPPORTED_SIZE;
+    if (g->ndim_fft >= 2 && !fft_size_supported(g->H)) return GLEAM_E_UNSUPPORTED_SIZE;
     if (g->ndim_fft == 3 && !fft_size_supported(g->D)) return GLEAM_E_UNSUPPORTED_SIZE;
     return GLEAM_OK;
 }

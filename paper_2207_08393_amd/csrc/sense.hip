@@ -198,6 +198,116 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsAr
     }
 }
 
+// One transformed axis only (ndim_fft = 1: the mask does not depend on the other image axes, e.g. line masks of
+// 2D Cartesian sampling after the transform along the fully sampled axis has been taken out of the data): the
+// whole operator in one sweep, nothing but S, x, y and the mask is read and only the image is written.  A tile is
+// LR image rows x CG coils as in rows_reduce_kernel; per coil group: S*x -> forward transform ->
+// mask ? k - y : 0 -> inverse transform -> accumulate conj(S)*row.
+template <int N>
+__global__ __launch_bounds__(reduce_threads<N>()) void rows_fused_kernel(RowsArgs a, const float2* __restrict__ y,
+                                                                         const unsigned char* __restrict__ M) {
+    constexpr int L = reduce_lines<N>(), NT = reduce_threads<N>(), H2 = N / 2;
+    constexpr int PER = (H2 * L + NT - 1) / NT;
+    using Lay = Layout<N, L, 1>;
+    __shared__ float2 buf[Lay::kElems], tw[N];
+    __shared__ long long koff[L], soff[L], xoff[L];   // per image row of the tile: k-space (coil 0), coil map (coil 0), image
+    fill_twiddles<N, NT>(tw);
+    const int CG = a.C < L ? (int)a.C : L;
+    const int LR = L / CG;
+    const long long n_tiles = (a.n_rows + LR - 1) / LR;
+    const long long kstride = a.T * a.DH * N, sstride = a.DH * N;
+    for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        __syncthreads();
+        if (threadIdx.x < LR) {
+            const long long row = tile * LR + threadIdx.x;   // image row (b, t, dh)
+            long long ko = -1, so = -1, xo = -1;
+            if (row < a.n_rows) {
+                const long long dh = row % a.DH;
+                const long long bt = row / a.DH;
+                const long long t = bt % a.T, b = bt / a.T;
+                ko = (((b * a.C) * a.T + t) * a.DH + dh) * N;
+                so = ((b * a.C) * a.DH + dh) * N;
+                xo = row * N;
+            }
+            koff[threadIdx.x] = ko;
+            soff[threadIdx.x] = so;
+            xoff[threadIdx.x] = xo;
+        }
+        __syncthreads();
+        float4 acc[PER];
+#pragma unroll
+        for (int m = 0; m < PER; ++m) acc[m] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int c0 = 0; c0 < a.C; c0 += CG) {
+            const int ncg = a.C - c0 < CG ? (int)(a.C - c0) : CG;
+            // line l = r*CG + c holds coil c0 + c of image row r; unused lines are zero
+            for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
+                const int line = idx / H2, p = 2 * (idx % H2);
+                const int r = line / CG, c = line % CG;
+                float2 v0 = make_float2(0.f, 0.f), v1 = v0;
+                if (r < LR && c < ncg && xoff[r] >= 0) {
+                    const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[r] + (c0 + c) * sstride + p);
+                    const float4 xv = *reinterpret_cast<const float4*>(a.x + xoff[r] + p);
+                    v0 = cmul(make_float2(sv.x, sv.y), make_float2(xv.x, xv.y));
+                    v1 = cmul(make_float2(sv.z, sv.w), make_float2(xv.z, xv.w));
+                }
+                buf[Lay::at(line, p)] = v0;
+                buf[Lay::at(line, p + 1)] = v1;
+            }
+            __syncthreads();
+            fft_lines<N, L, 1, false, NT>(buf, tw);
+            for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
+                const int line = idx / H2, p = 2 * (idx % H2);
+                const int r = line / CG, c = line % CG;
+                if (r < LR && c < ncg && xoff[r] >= 0) {
+                    const unsigned short mm = *reinterpret_cast<const unsigned short*>(M + xoff[r] + p);
+                    float4 yv = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (y) yv = *reinterpret_cast<const float4*>(y + koff[r] + (c0 + c) * kstride + p);
+                    const float2 k0 = buf[Lay::at(line, p)], k1 = buf[Lay::at(line, p + 1)];
+                    buf[Lay::at(line, p)] = (mm & 0xff) ? make_float2(k0.x * a.scale - yv.x, k0.y * a.scale - yv.y) : make_float2(0.f, 0.f);
+                    buf[Lay::at(line, p + 1)] = (mm >> 8) ? make_float2(k1.x * a.scale - yv.z, k1.y * a.scale - yv.w) : make_float2(0.f, 0.f);
+                }
+            }
+            __syncthreads();
+            fft_lines<N, L, 1, true, NT>(buf, tw);
+#pragma unroll
+            for (int m = 0; m < PER; ++m) {
+                const int e = threadIdx.x + m * NT;      // pair index over LR rows
+                if (e < H2 * LR) {
+                    const int r = e / H2, p = 2 * (e % H2);
+                    if (xoff[r] >= 0) {
+                        for (int c = 0; c < ncg; ++c) {
+                            const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[r] + (c0 + c) * sstride + p);
+                            const float2 v0 = buf[Lay::at(r * CG + c, p)], v1 = buf[Lay::at(r * CG + c, p + 1)];
+                            const float2 p0 = cmul_conj(v0, make_float2(sv.x, sv.y));
+                            const float2 p1 = cmul_conj(v1, make_float2(sv.z, sv.w));
+                            acc[m].x += p0.x; acc[m].y += p0.y; acc[m].z += p1.x; acc[m].w += p1.y;
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        const float gsc = a.gs * a.scale;
+#pragma unroll
+        for (int m = 0; m < PER; ++m) {
+            const int e = threadIdx.x + m * NT;
+            if (e < H2 * LR) {
+                const int r = e / H2, p = 2 * (e % H2);
+                if (xoff[r] >= 0) {
+                    const long long o = xoff[r] + p;
+                    float4 res = make_float4(gsc * acc[m].x, gsc * acc[m].y, gsc * acc[m].z, gsc * acc[m].w);
+                    if (a.xs != 0.f) {
+                        const float4 xv = *reinterpret_cast<const float4*>(a.x + o);
+                        res.x = fmaf(a.xs, xv.x, res.x); res.y = fmaf(a.xs, xv.y, res.y);
+                        res.z = fmaf(a.xs, xv.z, res.z); res.w = fmaf(a.xs, xv.w, res.w);
+                    }
+                    *reinterpret_cast<float4*>(a.out + o) = res;
+                }
+            }
+        }
+    }
+}
+
 struct ColsArgs {
     float2* k;             // k-space viewed as [outer][N][inner], transformed in place along N
     const float2* y;       // measured k-space, same view (mid only; may be null)
@@ -348,6 +458,24 @@ static hipError_t launch_rows(bool reduce, int N, const RowsArgs& a, hipStream_t
     return hipGetLastError();
 }
 
+static hipError_t launch_rows_fused(int N, const RowsArgs& a, const float2* y, const unsigned char* M, hipStream_t st) {
+    switch (N) {
+#define X(NN)                                                                                          \
+    case NN: {                                                                                         \
+        constexpr int LR_ = reduce_lines<NN>();                                                        \
+        const int cg = a.C < LR_ ? (int)a.C : LR_;                                                     \
+        const long long per = LR_ / cg;                                                                \
+        const long long tiles = (a.n_rows + per - 1) / per;                                            \
+        hipLaunchKernelGGL(rows_fused_kernel<NN>, dim3(grid_for(tiles)), dim3(reduce_threads<NN>()), 0, st, a, y, M); \
+        break;                                                                                         \
+    }
+        GLEAM_FFT_SIZES(X)
+#undef X
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 static hipError_t launch_cols(int mode, int N, const ColsArgs& a, hipStream_t st) {
     switch (N) {
 #define X(NN)                                                                                          \
@@ -379,6 +507,11 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
     const double P8 = 8.0 * (double)(g.B * g.T * g.D * g.H * g.W);          // bytes of one image
     const double S8 = E8 / (double)g.T, M1 = P8 / 8.0;
     hipError_t e;
+    if (g.ndim_fft == 1) {   // one transformed axis: the whole operator in one sweep, no k-space buffer
+        ra.n_rows = g.B * g.T * DH;
+        KernelScope ks("sense_rows_fused", 0.0, S8 + P8 + (y ? E8 : 0.0) + M1 + P8 + (xs != 0.f ? P8 : 0.0), st);
+        return launch_rows_fused((int)g.W, ra, y, M, st);
+    }
     {
         KernelScope ks("sense_rows_expand", 0.0, S8 + P8 + E8, st);
         e = launch_rows(false, (int)g.W, ra, st);

@@ -48,7 +48,7 @@ def _status(fn, *a):
 
 def test_bad_geometry_and_sizes_are_rejected():
     good = synth.Geom(2, 1, 2, 1, 1, 8, 8)
-    for field, val, code in (("ndim_fft", 1, gb.GLEAM_E_DIMS), ("ndim_fft", 4, gb.GLEAM_E_DIMS),
+    for field, val, code in (("ndim_fft", 0, gb.GLEAM_E_DIMS), ("ndim_fft", 4, gb.GLEAM_E_DIMS),
                              ("B", 0, gb.GLEAM_E_DIMS), ("C", -1, gb.GLEAM_E_DIMS),
                              ("W", 7, gb.GLEAM_E_UNSUPPORTED_SIZE), ("H", 9, gb.GLEAM_E_UNSUPPORTED_SIZE)):
         g = synth.Geom(**{**good.__dict__, field: val})
@@ -269,3 +269,15 @@ def test_step_size_gradient_entry_point_rejects_bad_arguments_before_launch():
     p = gb.make_prox(relu_first)
     a = list(args); a[1] = C.byref(p)
     assert L.gleam_module_bwd_alpha(*a) == gb.GLEAM_E_DESC
+
+
+def test_single_axis_geometry_is_accepted_and_needs_only_w_to_have_a_transform():
+    prox = gb.make_prox(synth.resblock_prox(4, 1))
+    g = gb.make_geom(synth.Geom(1, 1, 2, 1, 3, 7, 64))            # H = 7 has no transform kernel, and needs none
+    ws, saved = gb.gleam_workspace_bytes(g, prox)
+    assert ws > 0 and saved > 0
+    w, s_ = C.c_size_t(0), C.c_size_t(0)
+    bad = gb.make_geom(synth.Geom(1, 1, 2, 1, 1, 8, 7))
+    assert gb.lib().gleam_workspace_bytes(C.byref(bad), C.byref(prox), C.byref(w), C.byref(s_)) == gb.GLEAM_E_UNSUPPORTED_SIZE
+    bad = gb.make_geom(synth.Geom(0, 1, 2, 1, 1, 8, 8))
+    assert gb.lib().gleam_workspace_bytes(C.byref(bad), C.byref(prox), C.byref(w), C.byref(s_)) == gb.GLEAM_E_DIMS

@@ -29,6 +29,11 @@ SENSE_SHAPES = [
     (3, 1, 3, 2, 16, 20, 6, "random2d"),
     (2, 1, 2, 1, 1, 160, 192, "vd"),
     (2, 1, 1, 1, 1, 256, 320, "vd"),
+    # one transformed axis (single-sweep kernel): H and D are batch axes, any size
+    (1, 2, 3, 2, 1, 7, 12, "uniform"),
+    (1, 1, 15, 1, 1, 5, 368, "vd"),         # more coils than lines in a tile: coil groups
+    (1, 1, 4, 1, 3, 9, 64, "random2d"),     # a mask that does vary along H and D is still a valid 1D problem
+    (1, 1, 2, 1, 1, 33, 640, "vd"),
 ]
 
 
@@ -414,3 +419,22 @@ def test_direct_kernels_still_cover_the_winograd_shapes():
     out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
     print(out.stdout, out.stderr[-2000:], flush=True)
     assert out.returncode == 0
+
+
+# ----------------------------------------------------------------------------- one transformed axis
+def test_single_axis_module_matches_oracle_and_the_2d_problem():
+    """ndim_fft = 1: module step against the oracle, and the same 2D problem (line mask, constant along H) solved
+    through the 2D path gives the same data-consistency step when its k-space is taken to hybrid space first."""
+    prox = synth.resblock_prox(8, 1)
+    c2 = synth.make_custom(81, synth.Geom(2, 2, 3, 1, 1, 12, 20), prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.7)
+    assert np.all(c2.M == c2.M[..., :1, :])
+    y_hyb = og.dft_axis(c2.y.astype(np.complex128), axis=c2.y.ndim - 2, inverse=True).astype(np.complex64)
+    g1 = synth.Geom(1, 2, 3, 1, 1, 12, 20)
+    c1 = synth.Case(**{**c2.__dict__, "geom": g1, "y": y_hyb})
+    print("case single axis", flush=True)
+    r1, f1 = check_module(c1, alpha=0.7)
+    r2 = ModuleRunner(c2, alpha=0.7)
+    r2.step()
+    x1, l1, gr1 = r1.results()
+    x2, l2, gr2 = r2.results()
+    assert rel_l2(x1, x2) <= TOL and abs(l1 - l2) <= TOL * abs(l2) and rel_l2(gr1, gr2) <= TOL

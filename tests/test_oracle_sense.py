@@ -210,3 +210,21 @@ def test_generator_mask_counts_all_configs():
     assert len(g._draw_lines(rng, 160, 13, 8, "vd")) == 13
     plane = g.poisson_disc_plane(rng, 40, 40, 200, 6)
     assert plane.sum() == 200 and plane[np.ix_(g.lowest_freq_indices(40, 6), g.lowest_freq_indices(40, 6))].all()
+
+
+def test_mask_constant_along_an_axis_reduces_the_transform_dimension():
+    """A mask that does not depend on H commutes with the transform along H, so the 2D operator on (x, y) equals
+    the 1D operator (W only, H as a batch axis) on y inverse-transformed along H: the identity behind
+    ndim_fft = 1 (and behind decoupling a fully sampled read-out)."""
+    from paper_2207_08393_amd import synth
+    c = synth.make_custom(5, synth.Geom(2, 2, 3, 1, 1, 6, 8), synth.resblock_prox(2, 1), accel=2.0, centre=2)
+    assert np.all(c.M == c.M[..., :1, :])                         # 1D line mask: constant along H
+    x = c.x_in.astype(np.complex128)
+    y = c.y.astype(np.complex128)
+    y_hyb = og.dft_axis(y, axis=y.ndim - 2, inverse=True)         # k-space -> (h, kw) hybrid space
+    assert np.allclose(og.sense_normal(x, c.S, c.M, 2), og.sense_normal(x, c.S, c.M, 1), atol=1e-12)
+    assert np.allclose(og.dc_step(x, c.S, c.M, y, 0.7, 2), og.dc_step(x, c.S, c.M, y_hyb, 0.7, 1), atol=1e-12)
+    # and a mask that does depend on H breaks it
+    M2 = c.M.copy()
+    M2[..., 0, :] = 1 - M2[..., 0, :]
+    assert not np.allclose(og.sense_normal(x, c.S, M2, 2), og.sense_normal(x, c.S, M2, 1), atol=1e-6)
