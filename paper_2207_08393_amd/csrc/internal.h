@@ -49,6 +49,7 @@ struct ProxPlan {
     size_t partial_off, partial_bytes;
     size_t bias_partial_off;          // [n_split][kMaxChannels] floats
     size_t wimg_off_fwd, wimg_off_bwd;  // re-laid weights of the layer being run (inside ws)
+    size_t wino_u_off;                  // behind either of them: transformed weights of all Winograd layers of the pass
     size_t red_off;                   // loss partial sums (doubles)
     size_t k_bytes;                   // coil k-space buffer at the head of ws (forward)
     size_t ws_bytes;

@@ -1068,7 +1068,7 @@ static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw,
     return hipGetLastError();
 }
 
-static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scratch, hipStream_t st) {
+static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scratch, hipStream_t st, const float* wino_u = nullptr) {
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
     {   // two input channels and a wide output: HBM-bound kernel without MFMA
         bool hit = false;
@@ -1087,7 +1087,7 @@ static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scrat
         wa.H = a.d.H; wa.W = a.d.W; wa.NI = a.d.Q / ((long long)a.d.H * a.d.W);
         char name[56];
         snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
-        return launch_conv_wino(wa, cw.w, cw.sn, cw.st, cw.sk, a.flip, a.relu_in, wt_scratch, name, st);
+        return launch_conv_wino(wa, cw.w, cw.sn, cw.st, cw.sk, a.flip, a.relu_in, wt_scratch, wino_u, name, st);
     }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
     {
@@ -1855,7 +1855,19 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
             max_img = bb > max_img ? bb : max_img;
         }
     }
-    const size_t img_bytes = align256(max_img * sizeof(float));
+    // behind the per-layer scratch: the transformed weights of all Winograd layers of one pass, made in one launch
+    size_t wino_floats = 0;
+    if (p.dtype == 0)
+        for (int l = 0; l < L; ++l) {
+            const gleam_conv& c = p.layers[l];
+            PixDims dd{};
+            dd.T = (int)g.T; dd.D = (int)g.D; dd.H = (int)g.H; dd.W = (int)g.W;
+            dd.kt = c.kt; dd.kd = c.kd; dd.kh = c.kh; dd.kw = c.kw;
+            if (conv_wino_applies(dd, c.cin, c.cout) || conv_wino_applies(dd, c.cout, c.cin))
+                wino_floats += (conv_wino_weight_floats(c.cin, c.cout) + 63) / 64 * 64;
+        }
+    plan.wino_u_off = align256(max_img * sizeof(float));
+    const size_t img_bytes = plan.wino_u_off + align256(wino_floats * sizeof(float));
     plan.wimg_off_bwd = w;
     w += img_bytes;
     const size_t bwd_ws = w;
@@ -1873,6 +1885,20 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
                         unsigned char* act_base, const float2* x_ref, float2* x_out, float* loss, void* ws,
                         hipStream_t st) {
     const int L = p.n_layers;
+    const float* wino_u[kMaxLayers] = {};
+    if (p.dtype == 0 && wino_enabled()) {   // transformed weights of every Winograd layer, one launch
+        WinoWeightBatch wb{};
+        float* up = reinterpret_cast<float*>((unsigned char*)ws + plan.wimg_off_fwd + plan.wino_u_off);
+        for (int l = 0; l < L; ++l) {
+            const gleam_conv& c = p.layers[l];
+            if (!conv_wino_applies(pix_dims(g, c), c.cin, c.cout)) continue;
+            wb.job[wb.n++] = WinoWeightJob{theta + plan.w_off[l], (long long)(9 * c.cin), (long long)c.cin, 1, 0, c.cin, c.cout, up};
+            wino_u[l] = up;
+            up += (conv_wino_weight_floats(c.cin, c.cout) + 63) / 64 * 64;
+        }
+        const hipError_t e = wino_weights_batch(wb, st);
+        if (e != hipSuccess) return e;
+    }
     for (int l = 0; l < L; ++l) {
         const gleam_conv& c = p.layers[l];
         const size_t taps = (size_t)c.kt * c.kd * c.kh * c.kw;
@@ -1912,7 +1938,7 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
                                      reinterpret_cast<unsigned short*>((unsigned char*)ws + plan.wimg_off_fwd), st);
             }
         } else {
-            e = launch_conv(a, cw, reinterpret_cast<float*>((unsigned char*)ws + plan.wimg_off_fwd), st);
+            e = launch_conv(a, cw, reinterpret_cast<float*>((unsigned char*)ws + plan.wimg_off_fwd), st, wino_u[l]);
         }
         if (e != hipSuccess) return e;
     }
@@ -2090,6 +2116,21 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
     // pending[s]: layer (1-based) whose output gradient also flows into t_s through its skip, or 0
     int pending[kMaxLayers + 1] = {0};
 
+    const float* wino_u[kMaxLayers] = {};   // transformed (mirrored, transposed) weights of the data gradients, one launch
+    if (p.dtype == 0 && wino_enabled()) {
+        WinoWeightBatch wb{};
+        float* up = reinterpret_cast<float*>(wsb + plan.wimg_off_bwd + plan.wino_u_off);
+        for (int l = 2; l <= L; ++l) {   // the data gradient of layer l maps cout -> cin channels
+            const gleam_conv& c = p.layers[l - 1];
+            if (!conv_wino_applies(pix_dims(g, c), c.cout, c.cin)) continue;
+            wb.job[wb.n++] = WinoWeightJob{theta + plan.w_off[l - 1], 1, (long long)c.cin, (long long)(9 * c.cin), 1, c.cout, c.cin, up};
+            wino_u[l - 1] = up;
+            up += (conv_wino_weight_floats(c.cout, c.cin) + 63) / 64 * 64;
+        }
+        const hipError_t e = wino_weights_batch(wb, st);
+        if (e != hipSuccess) return e;
+    }
+
     for (int l = L; l >= 1; --l) {  // layer l maps t_{l-1} -> t_l
         const gleam_conv& c = p.layers[l - 1];
         const size_t taps = (size_t)c.kt * c.kd * c.kh * c.kw;
@@ -2231,7 +2272,7 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                 e = launch_conv_bf16(b, cw.w, cw.sn, cw.st, cw.sk, 1, reinterpret_cast<unsigned short*>(wsb + plan.wimg_off_bwd), st);
             }
         } else {
-            e = launch_conv(a, cw, reinterpret_cast<float*>(wsb + plan.wimg_off_bwd), st);
+            e = launch_conv(a, cw, reinterpret_cast<float*>(wsb + plan.wimg_off_bwd), st, wino_u[l - 1]);
         }
         if (e != hipSuccess) return e;
     }

@@ -165,8 +165,22 @@ struct WinoArgs {
 };
 bool conv_wino_applies(const PixDims& d, int K, int Nn);
 size_t conv_wino_weight_floats(int K, int Nn);
+// u_ready: transformed weights made earlier by wino_weights_batch (then w and the strides are not used);
+// otherwise they are made now, into u_scratch.
 hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st, long long sk, int flip, int relu_in,
-                            float* u_scratch, const char* name, hipStream_t stream);
+                            float* u_scratch, const float* u_ready, const char* name, hipStream_t stream);
+// Transformed weights of several layers in one launch (a launch costs more than the transform of one layer).
+struct WinoWeightJob {
+    const float* w;
+    long long sn, st, sk;
+    int flip, K, Nn;
+    float* u;          // conv_wino_weight_floats(K, Nn) floats
+};
+struct WinoWeightBatch {
+    int n;
+    WinoWeightJob job[kMaxLayers];
+};
+hipError_t wino_weights_batch(const WinoWeightBatch& b, hipStream_t stream);
 
 // Winograd weight gradient of a 3x3 layer, float32 (prox_wino.hip): partial sums of the 16 transformed
 // products per workgroup, then a fixed-order reduction and the back-transform to the nine taps.

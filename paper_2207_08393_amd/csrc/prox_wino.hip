@@ -300,8 +300,12 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
 // U = G g G^T for every (output channel n, input channel k), laid out as the kernel's LDS image:
 // u[((((ny*n_kc + kc)*16 + pos)*2 + hq)*64 + nn)*4 + kk], n = 64*ny + nn, k = 8*kc + 4*hq + kk, pos = 4*xi + nu; one zero
 // quad follows.  Source weight (n, tap, k) at w[n*sn + tapidx*st + k*sk], taps mirrored for the data gradient.
-__global__ __launch_bounds__(256) void wino_weights_kernel(const float* __restrict__ w, long long sn, long long st_, long long sk,
-                                                           int flip, int K, int Nn, float* __restrict__ u) {
+__global__ __launch_bounds__(256) void wino_weights_kernel(WinoWeightBatch b) {
+    const WinoWeightJob& jb = b.job[blockIdx.y];
+    const float* __restrict__ w = jb.w;
+    float* __restrict__ u = jb.u;
+    const long long sn = jb.sn, st_ = jb.st, sk = jb.sk;
+    const int flip = jb.flip, K = jb.K, Nn = jb.Nn;
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx == 0) {
         float* z = u + (size_t)16 * K * Nn;
@@ -600,15 +604,32 @@ bool conv_wino_applies(const PixDims& d, int K, int Nn) {
 
 size_t conv_wino_weight_floats(int K, int Nn) { return (size_t)16 * K * Nn + 4; }
 
-hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st_, long long sk, int flip, int relu_in,
-                            float* u_scratch, const char* name, hipStream_t st) {
-    {
-        KernelScope ks("weights_image", 0.0, 4.0 * (double)(9 + 16) * a.K * a.Nn, st);
-        hipLaunchKernelGGL(wino_weights_kernel, dim3((unsigned)((a.K * a.Nn + 255) / 256)), dim3(256), 0, st, w, sn, st_, sk, flip,
-                           a.K, a.Nn, u_scratch);
+hipError_t wino_weights_batch(const WinoWeightBatch& b, hipStream_t st) {
+    if (b.n < 1) return hipSuccess;
+    int most = 0;
+    double bytes = 0.0;
+    for (int i = 0; i < b.n; ++i) {
+        const int kn = b.job[i].K * b.job[i].Nn;
+        most = kn > most ? kn : most;
+        bytes += 4.0 * (9 + 16) * kn;
     }
-    a.u = u_scratch;
-    a.zero = u_scratch + (size_t)16 * a.K * a.Nn;
+    KernelScope ks("weights_image", 0.0, bytes, st);
+    hipLaunchKernelGGL(wino_weights_kernel, dim3((unsigned)((most + 255) / 256), (unsigned)b.n), dim3(256), 0, st, b);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st_, long long sk, int flip, int relu_in,
+                            float* u_scratch, const float* u_ready, const char* name, hipStream_t st) {
+    if (!u_ready) {
+        WinoWeightBatch one{};
+        one.n = 1;
+        one.job[0] = WinoWeightJob{w, sn, st_, sk, flip, a.K, a.Nn, u_scratch};
+        const hipError_t e = wino_weights_batch(one, st);
+        if (e != hipSuccess) return e;
+        u_ready = u_scratch;
+    }
+    a.u = u_ready;
+    a.zero = u_ready + (size_t)16 * a.K * a.Nn;
     a.bx_n = (a.W + 31) / 32;
     a.by_n = (a.H + 3) / 4;
     a.n_blocks = a.NI * (long long)a.bx_n * a.by_n;
