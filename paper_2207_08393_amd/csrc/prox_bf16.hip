@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 
 #include <type_traits>
 
@@ -52,7 +53,7 @@ __global__ void weights_image_bf16_kernel(WimgBf16Args a) {
 static inline int bf_nb(int Nn) { return Nn <= 32 ? 32 : 64; }
 size_t conv_bf16_wimg_elems(int K, int Nn, int taps) {
     const int nb = bf_nb(Nn);
-    return (size_t)taps * ((K + kBfCK - 1) / kBfCK) * kBfCK * ((Nn + nb - 1) / nb) * nb;
+    return (size_t)taps * ((K + kBfCK - 1) / kBfCK) * kBfCK * ((Nn + nb - 1) / nb) * nb + 16;   // + a zero quad for the 2D kernel
 }
 
 // ------------------------------------------------------------------ forward / data gradient
@@ -316,9 +317,252 @@ static void launch_conv_bf16_k(const ConvBf16Args& a, hipStream_t st) {
     else hipLaunchKernelGGL((conv_bf16_kernel<NB, KW, false, PJ>), grid, dim3(256), 0, st, a);
 }
 
+// ------------------------------------------------------------------ 3x3 layers: two-dimensional tiles
+// Forward / data gradient of 3x3 layers in the plane with cin a multiple of 32 and cout a multiple of 64.  The
+// flattened-pixel kernel above re-reads the weights for every 128 pixels and every row tap's slab separately,
+// and stores 8-byte pieces 256 bytes apart; it spends more time waiting for staged data and on its stores than
+// on the MFMAs.  Here a workgroup of 4 waves owns 8 x 32 output pixels x 64 output channels: per 16-channel
+// chunk the raw 10 x 34 pixel region (zero outside the image, so no tap masks) and all nine taps' weights are
+// staged by direct loads (two buffers); a wave owns two image rows, reads the 4 x 3 pixel operands its nine
+// taps need once and feeds 36 MFMAs per chunk; the output goes through LDS so that the fused epilogue reads and
+// writes 64 contiguous bytes per pixel.  LDS layouts put the 16 lanes a 128-bit access serves together on 16
+// neighbouring 16-byte slots.  Two workgroups per CU.
+constexpr int kB2RegQuads = 704;      // 10 rows x 2 channel quads x 34 columns = 680, rounded up to whole wave loads
+constexpr int kB2WQuads = 9 * 2 * 64; // nine taps x 2 channel quads x 64 output channels
+constexpr int kB2BufQuads = kB2RegQuads + kB2WQuads;
+constexpr int kB2StageStride = 34;    // floats per staged output pixel: 32 channels + 2 (bank spread)
+
+// weights as LDS images: wt[((((ny*n_kc + kc)*9 + tap)*2 + hq)*64 + nn)*8 + kk], k = 16*kc + 8*hq + kk, n = 64*ny + nn;
+// one zero quad follows.  Source (n, tap, k) at w[n*sn + tapidx*st + k*sk], taps mirrored for the data gradient.
+__global__ __launch_bounds__(256) void weights_image_bf16_2d_kernel(const float* __restrict__ w, long long sn, long long st_, long long sk,
+                                                                    int flip, int K, int Nn, unsigned short* __restrict__ wt) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long total = 9LL * K * Nn;
+    if (i < 8) wt[total + i] = 0;
+    if (i >= total) return;
+    const int kk = (int)(i & 7), nn = (int)((i >> 3) & 63), hq = (int)((i >> 9) & 1);
+    const long long rest = i >> 10;
+    const int tap = (int)(rest % 9);
+    const long long ck = rest / 9;
+    const int n_kc = K / 16;
+    const int kc = (int)(ck % n_kc), ny = (int)(ck / n_kc);
+    const int k = 16 * kc + 8 * hq + kk, n = 64 * ny + nn;
+    wt[i] = f32_to_bf16(w[n * sn + (flip ? 8 - tap : tap) * st_ + k * sk]);
+}
+
+template <bool RELU>
+__global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, int bx_n, int by_n, long long n_blocks) {
+    __shared__ uint4 bufs[2 * kB2BufQuads];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    const int H = a.d.H, W = a.d.W;
+    const XcdRange xr = xcd_range(n_blocks);
+    if (xr.first >= xr.end) return;   // uniform for the workgroup
+    const int ny = blockIdx.y, n0 = 64 * ny, n_kc = a.K / 16;
+    const unsigned short* zero = a.wt + 9LL * a.K * a.Nn;
+
+    // direct-load slots of this lane: three quads of the region (slot = (row*2 + channel quad)*34 + column), five of
+    // the weights; the position of a quad inside the region does not depend on the block
+    int s_row[3], s_col[3], s_hq[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int s = tid + 256 * i;
+        const int rq = s / 34;
+        s_col[i] = s - rq * 34;
+        s_row[i] = s < 680 ? (rq >> 1) : -100000;   // slots past the region always read the zero quad
+        s_hq[i] = rq & 1;
+    }
+    struct Block {
+        int x0, y0;
+        long long img;
+        const unsigned short* gp[3];
+        int gstep[3];
+    };
+    auto setup = [&](long long item) {
+        Block b;
+        const int bx = (int)(item % bx_n);
+        const long long rest = item / bx_n;
+        const int by = (int)(rest % by_n);
+        b.img = rest / by_n;
+        b.x0 = bx * 32;
+        b.y0 = by * 8;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int yy = b.y0 - 1 + s_row[i], xx = b.x0 - 1 + s_col[i];
+            const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
+            b.gp[i] = ok ? a.in + ((b.img * H + yy) * W + xx) * a.K + 8 * s_hq[i] : zero;
+            b.gstep[i] = ok ? 16 : 0;
+        }
+        return b;
+    };
+    const unsigned short* wbase = a.wt + (size_t)ny * n_kc * (kB2WQuads * 8) + tid * 8;
+    auto issue = [&](const Block& b, int kc, uint4* dst) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int o = wave + 4 * i;
+            if (o < kB2RegQuads / 64)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b.gp[i] + kc * b.gstep[i]),
+                                                 (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            const int o = wave + 4 * i;
+            if (o < kB2WQuads / 64)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wbase + (size_t)kc * (kB2WQuads * 8) + i * 2048),
+                                                 (__attribute__((address_space(3))) void*)(dst + kB2RegQuads + o * 64), 16, 0, 0);
+        }
+    };
+
+    // this lane's operands: pixel (region row 2*wave + r, column m + dx), channel quad h; weights (tap, quad h, cout m + 32 j)
+    const int pb0 = ((2 * wave) * 2 + h) * 34 + m;
+    const int wa0 = kB2RegQuads + h * 64 + m;
+
+    floatx16 acc[2][2];   // [image row of the wave][cout block]
+    auto compute = [&](int boff) {
+        const uint4* buf = bufs + boff;
+        bf16x8 pv[4][3];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int dx = 0; dx < 3; ++dx) {
+                uint4 pb = buf[pb0 + r * 68 + dx];
+                if (RELU) {
+                    pb.x = relu_bf16x2(pb.x); pb.y = relu_bf16x2(pb.y); pb.z = relu_bf16x2(pb.z); pb.w = relu_bf16x2(pb.w);
+                }
+                pv[r][dx] = __builtin_bit_cast(bf16x8, pb);
+            }
+#pragma unroll
+        for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < 3; ++dx) {
+                const bf16x8 w0 = __builtin_bit_cast(bf16x8, buf[wa0 + (dy * 3 + dx) * 128]);
+                const bf16x8 w1 = __builtin_bit_cast(bf16x8, buf[wa0 + (dy * 3 + dx) * 128 + 32]);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, pv[dy][dx], acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, pv[dy][dx], acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, pv[dy + 1][dx], acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, pv[dy + 1][dx], acc[1][1], 0, 0, 0);
+            }
+    };
+
+    // epilogue constants: a thread finishes 4 output channels (one 8-byte bf16 piece) of 4 pixels per pass
+    const int e_piece = tid & 7;
+    Block cur = setup(xr.first);
+    issue(cur, 0, bufs);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (long long item = xr.first; item < xr.end; item += xr.stride) {
+        const bool has_next = item + xr.stride < xr.end;
+        const Block nxt = setup(has_next ? item + xr.stride : item);
+#pragma unroll
+        for (int pj = 0; pj < 2; ++pj)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
+        for (int kc = 0; kc < n_kc; ++kc) {
+            // the first chunk of the next block is fetched under the last MFMAs of this one
+            if (kc + 1 < n_kc) issue(cur, kc + 1, bufs + ((kc + 1) & 1) * kB2BufQuads);
+            else if (has_next) issue(nxt, 0, bufs + ((kc + 1) & 1) * kB2BufQuads);
+            __builtin_amdgcn_sched_barrier(0);
+            compute((kc & 1) * kB2BufQuads);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+        }
+        // Output through LDS, one pass per (image row of the wave, cout block): float32 [128 pixels][32 channels],
+        // then bias / ReLU / ReLU mask / add and 8-byte stores that are contiguous per pixel.  The staging area is
+        // the chunk buffer that the prefetch of the next block does not use.
+        float* stage = reinterpret_cast<float*>(bufs + kB2BufQuads);   // n_kc is even: the prefetch went into the first buffer
+#pragma unroll
+        for (int pj = 0; pj < 2; ++pj)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg)
+                    *reinterpret_cast<float4*>(stage + (wave * 32 + m) * kB2StageStride + 8 * rg + 4 * h) =
+                        make_float4(acc[pj][j][4 * rg], acc[pj][j][4 * rg + 1], acc[pj][j][4 * rg + 2], acc[pj][j][4 * rg + 3]);
+                __syncthreads();
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int px = (tid >> 3) + 32 * it;          // 0..127: wave row px>>5, column px&31
+                    const int y = cur.y0 + 2 * (px >> 5) + pj, x = cur.x0 + (px & 31);
+                    const float4 v4 = *reinterpret_cast<const float4*>(stage + px * kB2StageStride + 4 * e_piece);
+                    if (y < H && x < W) {
+                        const int co = n0 + 32 * j + 4 * e_piece;
+                        const long long o = ((cur.img * H + y) * W + x) * a.Nn + co;
+                        float xv[4] = {v4.x, v4.y, v4.z, v4.w};
+                        if (a.bias) {
+                            const float4 bv = *reinterpret_cast<const float4*>(a.bias + co);
+                            xv[0] += bv.x; xv[1] += bv.y; xv[2] += bv.z; xv[3] += bv.w;
+                        }
+                        if (a.relu_out) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) xv[e] = fmaxf(xv[e], 0.f);
+                        }
+                        uint2 rf = make_uint2(0x3f803f80u, 0x3f803f80u);   // 1.0 in every half
+                        if (a.mask_ref) rf = *reinterpret_cast<const uint2*>(a.mask_ref + o);
+                        const float ref[4] = {bf16_to_f32((unsigned short)rf.x), bf16_to_f32((unsigned short)(rf.x >> 16)),
+                                              bf16_to_f32((unsigned short)rf.y), bf16_to_f32((unsigned short)(rf.y >> 16))};
+                        if (a.mask_acc) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) xv[e] = ref[e] > 0.f ? xv[e] : 0.f;
+                        }
+                        if (a.add) {
+                            const uint2 av = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned short*>(a.add) + o);
+                            const float ad[4] = {bf16_to_f32((unsigned short)av.x), bf16_to_f32((unsigned short)(av.x >> 16)),
+                                                 bf16_to_f32((unsigned short)av.y), bf16_to_f32((unsigned short)(av.y >> 16))};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) xv[e] += (a.mask_add && !(ref[e] > 0.f)) ? 0.f : ad[e];
+                        }
+                        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.out) + o) =
+                            make_uint2(pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]));
+                    }
+                }
+                __syncthreads();
+            }
+        cur = nxt;
+    }
+}
+
+static bool conv_bf16_2d_applies(const ConvBf16Args& a) {
+    return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && a.K % 32 == 0 && a.Nn % 64 == 0 && !a.out_f32;   // an even number of 16-channel chunks
+}
+
+static hipError_t launch_conv_bf16_2d(ConvBf16Args a, const float* w, long long sn, long long st_, long long sk, int flip,
+                                      unsigned short* wt_scratch, hipStream_t st) {
+    {
+        const long long total = 9LL * a.K * a.Nn;
+        KernelScope ks("weights_image_bf16", 0.0, 6.0 * (double)total, st);
+        hipLaunchKernelGGL(weights_image_bf16_2d_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w, sn, st_, sk, flip,
+                           a.K, a.Nn, wt_scratch);
+    }
+    a.wt = wt_scratch;
+    const int bx_n = (a.d.W + 31) / 32, by_n = (a.d.H + 7) / 8;
+    const long long n_img = a.d.Q / ((long long)a.d.H * a.d.W);
+    const long long n_blocks = n_img * bx_n * by_n;
+    const long long cap = 512 / (a.Nn / 64) > 8 ? 512 / (a.Nn / 64) : 8;   // two workgroups per CU in total
+    const long long gx = ((n_blocks < cap ? n_blocks : cap) + 7) / 8 * 8;
+    dim3 grid((unsigned)gx, (unsigned)(a.Nn / 64));
+    char name[56];
+    snprintf(name, sizeof(name), "conv_bf16_%s_%dto%d_t9", flip ? "dgrad" : "fwd", a.K, a.Nn);
+    KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * 9, 2.0 * (double)a.d.Q * (a.K + a.Nn), st);
+    if (a.relu_in) hipLaunchKernelGGL((conv_bf16_2d_kernel<true>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+    else hipLaunchKernelGGL((conv_bf16_2d_kernel<false>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+    return hipGetLastError();
+}
+
+static bool bf16_2d_enabled() {   // GLEAM_NO_BF16_2D=1 keeps the flattened-pixel kernel for comparison
+    static const bool on = [] {
+        const char* e = getenv("GLEAM_NO_BF16_2D");
+        return !(e && e[0] == '1');
+    }();
+    return on;
+}
+
 hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long sn, long long st_, long long sk, int flip,
                             unsigned short* wt_scratch, hipStream_t stream) {
     ConvBf16Args a = a_in;
+    if (bf16_2d_enabled() && conv_bf16_2d_applies(a)) return launch_conv_bf16_2d(a, w, sn, st_, sk, flip, wt_scratch, stream);
     const int taps = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
     const int nb = bf_nb(a.Nn);
     {
