@@ -10,6 +10,9 @@
 //                      partial sums reduced in a fixed order (deterministic).
 // Zero padding is a per-pixel 32-bit tap-validity mask, so pixel tiles are plain runs of the flattened
 // index and never ragged except at the very end of the tensor.
+// 3x3 layers in the plane whose channel counts are multiples of 64 take the Winograd F(2x2, 3x3) kernels of
+// prox_wino.hip instead (forward, data gradient and weight gradient); this file keeps the direct kernels for
+// every other shape, the two-channel first / last layers, the loss, the reductions and the host side.
 #include <hip/hip_runtime.h>
 
 #include <cmath>

@@ -6,6 +6,8 @@
 //   conv_bf16_kernel  : forward and data gradient, same scheme as the float32 direct-to-LDS kernel - two
 //                       LDS chunk buffers filled by global->LDS direct loads, XOR-swizzled 16-byte quads
 //                       (8 channels), 32 input channels per chunk (two MFMA K-blocks per tap).
+//   conv_bf16_2d_kernel : forward and data gradient of 3x3 layers on two-dimensional pixel tiles (zero-filled
+//                       halo instead of tap masks, all nine taps per chunk, output through LDS).
 //   wgrad_bf16_kernel : weight gradient; the contraction runs over pixels, so g and a are transposed into
 //                       LDS ([channel][pixel]) while they are staged and each lane reads its 8 pixels as
 //                       one 16-byte word; the three taps along W come from one 20-byte window by shifts.
