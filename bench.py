@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # profiles/module_step_knee2d_hbm_traffic.txt.  Scaling: the 256 MiB calibration copy reads 131 100 KiB on
 # FETCH_SIZE (factor 2.0: the counter under-reports 128-byte requests) and 262 144 KiB on WRITE_SIZE (1.0).
 MEASURED_TRAFFIC = {
-    "conv_wino_kernel<RELU> fwd+dgrad 64->64 3x3 (Winograd F(2x2,3x3))": 1.3876e5 * 1024 * 2.0 + 1.1776e5 * 1024 * 1.0,
+    "conv_wino_kernel<RELU> fwd+dgrad 64->64 3x3 (Winograd F(2x2,3x3))": 1.126e5 * 1024 * 2.0 + 1.192e5 * 1024 * 1.0,
     "wgrad_wino_kernel<RELU> wgrad 64->64 3x3 (Winograd F(2x2,3x3))": 1.18465e5 * 1024 * 2.0 + 6.56e4 * 1024 * 1.0,
 }
 

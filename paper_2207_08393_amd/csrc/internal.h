@@ -44,6 +44,7 @@ struct ProxPlan {
     long long Q;                      // pixels B*T*D*H*W
     size_t act_off[kMaxLayers + 1];   // t_l inside saved, l < L
     size_t gz_off;
+    size_t sign_off[kMaxLayers + 1];  // sign words of t_l inside saved, or 0 when there are none (see plan_prox)
     size_t saved_bytes;
     size_t grad_off[kMaxLayers + 1];  // G_l inside ws, 1 <= l < L
     size_t partial_off, partial_bytes;

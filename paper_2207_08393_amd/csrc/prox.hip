@@ -32,6 +32,8 @@ struct ConvArgs {
     const float* bias;      // [Nn] or null
     const float* mask_ref;  // [Q][Nn] or null: ReLU mask source (value > 0 passes)
     const float* add;       // [Q][Nn] or null: added to the result
+    const unsigned* bits_in;   // Winograd launches only, or null: sign words that stand in for mask_ref
+    unsigned* bits_out;        // Winograd launches only, or null: sign words of the output
     int K, Nn;              // input / output channels of this GEMM
     int flip;               // 1: data gradient (only used for naming)
     int relu_in, relu_out, mask_acc, mask_add;
@@ -984,15 +986,20 @@ static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, bool
     else hipLaunchKernelGGL((conv_thin_in_kernel<KT, KD, KH, KW, false>), grid, dim3(256), lds, st, t);
 }
 
+static bool conv_thin_in_applies(const PixDims& d, int K, int Nn) {
+    if (!(K == 2 && Nn >= 8 && Nn <= 256)) return false;
+    const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
+    const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
+    return k2 || k3 || kt3;
+}
+
 // Launches the two-channel-input kernel when the layer fits it; *hit tells whether it did.
 static hipError_t launch_conv_thin_in(const ConvArgs& a, const ConvWeights& cw, bool bf, bool* hit, hipStream_t st) {
     *hit = false;
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
-    if (!(a.K == 2 && a.Nn >= 8 && a.Nn <= 256)) return hipSuccess;
+    if (!conv_thin_in_applies(a.d, a.K, a.Nn)) return hipSuccess;
     const PixDims& d = a.d;
     const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
-    const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
-    if (!k2 && !k3 && !kt3) return hipSuccess;
     char name[56];
     snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
     KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, (bf ? 2.0 : 4.0) * (double)a.d.Q * a.Nn + 8.0 * (double)a.d.Q, st);
@@ -1086,6 +1093,7 @@ static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scrat
     if (wino_enabled() && conv_wino_applies(a.d, a.K, a.Nn)) {   // 3x3 in the plane: Winograd F(2x2, 3x3)
         WinoArgs wa{};
         wa.in = a.in; wa.out = a.out; wa.bias = a.bias; wa.mask_ref = a.mask_ref; wa.add = a.add;
+        wa.bits_in = a.bits_in; wa.bits_out = a.bits_out;
         wa.K = a.K; wa.Nn = a.Nn; wa.relu_out = a.relu_out; wa.mask_acc = a.mask_acc; wa.mask_add = a.mask_add;
         wa.H = a.d.H; wa.W = a.d.W; wa.NI = a.d.Q / ((long long)a.d.H * a.d.W);
         char name[56];
@@ -1813,6 +1821,24 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     }
     plan.gz_off = off;
     off += align256(Q * 2 * sizeof(float));
+    // ReLU masks as sign bits: where both the layer that produces t_l and the data gradient that flows back into
+    // it run on the Winograd kernel, the forward launch leaves one bit per value and the backward launch reads
+    // those (1/32 of the bytes of t_l)
+    for (int l = 0; l <= kMaxLayers; ++l) plan.sign_off[l] = 0;
+    if (p.dtype == 0)
+        for (int l = 1; l < L; ++l) {
+            const gleam_conv& below = p.layers[l - 1];
+            const gleam_conv& above = p.layers[l];
+            if (!(above.relu_in || below.relu_out)) continue;
+            PixDims db{}, da{};
+            db.T = da.T = (int)g.T; db.D = da.D = (int)g.D; db.H = da.H = (int)g.H; db.W = da.W = (int)g.W;
+            db.Q = da.Q = plan.Q;
+            db.kt = below.kt; db.kd = below.kd; db.kh = below.kh; db.kw = below.kw;
+            da.kt = above.kt; da.kd = above.kd; da.kh = above.kh; da.kw = above.kw;
+            if (!conv_wino_applies(db, below.cin, below.cout) || !conv_wino_applies(da, above.cout, above.cin)) continue;
+            plan.sign_off[l] = off;
+            off += align256(conv_wino_sign_words(db, below.cout) * sizeof(unsigned));
+        }
     plan.saved_bytes = off;
 
     // split-K: enough workgroups to fill the chip, never more than there are pixel chunks
@@ -1912,6 +1938,7 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
         a.bias = c.has_bias ? theta + plan.b_off[l] : nullptr;
         a.add = c.skip_src >= 0 ? reinterpret_cast<const float*>(act_base + plan.act_off[c.skip_src]) : nullptr;
         a.K = c.cin; a.Nn = c.cout;
+        if (wino_u[l] && l + 1 < L && plan.sign_off[l + 1]) a.bits_out = reinterpret_cast<unsigned*>(act_base + plan.sign_off[l + 1]);
         a.relu_in = (c.relu_in && !plan.post_relu[l]) ? 1 : 0;
         a.relu_out = (c.relu_out || (l + 1 < L && plan.post_relu[l + 1])) ? 1 : 0;
         a.d = pix_dims(g, c);
@@ -2257,6 +2284,8 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
         a.mask_add = below.relu_out ? 1 : 0;
         a.mask_ref = (a.mask_acc || a.mask_add) ? act(l - 1) : nullptr;
         a.add = pending[l - 1] ? G(pending[l - 1]) : nullptr;
+        if (p.dtype == 0 && wino_enabled() && a.mask_ref && plan.sign_off[l - 1])   // then the forward pass wrote them
+            a.bits_in = reinterpret_cast<const unsigned*>(saved + plan.sign_off[l - 1]);
         a.d = d;
         if (p.dtype == 1) {
             if (l == L) {           // float32 loss gradient in, bfloat16 gradient out

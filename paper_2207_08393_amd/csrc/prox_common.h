@@ -158,6 +158,8 @@ struct WinoArgs {
     const float* bias;      // [Nn] or null
     const float* mask_ref;  // [Q][Nn] or null: ReLU mask source (value > 0 passes)
     const float* add;       // [Q][Nn] or null
+    const unsigned* bits_in;   // or null: sign words of the mask source written by an earlier launch (replace mask_ref)
+    unsigned* bits_out;        // or null: sign words of this launch's output, conv_wino_sign_words() of them
     int K, Nn, relu_out, mask_acc, mask_add;
     long long NI;           // images (B*T*D)
     int H, W, bx_n, by_n;
@@ -165,6 +167,8 @@ struct WinoArgs {
 };
 bool conv_wino_applies(const PixDims& d, int K, int Nn);
 size_t conv_wino_weight_floats(int K, int Nn);
+// 32-bit words of the sign-bit image of a [pixels][Nn] tensor as the Winograd kernel's threads write and read it
+size_t conv_wino_sign_words(const PixDims& d, int Nn);
 // u_ready: transformed weights made earlier by wino_weights_batch (then w and the strides are not used);
 // otherwise they are made now, into u_scratch.
 hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st, long long sk, int flip, int relu_in,

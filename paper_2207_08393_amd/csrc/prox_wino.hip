@@ -239,6 +239,13 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
             okp[i][jj] = ey + i < a.H && ex_ + jj < a.W;
             op[i][jj] = okp[i][jj] ? ((img * a.H + ey + i) * a.W + ex_ + jj) * a.Nn + n0 + 4 * e_cq : (long long)(n0 + 4 * e_cq);
         }
+    // ReLU mask as sign bits: bit 16*jp + 4*(2*i + jj) + e of this thread's word says whether the value of pass jp,
+    // tile pixel (i, jj), channel e of its quad is positive.  The forward launch that produces an activation
+    // writes the words, the data-gradient launch into the same tensor (same geometry, hence the same thread for
+    // the same values) reads them instead of the activation itself.
+    const long long word_idx = ((long long)ny * a.n_blocks + item) * 256 + tid_b;
+    unsigned sign_in = 0u, sign_out = 0u;
+    if (a.bits_in) sign_in = a.bits_in[word_idx];
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) {
         if (jp) __syncthreads();
@@ -249,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
             for (int jj = 0; jj < 2; ++jj) {
                 refv[i][jj] = make_float4(1.f, 1.f, 1.f, 1.f);
                 addv[i][jj] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (a.mask_ref) refv[i][jj] = *reinterpret_cast<const float4*>(a.mask_ref + op[i][jj] + 32 * jp);
+                if (a.mask_ref && !a.bits_in) refv[i][jj] = *reinterpret_cast<const float4*>(a.mask_ref + op[i][jj] + 32 * jp);
                 if (a.add) addv[i][jj] = *reinterpret_cast<const float4*>(a.add + op[i][jj] + 32 * jp);
             }
 #pragma unroll
@@ -282,16 +289,25 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
                 }
                 const float rr[4] = {refv[i][jj].x, refv[i][jj].y, refv[i][jj].z, refv[i][jj].w};
                 const float aa[4] = {addv[i][jj].x, addv[i][jj].y, addv[i][jj].z, addv[i][jj].w};
+                const int bit0 = 16 * jp + 4 * (2 * i + jj);
+                bool pos[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pos[e] = a.bits_in ? ((sign_in >> (bit0 + e)) & 1u) != 0u : rr[e] > 0.f;
                 if (a.mask_acc) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = rr[e] > 0.f ? v[e] : 0.f;
+                    for (int e = 0; e < 4; ++e) v[e] = pos[e] ? v[e] : 0.f;
                 }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
+                for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !pos[e]) ? 0.f : aa[e];
+                if (a.bits_out) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sign_out |= (v[e] > 0.f ? 1u : 0u) << (bit0 + e);
+                }
                 if (okp[i][jj]) *reinterpret_cast<float4*>(a.out + op[i][jj] + 32 * jp) = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
     }
+    if (a.bits_out) a.bits_out[word_idx] = sign_out;
     __syncthreads();   // the exchange lived in the second chunk buffer, which the next block loads into first
     cur = nxt;
     }
@@ -603,6 +619,11 @@ bool conv_wino_applies(const PixDims& d, int K, int Nn) {
 }
 
 size_t conv_wino_weight_floats(int K, int Nn) { return (size_t)16 * K * Nn + 4; }
+
+size_t conv_wino_sign_words(const PixDims& d, int Nn) {   // one word per thread, block and group of 64 channels
+    const size_t n_img = (size_t)d.Q / ((size_t)d.H * d.W);
+    return n_img * ((d.W + 31) / 32) * ((d.H + 3) / 4) * 256 * (size_t)(Nn / 64);
+}
 
 hipError_t wino_weights_batch(const WinoWeightBatch& b, hipStream_t st) {
     if (b.n < 1) return hipSuccess;
