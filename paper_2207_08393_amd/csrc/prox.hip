@@ -1825,6 +1825,20 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
     // it run on the Winograd kernel, the forward launch leaves one bit per value and the backward launch reads
     // those (1/32 of the bytes of t_l)
     for (int l = 0; l <= kMaxLayers; ++l) plan.sign_off[l] = 0;
+    if (p.dtype == 1)   // the same between two launches of the two-dimensional-tile bfloat16 kernel
+        for (int l = 2; l + 1 < L; ++l) {   // t_1 comes from, and the gradient into t_{L-1} goes through, the thin kernels
+            const gleam_conv& below = p.layers[l - 1];
+            const gleam_conv& above = p.layers[l];
+            if (!(above.relu_in || below.relu_out)) continue;
+            PixDims db{}, da{};
+            db.T = da.T = (int)g.T; db.D = da.D = (int)g.D; db.H = da.H = (int)g.H; db.W = da.W = (int)g.W;
+            db.Q = da.Q = plan.Q;
+            db.kt = below.kt; db.kd = below.kd; db.kh = below.kh; db.kw = below.kw;
+            da.kt = above.kt; da.kd = above.kd; da.kh = above.kh; da.kw = above.kw;
+            if (!conv_bf16_takes_sign_words(db, below.cin, below.cout) || !conv_bf16_takes_sign_words(da, above.cout, above.cin)) continue;
+            plan.sign_off[l] = off;
+            off += align256(conv_bf16_sign_words(db, below.cout) * sizeof(unsigned));
+        }
     if (p.dtype == 0)
         for (int l = 1; l < L; ++l) {
             const gleam_conv& below = p.layers[l - 1];
@@ -1964,6 +1978,7 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
                 b.out_f32 = (l == L - 1) ? 1 : 0;
                 b.relu_in = a.relu_in; b.relu_out = a.relu_out;
                 b.d = a.d;
+                if (l + 1 < L && plan.sign_off[l + 1]) b.bits_out = reinterpret_cast<unsigned*>(act_base + plan.sign_off[l + 1]);
                 e = launch_conv_bf16(b, cw.w, cw.sn, cw.st, cw.sk, 0,
                                      reinterpret_cast<unsigned short*>((unsigned char*)ws + plan.wimg_off_fwd), st);
             }
@@ -2301,6 +2316,7 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                 b.K = a.K; b.Nn = a.Nn;
                 b.mask_acc = a.mask_acc; b.mask_add = a.mask_add;
                 b.d = d;
+                if (a.mask_ref && plan.sign_off[l - 1]) b.bits_in = reinterpret_cast<const unsigned*>(saved + plan.sign_off[l - 1]);
                 e = launch_conv_bf16(b, cw.w, cw.sn, cw.st, cw.sk, 1, reinterpret_cast<unsigned short*>(wsb + plan.wimg_off_bwd), st);
             }
         } else {

@@ -475,6 +475,14 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
         // then bias / ReLU / ReLU mask / add and 8-byte stores that are contiguous per pixel.  The staging area is
         // the chunk buffer that the prefetch of the next block does not use.
         float* stage = reinterpret_cast<float*>(bufs + kB2BufQuads);   // n_kc is even: the prefetch went into the first buffer
+        // ReLU mask as sign bits: bit 16*j + 4*it + e of this thread's word pj says whether the value of pass (pj, j),
+        // pixel `it`, channel e of its piece is positive.  The forward launch that produces an activation writes
+        // the words, the data-gradient launch into the same tensor (same geometry, so the same thread holds the
+        // same values) reads them instead of the activation.
+        const long long word_idx = (((long long)ny * n_blocks + item) * 256 + tid) * 2;
+        uint2 sign_in = make_uint2(0u, 0u);
+        unsigned sign_out[2] = {0u, 0u};
+        if (a.bits_in) sign_in = *reinterpret_cast<const uint2*>(a.bits_in + word_idx);
 #pragma unroll
         for (int pj = 0; pj < 2; ++pj)
 #pragma unroll
@@ -502,32 +510,62 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
                             for (int e = 0; e < 4; ++e) xv[e] = fmaxf(xv[e], 0.f);
                         }
                         uint2 rf = make_uint2(0x3f803f80u, 0x3f803f80u);   // 1.0 in every half
-                        if (a.mask_ref) rf = *reinterpret_cast<const uint2*>(a.mask_ref + o);
+                        if (a.mask_ref && !a.bits_in) rf = *reinterpret_cast<const uint2*>(a.mask_ref + o);
                         const float ref[4] = {bf16_to_f32((unsigned short)rf.x), bf16_to_f32((unsigned short)(rf.x >> 16)),
                                               bf16_to_f32((unsigned short)rf.y), bf16_to_f32((unsigned short)(rf.y >> 16))};
+                        const int bit0 = 16 * j + 4 * it;
+                        const unsigned sw = pj ? sign_in.y : sign_in.x;
+                        bool pos[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) pos[e] = a.bits_in ? ((sw >> (bit0 + e)) & 1u) != 0u : ref[e] > 0.f;
                         if (a.mask_acc) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) xv[e] = ref[e] > 0.f ? xv[e] : 0.f;
+                            for (int e = 0; e < 4; ++e) xv[e] = pos[e] ? xv[e] : 0.f;
                         }
                         if (a.add) {
                             const uint2 av = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned short*>(a.add) + o);
                             const float ad[4] = {bf16_to_f32((unsigned short)av.x), bf16_to_f32((unsigned short)(av.x >> 16)),
                                                  bf16_to_f32((unsigned short)av.y), bf16_to_f32((unsigned short)(av.y >> 16))};
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) xv[e] += (a.mask_add && !(ref[e] > 0.f)) ? 0.f : ad[e];
+                            for (int e = 0; e < 4; ++e) xv[e] += (a.mask_add && !pos[e]) ? 0.f : ad[e];
                         }
-                        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.out) + o) =
-                            make_uint2(pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]));
+                        const uint2 packed = make_uint2(pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]));
+                        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.out) + o) = packed;
+                        if (a.bits_out) {   // the sign of what was stored, i.e. of the rounded value: 0x0001 .. 0x7fff
+                            const unsigned hv[4] = {packed.x & 0xffffu, packed.x >> 16, packed.y & 0xffffu, packed.y >> 16};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) sign_out[pj] |= (hv[e] - 1u < 0x7fffu ? 1u : 0u) << (bit0 + e);
+                        }
                     }
                 }
                 __syncthreads();
             }
+        if (a.bits_out) *reinterpret_cast<uint2*>(a.bits_out + word_idx) = make_uint2(sign_out[0], sign_out[1]);
         cur = nxt;
     }
 }
 
 static bool conv_bf16_2d_applies(const ConvBf16Args& a) {
     return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && a.K % 32 == 0 && a.Nn % 64 == 0 && !a.out_f32;   // an even number of 16-channel chunks
+}
+
+static bool bf16_2d_enabled() {   // GLEAM_NO_BF16_2D=1 keeps the flattened-pixel kernel for comparison
+    static const bool on = [] {
+        const char* e = getenv("GLEAM_NO_BF16_2D");
+        return !(e && e[0] == '1');
+    }();
+    return on;
+}
+
+bool conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn) {
+    ConvBf16Args a{};
+    a.d = d; a.K = K; a.Nn = Nn;
+    return bf16_2d_enabled() && conv_bf16_2d_applies(a);
+}
+
+size_t conv_bf16_sign_words(const PixDims& d, int Nn) {   // two words per thread, block and group of 64 channels
+    const size_t n_img = (size_t)d.Q / ((size_t)d.H * d.W);
+    return n_img * ((d.W + 31) / 32) * ((d.H + 7) / 8) * 256 * 2 * (size_t)(Nn / 64);
 }
 
 static hipError_t launch_conv_bf16_2d(ConvBf16Args a, const float* w, long long sn, long long st_, long long sk, int flip,
@@ -551,14 +589,6 @@ static hipError_t launch_conv_bf16_2d(ConvBf16Args a, const float* w, long long 
     if (a.relu_in) hipLaunchKernelGGL((conv_bf16_2d_kernel<true>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
     else hipLaunchKernelGGL((conv_bf16_2d_kernel<false>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
     return hipGetLastError();
-}
-
-static bool bf16_2d_enabled() {   // GLEAM_NO_BF16_2D=1 keeps the flattened-pixel kernel for comparison
-    static const bool on = [] {
-        const char* e = getenv("GLEAM_NO_BF16_2D");
-        return !(e && e[0] == '1');
-    }();
-    return on;
 }
 
 hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long sn, long long st_, long long sk, int flip,

@@ -213,11 +213,17 @@ struct ConvBf16Args {
     const float* bias;
     const unsigned short* mask_ref;
     const void* add;
+    const unsigned* bits_in;   // or null: sign words of the mask source written by an earlier launch (replace mask_ref)
+    unsigned* bits_out;        // or null: sign words of this launch's output, conv_bf16_sign_words() of them
     int K, Nn;
     int out_f32;
     int relu_in, relu_out, mask_acc, mask_add;
     PixDims d;
 };
+// Whether a (K -> Nn) layer with bfloat16 output runs on the two-dimensional-tile kernel, whose launches can leave
+// and take ReLU masks as sign words, and how many 32-bit words those are for a [pixels][Nn] tensor.
+bool conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn);
+size_t conv_bf16_sign_words(const PixDims& d, int Nn);
 hipError_t launch_conv_bf16(const ConvBf16Args& a, const float* w, long long sn, long long st, long long sk, int flip,
                             unsigned short* wt_scratch, hipStream_t stream);
 size_t conv_bf16_wimg_elems(int K, int Nn, int taps);
