@@ -1071,6 +1071,10 @@ static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw,
     char name[56];
     snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
     KernelScope ks(name, 2.0 * (double)d.Q * a.K * a.Nn * taps_, (bf ? 2.0 : 4.0) * (double)d.Q * a.K + 8.0 * (double)d.Q, st);
+    if (conv_thin_out_mfma_applies(d, a.K, bf)) {   // 3x3 in the plane: dense product on the matrix cores + shifted sum
+        *hit = true;
+        return launch_conv_thin_out_mfma(a.in, wts, a.bias, a.add, a.out, a.K, a.relu_in, a.relu_out, d, bf, st);
+    }
     if (k2) launch_conv_thin_out_t<1, 1, 3, 3>(t, wts, bf, st);
     else if (k3) launch_conv_thin_out_t<1, 3, 3, 3>(t, wts, bf, st);
     else launch_conv_thin_out_t<3, 1, 1, 1>(t, wts, bf, st);

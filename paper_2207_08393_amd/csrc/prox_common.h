@@ -206,6 +206,11 @@ hipError_t launch_wgrad_wino(WinoWgradArgs a, int relu_in, int n_split, hipStrea
 // partial + n_split*16*Co*Ci by reduce_partials_kernel)
 hipError_t wgrad_wino_finish(const float* psum, int Co, int Ci, float* grad_w, hipStream_t stream);
 
+// Two-channel-output 3x3 layer on the matrix cores (prox_thin.hip); wts is [2][9][K] float32, in is bfloat16 when bf.
+bool conv_thin_out_mfma_applies(const PixDims& d, int K, bool bf);
+hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const float* bias, const float* add, float* out, int K,
+                                     int relu_in, int relu_out, const PixDims& d, bool bf, hipStream_t stream);
+
 struct ConvBf16Args {
     const unsigned short* in;
     void* out;
