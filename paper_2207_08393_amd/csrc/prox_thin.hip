@@ -1,17 +1,22 @@
-// Two-channel-OUTPUT 3x3 convolution (last layer of the prox, Eq. 4-5) on the matrix cores.
+// Two-channel-OUTPUT convolution (last layer of the prox, Eq. 4-5) on the matrix cores.
 //
 // out[p][n] = b[n] + sum_{tap,k} W[n][tap][k] * in[p + off(tap)][k] is split into a dense product and a shifted
-// sum: first c[p][tap][n] = sum_k W[n][tap][k] * in[p][k] for every pixel of a tile and its one-pixel halo (an
-// [18 x K] . [K x pixels] product, the 18 rows padded to one 32-row MFMA block), then
+// sum: first c[p][tap][n] = sum_k W[n][tap][k] * in[p][k] for every pixel of a tile and its halo (a
+// [2*taps x K] . [K x pixels] product, the rows padded to one 32-row MFMA block), then
 // out[p][n] = b[n] + sum_tap c[p + off(tap)][tap][n] from LDS.  The kernel reads its input once (plus the halo,
 // served by L2) and is bound by that read; the lane-per-pixel kernel it replaces spent its time on scalar
 // weight loads and LDS traffic.
 //
-// A workgroup of four waves owns 8 x 32 output pixels; the 10 x 34 input region is 340 pixel slots, padded to
-// eleven 32-pixel blocks that are dealt to the waves.  Lane (m, h) of a wave loads the channels of ITS pixel
-// slot straight from memory into the B operand (float32: channels K/2*h .. K/2*h + K/2 - 1, one per
-// v_mfma_f32_32x32x2_f32; bfloat16: eight channels 16*i + 8*h .. per v_mfma_f32_32x32x16_bf16), so the input
-// never passes through LDS; the weights sit in registers as the A operand for the life of the workgroup.
+// Kernel shapes: KP x KP taps in the image plane (KP = 3 is what is launched), times KO taps (1 or 3) along one
+// outer axis (the depth of a 3x3x3 layer).  The outer taps are a loop: per outer tap the plane it points at is
+// multiplied with that tap's 2*KP*KP weight rows and summed into the same outputs.
+//
+// A workgroup of four waves owns 8 x 32 output pixels of one plane; the (8 + KP - 1) x (32 + KP - 1) input
+// region is padded to 32-pixel blocks (eleven for KP = 3, eight for KP = 1) that are dealt to the waves.  Lane
+// (m, h) of a wave loads the channels of ITS pixel slot straight from memory into the B operand (float32:
+// channels K/2*h .. K/2*h + K/2 - 1, one per v_mfma_f32_32x32x2_f32; bfloat16: eight channels 16*i + 8*h .. per
+// v_mfma_f32_32x32x16_bf16), so the input never passes through LDS; the weights sit in registers as the A
+// operand for the life of the workgroup.
 #include <type_traits>
 
 #include "prox_common.h"
@@ -19,46 +24,51 @@
 namespace gleam {
 
 struct ThinOutMfmaArgs {
-    const void* in;       // [NI][H][W][K] float32 or bfloat16
-    const float* wts;     // [2][9][K]
+    const void* in;       // [NI][H][W][K] float32 or bfloat16, NI = all planes (batch, time, depth)
+    const float* wts;     // [2][KO*KP*KP][K]
     const float* bias;    // [2] or null
     const float* add;     // [NI][H][W][2] or null
     float* out;           // [NI][H][W][2]
     int relu_in, relu_out, H, W, bx_n, by_n;
+    int o_n, o_stride;    // outer axis: extent, and its stride in planes (plane index = (.. * o_n + pos) * o_stride + ..)
     long long n_blocks;
 };
 
-constexpr int kTORegionW = 34, kTORegionPx = 10 * kTORegionW, kTOBlocks = (kTORegionPx + 31) / 32;
-constexpr int kTOStride = 20;   // floats per pixel slot in LDS: 18 tap contributions + 2
+constexpr int kTOStride = 20;   // floats per pixel slot in LDS: up to 18 tap contributions + 2
 
-template <int K, bool BF>
+template <int K, bool BF, int KP, int KO>
 __global__ __launch_bounds__(256) void conv_thin_out_mfma_kernel(ThinOutMfmaArgs a) {
     constexpr int NM = BF ? K / 16 : K / 2;   // MFMAs per 32-pixel block
-    __shared__ __attribute__((aligned(16))) float c[kTOBlocks * 32 * kTOStride];
+    constexpr int RW = 32 + KP - 1, RPX = (8 + KP - 1) * RW, NBLK = (RPX + 31) / 32, PT = KP * KP;
+    static_assert(NBLK > 4 && NBLK <= 12, "two or three blocks per wave");
+    __shared__ __attribute__((aligned(16))) float c[NBLK * 32 * kTOStride];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 31, h = lane >> 5;
     const int H = a.H, W = a.W;
 
-    // A operand: row j = 2*tap + n of the 32-row block, rows 18..31 are zero
-    float wf[BF ? 1 : NM];
-    bf16x8 wb[BF ? NM : 1];
+    // A operand: row j = 2*(tap in the plane) + n of the 32-row block, rows 2*PT..31 are zero; one set per outer tap
+    float wf[BF ? 1 : KO][BF ? 1 : NM];
+    bf16x8 wb[BF ? KO : 1][BF ? NM : 1];
     {
-        const bool row_ok = m < 18;
-        const float* wrow = a.wts + (size_t)((m & 1) * 9 + (row_ok ? (m >> 1) : 0)) * K;
-        if constexpr (BF) {
+        const bool row_ok = m < 2 * PT;
 #pragma unroll
-            for (int i = 0; i < NM; ++i) {
-                const float* wp = wrow + 16 * i + 8 * h;
-                uint4 u;
-                u.x = pack_bf16x2(wp[0], wp[1]); u.y = pack_bf16x2(wp[2], wp[3]);
-                u.z = pack_bf16x2(wp[4], wp[5]); u.w = pack_bf16x2(wp[6], wp[7]);
-                if (!row_ok) u = make_uint4(0u, 0u, 0u, 0u);
-                wb[i] = __builtin_bit_cast(bf16x8, u);
+        for (int ko = 0; ko < KO; ++ko) {
+            const float* wrow = a.wts + (size_t)((m & 1) * (KO * PT) + ko * PT + (row_ok ? (m >> 1) : 0)) * K;
+            if constexpr (BF) {
+#pragma unroll
+                for (int i = 0; i < NM; ++i) {
+                    const float* wp = wrow + 16 * i + 8 * h;
+                    uint4 u;
+                    u.x = pack_bf16x2(wp[0], wp[1]); u.y = pack_bf16x2(wp[2], wp[3]);
+                    u.z = pack_bf16x2(wp[4], wp[5]); u.w = pack_bf16x2(wp[6], wp[7]);
+                    if (!row_ok) u = make_uint4(0u, 0u, 0u, 0u);
+                    wb[ko][i] = __builtin_bit_cast(bf16x8, u);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NM; ++i) wf[ko][i] = row_ok ? wrow[NM * h + i] : 0.f;
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < NM; ++i) wf[i] = row_ok ? wrow[NM * h + i] : 0.f;
         }
     }
     const float bias0 = a.bias ? a.bias[0] : 0.f, bias1 = a.bias ? a.bias[1] : 0.f;
@@ -70,85 +80,103 @@ __global__ __launch_bounds__(256) void conv_thin_out_mfma_kernel(ThinOutMfmaArgs
         const int by = (int)(rest % a.by_n);
         const long long img = rest / a.by_n;
         const int x0 = bx * 32, y0 = by * 8;
-        // the wave's blocks are wave, wave + 4 and (waves 0..2) wave + 8; the loads of a block are issued before
-        // the MFMAs of the block ahead of it
-        using Vec = typename std::conditional<BF, uint4, float4>::type;
-        constexpr int NV = BF ? NM : NM / 4;
-        auto slot_ok = [&](int b) {
-            const int s = 32 * b + m;
-            const int ry = s / kTORegionW, rx = s - ry * kTORegionW;
-            const int y = y0 - 1 + ry, x = x0 - 1 + rx;
-            return s < kTORegionPx && y >= 0 && y < H && x >= 0 && x < W;
-        };
-        auto load = [&](int b, Vec* v) {
-            const int s = 32 * b + m;
-            const int ry = s / kTORegionW, rx = s - ry * kTORegionW;
-            const long long pix = slot_ok(b) ? (img * H + (y0 - 1 + ry)) * W + (x0 - 1 + rx) : 0;   // clamped: the loads are unconditional
-            if constexpr (BF) {
-                const unsigned short* p = reinterpret_cast<const unsigned short*>(a.in) + pix * K + 8 * h;
+        int opos = 0;
+        if constexpr (KO > 1) opos = (int)((img / a.o_stride) % a.o_n);
+        float o0 = bias0, o1 = bias1;
 #pragma unroll
-                for (int i = 0; i < NV; ++i) v[i] = *reinterpret_cast<const uint4*>(p + 16 * i);
-            } else {
-                const float* p = reinterpret_cast<const float*>(a.in) + pix * K + NM * h;
-#pragma unroll
-                for (int q = 0; q < NV; ++q) v[q] = *reinterpret_cast<const float4*>(p + 4 * q);
+        for (int ko = 0; ko < KO; ++ko) {
+            long long src = img;
+            if constexpr (KO > 1) {
+                const int z = opos + ko - KO / 2;
+                if (z < 0 || z >= a.o_n) continue;   // uniform: the plane of this outer tap lies outside the grid
+                src = img + (long long)(ko - KO / 2) * a.o_stride;
             }
-        };
-        auto compute = [&](int b, const Vec* v) {
-            const bool ok = slot_ok(b);
-            floatx16 acc;
+            // the wave's blocks are wave, wave + 4 and (where there are that many) wave + 8; the loads of a block
+            // are issued before the MFMAs of the block ahead of it
+            using Vec = typename std::conditional<BF, uint4, float4>::type;
+            constexpr int NV = BF ? NM : NM / 4;
+            auto slot_ok = [&](int b) {
+                const int s = 32 * b + m;
+                const int ry = s / RW, rx = s - ry * RW;
+                const int y = y0 - KP / 2 + ry, x = x0 - KP / 2 + rx;
+                return s < RPX && y >= 0 && y < H && x >= 0 && x < W;
+            };
+            auto load = [&](int b, Vec* v) {
+                const int s = 32 * b + m;
+                const int ry = s / RW, rx = s - ry * RW;
+                const long long pix = slot_ok(b) ? (src * H + (y0 - KP / 2 + ry)) * W + (x0 - KP / 2 + rx) : 0;   // clamped: the loads are unconditional
+                if constexpr (BF) {
+                    const unsigned short* p = reinterpret_cast<const unsigned short*>(a.in) + pix * K + 8 * h;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-            if constexpr (BF) {
+                    for (int i = 0; i < NV; ++i) v[i] = *reinterpret_cast<const uint4*>(p + 16 * i);
+                } else {
+                    const float* p = reinterpret_cast<const float*>(a.in) + pix * K + NM * h;
 #pragma unroll
-                for (int i = 0; i < NV; ++i) {
-                    uint4 u = v[i];
-                    if (a.relu_in) { u.x = relu_bf16x2(u.x); u.y = relu_bf16x2(u.y); u.z = relu_bf16x2(u.z); u.w = relu_bf16x2(u.w); }
-                    if (!ok) u = make_uint4(0u, 0u, 0u, 0u);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[i], __builtin_bit_cast(bf16x8, u), acc, 0, 0, 0);
+                    for (int q = 0; q < NV; ++q) v[q] = *reinterpret_cast<const float4*>(p + 4 * q);
                 }
-            } else {
+            };
+            auto compute = [&](int b, const Vec* v) {
+                const bool ok = slot_ok(b);
+                floatx16 acc;
 #pragma unroll
-                for (int q = 0; q < NV; ++q) {
-                    const float e[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+                if constexpr (BF) {
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        float xv = a.relu_in ? fmaxf(e[t], 0.f) : e[t];
-                        xv = ok ? xv : 0.f;
-                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[4 * q + t], xv, acc, 0, 0, 0);
+                    for (int i = 0; i < NV; ++i) {
+                        uint4 u = v[i];
+                        if (a.relu_in) { u.x = relu_bf16x2(u.x); u.y = relu_bf16x2(u.y); u.z = relu_bf16x2(u.z); u.w = relu_bf16x2(u.w); }
+                        if (!ok) u = make_uint4(0u, 0u, 0u, 0u);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[ko][i], __builtin_bit_cast(bf16x8, u), acc, 0, 0, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) {
+                        const float e[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            float xv = a.relu_in ? fmaxf(e[t], 0.f) : e[t];
+                            xv = ok ? xv : 0.f;
+                            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[ko][4 * q + t], xv, acc, 0, 0, 0);
+                        }
                     }
                 }
-            }
-            // accumulator r holds row 8*(r/4) + 4*h + r%4 of this lane's pixel: rows 0..19 are kept
-            float* cs = c + (32 * b + m) * kTOStride;
-            *reinterpret_cast<float4*>(cs + 4 * h) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-            *reinterpret_cast<float4*>(cs + 8 + 4 * h) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-            if (h == 0) *reinterpret_cast<float4*>(cs + 16) = make_float4(acc[8], acc[9], acc[10], acc[11]);
-        };
-        {
-            static_assert(kTOBlocks > 8 && kTOBlocks <= 12, "two or three blocks per wave");
-            const bool third = wave + 8 < kTOBlocks;   // uniform per wave
-            Vec va[NV], vb[NV];
-            load(wave, va);
-            load(wave + 4, vb);
-            compute(wave, va);
-            if (third) load(wave + 8, va);
-            compute(wave + 4, vb);
-            if (third) compute(wave + 8, va);
-        }
-        __syncthreads();
-        {
-            const int oy = tid >> 5, ox = tid & 31;
-            const int y = y0 + oy, x = x0 + ox;
-            float o0 = bias0, o1 = bias1;
-#pragma unroll
-            for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-                for (int dx = 0; dx < 3; ++dx) {
-                    const float2 v = *reinterpret_cast<const float2*>(c + ((oy + dy) * kTORegionW + ox + dx) * kTOStride + (dy * 3 + dx) * 2);
-                    o0 += v.x;
-                    o1 += v.y;
+                // accumulator r holds row 8*(r/4) + 4*h + r%4 of this lane's pixel: rows 0..19 are kept
+                float* cs = c + (32 * b + m) * kTOStride;
+                *reinterpret_cast<float4*>(cs + 4 * h) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                if (PT > 4) {
+                    *reinterpret_cast<float4*>(cs + 8 + 4 * h) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+                    if (h == 0) *reinterpret_cast<float4*>(cs + 16) = make_float4(acc[8], acc[9], acc[10], acc[11]);
                 }
+            };
+            {
+                const bool third = wave + 8 < NBLK;   // uniform per wave
+                Vec va[NV], vb[NV];
+                load(wave, va);
+                load(wave + 4, vb);
+                __builtin_amdgcn_sched_barrier(0);   // all loads of both blocks are in flight before the first MFMA
+                compute(wave, va);
+                __builtin_amdgcn_sched_barrier(0);
+                if (third) load(wave + 8, va);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(wave + 4, vb);
+                if (third) compute(wave + 8, va);
+            }
+            __syncthreads();
+            {
+                const int oy = tid >> 5, ox = tid & 31;
+#pragma unroll
+                for (int dy = 0; dy < KP; ++dy)
+#pragma unroll
+                    for (int dx = 0; dx < KP; ++dx) {
+                        const float2 v = *reinterpret_cast<const float2*>(c + ((oy + dy) * RW + ox + dx) * kTOStride + (dy * KP + dx) * 2);
+                        o0 += v.x;
+                        o1 += v.y;
+                    }
+            }
+            __syncthreads();   // the next pass overwrites c
+        }
+        {
+            const int y = y0 + (tid >> 5), x = x0 + (tid & 31);
             if (y < H && x < W) {
                 const long long q = (img * H + y) * W + x;
                 if (a.relu_out) { o0 = fmaxf(o0, 0.f); o1 = fmaxf(o1, 0.f); }
@@ -160,42 +188,59 @@ __global__ __launch_bounds__(256) void conv_thin_out_mfma_kernel(ThinOutMfmaArgs
                 *reinterpret_cast<float2*>(a.out + 2 * q) = make_float2(o0, o1);
             }
         }
-        __syncthreads();   // the next tile overwrites c
     }
 }
 
-bool conv_thin_out_mfma_applies(const PixDims& d, int K, bool bf) {
+// 0: not covered; 1: 3x3 in the plane; 2: 3x3x3 (outer axis = depth).  A 3x1x1 layer (outer axis = time, no taps in
+// the plane) has no halo to share and was slower here than on the lane-per-pixel kernel (125 against 97 us).
+static int thin_out_mfma_shape(const PixDims& d, int K, bool bf) {
     static const bool on = [] {   // GLEAM_NO_THIN_MFMA=1 keeps the lane-per-pixel kernel for comparison
         const char* e = getenv("GLEAM_NO_THIN_MFMA");
         return !(e && e[0] == '1');
     }();
-    if (!on || !(d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3)) return false;
-    return bf ? (K == 64 || K == 128) : (K == 32 || K == 64 || K == 128);
+    if (!on) return 0;
+    if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) return (bf ? (K == 64 || K == 128) : (K == 32 || K == 64 || K == 128)) ? 1 : 0;
+    if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) return (!bf && (K == 32 || K == 64)) ? 2 : 0;
+    return 0;
 }
 
-template <int K, bool BF>
+bool conv_thin_out_mfma_applies(const PixDims& d, int K, bool bf) { return thin_out_mfma_shape(d, K, bf) != 0; }
+
+template <int K, bool BF, int KP, int KO>
 static void launch_thin_out_mfma_t(const ThinOutMfmaArgs& a, hipStream_t st) {
-    const long long cap = 256 * ((BF || K <= 64) ? 3 : 2);   // workgroups per CU that the instantiation's registers allow
+    // persistent workgroups: three per CU (four measured slower on the 64-channel float32 layer), two where the
+    // instantiation's registers (weights of all outer taps + two blocks of input) leave room for no more
+    constexpr int per_cu = (!BF && K * KO >= 128) ? 2 : 3;
+    const long long cap = 256LL * per_cu;
     const long long gx = ((a.n_blocks < cap ? a.n_blocks : cap) + 7) / 8 * 8;
-    hipLaunchKernelGGL((conv_thin_out_mfma_kernel<K, BF>), dim3((unsigned)gx), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((conv_thin_out_mfma_kernel<K, BF, KP, KO>), dim3((unsigned)gx), dim3(256), 0, st, a);
 }
 
-// wts: [2][9][K] float32 (theta's own layout of a K -> 2 layer); in is bfloat16 when bf.
+// wts: [2][taps][K] float32 (theta's own layout of a K -> 2 layer); in is bfloat16 when bf.
 hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const float* bias, const float* add, float* out, int K,
                                      int relu_in, int relu_out, const PixDims& d, bool bf, hipStream_t st) {
+    const int shape = thin_out_mfma_shape(d, K, bf);
+    if (shape == 0) return hipErrorInvalidValue;
     ThinOutMfmaArgs a{};
     a.in = in; a.wts = wts; a.bias = bias; a.add = add; a.out = out;
     a.relu_in = relu_in; a.relu_out = relu_out; a.H = d.H; a.W = d.W;
     a.bx_n = (d.W + 31) / 32;
     a.by_n = (d.H + 7) / 8;
     a.n_blocks = d.Q / ((long long)d.H * d.W) * a.bx_n * a.by_n;
-    if (bf) {
-        if (K == 64) launch_thin_out_mfma_t<64, true>(a, st);
-        else launch_thin_out_mfma_t<128, true>(a, st);
+    a.o_n = 1; a.o_stride = 1;
+    if (shape == 2) { a.o_n = d.D; a.o_stride = 1; }        // planes are ordered (batch, time, depth)
+    if (shape == 1) {
+        if (bf) {
+            if (K == 64) launch_thin_out_mfma_t<64, true, 3, 1>(a, st);
+            else launch_thin_out_mfma_t<128, true, 3, 1>(a, st);
+        } else {
+            if (K == 32) launch_thin_out_mfma_t<32, false, 3, 1>(a, st);
+            else if (K == 64) launch_thin_out_mfma_t<64, false, 3, 1>(a, st);
+            else launch_thin_out_mfma_t<128, false, 3, 1>(a, st);
+        }
     } else {
-        if (K == 32) launch_thin_out_mfma_t<32, false>(a, st);
-        else if (K == 64) launch_thin_out_mfma_t<64, false>(a, st);
-        else launch_thin_out_mfma_t<128, false>(a, st);
+        if (K == 32) launch_thin_out_mfma_t<32, false, 3, 3>(a, st);
+        else launch_thin_out_mfma_t<64, false, 3, 3>(a, st);
     }
     return hipGetLastError();
 }
