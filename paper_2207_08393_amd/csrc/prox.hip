@@ -1003,6 +1003,15 @@ static hipError_t launch_conv_thin_in(const ConvArgs& a, const ConvWeights& cw, 
     char name[56];
     snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
     KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, (bf ? 2.0 : 4.0) * (double)a.d.Q * a.Nn + 8.0 * (double)a.d.Q, st);
+    if (conv_thin_in_mfma_applies(d, a.Nn)) {   // 3x3x3: one MFMA of depth two per tap and 32 output channels
+        ThinInMfmaArgs t{};
+        t.in = a.in; t.out = a.out; t.bias = a.bias; t.mask_ref = a.mask_ref; t.add = a.add;
+        t.w = cw.w; t.sn = cw.sn; t.st = cw.st; t.sk = cw.sk;
+        t.Nn = a.Nn; t.flip = a.flip; t.relu_in = a.relu_in; t.relu_out = a.relu_out; t.mask_acc = a.mask_acc; t.mask_add = a.mask_add;
+        t.d = d;
+        *hit = true;
+        return launch_conv_thin_in_mfma(t, bf, st);
+    }
     if (k2) launch_conv_thin_in_t<1, 1, 3, 3>(a, cw, bf, st);
     else if (k3) launch_conv_thin_in_t<1, 3, 3, 3>(a, cw, bf, st);
     else launch_conv_thin_in_t<3, 1, 1, 1>(a, cw, bf, st);

@@ -211,6 +211,23 @@ bool conv_thin_out_mfma_applies(const PixDims& d, int K, bool bf);
 hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const float* bias, const float* add, float* out, int K,
                                      int relu_in, int relu_out, const PixDims& d, bool bf, hipStream_t stream);
 
+// Two-channel-input 3x3x3 layer on the matrix cores (prox_thin.hip).  out, mask_ref and add are bfloat16 when
+// the launch says so; the 2-channel input and the weights are float32; weight (n, tap, e) at w[n*sn + tapidx*st + e*sk],
+// taps mirrored when flip.
+struct ThinInMfmaArgs {
+    const float* in;        // [Q][2]
+    void* out;              // [Q][Nn]
+    const float* bias;      // [Nn] or null
+    const void* mask_ref;   // [Q][Nn] or null: ReLU mask source (value > 0 passes)
+    const void* add;        // [Q][Nn] or null
+    const float* w;
+    long long sn, st, sk;
+    int Nn, flip, relu_in, relu_out, mask_acc, mask_add;
+    PixDims d;
+};
+bool conv_thin_in_mfma_applies(const PixDims& d, int Nn);
+hipError_t launch_conv_thin_in_mfma(const ThinInMfmaArgs& a, bool bf, hipStream_t stream);
+
 struct ConvBf16Args {
     const unsigned short* in;
     void* out;

@@ -245,4 +245,178 @@ hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const flo
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Two-channel-INPUT 3x3x3 convolution (first layer of the prox; data gradient of the last layer) on the matrix cores.
+//
+// out[p][n] = b[n] + sum_{tap,e} W[n][tap][e] * in[p + off(tap)][e] with e = 0, 1: one v_mfma_f32_32x32x2_f32 per
+// tap and block of 32 output channels, its depth of two being exactly the two input channels.  Lane (m, h) of a
+// wave supplies W[32*nb + m][tap][h] (registers, for the life of the wave) and in[p_m + off(tap)][h] (one 4-byte
+// load per tap, 256 contiguous bytes per wave, zero outside the grid), and ends up with 16 output channels of its
+// pixel in groups of four, which go through the usual fused epilogue (bias, ReLU, ReLU mask, add) into 16-byte
+// (float32) or 8-byte (bfloat16) stores after a turn through the wave's own LDS rows.  No barriers: every wave
+// walks 32-pixel row segments on its own.  The kernel it replaces for these shapes computes on the vector ALUs, 2*taps multiply-adds per output.
+
+template <int KD, int NB, int NH, bool BF>
+__global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a) {
+    // NH passes of NB blocks of 32 output channels each: Nn = 32 * NB * NH
+    constexpr int TAPS = KD * 9, NP = 32 * NB, NN = NP * NH, SS = NP + 4;   // SS: floats per pixel row of the wave's LDS rows
+    __shared__ __attribute__((aligned(16))) float stage_all[4 * 32 * SS];
+    const PixDims d = a.d;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    float* stage = stage_all + wave * 32 * SS;
+    float wreg[NH][NB][TAPS];
+#pragma unroll
+    for (int hb = 0; hb < NH; ++hb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t)
+                wreg[hb][nb][t] = a.w[(NP * hb + 32 * nb + m) * a.sn + (a.flip ? TAPS - 1 - t : t) * a.st + h * a.sk];
+    const int segs = (d.W + 31) / 32;
+    const long long n_items = d.Q / d.W * segs;
+    const long long first = (long long)blockIdx.x * 4 + wave, step = (long long)gridDim.x * 4;
+    const float* in = a.in;
+    for (long long item = first; item < n_items; item += step) {
+        const long long row = item / segs;
+        const int x = (int)(item - row * segs) * 32 + m;
+        const int y = (int)(row % d.H);
+        const int z = (int)((row / d.H) % d.D);
+        const long long q = row * d.W + x;
+        const bool px_ok = x < d.W;
+        float v[TAPS];
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) {
+            const int iz = KD == 1 ? 0 : t / 9 - 1, iy = (t / 3) % 3 - 1, ix = t % 3 - 1;
+            const bool ok = px_ok && (unsigned)(x + ix) < (unsigned)d.W && (unsigned)(y + iy) < (unsigned)d.H &&
+                            (KD == 1 || (unsigned)(z + iz) < (unsigned)d.D);
+            const long long off = ((long long)iz * d.H + iy) * d.W + ix;
+            const float f = in[ok ? 2 * (q + off) + h : h];   // clamped: the loads are unconditional
+            v[t] = ok ? (a.relu_in ? fmaxf(f, 0.f) : f) : 0.f;
+        }
+        __builtin_amdgcn_sched_barrier(0);   // all tap loads are in flight before the first MFMA
+        const long long q0 = q - m;   // first pixel of the segment
+        const int x_seg = x - m;
+#pragma unroll
+        for (int hb = 0; hb < NH; ++hb) {
+            floatx16 acc[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[hb][nb][t], v[t], acc[nb], 0, 0, 0);
+            // accumulator r of block nb: output channel NP*hb + 32*nb + 8*(r/4) + 4*h + r%4 of this lane's pixel.  The
+            // wave turns its 32 pixels x NP channels around in its own LDS rows, so that the epilogue's loads and stores
+            // cover whole runs of NP channels per pixel; LDS accesses of one wave complete in order, no barrier.
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4*>(stage + m * SS + 32 * nb + 8 * g + 4 * h) =
+                        make_float4(acc[nb][4 * g], acc[nb][4 * g + 1], acc[nb][4 * g + 2], acc[nb][4 * g + 3]);
+            __builtin_amdgcn_wave_barrier();
+            constexpr int PASSES = NB * 4, UN = 4;   // 64 pieces of four channels per pass
+#pragma unroll
+            for (int p0 = 0; p0 < PASSES; p0 += UN) {
+                float4 accv[UN], refv[UN], addv[UN];
+                long long oo[UN];
+                bool okk[UN];
+#pragma unroll
+                for (int u = 0; u < UN; ++u) {
+                    const int j = (p0 + u) * 64 + lane;
+                    const int px = j / (NP / 4), cq = j - px * (NP / 4);
+                    okk[u] = x_seg + px < d.W;
+                    oo[u] = okk[u] ? (q0 + px) * NN + NP * hb + 4 * cq : 0;   // clamped for the loads
+                    accv[u] = *reinterpret_cast<const float4*>(stage + px * SS + 4 * cq);
+                    refv[u] = make_float4(1.f, 1.f, 1.f, 1.f);
+                    addv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if constexpr (BF) {
+                        if (a.mask_ref) {
+                            const uint2 w2 = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned short*>(a.mask_ref) + oo[u]);
+                            refv[u] = make_float4(bf16_to_f32((unsigned short)w2.x), bf16_to_f32((unsigned short)(w2.x >> 16)),
+                                                  bf16_to_f32((unsigned short)w2.y), bf16_to_f32((unsigned short)(w2.y >> 16)));
+                        }
+                        if (a.add) {
+                            const uint2 w2 = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned short*>(a.add) + oo[u]);
+                            addv[u] = make_float4(bf16_to_f32((unsigned short)w2.x), bf16_to_f32((unsigned short)(w2.x >> 16)),
+                                                  bf16_to_f32((unsigned short)w2.y), bf16_to_f32((unsigned short)(w2.y >> 16)));
+                        }
+                    } else {
+                        if (a.mask_ref) refv[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.mask_ref) + oo[u]);
+                        if (a.add) addv[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.add) + oo[u]);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UN; ++u) {
+                    const int j = (p0 + u) * 64 + lane;
+                    const int co = NP * hb + 4 * (j % (NP / 4));
+                    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (a.bias) bv = make_float4(a.bias[co], a.bias[co + 1], a.bias[co + 2], a.bias[co + 3]);
+                    float xv[4] = {accv[u].x + bv.x, accv[u].y + bv.y, accv[u].z + bv.z, accv[u].w + bv.w};
+                    const float rr[4] = {refv[u].x, refv[u].y, refv[u].z, refv[u].w};
+                    const float aa[4] = {addv[u].x, addv[u].y, addv[u].z, addv[u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (a.relu_out) xv[e] = fmaxf(xv[e], 0.f);
+                        if (a.mask_acc) xv[e] = rr[e] > 0.f ? xv[e] : 0.f;
+                        xv[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
+                    }
+                    if (okk[u]) {
+                        if constexpr (BF)
+                            *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.out) + oo[u]) =
+                                make_uint2(pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]));
+                        else
+                            *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + oo[u]) = make_float4(xv[0], xv[1], xv[2], xv[3]);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+template <int KD, int NB, int NH, bool BF>
+static void launch_thin_in_mfma_t(const ThinInMfmaArgs& a, hipStream_t st) {
+    static const int per_cu = [] {   // persistent waves: what the instantiation's registers allow, at most four workgroups
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, conv_thin_in_mfma_kernel<KD, NB, NH, BF>, 256, 0) != hipSuccess) n = 1;
+        return n < 1 ? 1 : (n > 4 ? 4 : n);
+    }();
+    const long long n_items = a.d.Q / a.d.W * ((a.d.W + 31) / 32);
+    const long long want = (n_items + 3) / 4, cap = 256LL * per_cu;
+    hipLaunchKernelGGL((conv_thin_in_mfma_kernel<KD, NB, NH, BF>), dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, st, a);
+}
+
+template <int KD, bool BF>
+static void launch_thin_in_mfma_n(const ThinInMfmaArgs& a, hipStream_t st) {
+    switch (a.Nn / 32) {
+        case 1: launch_thin_in_mfma_t<KD, 1, 1, BF>(a, st); break;
+        case 2: launch_thin_in_mfma_t<KD, 2, 1, BF>(a, st); break;
+        default: launch_thin_in_mfma_t<KD, 2, 2, BF>(a, st); break;
+    }
+}
+
+bool conv_thin_in_mfma_applies(const PixDims& d, int Nn) {
+    static const bool on = [] {   // GLEAM_NO_THIN_MFMA=1 keeps the vector-ALU kernel for comparison
+        const char* e = getenv("GLEAM_NO_THIN_MFMA");
+        return !(e && e[0] == '1');
+    }();
+    // 3x3 layers in the plane stay on the vector-ALU kernel: with 18 multiply-adds per output it already runs at the
+    // speed of its stores (knee: 38 against 40 us forward, 54 against 54 us data gradient; brain, bfloat16 output:
+    // 116 against 96 us forward, 231 against 265 us data gradient); with 54 it does not
+    if (!on || !(d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3)) return false;
+    return Nn == 32 || Nn == 64 || Nn == 128;
+}
+
+hipError_t launch_conv_thin_in_mfma(const ThinInMfmaArgs& a, bool bf, hipStream_t st) {
+    if (!conv_thin_in_mfma_applies(a.d, a.Nn)) return hipErrorInvalidValue;
+    if (bf) launch_thin_in_mfma_n<3, true>(a, st);
+    else launch_thin_in_mfma_n<3, false>(a, st);
+    return hipGetLastError();
+}
+
 }  // namespace gleam
