@@ -87,6 +87,12 @@ def module_cases():
     yield "wino_ragged", synth.Geom(2, 2, 2, 1, 1, 10, 46), synth.resblock_prox(64, 1), 0
     yield "wino_128", synth.Geom(2, 1, 2, 1, 1, 6, 96), synth.chain_prox([2, 64, 128, 64, 2], [K2] * 4), 0
     yield "wino_nobias_l1", synth.Geom(2, 1, 2, 3, 1, 6, 46), synth.chain_prox([2, 64, 64, 2], [K2] * 3, has_bias=0), 1
+    # the matrix-core kernels of the two-channel layers: every channel count they are built for, images that
+    # their 8 x 32 tiles / 32-pixel row segments do not divide, shallow volumes
+    yield "thin_out_128", synth.Geom(2, 1, 2, 1, 1, 10, 46), synth.chain_prox([2, 32, 128, 2], [K2] * 3), 0
+    yield "thin_out_32", synth.Geom(2, 2, 2, 1, 1, 6, 20), synth.chain_prox([2, 128, 32, 2], [K2] * 3), 0
+    yield "thin_vol64", synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 64, 64, 2], [K3] * 3), 0
+    yield "thin_vol128_flat", synth.Geom(3, 1, 2, 1, 4, 6, 46), synth.chain_prox([2, 128, 32, 2], [K3, (1, 1, 1, 1), K3], has_bias=0), 1
 
 
 def check_module(c, tol=TOL, alpha=None):
@@ -212,6 +218,7 @@ def bf16_cases():
     yield "vol32", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3, dtype=1), 0
     yield "cine64", synth.Geom(2, 1, 2, 6, 1, 12, 16), synth.chain_prox([2, 64, 64, 64, 2], [KS, KT, KS, KT], dtype=1), 0
     # 96 channels x 27 taps: the weight gradient's two staging buffers exceed LDS, so it runs single-buffered
+    yield "thin_vol64", synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 64, 64, 2], [K3] * 3, dtype=1), 0
     yield "vol96_one_buffer", synth.Geom(3, 1, 2, 1, 6, 8, 12), synth.chain_prox([2, 96, 96, 2], [K3] * 3, dtype=1), 0
 
 
