@@ -1239,7 +1239,10 @@ struct WgradPipeArgs {
     float* bias_partial;  // [n_split][Co] or null
 };
 
-template <int JT, int PG, int PA, int NW>
+// BAL (one 32x32 channel block, more taps than waves): the taps are dealt to all NW waves in runs whose lengths
+// differ by at most one, longest first, so that the waves sharing a SIMD (w and w + 4) carry nearly the same
+// number of MFMAs; JT is then the longest run.
+template <int JT, int PG, int PA, int NW, bool BAL = false>
 __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     constexpr int NT = NW * 64;
     extern __shared__ __attribute__((aligned(16))) float smem[];
@@ -1255,10 +1258,12 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
     const int lane = tid & 63, wave = tid >> 6, m = lane & 31, h = lane >> 5;
     const int ncb = (a.Co + 31) / 32, nib = (a.Ci + 31) / 32, tapgroups = (taps + JT - 1) / JT;
     const int job = blockIdx.y * NW + wave;
-    const bool active = job < ncb * nib * tapgroups;
+    const bool active = BAL || job < ncb * nib * tapgroups;
     const int tg = job % tapgroups, pair = job / tapgroups;
-    const int cb = pair / nib, ib = pair % nib;
-    const int tap0 = tg * JT;
+    const int cb = BAL ? 0 : pair / nib, ib = BAL ? 0 : pair % nib;
+    const int bal_base = taps / NW, bal_extra = taps % NW;
+    const int tap0 = BAL ? wave * bal_base + (wave < bal_extra ? wave : bal_extra) : tg * JT;
+    const int n_my = BAL ? bal_base + (wave < bal_extra ? 1 : 0) : JT;   // taps of this wave (uniform per wave)
     const int n_g4 = kWgTM * Co4, n_a4 = rowtaps * n_pa * Ci4;
 
     // Per-thread staging descriptors: the float4 slots this thread moves are the same for every chunk.
@@ -1412,7 +1417,8 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
 #pragma unroll
                 for (int j = 0; j < JT; ++j) bv_n[j] = as[b_off[j] + 2 * sn * RSa];
 #pragma unroll
-                for (int j = 0; j < JT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[j], acc[j], 0, 0, 0);
+                for (int j = 0; j < JT; ++j)
+                    if (!BAL || j < JT - 1 || n_my == JT) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[j], acc[j], 0, 0, 0);
                 av = av_n;
 #pragma unroll
                 for (int j = 0; j < JT; ++j) bv[j] = bv_n[j];
@@ -1427,7 +1433,7 @@ __global__ __launch_bounds__(NW * 64) void wgrad_pipe_kernel(WgradPipeArgs pa) {
 #pragma unroll
         for (int j = 0; j < JT; ++j) {
             const int tap = tap0 + j;
-            if (tap >= taps || ci >= a.Ci) continue;
+            if (tap >= taps || j >= n_my || ci >= a.Ci) continue;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int cc = cb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
@@ -2009,15 +2015,15 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
     return hipSuccess;
 }
 
-template <int JT, int PG, int PA, int NW>
+template <int JT, int PG, int PA, int NW, bool BAL = false>
 static void launch_wgrad_pipe_t(const WgradPipeArgs& pa, dim3 grid, size_t lds, hipStream_t st) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)wgrad_pipe_kernel<JT, PG, PA, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        (void)hipFuncSetAttribute((const void*)wgrad_pipe_kernel<JT, PG, PA, NW, BAL>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         once = true;
     }
     if (lds < (size_t)PG * NW * 64 * sizeof(float4)) lds = (size_t)PG * NW * 64 * sizeof(float4);
-    hipLaunchKernelGGL((wgrad_pipe_kernel<JT, PG, PA, NW>), grid, dim3(NW * 64), lds, st, pa);
+    hipLaunchKernelGGL((wgrad_pipe_kernel<JT, PG, PA, NW, BAL>), grid, dim3(NW * 64), lds, st, pa);
 }
 
 template <int KT, int KD, int KH, int KW>
@@ -2107,7 +2113,14 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
             const int jobs3 = blocks * ((taps + 2) / 3), jobs1 = blocks * taps;
             const int pg12 = (kWgTM * (a.Co / 4) + 767) / 768, pa12 = (rowtaps * n_pa * (a.Ci / 4) + 767) / 768;
             const dim3 g12(n_split, 1);
-            if (taps % 3 == 0 && jobs3 >= 7 && jobs3 <= 12 && pg12 <= 1 && pa12 <= 4) {
+            const int pg8b = (kWgTM * (a.Co / 4) + 511) / 512, pa8b = (rowtaps * n_pa * (a.Ci / 4) + 511) / 512;
+            static const bool bal_on = [] { const char* e = getenv("GLEAM_NO_WGRAD_BAL"); return !(e && e[0] == '1'); }();
+            if (bal_on && blocks == 1 && taps == 27 && pg8b <= 1 && pa8b <= 5) {
+                // 27 taps on one channel block: nine 3-tap jobs would put three on one SIMD and two on the others;
+                // eight waves with 4,4,4,3,3,3,3,3 taps load the SIMDs 7,7,7,6
+                launch_wgrad_pipe_t<4, 1, 5, 8, true>(pa, g12, lds, st);
+                hit_none = false;
+            } else if (taps % 3 == 0 && jobs3 >= 7 && jobs3 <= 12 && pg12 <= 1 && pa12 <= 4) {
                 if (pa12 <= 3) launch_wgrad_pipe_t<3, 1, 3, 12>(pa, g12, lds, st);
                 else launch_wgrad_pipe_t<3, 1, 4, 12>(pa, g12, lds, st);
                 hit_none = false;
