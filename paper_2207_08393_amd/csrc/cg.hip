@@ -22,10 +22,14 @@ __device__ inline double block_sum(double v, double* red) {
     return red[0];
 }
 
-__device__ inline double sum_partials(const double* __restrict__ part, int nb) {
+// Sum of a sample's nb partials, the same value in every thread: strided per-thread sums in a fixed order, then
+// the block tree.  Ends with a barrier so that red can be used again at once.
+__device__ inline double sum_partials(const double* __restrict__ part, int nb, double* red) {
     double s = 0.0;
-    for (int i = 0; i < nb; ++i) s += part[i];
-    return s;
+    for (int i = threadIdx.x; i < nb; i += kCgThreads) s += part[i];
+    const double total = block_sum(s, red);
+    __syncthreads();
+    return total;
 }
 
 }  // namespace
@@ -75,8 +79,8 @@ __global__ __launch_bounds__(kCgThreads) void cg_update_xr_kernel(float2* __rest
                                                                   const double* __restrict__ pq, double* __restrict__ rr_new) {
     __shared__ double red[kCgThreads];
     const int nb = gridDim.x;
-    const double num = sum_partials(rr_old + (size_t)blockIdx.y * nb, nb);
-    const double den = sum_partials(pq + (size_t)blockIdx.y * nb, nb);
+    const double num = sum_partials(rr_old + (size_t)blockIdx.y * nb, nb, red);
+    const double den = sum_partials(pq + (size_t)blockIdx.y * nb, nb, red);
     const float a = den > 0.0 ? (float)(num / den) : 0.f;
     const long long base = (long long)blockIdx.y * n;
     double s = 0.0;
@@ -98,8 +102,9 @@ __global__ __launch_bounds__(kCgThreads) void cg_update_p_kernel(const float2* _
                                                                  const double* __restrict__ rr_old,
                                                                  const double* __restrict__ rr_new) {
     const int nb = gridDim.x;
-    const double den = sum_partials(rr_old + (size_t)blockIdx.y * nb, nb);
-    const double num = sum_partials(rr_new + (size_t)blockIdx.y * nb, nb);
+    __shared__ double red[kCgThreads];
+    const double den = sum_partials(rr_old + (size_t)blockIdx.y * nb, nb, red);
+    const double num = sum_partials(rr_new + (size_t)blockIdx.y * nb, nb, red);
     const float beta = den > 0.0 ? (float)(num / den) : 0.f;
     const long long base = (long long)blockIdx.y * n;
     for (long long i = (long long)blockIdx.x * kCgThreads + threadIdx.x; i < n; i += (long long)gridDim.x * kCgThreads) {

@@ -91,7 +91,7 @@ hipError_t loss_and_grad(const float2* x, const float2* x_ref, float2* g, long l
 
 // n_cg conjugate-gradient steps from zero on (A^H A + mu I) x = c1*u + c2*v (v may be null), one system per
 // batch sample.  x may alias u.  kbuf: coil k-space buffer of sense_dc; scratch: cg_scratch_bytes(g) bytes.
-constexpr int kCgBlocksMax = 64;   // workgroups (= partial sums) per batch sample
+constexpr int kCgBlocksMax = 512;  // workgroups (= partial sums) per batch sample
 size_t cg_scratch_bytes(const gleam_geom& g);
 hipError_t cg_solve(const gleam_geom& g, const float2* S, const unsigned char* M, float mu, int n_cg, const float2* u,
                     const float2* v, float c1, float c2, float2* x, float2* kbuf, void* scratch, hipStream_t st);
