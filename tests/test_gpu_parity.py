@@ -428,6 +428,38 @@ def test_direct_kernels_still_cover_the_winograd_shapes():
     assert out.returncode == 0
 
 
+def test_fallback_kernels_of_the_two_channel_layers_and_the_27_tap_gradient():
+    """GLEAM_NO_THIN_MFMA=1, GLEAM_NO_BF16_2D=1 and GLEAM_NO_WGRAD_BAL=1 (each read once per process) route the
+    shapes that normally take the matrix-core two-channel kernels, the two-dimensional-tile bf16 kernel and the
+    balanced 27-tap weight gradient through the kernels they replaced; a fresh interpreter checks a 2D fp32, a 2D
+    bf16 and a 3D module step on those against the oracle."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import numpy as np\n"
+        "from oracle import gleam_oracle as og\n"
+        "from paper_2207_08393_amd import synth\n"
+        "from paper_2207_08393_amd.runner import ModuleRunner\n"
+        "rel = lambda a, b: float(np.linalg.norm(np.asarray(a, np.complex128) - b) / np.linalg.norm(b))\n"
+        "K2, K3 = (1, 1, 3, 3), (1, 3, 3, 3)\n"
+        "cases = [(synth.Geom(2, 1, 2, 1, 1, 10, 46), synth.chain_prox([2, 64, 64, 2], [K2] * 3), 1e-4),\n"
+        "         (synth.Geom(2, 1, 2, 1, 1, 20, 24), synth.chain_prox([2, 128, 128, 2], [K2] * 3, dtype=1), 2e-2),\n"
+        "         (synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), 1e-4)]\n"
+        "for geom, prox, tol in cases:\n"
+        "    c = synth.make_custom(37, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.8)\n"
+        "    r = ModuleRunner(c, alpha=0.8); r.step(); x, loss, grad = r.results()\n"
+        "    f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, c.theta, c.x_true); g = og.module_bwd(c.prox, c.theta, f)\n"
+        "    e = (rel(x, f['x_out']), abs(loss - f['loss']) / abs(f['loss']), rel(grad, g))\n"
+        "    print('fallback-kernel rel errors', e, flush=True)\n"
+        "    assert max(e) <= tol, e\n")
+    env = dict(os.environ, GLEAM_NO_THIN_MFMA="1", GLEAM_NO_BF16_2D="1", GLEAM_NO_WGRAD_BAL="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
+    print(out.stdout, out.stderr[-2000:], flush=True)
+    assert out.returncode == 0
+
+
 # ----------------------------------------------------------------------------- one transformed axis
 def test_single_axis_module_matches_oracle_and_the_2d_problem():
     """ndim_fft = 1: module step against the oracle, and the same 2D problem (line mask, constant along H) solved
