@@ -191,8 +191,106 @@ __global__ __launch_bounds__(256) void conv_thin_out_mfma_kernel(ThinOutMfmaArgs
     }
 }
 
-// 0: not covered; 1: 3x3 in the plane; 2: 3x3x3 (outer axis = depth).  A 3x1x1 layer (outer axis = time, no taps in
-// the plane) has no halo to share and was slower here than on the lane-per-pixel kernel (125 against 97 us).
+// 3x1x1 layers (three taps along time, none in the plane): a tile is 32 neighbouring positions of one volume times
+// ALL frames, so the shifted sum out[t] = b + sum_dt c[t + dt - 1][dt] never leaves the tile and every input value is
+// read exactly once.  Frame t of the tile is one 32-pixel block (dealt to wave t % 4); rows 2*dt + n of the product.
+constexpr int kTOTimeMaxT = 32;
+
+struct ThinOutTimeArgs {
+    const float* in;      // [B][T][S][K], S = D*H*W positions per frame
+    const float* wts;     // [2][3][K]
+    const float* bias;    // [2] or null
+    const float* add;     // [B][T][S][2] or null
+    float* out;           // [B][T][S][2]
+    int relu_in, relu_out, T, segs;
+    long long S, n_blocks;   // n_blocks = B * segs, segs = ceil(S / 32)
+};
+
+template <int K>
+__global__ __launch_bounds__(256) void conv_thin_out_time_mfma_kernel(ThinOutTimeArgs a) {
+    constexpr int NM = K / 2, NV = NM / 4;
+    __shared__ __attribute__((aligned(16))) float c[kTOTimeMaxT * 32 * 8];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    const int T = a.T;
+    float wf[NM];   // A operand: row j = 2*dt + n, rows 6..31 are zero
+#pragma unroll
+    for (int i = 0; i < NM; ++i) wf[i] = m < 6 ? a.wts[(size_t)((m & 1) * 3 + (m >> 1)) * K + NM * h + i] : 0.f;
+    const float bias0 = a.bias ? a.bias[0] : 0.f, bias1 = a.bias ? a.bias[1] : 0.f;
+    const XcdRange xr = xcd_range(a.n_blocks);
+    for (long long item = xr.first; item < xr.end; item += xr.stride) {
+        const long long b = item / a.segs;
+        const long long s0 = (item - b * a.segs) * 32;
+        const bool px_ok = s0 + m < a.S;
+        auto load = [&](int t, float4* v) {
+            const long long pix = px_ok ? (b * T + t) * a.S + s0 + m : 0;   // clamped: the loads are unconditional
+            const float* p = a.in + pix * K + NM * h;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) v[q] = *reinterpret_cast<const float4*>(p + 4 * q);
+        };
+        auto compute = [&](int t, const float4* v) {
+            floatx16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const float e[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float xv = a.relu_in ? fmaxf(e[u], 0.f) : e[u];
+                    xv = px_ok ? xv : 0.f;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[4 * q + u], xv, acc, 0, 0, 0);
+                }
+            }
+            // accumulator r holds row 4*h + r (r < 4) of this lane's pixel: rows 0..7 are kept
+            *reinterpret_cast<float4*>(c + (t * 32 + m) * 8 + 4 * h) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        };
+        // frames wave, wave + 4, ...: the loads of a frame are issued before the MFMAs of the frame ahead of it
+        {
+            float4 va[NV], vb[NV];
+            if (wave < T) load(wave, va);
+            for (int t = wave; t < T; t += 8) {
+                if (t + 4 < T) load(t + 4, vb);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(t, va);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 8 < T) load(t + 8, va);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 4 < T) compute(t + 4, vb);
+            }
+        }
+        __syncthreads();
+        for (int t = tid >> 5; t < T; t += 8) {
+            const int px = tid & 31;
+            float o0 = bias0, o1 = bias1;
+#pragma unroll
+            for (int dt = 0; dt < 3; ++dt) {
+                const int tt = t + dt - 1;
+                if (tt >= 0 && tt < T) {
+                    const float2 v = *reinterpret_cast<const float2*>(c + (tt * 32 + px) * 8 + 2 * dt);
+                    o0 += v.x;
+                    o1 += v.y;
+                }
+            }
+            if (s0 + px < a.S) {
+                const long long q = (b * T + t) * a.S + s0 + px;
+                if (a.relu_out) { o0 = fmaxf(o0, 0.f); o1 = fmaxf(o1, 0.f); }
+                if (a.add) {
+                    const float2 av = *reinterpret_cast<const float2*>(a.add + 2 * q);
+                    o0 += av.x;
+                    o1 += av.y;
+                }
+                *reinterpret_cast<float2*>(a.out + 2 * q) = make_float2(o0, o1);
+            }
+        }
+        __syncthreads();   // the next tile overwrites c
+    }
+}
+
+// 0: not covered; 1: 3x3 in the plane; 2: 3x3x3 (outer axis = depth); 3: 3x1x1 on tiles that span all frames (as a
+// loop over three planes of an 8 x 32 tile it re-read every input three times and was slower than the lane-per-pixel
+// kernel, 125 against 97 us).
 static int thin_out_mfma_shape(const PixDims& d, int K, bool bf) {
     static const bool on = [] {   // GLEAM_NO_THIN_MFMA=1 keeps the lane-per-pixel kernel for comparison
         const char* e = getenv("GLEAM_NO_THIN_MFMA");
@@ -201,6 +299,7 @@ static int thin_out_mfma_shape(const PixDims& d, int K, bool bf) {
     if (!on) return 0;
     if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) return (bf ? (K == 64 || K == 128) : (K == 32 || K == 64 || K == 128)) ? 1 : 0;
     if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) return (!bf && (K == 32 || K == 64)) ? 2 : 0;
+    if (d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1) return (!bf && (K == 32 || K == 64) && d.T <= kTOTimeMaxT) ? 3 : 0;
     return 0;
 }
 
@@ -221,6 +320,19 @@ hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const flo
                                      int relu_in, int relu_out, const PixDims& d, bool bf, hipStream_t st) {
     const int shape = thin_out_mfma_shape(d, K, bf);
     if (shape == 0) return hipErrorInvalidValue;
+    if (shape == 3) {
+        ThinOutTimeArgs t{};
+        t.in = reinterpret_cast<const float*>(in); t.wts = wts; t.bias = bias; t.add = add; t.out = out;
+        t.relu_in = relu_in; t.relu_out = relu_out; t.T = d.T;
+        t.S = (long long)d.D * d.H * d.W;
+        t.segs = (int)((t.S + 31) / 32);
+        t.n_blocks = d.Q / ((long long)d.T * t.S) * t.segs;
+        const long long cap = 256LL * 3;
+        const long long gx = ((t.n_blocks < cap ? t.n_blocks : cap) + 7) / 8 * 8;
+        if (K == 32) hipLaunchKernelGGL((conv_thin_out_time_mfma_kernel<32>), dim3((unsigned)gx), dim3(256), 0, st, t);
+        else hipLaunchKernelGGL((conv_thin_out_time_mfma_kernel<64>), dim3((unsigned)gx), dim3(256), 0, st, t);
+        return hipGetLastError();
+    }
     ThinOutMfmaArgs a{};
     a.in = in; a.wts = wts; a.bias = bias; a.add = add; a.out = out;
     a.relu_in = relu_in; a.relu_out = relu_out; a.H = d.H; a.W = d.W;

@@ -92,6 +92,8 @@ def module_cases():
     yield "thin_out_128", synth.Geom(2, 1, 2, 1, 1, 10, 46), synth.chain_prox([2, 32, 128, 2], [K2] * 3), 0
     yield "thin_out_32", synth.Geom(2, 2, 2, 1, 1, 6, 20), synth.chain_prox([2, 128, 32, 2], [K2] * 3), 0
     yield "thin_vol64", synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 64, 64, 2], [K3] * 3), 0
+    yield "thin_time32", synth.Geom(2, 2, 2, 5, 1, 6, 10), synth.chain_prox([2, 32, 2], [KS, KT]), 0
+    yield "thin_time64_l1", synth.Geom(2, 1, 2, 3, 1, 6, 46), synth.chain_prox([2, 64, 2], [KS, KT], has_bias=0), 1
     yield "thin_vol128_flat", synth.Geom(3, 1, 2, 1, 4, 6, 46), synth.chain_prox([2, 128, 32, 2], [K3, (1, 1, 1, 1), K3], has_bias=0), 1
 
 
