@@ -696,8 +696,8 @@ __global__ __launch_bounds__(256) void conv_thin_in_kernel(ConvThinInArgs ta) {
     }
 }
 
-// Convolution whose OUTPUT has two channels (last layer forward): K wide -> 2.  HBM-bound on its input,
-// so no MFMA.  A tile is 64 neighbouring pixels of one image row, one lane each.  The input rows of every
+// Convolution whose OUTPUT has two channels (last layer forward): K wide -> 2, for the shapes the matrix-core
+// kernels of prox_thin.hip do not cover.  HBM-bound on its input, vector ALUs only.  A tile is 64 neighbouring pixels of one image row, one lane each.  The input rows of every
 // row tap are staged in LDS (KC channels per round, zero outside the grid, ReLU applied), pixel stride
 // KC + 4 floats so that 16-byte reads of neighbouring lanes do not collide.  Work items (row tap,
 // 16-channel chunk) are dealt to the four waves; the two output channels' weights of an item are
@@ -1093,12 +1093,12 @@ static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw,
 
 static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scratch, hipStream_t st, const float* wino_u = nullptr) {
     const int taps_ = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
-    {   // two input channels and a wide output: HBM-bound kernel without MFMA
+    {   // two input channels and a wide output: HBM-bound kernels (matrix cores for 3x3x3 taps, vector ALUs otherwise)
         bool hit = false;
         const hipError_t e = launch_conv_thin_in(a, cw, false, &hit, st);
         if (hit || e != hipSuccess) return e;
     }
-    {   // two output channels and a wide input (forward): HBM-bound kernel without MFMA
+    {   // two output channels and a wide input (forward): HBM-bound kernels (prox_thin.hip where it has the shape)
         bool hit = false;
         const hipError_t e = launch_conv_thin_out(a, cw, false, wt_scratch, &hit, st);
         if (hit || e != hipSuccess) return e;
