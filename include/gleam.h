@@ -99,6 +99,22 @@ int gleam_fft_size_supported(int64_t n);
 int gleam_sense_normal(const gleam_geom* geom, const gleam_c64* x, const gleam_c64* S, const uint8_t* M,
                        gleam_c64* out, void* ws, size_t ws_bytes, void* stream);
 
+/* gleam_sense_normal for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results, but the coil k-space buffer is a device array of GLEAM_STATIC_SCRATCH_BYTES that the library holds at
+ * file scope (one copy per GPU, resident from the moment the library is loaded on that GPU until the process
+ * ends).  The call allocates and frees nothing on the device or through any allocating library routine; the
+ * first call on a device looks up the array's address there (a runtime symbol query, not an allocation).
+ *   - Geometries whose k-space B*C*T*D*H*W*8 bytes exceeds GLEAM_STATIC_SCRATCH_BYTES return GLEAM_E_WORKSPACE
+ *     (ndim_fft = 1 uses no buffer but is held to the same limit).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *     threads) race; order them on one stream.  Nothing needs clearing between calls: the first sweep of a call
+ *     writes every element the later sweeps read.
+ *   - With gleam_profile_begin active the per-launch bracketing creates HIP events; leave it off for such callers. */
+#define GLEAM_STATIC_SCRATCH_BYTES (64u << 20)
+int gleam_sense_normal_static(const gleam_geom* geom, const gleam_c64* x, const gleam_c64* S, const uint8_t* M,
+                              gleam_c64* out, void* stream);
+
 /* Forward pass of one module, x_out = f_theta(DC(x_in)) (Eq. 3-5; Alg. 1, forward step).
  *   x_ref  : fully sampled reference image, or NULL for inference (then `loss` and `saved` may be NULL
  *            and no backward pass may follow).

@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
         L.gleam_theta_count.argtypes = [pp, C.POINTER(sz)]
         L.gleam_workspace_bytes.argtypes = [pg, pp, C.POINTER(sz), C.POINTER(sz)]
         L.gleam_sense_normal.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
+        L.gleam_sense_normal_static.argtypes = [pg, vp, vp, vp, vp, vp]
         L.gleam_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_module_bwd.argtypes = [pg, pp, vp, vp, sz, vp, vp, sz, vp]
         L.gleam_module_bwd_alpha.argtypes = [pg, pp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, sz, vp]
@@ -91,7 +92,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
-           "gleam_sense_normal", "gleam_module_fwd", "gleam_module_bwd", "gleam_module_bwd_alpha", "gleam_deep_workspace_bytes",
+           "gleam_sense_normal", "gleam_sense_normal_static", "gleam_module_fwd", "gleam_module_bwd", "gleam_module_bwd_alpha", "gleam_deep_workspace_bytes",
            "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_sense_adjoint", "gleam_modl_workspace_bytes",
            "gleam_modl_module_fwd", "gleam_modl_module_bwd", "gleam_adam_step",
            "gleam_greedy_iteration", "gleam_unrolled_infer", "gleam_profile_begin", "gleam_profile_end")
@@ -165,6 +166,14 @@ def gleam_workspace_bytes(geom: gleam_geom, prox: Optional[gleam_prox_desc]):
 def gleam_sense_normal(geom, x, S, M, out, ws, stream=None):
     _check(lib().gleam_sense_normal(C.byref(geom), _ptr(x), _ptr(S), _ptr(M), _ptr(out), _ptr(ws), _nbytes(ws),
                                     _stream(stream)), "gleam_sense_normal")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20   # GLEAM_STATIC_SCRATCH_BYTES of include/gleam.h
+
+
+def gleam_sense_normal_static(geom, x, S, M, out, stream=None):
+    _check(lib().gleam_sense_normal_static(C.byref(geom), _ptr(x), _ptr(S), _ptr(M), _ptr(out), _stream(stream)),
+           "gleam_sense_normal_static")
 
 
 def gleam_module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref, x_out, loss, saved, ws, stream=None):

@@ -6,6 +6,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "internal.h"
@@ -37,7 +38,29 @@ void prof_end(hipStream_t st) {
 }
 }  // namespace gleam
 
+// Coil k-space buffer of gleam_sense_normal_static: file-scope device memory, one copy per GPU, held until the
+// process ends.  Host code never uses the array's name as an address; static_scratch() asks the runtime for
+// the address of the current device's copy once and hands that pointer to the kernels.
+static __device__ __align__(256) unsigned char scratch[GLEAM_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device), or null.
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -178,6 +201,21 @@ int gleam_sense_normal(const gleam_geom* geom, const gleam_c64* x, const gleam_c
     if (!aligned(ws) || ws_bytes < n_coil_pixels(*geom) * sizeof(float2)) return GLEAM_E_WORKSPACE;
     hipError_t e = sense_dc(*geom, (const float2*)x, (const float2*)S, M, nullptr, 0.f, 1.f, (float2*)out,
                             (float2*)ws, (hipStream_t)stream);
+    return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+int gleam_sense_normal_static(const gleam_geom* geom, const gleam_c64* x, const gleam_c64* S, const uint8_t* M,
+                              gleam_c64* out, void* stream) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    if (!x || !S || !M || !out) return GLEAM_E_NULL;
+    if (n_coil_pixels(*geom) * sizeof(float2) > (size_t)GLEAM_STATIC_SCRATCH_BYTES) return GLEAM_E_WORKSPACE;
+    void* kbuf = static_scratch();
+    if (!kbuf) return GLEAM_E_LAUNCH;
+    // every k-space element the later sweeps read is written by the first sweep of the same call, so nothing
+    // of the previous call's contents has to be cleared
+    hipError_t e = sense_dc(*geom, (const float2*)x, (const float2*)S, M, nullptr, 0.f, 1.f, (float2*)out,
+                            (float2*)kbuf, (hipStream_t)stream);
     return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
 }
 
