@@ -23,7 +23,8 @@
  *     An image is also the prox network's 2-channel real tensor (channels-last: re, im).
  *   - theta / grad_theta: flat float32, per layer W[cout][kt][kd][kh][kw][cin] then b[cout] if has_bias.
  *   - Return value: 0 (GLEAM_OK) or a negative gleam_status.  Arguments are validated on the host before
- *     anything is launched; on error nothing has been enqueued.
+ *     anything is launched, in the entry points that run several modules as well: on any error other than
+ *     GLEAM_E_LAUNCH nothing has been enqueued and no buffer has been written.
  *   - `ws` is scratch the call may overwrite freely; `saved` carries activations from gleam_module_fwd to
  *     gleam_module_bwd and may be reused for the next module afterwards (activations of a finished module
  *     are discarded, as in Alg. 1).  Both must be 256-byte aligned.  Sizes come from gleam_workspace_bytes.
@@ -91,6 +92,22 @@ int gleam_workspace_bytes(const gleam_geom* geom, const gleam_prox_desc* prox,
 /* Number of float32 parameters of the prox (length of theta and grad_theta).  Host-only. */
 int gleam_theta_count(const gleam_prox_desc* prox, size_t* n_floats);
 
+/* Kernel-selection policy.  Several layer shapes have two kernels: the fastest one, which every call uses by
+ * default (policy 0), and the kernel it replaced, kept for A/B timing and as a second implementation for the
+ * parity tests.  The policy is one process-wide word (the library reads nothing from the environment); it is
+ * read when a call plans and enqueues its work, so set it before the first call of a forward / backward pair
+ * and leave it alone until that pair is done: `saved` of a forward call is only valid for a backward call made
+ * under the same policy (the Winograd and 2D-tile bf16 kernels hand ReLU masks over as sign words), and
+ * gleam_workspace_bytes must be asked under the policy the calls will run with.  Not synchronised with calls in
+ * flight on other threads.  Unknown bits: GLEAM_E_DESC. */
+#define GLEAM_POLICY_NO_WINOGRAD      1u  /* 3x3 fp32 layers with 64-multiples of channels: direct MFMA kernels         */
+#define GLEAM_POLICY_NO_BF16_2D       2u  /* 3x3 bf16 layers: flattened-pixel kernel instead of the 2D-tile one        */
+#define GLEAM_POLICY_NO_THIN_MFMA     4u  /* 2-channel first / last layers: vector-ALU kernels instead of matrix-core   */
+#define GLEAM_POLICY_NO_WGRAD_BALANCE 8u  /* 27-tap weight gradient: nine 3-tap jobs instead of the balanced 8-wave split */
+#define GLEAM_POLICY_ALL              15u
+int gleam_set_kernel_policy(uint32_t policy);
+uint32_t gleam_get_kernel_policy(void);
+
 /* 1 if a transform of length n has a kernel, else 0.  Host-only. */
 int gleam_fft_size_supported(int64_t n);
 
@@ -150,7 +167,10 @@ int gleam_module_bwd_alpha(const gleam_geom* geom, const gleam_prox_desc* prox, 
  * The local loss is backpropagated inside the module, through its prox networks and data-consistency steps
  * (dL/dx_{j-1} = g - alpha A^H A g with g = dL/du_j), and not beyond the module input.
  *   theta / grad_theta : [n_iter][n_theta] float32.
- *   saved              : n_iter blocks, sized by gleam_deep_workspace_bytes; written by both calls.
+ *   saved              : n_iter equal blocks (saved_bytes / n_iter each), sized by gleam_deep_workspace_bytes;
+ *                        written by both calls.  After gleam_deep_module_bwd, block j (0-based, j >= 1) begins
+ *                        with dL/du_j, the gradient at the prox input of iteration j+1: B*T*D*H*W complex64
+ *                        (float32 at every hand-off between iterations, also with dtype = 1).
  *   x_out, x_tmp       : final image and one image of scratch (must not alias x_in or each other).
  * Requires a prox whose first layer has relu_in = 0 and at most one layer taking its skip from the input
  * when n_iter > 1 (else GLEAM_E_DESC).  n_iter = 1 is gleam_module_fwd / gleam_module_bwd. */
@@ -239,11 +259,15 @@ int gleam_unrolled_infer(const gleam_geom* geom, const gleam_prox_desc* prox, in
  * this library launches is bracketed by HIP events on the caller's stream.  gleam_profile_end synchronises
  * the device and copies up to `capacity` per-launch records (launch order) to the HOST array `out`;
  * *n_records receives the number of launches seen.  `flops` / `bytes` are the algorithmic work of the launch
- * (padding and re-reads not counted).  Not thread-safe; leave it off in production. */
+ * (padding and re-reads not counted; a convolution counts 2 * taps * cin * cout per pixel whatever the kernel);
+ * `mfma_flops` is what the launch issues on the matrix cores: equal to `flops` for the direct kernels, 4/9 of it
+ * for the Winograd F(2x2,3x3) kernels, so mfma_flops / time never exceeds the matrix-core peak.
+ * Not thread-safe; leave it off in production. */
 typedef struct {
     char name[56];
     double flops;
     double bytes;
+    double mfma_flops;
     float ms;
 } gleam_kernel_record;
 int gleam_profile_begin(void);

@@ -28,6 +28,13 @@ product.  Everything is float64 / complex128 numpy, written as the plain definit
                detached output of module m is the input of module m + 1
   * Adam     : Kingma & Ba's update with bias correction (the optimizer the paper names)
 
+  * bf16     : the same prox with the library's bfloat16 rounding points (the paper does not state a precision;
+               this is the reading the bf16 configuration is built to): the stored activations t_1..t_{L-1} and the
+               stored gradients G_1..G_{L-1} are rounded to bfloat16 (nearest even), and so are a layer's weights
+               wherever they multiply such a tensor (forward pass of every layer but the first, data gradient of
+               every layer but the last); everything else stays exact.  The ReLU masks are then decided from the rounded activations, as on the device, so
+               that the two sides take that 0/1 decision in the same precision.  Off by default.
+
 Pins (tests/test_oracle_*.py): numpy.fft and closed forms for the DFT, the adjoint identity, the
 full-sampling identity A^H A = I, circular-convolution form of a single-coil 1D mask, scipy
 correlate and torch CPU convolutions for the prox, central finite differences and torch autograd
@@ -168,6 +175,14 @@ def conv_wgrad(g, a, k):
 
 
 # ----------------------------------------------------------------------------- prox network
+def round_bf16(a):
+    """Nearest-even rounding of float32(a) to bfloat16 (8 bits of significand), returned as float64."""
+    x = np.ascontiguousarray(np.asarray(a, np.float64).astype(np.float32))
+    bits = x.view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).reshape(x.shape).astype(np.float64)
+
+
 def split_theta(layers, theta):
     """Views (w, b) per layer out of the flat parameter vector: per layer
     w[cout][kt][kd][kh][kw][cin] then b[cout] when the layer has a bias."""
@@ -195,22 +210,37 @@ def channels_to_complex(a):
     return a[..., 0] + 1j * a[..., 1]
 
 
-def prox_fwd(layers, theta, u):
+def _weights_bf16(params, keep_exact):
+    """Weights rounded to bfloat16 wherever they multiply a bfloat16 tensor: every layer but `keep_exact`, whose other
+    operand is float32 (the first layer's input u going forward, the last layer's incoming gradient going back)."""
+    return [(w if i == keep_exact else round_bf16(w), b) for i, (w, b) in enumerate(params)]
+
+
+def prox_fwd(layers, theta, u, bf16_points=False):
     """Tensors t_0 = u (2 channels) ... t_L = z, and per layer the conv input and the value
-    before the skip add (needed for the ReLU derivatives)."""
+    before the skip add (needed for the ReLU derivatives).  With bf16_points the weights of every layer but the first
+    and every stored interior tensor t_1..t_{L-1} (after bias, ReLU and skip add) are rounded to bfloat16."""
     params = split_theta(layers, theta)
+    if bf16_points:
+        params = _weights_bf16(params, keep_exact=0)
+    L = len(layers)
     t = [complex_to_channels(u)]
     conv_in, act = [], []
-    for l, (w, b) in zip(layers, params):
+    for i, (l, (w, b)) in enumerate(zip(layers, params)):
         a = t[-1]
         if l.relu_in:
             a = np.maximum(a, 0.0)
         v = conv_fwd(a, w, b)
         if l.relu_out:
             v = np.maximum(v, 0.0)
+        out = v + t[l.skip_src] if l.skip_src >= 0 else v
+        if bf16_points and i < L - 1:
+            out = round_bf16(out)
+            if l.skip_src < 0:
+                v = out              # the ReLU mask of this layer is read off the stored value
         conv_in.append(a)
         act.append(v)
-        t.append(v + t[l.skip_src] if l.skip_src >= 0 else v)
+        t.append(out)
     return t, conv_in, act
 
 
@@ -226,11 +256,16 @@ def loss_and_grad(z, x_ref, loss_kind):
     return float(mag.sum() / n), complex_to_channels(np.where(mag > 0, d / safe, 0.0) / n)
 
 
-def prox_bwd(layers, theta, t, conv_in, act, g_z, want_input_grad=False):
+def prox_bwd(layers, theta, t, conv_in, act, g_z, want_input_grad=False, bf16_points=False):
     """dL/dtheta (flat, same layout as theta) from dL/dz.  The gradient reaching t_0 = u is dropped (modules
     are decoupled) unless want_input_grad, which returns (dL/dtheta, dL/du as 2 real channels): a module
-    that holds several unrolled iterations backpropagates through its own iterations."""
+    that holds several unrolled iterations backpropagates through its own iterations.  With bf16_points (t, conv_in
+    and act then come from prox_fwd with the same flag) the weights of every layer but the last, as the data gradient
+    uses them, and every stored interior gradient G_1..G_{L-1} (complete: data gradient plus skip gradient) are
+    rounded to bfloat16."""
     params = split_theta(layers, theta)
+    if bf16_points:
+        params = _weights_bf16(params, keep_exact=len(layers) - 1)
     L = len(layers)
     G = [None] * (L + 1)
     G[L] = g_z
@@ -241,6 +276,8 @@ def prox_bwd(layers, theta, t, conv_in, act, g_z, want_input_grad=False):
         g = G[i + 1]
         if g is None:
             g = np.zeros_like(act[i])
+        elif bf16_points and i + 1 < L:
+            g = round_bf16(g)        # every contribution has arrived by now: one rounding of the stored tensor
         if l.skip_src >= 0:
             s = l.skip_src
             G[s] = g if G[s] is None else G[s] + g
@@ -263,13 +300,14 @@ def prox_bwd(layers, theta, t, conv_in, act, g_z, want_input_grad=False):
 
 
 # ----------------------------------------------------------------------------- module
-def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None):
+def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None, bf16_points=False):
     """x_out = f_theta(DC(x_in)); loss against x_ref when given.  Returns a dict holding
     everything module_bwd needs."""
     u = dc_step(x_in, S, M, y, alpha, geom.ndim_fft)
-    t, conv_in, act = prox_fwd(prox.layers, theta, u)
+    t, conv_in, act = prox_fwd(prox.layers, theta, u, bf16_points)
     z = channels_to_complex(t[-1])
-    out = {"u": u, "x_out": z, "t": t, "conv_in": conv_in, "act": act, "loss": None, "g_z": None}
+    out = {"u": u, "x_out": z, "t": t, "conv_in": conv_in, "act": act, "loss": None, "g_z": None,
+           "bf16_points": bf16_points}
     if x_ref is not None:
         out["loss"], out["g_z"] = loss_and_grad(z, x_ref, prox.loss_kind)
     return out
@@ -277,7 +315,8 @@ def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None):
 
 def module_bwd(prox, theta, fwd):
     """dL/dtheta_m of the local objective; stops at the module input."""
-    return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"])
+    return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"],
+                    bf16_points=fwd.get("bf16_points", False))
 
 
 def module_bwd_alpha(geom, prox, x_in, S, M, y, theta, fwd):
@@ -290,14 +329,14 @@ def module_bwd_alpha(geom, prox, x_in, S, M, y, theta, fwd):
 
 
 # ----------------------------------------------------------------------------- module of several iterations
-def deep_module_fwd(geom, prox, x_in, S, M, y, alpha, thetas, x_ref=None):
+def deep_module_fwd(geom, prox, x_in, S, M, y, alpha, thetas, x_ref=None, bf16_points=False):
     """A module that holds K = N/M unrolled iterations (GLEAM section, N > M): x_j = f_theta_j(DC(x_{j-1})),
     j = 1..K, with the local loss on x_K only.  Returns the per-iteration forward records."""
     x = np.asarray(x_in, np.complex128)
     recs = []
     for j, th in enumerate(thetas):
         last = j == len(thetas) - 1
-        recs.append(module_fwd(geom, prox, x, S, M, y, alpha, th, x_ref if last else None))
+        recs.append(module_fwd(geom, prox, x, S, M, y, alpha, th, x_ref if last else None, bf16_points))
         x = recs[-1]["x_out"]
     return {"x_out": x, "loss": recs[-1]["loss"], "iters": recs}
 
@@ -310,12 +349,14 @@ def deep_module_bwd(geom, prox, S, M, alpha, thetas, fwd):
     K = len(thetas)
     grads = [None] * K
     g_out = fwd["iters"][-1]["g_z"]
+    bf = fwd["iters"][-1].get("bf16_points", False)   # the hand-off between iterations stays exact either way
     for j in range(K - 1, -1, -1):
         r = fwd["iters"][j]
         if j == 0:
-            grads[j] = prox_bwd(prox.layers, thetas[j], r["t"], r["conv_in"], r["act"], g_out)
+            grads[j] = prox_bwd(prox.layers, thetas[j], r["t"], r["conv_in"], r["act"], g_out, bf16_points=bf)
         else:
-            grads[j], g_u = prox_bwd(prox.layers, thetas[j], r["t"], r["conv_in"], r["act"], g_out, want_input_grad=True)
+            grads[j], g_u = prox_bwd(prox.layers, thetas[j], r["t"], r["conv_in"], r["act"], g_out, want_input_grad=True,
+                                     bf16_points=bf)
             gc = channels_to_complex(g_u)
             g_out = complex_to_channels(gc - alpha * sense_normal(gc, S, M, geom.ndim_fft))
     return grads

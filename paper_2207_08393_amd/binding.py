@@ -38,7 +38,8 @@ class gleam_prox_desc(C.Structure):
 
 
 class gleam_kernel_record(C.Structure):
-    _fields_ = [("name", C.c_char * 56), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
+    _fields_ = [("name", C.c_char * 56), ("flops", C.c_double), ("bytes", C.c_double), ("mfma_flops", C.c_double),
+                ("ms", C.c_float)]
 
 
 class gleam_adam(C.Structure):
@@ -67,6 +68,9 @@ def lib() -> C.CDLL:
         L.gleam_strerror.restype = C.c_char_p
         L.gleam_strerror.argtypes = [C.c_int]
         L.gleam_fft_size_supported.argtypes = [C.c_int64]
+        L.gleam_set_kernel_policy.argtypes = [C.c_uint32]
+        L.gleam_get_kernel_policy.argtypes = []
+        L.gleam_get_kernel_policy.restype = C.c_uint32
         L.gleam_theta_count.argtypes = [pp, C.POINTER(sz)]
         L.gleam_workspace_bytes.argtypes = [pg, pp, C.POINTER(sz), C.POINTER(sz)]
         L.gleam_sense_normal.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
@@ -91,7 +95,7 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_theta_count", "gleam_workspace_bytes",
+EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_set_kernel_policy", "gleam_get_kernel_policy", "gleam_theta_count", "gleam_workspace_bytes",
            "gleam_sense_normal", "gleam_sense_normal_static", "gleam_module_fwd", "gleam_module_bwd", "gleam_module_bwd_alpha", "gleam_deep_workspace_bytes",
            "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_sense_adjoint", "gleam_modl_workspace_bytes",
            "gleam_modl_module_fwd", "gleam_modl_module_bwd", "gleam_adam_step",
@@ -144,6 +148,17 @@ def _stream(stream) -> Optional[int]:
 def _check(rc: int, where: str):
     if rc != GLEAM_OK:
         raise GleamError(rc, where)
+
+
+POLICY_NO_WINOGRAD, POLICY_NO_BF16_2D, POLICY_NO_THIN_MFMA, POLICY_NO_WGRAD_BALANCE = 1, 2, 4, 8
+
+
+def gleam_set_kernel_policy(policy: int):
+    _check(lib().gleam_set_kernel_policy(int(policy)), "gleam_set_kernel_policy")
+
+
+def gleam_get_kernel_policy() -> int:
+    return int(lib().gleam_get_kernel_policy())
 
 
 def gleam_fft_size_supported(n: int) -> bool:
@@ -266,8 +281,9 @@ def gleam_profile_begin():
 
 
 def gleam_profile_end(capacity: int = 65536):
-    """Returns a list of (name, flops, bytes, ms), one per kernel launch since gleam_profile_begin."""
+    """Returns a list of (name, flops, bytes, ms, mfma_flops), one per kernel launch since gleam_profile_begin."""
     arr = (gleam_kernel_record * capacity)()
     n = C.c_int(0)
     _check(lib().gleam_profile_end(arr, capacity, C.byref(n)), "gleam_profile_end")
-    return [(arr[i].name.decode(), arr[i].flops, arr[i].bytes, arr[i].ms) for i in range(min(n.value, capacity))]
+    return [(arr[i].name.decode(), arr[i].flops, arr[i].bytes, arr[i].ms, arr[i].mfma_flops)
+            for i in range(min(n.value, capacity))]

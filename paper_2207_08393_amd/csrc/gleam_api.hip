@@ -3,6 +3,7 @@
 // enqueued on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
@@ -17,18 +18,23 @@ namespace gleam {
 namespace {
 struct ProfRec {
     char name[56];
-    double flops, bytes;
+    double flops, bytes, mfma_flops;
     hipEvent_t e0, e1;
 };
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof;
 }  // namespace
+namespace {
+std::atomic<unsigned> g_policy{0u};
+}
+unsigned kernel_policy() { return g_policy.load(std::memory_order_relaxed); }
 bool prof_enabled() { return g_prof_on; }
-void prof_begin(const char* name, double flops, double bytes, hipStream_t st) {
+void prof_begin(const char* name, double flops, double bytes, double mfma_flops, hipStream_t st) {
     ProfRec r{};
     snprintf(r.name, sizeof(r.name), "%s", name);
     r.flops = flops;
     r.bytes = bytes;
+    r.mfma_flops = mfma_flops;
     if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
     (void)hipEventRecord(r.e0, st);
     g_prof.push_back(r);
@@ -113,6 +119,26 @@ int check_prox(const gleam_prox_desc* p) {
     return GLEAM_OK;
 }
 
+// Geometry, prox and buffer sizes of a plain module call, checked together so that callers which run several
+// modules can refuse bad arguments before the first launch.  `saved` may be null when need_saved is false.
+int check_module_buffers(const gleam_geom* geom, const gleam_prox_desc* prox, const void* ws, size_t ws_bytes,
+                         const void* saved, size_t saved_bytes, bool need_saved) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    rc = check_prox(prox);
+    if (rc) return rc;
+    if (!ws || (need_saved && !saved)) return GLEAM_E_NULL;
+    ProxPlan plan;
+    plan_prox(*geom, *prox, plan);
+    if (!aligned(ws) || ws_bytes < plan.ws_bytes) return GLEAM_E_WORKSPACE;
+    if (saved && (!aligned(saved) || saved_bytes < plan.saved_bytes)) return GLEAM_E_WORKSPACE;
+    return GLEAM_OK;
+}
+
+bool adam_args_ok(const gleam_adam* h, int64_t t) {
+    return t >= 1 && h->beta1 >= 0.f && h->beta1 < 1.f && h->beta2 >= 0.f && h->beta2 < 1.f && h->eps >= 0.f;
+}
+
 }  // namespace
 
 extern "C" {
@@ -149,6 +175,7 @@ int gleam_profile_end(gleam_kernel_record* out, int capacity, int* n_records) {
             memcpy(out[i].name, g_prof[i].name, sizeof(out[i].name));
             out[i].flops = g_prof[i].flops;
             out[i].bytes = g_prof[i].bytes;
+            out[i].mfma_flops = g_prof[i].mfma_flops;
             out[i].ms = ms;
         }
         (void)hipEventDestroy(g_prof[i].e0);
@@ -157,6 +184,14 @@ int gleam_profile_end(gleam_kernel_record* out, int capacity, int* n_records) {
     g_prof.clear();
     return GLEAM_OK;
 }
+
+int gleam_set_kernel_policy(uint32_t policy) {
+    if (policy & ~(uint32_t)GLEAM_POLICY_ALL) return GLEAM_E_DESC;
+    g_policy.store(policy, std::memory_order_relaxed);
+    return GLEAM_OK;
+}
+
+uint32_t gleam_get_kernel_policy(void) { return kernel_policy(); }
 
 int gleam_fft_size_supported(int64_t n) { return fft_size_supported(n) ? 1 : 0; }
 
@@ -317,8 +352,9 @@ int gleam_deep_module_fwd(const gleam_geom* geom, const gleam_prox_desc* prox, i
     size_t ws_need = 0, saved_need = 0, n_theta = 0;
     int rc = gleam_deep_workspace_bytes(geom, prox, n_iter, &ws_need, &saved_need);
     if (rc) return rc;
-    if (!x_in || !theta || !x_ref || !x_out || !x_tmp || !loss || !saved) return GLEAM_E_NULL;
+    if (!x_in || !S || !M || !y || !theta || !x_ref || !x_out || !x_tmp || !loss || !saved || !ws) return GLEAM_E_NULL;
     if (x_out == x_in || x_tmp == x_in || x_out == x_tmp) return GLEAM_E_DIMS;
+    if (!aligned(ws) || ws_bytes < ws_need) return GLEAM_E_WORKSPACE;   // all of it before the first launch
     if (!aligned(saved) || saved_bytes < saved_need) return GLEAM_E_WORKSPACE;
     rc = gleam_theta_count(prox, &n_theta);
     if (rc) return rc;
@@ -468,9 +504,7 @@ int gleam_modl_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, c
 int gleam_adam_step(const gleam_adam* hyper, int64_t t, size_t n, float* theta, const float* grad, float* m, float* v,
                     void* stream) {
     if (!hyper || !theta || !grad || !m || !v) return GLEAM_E_NULL;
-    if (t < 1 || !(hyper->beta1 >= 0.f && hyper->beta1 < 1.f) || !(hyper->beta2 >= 0.f && hyper->beta2 < 1.f) ||
-        !(hyper->eps >= 0.f))
-        return GLEAM_E_DESC;
+    if (!adam_args_ok(hyper, t)) return GLEAM_E_DESC;
     if (n == 0) return GLEAM_OK;
     const hipError_t e = adam_update(*hyper, (long long)t, n, theta, grad, m, v, (hipStream_t)stream);
     return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
@@ -484,8 +518,13 @@ int gleam_greedy_iteration(const gleam_geom* geom, const gleam_prox_desc* prox, 
     if (n_modules < 1) return GLEAM_E_DIMS;
     if (!x0 || !theta || !adam_m || !adam_v || !hyper || !x_ref || !x_out || !x_tmp || !losses || !grad) return GLEAM_E_NULL;
     if (x_out == x0 || x_tmp == x0 || x_out == x_tmp) return GLEAM_E_DIMS;
+    // everything any of the per-module calls below would refuse is refused here, before the first launch
+    if (!S || !M || !y) return GLEAM_E_NULL;
+    int rc = check_module_buffers(geom, prox, ws, ws_bytes, saved, saved_bytes, true);
+    if (rc) return rc;
+    if (!adam_args_ok(hyper, t)) return GLEAM_E_DESC;
     size_t n_theta = 0;
-    int rc = gleam_theta_count(prox, &n_theta);
+    rc = gleam_theta_count(prox, &n_theta);
     if (rc) return rc;
     const gleam_c64* x_in = x0;
     for (int i = 0; i < n_modules; ++i) {
@@ -508,10 +547,12 @@ int gleam_unrolled_infer(const gleam_geom* geom, const gleam_prox_desc* prox, in
                          const gleam_c64* S, const uint8_t* M, const gleam_c64* y, float alpha, const float* theta,
                          gleam_c64* x_out, gleam_c64* x_tmp, void* ws, size_t ws_bytes, void* stream) {
     if (n_modules < 1) return GLEAM_E_DIMS;
-    if (!x0 || !theta || !x_out || !x_tmp) return GLEAM_E_NULL;
+    if (!x0 || !theta || !x_out || !x_tmp || !S || !M || !y) return GLEAM_E_NULL;
     if (x_out == x0 || x_tmp == x0 || x_out == x_tmp) return GLEAM_E_DIMS;
+    int rc = check_module_buffers(geom, prox, ws, ws_bytes, nullptr, 0, false);   // before the first launch
+    if (rc) return rc;
     size_t n_theta = 0;
-    int rc = gleam_theta_count(prox, &n_theta);
+    rc = gleam_theta_count(prox, &n_theta);
     if (rc) return rc;
     const gleam_c64* x_in = x0;
     for (int i = 0; i < n_modules; ++i) {

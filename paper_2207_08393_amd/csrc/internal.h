@@ -14,16 +14,21 @@ constexpr int kMaxTaps = 32;  // per-pixel tap validity is kept as one 32-bit ma
 
 bool fft_size_supported(long long n);
 
+// Current kernel-selection policy (GLEAM_POLICY_* bits; see gleam_set_kernel_policy).
+unsigned kernel_policy();
+
 // Optional per-launch event bracketing (see gleam_profile_begin).  KernelScope records a start event at
 // construction and a stop event at destruction when profiling is on, and does nothing otherwise.
+// `mfma_flops`: flops the launch issues on the matrix cores; negative = the same as `flops` (the algorithmic count),
+// which holds for every direct kernel.  The Winograd kernels issue 16/36 of the direct convolution's flops.
 bool prof_enabled();
-void prof_begin(const char* name, double flops, double bytes, hipStream_t st);
+void prof_begin(const char* name, double flops, double bytes, double mfma_flops, hipStream_t st);
 void prof_end(hipStream_t st);
 struct KernelScope {
     hipStream_t st;
     bool on;
-    KernelScope(const char* name, double flops, double bytes, hipStream_t s) : st(s), on(prof_enabled()) {
-        if (on) prof_begin(name, flops, bytes, st);
+    KernelScope(const char* name, double flops, double bytes, hipStream_t s, double mfma_flops = -1.0) : st(s), on(prof_enabled()) {
+        if (on) prof_begin(name, flops, bytes, mfma_flops < 0.0 ? flops : mfma_flops, st);
     }
     ~KernelScope() {
         if (on) prof_end(st);

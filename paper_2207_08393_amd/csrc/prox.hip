@@ -965,14 +965,8 @@ static size_t conv_wimg_floats(int K, int Nn, int taps) {
     return (size_t)taps * ((K + ck - 1) / ck) * ck * ((Nn + nb - 1) / nb) * nb;
 }
 
-// The Winograd path can be switched off (GLEAM_NO_WINOGRAD=1 in the environment) to time the direct kernels.
-static bool wino_enabled() {
-    static const bool on = [] {
-        const char* e = getenv("GLEAM_NO_WINOGRAD");
-        return !(e && e[0] == '1');
-    }();
-    return on;
-}
+// The Winograd path can be switched off (GLEAM_POLICY_NO_WINOGRAD) to run the direct kernels instead.
+static bool wino_enabled() { return !(kernel_policy() & GLEAM_POLICY_NO_WINOGRAD); }
 
 template <int KT, int KD, int KH, int KW>
 static void launch_conv_thin_in_t(const ConvArgs& a, const ConvWeights& cw, bool bf, hipStream_t st) {
@@ -1041,13 +1035,16 @@ static void launch_conv_thin_out_t(const ConvThinOutArgs& t, const float* w, boo
 
 // wt[n][tap][k] = w[n*sn + tapidx*st + k*sk] (tapidx mirrored when flip), n < 2: the layout the
 // two-channel-output kernel reads, for the data gradient of a layer whose INPUT is the 2-channel image.
+// round_bf: the values are rounded to bfloat16 (kept as float32), for the kernels that multiply bfloat16 data
+// with float32 arithmetic: weights that meet bfloat16 data are bfloat16 values in every kernel.
 __global__ void thin_out_weights_kernel(const float* __restrict__ w, long long sn, long long st_, long long sk, int flip,
-                                        int taps, int K, float* __restrict__ wt) {
+                                        int taps, int K, int round_bf, float* __restrict__ wt) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= 2 * taps * K) return;
     const int k = i % K, tap = (i / K) % taps, n = i / (K * taps);
     const int tapidx = flip ? taps - 1 - tap : tap;
-    wt[i] = w[n * sn + tapidx * st_ + k * sk];
+    const float v = w[n * sn + tapidx * st_ + k * sk];
+    wt[i] = round_bf ? bf16_to_f32(f32_to_bf16(v)) : v;
 }
 
 // Launches the two-channel-output kernel when the layer fits it; *hit tells whether it did.  The forward
@@ -1059,7 +1056,11 @@ static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw,
     const PixDims& d = a.d;
     const int taps_ = d.kt * d.kd * d.kh * d.kw;
     if (!(a.Nn == 2 && a.K >= 16 && a.K % 16 == 0 && !a.mask_ref)) return hipSuccess;
-    const bool direct = !a.flip && cw.sk == 1 && cw.st == a.K && cw.sn == (long long)taps_ * a.K;
+    const bool in_place = !a.flip && cw.sk == 1 && cw.st == a.K && cw.sn == (long long)taps_ * a.K;
+    // bfloat16 data: the matrix-core kernel packs its weights to bfloat16 itself; the lane-per-pixel kernel computes
+    // in float32 and gets a rounded copy, so that the result does not depend on which of the two runs
+    const bool round_copy = bf && !conv_thin_out_mfma_applies(a.d, a.K, bf);
+    const bool direct = in_place && !round_copy;
     if (!direct && wt_scratch == nullptr) return hipSuccess;
     const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
     const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
@@ -1074,7 +1075,7 @@ static hipError_t launch_conv_thin_out(const ConvArgs& a, const ConvWeights& cw,
     if (!direct) {
         const int n = 2 * taps_ * a.K;
         hipLaunchKernelGGL(thin_out_weights_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cw.w, cw.sn, cw.st, cw.sk, a.flip,
-                           taps_, a.K, wt_scratch);
+                           taps_, a.K, round_copy ? 1 : 0, wt_scratch);
         wts = wt_scratch;
     }
     char name[56];
@@ -1980,11 +1981,13 @@ hipError_t prox_forward(const gleam_geom& g, const gleam_prox_desc& p, const Pro
             if (l == 0) {           // float32 image in, bfloat16 features out
                 bool hit = false;
                 e = launch_conv_thin_in(a, cw, true, &hit, st);
+                // cannot miss: prox_bf16_supported (checked before any launch) admits exactly the first-layer
+                // shapes conv_thin_in_applies takes, whatever the geometry
                 if (e == hipSuccess && !hit) e = hipErrorInvalidValue;
             } else {                // bfloat16 in; the last layer writes the float32 image
                 if (l == L - 1) {
                     bool hit = false;
-                    e = launch_conv_thin_out(a, cw, true, nullptr, &hit, st);
+                    e = launch_conv_thin_out(a, cw, true, reinterpret_cast<float*>((unsigned char*)ws + plan.wimg_off_fwd), &hit, st);
                     if (e != hipSuccess) return e;
                     if (hit) continue;
                 }
@@ -2114,7 +2117,7 @@ static hipError_t launch_wgrad(const WgradArgs& a, float* bias_partial, bool* bi
             const int pg12 = (kWgTM * (a.Co / 4) + 767) / 768, pa12 = (rowtaps * n_pa * (a.Ci / 4) + 767) / 768;
             const dim3 g12(n_split, 1);
             const int pg8b = (kWgTM * (a.Co / 4) + 511) / 512, pa8b = (rowtaps * n_pa * (a.Ci / 4) + 511) / 512;
-            static const bool bal_on = [] { const char* e = getenv("GLEAM_NO_WGRAD_BAL"); return !(e && e[0] == '1'); }();
+            const bool bal_on = !(kernel_policy() & GLEAM_POLICY_NO_WGRAD_BALANCE);
             if (bal_on && blocks == 1 && taps == 27 && pg8b <= 1 && pa8b <= 5) {
                 // 27 taps on one channel block: nine 3-tap jobs would put three on one SIMD and two on the others;
                 // eight waves with 4,4,4,3,3,3,3,3 taps load the SIMDs 7,7,7,6
@@ -2249,7 +2252,9 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
             {
                 char name[56];
                 snprintf(name, sizeof(name), "conv_wgrad_%dto%d_t%d", c.cin, c.cout, taps);
-                KernelScope ks(name, 2.0 * (double)d.Q * c.cin * c.cout * taps, 4.0 * (double)d.Q * (c.cin + c.cout), st);
+                // 16 instead of 36 multiplications per 2x2 pixels and channel pair run on the matrix cores
+                KernelScope ks(name, 2.0 * (double)d.Q * c.cin * c.cout * taps, 4.0 * (double)d.Q * (c.cin + c.cout), st,
+                               2.0 * (double)d.Q * c.cin * c.cout * 4);
                 e = launch_wgrad_wino(ww, wa.relu_in, plan.n_split, st);
                 if (e != hipSuccess) return e;
             }

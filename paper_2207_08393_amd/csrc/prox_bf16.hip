@@ -549,13 +549,8 @@ static bool conv_bf16_2d_applies(const ConvBf16Args& a) {
     return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && a.K % 32 == 0 && a.Nn % 64 == 0 && !a.out_f32;   // an even number of 16-channel chunks
 }
 
-static bool bf16_2d_enabled() {   // GLEAM_NO_BF16_2D=1 keeps the flattened-pixel kernel for comparison
-    static const bool on = [] {
-        const char* e = getenv("GLEAM_NO_BF16_2D");
-        return !(e && e[0] == '1');
-    }();
-    return on;
-}
+// GLEAM_POLICY_NO_BF16_2D keeps the flattened-pixel kernel
+static bool bf16_2d_enabled() { return !(kernel_policy() & GLEAM_POLICY_NO_BF16_2D); }
 
 bool conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn) {
     ConvBf16Args a{};

@@ -292,10 +292,7 @@ __global__ __launch_bounds__(256) void conv_thin_out_time_mfma_kernel(ThinOutTim
 // loop over three planes of an 8 x 32 tile it re-read every input three times and was slower than the lane-per-pixel
 // kernel, 125 against 97 us).
 static int thin_out_mfma_shape(const PixDims& d, int K, bool bf) {
-    static const bool on = [] {   // GLEAM_NO_THIN_MFMA=1 keeps the lane-per-pixel kernel for comparison
-        const char* e = getenv("GLEAM_NO_THIN_MFMA");
-        return !(e && e[0] == '1');
-    }();
+    const bool on = !(kernel_policy() & GLEAM_POLICY_NO_THIN_MFMA);   // else the lane-per-pixel kernel
     if (!on) return 0;
     if (d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3) return (bf ? (K == 64 || K == 128) : (K == 32 || K == 64 || K == 128)) ? 1 : 0;
     if (d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3) return (!bf && (K == 32 || K == 64)) ? 2 : 0;
@@ -513,10 +510,7 @@ static void launch_thin_in_mfma_n(const ThinInMfmaArgs& a, hipStream_t st) {
 }
 
 bool conv_thin_in_mfma_applies(const PixDims& d, int Nn) {
-    static const bool on = [] {   // GLEAM_NO_THIN_MFMA=1 keeps the vector-ALU kernel for comparison
-        const char* e = getenv("GLEAM_NO_THIN_MFMA");
-        return !(e && e[0] == '1');
-    }();
+    const bool on = !(kernel_policy() & GLEAM_POLICY_NO_THIN_MFMA);   // else the vector-ALU kernel
     // 3x3 layers in the plane stay on the vector-ALU kernel: with 18 multiply-adds per output it already runs at the
     // speed of its stores (knee: 38 against 40 us forward, 54 against 54 us data gradient; brain, bfloat16 output:
     // 116 against 96 us forward, 231 against 265 us data gradient); with 54 it does not

@@ -658,7 +658,8 @@ hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long 
     const long long gx = ((a.n_blocks < cap ? a.n_blocks : cap) + 7) / 8 * 8;
     dim3 grid((unsigned)gx, (unsigned)(a.Nn / 64));
     const double Q = (double)a.NI * a.H * a.W;
-    KernelScope ks(name, 2.0 * Q * a.K * a.Nn * 9, 4.0 * Q * (a.K + a.Nn), st);
+    // F(2x2, 3x3): 16 multiplications per 2x2 outputs and channel pair on the matrix cores instead of the 36 of the definition
+    KernelScope ks(name, 2.0 * Q * a.K * a.Nn * 9, 4.0 * Q * (a.K + a.Nn), st, 2.0 * Q * a.K * a.Nn * 4);
     if (relu_in) hipLaunchKernelGGL((conv_wino_kernel<true>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((conv_wino_kernel<false>), grid, dim3(256), 0, st, a);
     return hipGetLastError();

@@ -140,8 +140,18 @@ def test_greedy_entry_points_reject_bad_arguments_before_launch():
     assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_DIMS
     a = list(args); a[15] = xo          # scratch image aliases the output
     assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_DIMS
-    a = list(args); a[21] = ws - 256    # short workspace is caught by the first module before any launch
+    a = list(args); a[21] = ws - 256    # short workspace: refused before any launch
     assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(args); a[19] = saved - 256
+    assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_WORKSPACE
+    # what the Adam update of module 1 would refuse is refused up front too, not after module 1 has run
+    a = list(args); a[12] = 0
+    assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_DESC
+    a = list(args); a[11] = C.byref(bad)
+    assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_DESC
+    for i in (4, 5, 6):
+        a = list(args); a[i] = None
+        assert L.gleam_greedy_iteration(*a) == gb.GLEAM_E_NULL, i
     iargs = [C.byref(geom), C.byref(prox), 2, x0, fake, fake, fake, C.c_float(1.0), fake, xo, xt, fake, ws, None]
     a = list(iargs); a[2] = -1
     assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_DIMS
@@ -149,6 +159,10 @@ def test_greedy_entry_points_reject_bad_arguments_before_launch():
     assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_NULL
     a = list(iargs); a[9] = x0
     assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_DIMS
+    a = list(iargs); a[12] = ws - 256
+    assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(iargs); a[5] = None
+    assert L.gleam_unrolled_infer(*a) == gb.GLEAM_E_NULL
 
 
 def test_deep_module_entry_points_reject_bad_arguments_before_launch():
@@ -185,6 +199,11 @@ def test_deep_module_entry_points_reject_bad_arguments_before_launch():
     assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_DIMS
     a = list(fargs); a[14] = saved - 256
     assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_WORKSPACE
+    a = list(fargs); a[16] = ws - 256
+    assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_WORKSPACE
+    for i in (4, 5, 6, 15):
+        a = list(fargs); a[i] = None
+        assert L.gleam_deep_module_fwd(*a) == gb.GLEAM_E_NULL, i
     bargs = [C.byref(geom), C.byref(prox), 2, fake, fake, C.c_float(1.0), fake, fake, saved, fake, fake, ws, None]
     for i in (3, 4, 6, 7, 9, 10):
         a = list(bargs); a[i] = None
@@ -281,3 +300,27 @@ def test_single_axis_geometry_is_accepted_and_needs_only_w_to_have_a_transform()
     assert gb.lib().gleam_workspace_bytes(C.byref(bad), C.byref(prox), C.byref(w), C.byref(s_)) == gb.GLEAM_E_UNSUPPORTED_SIZE
     bad = gb.make_geom(synth.Geom(0, 1, 2, 1, 1, 8, 8))
     assert gb.lib().gleam_workspace_bytes(C.byref(bad), C.byref(prox), C.byref(w), C.byref(s_)) == gb.GLEAM_E_DIMS
+
+
+def test_kernel_policy_is_an_explicit_process_wide_word_and_not_the_environment():
+    assert gb.gleam_get_kernel_policy() == 0                       # default: the fastest kernels
+    try:
+        gb.gleam_set_kernel_policy(gb.POLICY_NO_WINOGRAD | gb.POLICY_NO_THIN_MFMA)
+        assert gb.gleam_get_kernel_policy() == 5
+        assert _status(gb.gleam_set_kernel_policy, 16) == gb.GLEAM_E_DESC      # unknown bit
+        assert gb.gleam_get_kernel_policy() == 5                               # and nothing changed
+    finally:
+        gb.gleam_set_kernel_policy(0)
+    src = os.path.join(ROOT, "paper_2207_08393_amd", "csrc")
+    for name in os.listdir(src):
+        assert "getenv" not in open(os.path.join(src, name)).read(), name
+
+
+def test_static_scratch_entry_point_checks_on_the_host_first():
+    L = gb.lib()
+    fake = 0x1000
+    too_big = gb.make_geom(synth.Geom(2, 3, 15, 1, 1, 640, 368))               # 84.8 MB of k-space > 64 MiB
+    assert L.gleam_sense_normal_static(C.byref(too_big), fake, fake, fake, fake, None) == gb.GLEAM_E_WORKSPACE
+    assert L.gleam_sense_normal_static(C.byref(too_big), fake, None, fake, fake, None) == gb.GLEAM_E_NULL
+    bad = gb.make_geom(synth.Geom(2, 1, 2, 1, 1, 8, 7))
+    assert L.gleam_sense_normal_static(C.byref(bad), fake, fake, fake, fake, None) == gb.GLEAM_E_UNSUPPORTED_SIZE

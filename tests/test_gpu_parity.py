@@ -7,7 +7,8 @@ import torch
 from oracle import gleam_oracle as og
 from paper_2207_08393_amd import binding as gb
 from paper_2207_08393_amd import synth
-from tests.gpu_util import ModuleRunner, rel_l2, run_sense_normal
+from tests.gpu_util import (ModuleRunner, assert_close, assert_grad_close, assert_image_close, rel_l2,
+                            run_sense_normal)
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
@@ -45,8 +46,7 @@ def test_sense_normal_matches_oracle(shape):
     print("case", shape, flush=True)
     got = run_sense_normal(geom, c.x_true, c.S, c.M)
     ref = og.sense_normal(c.x_true, c.S, c.M, nd)
-    err = rel_l2(got, ref)
-    assert err <= TOL
+    assert_image_close(got, ref, TOL, "A^H A x")
 
 
 def test_sense_normal_mask_extremes_are_exact():
@@ -57,13 +57,18 @@ def test_sense_normal_mask_extremes_are_exact():
     full = run_sense_normal(geom, c.x_true, c.S, c.M)
     assert rel_l2(full, c.x_true) <= TOL                           # A^H A = I under full sampling
     # a mask with one sampled k-space point per frame: every index must land where the oracle puts it
-    for (h, w) in ((0, 0), (3, 17), (15, 23)):
+    seen = []
+    for (h, w) in ((0, 0), (3, 17), (15, 23), (8, 1), (15, 0)):
         M = np.zeros_like(c.M)
         M[..., h, w] = 1
         got = run_sense_normal(geom, c.x_true, c.S, M)
         ref = og.sense_normal(c.x_true, c.S, M, 2)
-        err = rel_l2(got, ref)
-    assert err <= TOL
+        assert_close(got, ref, TOL, f"one sampled point at ({h}, {w})")      # every point, element by element
+        # a single k-space sample is a rank-one operator per coil pair: its image is dense and differs from every
+        # other point's by far more than the tolerance, so a misplaced index cannot pass
+        for other in seen:
+            assert rel_l2(got, other) > 100 * TOL
+        seen.append(got)
     # any non-zero byte means sampled
     M7 = (c.M * 7).astype(np.uint8)
     assert np.array_equal(run_sense_normal(geom, c.x_true, c.S, M7), full)
@@ -97,7 +102,29 @@ def module_cases():
     yield "thin_vol128_flat", synth.Geom(3, 1, 2, 1, 4, 6, 46), synth.chain_prox([2, 128, 32, 2], [K3, (1, 1, 1, 1), K3], has_bias=0), 1
 
 
-def check_module(c, tol=TOL, alpha=None):
+BF16_TOL = 2e-2          # bfloat16 operands (8 significant bits), float32 accumulation, against the exact float64 oracle
+# Against the oracle run with the library's own bfloat16 rounding points, what is left is float32 against float64
+# accumulation.  A float32 sum of 10^2..10^3 products is off by a few 1e-6 relative; when that moves it across a
+# rounding boundary (spacing 2^-8..2^-7 relative, so for about 3e-6 / 5e-3 = 6e-4 of the elements) the stored value
+# differs by one spacing: a relative L2 difference of 5e-3 * sqrt(6e-4) = 1.2e-4 per stored tensor, a tenth of the
+# 2^-9 / sqrt(3) = 1.1e-3 the rounding itself causes, and a ReLU mask decided from such a value can differ.  A result
+# meets about six stored tensors: 3e-4 where the rounding-point oracle is about 3e-3 from the exact one.  The floor
+# below is ten times the float32 tolerance; a layer that the rounding moves by more than that (see assert_grad_close)
+# gets 0.15 of that movement instead.
+BF16_POINT_TOL = 1e-3
+
+
+def check_module(c, tol=None, alpha=None):
+    """One module step through the C ABI against the oracle.  float32: every output against the exact oracle at TOL, as
+    a whole, per batch sample, and per layer with weights and bias apart (on the benchmark networks the interior
+    layers hold 98 % of the parameters: one norm over the flat vector would let the two-channel layers hide), each
+    with the element-wise bound of assert_close.  bfloat16 operands: the whole outputs against the exact oracle at
+    BF16_TOL, and the per-sample / per-layer / per-element comparison against the oracle run with the same rounding
+    points at BF16_POINT_TOL (both sides then decide every ReLU mask in the same precision; against the exact oracle
+    the gradient of the first layer alone is off by 3-5e-2 in such networks, in the library and in a torch emulation
+    of the rounding points alike, because mask flips near zero do not average out of it)."""
+    bf = c.prox.dtype == 1
+    tol = (BF16_TOL if bf else TOL) if tol is None else tol
     alpha = c.alpha if alpha is None else alpha
     r = ModuleRunner(c, alpha=alpha)
     r.step()
@@ -107,6 +134,16 @@ def check_module(c, tol=TOL, alpha=None):
     errs = (rel_l2(x_out, f["x_out"]), abs(loss - f["loss"]) / abs(f["loss"]), rel_l2(grad, gref))
     print("rel errors x_out / loss / grad:", errs, flush=True)
     assert errs[0] <= tol and errs[1] <= tol and errs[2] <= tol
+    if bf:
+        fp = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, c.theta, c.x_true, bf16_points=True)
+        gp = og.module_bwd(c.prox, c.theta, fp)
+        assert abs(loss - fp["loss"]) <= BF16_POINT_TOL * abs(fp["loss"])
+        assert_image_close(x_out, fp["x_out"], BF16_POINT_TOL)
+        per_layer = assert_grad_close(c.prox, grad, gp, BF16_POINT_TOL, exact=gref)
+    else:
+        assert_image_close(x_out, f["x_out"], tol)
+        per_layer = assert_grad_close(c.prox, grad, gref, tol)
+    print("per-layer gradient errors:", {k: float(f"{v:.2e}") for k, v in per_layer.items()}, flush=True)
     return r, f
 
 
@@ -183,6 +220,28 @@ def test_config1_knee2d_full_size():
     check_module(c)
 
 
+@pytest.mark.timeout(900)
+def test_config1_knee2d_full_size_nonzero_biases_complex_l1_loss():
+    """The same workload with what the benchmark configuration leaves at zero: biases drawn N(0, 0.05^2) (so that a
+    bias that is dropped, or added to the wrong channel, moves every activation) and the complex-l1 loss the paper
+    trains with (loss_kind = 1)."""
+    c = synth.make_case(1)
+    c.theta = synth.init_theta(np.random.default_rng(77), c.prox, 0.05)
+    c.prox.loss_kind = 1
+    print("case cfg1 knee, non-zero biases, l1", flush=True)
+    check_module(c)
+
+
+@pytest.mark.timeout(600)
+def test_config4_cine2dt_full_size_without_biases_complex_l1_loss():
+    """(2+1)D workload at full size with has_bias = 0 on every layer and the complex-l1 loss."""
+    c = synth.make_case(4)
+    c.prox = synth.chain_prox([2, 64, 64, 64, 2], [KS, KT, KS, KT], has_bias=0, loss_kind=1)
+    c.theta = synth.init_theta(np.random.default_rng(78), c.prox)
+    print("case cfg4 cine, no biases, l1", flush=True)
+    check_module(c)
+
+
 @pytest.mark.timeout(600)
 def test_config4_cine2dt_full_size():
     """Dynamic 2D+t workload at full size ((2+1)D prox: 3x3x1 spatial and 1x1x3 temporal layers)."""
@@ -197,7 +256,8 @@ def test_config2_brain2d_full_size_fp32_convs():
     the float32 tolerance (its bfloat16 mode is test_config2_brain2d_full_size_bf16)."""
     c = synth.make_case(2)
     c.prox.dtype = 0
-    print("case cfg2 brain, fp32 convs", flush=True)
+    c.theta = synth.init_theta(np.random.default_rng(79), c.prox, 0.05)      # non-zero biases
+    print("case cfg2 brain, fp32 convs, non-zero biases", flush=True)
     check_module(c)
 
 
@@ -207,9 +267,6 @@ def test_config3_vol3d_full_size():
     c = synth.make_case(3)
     print("case cfg3 vol3d", flush=True)
     check_module(c)
-
-
-BF16_TOL = 2e-2   # bfloat16 operands (8 mantissa bits), float32 accumulation; oracle stays float64
 
 
 def bf16_cases():
@@ -293,13 +350,46 @@ def test_greedy_iteration_and_inference_match_oracle(n_modules):
         assert np.allclose(ls, losses, rtol=TOL)
         # parameters move by ~lr per step: compare the accumulated update as well as the parameters
         assert rel_l2(th, np.stack(ref_t)) <= TOL
-        assert rel_l2(m, np.stack(ref_m)) <= 10 * TOL and rel_l2(v, np.stack(ref_v)) <= 10 * TOL
+        # the first moment is linear in the gradients seen so far (tolerance of the gradient itself), the second
+        # quadratic (twice that), module by module and layer by layer
+        for i in range(n_modules):
+            assert_grad_close(c.prox, m[i], ref_m[i], TOL, f"Adam m, module {i + 1}")
+            assert_grad_close(c.prox, v[i], ref_v[i], 2 * TOL, f"Adam v, module {i + 1}")
         upd = th - np.stack(thetas)
         ref_upd = np.stack(ref_t) - np.stack([a.astype(np.float64) for a in thetas])
         assert rel_l2(upd, ref_upd) <= 2e-3          # first steps are ~lr*sign(g): tiny gradients may flip
     for depth in range(1, n_modules + 1):            # early exit at any depth
         xi = r.infer(depth)
         assert rel_l2(xi, og.unrolled_inference(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, ref_t[:depth])) <= TOL
+
+
+
+
+@pytest.mark.timeout(900)
+def test_greedy_iteration_knee2d_full_size():
+    """One greedy iteration (Alg. 1) over two modules at the knee workload's full size: the persistent, XCD-range and
+    split-K paths run with their real work counts, the second module starts from the first one's detached output."""
+    from paper_2207_08393_amd.runner import GreedyRunner
+    c = synth.make_case(1)
+    rng = np.random.default_rng(11)
+    thetas = [synth.init_theta(rng, c.prox, 0.02) for _ in range(2)]
+    lr = 1e-3
+    r = GreedyRunner(c, thetas, lr)
+    print("case greedy iteration, knee full size", flush=True)
+    r.iteration(1)
+    x, ls, th, m, v = r.results()
+    zeros = [np.zeros(c.theta.size) for _ in thetas]
+    x_ref, losses, ref_t, ref_m, ref_v = og.greedy_iteration(c.geom, c.prox, c.x_in, c.S, c.M, c.y, c.alpha,
+                                                             [t.astype(np.float64) for t in thetas], zeros, list(zeros), 1,
+                                                             lr, c.x_true)
+    assert_image_close(x, x_ref, TOL)
+    assert np.allclose(ls, losses, rtol=TOL)
+    for i in range(2):
+        assert_grad_close(c.prox, m[i], ref_m[i], TOL, f"Adam m, module {i + 1}")      # = 0.1 * gradient
+        assert_grad_close(c.prox, v[i], ref_v[i], 2 * TOL, f"Adam v, module {i + 1}")
+        assert rel_l2(th[i], ref_t[i]) <= TOL
+    xi = r.infer(2)
+    assert_image_close(xi, og.unrolled_inference(c.geom, c.prox, c.x_in, c.S, c.M, c.y, c.alpha, ref_t), TOL, "inference")
 
 
 # ----------------------------------------------------------------------------- modules of several iterations
@@ -335,6 +425,81 @@ def test_deep_module_matches_oracle(name, geom, prox, n_iter, bf, loss_kind):
     # the sampled part of the signal shrinks.  fp32 keeps the plain tolerance; bf16 gets the bound.
     for j in range(n_iter):
         assert errs[2][j] <= (tol / (1.0 - 0.7) ** (n_iter - 1 - j) if bf else tol)
+        if not bf:
+            assert_grad_close(c.prox, grad[j], g[j], tol, f"grad_theta of iteration {j + 1}")
+
+
+
+
+@pytest.mark.timeout(900)
+def test_deep_module_knee2d_full_size():
+    """A module of two unrolled iterations at the knee workload's full size (gradient through the DC step between
+    them: three more SENSE sweeps on the full k-space buffer)."""
+    from paper_2207_08393_amd.runner import DeepModuleRunner
+    c = synth.make_case(1)
+    rng = np.random.default_rng(12)
+    thetas = [synth.init_theta(rng, c.prox, 0.02) for _ in range(2)]
+    r = DeepModuleRunner(c, thetas, alpha=0.7)
+    print("case deep module, knee full size", flush=True)
+    r.step()
+    x, loss, grad = r.results()
+    f = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.7, thetas, c.x_true)
+    g = og.deep_module_bwd(c.geom, c.prox, c.S, c.M, 0.7, thetas, f)
+    assert_image_close(x, f["x_out"], TOL)
+    assert abs(loss - f["loss"]) <= TOL * abs(f["loss"])
+    for j in range(2):
+        assert_grad_close(c.prox, grad[j], g[j], TOL, f"grad_theta of iteration {j + 1}")
+
+
+def test_deep_module_bf16_stage_by_stage():
+    """bfloat16 operands, three iterations.  Against the exact oracle the gradient of iteration j has crossed K-1-j
+    data-consistency gradients I - alpha A^H A, each of which can raise a relative error by its condition number
+    1/(1-alpha) (eigenvalues in [1-alpha, 1]): the end-to-end bound is BF16_TOL / (1-alpha)^(K-1-j), a derived bound,
+    not the plain tolerance.  What is held to the plain tolerances is (i) every iteration against the oracle with the
+    library's rounding points, per layer (the hand-off between iterations is float32 on the device and exact in the
+    oracle, so nothing but accumulation order separates the two; the same conditioning applies to that small
+    difference), and (ii) every iteration on its own: its gradient against the oracle's backward sweep STARTED FROM
+    THE LIBRARY'S OWN incoming gradient (after gleam_deep_module_bwd, block j >= 1 of `saved` begins with dL/du of
+    that iteration; the oracle applies I - alpha A^H A to it in float64)."""
+    from paper_2207_08393_amd.runner import DeepModuleRunner, to_complex
+    K, alpha = 3, 0.7
+    geom = synth.Geom(2, 1, 2, 1, 1, 20, 24)
+    prox = synth.chain_prox([2, 40, 40, 2], [K2] * 3, dtype=1)
+    c = synth.make_custom(53, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=alpha)
+    rng = np.random.default_rng(K)
+    thetas = [c.theta + np.float32(0.03 * k) * rng.standard_normal(c.theta.size).astype(np.float32) for k in range(K)]
+    r = DeepModuleRunner(c, thetas, alpha=alpha)
+    r.step()
+    x, loss, grad = r.results()
+    f = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, thetas, c.x_true)
+    g = og.deep_module_bwd(c.geom, c.prox, c.S, c.M, alpha, thetas, f)
+    fp = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, thetas, c.x_true, bf16_points=True)
+    gp = og.deep_module_bwd(c.geom, c.prox, c.S, c.M, alpha, thetas, fp)
+    assert rel_l2(x, f["x_out"]) <= BF16_TOL and abs(loss - f["loss"]) <= BF16_TOL * abs(f["loss"])
+    assert_image_close(x, fp["x_out"], BF16_POINT_TOL)
+    block = r.saved.numel() // K
+    n_img = geom.B * geom.T * geom.D * geom.H * geom.W
+    for j in range(K - 1, -1, -1):
+        cond = (1.0 - alpha) ** -(K - 1 - j)
+        end_to_end = rel_l2(grad[j], g[j])
+        assert end_to_end <= BF16_TOL * cond                                               # derived bound
+        # the activations of iteration j + 1 have come through j + 1 prox passes, each of which adds its own
+        # accumulation-order difference between the two sides: the single-module bounds, j + 1 times
+        per_layer = assert_grad_close(c.prox, grad[j], gp[j], BF16_POINT_TOL * cond * (j + 1), f"iteration {j + 1}, rounding points",
+                                      exact=g[j], share=0.15 * (j + 1))
+        print("case deep bf16 iteration", j + 1, "end to end", end_to_end, "per layer vs rounding-point oracle",
+              {k: float(f"{v:.1e}") for k, v in per_layer.items()}, flush=True)
+        if j == K - 1:
+            continue
+        # iteration j + 1 on its own, started from the library's float32 dL/du of iteration j + 2
+        g_u = to_complex(r.saved[(j + 1) * block: (j + 1) * block + 8 * n_img].view(torch.float32).reshape(geom.image_shape + (2,)))
+        g_in = og.complex_to_channels(g_u.astype(np.complex128) - alpha * og.sense_normal(g_u, c.S, c.M, 2))
+        rec, recp = f["iters"][j], fp["iters"][j]
+        ref = og.prox_bwd(c.prox.layers, thetas[j], rec["t"], rec["conv_in"], rec["act"], g_in)
+        refp = og.prox_bwd(c.prox.layers, thetas[j], recp["t"], recp["conv_in"], recp["act"], g_in, bf16_points=True)
+        assert rel_l2(grad[j], ref) <= BF16_TOL                                            # plain tolerance
+        assert_grad_close(c.prox, grad[j], refp, BF16_POINT_TOL * (j + 1), f"iteration {j + 1} from the library's own incoming gradient",
+                          exact=ref, share=0.15 * (j + 1))
 
 
 # ----------------------------------------------------------------------------- MoDL module (Eq. 6-8)
@@ -383,6 +548,36 @@ def test_modl_module_survives_an_exactly_converged_solve():
     assert rel_l2(x, f["x_out"]) <= TOL and rel_l2(grad, g) <= TOL
 
 
+
+
+@pytest.mark.timeout(900)
+def test_modl_module_knee2d_full_size():
+    """One MoDL module (prox, then 10 CG steps on A^H A + mu I, both ways) at the knee workload's full size."""
+    from paper_2207_08393_amd.runner import ModlRunner
+    c = synth.make_case(1)
+    c.theta = synth.init_theta(np.random.default_rng(13), c.prox, 0.02)
+    mu, n_cg = 0.05, 10
+    r = ModlRunner(c, mu, n_cg)
+    print("case MoDL module, knee full size", flush=True)
+    r.step()
+    x, loss, grad, aty = r.results()
+    aty_o = og.sense_adjoint(c.y.astype(np.complex128), c.S, c.M, 2)
+    f = og.modl_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, aty_o, mu, n_cg, c.theta, c.x_true)
+    g = og.modl_module_bwd(c.geom, c.prox, c.S, c.M, mu, n_cg, c.theta, f)
+    assert_image_close(aty, aty_o, TOL, "A^H y")
+    assert_image_close(x, f["x_out"], TOL)
+    assert abs(loss - f["loss"]) <= TOL * abs(f["loss"])
+    assert rel_l2(grad, g) <= TOL
+    # Per layer: the loss gradient reaches the prox through the truncated solve, which multiplies a relative
+    # perturbation by up to kappa = (1 + mu) / mu = 21; each of its n_cg float32 operator applications carries about
+    # 1.5e-7 (what the A^H A parity cases measure), so the solved gradient is off by up to kappa * n_cg * 1.5e-7 =
+    # 3e-5, and the first layer's weight gradient, which is several times as sensitive as the rest (it sums over every
+    # later ReLU mask), by 1-2e-4.  Bound: TOL * kappa / 10.
+    kappa = (1.0 + mu) / mu
+    per_layer = assert_grad_close(c.prox, grad, g, TOL * max(1.0, kappa / 10.0))
+    print("per-layer gradient errors:", {k: float(f"{v:.2e}") for k, v in per_layer.items()}, flush=True)
+
+
 # ----------------------------------------------------------------------------- learnable step size
 @pytest.mark.parametrize("name,geom,prox,loss_kind", [
     ("res8", synth.Geom(2, 2, 3, 1, 1, 12, 10), synth.resblock_prox(8, 1), 0),
@@ -405,61 +600,41 @@ def test_step_size_gradient_matches_oracle(name, geom, prox, loss_kind):
     assert errs[0] <= tol and errs[1] <= tol
 
 
-def test_direct_kernels_still_cover_the_winograd_shapes():
-    """GLEAM_NO_WINOGRAD=1 (read once per process) routes the 64-channel 3x3 layers through the direct MFMA
-    kernels; a fresh interpreter runs one module step that way and checks it against the oracle."""
-    import os
-    import subprocess
-    import sys
-    code = (
-        "import numpy as np\n"
-        "from oracle import gleam_oracle as og\n"
-        "from paper_2207_08393_amd import synth\n"
-        "from paper_2207_08393_amd.runner import ModuleRunner\n"
-        "c = synth.make_custom(31, synth.Geom(2, 1, 2, 1, 1, 24, 46), synth.resblock_prox(64, 1), accel=2.0, centre=2, bias_std=0.1, alpha=0.8)\n"
-        "r = ModuleRunner(c, alpha=0.8); r.step(); x, loss, grad = r.results()\n"
-        "f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, c.theta, c.x_true); g = og.module_bwd(c.prox, c.theta, f)\n"
-        "rel = lambda a, b: float(np.linalg.norm(np.asarray(a, np.complex128) - b) / np.linalg.norm(b))\n"
-        "e = (rel(x, f['x_out']), abs(loss - f['loss']) / abs(f['loss']), rel(grad, g))\n"
-        "print('direct-kernel rel errors', e)\n"
-        "assert max(e) <= 1e-4, e\n")
-    env = dict(os.environ, GLEAM_NO_WINOGRAD="1")
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
-    print(out.stdout, out.stderr[-2000:], flush=True)
-    assert out.returncode == 0
+@pytest.fixture
+def kernel_policy():
+    """Sets the library's kernel-selection policy for one test and restores the default afterwards."""
+    def set_policy(bits):
+        gb.gleam_set_kernel_policy(bits)
+    yield set_policy
+    gb.gleam_set_kernel_policy(0)
 
 
-def test_fallback_kernels_of_the_two_channel_layers_and_the_27_tap_gradient():
-    """GLEAM_NO_THIN_MFMA=1, GLEAM_NO_BF16_2D=1 and GLEAM_NO_WGRAD_BAL=1 (each read once per process) route the
-    shapes that normally take the matrix-core two-channel kernels, the two-dimensional-tile bf16 kernel and the
-    balanced 27-tap weight gradient through the kernels they replaced; a fresh interpreter checks a 2D fp32, a 2D
-    bf16 and a 3D module step on those against the oracle."""
-    import os
-    import subprocess
-    import sys
-    code = (
-        "import numpy as np\n"
-        "from oracle import gleam_oracle as og\n"
-        "from paper_2207_08393_amd import synth\n"
-        "from paper_2207_08393_amd.runner import ModuleRunner\n"
-        "rel = lambda a, b: float(np.linalg.norm(np.asarray(a, np.complex128) - b) / np.linalg.norm(b))\n"
-        "K2, K3 = (1, 1, 3, 3), (1, 3, 3, 3)\n"
-        "cases = [(synth.Geom(2, 1, 2, 1, 1, 10, 46), synth.chain_prox([2, 64, 64, 2], [K2] * 3), 1e-4),\n"
-        "         (synth.Geom(2, 1, 2, 1, 1, 20, 24), synth.chain_prox([2, 128, 128, 2], [K2] * 3, dtype=1), 2e-2),\n"
-        "         (synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), 1e-4)]\n"
-        "for geom, prox, tol in cases:\n"
-        "    c = synth.make_custom(37, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.8)\n"
-        "    r = ModuleRunner(c, alpha=0.8); r.step(); x, loss, grad = r.results()\n"
-        "    f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.8, c.theta, c.x_true); g = og.module_bwd(c.prox, c.theta, f)\n"
-        "    e = (rel(x, f['x_out']), abs(loss - f['loss']) / abs(f['loss']), rel(grad, g))\n"
-        "    print('fallback-kernel rel errors', e, flush=True)\n"
-        "    assert max(e) <= tol, e\n")
-    env = dict(os.environ, GLEAM_NO_THIN_MFMA="1", GLEAM_NO_BF16_2D="1", GLEAM_NO_WGRAD_BAL="1")
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
-    print(out.stdout, out.stderr[-2000:], flush=True)
-    assert out.returncode == 0
+def test_direct_kernels_still_cover_the_winograd_shapes(kernel_policy):
+    """GLEAM_POLICY_NO_WINOGRAD routes the 64-channel 3x3 layers through the direct MFMA kernels: one module step
+    that way against the oracle, and the default (Winograd) step on the same inputs beside it."""
+    c = synth.make_custom(31, synth.Geom(2, 1, 2, 1, 1, 24, 46), synth.resblock_prox(64, 1), accel=2.0, centre=2,
+                          bias_std=0.1, alpha=0.8)
+    kernel_policy(gb.POLICY_NO_WINOGRAD)
+    print("case direct kernels for the Winograd shapes", flush=True)
+    r_direct, _ = check_module(c)
+    gd = r_direct.results()[2].copy()
+    kernel_policy(0)
+    r_wino, _ = check_module(c)
+    assert not np.array_equal(r_wino.results()[2], gd)            # two different kernels did run
+
+
+def test_fallback_kernels_of_the_two_channel_layers_and_the_27_tap_gradient(kernel_policy):
+    """GLEAM_POLICY_NO_THIN_MFMA, _NO_BF16_2D and _NO_WGRAD_BALANCE route the shapes that normally take the
+    matrix-core two-channel kernels, the two-dimensional-tile bf16 kernel and the balanced 27-tap weight gradient
+    through the kernels they replaced: a 2D fp32, a 2D bf16 and a 3D module step on those against the oracle."""
+    kernel_policy(gb.POLICY_NO_THIN_MFMA | gb.POLICY_NO_BF16_2D | gb.POLICY_NO_WGRAD_BALANCE)
+    cases = [(synth.Geom(2, 1, 2, 1, 1, 10, 46), synth.chain_prox([2, 64, 64, 2], [K2] * 3), TOL),
+             (synth.Geom(2, 1, 2, 1, 1, 20, 24), synth.chain_prox([2, 128, 128, 2], [K2] * 3, dtype=1), BF16_TOL),
+             (synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), TOL)]
+    for geom, prox, tol in cases:
+        c = synth.make_custom(37, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.8)
+        print("case fallback kernels", geom, flush=True)
+        check_module(c, tol=tol)
 
 
 # ----------------------------------------------------------------------------- one transformed axis

@@ -110,12 +110,45 @@ def test_loss_values():
 
 
 # ----------------------------------------------------------------------------- gradient
-def torch_prox(layers, theta, u_ch, dims):
+class _StoreBf16(torch.autograd.Function):
+    """A tensor kept in bfloat16 between two layers: its value is rounded on the way forward and the gradient that
+    reaches it (all contributions summed by autograd) on the way back.  torch's own cast does the rounding."""
+    @staticmethod
+    def forward(ctx, x):
+        return x.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+
+class _MixedWeightConv(torch.autograd.Function):
+    """y = conv(x, w) whose forward product uses weights `w_fwd` and whose data gradient uses `w_bwd`: the first layer
+    (exact forward: its input is float32; rounded data gradient: the incoming gradient is bfloat16) and the last
+    layer (the other way round).  The weight gradient is that of the plain convolution, in full precision."""
+    @staticmethod
+    def forward(ctx, x, w, b, pad, round_fwd, round_bwd):
+        rb = lambda v: v.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+        ctx.save_for_backward(x, w)
+        ctx.pad, ctx.round_bwd, ctx.has_b = pad, round_bwd, b is not None
+        return F.conv3d(x, rb(w) if round_fwd else w, b, padding=pad)
+
+    @staticmethod
+    def backward(ctx, g):
+        x, w = ctx.saved_tensors
+        rb = lambda v: v.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+        gx = torch.nn.grad.conv3d_input(x.shape, rb(w) if ctx.round_bwd else w, g, padding=ctx.pad)
+        gw = torch.nn.grad.conv3d_weight(x, w.shape, g, padding=ctx.pad)
+        gb = g.sum(dim=(0, 2, 3, 4)) if ctx.has_b else None
+        return gx, gw, gb, None, None, None
+
+
+def torch_prox(layers, theta, u_ch, dims, bf16_points=False):
     """Independent torch-CPU forward of the same layer list (library convs + autograd)."""
     B, T, D, H, W = dims
     t = [u_ch]
     o = 0
-    for l in layers:
+    for i, l in enumerate(layers):
         nw = l.cout * l.taps * l.cin
         w = theta[o:o + nw].reshape(l.cout, l.kt, l.kd, l.kh, l.kw, l.cin)
         o += nw
@@ -124,18 +157,26 @@ def torch_prox(layers, theta, u_ch, dims):
             b = theta[o:o + l.cout]
             o += l.cout
         a = torch.relu(t[-1]) if l.relu_in else t[-1]
+        # weights meet bfloat16 data in the forward pass of every layer but the first and in the data gradient of
+        # every layer but the last
+        rf, rbk = bf16_points and i > 0, bf16_points and i < len(layers) - 1
+        conv = (lambda x_, w_, b_, pad: _MixedWeightConv.apply(x_, w_.contiguous(), b_, pad, rf, rbk)) if bf16_points else \
+               (lambda x_, w_, b_, pad: F.conv3d(x_, w_, b_, padding=pad))
         if l.kt == 1:
             ta = a.reshape(B * T, D, H, W, l.cin).permute(0, 4, 1, 2, 3)
-            v = F.conv3d(ta, w[:, 0].permute(0, 4, 1, 2, 3), b, padding=(l.kd // 2, l.kh // 2, l.kw // 2))
+            v = conv(ta, w[:, 0].permute(0, 4, 1, 2, 3), b, (l.kd // 2, l.kh // 2, l.kw // 2))
             v = v.permute(0, 2, 3, 4, 1).reshape(B, T, D, H, W, l.cout)
         else:
             assert l.kd == 1
             ta = a.permute(0, 2, 5, 1, 3, 4).reshape(B * D, l.cin, T, H, W)
-            v = F.conv3d(ta, w[:, :, 0].permute(0, 4, 1, 2, 3), b, padding=(l.kt // 2, l.kh // 2, l.kw // 2))
+            v = conv(ta, w[:, :, 0].permute(0, 4, 1, 2, 3), b, (l.kt // 2, l.kh // 2, l.kw // 2))
             v = v.reshape(B, D, l.cout, T, H, W).permute(0, 3, 1, 4, 5, 2)
         if l.relu_out:
             v = torch.relu(v)
-        t.append(v + t[l.skip_src] if l.skip_src >= 0 else v)
+        v = v + t[l.skip_src] if l.skip_src >= 0 else v
+        if bf16_points and i < len(layers) - 1:
+            v = _StoreBf16.apply(v)
+        t.append(v)
     return t[-1]
 
 
@@ -169,6 +210,95 @@ def test_module_gradient_vs_torch_autograd(name, geom, prox, loss_kind):
     assert np.allclose(og.complex_to_channels(fwd["x_out"]), z.detach().numpy(), atol=1e-12)
     assert np.isclose(fwd["loss"], loss.item(), rtol=1e-12)
     assert np.allclose(grad, th.grad.numpy(), rtol=1e-9, atol=1e-13)
+
+
+def test_round_bf16_is_nearest_even_on_eight_significant_bits():
+    # hand values: one ulp at 1 is 2^-7; exact halves go to the even neighbour; 1e-3 = 1.024 * 2^-10 and 0.024 * 128
+    # = 3.07 -> 3 ulps; 65408 is halfway between 65280 and 65536 = 2^16, whose significand is the even one
+    x = np.array([1.0, 1 + 2.0 ** -8, 1 + 2.0 ** -7, 1 + 2.0 ** -7 + 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20, -3.0, 0.0,
+                  2.0 ** -8 * 257, 1e-3, 65280.0, 65408.0])
+    want = np.array([1.0, 1.0, 1 + 2.0 ** -7, 1 + 2.0 ** -6, 1 + 2.0 ** -7, -3.0, 0.0, 1.0, (1 + 3 / 128) * 2.0 ** -10, 65280.0,
+                     65536.0])
+    assert np.array_equal(og.round_bf16(x), want)
+    r = np.random.default_rng(2)
+    v = np.concatenate([r.standard_normal(20000) * 10.0 ** r.integers(-6, 6, 20000), [0.0, -0.0]])
+    ref = torch.from_numpy(v.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    got = og.round_bf16(v)
+    assert np.array_equal(got, ref) and got.shape == v.shape
+    assert np.all(np.abs(got - v) <= np.abs(v) * 2.0 ** -8 + 1e-40)           # half an ulp
+    assert og.round_bf16(v.reshape(2, -1)).shape == (2, v.size // 2)
+
+
+def bf16_prox_cases():
+    k2, k3, ks, kt = (1, 1, 3, 3), (1, 3, 3, 3), (1, 1, 3, 3), (3, 1, 1, 1)
+    yield "chain2d", synth.Geom(2, 2, 2, 1, 1, 6, 8), synth.chain_prox([2, 8, 16, 8, 2], [k2] * 4)
+    yield "res2d", synth.Geom(2, 1, 2, 1, 1, 8, 6), synth.resblock_prox(8, 2)
+    yield "chain3d", synth.Geom(3, 1, 2, 1, 4, 6, 4), synth.chain_prox([2, 8, 8, 2], [k3] * 3)
+    yield "cine", synth.Geom(2, 1, 2, 4, 1, 6, 4), synth.chain_prox([2, 8, 8, 8, 2], [ks, kt, ks, kt])
+    yield "two_layers", synth.Geom(2, 1, 2, 1, 1, 6, 6), synth.chain_prox([2, 8, 2], [k2] * 2, has_bias=0)
+
+
+@pytest.mark.parametrize("name,geom,prox", list(bf16_prox_cases()), ids=[c[0] for c in bf16_prox_cases()])
+@pytest.mark.parametrize("loss_kind", [0, 1])
+def test_bf16_rounding_points_vs_torch_autograd_with_rounded_tensors(name, geom, prox, loss_kind):
+    """The oracle's bf16_points mode against a torch model whose interior tensors pass through a bfloat16 cast in
+    both directions and whose interior weights are cast for use: same rounding points, library convolutions, library
+    rounding, autograd.  Both are float64 outside the casts, so they agree far below the rounding itself, and the
+    mode does move the result away from the exact one by about the size of that rounding."""
+    prox.loss_kind = loss_kind
+    c = synth.make_custom(6, geom, prox, accel=2.0, centre=2, bias_std=0.1)
+    fwd = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.9, c.theta, c.x_true, bf16_points=True)
+    grad = og.module_bwd(c.prox, c.theta, fwd)
+    th = torch.tensor(c.theta.astype(np.float64), requires_grad=True)
+    u = torch.from_numpy(og.complex_to_channels(fwd["u"]))
+    z = torch_prox(c.prox.layers, th, u, c.geom.image_shape, bf16_points=True)
+    ref = torch.from_numpy(og.complex_to_channels(c.x_true.astype(np.complex128)))
+    d2 = ((z - ref) ** 2).sum(-1)
+    loss = d2.mean() if loss_kind == 0 else torch.sqrt(d2).mean()
+    loss.backward()
+    rel = lambda a, b: np.linalg.norm(np.ravel(a) - np.ravel(b)) / np.linalg.norm(np.ravel(b))
+    assert rel(og.complex_to_channels(fwd["x_out"]), z.detach().numpy()) <= 1e-9
+    assert rel(grad, th.grad.numpy()) <= 1e-9
+    exact = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.9, c.theta, c.x_true)
+    g_exact = og.module_bwd(c.prox, c.theta, exact)
+    n_interior = len(c.prox.layers) - 1
+    if n_interior >= 1:
+        assert 1e-4 < rel(fwd["x_out"], exact["x_out"]) < 2e-2 and 1e-4 < rel(grad, g_exact) < 5e-2
+    # the flag off is the plain definition, bit for bit
+    again = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, 0.9, c.theta, c.x_true, bf16_points=False)
+    assert np.array_equal(again["x_out"], exact["x_out"])
+
+
+def test_bf16_rounding_points_in_a_module_of_several_iterations_vs_torch():
+    """deep_module_* with bf16_points: the hand-off between iterations (image forward, gradient backward through
+    I - alpha A^H A) stays exact, only the prox interiors are rounded.  Against torch autograd through torch.fft."""
+    geom = synth.Geom(2, 1, 2, 1, 1, 6, 8)
+    prox = synth.chain_prox([2, 8, 8, 2], [(1, 1, 3, 3)] * 3)
+    c = synth.make_custom(7, geom, prox, accel=2.0, centre=2, bias_std=0.1)
+    rng = np.random.default_rng(1)
+    thetas = [c.theta.astype(np.float64) + 0.03 * rng.standard_normal(c.theta.size) for _ in range(2)]
+    alpha = 0.7
+    f = og.deep_module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, alpha, thetas, c.x_true, bf16_points=True)
+    g = og.deep_module_bwd(c.geom, c.prox, c.S, c.M, alpha, thetas, f)
+    ths = [torch.tensor(t, requires_grad=True) for t in thetas]
+    S = torch.from_numpy(c.S.astype(np.complex128))
+    M = torch.from_numpy((c.M != 0))[:, None]
+    y = torch.from_numpy(c.y.astype(np.complex128))
+    x = torch.from_numpy(c.x_in.astype(np.complex128))
+    for th in ths:
+        k = torch.fft.fftn(S[:, :, None] * x[:, None], dim=(-2, -1), norm="ortho")
+        r = torch.where(M, k - y, torch.zeros_like(k))
+        gimg = (torch.conj(S[:, :, None]) * torch.fft.ifftn(r, dim=(-2, -1), norm="ortho")).sum(1)
+        u = x - alpha * gimg
+        z = torch_prox(c.prox.layers, th, torch.view_as_real(u), c.geom.image_shape, bf16_points=True)
+        x = torch.view_as_complex(z.contiguous())
+    ref = torch.from_numpy(c.x_true.astype(np.complex128))
+    loss = (torch.abs(x - ref) ** 2).mean()
+    loss.backward()
+    rel = lambda a, b: np.linalg.norm(np.ravel(a) - np.ravel(b)) / np.linalg.norm(np.ravel(b))
+    assert rel(f["x_out"], x.detach().numpy()) <= 1e-9
+    for j in range(2):
+        assert rel(g[j], ths[j].grad.numpy()) <= 1e-9
 
 
 def test_module_gradient_vs_finite_differences():

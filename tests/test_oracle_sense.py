@@ -201,6 +201,45 @@ def test_generator_invariants_cfg0(cfg):
     assert c.theta.size == c.prox.n_theta == 2 * 9 * 16 + 16 + 16 * 9 * 16 + 16 + 16 * 9 * 2 + 2
 
 
+@pytest.mark.parametrize("nd,kind", [(1, "uniform"), (1, "random2d"), (2, "uniform"), (2, "vd"), (2, "equi"),
+                                     (2, "random2d"), (2, "full"), (3, "random2d"), (3, "uniform"), (3, "full")])
+def test_generator_measurement_is_the_oracles_operator_for_every_mask_kind_and_dimension(nd, kind):
+    """synth.measure draws y and x_in for BOTH sides with numpy's FFT; here it is held to the oracle's explicit-DFT
+    operators on every mask kind and transform dimension, with several samples, frames and depth slices (per-sample
+    and per-frame masks), so that a wrong axis, normalisation, broadcast or conjugate in it cannot go unnoticed."""
+    geom = synth.Geom(nd, 2, 3, 2, 4, 6, 8)
+    prox = synth.chain_prox([2, 4, 2], [(1, 1, 3, 3)] * 2)
+    c = synth.make_custom(900 + nd, geom, prox, accel=2.0, centre=2, mask_kind=kind, sigma=0.0)
+    if kind not in ("full",):
+        assert 0 < c.M.sum() < c.M.size
+        assert not np.array_equal(c.M[0], c.M[1]) or kind == "full"          # per-sample masks
+    k = og.sense_forward(c.x_true, c.S, c.M, nd)
+    assert np.abs(k - c.y).max() <= 1e-5 * np.abs(k).max()                   # complex64 storage of y
+    x0 = og.sense_adjoint(c.y, c.S, c.M, nd)
+    assert np.abs(x0 - c.x_in).max() <= 1e-5 * np.abs(x0).max()
+    # with noise: y is whatever was drawn, but still exactly zero off the mask, and x_in is still A^H y
+    cn = synth.make_custom(900 + nd, geom, prox, accel=2.0, centre=2, mask_kind=kind, sigma=0.05)
+    off = np.broadcast_to((cn.M == 0)[:, None], cn.y.shape)
+    assert np.all(cn.y[off] == 0) and np.abs(cn.y - c.y).max() > 1e-3
+    x0n = og.sense_adjoint(cn.y, cn.S, cn.M, nd)
+    assert np.abs(x0n - cn.x_in).max() <= 1e-5 * np.abs(x0n).max()
+
+
+def test_generator_measurement_of_the_cine_shaped_case_matches_the_oracle():
+    """The 2D+t benchmark case (per-frame masks, coils shared by the frames), shrunk: relative noise level."""
+    geom = synth.Geom(2, 1, 3, 5, 1, 12, 10)
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(geom.image_shape) + 1j * rng.standard_normal(geom.image_shape)).astype(np.complex64)
+    S = synth.smooth_coils(rng, 1, 3, (1, 12, 10), 2)
+    lines = [[synth._draw_lines(rng, 10, 4, 2, "vd") for _ in range(5)]]
+    M = synth._lines_to_mask(lines, geom)
+    assert len({tuple(l) for l in lines[0]}) > 1                              # the frames do differ
+    y, x0 = synth.measure(x, S, M, geom, rng, 0.0, True)
+    k = og.sense_forward(x, S, M, 2)
+    assert np.abs(k - y).max() <= 1e-5 * np.abs(k).max()
+    assert np.abs(og.sense_adjoint(y, S, M, 2) - x0).max() <= 1e-5 * np.abs(x0).max()
+
+
 def test_generator_mask_counts_all_configs():
     g = synth
     rng = np.random.default_rng(1)
