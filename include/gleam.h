@@ -55,11 +55,16 @@ typedef enum {
 /* Problem geometry.  ndim_fft = 2 transforms (H, W) and batches over D; ndim_fft = 3 transforms (D, H, W).
  * T counts temporal frames that are never transformed (2D+t cine); D = 1 and T = 1 for plain 2D.
  * ndim_fft = 1 transforms W only and batches over D and H: the form a problem takes when its mask does not
- * depend on an axis (line masks of 2D Cartesian sampling, a fully sampled read-out), after the caller has
- * inverse-transformed the measured k-space along that axis once; the whole operator then runs in a single
- * sweep without the k-space buffer.  Every entry point accepts it. */
+ * depend on an axis (line masks of 2D Cartesian sampling, a fully sampled read-out), after the measured k-space
+ * has been inverse-transformed along that axis once (gleam_kspace_to_hybrid); the whole operator then runs in a
+ * single sweep without the k-space buffer.  Every entry point accepts it.
+ * centred = 0: zero frequency and spatial origin at index 0 of every transformed axis (the default reading of `F`
+ * in Eq. 1, which the paper leaves open).  centred = 1: both in the middle of the axis (index n/2), i.e. the
+ * transform fftshift . F . ifftshift that most MRI data comes in; mask and k-space are then indexed that way.
+ * Every transformed length is even, so this costs only sign flips at the loads and stores of the sweeps. */
 typedef struct {
     int32_t ndim_fft;
+    int32_t centred;
     int64_t B, C, T, D, H, W;
 } gleam_geom;
 
@@ -191,6 +196,20 @@ int gleam_deep_module_bwd(const gleam_geom* geom, const gleam_prox_desc* prox, i
  * (B*T*D*H*W complex64), or simply by gleam_modl_workspace_bytes.  out must not alias y. */
 int gleam_sense_adjoint(const gleam_geom* geom, const gleam_c64* S, const uint8_t* M, const gleam_c64* y,
                         gleam_c64* out, void* ws, size_t ws_bytes, void* stream);
+
+/* Measured k-space to hybrid space: y_out = inverse transform of y_in along the OUTERMOST transformed axis of
+ * `geom` (H when ndim_fft = 2, D when ndim_fft = 3), every other axis untouched; orthonormal, centred when the
+ * geometry is.  When the mask does not depend on that axis (gleam_mask_constant_along_outer_axis), the transform
+ * along it cancels in A^H A, and the same problem (same x, S, mask, same results) runs with one transformed axis
+ * less on y_out: pass the same sizes with ndim_fft - 1 to every other entry point (the axis becomes a batch
+ * axis; two sweeps fewer per operator, a single sweep for ndim_fft = 1).  Done once per scan.
+ * y_in, y_out: k-space [B][C][T][D][H][W]; y_out may be y_in (in place), otherwise y_in is not written.
+ * ndim_fft = 1 has no such axis: GLEAM_E_DIMS. */
+int gleam_kspace_to_hybrid(const gleam_geom* geom, const gleam_c64* y_in, gleam_c64* y_out, void* stream);
+
+/* Host-only check on a HOST copy of the mask [B][T][D][H][W]: *constant = 1 when "sampled / not sampled" does
+ * not depend on the index along the outermost transformed axis (H for ndim_fft = 2, D for 3), else 0. */
+int gleam_mask_constant_along_outer_axis(const gleam_geom* geom, const uint8_t* M_host, int* constant);
 
 /* One MoDL module (MoDL section, Eq. 6-8):
  *     z = f_theta(x_in)                                   (Eq. 8)

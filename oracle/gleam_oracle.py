@@ -4,8 +4,9 @@ Only the tests, the smoke check and the benchmark's CPU-baseline leg may import 
 product (the HIP library and its binding) never does, and this file imports nothing of the
 product.  Everything is float64 / complex128 numpy, written as the plain definitions:
 
-  * F        : orthonormal, uncentred DFT applied as an explicit n x n matrix product per axis
-               (direct O(n^2) definition; `F` of the sensing model, Eq. 1)
+  * F        : orthonormal DFT applied as an explicit n x n matrix product per axis (direct O(n^2) definition; `F`
+               of the sensing model, Eq. 1), uncentred by default (zero frequency at index 0) or, for a geometry
+               with `centred` set, with frequency and spatial origin in the middle of every transformed axis
   * A        : A = Omega F S and its Hermitian transpose A^H = S^H F^H Omega (Eq. 1, Eq. 2, PGD section)
   * DC       : u = x - alpha A^H (A x - y), alpha = 2t   (data-consistency step of PGD, Eq. 3, read with
                the same iterate on both sides)
@@ -51,64 +52,72 @@ import numpy as np
 
 
 # ----------------------------------------------------------------------------- Fourier
-def dft_matrix(n: int, inverse: bool = False) -> np.ndarray:
-    """F[q, j] = n^(-1/2) exp(-+ 2 pi i ((j q) mod n) / n)."""
-    j = np.arange(n, dtype=np.int64)
+def dft_matrix(n: int, inverse: bool = False, centred: bool = False) -> np.ndarray:
+    """F[q, j] = n^(-1/2) exp(-+ 2 pi i ((j - c)(q - c) mod n) / n), with c = 0 (zero frequency and the spatial origin
+    at index 0) or, centred, c = floor(n/2) (both in the middle of the array: the transform that the MRI literature
+    writes as fftshift . F . ifftshift).  The paper leaves the convention of `F` in Eq. 1 open; uncentred is the
+    default reading here and the centred one a variant."""
+    c = n // 2 if centred else 0
+    j = np.arange(n, dtype=np.int64) - c
     jq = np.outer(j, j) % n
     sign = 1.0 if inverse else -1.0
     return np.exp(sign * 2j * np.pi * jq / n) / np.sqrt(n)
 
 
-def dft_axis(a: np.ndarray, axis: int, inverse: bool = False) -> np.ndarray:
+def dft_axis(a: np.ndarray, axis: int, inverse: bool = False, centred: bool = False) -> np.ndarray:
     """X[..., q, ...] = sum_j F[q, j] a[..., j, ...] along one axis."""
-    F = dft_matrix(a.shape[axis], inverse)
+    F = dft_matrix(a.shape[axis], inverse, centred)
     moved = np.moveaxis(np.asarray(a, np.complex128), axis, -1)
     return np.moveaxis(moved @ F.T, -1, axis)
 
 
-def dft_nd(a: np.ndarray, ndim_fft: int, inverse: bool = False) -> np.ndarray:
+def dft_nd(a: np.ndarray, ndim_fft: int, inverse: bool = False, centred: bool = False) -> np.ndarray:
     """Separable DFT over the last `ndim_fft` axes."""
     out = np.asarray(a, np.complex128)
     for ax in range(a.ndim - ndim_fft, a.ndim):
-        out = dft_axis(out, ax, inverse)
+        out = dft_axis(out, ax, inverse, centred)
     return out
 
 
+def _centred(geom) -> bool:
+    return bool(getattr(geom, "centred", 0))
+
+
 # ----------------------------------------------------------------------------- SENSE operator
-def sense_forward(x, S, M, ndim_fft):
+def sense_forward(x, S, M, ndim_fft, centred=False):
     """A x = Omega F S x  ->  k-space [B,C,T,D,H,W]."""
     x = np.asarray(x, np.complex128)
     S = np.asarray(S, np.complex128)
     c = S[:, :, None] * x[:, None]
-    k = dft_nd(c, ndim_fft)
+    k = dft_nd(c, ndim_fft, centred=centred)
     return np.where((np.asarray(M) != 0)[:, None], k, 0.0)
 
 
-def sense_adjoint(k, S, M, ndim_fft):
+def sense_adjoint(k, S, M, ndim_fft, centred=False):
     """A^H k = S^H F^H Omega k  ->  image [B,T,D,H,W]."""
     S = np.asarray(S, np.complex128)
     r = np.where((np.asarray(M) != 0)[:, None], np.asarray(k, np.complex128), 0.0)
-    rt = dft_nd(r, ndim_fft, inverse=True)
+    rt = dft_nd(r, ndim_fft, inverse=True, centred=centred)
     return (np.conj(S)[:, :, None] * rt).sum(axis=1)
 
 
-def sense_normal(x, S, M, ndim_fft):
+def sense_normal(x, S, M, ndim_fft, centred=False):
     """A^H A x."""
-    return sense_adjoint(sense_forward(x, S, M, ndim_fft), S, M, ndim_fft)
+    return sense_adjoint(sense_forward(x, S, M, ndim_fft, centred), S, M, ndim_fft, centred)
 
 
-def masked_residual(x, S, M, y, ndim_fft):
+def masked_residual(x, S, M, y, ndim_fft, centred=False):
     """r = Omega (F S x - y): exactly zero off the mask, whatever y holds there."""
     x = np.asarray(x, np.complex128)
     S = np.asarray(S, np.complex128)
-    k = dft_nd(S[:, :, None] * x[:, None], ndim_fft)
+    k = dft_nd(S[:, :, None] * x[:, None], ndim_fft, centred=centred)
     return np.where((np.asarray(M) != 0)[:, None], k - np.asarray(y, np.complex128), 0.0)
 
 
-def dc_step(x, S, M, y, alpha, ndim_fft):
+def dc_step(x, S, M, y, alpha, ndim_fft, centred=False):
     """u = x - alpha A^H (A x - y)."""
-    r = masked_residual(x, S, M, y, ndim_fft)
-    g = sense_adjoint(r, S, np.ones_like(np.asarray(M)), ndim_fft)
+    r = masked_residual(x, S, M, y, ndim_fft, centred)
+    g = sense_adjoint(r, S, np.ones_like(np.asarray(M)), ndim_fft, centred)
     return np.asarray(x, np.complex128) - alpha * g
 
 
@@ -303,7 +312,7 @@ def prox_bwd(layers, theta, t, conv_in, act, g_z, want_input_grad=False, bf16_po
 def module_fwd(geom, prox, x_in, S, M, y, alpha, theta, x_ref=None, bf16_points=False):
     """x_out = f_theta(DC(x_in)); loss against x_ref when given.  Returns a dict holding
     everything module_bwd needs."""
-    u = dc_step(x_in, S, M, y, alpha, geom.ndim_fft)
+    u = dc_step(x_in, S, M, y, alpha, geom.ndim_fft, _centred(geom))
     t, conv_in, act = prox_fwd(prox.layers, theta, u, bf16_points)
     z = channels_to_complex(t[-1])
     out = {"u": u, "x_out": z, "t": t, "conv_in": conv_in, "act": act, "loss": None, "g_z": None,
@@ -324,7 +333,7 @@ def module_bwd_alpha(geom, prox, x_in, S, M, y, theta, fwd):
     data-consistency step (Eq. 3), for a learnable step size.  u = x - alpha r with r = A^H (A x - y), so
     dL/dalpha = -<dL/du, r> over the real and imaginary parts; still nothing goes to x_in."""
     g_theta, g_u = prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], fwd["g_z"], want_input_grad=True)
-    r = sense_adjoint(masked_residual(x_in, S, M, y, geom.ndim_fft), S, M, geom.ndim_fft)
+    r = sense_adjoint(masked_residual(x_in, S, M, y, geom.ndim_fft, _centred(geom)), S, M, geom.ndim_fft, _centred(geom))
     return g_theta, float(-(g_u * complex_to_channels(r)).sum())
 
 
@@ -358,12 +367,12 @@ def deep_module_bwd(geom, prox, S, M, alpha, thetas, fwd):
             grads[j], g_u = prox_bwd(prox.layers, thetas[j], r["t"], r["conv_in"], r["act"], g_out, want_input_grad=True,
                                      bf16_points=bf)
             gc = channels_to_complex(g_u)
-            g_out = complex_to_channels(gc - alpha * sense_normal(gc, S, M, geom.ndim_fft))
+            g_out = complex_to_channels(gc - alpha * sense_normal(gc, S, M, geom.ndim_fft, _centred(geom)))
     return grads
 
 
 # ----------------------------------------------------------------------------- MoDL module (Eq. 6-8)
-def cg_solve(x_shape, S, M, mu, b, n_cg, ndim_fft):
+def cg_solve(x_shape, S, M, mu, b, n_cg, ndim_fft, centred=False):
     """n_cg conjugate-gradient steps from x = 0 on (A^H A + mu I) x = b, one system per batch sample
     (leading axis): the textbook recurrence
         a = <r,r> / <p, Q p> ; x += a p ; r -= a Q p ; beta = <r,r>_new / <r,r>_old ; p = r + beta p.
@@ -377,7 +386,7 @@ def cg_solve(x_shape, S, M, mu, b, n_cg, ndim_fft):
     bc = (slice(None),) + (None,) * (b.ndim - 1)
     rr = np.sum(np.abs(r) ** 2, axis=axes)
     for _ in range(n_cg):
-        Qp = sense_normal(p, S, M, ndim_fft) + mu * p
+        Qp = sense_normal(p, S, M, ndim_fft, centred) + mu * p
         pQp = np.sum((np.conj(p) * Qp).real, axis=axes)
         a = np.where(pQp > 0, rr / np.where(pQp > 0, pQp, 1.0), 0.0)
         x = x + a[bc] * p
@@ -395,7 +404,7 @@ def modl_module_fwd(geom, prox, x_in, S, M, aty, mu, n_cg, theta, x_ref=None):
     (Eq. 7); aty is A^H y.  Loss against x_ref when given."""
     t, conv_in, act = prox_fwd(prox.layers, theta, np.asarray(x_in, np.complex128))
     z = channels_to_complex(t[-1])
-    x_out = cg_solve(z.shape, S, M, mu, np.asarray(aty, np.complex128) + mu * z, n_cg, geom.ndim_fft)
+    x_out = cg_solve(z.shape, S, M, mu, np.asarray(aty, np.complex128) + mu * z, n_cg, geom.ndim_fft, _centred(geom))
     out = {"z": z, "x_out": x_out, "t": t, "conv_in": conv_in, "act": act, "loss": None, "g_x": None}
     if x_ref is not None:
         out["loss"], out["g_x"] = loss_and_grad(x_out, x_ref, prox.loss_kind)
@@ -407,7 +416,7 @@ def modl_module_bwd(geom, prox, S, M, mu, n_cg, theta, fwd):
     dL/dz = mu Q^-1 dL/dx_out; the inverse is again applied by n_cg CG steps (the same truncated solve as
     the forward pass), then the prox is swept backwards.  Nothing goes to the module input."""
     gx = channels_to_complex(fwd["g_x"])
-    g_z = complex_to_channels(mu * cg_solve(gx.shape, S, M, mu, gx, n_cg, geom.ndim_fft))
+    g_z = complex_to_channels(mu * cg_solve(gx.shape, S, M, mu, gx, n_cg, geom.ndim_fft, _centred(geom)))
     return prox_bwd(prox.layers, theta, fwd["t"], fwd["conv_in"], fwd["act"], g_z)
 
 

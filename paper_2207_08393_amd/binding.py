@@ -23,7 +23,7 @@ GLEAM_E_LAUNCH = -6
 
 
 class gleam_geom(C.Structure):
-    _fields_ = [("ndim_fft", C.c_int32), ("B", C.c_int64), ("C", C.c_int64), ("T", C.c_int64),
+    _fields_ = [("ndim_fft", C.c_int32), ("centred", C.c_int32), ("B", C.c_int64), ("C", C.c_int64), ("T", C.c_int64),
                 ("D", C.c_int64), ("H", C.c_int64), ("W", C.c_int64)]
 
 
@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
         L.gleam_deep_module_fwd.argtypes = [pg, pp, C.c_int, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_deep_module_bwd.argtypes = [pg, pp, C.c_int, vp, vp, C.c_float, vp, vp, sz, vp, vp, sz, vp]
         L.gleam_sense_adjoint.argtypes = [pg, vp, vp, vp, vp, vp, sz, vp]
+        L.gleam_kspace_to_hybrid.argtypes = [pg, vp, vp, vp]
+        L.gleam_mask_constant_along_outer_axis.argtypes = [pg, vp, C.POINTER(C.c_int)]
         L.gleam_modl_workspace_bytes.argtypes = [pg, pp, C.POINTER(sz), C.POINTER(sz)]
         L.gleam_modl_module_fwd.argtypes = [pg, pp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, vp, vp, vp, sz, vp, sz, vp]
         L.gleam_modl_module_bwd.argtypes = [pg, pp, vp, vp, C.c_float, C.c_int, vp, vp, sz, vp, vp, sz, vp]
@@ -97,7 +99,8 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("gleam_strerror", "gleam_fft_size_supported", "gleam_set_kernel_policy", "gleam_get_kernel_policy", "gleam_theta_count", "gleam_workspace_bytes",
            "gleam_sense_normal", "gleam_sense_normal_static", "gleam_module_fwd", "gleam_module_bwd", "gleam_module_bwd_alpha", "gleam_deep_workspace_bytes",
-           "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_sense_adjoint", "gleam_modl_workspace_bytes",
+           "gleam_deep_module_fwd", "gleam_deep_module_bwd", "gleam_sense_adjoint", "gleam_kspace_to_hybrid",
+           "gleam_mask_constant_along_outer_axis", "gleam_modl_workspace_bytes",
            "gleam_modl_module_fwd", "gleam_modl_module_bwd", "gleam_adam_step",
            "gleam_greedy_iteration", "gleam_unrolled_infer", "gleam_profile_begin", "gleam_profile_end")
 
@@ -107,8 +110,8 @@ def strerror(status: int) -> str:
 
 
 def make_geom(g) -> gleam_geom:
-    """From any object with ndim_fft, B, C, T, D, H, W attributes."""
-    return gleam_geom(int(g.ndim_fft), int(g.B), int(g.C), int(g.T), int(g.D), int(g.H), int(g.W))
+    """From any object with ndim_fft, B, C, T, D, H, W (and optionally centred) attributes."""
+    return gleam_geom(int(g.ndim_fft), int(getattr(g, "centred", 0)), int(g.B), int(g.C), int(g.T), int(g.D), int(g.H), int(g.W))
 
 
 def make_prox(p) -> gleam_prox_desc:
@@ -232,6 +235,22 @@ def gleam_deep_module_bwd(geom, prox, n_iter, S, M, alpha, theta, saved, grad_th
 def gleam_sense_adjoint(geom, S, M, y, out, ws, stream=None):
     _check(lib().gleam_sense_adjoint(C.byref(geom), _ptr(S), _ptr(M), _ptr(y), _ptr(out), _ptr(ws), _nbytes(ws),
                                      _stream(stream)), "gleam_sense_adjoint")
+
+
+def gleam_kspace_to_hybrid(geom, y_in, y_out, stream=None):
+    _check(lib().gleam_kspace_to_hybrid(C.byref(geom), _ptr(y_in), _ptr(y_out), _stream(stream)), "gleam_kspace_to_hybrid")
+
+
+def gleam_mask_constant_along_outer_axis(geom, mask_host) -> bool:
+    """mask_host: contiguous uint8 numpy array [B][T][D][H][W] in host memory."""
+    import numpy as np
+    m = np.ascontiguousarray(mask_host, dtype=np.uint8)
+    if m.size != geom.B * geom.T * geom.D * geom.H * geom.W:
+        raise ValueError("mask size does not match the geometry")
+    out = C.c_int(0)
+    _check(lib().gleam_mask_constant_along_outer_axis(C.byref(geom), m.ctypes.data_as(C.c_void_p), C.byref(out)),
+           "gleam_mask_constant_along_outer_axis")
+    return bool(out.value)
 
 
 def gleam_modl_workspace_bytes(geom, prox):

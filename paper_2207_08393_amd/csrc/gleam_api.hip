@@ -75,6 +75,7 @@ inline bool aligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) % kA
 int check_geom(const gleam_geom* g) {
     if (!g) return GLEAM_E_NULL;
     if (g->ndim_fft < 1 || g->ndim_fft > 3) return GLEAM_E_DIMS;
+    if (g->centred != 0 && g->centred != 1) return GLEAM_E_DIMS;
     if (g->B < 1 || g->C < 1 || g->T < 1 || g->D < 1 || g->H < 1 || g->W < 1) return GLEAM_E_DIMS;
     const long long lim = 1LL << 40;  // keeps every byte offset far inside int64
     long long e = 1;
@@ -419,6 +420,42 @@ int gleam_sense_adjoint(const gleam_geom* geom, const gleam_c64* S, const uint8_
     if (e != hipSuccess) return GLEAM_E_LAUNCH;
     e = sense_dc(*geom, zero, (const float2*)S, M, (const float2*)y, 0.f, -1.f, (float2*)out, (float2*)ws, st);
     return e == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+int gleam_kspace_to_hybrid(const gleam_geom* geom, const gleam_c64* y_in, gleam_c64* y_out, void* stream) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    if (geom->ndim_fft < 2) return GLEAM_E_DIMS;
+    if (!y_in || !y_out) return GLEAM_E_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (y_out != y_in &&
+        hipMemcpyAsync(y_out, y_in, n_coil_pixels(*geom) * sizeof(float2), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return GLEAM_E_LAUNCH;
+    return kspace_to_hybrid(*geom, (float2*)y_out, st) == hipSuccess ? GLEAM_OK : GLEAM_E_LAUNCH;
+}
+
+int gleam_mask_constant_along_outer_axis(const gleam_geom* geom, const uint8_t* M_host, int* constant) {
+    int rc = check_geom(geom);
+    if (rc) return rc;
+    if (geom->ndim_fft < 2) return GLEAM_E_DIMS;
+    if (!M_host || !constant) return GLEAM_E_NULL;
+    // mask viewed as [outer][n][inner] with n the axis in question
+    const long long n = geom->ndim_fft == 2 ? geom->H : geom->D;
+    const long long inner = geom->ndim_fft == 2 ? geom->W : geom->H * geom->W;
+    const long long outer = geom->B * geom->T * (geom->ndim_fft == 2 ? geom->D : 1);
+    *constant = 1;
+    for (long long o = 0; o < outer; ++o) {
+        const uint8_t* first = M_host + o * n * inner;
+        for (long long i = 1; i < n; ++i) {
+            const uint8_t* row = first + i * inner;
+            for (long long j = 0; j < inner; ++j)
+                if ((row[j] != 0) != (first[j] != 0)) {
+                    *constant = 0;
+                    return GLEAM_OK;
+                }
+        }
+    }
+    return GLEAM_OK;
 }
 
 static int check_modl(const gleam_geom* geom, const gleam_prox_desc* prox, float mu, int n_cg) {

@@ -40,6 +40,9 @@ struct KernelScope {
 hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const unsigned char* M,
                     const float2* y, float xs, float gs, float2* out, float2* kbuf, hipStream_t st);
 
+// y: measured k-space, inverse-transformed in place along the outermost transformed axis (ndim_fft 2 or 3).
+hipError_t kspace_to_hybrid(const gleam_geom& g, float2* y, hipStream_t st);
+
 // Byte offsets of everything the prox keeps between and during calls.
 //   saved : t_0 (= u, fp32 2 channels), t_1 .. t_{L-1} (fp32), g_z = dL/dz (fp32 2 channels)
 //   ws    : [k-space | activations when the caller gave no saved buffer] for forward;

@@ -34,7 +34,25 @@ struct RowsArgs {
     long long n_rows;     // expand: B*C*T*DH k-space rows ; reduce: B*T*DH image rows
     float scale;          // N^-1/2
     float xs, gs;         // reduce: out = xs*x + gs*g
+    // Centred transform (frequency and spatial origin in the middle of every transformed axis; all lengths are even):
+    // F_c = (-1)^(n/2) D F D per axis with D = diag((-1)^index), so the operator is the uncentred one on D x and
+    // (sign) D y, times D.  cen: 0 / 1; par_h, par_d: whether the row index h / d takes part in the parity (the
+    // axis is transformed); Hh: H, to split a row index into (d, h); ysign_bit: 1 when the product of the
+    // (-1)^(n/2) over the transformed axes is -1.
+    int cen, par_h, par_d, ysign_bit;
+    long long Hh;
 };
+
+// v with its sign flipped when bit is 1 (bit is 0 or 1)
+__device__ __forceinline__ float2 flip_sign(float2 v, unsigned bit) {
+    return make_float2(__uint_as_float(__float_as_uint(v.x) ^ (bit << 31)), __uint_as_float(__float_as_uint(v.y) ^ (bit << 31)));
+}
+// parity of the transformed row coordinates of row dh = d*H + h (0 when the transform is not centred)
+__device__ __forceinline__ unsigned row_parity(const RowsArgs& a, long long dh) {
+    if (!a.cen) return 0u;
+    const long long h = dh % a.Hh, d = dh / a.Hh;
+    return (unsigned)(((a.par_h ? h : 0) + (a.par_d ? d : 0)) & 1);
+}
 
 // Forward transform along W of S*x: L consecutive k-space rows per tile, coil multiply fused into the
 // load, two complex values (16 bytes) per global access.
@@ -44,6 +62,7 @@ __global__ __launch_bounds__(rows_threads<N>()) void rows_expand_kernel(RowsArgs
     using Lay = Layout<N, L, 1>;
     __shared__ float2 buf[Lay::kElems], tw[N];
     __shared__ long long xoff[L], soff[L];
+    __shared__ unsigned lpar[L];
     fill_twiddles<N, NT>(tw);
     const long long n_tiles = (a.n_rows + L - 1) / L;
     for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -51,15 +70,18 @@ __global__ __launch_bounds__(rows_threads<N>()) void rows_expand_kernel(RowsArgs
         if (threadIdx.x < L) {
             const long long row = tile * L + threadIdx.x;   // k-space row (b, c, t, dh)
             long long xo = -1, so = -1;
+            unsigned par = 0u;
             if (row < a.n_rows) {
                 const long long dh = row % a.DH;
                 const long long t = (row / a.DH) % a.T;
                 const long long bc = row / (a.DH * a.T);
                 xo = (((bc / a.C) * a.T + t) * a.DH + dh) * N;
                 so = (bc * a.DH + dh) * N;
+                par = row_parity(a, dh);
             }
             xoff[threadIdx.x] = xo;
             soff[threadIdx.x] = so;
+            lpar[threadIdx.x] = par;
         }
         __syncthreads();
         for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
@@ -70,6 +92,10 @@ __global__ __launch_bounds__(rows_threads<N>()) void rows_expand_kernel(RowsArgs
                 const float4 xv = *reinterpret_cast<const float4*>(a.x + xoff[line] + p);
                 v0 = cmul(make_float2(sv.x, sv.y), make_float2(xv.x, xv.y));
                 v1 = cmul(make_float2(sv.z, sv.w), make_float2(xv.z, xv.w));
+                if (a.cen) {   // D x: p is even, so the pair's signs are the row's parity and its opposite
+                    v0 = flip_sign(v0, lpar[line]);
+                    v1 = flip_sign(v1, lpar[line] ^ 1u);
+                }
             }
             buf[Lay::at(line, p)] = v0;
             buf[Lay::at(line, p + 1)] = v1;
@@ -91,13 +117,14 @@ __global__ __launch_bounds__(rows_threads<N>()) void rows_expand_kernel(RowsArgs
 // transformed together; then out = xs*x + gs * sum_c conj(S_c) * row_c is accumulated in registers,
 // looping over coil groups when C > CG.  The per-coil images never leave LDS.
 template <int N>
-__global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsArgs a) {
+__global__ __launch_bounds__(reduce_threads<N>(), N == 368 ? 2 : 1) void rows_reduce_kernel(RowsArgs a) {
     constexpr int L = reduce_lines<N>(), NT = reduce_threads<N>(), H2 = N / 2;
     constexpr int PER = (H2 * L + NT - 1) / NT;   // output pairs per thread (upper bound: CG = 1)
     constexpr int kSPre = 8;                      // coil-map values per thread fetched ahead of the transform
     using Lay = Layout<N, L, 1>;
     __shared__ float2 buf[Lay::kElems], tw[N];
     __shared__ long long koff[L], soff[L];        // per image row of the tile, coil 0
+    __shared__ unsigned lpar[L];
     fill_twiddles<N, NT>(tw);
     const int CG = a.C < L ? (int)a.C : L;        // coils transformed together
     const int LR = L / CG;                        // image rows per tile
@@ -108,15 +135,18 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsAr
         if (threadIdx.x < LR) {
             const long long row = tile * LR + threadIdx.x;   // image row (b, t, dh)
             long long ko = -1, so = -1;
+            unsigned par = 0u;
             if (row < a.n_rows) {
                 const long long dh = row % a.DH;
                 const long long bt = row / a.DH;
                 const long long t = bt % a.T, b = bt / a.T;
                 ko = (((b * a.C) * a.T + t) * a.DH + dh) * N;
                 so = ((b * a.C) * a.DH + dh) * N;
+                par = row_parity(a, dh);
             }
             koff[threadIdx.x] = ko;
             soff[threadIdx.x] = so;
+            lpar[threadIdx.x] = par;
         }
         __syncthreads();
         float4 acc[PER];
@@ -185,7 +215,8 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsAr
                 const int r = e / H2, p = 2 * (e % H2);
                 if (koff[r] >= 0) {
                     const long long o = (tile * LR + r) * N + p;
-                    float4 res = make_float4(gsc * acc[m].x, gsc * acc[m].y, gsc * acc[m].z, gsc * acc[m].w);
+                    const float g0 = (a.cen && lpar[r]) ? -gsc : gsc, g1 = a.cen ? -g0 : g0;   // D g when centred: p is even
+                    float4 res = make_float4(g0 * acc[m].x, g0 * acc[m].y, g1 * acc[m].z, g1 * acc[m].w);
                     if (a.xs != 0.f) {
                         const float4 xv = *reinterpret_cast<const float4*>(a.x + o);
                         res.x = fmaf(a.xs, xv.x, res.x); res.y = fmaf(a.xs, xv.y, res.y);
@@ -249,6 +280,7 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_fused_kernel(RowsArg
                     const float4 xv = *reinterpret_cast<const float4*>(a.x + xoff[r] + p);
                     v0 = cmul(make_float2(sv.x, sv.y), make_float2(xv.x, xv.y));
                     v1 = cmul(make_float2(sv.z, sv.w), make_float2(xv.z, xv.w));
+                    if (a.cen) v1 = flip_sign(v1, 1u);   // D x along the one transformed axis: p is even
                 }
                 buf[Lay::at(line, p)] = v0;
                 buf[Lay::at(line, p + 1)] = v1;
@@ -262,6 +294,10 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_fused_kernel(RowsArg
                     const unsigned short mm = *reinterpret_cast<const unsigned short*>(M + xoff[r] + p);
                     float4 yv = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (y) yv = *reinterpret_cast<const float4*>(y + koff[r] + (c0 + c) * kstride + p);
+                    if (a.cen) {   // (-1)^(N/2) D y
+                        const float s0 = a.ysign_bit ? -1.f : 1.f;
+                        yv.x *= s0; yv.y *= s0; yv.z *= -s0; yv.w *= -s0;
+                    }
                     const float2 k0 = buf[Lay::at(line, p)], k1 = buf[Lay::at(line, p + 1)];
                     buf[Lay::at(line, p)] = (mm & 0xff) ? make_float2(k0.x * a.scale - yv.x, k0.y * a.scale - yv.y) : make_float2(0.f, 0.f);
                     buf[Lay::at(line, p + 1)] = (mm >> 8) ? make_float2(k1.x * a.scale - yv.z, k1.y * a.scale - yv.w) : make_float2(0.f, 0.f);
@@ -296,6 +332,7 @@ __global__ __launch_bounds__(reduce_threads<N>()) void rows_fused_kernel(RowsArg
                 if (xoff[r] >= 0) {
                     const long long o = xoff[r] + p;
                     float4 res = make_float4(gsc * acc[m].x, gsc * acc[m].y, gsc * acc[m].z, gsc * acc[m].w);
+                    if (a.cen) { res.z = -res.z; res.w = -res.w; }   // D g: p is even
                     if (a.xs != 0.f) {
                         const float4 xv = *reinterpret_cast<const float4*>(a.x + o);
                         res.x = fmaf(a.xs, xv.x, res.x); res.y = fmaf(a.xs, xv.y, res.y);
@@ -315,13 +352,20 @@ struct ColsArgs {
     long long outer, inner;  // inner is even (it is a product of transform lengths, all even)
     long long C, T, Dq;    // outer = ((b*C + c)*T + t)*Dq + dq ; mask row = (b*T + t)*Dq + dq
     float scale;           // N^-1/2, applied at the store (mid applies its forward N^-1/2 in LDS)
+    // Centred transform.  cen_y (mid sweep): the measured k-space enters as (sign) D y, where the parity of an
+    // element is p + (column / Wrow) + (column % Wrow) (the inner index is h*W + w when three axes are transformed,
+    // w alone otherwise: then column / Wrow is 0) and ysign_bit is 1 when the product of (-1)^(n/2) over the
+    // transformed axes is -1.  cen_io (MODE 1 on its own, k-space to hybrid space): the centred inverse transform
+    // of this axis, (-1)^(N/2) D F^H D: input and output signs by the parity of p.
+    int cen_y, ysign_bit, cen_io;
+    long long Wrow;
 };
 
 // Strided axis: a tile is 16 neighbouring columns (128 contiguous bytes per row) of one [N][inner] plane.
 // MODE 0: forward, 1: inverse, 2: forward -> (mask ? k - y : 0) -> inverse.  In MODE 2 the measured
 // k-space and the mask bytes of the tile are fetched into registers before the forward transform.
 template <int N, int MODE>
-__global__ __launch_bounds__(cols_threads<N>(), (N >= 512 ? 2 : 1) * cols_threads<N>() / 256) void cols_kernel(ColsArgs a) {
+__global__ __launch_bounds__(cols_threads<N>(), ((N >= 512 || (N == 256 && MODE == 2)) ? 2 : 1) * cols_threads<N>() / 256) void cols_kernel(ColsArgs a) {
     constexpr int L = cols_lines<N>(), NT = cols_threads<N>(), L2 = L / 2;
     constexpr int PER = (N * L2 + NT - 1) / NT;
     using Lay = Layout<N, L, 0>;
@@ -357,6 +401,9 @@ __global__ __launch_bounds__(cols_threads<N>(), (N >= 512 ? 2 : 1) * cols_thread
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 const long long off = (long long)p * a.inner + l;
                 if (l < valid) v = *reinterpret_cast<const float4*>(a.k + base + off);
+                if constexpr (MODE == 1) {
+                    if (a.cen_io && (p & 1)) v = make_float4(-v.x, -v.y, -v.z, -v.w);
+                }
                 buf[Lay::at(l, p)] = make_float2(v.x, v.y);
                 buf[Lay::at(l + 1, p)] = make_float2(v.z, v.w);
                 if constexpr (kPre) {
@@ -378,6 +425,16 @@ __global__ __launch_bounds__(cols_threads<N>(), (N >= 512 ? 2 : 1) * cols_thread
         if constexpr (MODE == 2) {
             // the forward transform of this axis carries N^-1/2; apply it before subtracting y
             const float fs = rsqrtf((float)N);
+            // Centred transform: y enters as (sign) D y.  A thread's elements of one tile share the parity of p (the
+            // thread count is an even multiple of the column pairs) and its column pair starts at an even column of
+            // an even-length row, so the pair's signs are (p + row of the column + sign bit) and the opposite.
+            static_assert((NT / L2) % 2 == 0, "parity of p must not depend on m");
+            float ysgn = 1.f, ysgn1 = 1.f;
+            if (a.cen_y) {
+                const long long col = i0 + 2 * (threadIdx.x % L2);
+                ysgn = (((threadIdx.x / L2) + col / a.Wrow + a.ysign_bit) & 1) ? -1.f : 1.f;
+                ysgn1 = -ysgn;
+            }
 #pragma unroll
             for (int m = 0; m < PER; ++m) {
                 const int idx = threadIdx.x + m * NT;
@@ -395,6 +452,7 @@ __global__ __launch_bounds__(cols_threads<N>(), (N >= 512 ? 2 : 1) * cols_thread
                         mm = *reinterpret_cast<const unsigned short*>(a.M + mbase + off);
                         if (a.y != nullptr) yy = *reinterpret_cast<const float4*>(a.y + base + off);
                     }
+                    yy.x *= ysgn; yy.y *= ysgn; yy.z *= ysgn1; yy.w *= ysgn1;   // (sign) D y when centred
                     if (mm & 0x00ffu) r0 = make_float2(v0.x * fs - yy.x, v0.y * fs - yy.y);
                     if (mm & 0xff00u) r1 = make_float2(v1.x * fs - yy.z, v1.y * fs - yy.w);
                     buf[Lay::at(l, p)] = r0;
@@ -411,8 +469,12 @@ __global__ __launch_bounds__(cols_threads<N>(), (N >= 512 ? 2 : 1) * cols_thread
                 const int l = 2 * (idx % L2), p = idx / L2;
                 if (l < valid) {
                     const float2 v0 = buf[Lay::at(l, p)], v1 = buf[Lay::at(l + 1, p)];
+                    float sc = a.scale;
+                    if constexpr (MODE == 1) {
+                        if (a.cen_io && ((p + N / 2) & 1)) sc = -sc;
+                    }
                     *reinterpret_cast<float4*>(a.k + base + (long long)p * a.inner + l) =
-                        make_float4(v0.x * a.scale, v0.y * a.scale, v1.x * a.scale, v1.y * a.scale);
+                        make_float4(v0.x * sc, v0.y * sc, v1.x * sc, v1.y * sc);
                 }
             }
         }
@@ -502,6 +564,11 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
     ra.C = g.C; ra.T = g.T; ra.DH = DH;
     ra.scale = 1.0f / sqrtf((float)g.W);
     ra.xs = xs; ra.gs = gs;
+    ra.cen = g.centred ? 1 : 0; ra.par_h = g.ndim_fft >= 2; ra.par_d = g.ndim_fft >= 3; ra.Hh = g.H;
+    {
+        long long half = g.W / 2 + (g.ndim_fft >= 2 ? g.H / 2 : 0) + (g.ndim_fft >= 3 ? g.D / 2 : 0);
+        ra.ysign_bit = (int)(half & 1);
+    }
     ra.n_rows = g.B * g.C * g.T * DH;
     const double E8 = 8.0 * (double)(g.B * g.C * g.T * g.D * g.H * g.W);   // bytes of one k-space sweep
     const double P8 = 8.0 * (double)(g.B * g.T * g.D * g.H * g.W);          // bytes of one image
@@ -520,6 +587,7 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
 
     ColsArgs ca{};
     ca.k = kbuf; ca.y = y; ca.M = M; ca.C = g.C; ca.T = g.T;
+    ca.cen_y = (g.centred && y) ? 1 : 0; ca.ysign_bit = ra.ysign_bit; ca.cen_io = 0; ca.Wrow = g.W;
     if (g.ndim_fft == 2) {
         ca.outer = g.B * g.C * g.T * g.D; ca.inner = g.W; ca.Dq = g.D;
         ca.scale = 1.0f / sqrtf((float)g.H);
@@ -530,6 +598,7 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
         if (e != hipSuccess) return e;
     } else {
         ColsArgs ha = ca;  // H axis: [B*C*T*D][H][W]
+        ha.cen_y = 0;
         ha.outer = g.B * g.C * g.T * g.D; ha.inner = g.W; ha.Dq = g.D;
         ha.scale = 1.0f / sqrtf((float)g.H);
         {
@@ -553,6 +622,24 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
     ra.n_rows = g.B * g.T * DH;
     KernelScope ks("sense_rows_reduce", 0.0, E8 + S8 + P8 + (xs != 0.f ? P8 : 0.0), st);
     return launch_rows(true, (int)g.W, ra, st);
+}
+
+// Measured k-space to hybrid space: the inverse transform (centred when the geometry says so) along the outermost
+// transformed axis, in place: H for two transformed axes, D for three.
+hipError_t kspace_to_hybrid(const gleam_geom& g, float2* y, hipStream_t st) {
+    ColsArgs ca{};
+    ca.k = y; ca.C = g.C; ca.T = g.T; ca.Wrow = g.W;
+    ca.cen_io = g.centred ? 1 : 0;
+    int n;
+    if (g.ndim_fft == 2) {
+        ca.outer = g.B * g.C * g.T * g.D; ca.inner = g.W; ca.Dq = g.D; n = (int)g.H;
+    } else {
+        ca.outer = g.B * g.C * g.T; ca.inner = g.H * g.W; ca.Dq = 1; n = (int)g.D;
+    }
+    ca.scale = 1.0f / sqrtf((float)n);
+    const double E8 = 8.0 * (double)(g.B * g.C * g.T * g.D * g.H * g.W);
+    KernelScope ks("kspace_to_hybrid", 0.0, 2.0 * E8, st);
+    return launch_cols(1, n, ca, st);
 }
 
 }  // namespace gleam

@@ -44,18 +44,31 @@ class SenseRunner:
         return to_complex(self.out)
 
 
-class ModuleRunner:
-    """Device-resident copy of a case; `step()` = one gleam_module_fwd + one gleam_module_bwd."""
+def reduce_if_separable(geom, M_host, y_dev):
+    """When the mask does not depend on the outermost transformed axis, that transform cancels in A^H A: takes the
+    device k-space `y_dev` to hybrid space in place (gleam_kspace_to_hybrid) and returns the geometry with one
+    transformed axis less; otherwise returns `geom` unchanged.  geom: a binding.gleam_geom."""
+    if geom.ndim_fft < 2 or not gb.gleam_mask_constant_along_outer_axis(geom, M_host):
+        return geom
+    gb.gleam_kspace_to_hybrid(geom, y_dev, y_dev)
+    return gb.gleam_geom(geom.ndim_fft - 1, geom.centred, geom.B, geom.C, geom.T, geom.D, geom.H, geom.W)
 
-    def __init__(self, case, theta=None, alpha=None, x_in=None):
+
+class ModuleRunner:
+    """Device-resident copy of a case; `step()` = one gleam_module_fwd + one gleam_module_bwd.
+    separable: use the reduced problem (one transformed axis less, k-space in hybrid space) when the mask allows."""
+
+    def __init__(self, case, theta=None, alpha=None, x_in=None, separable=False):
         self.case = case
         self.geom = gb.make_geom(case.geom)
         self.prox = gb.make_prox(case.prox)
+        self.S, self.M, self.y = cplx(case.S), dev(case.M), cplx(case.y)
+        if separable:
+            self.geom = reduce_if_separable(self.geom, case.M, self.y)
         self.ws_bytes, self.saved_bytes = gb.gleam_workspace_bytes(self.geom, self.prox)
         self.ws = byte_buffer(self.ws_bytes)
         self.saved = byte_buffer(self.saved_bytes)
         self.x_in = cplx(case.x_in if x_in is None else x_in)
-        self.S, self.M, self.y = cplx(case.S), dev(case.M), cplx(case.y)
         self.x_ref = cplx(case.x_true)
         self.theta = dev(np.asarray(case.theta if theta is None else theta, np.float32))
         self.alpha = float(case.alpha if alpha is None else alpha)

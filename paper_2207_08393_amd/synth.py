@@ -13,8 +13,8 @@ Layouts (row-major, last dimension contiguous):
   mask    M  [B][T][D][H][W]        uint8       (non-zero = sampled; no coil dimension)
   k-space y  [B][C][T][D][H][W]     complex64
   theta      flat float32: per layer W[cout][kt][kd][kh][kw][cin], then b[cout] if has_bias
-The Fourier transform is orthonormal and uncentred (zero frequency at index 0) over the
-last `ndim_fft` dimensions.
+The Fourier transform is orthonormal over the last `ndim_fft` dimensions, uncentred (zero
+frequency at index 0) unless the geometry says `centred`.
 """
 from __future__ import annotations
 
@@ -36,6 +36,7 @@ class Geom:
     D: int
     H: int
     W: int
+    centred: int = 0   # 1: frequency and spatial origin in the middle of every transformed axis (fftshift convention)
 
     @property
     def image_shape(self):
@@ -315,13 +316,19 @@ def measure(x_true, S, M, geom: Geom, rng, sigma: float, sigma_rel: bool):
     the Training paragraph names as the network input."""
     axes = tuple(range(6 - geom.ndim_fft, 6))
     c = S[:, :, None].astype(np.complex128) * x_true[:, None].astype(np.complex128)
-    k = np.fft.fftn(c, axes=axes, norm="ortho")
+    if geom.centred:
+        fwd = lambda a: np.fft.fftshift(np.fft.fftn(np.fft.ifftshift(a, axes=axes), axes=axes, norm="ortho"), axes=axes)
+        inv = lambda a: np.fft.fftshift(np.fft.ifftn(np.fft.ifftshift(a, axes=axes), axes=axes, norm="ortho"), axes=axes)
+    else:
+        fwd = lambda a: np.fft.fftn(a, axes=axes, norm="ortho")
+        inv = lambda a: np.fft.ifftn(a, axes=axes, norm="ortho")
+    k = fwd(c)
     m = (M != 0)[:, None]
     k = k * m
     scale = sigma * (np.abs(k).max() if sigma_rel else 1.0)
     noise = rng.standard_normal(k.shape) + 1j * rng.standard_normal(k.shape)
     y = ((k + scale * noise) * m).astype(np.complex64)
-    x0 = (np.conj(S[:, :, None]) * np.fft.ifftn(y.astype(np.complex128), axes=axes, norm="ortho")).sum(1)
+    x0 = (np.conj(S[:, :, None]) * inv(y.astype(np.complex128))).sum(1)
     return y, x0.astype(np.complex64)
 
 
@@ -368,6 +375,8 @@ def make_custom(seed: int, geom: Geom, prox: ProxDesc, accel: float = 4.0, centr
         lines = [[_draw_lines(rng, geom.W, total, cen, mask_kind) for _ in range(geom.T)]
                  for _ in range(geom.B)]
         M = _lines_to_mask(lines, geom)
+    if geom.centred:   # the generators put the low frequencies at index 0: move them to the middle of the array
+        M = np.ascontiguousarray(np.fft.fftshift(M, axes=tuple(range(5 - geom.ndim_fft, 5))))
     y, x0 = measure(x, S, M, geom, rng, sigma, False)
     theta = init_theta(rng, prox, bias_std)
     return Case(name, geom, prox, alpha, x, S, M, y, x0, theta, 1)

@@ -324,3 +324,35 @@ def test_static_scratch_entry_point_checks_on_the_host_first():
     assert L.gleam_sense_normal_static(C.byref(too_big), fake, None, fake, fake, None) == gb.GLEAM_E_NULL
     bad = gb.make_geom(synth.Geom(2, 1, 2, 1, 1, 8, 7))
     assert L.gleam_sense_normal_static(C.byref(bad), fake, fake, fake, fake, None) == gb.GLEAM_E_UNSUPPORTED_SIZE
+
+
+def test_centred_flag_and_hybrid_space_entry_points_check_on_the_host():
+    import numpy as np
+    L = gb.lib()
+    fake = 0x1000
+    w, s_ = C.c_size_t(0), C.c_size_t(0)
+    bad = gb.make_geom(synth.Geom(2, 1, 2, 1, 1, 8, 8, centred=2))
+    assert L.gleam_workspace_bytes(C.byref(bad), None, C.byref(w), C.byref(s_)) == gb.GLEAM_E_DIMS
+    ok = gb.make_geom(synth.Geom(2, 1, 2, 1, 1, 8, 8, centred=1))
+    assert L.gleam_workspace_bytes(C.byref(ok), None, C.byref(w), C.byref(s_)) == gb.GLEAM_OK
+    assert L.gleam_kspace_to_hybrid(C.byref(ok), None, fake, None) == gb.GLEAM_E_NULL
+    assert L.gleam_kspace_to_hybrid(C.byref(ok), fake, None, None) == gb.GLEAM_E_NULL
+    one_axis = gb.make_geom(synth.Geom(1, 1, 2, 1, 1, 8, 8))
+    assert L.gleam_kspace_to_hybrid(C.byref(one_axis), fake, fake, None) == gb.GLEAM_E_DIMS       # no axis to remove
+    # mask check: nonzero-ness, per outer index, along H (two transformed axes) or D (three)
+    g2 = synth.Geom(2, 2, 1, 2, 3, 4, 6)
+    M = np.zeros(g2.image_shape, np.uint8)
+    M[..., [0, 3]] = 1                                  # lines along W, the same for every H: constant along H
+    M[1, 1, 2, :, 5] = 7                                # another line in one slice, any non-zero byte counts
+    assert gb.gleam_mask_constant_along_outer_axis(gb.make_geom(g2), M)
+    M2 = M.copy(); M2[1, 0, 1, 2, 4] = 1                # one extra point: H matters now
+    assert not gb.gleam_mask_constant_along_outer_axis(gb.make_geom(g2), M2)
+    g3 = synth.Geom(3, 1, 1, 2, 4, 4, 6)
+    P = (np.random.default_rng(0).random((1, 2, 1, 4, 6)) < 0.4).astype(np.uint8)
+    M3 = np.broadcast_to(P, g3.image_shape).copy()      # a pattern on the (H, W) plane, the same for every D
+    assert gb.gleam_mask_constant_along_outer_axis(gb.make_geom(g3), M3)
+    M3[0, 1, 2, 0, 0] ^= 1
+    assert not gb.gleam_mask_constant_along_outer_axis(gb.make_geom(g3), M3)
+    out = C.c_int(0)
+    assert L.gleam_mask_constant_along_outer_axis(C.byref(one_axis), fake, C.byref(out)) == gb.GLEAM_E_DIMS
+    assert L.gleam_mask_constant_along_outer_axis(C.byref(ok), None, C.byref(out)) == gb.GLEAM_E_NULL

@@ -38,14 +38,15 @@ SENSE_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("centred", [0, 1], ids=["uncentred", "centred"])
 @pytest.mark.parametrize("shape", SENSE_SHAPES, ids=lambda s: "x".join(map(str, s[:-1])) + s[-1])
-def test_sense_normal_matches_oracle(shape):
+def test_sense_normal_matches_oracle(shape, centred):
     nd, B, C_, T, D, H, W, kind = shape
-    geom = synth.Geom(nd, B, C_, T, D, H, W)
+    geom = synth.Geom(nd, B, C_, T, D, H, W, centred=centred)
     c = synth.make_custom(100 + H + W, geom, _tiny_prox(), accel=3.0, centre=2, mask_kind=kind)
-    print("case", shape, flush=True)
+    print("case", shape, "centred" if centred else "uncentred", flush=True)
     got = run_sense_normal(geom, c.x_true, c.S, c.M)
-    ref = og.sense_normal(c.x_true, c.S, c.M, nd)
+    ref = og.sense_normal(c.x_true, c.S, c.M, nd, centred=bool(centred))
     assert_image_close(got, ref, TOL, "A^H A x")
 
 
@@ -637,20 +638,91 @@ def test_fallback_kernels_of_the_two_channel_layers_and_the_27_tap_gradient(kern
         check_module(c, tol=tol)
 
 
-# ----------------------------------------------------------------------------- one transformed axis
-def test_single_axis_module_matches_oracle_and_the_2d_problem():
-    """ndim_fft = 1: module step against the oracle, and the same 2D problem (line mask, constant along H) solved
-    through the 2D path gives the same data-consistency step when its k-space is taken to hybrid space first."""
-    prox = synth.resblock_prox(8, 1)
-    c2 = synth.make_custom(81, synth.Geom(2, 2, 3, 1, 1, 12, 20), prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.7)
-    assert np.all(c2.M == c2.M[..., :1, :])
-    y_hyb = og.dft_axis(c2.y.astype(np.complex128), axis=c2.y.ndim - 2, inverse=True).astype(np.complex64)
-    g1 = synth.Geom(1, 2, 3, 1, 1, 12, 20)
-    c1 = synth.Case(**{**c2.__dict__, "geom": g1, "y": y_hyb})
-    print("case single axis", flush=True)
-    r1, f1 = check_module(c1, alpha=0.7)
-    r2 = ModuleRunner(c2, alpha=0.7)
-    r2.step()
+# ----------------------------------------------------------------------------- centred transform
+def centred_cases():
+    yield "res2d", synth.Geom(2, 2, 3, 1, 1, 12, 10, centred=1), synth.resblock_prox(8, 1), "vd", 1
+    yield "odd_halves", synth.Geom(2, 1, 2, 1, 1, 6, 10, centred=1), synth.resblock_prox(4, 1), "uniform", 0   # 3 + 5: sign -1... +1
+    yield "vol3d", synth.Geom(3, 1, 2, 1, 6, 10, 12, centred=1), synth.chain_prox([2, 8, 8, 2], [K3] * 3), "random2d", 0
+    yield "cine", synth.Geom(2, 1, 2, 4, 1, 6, 8, centred=1), synth.chain_prox([2, 8, 8, 2], [KS, KT, KT]), "vd", 0
+    yield "slices", synth.Geom(2, 1, 2, 1, 3, 10, 6, centred=1), synth.resblock_prox(4, 1), "random2d", 0      # D batched
+    yield "one_axis", synth.Geom(1, 2, 3, 1, 2, 5, 46, centred=1), synth.resblock_prox(4, 1), "vd", 0
+
+
+@pytest.mark.parametrize("name,geom,prox,kind,loss_kind", list(centred_cases()), ids=[m[0] for m in centred_cases()])
+def test_centred_module_matches_oracle(name, geom, prox, kind, loss_kind):
+    """centred = 1 (frequency and spatial origin in the middle of every transformed axis): the module step against the
+    oracle's explicit centred DFT, with measured k-space and mask in centred index order."""
+    prox.loss_kind = loss_kind
+    c = synth.make_custom(91, geom, prox, accel=2.0, centre=2, mask_kind=kind, bias_std=0.1, alpha=0.8)
+    print("case centred", name, flush=True)
+    check_module(c)
+    # junk off the mask is still ignored, and the uncentred reading of the same arrays is a different problem
+    r = ModuleRunner(c)
+    r.fwd()
+    x_c = r.results()[0].copy()
+    cu = synth.Case(**{**c.__dict__, "geom": synth.Geom(**{**c.geom.__dict__, "centred": 0})})
+    ru = ModuleRunner(cu)
+    ru.fwd()
+    assert rel_l2(ru.results()[0], x_c) > 100 * TOL
+
+
+# ----------------------------------------------------------------------------- hybrid space / one transformed axis less
+@pytest.mark.parametrize("centred", [0, 1], ids=["uncentred", "centred"])
+@pytest.mark.parametrize("nd,dims", [(2, (2, 3, 2, 2, 12, 20)), (2, (1, 2, 1, 1, 46, 6)), (3, (1, 2, 2, 16, 6, 10)),
+                                     (3, (1, 3, 1, 8, 12, 20))],
+                         ids=["2d", "2d_radix23", "3d", "3d_b"])
+def test_kspace_to_hybrid_matches_oracle(nd, dims, centred):
+    """gleam_kspace_to_hybrid: the inverse transform along the outermost transformed axis only, out of place (input
+    untouched) and in place, against the oracle's explicit DFT along that axis."""
+    from paper_2207_08393_amd.runner import cplx, to_complex
+    B, C_, T, D, H, W = dims
+    geom = synth.Geom(nd, B, C_, T, D, H, W, centred=centred)
+    rng = np.random.default_rng(nd + 10 * centred)
+    y = (rng.standard_normal(geom.kspace_shape) + 1j * rng.standard_normal(geom.kspace_shape)).astype(np.complex64)
+    axis = y.ndim - nd
+    ref = og.dft_axis(y.astype(np.complex128), axis, inverse=True, centred=bool(centred))
+    g = gb.make_geom(geom)
+    y_dev = cplx(y)
+    out = torch.full_like(y_dev, float("nan"))
+    gb.gleam_kspace_to_hybrid(g, y_dev, out)
+    torch.cuda.synchronize()
+    assert_close(to_complex(out), ref, TOL, "hybrid k-space, out of place")
+    assert np.array_equal(to_complex(y_dev), y)
+    gb.gleam_kspace_to_hybrid(g, y_dev, y_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_complex(y_dev).view(np.uint32), to_complex(out).view(np.uint32))   # in place: same bits
+
+
+@pytest.mark.parametrize("centred", [0, 1], ids=["uncentred", "centred"])
+@pytest.mark.parametrize("nd", [2, 3])
+def test_reduced_problem_built_by_the_library_equals_the_full_one(nd, centred):
+    """A mask that does not depend on the outermost transformed axis (line masks along W for two transformed axes, a
+    fully sampled read-out D for three): the runner asks gleam_mask_constant_along_outer_axis, takes the measured
+    k-space to hybrid space with gleam_kspace_to_hybrid and runs the module with one transformed axis less.  That
+    step against the oracle ON THE FULL PROBLEM, and against the library's own full-dimensional step."""
+    if nd == 2:
+        geom = synth.Geom(2, 2, 3, 1, 1, 12, 20, centred=centred)
+        c = synth.make_custom(81, geom, synth.resblock_prox(8, 1), accel=2.0, centre=2, bias_std=0.1, alpha=0.7)
+        assert np.all(c.M == c.M[..., :1, :])
+    else:
+        geom = synth.Geom(3, 1, 2, 1, 8, 10, 12, centred=centred)
+        c = synth.make_custom(82, geom, synth.chain_prox([2, 8, 8, 2], [K3] * 3), accel=2.0, centre=2, mask_kind="random2d",
+                              bias_std=0.1, alpha=0.7)
+        assert np.all(c.M == c.M[:, :, :1])
+    print("case reduced problem", nd, "centred" if centred else "uncentred", flush=True)
+    r1 = ModuleRunner(c, separable=True)
+    assert r1.geom.ndim_fft == nd - 1
+    r1.step()
     x1, l1, gr1 = r1.results()
+    f = og.module_fwd(c.geom, c.prox, c.x_in, c.S, c.M, c.y, c.alpha, c.theta, c.x_true)      # the full problem
+    gref = og.module_bwd(c.prox, c.theta, f)
+    assert_image_close(x1, f["x_out"], TOL)
+    assert abs(l1 - f["loss"]) <= TOL * abs(f["loss"])
+    assert_grad_close(c.prox, gr1, gref, TOL)
+    r2 = ModuleRunner(c)
+    r2.step()
     x2, l2, gr2 = r2.results()
     assert rel_l2(x1, x2) <= TOL and abs(l1 - l2) <= TOL * abs(l2) and rel_l2(gr1, gr2) <= TOL
+    # a mask that does depend on the axis keeps the full problem
+    c.M[0, 0, 0, 1, 1] ^= 1
+    assert ModuleRunner(c, separable=True).geom.ndim_fft == nd

@@ -240,6 +240,68 @@ def test_generator_measurement_of_the_cine_shaped_case_matches_the_oracle():
     assert np.abs(og.sense_adjoint(y, S, M, 2) - x0).max() <= 1e-5 * np.abs(x0).max()
 
 
+# ----------------------------------------------------------------------------- centred transform (variant of F)
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 8, 10, 23, 46, 160])
+def test_centred_dft_is_fftshift_fft_ifftshift(n):
+    """The centred matrix against the library composition fftshift . fft . ifftshift (odd lengths included, where the
+    two shifts differ), forward and inverse, and the closed forms that fix what "centred" means: a delta at the
+    spatial centre transforms to a constant, a constant to a delta at the frequency centre."""
+    r = np.random.default_rng(n)
+    x = r.standard_normal((3, n)) + 1j * r.standard_normal((3, n))
+    ref = np.fft.fftshift(np.fft.fft(np.fft.ifftshift(x, axes=-1), axis=-1, norm="ortho"), axes=-1)
+    got = og.dft_axis(x, 1, centred=True)
+    assert np.allclose(got, ref, atol=1e-12)
+    refi = np.fft.fftshift(np.fft.ifft(np.fft.ifftshift(x, axes=-1), axis=-1, norm="ortho"), axes=-1)
+    assert np.allclose(og.dft_axis(x, 1, inverse=True, centred=True), refi, atol=1e-12)
+    assert np.allclose(og.dft_axis(got, 1, inverse=True, centred=True), x, atol=1e-12)          # unitary
+    d = np.zeros((1, n), complex)
+    d[0, n // 2] = 1.0
+    assert np.allclose(og.dft_axis(d, 1, centred=True), 1.0 / np.sqrt(n), atol=1e-12)
+    assert np.allclose(og.dft_axis(np.ones((1, n)), 1, centred=True), np.sqrt(n) * d, atol=1e-12)
+    if n > 2:
+        assert not np.allclose(got, og.dft_axis(x, 1), atol=1e-6)                              # and it is a different transform
+
+
+def test_centred_dft_for_even_lengths_is_sign_flips_around_the_uncentred_one():
+    """For even n: F_c = (-1)^(n/2) D F D with D = diag((-1)^index): the identity the device path uses to run the
+    centred variant on its uncentred transform (sign of the inputs and outputs, nothing else)."""
+    for n in (2, 4, 6, 10, 46, 160):
+        r = np.random.default_rng(n)
+        x = r.standard_normal(n) + 1j * r.standard_normal(n)
+        D = (-1.0) ** np.arange(n)
+        s = (-1.0) ** (n // 2)
+        assert np.allclose(og.dft_axis(x[None], 1, centred=True)[0], s * D * og.dft_axis((D * x)[None], 1)[0], atol=1e-12)
+
+
+@pytest.mark.parametrize("nd", [1, 2, 3])
+def test_centred_operator_adjoint_identity_full_sampling_and_sign_flip_form(nd):
+    geom = synth.Geom(nd, 2, 3, 2, 4, 6, 8, centred=1)
+    prox = synth.chain_prox([2, 4, 2], [(1, 1, 3, 3)] * 2)
+    c = synth.make_custom(40 + nd, geom, prox, accel=2.0, centre=2, mask_kind="random2d" if nd > 1 else "uniform", sigma=0.0)
+    r = np.random.default_rng(nd)
+    x = r.standard_normal(geom.image_shape) + 1j * r.standard_normal(geom.image_shape)
+    z = r.standard_normal(geom.kspace_shape) + 1j * r.standard_normal(geom.kspace_shape)
+    Ax = og.sense_forward(x, c.S, c.M, nd, centred=True)
+    AHz = og.sense_adjoint(z, c.S, c.M, nd, centred=True)
+    assert np.isclose(np.vdot(z, Ax), np.vdot(AHz, x), rtol=1e-12)                            # <Ax, z> = <x, A^H z>
+    ones = np.ones_like(c.M)
+    assert np.allclose(og.sense_normal(x, c.S, ones, nd, centred=True), x, atol=1e-12)          # full sampling: identity
+    # the generator's measurement (library FFT with shifts) is the centred operator, and x_in its adjoint on y
+    assert np.allclose(og.sense_forward(c.x_true, c.S, c.M, nd, centred=True), c.y, atol=1e-5)
+    assert np.allclose(og.sense_adjoint(c.y, c.S, c.M, nd, centred=True), c.x_in, atol=1e-5)
+    # sign-flip form of the whole data-consistency step: u = D dc_uncentred(D x, s D y) with the mask array as stored
+    axes = geom.image_shape[5 - nd:]
+    idx = np.indices(axes).sum(0)
+    D = (-1.0) ** idx
+    s = np.prod([(-1.0) ** (n // 2) for n in axes])
+    u_c = og.dc_step(x, c.S, c.M, c.y, 0.8, nd, centred=True)
+    u_u = D * og.dc_step(D * x, c.S, c.M, s * D * c.y, 0.8, nd)
+    assert np.allclose(u_c, u_u, atol=1e-10)
+    # and the mask of a centred case keeps its low frequencies in the middle of the array
+    mid = tuple(n // 2 for n in axes)
+    assert np.all(c.M[(slice(None),) * (5 - nd) + mid] == 1) or nd == 1
+
+
 def test_generator_mask_counts_all_configs():
     g = synth
     rng = np.random.default_rng(1)
