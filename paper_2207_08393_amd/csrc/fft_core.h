@@ -1,7 +1,7 @@
 // In-LDS mixed-radix Stockham FFT building blocks for gfx950 (wave64).
 //
-// A transform of length N is a product of radices chosen at compile time (16 or whatever
-// remains once it fits in registers, e.g. 368 = 16 * 23, 320 = 16 * 20, 640 = 16 * 8 * 5).  Each stage reads R points at stride
+// A transform of length N is a product of radices chosen at compile time (see next_radix: e.g. 368 = 23 * 4 * 4,
+// 320 = 20 * 4 * 4, 640 = 20 * 4 * 4 * 2, 46 = 2 * 23).  Each stage reads R points at stride
 // N/R from the LDS buffer, applies the stage twiddles and an R-point DFT held in registers, and
 // writes them back autosorted (in place, with a barrier between the reads and the writes), so the
 // result comes out in natural order with no bit-reversal pass.  Transforms are unnormalised here; callers scale at their global store.
@@ -188,10 +188,30 @@ template <int R, bool INV> __device__ __forceinline__ void dft_r(float2 (&u)[R])
 }
 
 // ------------------------------------------------------------------ radix plan
-// Radix of the stage that follows a partial product P (P divides N): whatever is left once it fits in
-// registers (<= 24 points), otherwise the largest power of two up to 16, otherwise a small prime.
-constexpr int next_radix(int N, int P) {
+// Radix of the stage that follows a partial product P (P divides N), for one of two plans.
+// PLAN 0: whatever is left once it fits in registers (<= 24 points), otherwise the largest power of two up to 16,
+//         otherwise a small prime (368 = 16.23, 320 = 16.20, 640 = 16.8.5, 160 = 16.10): few stages, few barriers.
+// PLAN 1: one large in-register DFT first - it needs no stage twiddles - then radix-4 stages (640 = 20.4.4.2,
+//         368 = 23.4.4, 320 = 20.4.4, 192 = 12.4.4, 160 = 10.4.4), which with the right number of lines per tile gives
+//         every stage a whole multiple of 256 butterflies, so that the four waves of a 256-thread workgroup carry the
+//         same load in every stage; lengths without such a split fall back to plan 0.
+// Which plan a sweep uses is part of its tile configuration (sense.hip), chosen by measurement.
+constexpr int plan1_first_radix(int N) {
+    switch (N) {
+        case 640: return 20;
+        case 368: return 23;
+        case 320: return 20;
+        case 192: return 12;
+        case 160: return 10;
+        default: return 0;
+    }
+}
+constexpr int next_radix(int N, int P, int PLAN = 0) {
     int m = N / P;
+    if (PLAN == 1 && plan1_first_radix(N) != 0) {
+        if (P == 1) return plan1_first_radix(N);
+        return m % 4 == 0 ? 4 : m;
+    }
     if (m <= 24) return m;
     if (m % 16 == 0) return 16;
     if (m % 8 == 0) return 8;
@@ -215,9 +235,9 @@ template <int N, int L, int PAD> struct Layout {
 // One Stockham stage over L lines held in one LDS buffer, in place: every thread first pulls the
 // inputs of all its butterflies into registers, the workgroup synchronises, then results are written
 // back autosorted.  Ends with a barrier, so the buffer is ready for the next stage or for readers.
-template <int N, int L, int PAD, bool INV, int P, int NT>
+template <int N, int L, int PAD, bool INV, int P, int NT, int PLAN>
 __device__ __forceinline__ void fft_stage(float2* __restrict__ buf, const float2* __restrict__ tw) {
-    constexpr int R = next_radix(N, P);
+    constexpr int R = next_radix(N, P, PLAN);
     constexpr int T = N / R;
     constexpr int PER = (L * T + NT - 1) / NT;
     using Lay = Layout<N, L, PAD>;
@@ -257,11 +277,11 @@ __device__ __forceinline__ void fft_stage(float2* __restrict__ buf, const float2
 
 // All stages, in place.  The caller synchronises after filling `buf`; the result is visible to the
 // whole workgroup on return.
-template <int N, int L, int PAD, bool INV, int NT, int P = 1>
+template <int N, int L, int PAD, bool INV, int NT, int PLAN = 0, int P = 1>
 __device__ __forceinline__ void fft_lines(float2* buf, const float2* tw) {
     if constexpr (P < N) {
-        fft_stage<N, L, PAD, INV, P, NT>(buf, tw);
-        fft_lines<N, L, PAD, INV, NT, P * next_radix(N, P)>(buf, tw);
+        fft_stage<N, L, PAD, INV, P, NT, PLAN>(buf, tw);
+        fft_lines<N, L, PAD, INV, NT, PLAN, P * next_radix(N, P, PLAN)>(buf, tw);
     }
 }
 

@@ -16,14 +16,22 @@
 namespace gleam {
 
 // Lines (rows or columns) per workgroup tile and threads per workgroup, by transform length.  Tiles hold
-// 16 or more lines so that every LDS access of a butterfly stage is conflict free (see Layout).
+// 8 or more lines so that every LDS access of a butterfly stage is conflict free (see Layout).  Chosen by
+// measurement on the transform-only sweeps (load, transform, store): e.g. 160 x 32 lines on 512 threads and
+// 368 x 16 lines on 256 threads for the contiguous axis, 640 x 8 and 256 x 32 lines on 512 threads for the strided one.
 template <int N> constexpr int rows_lines() { return N > 384 ? 8 : (N >= 192 ? 16 : (N >= 96 ? 32 : 64)); }
-template <int N> constexpr int rows_threads() { return N * rows_lines<N>() >= 4096 ? 512 : 256; }
-// The coil-reduction kernel transforms fewer lines at a time: smaller tiles, more workgroups per CU.
-template <int N> constexpr int reduce_lines() { return N >= 192 ? 8 : rows_lines<N>(); }
-template <int N> constexpr int reduce_threads() { return N >= 192 ? 256 : rows_threads<N>(); }
-template <int N> constexpr int cols_lines() { return N >= 512 ? 8 : 16; }
+template <int N> constexpr int rows_threads() { return (N * rows_lines<N>() >= 4096 && N != 368) ? 512 : 256; }
+// The coil-reduction kernel transforms the same tiles.
+template <int N> constexpr int reduce_lines() { return rows_lines<N>(); }
+template <int N> constexpr int reduce_threads() { return rows_threads<N>(); }
+template <int N> constexpr int cols_lines() { return N >= 512 ? 8 : (N == 256 ? 32 : 16); }
 template <int N> constexpr int cols_threads() { return N >= 192 ? 512 : 256; }
+// Waves per SIMD the compiler is asked to leave room for.  The middle sweep of the lengths whose butterflies are at
+// most 16 points wide would otherwise take ~140-150 registers (the unrolled mask stage) and drop from two resident
+// 512-thread workgroups per CU to one; at 128 registers it keeps two (a handful of spilled values, measured faster).
+template <int N, int MODE> constexpr int cols_min_waves() {
+    return (MODE >= 2 && (N == 640 || N == 256 || N == 192)) ? 4 : 1;
+}
 
 struct RowsArgs {
     const float2* x;      // image [B][T][DH][W]
@@ -31,7 +39,7 @@ struct RowsArgs {
     float2* k;            // k-space [B][C][T][DH][W]
     float2* out;          // image (reduce only)
     long long C, T, DH;   // DH = D*H rows per frame
-    long long n_rows;     // expand: B*C*T*DH k-space rows ; reduce: B*T*DH image rows
+    long long n_rows;     // B*T*DH image rows
     float scale;          // N^-1/2
     float xs, gs;         // reduce: out = xs*x + gs*g
     // Centred transform (frequency and spatial origin in the middle of every transformed axis; all lengths are even):
@@ -54,80 +62,106 @@ __device__ __forceinline__ unsigned row_parity(const RowsArgs& a, long long dh) 
     return (unsigned)(((a.par_h ? h : 0) + (a.par_d ? d : 0)) & 1);
 }
 
-// Forward transform along W of S*x: L consecutive k-space rows per tile, coil multiply fused into the
-// load, two complex values (16 bytes) per global access.
+// Forward transform along W of S*x.  A tile is LR image rows x CG coils (LR*CG <= L lines), so that an image row
+// is fetched from memory once and reused from cache for all of its coils (tiles of consecutive k-space rows would
+// come back to the same image row once per coil, megabytes later); coil multiply fused into the load, two complex
+// values (16 bytes) per global access.
 template <int N>
 __global__ __launch_bounds__(rows_threads<N>()) void rows_expand_kernel(RowsArgs a) {
     constexpr int L = rows_lines<N>(), NT = rows_threads<N>(), H2 = N / 2;
     using Lay = Layout<N, L, 1>;
     __shared__ float2 buf[Lay::kElems], tw[N];
-    __shared__ long long xoff[L], soff[L];
+    __shared__ long long xoff[L], soff[L], koff[L];   // per image row of the tile: image, coil map (coil 0), k-space (coil 0)
     __shared__ unsigned lpar[L];
     fill_twiddles<N, NT>(tw);
-    const long long n_tiles = (a.n_rows + L - 1) / L;
+    const int CG = a.C < L ? (int)a.C : L;        // coils transformed together
+    const int LR = L / CG;                        // image rows per tile
+    const long long n_tiles = (a.n_rows + LR - 1) / LR;
+    const long long kstride = a.T * a.DH * N, sstride = a.DH * N;
     for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         __syncthreads();
-        if (threadIdx.x < L) {
-            const long long row = tile * L + threadIdx.x;   // k-space row (b, c, t, dh)
-            long long xo = -1, so = -1;
+        if (threadIdx.x < LR) {
+            const long long row = tile * LR + threadIdx.x;   // image row (b, t, dh)
+            long long xo = -1, so = -1, ko = -1;
             unsigned par = 0u;
             if (row < a.n_rows) {
                 const long long dh = row % a.DH;
-                const long long t = (row / a.DH) % a.T;
-                const long long bc = row / (a.DH * a.T);
-                xo = (((bc / a.C) * a.T + t) * a.DH + dh) * N;
-                so = (bc * a.DH + dh) * N;
+                const long long bt = row / a.DH;
+                const long long t = bt % a.T, b = bt / a.T;
+                xo = row * N;
+                so = ((b * a.C) * a.DH + dh) * N;
+                ko = (((b * a.C) * a.T + t) * a.DH + dh) * N;
                 par = row_parity(a, dh);
             }
             xoff[threadIdx.x] = xo;
             soff[threadIdx.x] = so;
+            koff[threadIdx.x] = ko;
             lpar[threadIdx.x] = par;
         }
         __syncthreads();
-        for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
-            const int line = idx / H2, p = 2 * (idx % H2);
-            float2 v0 = make_float2(0.f, 0.f), v1 = v0;
-            if (xoff[line] >= 0) {
-                const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[line] + p);
-                const float4 xv = *reinterpret_cast<const float4*>(a.x + xoff[line] + p);
-                v0 = cmul(make_float2(sv.x, sv.y), make_float2(xv.x, xv.y));
-                v1 = cmul(make_float2(sv.z, sv.w), make_float2(xv.z, xv.w));
-                if (a.cen) {   // D x: p is even, so the pair's signs are the row's parity and its opposite
-                    v0 = flip_sign(v0, lpar[line]);
-                    v1 = flip_sign(v1, lpar[line] ^ 1u);
+        for (int c0 = 0; c0 < a.C; c0 += CG) {
+            const int ncg = a.C - c0 < CG ? (int)(a.C - c0) : CG;
+            // line l = r*CG + c holds coil c0 + c of image row r; unused lines are zero
+            for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
+                const int line = idx / H2, p = 2 * (idx % H2);
+                const int r = line / CG, c = line % CG;
+                float2 v0 = make_float2(0.f, 0.f), v1 = v0;
+                if (r < LR && c < ncg && xoff[r] >= 0) {
+                    const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[r] + (c0 + c) * sstride + p);
+                    const float4 xv = *reinterpret_cast<const float4*>(a.x + xoff[r] + p);
+                    v0 = cmul(make_float2(sv.x, sv.y), make_float2(xv.x, xv.y));
+                    v1 = cmul(make_float2(sv.z, sv.w), make_float2(xv.z, xv.w));
+                    if (a.cen) {   // D x: p is even, so the pair's signs are the row's parity and its opposite
+                        v0 = flip_sign(v0, lpar[r]);
+                        v1 = flip_sign(v1, lpar[r] ^ 1u);
+                    }
+                }
+                buf[Lay::at(line, p)] = v0;
+                buf[Lay::at(line, p + 1)] = v1;
+            }
+            __syncthreads();
+            fft_lines<N, L, 1, false, NT>(buf, tw);
+            for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
+                const int line = idx / H2, p = 2 * (idx % H2);
+                const int r = line / CG, c = line % CG;
+                if (r < LR && c < ncg && xoff[r] >= 0) {
+                    const float2 v0 = buf[Lay::at(line, p)], v1 = buf[Lay::at(line, p + 1)];
+                    *reinterpret_cast<float4*>(a.k + koff[r] + (c0 + c) * kstride + p) =
+                        make_float4(v0.x * a.scale, v0.y * a.scale, v1.x * a.scale, v1.y * a.scale);
                 }
             }
-            buf[Lay::at(line, p)] = v0;
-            buf[Lay::at(line, p + 1)] = v1;
-        }
-        __syncthreads();
-        fft_lines<N, L, 1, false, NT>(buf, tw);
-        for (int idx = threadIdx.x; idx < H2 * L; idx += NT) {
-            const int line = idx / H2, p = 2 * (idx % H2);
-            if (xoff[line] >= 0) {
-                const float2 v0 = buf[Lay::at(line, p)], v1 = buf[Lay::at(line, p + 1)];
-                *reinterpret_cast<float4*>(a.k + (tile * L + line) * N + p) =
-                    make_float4(v0.x * a.scale, v0.y * a.scale, v1.x * a.scale, v1.y * a.scale);
-            }
+            if (c0 + CG < a.C) __syncthreads();   // the next coil group overwrites the tile
         }
     }
 }
 
 // Inverse transform along W and coil reduction.  A tile is LR image rows x CG coils (LR*CG <= L lines)
 // transformed together; then out = xs*x + gs * sum_c conj(S_c) * row_c is accumulated in registers,
-// looping over coil groups when C > CG.  The per-coil images never leave LDS.
+// looping over coil groups when C > CG.  The per-coil images never leave LDS.  LR is capped so that a thread
+// owns at most kRedAcc output pairs (two accumulators keep the register count where three workgroups fit a CU).
+constexpr int kRedAcc = 2;
+template <int N> constexpr int reduce_rows_max() {
+    constexpr int m = kRedAcc * reduce_threads<N>() / (N / 2);
+    return m < 1 ? 1 : m;
+}
+static inline int reduce_rows_per_tile(int L, int LRmax, long long C) {
+    const int cg = C < L ? (int)C : L;
+    const int lr = L / cg;
+    return lr < LRmax ? lr : LRmax;
+}
+
 template <int N>
-__global__ __launch_bounds__(reduce_threads<N>(), N == 368 ? 2 : 1) void rows_reduce_kernel(RowsArgs a) {
+__global__ __launch_bounds__(reduce_threads<N>()) void rows_reduce_kernel(RowsArgs a) {
     constexpr int L = reduce_lines<N>(), NT = reduce_threads<N>(), H2 = N / 2;
-    constexpr int PER = (H2 * L + NT - 1) / NT;   // output pairs per thread (upper bound: CG = 1)
-    constexpr int kSPre = 8;                      // coil-map values per thread fetched ahead of the transform
+    constexpr int PER = kRedAcc;
+    static_assert(H2 <= PER * NT, "one image row must fit the accumulators");
     using Lay = Layout<N, L, 1>;
     __shared__ float2 buf[Lay::kElems], tw[N];
     __shared__ long long koff[L], soff[L];        // per image row of the tile, coil 0
     __shared__ unsigned lpar[L];
     fill_twiddles<N, NT>(tw);
     const int CG = a.C < L ? (int)a.C : L;        // coils transformed together
-    const int LR = L / CG;                        // image rows per tile
+    const int LR = (L / CG) < reduce_rows_max<N>() ? (L / CG) : reduce_rows_max<N>();   // image rows per tile
     const long long n_tiles = (a.n_rows + LR - 1) / LR;
     const long long kstride = a.T * a.DH * N, sstride = a.DH * N;
     for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -164,18 +198,6 @@ __global__ __launch_bounds__(reduce_threads<N>(), N == 368 ? 2 : 1) void rows_re
                 buf[Lay::at(line, p)] = make_float2(v.x, v.y);
                 buf[Lay::at(line, p + 1)] = make_float2(v.z, v.w);
             }
-            // the coil maps of this thread's first output pair are fetched before the transform, so their
-            // latency is hidden behind it (tiles of one image row, the common case, have one pair per thread)
-            float4 s0[kSPre];
-            {
-                const int e = threadIdx.x;
-                const int r = e / H2, p = 2 * (e % H2);
-                const bool ok = e < H2 * LR && koff[r < LR ? r : 0] >= 0;
-                const float2* sp = a.S + (ok ? soff[r] + (long long)c0 * sstride + p : 0);
-#pragma unroll
-                for (int c = 0; c < kSPre; ++c)
-                    s0[c] = *reinterpret_cast<const float4*>(sp + (ok && c < ncg ? c * sstride : 0));
-            }
             __syncthreads();
             fft_lines<N, L, 1, true, NT>(buf, tw);
 #pragma unroll
@@ -184,23 +206,22 @@ __global__ __launch_bounds__(reduce_threads<N>(), N == 368 ? 2 : 1) void rows_re
                 if (e < H2 * LR) {
                     const int r = e / H2, p = 2 * (e % H2);
                     if (koff[r] >= 0) {
-                        if (m == 0 && CG <= kSPre) {
+                        const float2* sp = a.S + soff[r] + (long long)c0 * sstride + p;
+                        // coil maps four at a time: the loads of a group are in flight together
+                        for (int c = 0; c < ncg; c += 4) {
+                            float4 sv[4];
 #pragma unroll
-                            for (int c = 0; c < kSPre; ++c) {
-                                if (c < ncg) {
-                                    const float2 v0 = buf[Lay::at(r * CG + c, p)], v1 = buf[Lay::at(r * CG + c, p + 1)];
-                                    const float2 p0 = cmul_conj(v0, make_float2(s0[c].x, s0[c].y));
-                                    const float2 p1 = cmul_conj(v1, make_float2(s0[c].z, s0[c].w));
+                            for (int j = 0; j < 4; ++j)
+                                sv[j] = *reinterpret_cast<const float4*>(sp + (c + j < ncg ? (c + j) * sstride : 0));
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                if (c + j < ncg) {
+                                    const float2 v0 = buf[Lay::at(r * CG + c + j, p)], v1 = buf[Lay::at(r * CG + c + j, p + 1)];
+                                    const float2 p0 = cmul_conj(v0, make_float2(sv[j].x, sv[j].y));
+                                    const float2 p1 = cmul_conj(v1, make_float2(sv[j].z, sv[j].w));
                                     acc[m].x += p0.x; acc[m].y += p0.y; acc[m].z += p1.x; acc[m].w += p1.y;
                                 }
                             }
-                        } else
-                        for (int c = 0; c < ncg; ++c) {
-                            const float4 sv = *reinterpret_cast<const float4*>(a.S + soff[r] + (c0 + c) * sstride + p);
-                            const float2 v0 = buf[Lay::at(r * CG + c, p)], v1 = buf[Lay::at(r * CG + c, p + 1)];
-                            const float2 p0 = cmul_conj(v0, make_float2(sv.x, sv.y));
-                            const float2 p1 = cmul_conj(v1, make_float2(sv.z, sv.w));
-                            acc[m].x += p0.x; acc[m].y += p0.y; acc[m].z += p1.x; acc[m].w += p1.y;
                         }
                     }
                 }
@@ -238,13 +259,13 @@ template <int N>
 __global__ __launch_bounds__(reduce_threads<N>()) void rows_fused_kernel(RowsArgs a, const float2* __restrict__ y,
                                                                          const unsigned char* __restrict__ M) {
     constexpr int L = reduce_lines<N>(), NT = reduce_threads<N>(), H2 = N / 2;
-    constexpr int PER = (H2 * L + NT - 1) / NT;
+    constexpr int PER = kRedAcc;
     using Lay = Layout<N, L, 1>;
     __shared__ float2 buf[Lay::kElems], tw[N];
     __shared__ long long koff[L], soff[L], xoff[L];   // per image row of the tile: k-space (coil 0), coil map (coil 0), image
     fill_twiddles<N, NT>(tw);
     const int CG = a.C < L ? (int)a.C : L;
-    const int LR = L / CG;
+    const int LR = (L / CG) < reduce_rows_max<N>() ? (L / CG) : reduce_rows_max<N>();
     const long long n_tiles = (a.n_rows + LR - 1) / LR;
     const long long kstride = a.T * a.DH * N, sstride = a.DH * N;
     for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -361,15 +382,47 @@ struct ColsArgs {
     long long Wrow;
 };
 
+// Mask bytes of a column tile ([N rows][L columns], row p at mb + p*L) into LDS.  One thread fetches a whole row
+// segment with a single 8- or 16-byte load where the addresses allow it (2-byte loads per element pair would issue as
+// many memory requests as the k-space tile itself); columns past `valid` read as 0.
+template <int N, int L, int NT>
+__device__ __forceinline__ void load_mask_tile(const unsigned char* __restrict__ M, long long mbase, long long inner, int valid,
+                                               unsigned char* mb) {
+    const bool vec = valid == L && (inner % L) == 0 && ((reinterpret_cast<unsigned long long>(M) + (unsigned long long)mbase) % L) == 0;
+    if (vec) {
+        if constexpr (L == 8) {
+            for (int p = threadIdx.x; p < N; p += NT)
+                *reinterpret_cast<uint2*>(mb + p * L) = *reinterpret_cast<const uint2*>(M + mbase + (long long)p * inner);
+        } else {
+            constexpr int Q = L / 16;
+            for (int i = threadIdx.x; i < N * Q; i += NT) {
+                const int p = i / Q, q = i % Q;
+                *reinterpret_cast<uint4*>(mb + p * L + 16 * q) = *reinterpret_cast<const uint4*>(M + mbase + (long long)p * inner + 16 * q);
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < N * (L / 2); i += NT) {
+            const int l = 2 * (i % (L / 2)), p = i / (L / 2);
+            unsigned short v = 0;
+            if (l < valid) v = *reinterpret_cast<const unsigned short*>(M + mbase + (long long)p * inner + l);
+            *reinterpret_cast<unsigned short*>(mb + p * L + l) = v;
+        }
+    }
+}
+
 // Strided axis: a tile is 16 neighbouring columns (128 contiguous bytes per row) of one [N][inner] plane.
-// MODE 0: forward, 1: inverse, 2: forward -> (mask ? k - y : 0) -> inverse.  In MODE 2 the measured
+// MODE 0: forward, 1: inverse, 2: forward -> (mask ? k : 0) -> inverse, 3: forward -> (mask ? k - y : 0) -> inverse
+// (a kernel of its own: with the y path merely compiled in, the sweep without y ran 20-30 % slower).  In MODE 2 the measured
 // k-space and the mask bytes of the tile are fetched into registers before the forward transform.
 template <int N, int MODE>
-__global__ __launch_bounds__(cols_threads<N>(), ((N >= 512 || (N == 256 && MODE == 2)) ? 2 : 1) * cols_threads<N>() / 256) void cols_kernel(ColsArgs a) {
+__global__ __launch_bounds__(cols_threads<N>(), (cols_min_waves<N, MODE>())) void cols_kernel(ColsArgs a) {
     constexpr int L = cols_lines<N>(), NT = cols_threads<N>(), L2 = L / 2;
     constexpr int PER = (N * L2 + NT - 1) / NT;
+    constexpr int kMaskUnroll = PER > 4 ? 4 : PER;   // y loads in flight per thread at the mask stage
     using Lay = Layout<N, L, 0>;
-    __shared__ float2 buf[Lay::kElems], tw[N];
+    __shared__ __attribute__((aligned(16))) float2 buf[Lay::kElems];
+    __shared__ float2 tw[N];
+    __shared__ __attribute__((aligned(16))) unsigned char mb[MODE >= 2 ? N * L : 16];
     fill_twiddles<N, NT>(tw);
     const long long tiles_per = (a.inner + L - 1) / L;
     const long long n_tiles = a.outer * tiles_per;
@@ -381,39 +434,26 @@ __global__ __launch_bounds__(cols_threads<N>(), ((N >= 512 || (N == 256 && MODE 
         const long long base = o * N * a.inner + i0;
         const int valid = (int)((a.inner - i0) < L ? (a.inner - i0) : L);   // even
         long long mbase = 0;
-        if constexpr (MODE == 2) {
+        if constexpr (MODE >= 2) {
             const long long dq = o % a.Dq;
             const long long t = (o / a.Dq) % a.T;
             const long long b = o / (a.Dq * a.T * a.C);
             mbase = ((b * a.T + t) * a.Dq + dq) * N * a.inner + i0;
         }
         __syncthreads();
-        // Long transforms keep two workgroups per CU resident instead (register budget), and fetch the
-        // measured k-space at the mask stage while the other workgroup computes.
-        constexpr bool kPre = MODE == 2 && N < 512;
-        float4 yv[kPre ? PER : 1];
-        unsigned mk[kPre ? PER : 1];
+        if constexpr (MODE >= 2) load_mask_tile<N, L, NT>(a.M, mbase, a.inner, valid, mb);
+        // an element pair (lines l, l+1 of position p) is 16 contiguous bytes in memory and in the LDS tile
 #pragma unroll
         for (int m = 0; m < PER; ++m) {
             const int idx = threadIdx.x + m * NT;
             if (idx < N * L2) {
                 const int l = 2 * (idx % L2), p = idx / L2;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                const long long off = (long long)p * a.inner + l;
-                if (l < valid) v = *reinterpret_cast<const float4*>(a.k + base + off);
+                if (l < valid) v = *reinterpret_cast<const float4*>(a.k + base + (long long)p * a.inner + l);
                 if constexpr (MODE == 1) {
                     if (a.cen_io && (p & 1)) v = make_float4(-v.x, -v.y, -v.z, -v.w);
                 }
-                buf[Lay::at(l, p)] = make_float2(v.x, v.y);
-                buf[Lay::at(l + 1, p)] = make_float2(v.z, v.w);
-                if constexpr (kPre) {
-                    yv[m] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    mk[m] = 0u;
-                    if (l < valid) {
-                        mk[m] = *reinterpret_cast<const unsigned short*>(a.M + mbase + off);
-                        if (a.y != nullptr) yv[m] = *reinterpret_cast<const float4*>(a.y + base + off);
-                    }
-                }
+                *reinterpret_cast<float4*>(&buf[Lay::at(l, p)]) = v;
             }
         }
         __syncthreads();
@@ -422,7 +462,7 @@ __global__ __launch_bounds__(cols_threads<N>(), ((N >= 512 || (N == 256 && MODE 
         } else {
             fft_lines<N, L, 0, false, NT>(buf, tw);
         }
-        if constexpr (MODE == 2) {
+        if constexpr (MODE >= 2) {
             // the forward transform of this axis carries N^-1/2; apply it before subtracting y
             const float fs = rsqrtf((float)N);
             // Centred transform: y enters as (sign) D y.  A thread's elements of one tile share the parity of p (the
@@ -430,33 +470,30 @@ __global__ __launch_bounds__(cols_threads<N>(), ((N >= 512 || (N == 256 && MODE 
             // an even-length row, so the pair's signs are (p + row of the column + sign bit) and the opposite.
             static_assert((NT / L2) % 2 == 0, "parity of p must not depend on m");
             float ysgn = 1.f, ysgn1 = 1.f;
-            if (a.cen_y) {
-                const long long col = i0 + 2 * (threadIdx.x % L2);
-                ysgn = (((threadIdx.x / L2) + col / a.Wrow + a.ysign_bit) & 1) ? -1.f : 1.f;
-                ysgn1 = -ysgn;
+            if constexpr (MODE == 3) {
+                if (a.cen_y) {
+                    const long long col = i0 + 2 * (threadIdx.x % L2);
+                    ysgn = (((threadIdx.x / L2) + col / a.Wrow + a.ysign_bit) & 1) ? -1.f : 1.f;
+                    ysgn1 = -ysgn;
+                }
             }
-#pragma unroll
+            // The measured k-space is fetched here, a few loads in flight per thread: other resident workgroups cover
+            // the latency, and the registers of a full prefetch would cost one of them.
+#pragma unroll kMaskUnroll
             for (int m = 0; m < PER; ++m) {
                 const int idx = threadIdx.x + m * NT;
                 if (idx < N * L2) {
                     const int l = 2 * (idx % L2), p = idx / L2;
-                    const float2 v0 = buf[Lay::at(l, p)], v1 = buf[Lay::at(l + 1, p)];
-                    float2 r0 = make_float2(0.f, 0.f), r1 = r0;
                     float4 yy = make_float4(0.f, 0.f, 0.f, 0.f);
-                    unsigned mm = 0u;
-                    if constexpr (kPre) {
-                        yy = yv[m];
-                        mm = mk[m];
-                    } else if (l < valid) {
-                        const long long off = (long long)p * a.inner + l;
-                        mm = *reinterpret_cast<const unsigned short*>(a.M + mbase + off);
-                        if (a.y != nullptr) yy = *reinterpret_cast<const float4*>(a.y + base + off);
+                    if constexpr (MODE == 3) {
+                        if (l < valid) yy = *reinterpret_cast<const float4*>(a.y + base + (long long)p * a.inner + l);
                     }
-                    yy.x *= ysgn; yy.y *= ysgn; yy.z *= ysgn1; yy.w *= ysgn1;   // (sign) D y when centred
-                    if (mm & 0x00ffu) r0 = make_float2(v0.x * fs - yy.x, v0.y * fs - yy.y);
-                    if (mm & 0xff00u) r1 = make_float2(v1.x * fs - yy.z, v1.y * fs - yy.w);
-                    buf[Lay::at(l, p)] = r0;
-                    buf[Lay::at(l + 1, p)] = r1;
+                    const unsigned mm = *reinterpret_cast<const unsigned short*>(mb + p * L + l);
+                    const float4 v = *reinterpret_cast<const float4*>(&buf[Lay::at(l, p)]);
+                    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (mm & 0x00ffu) { r.x = v.x * fs - ysgn * yy.x; r.y = v.y * fs - ysgn * yy.y; }
+                    if (mm & 0xff00u) { r.z = v.z * fs - ysgn1 * yy.z; r.w = v.w * fs - ysgn1 * yy.w; }
+                    *reinterpret_cast<float4*>(&buf[Lay::at(l, p)]) = r;
                 }
             }
             __syncthreads();
@@ -468,13 +505,13 @@ __global__ __launch_bounds__(cols_threads<N>(), ((N >= 512 || (N == 256 && MODE 
             if (idx < N * L2) {
                 const int l = 2 * (idx % L2), p = idx / L2;
                 if (l < valid) {
-                    const float2 v0 = buf[Lay::at(l, p)], v1 = buf[Lay::at(l + 1, p)];
+                    const float4 v = *reinterpret_cast<const float4*>(&buf[Lay::at(l, p)]);
                     float sc = a.scale;
                     if constexpr (MODE == 1) {
                         if (a.cen_io && ((p + N / 2) & 1)) sc = -sc;
                     }
                     *reinterpret_cast<float4*>(a.k + base + (long long)p * a.inner + l) =
-                        make_float4(v0.x * sc, v0.y * sc, v1.x * sc, v1.y * sc);
+                        make_float4(v.x * sc, v.y * sc, v.z * sc, v.w * sc);
                 }
             }
         }
@@ -506,8 +543,8 @@ static hipError_t launch_rows(bool reduce, int N, const RowsArgs& a, hipStream_t
 #define X(NN)                                                                                          \
     case NN: {                                                                                         \
         constexpr int L_ = rows_lines<NN>(), LR_ = reduce_lines<NN>();                                 \
-        const int cg = a.C < LR_ ? (int)a.C : LR_;                                                     \
-        const long long per = reduce ? LR_ / cg : L_;                                                  \
+        const long long per = reduce ? reduce_rows_per_tile(LR_, reduce_rows_max<NN>(), a.C)           \
+                                     : reduce_rows_per_tile(L_, L_, a.C);                              \
         const long long tiles = (a.n_rows + per - 1) / per;                                            \
         if (reduce) hipLaunchKernelGGL(rows_reduce_kernel<NN>, dim3(grid_for(tiles)), dim3(reduce_threads<NN>()), 0, st, a); \
         else hipLaunchKernelGGL(rows_expand_kernel<NN>, dim3(grid_for(tiles)), dim3(rows_threads<NN>()), 0, st, a);   \
@@ -525,8 +562,7 @@ static hipError_t launch_rows_fused(int N, const RowsArgs& a, const float2* y, c
 #define X(NN)                                                                                          \
     case NN: {                                                                                         \
         constexpr int LR_ = reduce_lines<NN>();                                                        \
-        const int cg = a.C < LR_ ? (int)a.C : LR_;                                                     \
-        const long long per = LR_ / cg;                                                                \
+        const long long per = reduce_rows_per_tile(LR_, reduce_rows_max<NN>(), a.C);                   \
         const long long tiles = (a.n_rows + per - 1) / per;                                            \
         hipLaunchKernelGGL(rows_fused_kernel<NN>, dim3(grid_for(tiles)), dim3(reduce_threads<NN>()), 0, st, a, y, M); \
         break;                                                                                         \
@@ -546,7 +582,8 @@ static hipError_t launch_cols(int mode, int N, const ColsArgs& a, hipStream_t st
         const dim3 g(grid_for(tiles)), b(cols_threads<NN>());                                                         \
         if (mode == 0) hipLaunchKernelGGL((cols_kernel<NN, 0>), g, b, 0, st, a);                       \
         else if (mode == 1) hipLaunchKernelGGL((cols_kernel<NN, 1>), g, b, 0, st, a);                  \
-        else hipLaunchKernelGGL((cols_kernel<NN, 2>), g, b, 0, st, a);                                 \
+        else if (a.y == nullptr) hipLaunchKernelGGL((cols_kernel<NN, 2>), g, b, 0, st, a);             \
+        else hipLaunchKernelGGL((cols_kernel<NN, 3>), g, b, 0, st, a);                                 \
         break;                                                                                         \
     }
         GLEAM_FFT_SIZES(X)
@@ -569,7 +606,7 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
         long long half = g.W / 2 + (g.ndim_fft >= 2 ? g.H / 2 : 0) + (g.ndim_fft >= 3 ? g.D / 2 : 0);
         ra.ysign_bit = (int)(half & 1);
     }
-    ra.n_rows = g.B * g.C * g.T * DH;
+    ra.n_rows = g.B * g.T * DH;   // image rows: both row sweeps tile over (image row, coil)
     const double E8 = 8.0 * (double)(g.B * g.C * g.T * g.D * g.H * g.W);   // bytes of one k-space sweep
     const double P8 = 8.0 * (double)(g.B * g.T * g.D * g.H * g.W);          // bytes of one image
     const double S8 = E8 / (double)g.T, M1 = P8 / 8.0;
