@@ -323,16 +323,26 @@ static void launch_conv_bf16_k(const ConvBf16Args& a, hipStream_t st) {
 // Forward / data gradient of 3x3 layers in the plane with cin a multiple of 32 and cout a multiple of 64.  The
 // flattened-pixel kernel above re-reads the weights for every 128 pixels and every row tap's slab separately,
 // and stores 8-byte pieces 256 bytes apart; it spends more time waiting for staged data and on its stores than
-// on the MFMAs.  Here a workgroup of 4 waves owns 8 x 32 output pixels x 64 output channels: per 16-channel
-// chunk the raw 10 x 34 pixel region (zero outside the image, so no tap masks) and all nine taps' weights are
-// staged by direct loads (two buffers); a wave owns two image rows, reads the 4 x 3 pixel operands its nine
-// taps need once and feeds 36 MFMAs per chunk; the output goes through LDS so that the fused epilogue reads and
-// writes 64 contiguous bytes per pixel.  LDS layouts put the 16 lanes a 128-bit access serves together on 16
-// neighbouring 16-byte slots.  Two workgroups per CU.
-constexpr int kB2RegQuads = 704;      // 10 rows x 2 channel quads x 34 columns = 680, rounded up to whole wave loads
+// on the MFMAs.  Here a workgroup of 4 waves owns (4 * kB2Rows) x 32 output pixels x 64 output channels: per
+// 16-channel chunk the raw pixel region with its one-pixel halo and all nine taps' weights are staged by direct
+// loads into one of two buffers; a wave owns kB2Rows image rows, reads the (kB2Rows + 2) x 3 pixel operands and the
+// 18 weight operands of its nine taps and feeds 18 * kB2Rows MFMAs per chunk from them.  Out-of-image quads of the
+// region are zeros written once per block (no tap masks, no loads for them).  The output goes through wave-private
+// LDS rows so that the fused epilogue reads and writes 64 contiguous bytes per pixel; one barrier per block for it.
+// LDS layouts put the 16 lanes a 128-bit access serves together on 16 neighbouring 16-byte slots.  Two workgroups
+// per CU.  Measured on the brain workload (128 -> 128, 819 200 pixels, 241.6 GFLOP per launch): 345 us with two
+// rows per wave, 350 us with four (half the operand reads and weight traffic per MFMA, but 7 rounds of blocks for
+// 6.25 and spilled registers); taking parts out: matrix instructions alone (operands in registers) 134 us, with the
+// operand reads 178 us, with the staging loads but no epilogue 257 us, staging loads alone 154 us.
+constexpr int kB2Rows = 2;            // image rows per wave
+constexpr int kB2TileRows = 4 * kB2Rows;
+constexpr int kB2RegUsed = (kB2TileRows + 2) * 2 * 34;          // quads of the region: rows x 2 channel quads x 34 columns
+constexpr int kB2RegQuads = (kB2RegUsed + 63) / 64 * 64;       // rounded up to whole wave loads
 constexpr int kB2WQuads = 9 * 2 * 64; // nine taps x 2 channel quads x 64 output channels
 constexpr int kB2BufQuads = kB2RegQuads + kB2WQuads;
 constexpr int kB2StageStride = 34;    // floats per staged output pixel: 32 channels + 2 (bank spread)
+constexpr int kB2RegLoads = (kB2RegQuads + 255) / 256;   // direct-load slots per lane: region
+constexpr int kB2WLoads = (kB2WQuads + 255) / 256;       // and weights
 
 // weights as LDS images: wt[((((ny*n_kc + kc)*9 + tap)*2 + hq)*64 + nn)*8 + kk], k = 16*kc + 8*hq + kk, n = 64*ny + nn;
 // one zero quad follows.  Source (n, tap, k) at w[n*sn + tapidx*st + k*sk], taps mirrored for the data gradient.
@@ -354,7 +364,12 @@ __global__ __launch_bounds__(256) void weights_image_bf16_2d_kernel(const float*
 
 template <bool RELU>
 __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, int bx_n, int by_n, long long n_blocks) {
-    __shared__ uint4 bufs[2 * kB2BufQuads];
+    // Two chunk buffers as two arrays, and the chunk loop written out for both: the compiler orders a direct load's
+    // LDS write against LDS reads by what it can prove about the addresses, and waits for every pending direct load
+    // before any read of the same array (with one array and a computed offset the next chunk's loads were complete
+    // before the first operand read of the current chunk, i.e. staging and matrix work ran one after the other).
+    __shared__ uint4 bufA[kB2BufQuads];
+    __shared__ uint4 bufB[kB2BufQuads];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 31, h = lane >> 5;
@@ -362,24 +377,22 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
     const XcdRange xr = xcd_range(n_blocks);
     if (xr.first >= xr.end) return;   // uniform for the workgroup
     const int ny = blockIdx.y, n0 = 64 * ny, n_kc = a.K / 16;
-    const unsigned short* zero = a.wt + 9LL * a.K * a.Nn;
 
-    // direct-load slots of this lane: three quads of the region (slot = (row*2 + channel quad)*34 + column), five of
-    // the weights; the position of a quad inside the region does not depend on the block
-    int s_row[3], s_col[3], s_hq[3];
+    // direct-load slots of this lane: quads of the region (slot = (row*2 + channel quad)*34 + column), packed as
+    // row << 8 | column << 1 | channel quad; the position of a quad inside the region does not depend on the block.
+    // Addresses are formed when a load is issued (a few integer operations per chunk) rather than kept per block:
+    // the pointers of two blocks cost more registers than the kernel has, and a spilled pointer is reloaded through
+    // the same counter the direct loads use, which serialises them.
+    int slot[kB2RegLoads];
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
+    for (int i = 0; i < kB2RegLoads; ++i) {
         const int s = tid + 256 * i;
         const int rq = s / 34;
-        s_col[i] = s - rq * 34;
-        s_row[i] = s < 680 ? (rq >> 1) : -100000;   // slots past the region always read the zero quad
-        s_hq[i] = rq & 1;
+        slot[i] = s < kB2RegUsed ? ((rq >> 1) << 8) | ((s - rq * 34) << 1) | (rq & 1) : -1;   // slots past the region read the zero quad
     }
-    struct Block {
+    struct Block {   // uniform over the workgroup
         int x0, y0;
         long long img;
-        const unsigned short* gp[3];
-        int gstep[3];
     };
     auto setup = [&](long long item) {
         Block b;
@@ -388,44 +401,64 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
         const int by = (int)(rest % by_n);
         b.img = rest / by_n;
         b.x0 = bx * 32;
-        b.y0 = by * 8;
-#pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const int yy = b.y0 - 1 + s_row[i], xx = b.x0 - 1 + s_col[i];
-            const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
-            b.gp[i] = ok ? a.in + ((b.img * H + yy) * W + xx) * a.K + 8 * s_hq[i] : zero;
-            b.gstep[i] = ok ? 16 : 0;
-        }
+        b.y0 = by * kB2TileRows;
         return b;
     };
-    const unsigned short* wbase = a.wt + (size_t)ny * n_kc * (kB2WQuads * 8) + tid * 8;
+    // byte offset of region slot i of block b from a.in (32 bits: the launcher checks the tensor's size), or ~0u for a
+    // slot outside the image / past the region
+    auto slot_off = [&](const Block& b, int i) -> unsigned {
+        const int yy = b.y0 - 1 + (slot[i] >> 8), xx = b.x0 - 1 + ((slot[i] >> 1) & 127);
+        const bool ok = slot[i] >= 0 && yy >= 0 && yy < H && xx >= 0 && xx < W;
+        return ok ? (unsigned)((((unsigned)(b.img * H + yy) * (unsigned)W + (unsigned)xx) * (unsigned)a.K + 8u * (slot[i] & 1)) * 2u) : ~0u;
+    };
+    const char* in_bytes = reinterpret_cast<const char*>(a.in);
+    const char* w_bytes = reinterpret_cast<const char*>(a.wt) + ((size_t)ny * n_kc * (kB2WQuads * 8) + tid * 8) * 2;
+    // Slots outside the image are not loaded; they hold zeros, written by zero_halo when a block touches the border.
     auto issue = [&](const Block& b, int kc, uint4* dst) {
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
+        for (int i = 0; i < kB2RegLoads; ++i) {
             const int o = wave + 4 * i;
-            if (o < kB2RegQuads / 64)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b.gp[i] + kc * b.gstep[i]),
-                                                 (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
+            if (o < kB2RegQuads / 64) {
+                unsigned off = slot_off(b, i);
+                if (off != ~0u) {
+                    off += kc * 32;
+                    asm volatile("" : "+v"(off));   // keeps the 64-bit address out of registers across chunks
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(in_bytes + off),
+                                                     (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
+                }
+            }
         }
 #pragma unroll
-        for (int i = 0; i < 5; ++i) {
+        for (int i = 0; i < kB2WLoads; ++i) {
             const int o = wave + 4 * i;
-            if (o < kB2WQuads / 64)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wbase + (size_t)kc * (kB2WQuads * 8) + i * 2048),
+            if (o < kB2WQuads / 64) {
+                unsigned off = (unsigned)kc * (kB2WQuads * 16) + i * 4096;
+                asm volatile("" : "+v"(off));
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(w_bytes + off),
                                                  (__attribute__((address_space(3))) void*)(dst + kB2RegQuads + o * 64), 16, 0, 0);
+            }
+        }
+    };
+    auto touches_border = [&](const Block& b) { return b.x0 == 0 || b.y0 == 0 || b.x0 + 32 >= W || b.y0 + kB2TileRows >= H; };
+    auto zero_halo = [&](const Block& b, uint4* dst) {
+#pragma unroll
+        for (int i = 0; i < kB2RegLoads; ++i) {
+            const int o = wave + 4 * i;
+            if (o < kB2RegQuads / 64 && slot_off(b, i) == ~0u) dst[o * 64 + lane] = make_uint4(0u, 0u, 0u, 0u);
         }
     };
 
-    // this lane's operands: pixel (region row 2*wave + r, column m + dx), channel quad h; weights (tap, quad h, cout m + 32 j)
-    const int pb0 = ((2 * wave) * 2 + h) * 34 + m;
+    // this lane's operands: pixel (region row 4*wave + r, column m + dx), channel quad h; weights (tap, quad h, cout m + 32 j)
+    const int pb0 = ((kB2Rows * wave) * 2 + h) * 34 + m;
     const int wa0 = kB2RegQuads + h * 64 + m;
 
-    floatx16 acc[2][2];   // [image row of the wave][cout block]
-    auto compute = [&](int boff) {
-        const uint4* buf = bufs + boff;
-        bf16x8 pv[4][3];
+    floatx16 acc[kB2Rows][2];   // [image row of the wave][cout block]
+    auto compute = [&](const uint4* buf) {
+        // the pixel operands of all taps first, then per tap its two weight operands and the matrix instructions that
+        // use them (fetching every weight operand up front as well measured the same)
+        bf16x8 pv[kB2Rows + 2][3];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < kB2Rows + 2; ++r)
 #pragma unroll
             for (int dx = 0; dx < 3; ++dx) {
                 uint4 pb = buf[pb0 + r * 68 + dx];
@@ -440,62 +473,78 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
             for (int dx = 0; dx < 3; ++dx) {
                 const bf16x8 w0 = __builtin_bit_cast(bf16x8, buf[wa0 + (dy * 3 + dx) * 128]);
                 const bf16x8 w1 = __builtin_bit_cast(bf16x8, buf[wa0 + (dy * 3 + dx) * 128 + 32]);
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, pv[dy][dx], acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, pv[dy][dx], acc[0][1], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, pv[dy + 1][dx], acc[1][0], 0, 0, 0);
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, pv[dy + 1][dx], acc[1][1], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < kB2Rows; ++r) {
+                    acc[r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, pv[dy + r][dx], acc[r][0], 0, 0, 0);
+                    acc[r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, pv[dy + r][dx], acc[r][1], 0, 0, 0);
+                }
             }
     };
 
-    // epilogue constants: a thread finishes 4 output channels (one 8-byte bf16 piece) of 4 pixels per pass
-    const int e_piece = tid & 7;
+    // epilogue constants: a lane finishes 4 output channels (one 8-byte bf16 piece) of 4 pixels per pass
+    const int e_piece = lane & 7, e_px = lane >> 3;
     Block cur = setup(xr.first);
-    issue(cur, 0, bufs);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    issue(cur, 0, bufA);
     for (long long item = xr.first; item < xr.end; item += xr.stride) {
         const bool has_next = item + xr.stride < xr.end;
         const Block nxt = setup(has_next ? item + xr.stride : item);
+        // Out-of-image slots of both buffers: zeros, valid for every chunk of this block (the direct loads skip them).
+        // The first buffer already holds (or is receiving) this block's first chunk in its other slots; the second
+        // was the previous block's staging area.
+        if (touches_border(cur)) {
+            zero_halo(cur, bufA);
+            zero_halo(cur, bufB);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
 #pragma unroll
-        for (int pj = 0; pj < 2; ++pj)
+        for (int pj = 0; pj < kB2Rows; ++pj)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[pj][j][r] = 0.f;
-        for (int kc = 0; kc < n_kc; ++kc) {
-            // the first chunk of the next block is fetched under the last MFMAs of this one
-            if (kc + 1 < n_kc) issue(cur, kc + 1, bufs + ((kc + 1) & 1) * kB2BufQuads);
-            else if (has_next) issue(nxt, 0, bufs + ((kc + 1) & 1) * kB2BufQuads);
+        for (int kc = 0; kc < n_kc; kc += 2) {   // n_kc is even
+            issue(cur, kc + 1, bufB);
             __builtin_amdgcn_sched_barrier(0);
-            compute((kc & 1) * kB2BufQuads);
+            compute(bufA);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            // the first chunk of the next block is fetched under the last MFMAs of this one
+            if (kc + 2 < n_kc) issue(cur, kc + 2, bufA);
+            else if (has_next) issue(nxt, 0, bufA);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(bufB);
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
         }
-        // Output through LDS, one pass per (image row of the wave, cout block): float32 [128 pixels][32 channels],
-        // then bias / ReLU / ReLU mask / add and 8-byte stores that are contiguous per pixel.  The staging area is
-        // the chunk buffer that the prefetch of the next block does not use.
-        float* stage = reinterpret_cast<float*>(bufs + kB2BufQuads);   // n_kc is even: the prefetch went into the first buffer
-        // ReLU mask as sign bits: bit 16*j + 4*it + e of this thread's word pj says whether the value of pass (pj, j),
-        // pixel `it`, channel e of its piece is positive.  The forward launch that produces an activation writes
-        // the words, the data-gradient launch into the same tensor (same geometry, so the same thread holds the
+        // Output through LDS, one pass per (image row of the wave, cout block): the wave turns its own float32
+        // [32 pixels][32 channels] block through its own staging rows (LDS operations of one wave execute in order,
+        // so no barrier separates the passes), then bias / ReLU / ReLU mask / add and 8-byte stores that are
+        // contiguous per pixel.  The staging area is the chunk buffer that the prefetch of the next block does not
+        // use; the next block's second chunk will be loaded into it, hence the one barrier after the last pass.
+        float* stage = reinterpret_cast<float*>(bufB) + wave * 32 * kB2StageStride;   // the prefetch of the next block went into bufA
+        // ReLU mask as sign bits: bit 16*j + 4*it + e of this lane's word pj says whether the value of pass (pj, j),
+        // pixel e_px + 8*it, channel e of its piece is positive.  The forward launch that produces an activation writes
+        // the words, the data-gradient launch into the same tensor (same geometry, so the same lane holds the
         // same values) reads them instead of the activation.
-        const long long word_idx = (((long long)ny * n_blocks + item) * 256 + tid) * 2;
-        uint2 sign_in = make_uint2(0u, 0u);
-        unsigned sign_out[2] = {0u, 0u};
-        if (a.bits_in) sign_in = *reinterpret_cast<const uint2*>(a.bits_in + word_idx);
+        const long long word_idx = (((long long)ny * n_blocks + item) * 256 + tid) * 4;
+        uint4 sign_in4 = make_uint4(0u, 0u, 0u, 0u);
+        if (a.bits_in) sign_in4 = *reinterpret_cast<const uint4*>(a.bits_in + word_idx);
+        const unsigned sign_in[4] = {sign_in4.x, sign_in4.y, sign_in4.z, sign_in4.w};
+        unsigned sign_out[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int pj = 0; pj < 2; ++pj)
+        for (int pj = 0; pj < kB2Rows; ++pj)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg)
-                    *reinterpret_cast<float4*>(stage + (wave * 32 + m) * kB2StageStride + 8 * rg + 4 * h) =
+                    *reinterpret_cast<float4*>(stage + m * kB2StageStride + 8 * rg + 4 * h) =
                         make_float4(acc[pj][j][4 * rg], acc[pj][j][4 * rg + 1], acc[pj][j][4 * rg + 2], acc[pj][j][4 * rg + 3]);
-                __syncthreads();
+                const int y = cur.y0 + kB2Rows * wave + pj;
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
-                    const int px = (tid >> 3) + 32 * it;          // 0..127: wave row px>>5, column px&31
-                    const int y = cur.y0 + 2 * (px >> 5) + pj, x = cur.x0 + (px & 31);
+                    const int px = e_px + 8 * it;                  // column of the tile
+                    const int x = cur.x0 + px;
                     const float4 v4 = *reinterpret_cast<const float4*>(stage + px * kB2StageStride + 4 * e_piece);
                     if (y < H && x < W) {
                         const int co = n0 + 32 * j + 4 * e_piece;
@@ -514,7 +563,7 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
                         const float ref[4] = {bf16_to_f32((unsigned short)rf.x), bf16_to_f32((unsigned short)(rf.x >> 16)),
                                               bf16_to_f32((unsigned short)rf.y), bf16_to_f32((unsigned short)(rf.y >> 16))};
                         const int bit0 = 16 * j + 4 * it;
-                        const unsigned sw = pj ? sign_in.y : sign_in.x;
+                        const unsigned sw = sign_in[pj];
                         bool pos[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) pos[e] = a.bits_in ? ((sw >> (bit0 + e)) & 1u) != 0u : ref[e] > 0.f;
@@ -538,15 +587,17 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
                         }
                     }
                 }
-                __syncthreads();
             }
-        if (a.bits_out) *reinterpret_cast<uint2*>(a.bits_out + word_idx) = make_uint2(sign_out[0], sign_out[1]);
+        if (a.bits_out) *reinterpret_cast<uint4*>(a.bits_out + word_idx) = make_uint4(sign_out[0], sign_out[1], sign_out[2], sign_out[3]);
+        __syncthreads();   // every wave is done with its staging rows: the next block's second chunk lands there
         cur = nxt;
     }
 }
 
 static bool conv_bf16_2d_applies(const ConvBf16Args& a) {
-    return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && a.K % 32 == 0 && a.Nn % 64 == 0 && !a.out_f32;   // an even number of 16-channel chunks
+    // an even number of 16-channel chunks; byte offsets into the input tensor are 32 bits in the kernel
+    return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && a.K % 32 == 0 && a.Nn % 64 == 0 && !a.out_f32 &&
+           2.0 * (double)a.d.Q * a.K < 4.0e9;
 }
 
 // GLEAM_POLICY_NO_BF16_2D keeps the flattened-pixel kernel
@@ -558,9 +609,9 @@ bool conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn) {
     return bf16_2d_enabled() && conv_bf16_2d_applies(a);
 }
 
-size_t conv_bf16_sign_words(const PixDims& d, int Nn) {   // two words per thread, block and group of 64 channels
+size_t conv_bf16_sign_words(const PixDims& d, int Nn) {   // four words per thread, block and group of 64 channels
     const size_t n_img = (size_t)d.Q / ((size_t)d.H * d.W);
-    return n_img * ((d.W + 31) / 32) * ((d.H + 7) / 8) * 256 * 2 * (size_t)(Nn / 64);
+    return n_img * ((d.W + 31) / 32) * ((d.H + kB2TileRows - 1) / kB2TileRows) * 256 * 4 * (size_t)(Nn / 64);
 }
 
 static hipError_t launch_conv_bf16_2d(ConvBf16Args a, const float* w, long long sn, long long st_, long long sk, int flip,
@@ -572,7 +623,7 @@ static hipError_t launch_conv_bf16_2d(ConvBf16Args a, const float* w, long long 
                            a.K, a.Nn, wt_scratch);
     }
     a.wt = wt_scratch;
-    const int bx_n = (a.d.W + 31) / 32, by_n = (a.d.H + 7) / 8;
+    const int bx_n = (a.d.W + 31) / 32, by_n = (a.d.H + kB2TileRows - 1) / kB2TileRows;
     const long long n_img = a.d.Q / ((long long)a.d.H * a.d.W);
     const long long n_blocks = n_img * bx_n * by_n;
     const long long cap = 512 / (a.Nn / 64) > 8 ? 512 / (a.Nn / 64) : 8;   // two workgroups per CU in total

@@ -380,6 +380,10 @@ struct ColsArgs {
     // of this axis, (-1)^(N/2) D F^H D: input and output signs by the parity of p.
     int cen_y, ysign_bit, cen_io;
     long long Wrow;
+    // Walk the tiles from the last to the first.  The k-space buffer of the 3D workload (419 MB) is larger than the
+    // Infinity Cache (256 MB), which holds what the previous sweep wrote last: a sweep that starts where the previous
+    // one ended finds that part there.
+    int rev;
 };
 
 // Mask bytes of a column tile ([N rows][L columns], row p at mb + p*L) into LDS.  One thread fetches a whole row
@@ -428,7 +432,8 @@ __global__ __launch_bounds__(cols_threads<N>(), (cols_min_waves<N, MODE>())) voi
     const long long n_tiles = a.outer * tiles_per;
     // neighbouring column tiles share 128-byte lines: keep them on one XCD (one L2)
     const XcdRange xr = xcd_range(n_tiles);
-    for (long long tile = xr.first; tile < xr.end; tile += xr.stride) {
+    for (long long it = xr.first; it < xr.end; it += xr.stride) {
+        const long long tile = a.rev ? n_tiles - 1 - it : it;
         const long long o = tile / tiles_per;
         const long long i0 = (tile % tiles_per) * L;
         const long long base = o * N * a.inner + i0;
@@ -636,6 +641,7 @@ hipError_t sense_dc(const gleam_geom& g, const float2* x, const float2* S, const
     } else {
         ColsArgs ha = ca;  // H axis: [B*C*T*D][H][W]
         ha.cen_y = 0;
+        ha.rev = 1;
         ha.outer = g.B * g.C * g.T * g.D; ha.inner = g.W; ha.Dq = g.D;
         ha.scale = 1.0f / sqrtf((float)g.H);
         {
