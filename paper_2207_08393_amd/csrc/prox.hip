@@ -1114,6 +1114,15 @@ static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scrat
         snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
         return launch_conv_wino(wa, cw.w, cw.sn, cw.st, cw.sk, a.flip, a.relu_in, wt_scratch, wino_u, name, st);
     }
+    if (wino_enabled() && conv_wino3_applies(a.d, a.K, a.Nn)) {   // 3x3x3: Winograd in the slice, depth taps summed
+        WinoArgs wa{};
+        wa.in = a.in; wa.out = a.out; wa.bias = a.bias; wa.mask_ref = a.mask_ref; wa.add = a.add;
+        wa.K = a.K; wa.Nn = a.Nn; wa.relu_out = a.relu_out; wa.mask_acc = a.mask_acc; wa.mask_add = a.mask_add;
+        wa.H = a.d.H; wa.W = a.d.W; wa.D = a.d.D; wa.NI = a.d.Q / ((long long)a.d.H * a.d.W);
+        char name[56];
+        snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
+        return launch_conv_wino3(wa, cw.w, cw.sn, cw.st, cw.sk, a.flip, a.relu_in, wt_scratch, name, st);
+    }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
     {
         WimgArgs t{};
@@ -1910,6 +1919,10 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
         max_img = b > max_img ? b : max_img;
         if (taps == 9) {      // transformed weights of the Winograd path (16 values per channel pair)
             const size_t wn = conv_wino_weight_floats(c.cin, c.cout);
+            max_img = wn > max_img ? wn : max_img;
+        }
+        if (taps == 27) {     // ... and of its 3x3x3 form (16 values per depth tap)
+            const size_t wn = conv_wino3_weight_floats(c.cin, c.cout);
             max_img = wn > max_img ? wn : max_img;
         }
         if (p.dtype == 1) {   // bf16 images are half the bytes per element, but chunked by 32 channels

@@ -164,6 +164,7 @@ struct WinoArgs {
     long long NI;           // images (B*T*D)
     int H, W, bx_n, by_n;
     long long n_blocks;
+    int D;                  // slices per volume (3x3x3 kernel only)
 };
 bool conv_wino_applies(const PixDims& d, int K, int Nn);
 size_t conv_wino_weight_floats(int K, int Nn);
@@ -173,6 +174,12 @@ size_t conv_wino_sign_words(const PixDims& d, int Nn);
 // otherwise they are made now, into u_scratch.
 hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long st, long long sk, int flip, int relu_in,
                             float* u_scratch, const float* u_ready, const char* name, hipStream_t stream);
+// 3x3x3 layers: Winograd inside every slice, plain sum over the three depth taps (prox_wino3.hip).  The transformed
+// weights (conv_wino3_weight_floats(K, Nn) floats) are made at launch into u_scratch.
+bool conv_wino3_applies(const PixDims& d, int K, int Nn);
+size_t conv_wino3_weight_floats(int K, int Nn);
+hipError_t launch_conv_wino3(WinoArgs a, const float* w, long long sn, long long st, long long sk, int flip, int relu_in,
+                             float* u_scratch, const char* name, hipStream_t stream);
 // Transformed weights of several layers in one launch (a launch costs more than the transform of one layer).
 struct WinoWeightJob {
     const float* w;
