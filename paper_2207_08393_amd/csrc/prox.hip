@@ -1906,6 +1906,11 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
             const size_t need = align256(wgrad_wino_partial_floats(c.cin, c.cout, plan.n_split) * sizeof(float));
             if (need > plan.partial_bytes) plan.partial_bytes = need;
         }
+        if (p.dtype == 0 && wgrad_wino3_applies(dd, c.cin, c.cout)) {
+            dd.Q = plan.Q;
+            const size_t need = align256(wgrad_wino3_partial_floats(dd, c.cin, c.cout) * sizeof(float));
+            if (need > plan.partial_bytes) plan.partial_bytes = need;
+        }
     }
     w += plan.partial_bytes;
     plan.bias_partial_off = w;
@@ -2279,6 +2284,32 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                                    plan.n_split, np, psum, 1, nbw, (const float*)bpart, nb,
                                    c.has_bias ? grad_theta + plan.b_off[l - 1] : nullptr);
                 e = wgrad_wino_finish(psum, c.cout, c.cin, grad_theta + plan.w_off[l - 1], st);
+                if (e != hipSuccess) return e;
+            }
+            wino_wgrad_done = true;
+        } else if (wino_enabled() && wgrad_wino3_applies(d, c.cin, c.cout)) {
+            // 3x3x3: the same scheme inside every slice, one set of 16 products per depth tap
+            Wino3WgradArgs ww{};
+            ww.g = wa.g; ww.a = wa.a; ww.partial = partial; ww.bias_partial = c.has_bias ? bpart : nullptr;
+            ww.Co = c.cout; ww.Ci = c.cin;
+            const int n3 = wgrad_wino3_splits(d);
+            const long long np = 48LL * c.cout * c.cin, nb = c.has_bias ? c.cout : 0;
+            {
+                char name[56];
+                snprintf(name, sizeof(name), "conv_wgrad_%dto%d_t%d", c.cin, c.cout, taps);
+                KernelScope ks(name, 2.0 * (double)d.Q * c.cin * c.cout * taps, 4.0 * (double)d.Q * (c.cin + c.cout), st,
+                               2.0 * (double)d.Q * c.cin * c.cout * 12);
+                e = launch_wgrad_wino3(ww, d, wa.relu_in, st);
+                if (e != hipSuccess) return e;
+            }
+            float* psum = partial + (size_t)n3 * np;
+            {
+                KernelScope ks("wgrad_reduce", 0.0, 4.0 * (double)(np + nb) * (n3 + 1), st);
+                const int nbw = (int)((np + 63) / 64), nbb = (int)((nb + 15) / 16);
+                hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)(nbw + nbb)), dim3(256), 0, st, (const float*)partial,
+                                   n3, np, psum, 1, nbw, (const float*)bpart, nb,
+                                   c.has_bias ? grad_theta + plan.b_off[l - 1] : nullptr);
+                e = wgrad_wino3_finish(psum, c.cout, c.cin, grad_theta + plan.w_off[l - 1], st);
                 if (e != hipSuccess) return e;
             }
             wino_wgrad_done = true;

@@ -180,6 +180,23 @@ bool conv_wino3_applies(const PixDims& d, int K, int Nn);
 size_t conv_wino3_weight_floats(int K, int Nn);
 hipError_t launch_conv_wino3(WinoArgs a, const float* w, long long sn, long long st, long long sk, int flip, int relu_in,
                              float* u_scratch, const char* name, hipStream_t stream);
+// Weight gradient of a 3x3x3 layer by the same scheme (prox_wino3.hip): partial sums of the 3 x 16 transformed products
+// per workgroup, then reduce_partials_kernel and wgrad_wino3_finish.
+struct Wino3WgradArgs {
+    const float* g;         // [volumes][D][H][W][Co]  gradient at the conv output (already ReLU-masked)
+    const float* a;         // [volumes][D][H][W][Ci]  conv input before its optional ReLU
+    float* partial;         // [gridDim.x][3][16][Co][Ci], followed by [3][16][Co][Ci] for the reduced sums
+    float* bias_partial;    // [gridDim.x][Co] or null
+    int Co, Ci;
+    int D, H, W, bx_n, by_n;            // set by the launcher
+    int seg_len, segs_per_col;          // slices per run, runs per column
+    long long n_items;                  // runs in total
+};
+bool wgrad_wino3_applies(const PixDims& d, int Ci, int Co);
+int wgrad_wino3_splits(const PixDims& d);                                  // workgroups along x = partial sums written
+size_t wgrad_wino3_partial_floats(const PixDims& d, int Ci, int Co);      // partials and reduced sums
+hipError_t launch_wgrad_wino3(Wino3WgradArgs a, const PixDims& d, int relu_in, hipStream_t stream);
+hipError_t wgrad_wino3_finish(const float* psum, int Co, int Ci, float* grad_w, hipStream_t stream);
 // Transformed weights of several layers in one launch (a launch costs more than the transform of one layer).
 struct WinoWeightJob {
     const float* w;

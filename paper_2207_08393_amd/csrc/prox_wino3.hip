@@ -336,6 +336,309 @@ __global__ __launch_bounds__(256) void wino3_weights_kernel(const float* __restr
     }
 }
 
+// ------------------------------------------------------------------ weight gradient
+// dL/dg_kd = G^T [ sum over slices d and tiles of (A dY(d) A^T) .* (B^T x(d + kd - 1) B) ] G: per depth tap and position
+// of the 4x4 grid a [cout x tiles] . [tiles x cin] matrix product, 16 multiplications per tile, depth tap and channel
+// pair instead of 36.  A workgroup of 4 waves owns a 32 x 32 channel block; wave xi owns row xi of the grid for all
+// three depth taps: 3 x 4 accumulators of 32x32.  A chunk is 16 tiles (2 x 32 output pixels) of one column of the
+// volume at input slice tau: the transformed input operand is formed once and multiplied with the transformed
+// gradients of slices tau + 1, tau and tau - 1 (depth taps 0, 1, 2).  A workgroup walks a run of consecutive slices
+// of its column, so every chunk needs one new input region (4 x 34 pixels) and one new gradient region (2 x 32
+// pixels): the input regions alternate between two LDS buffers and the gradient regions rotate through four, all
+// filled by direct global -> LDS loads one chunk ahead.  The six buffers are separate LDS objects and the loop is
+// written out over the four rotations, so that the compiler knows which buffer every read touches and does not
+// make the reads wait for the loads in flight.  Both MFMA operands are formed on the fly as in the 2D kernel
+// (a lane holds one channel and one of the two tiles of a contraction step).  Every workgroup writes its partial
+// sums once; a fixed-order reduction and G^T . G follow.
+constexpr int k3XSlots = 4 * 34 * 8;   // input region: 4 rows x 34 columns x 8 channel quads
+constexpr int k3GSlots = 2 * 32 * 8;   // gradient region
+constexpr int k3XLoads = k3XSlots / 64, k3GLoads = k3GSlots / 64;
+static_assert(k3XSlots % 64 == 0 && k3GSlots % 64 == 0, "regions are whole wave loads");
+
+template <bool RELU>
+__global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
+    // element (pixel, channel) of a region sits at (pixel >> 1)*64 + (((pixel & 1) ^ ((pixel >> 1) & 1))*32 + channel:
+    // the two lane halves of a 4-byte operand read (pixels two apart) then use different banks
+    __shared__ __attribute__((aligned(16))) float X0[k3XSlots * 4];
+    __shared__ __attribute__((aligned(16))) float X1[k3XSlots * 4];
+    __shared__ __attribute__((aligned(16))) float G0[k3GSlots * 4];
+    __shared__ __attribute__((aligned(16))) float G1[k3GSlots * 4];
+    __shared__ __attribute__((aligned(16))) float G2[k3GSlots * 4];
+    __shared__ __attribute__((aligned(16))) float G3[k3GSlots * 4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int xi = wave;
+    const int m = lane & 31, h = lane >> 5;
+    const int nci = a.Ci / 32;
+    const int co0 = 32 * ((int)blockIdx.y / nci), ci0 = 32 * ((int)blockIdx.y % nci);
+    const size_t pblock = (size_t)a.Co * a.Ci;
+    float* const pout = a.partial + (size_t)blockIdx.x * 48 * pblock;
+    const XcdRange xr = xcd_range(a.n_items);
+    if (xr.first >= xr.end) {   // nothing to do: the partial of this workgroup is zero
+        for (int i = tid; i < 48 * 32 * 32; i += 256) {
+            const int pos = i >> 10, co = (i >> 5) & 31, ci = i & 31;
+            pout[((size_t)pos * a.Co + co0 + co) * a.Ci + ci0 + ci] = 0.f;
+        }
+        if (a.bias_partial && ci0 == 0 && tid < 32) a.bias_partial[(size_t)blockIdx.x * a.Co + co0 + tid] = 0.f;
+        return;
+    }
+
+    // Direct loads.  Slot s of a region (16 bytes at float offset 4*s) holds channel quad s & 7 of pixel
+    // 2*(s >> 4) + (((s >> 3) ^ (s >> 4)) & 1).  The slot tables are recomputed per chunk (a few dozen vector
+    // instructions against ~100 MFMAs): registers are what this kernel is short of.
+    auto fill = [&](const float* origin, bool plane_ok, bool interior, int y_first, int x_first, int cols, int loads, int C,
+                    float* dst) {
+        int t = tid;
+        asm volatile("" : "+v"(t));   // keeps the tables from being hoisted out of the chunk loop into registers
+        // Lanes whose pixel lies outside the volume store zeros themselves (a direct load writes lane l's 16 bytes at
+        // the wave's base + 16*l, masked-off lanes write nothing).  All zero stores of a region come before its
+        // direct loads: a store into a buffer waits for the loads already in flight into it.
+        unsigned valid = 0u;
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            const int o = wave + 4 * i;
+            if (o < loads) {
+                bool ok = plane_ok;
+                if (!interior) {
+                    const int s = t + 256 * i;
+                    const int pp = s >> 4;
+                    const int px = 2 * pp + (((s >> 3) ^ pp) & 1);
+                    const int row = px / cols, col = px - row * cols;
+                    const int yy = y_first + row, xx = x_first + col;
+                    ok = ok && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
+                }
+                if (ok) valid |= 1u << i;
+                else *reinterpret_cast<float4*>(dst + o * 256 + lane * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            const int o = wave + 4 * i;
+            if (o < loads && ((valid >> i) & 1u)) {
+                const int s = t + 256 * i;
+                const int pp = s >> 4, qd = s & 7;
+                const int px = 2 * pp + (((s >> 3) ^ pp) & 1);
+                const int row = px / cols, col = px - row * cols;
+                dma16_off(origin, 4u * (unsigned)((row * a.W + col) * C + 4 * qd), dst + o * 256);
+            }
+        }
+    };
+
+    // row xi of A dY (coefficients of the two gradient rows) and of B^T d (two of the four input rows)
+    const float ca = xi == 3 ? 0.f : 1.f, cb = xi == 0 ? 0.f : (xi == 1 ? 1.f : -1.f);
+    const int ra = xi == 0 ? 0 : (xi == 2 ? 2 : 1), rb = xi == 3 ? 3 : (xi == 2 ? 1 : 2);
+    const float sg = xi == 1 ? 1.f : -1.f;
+    // LDS float offsets of this lane: input pixel (row r, column 4q + 2h + 2cp + e) sits at xo[rs][cp] ^ (32*e), + 128*q;
+    // gradient pixel (row, column 4q + 2h + e) at go[e] + 1024*row + 128*q
+    int xo[2][2], go[2];
+#pragma unroll
+    for (int rs = 0; rs < 2; ++rs)
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp) {
+            const int r = rs ? rb : ra;
+            xo[rs][cp] = (17 * r + h + cp) * 64 + ((r + h + cp) & 1) * 32 + m;
+        }
+#pragma unroll
+    for (int e = 0; e < 2; ++e) go[e] = h * 64 + (e ^ h) * 32 + m;
+
+    floatx16 acc[3][4];   // [depth tap][column nu of the product grid]
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+        for (int nu = 0; nu < 4; ++nu)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[kd][nu][r] = 0.f;
+    float bsum = 0.f;
+
+    // One chunk: 8 contraction steps (tiles 2q and 2q+1 on the two lane halves), 12 MFMAs each.
+    // gp / gz / gm: gradient regions of slices tau + 1, tau, tau - 1 (depth taps 0, 1, 2).
+    auto run = [&](const float* x, const float* gp, const float* gz, const float* gm) __attribute__((always_inline)) {
+#pragma unroll 1
+        for (int q = 0; q < 8; ++q) {
+            float v[4];
+            {
+                float t[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float da = x[(xo[0][c >> 1] ^ (32 * (c & 1))) + 128 * q];
+                    float dbv = x[(xo[1][c >> 1] ^ (32 * (c & 1))) + 128 * q];
+                    if (RELU) {
+                        da = __int_as_float(__float_as_int(da) > 0 ? __float_as_int(da) : 0);
+                        dbv = __int_as_float(__float_as_int(dbv) > 0 ? __float_as_int(dbv) : 0);
+                    }
+                    t[c] = fmaf(sg, dbv, da);   // row xi of B^T d
+                }
+                v[0] = t[0] - t[2];
+                v[1] = t[1] + t[2];
+                v[2] = t[2] - t[1];
+                v[3] = t[1] - t[3];
+            }
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd) {
+                const float* g = kd == 0 ? gp : (kd == 1 ? gz : gm);
+                const float g00 = g[go[0] + 128 * q], g01 = g[go[1] + 128 * q];
+                const float g10 = g[go[0] + 1024 + 128 * q], g11 = g[go[1] + 1024 + 128 * q];
+                const float r0 = fmaf(cb, g10, ca * g00), r1 = fmaf(cb, g11, ca * g01);   // row xi of A dY
+                // (A dY A^T)[xi][nu]: r0, r0 + r1, r0 - r1, -r1
+                const float z1 = r0 + r1;
+                if (kd == 1 && xi == 1) bsum += z1;   // position (1,1) of A dY A^T = sum of the 2x2 block
+                acc[kd][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(r0, v[0], acc[kd][0], 0, 0, 0);
+                acc[kd][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(z1, v[1], acc[kd][1], 0, 0, 0);
+                acc[kd][2] = __builtin_amdgcn_mfma_f32_32x32x2f32(r0 - r1, v[2], acc[kd][2], 0, 0, 0);
+                acc[kd][3] = __builtin_amdgcn_mfma_f32_32x32x2f32(-r1, v[3], acc[kd][3], 0, 0, 0);
+            }
+        }
+    };
+
+    for (long long item = xr.first; item < xr.end; item += xr.stride) {
+        const int by = (int)(item % a.by_n);
+        long long rest = item / a.by_n;
+        const int bx = (int)(rest % a.bx_n);
+        rest /= a.bx_n;
+        const int seg = (int)(rest % a.segs_per_col);
+        const long long vol = rest / a.segs_per_col;
+        const int y0 = 2 * by, x0 = 32 * bx;
+        const int tau0 = seg * a.seg_len, tau1 = tau0 + a.seg_len < a.D ? tau0 + a.seg_len : a.D;
+        const bool interior = y0 >= 1 && y0 + 2 < a.H && x0 >= 1 && x0 + 32 < a.W;   // uniform
+        // origins of the regions in slice 0 of this volume; never dereferenced outside the tensors
+        const float* const ox = a.a + (((vol * a.D) * a.H + y0 - 1) * a.W + x0 - 1) * a.Ci + ci0;
+        const float* const og = a.g + (((vol * a.D) * a.H + y0) * a.W + x0) * a.Co + co0;
+        const long long px_plane = (long long)a.H * a.W;
+        auto load_x = [&](int tau, float* dst) {
+            fill(ox + tau * px_plane * a.Ci, tau >= 0 && tau < a.D, interior, y0 - 1, x0 - 1, 34, k3XLoads, a.Ci, dst);
+        };
+        auto load_g = [&](int tau, float* dst) {
+            fill(og + tau * px_plane * a.Co, tau >= 0 && tau < a.D, interior, y0, x0, 32, k3GLoads, a.Co, dst);
+        };
+        // the previous chunk ended with a barrier: all buffers are free
+        load_x(tau0, X0);
+        load_g(tau0 + 1, G0);
+        load_g(tau0, G1);
+        load_g(tau0 - 1, G2);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        int tau = tau0;
+        // chunk tau: input in xc, gradients of slices tau + 1, tau, tau - 1 in gp, gz, gm; the next chunk's input goes to
+        // xn and the gradient slice tau + 2 to gn (the buffer that held slice tau - 2)
+        auto chunk = [&](const float* xc, float* xn, const float* gp, const float* gz, const float* gm, float* gn)
+                         __attribute__((always_inline)) {
+            if (tau + 1 < tau1) {
+                load_x(tau + 1, xn);
+                load_g(tau + 2, gn);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            run(xc, gp, gz, gm);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            ++tau;
+        };
+        while (true) {
+            chunk(X0, X1, G0, G1, G2, G3);
+            if (tau >= tau1) break;
+            chunk(X1, X0, G3, G0, G1, G2);
+            if (tau >= tau1) break;
+            chunk(X0, X1, G2, G3, G0, G1);
+            if (tau >= tau1) break;
+            chunk(X1, X0, G1, G2, G3, G0);
+            if (tau >= tau1) break;
+        }
+    }
+
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+        for (int nu = 0; nu < 4; ++nu) {
+            const int pos = kd * 16 + 4 * xi + nu;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = co0 + 8 * (r >> 2) + 4 * h + (r & 3), ci = ci0 + m;
+                pout[((size_t)pos * a.Co + co) * a.Ci + ci] = acc[kd][nu][r];
+            }
+        }
+    if (a.bias_partial && ci0 == 0 && xi == 1) {
+        const float tot = bsum + __shfl_xor(bsum, 32);
+        if (h == 0) a.bias_partial[(size_t)blockIdx.x * a.Co + co0 + m] = tot;
+    }
+}
+
+// grad_w[co][kd*9 + tap][ci] = G^T P_kd G from the reduced sums P[kd*16 + pos][co][ci]
+__global__ __launch_bounds__(256) void wgrad_wino3_finish_kernel(const float* __restrict__ psum, int Co, int Ci, float* __restrict__ gw) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= 3 * Co * Ci) return;
+    const int ci = idx % Ci, co = (idx / Ci) % Co, kd = idx / (Ci * Co);
+    float P[4][4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int n = 0; n < 4; ++n) P[x][n] = psum[((size_t)(kd * 16 + 4 * x + n) * Co + co) * Ci + ci];
+    float gp[3][4];   // G^T P
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        gp[0][n] = P[0][n] + 0.5f * (P[1][n] + P[2][n]);
+        gp[1][n] = 0.5f * (P[1][n] - P[2][n]);
+        gp[2][n] = 0.5f * (P[1][n] + P[2][n]) + P[3][n];
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        float* o = gw + ((size_t)co * 27 + kd * 9 + t * 3) * Ci + ci;
+        o[0] = gp[t][0] + 0.5f * (gp[t][1] + gp[t][2]);
+        o[Ci] = 0.5f * (gp[t][1] - gp[t][2]);
+        o[2 * Ci] = 0.5f * (gp[t][1] + gp[t][2]) + gp[t][3];
+    }
+}
+
+bool wgrad_wino3_applies(const PixDims& d, int Ci, int Co) {
+    return d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3 && Ci % 32 == 0 && Co % 32 == 0 &&
+           16.0 * d.W * (Ci > Co ? Ci : Co) < 2.0e9;   // 32-bit lane byte offsets within four image rows
+}
+
+// Workgroups along x and the run of slices one of them walks per column: the choice that minimises
+// (runs per workgroup) x (run length + the chunk and a half a run's first loads cost).
+static void wgrad_wino3_split(const PixDims& d, int* grid_x, int* seg_len, int* segs_per_col) {
+    const long long vols = d.Q / ((long long)d.D * d.H * d.W);
+    const long long cols = vols * ((d.H + 1) / 2) * ((d.W + 31) / 32);
+    const long long cap = 512;   // two workgroups per CU
+    double best = 1e300;
+    *seg_len = d.D; *segs_per_col = 1;
+    for (int n = 1; n <= 64 && n <= d.D; ++n) {
+        const int len = (d.D + n - 1) / n;
+        const int nseg = (d.D + len - 1) / len;
+        const long long items = cols * nseg;
+        const long long wgs = items < cap ? items : cap;
+        const double cost = (double)((items + wgs - 1) / wgs) * (len + 1.5);
+        if (cost < best) { best = cost; *seg_len = len; *segs_per_col = nseg; }
+    }
+    const long long items = cols * *segs_per_col;
+    *grid_x = (int)(((items < cap ? items : cap) + 7) / 8 * 8);
+}
+
+int wgrad_wino3_splits(const PixDims& d) {
+    int gx, len, n;
+    wgrad_wino3_split(d, &gx, &len, &n);
+    return gx;
+}
+
+size_t wgrad_wino3_partial_floats(const PixDims& d, int Ci, int Co) { return (size_t)(wgrad_wino3_splits(d) + 1) * 48 * Ci * Co; }
+
+hipError_t launch_wgrad_wino3(Wino3WgradArgs a, const PixDims& d, int relu_in, hipStream_t st) {
+    int gx;
+    wgrad_wino3_split(d, &gx, &a.seg_len, &a.segs_per_col);
+    a.D = d.D; a.H = d.H; a.W = d.W;
+    a.bx_n = (a.W + 31) / 32;
+    a.by_n = (a.H + 1) / 2;
+    const long long vols = d.Q / ((long long)d.D * d.H * d.W);
+    a.n_items = vols * a.segs_per_col * (long long)a.bx_n * a.by_n;
+    dim3 grid((unsigned)gx, (unsigned)((a.Co / 32) * (a.Ci / 32)));
+    if (relu_in) hipLaunchKernelGGL((wgrad_wino3_kernel<true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_wino3_kernel<false>), grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t wgrad_wino3_finish(const float* psum, int Co, int Ci, float* grad_w, hipStream_t st) {
+    hipLaunchKernelGGL(wgrad_wino3_finish_kernel, dim3((unsigned)((3 * Co * Ci + 255) / 256)), dim3(256), 0, st, psum, Co, Ci, grad_w);
+    return hipGetLastError();
+}
+
 bool conv_wino3_applies(const PixDims& d, int K, int Nn) {
     return d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3 && K % 16 == 0 && Nn % 32 == 0 &&
            (long long)d.H * d.W * K < (1LL << 30);
