@@ -453,15 +453,31 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
     // One chunk: 8 contraction steps (tiles 2q and 2q+1 on the two lane halves), 12 MFMAs each.
     // gp / gz / gm: gradient regions of slices tau + 1, tau, tau - 1 (depth taps 0, 1, 2).
     auto run = [&](const float* x, const float* gp, const float* gz, const float* gm) __attribute__((always_inline)) {
+        float rg[3][4], rd[2][4];   // raw pixels of one step: gradient [depth tap][row*2 + column], input [row a/b][column]
+        auto load = [&](int q) {
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd) {
+                const float* g = kd == 0 ? gp : (kd == 1 ? gz : gm);
+                rg[kd][0] = g[go[0] + 128 * q];
+                rg[kd][1] = g[go[1] + 128 * q];
+                rg[kd][2] = g[go[0] + 1024 + 128 * q];
+                rg[kd][3] = g[go[1] + 1024 + 128 * q];
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                rd[0][c] = x[(xo[0][c >> 1] ^ (32 * (c & 1))) + 128 * q];
+                rd[1][c] = x[(xo[1][c >> 1] ^ (32 * (c & 1))) + 128 * q];
+            }
+        };
+        load(0);
 #pragma unroll 1
         for (int q = 0; q < 8; ++q) {
-            float v[4];
+            float v[4], z[3][4];
             {
                 float t[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    float da = x[(xo[0][c >> 1] ^ (32 * (c & 1))) + 128 * q];
-                    float dbv = x[(xo[1][c >> 1] ^ (32 * (c & 1))) + 128 * q];
+                    float da = rd[0][c], dbv = rd[1][c];
                     if (RELU) {
                         da = __int_as_float(__float_as_int(da) > 0 ? __float_as_int(da) : 0);
                         dbv = __int_as_float(__float_as_int(dbv) > 0 ? __float_as_int(dbv) : 0);
@@ -475,18 +491,20 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
             }
 #pragma unroll
             for (int kd = 0; kd < 3; ++kd) {
-                const float* g = kd == 0 ? gp : (kd == 1 ? gz : gm);
-                const float g00 = g[go[0] + 128 * q], g01 = g[go[1] + 128 * q];
-                const float g10 = g[go[0] + 1024 + 128 * q], g11 = g[go[1] + 1024 + 128 * q];
-                const float r0 = fmaf(cb, g10, ca * g00), r1 = fmaf(cb, g11, ca * g01);   // row xi of A dY
-                // (A dY A^T)[xi][nu]: r0, r0 + r1, r0 - r1, -r1
-                const float z1 = r0 + r1;
-                if (kd == 1 && xi == 1) bsum += z1;   // position (1,1) of A dY A^T = sum of the 2x2 block
-                acc[kd][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(r0, v[0], acc[kd][0], 0, 0, 0);
-                acc[kd][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(z1, v[1], acc[kd][1], 0, 0, 0);
-                acc[kd][2] = __builtin_amdgcn_mfma_f32_32x32x2f32(r0 - r1, v[2], acc[kd][2], 0, 0, 0);
-                acc[kd][3] = __builtin_amdgcn_mfma_f32_32x32x2f32(-r1, v[3], acc[kd][3], 0, 0, 0);
+                const float r0 = fmaf(cb, rg[kd][2], ca * rg[kd][0]), r1 = fmaf(cb, rg[kd][3], ca * rg[kd][1]);   // row xi of A dY
+                z[kd][0] = r0;            // (A dY A^T)[xi][nu]: r0, r0 + r1, r0 - r1, -r1; the last one's sign is
+                z[kd][1] = r0 + r1;       // applied to the reduced sums instead
+                z[kd][2] = r0 - r1;
+                z[kd][3] = r1;
             }
+            if (xi == 1) bsum += z[1][1];   // position (1,1) of A dY A^T = sum of the 2x2 block
+            load(q + 1 < 8 ? q + 1 : 7);    // the next step's pixels are on their way while this step's MFMAs issue
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+                for (int nu = 0; nu < 4; ++nu)
+                    acc[kd][nu] = __builtin_amdgcn_mfma_f32_32x32x2f32(z[kd][nu], v[nu], acc[kd][nu], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -561,7 +579,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
     }
 }
 
-// grad_w[co][kd*9 + tap][ci] = G^T P_kd G from the reduced sums P[kd*16 + pos][co][ci]
+// grad_w[co][kd*9 + tap][ci] = G^T P_kd G from the reduced sums P[kd*16 + pos][co][ci] (column 3 arrives negated)
 __global__ __launch_bounds__(256) void wgrad_wino3_finish_kernel(const float* __restrict__ psum, int Co, int Ci, float* __restrict__ gw) {
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= 3 * Co * Ci) return;
@@ -570,7 +588,10 @@ __global__ __launch_bounds__(256) void wgrad_wino3_finish_kernel(const float* __
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
-        for (int n = 0; n < 4; ++n) P[x][n] = psum[((size_t)(kd * 16 + 4 * x + n) * Co + co) * Ci + ci];
+        for (int n = 0; n < 4; ++n) {
+            const float v = psum[((size_t)(kd * 16 + 4 * x + n) * Co + co) * Ci + ci];
+            P[x][n] = n == 3 ? -v : v;
+        }
     float gp[3][4];   // G^T P
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
