@@ -105,11 +105,12 @@ int gleam_theta_count(const gleam_prox_desc* prox, size_t* n_floats);
  * under the same policy (the Winograd and 2D-tile bf16 kernels hand ReLU masks over as sign words), and
  * gleam_workspace_bytes must be asked under the policy the calls will run with.  Not synchronised with calls in
  * flight on other threads.  Unknown bits: GLEAM_E_DESC. */
-#define GLEAM_POLICY_NO_WINOGRAD      1u  /* 3x3 fp32 layers with 64-multiples of channels: direct MFMA kernels         */
+#define GLEAM_POLICY_NO_WINOGRAD      1u  /* 3x3 and 3x3x3 fp32 layers with wide channel counts: direct MFMA kernels    */
 #define GLEAM_POLICY_NO_BF16_2D       2u  /* 3x3 bf16 layers: flattened-pixel kernel instead of the 2D-tile one        */
 #define GLEAM_POLICY_NO_THIN_MFMA     4u  /* 2-channel first / last layers: vector-ALU kernels instead of matrix-core   */
 #define GLEAM_POLICY_NO_WGRAD_BALANCE 8u  /* 27-tap weight gradient: nine 3-tap jobs instead of the balanced 8-wave split */
-#define GLEAM_POLICY_ALL              15u
+#define GLEAM_POLICY_NO_FRAME_WALK    16u /* 3x1x1 weight gradient: one job per tap instead of the walk along the frames */
+#define GLEAM_POLICY_ALL              31u
 int gleam_set_kernel_policy(uint32_t policy);
 uint32_t gleam_get_kernel_policy(void);
 

@@ -153,7 +153,7 @@ def _check(rc: int, where: str):
         raise GleamError(rc, where)
 
 
-POLICY_NO_WINOGRAD, POLICY_NO_BF16_2D, POLICY_NO_THIN_MFMA, POLICY_NO_WGRAD_BALANCE = 1, 2, 4, 8
+POLICY_NO_WINOGRAD, POLICY_NO_BF16_2D, POLICY_NO_THIN_MFMA, POLICY_NO_WGRAD_BALANCE, POLICY_NO_FRAME_WALK = 1, 2, 4, 8, 16
 
 
 def gleam_set_kernel_policy(policy: int):

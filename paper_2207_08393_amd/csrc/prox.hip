@@ -1906,6 +1906,11 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
             const size_t need = align256(wgrad_wino_partial_floats(c.cin, c.cout, plan.n_split) * sizeof(float));
             if (need > plan.partial_bytes) plan.partial_bytes = need;
         }
+        if (p.dtype == 0 && wgrad_time_applies(dd, c.cin, c.cout)) {
+            dd.Q = plan.Q;
+            const size_t need = align256(wgrad_time_partial_floats(dd, c.cin, c.cout) * sizeof(float));
+            if (need > plan.partial_bytes) plan.partial_bytes = need;
+        }
         if (p.dtype == 0 && wgrad_wino3_applies(dd, c.cin, c.cout)) {
             dd.Q = plan.Q;
             const size_t need = align256(wgrad_wino3_partial_floats(dd, c.cin, c.cout) * sizeof(float));
@@ -2313,6 +2318,17 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                 if (e != hipSuccess) return e;
             }
             wino_wgrad_done = true;
+        } else if (!(kernel_policy() & GLEAM_POLICY_NO_FRAME_WALK) && wgrad_time_applies(d, c.cin, c.cout)) {
+            // temporal 3x1x1: walk along the frames, every input and gradient read once
+            TimeWgradArgs tw{};
+            tw.g = wa.g; tw.a = wa.a; tw.partial = partial; tw.bias_partial = c.has_bias ? bpart : nullptr;
+            tw.Co = c.cout; tw.Ci = c.cin;
+            char name[56];
+            snprintf(name, sizeof(name), "conv_wgrad_%dto%d_t%d", c.cin, c.cout, taps);
+            KernelScope ks(name, 2.0 * (double)d.Q * c.cin * c.cout * taps, 4.0 * (double)d.Q * (c.cin + c.cout), st);
+            e = launch_wgrad_time(tw, d, wa.relu_in, st);
+            used_split = wgrad_time_splits(d);
+            bias_done = c.has_bias;
         } else {
             e = launch_wgrad(wa, c.has_bias ? bpart : nullptr, &bias_done, plan.n_split,
                              plan.partial_bytes / sizeof(float), &used_split, st);

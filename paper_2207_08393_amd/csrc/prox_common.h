@@ -197,6 +197,21 @@ int wgrad_wino3_splits(const PixDims& d);                                  // wo
 size_t wgrad_wino3_partial_floats(const PixDims& d, int Ci, int Co);      // partials and reduced sums
 hipError_t launch_wgrad_wino3(Wino3WgradArgs a, const PixDims& d, int relu_in, hipStream_t stream);
 hipError_t wgrad_wino3_finish(const float* psum, int Co, int Ci, float* grad_w, hipStream_t stream);
+// Weight gradient of a temporal 3x1x1 layer by a walk along the frames (prox_time.hip): partial sums
+// [gridDim.x][Co][3][Ci] for reduce_partials_kernel.
+struct TimeWgradArgs {
+    const float* g;         // [samples][T][P][Co]  gradient at the conv output (already ReLU-masked)
+    const float* a;         // [samples][T][P][Ci]  conv input before its optional ReLU
+    float* partial;
+    float* bias_partial;    // [gridDim.x][Co] or null
+    int Co, Ci;
+    int T;                  // set by the launcher: frames, pixels per frame, segments per frame, segments in total
+    long long P, segs, n_items;
+};
+bool wgrad_time_applies(const PixDims& d, int Ci, int Co);
+int wgrad_time_splits(const PixDims& d);
+size_t wgrad_time_partial_floats(const PixDims& d, int Ci, int Co);
+hipError_t launch_wgrad_time(TimeWgradArgs a, const PixDims& d, int relu_in, hipStream_t stream);
 // Transformed weights of several layers in one launch (a launch costs more than the transform of one layer).
 struct WinoWeightJob {
     const float* w;

@@ -307,7 +307,7 @@ def test_kernel_policy_is_an_explicit_process_wide_word_and_not_the_environment(
     try:
         gb.gleam_set_kernel_policy(gb.POLICY_NO_WINOGRAD | gb.POLICY_NO_THIN_MFMA)
         assert gb.gleam_get_kernel_policy() == 5
-        assert _status(gb.gleam_set_kernel_policy, 16) == gb.GLEAM_E_DESC      # unknown bit
+        assert _status(gb.gleam_set_kernel_policy, 32) == gb.GLEAM_E_DESC      # unknown bit
         assert gb.gleam_get_kernel_policy() == 5                               # and nothing changed
     finally:
         gb.gleam_set_kernel_policy(0)

@@ -101,6 +101,14 @@ def module_cases():
     yield "thin_time32", synth.Geom(2, 2, 2, 5, 1, 6, 10), synth.chain_prox([2, 32, 2], [KS, KT]), 0
     yield "thin_time64_l1", synth.Geom(2, 1, 2, 3, 1, 6, 46), synth.chain_prox([2, 64, 2], [KS, KT], has_bias=0), 1
     yield "thin_vol128_flat", synth.Geom(3, 1, 2, 1, 4, 6, 46), synth.chain_prox([2, 128, 32, 2], [K3, (1, 1, 1, 1), K3], has_bias=0), 1
+    # 3x3x3 layers with 32-multiples of channels (Winograd inside the slices, runs along the depth): volumes that the
+    # 8 x 32 and 2 x 32 pixel blocks do not divide, one and two slices, two samples, two channel blocks, no bias
+    yield "vol_wino_ragged", synth.Geom(3, 2, 2, 1, 6, 6, 46), synth.chain_prox([2, 32, 64, 2], [K3] * 3), 0
+    yield "vol_wino_two_slices_l1", synth.Geom(2, 1, 2, 1, 2, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3, has_bias=0), 1
+    # temporal 3x1x1 layers between 64-multiples of channels (weight gradient walks the frames): frames whose pixel
+    # count the 32-pixel segments do not divide, one and two frames, two samples, two channel blocks
+    yield "time64_ragged", synth.Geom(2, 2, 2, 2, 1, 6, 10), synth.chain_prox([2, 64, 128, 2], [KS, KT, KS]), 0
+    yield "time64_one_frame_l1", synth.Geom(2, 1, 2, 1, 1, 6, 10), synth.chain_prox([2, 64, 64, 2], [KS, KT, KS], has_bias=0), 1
 
 
 BF16_TOL = 2e-2          # bfloat16 operands (8 significant bits), float32 accumulation, against the exact float64 oracle
@@ -622,16 +630,29 @@ def test_direct_kernels_still_cover_the_winograd_shapes(kernel_policy):
     kernel_policy(0)
     r_wino, _ = check_module(c)
     assert not np.array_equal(r_wino.results()[2], gd)            # two different kernels did run
+    # the same for a 3x3x3 layer between 32 channels
+    c = synth.make_custom(33, synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), accel=2.0, centre=2,
+                          bias_std=0.1, alpha=0.8)
+    kernel_policy(gb.POLICY_NO_WINOGRAD)
+    print("case direct kernels for the 3x3x3 Winograd shapes", flush=True)
+    r_direct, _ = check_module(c)
+    gd = r_direct.results()[2].copy()
+    kernel_policy(0)
+    r_wino, _ = check_module(c)
+    assert not np.array_equal(r_wino.results()[2], gd)
 
 
 def test_fallback_kernels_of_the_two_channel_layers_and_the_27_tap_gradient(kernel_policy):
-    """GLEAM_POLICY_NO_THIN_MFMA, _NO_BF16_2D and _NO_WGRAD_BALANCE route the shapes that normally take the
-    matrix-core two-channel kernels, the two-dimensional-tile bf16 kernel and the balanced 27-tap weight gradient
-    through the kernels they replaced: a 2D fp32, a 2D bf16 and a 3D module step on those against the oracle."""
-    kernel_policy(gb.POLICY_NO_THIN_MFMA | gb.POLICY_NO_BF16_2D | gb.POLICY_NO_WGRAD_BALANCE)
+    """GLEAM_POLICY_NO_THIN_MFMA, _NO_BF16_2D, _NO_WGRAD_BALANCE (with _NO_WINOGRAD, which otherwise takes the 27-tap
+    layer) and _NO_FRAME_WALK route the shapes that normally take the matrix-core two-channel kernels, the
+    two-dimensional-tile bf16 kernel, the balanced 27-tap weight gradient and the frame walk of the temporal weight
+    gradient through the kernels they replaced: 2D fp32, 2D bf16, 3D and 2D+t module steps on those against the oracle."""
+    kernel_policy(gb.POLICY_NO_THIN_MFMA | gb.POLICY_NO_BF16_2D | gb.POLICY_NO_WGRAD_BALANCE | gb.POLICY_NO_WINOGRAD |
+                  gb.POLICY_NO_FRAME_WALK)
     cases = [(synth.Geom(2, 1, 2, 1, 1, 10, 46), synth.chain_prox([2, 64, 64, 2], [K2] * 3), TOL),
              (synth.Geom(2, 1, 2, 1, 1, 20, 24), synth.chain_prox([2, 128, 128, 2], [K2] * 3, dtype=1), BF16_TOL),
-             (synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), TOL)]
+             (synth.Geom(3, 1, 2, 1, 4, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3), TOL),
+             (synth.Geom(2, 1, 2, 4, 1, 6, 10), synth.chain_prox([2, 64, 64, 2], [KS, KT, KS]), TOL)]
     for geom, prox, tol in cases:
         c = synth.make_custom(37, geom, prox, accel=2.0, centre=2, bias_std=0.1, alpha=0.8)
         print("case fallback kernels", geom, flush=True)
