@@ -39,8 +39,8 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC = {
     ("knee2d_640x368_c15_b2", "conv_fwd+dgrad_64to64_t9"): 1.126e5 * 1024 * 2.0 + 1.192e5 * 1024 * 1.0,
     ("knee2d_640x368_c15_b2", "conv_wgrad_64to64_t9"): 1.18465e5 * 1024 * 2.0 + 6.56e4 * 1024 * 1.0,
-    ("vol3d_256x160x160_c8_b1", "conv_fwd+dgrad_32to32_t27"): 1.731e6 * 1024 * 2.0 + 8.598e5 * 1024 * 1.0,
-    ("vol3d_256x160x160_c8_b1", "conv_wgrad_32to32_t27"): 1.648e6 * 1024 * 2.0 + 2.768e4 * 1024 * 1.0,
+    ("vol3d_256x160x160_c8_b1", "conv_fwd+dgrad_32to32_t27"): 1.205e6 * 1024 * 2.0 + 8.192e5 * 1024 * 1.0,
+    ("vol3d_256x160x160_c8_b1", "conv_wgrad_32to32_t27"): 8.772e5 * 1024 * 2.0 + 9.837e4 * 1024 * 1.0,
 }
 
 WORKLOAD_NAMES = ("tiny2d", "knee2d", "brain2d bf16", "vol3d", "cine2dt")
