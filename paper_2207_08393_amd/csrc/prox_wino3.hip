@@ -10,7 +10,7 @@
 // 2 groups x (32 tiles x 32 channels) = 8 MFMA accumulators of 32x32; a transformed-weight operand read from LDS
 // serves both groups.  A chunk is one depth tap x 8 input channels: the raw 10 x 34-pixel region of the tapped
 // slice (zero outside the volume) and that tap's transformed weights, both copied global -> LDS by direct loads
-// into the second of two buffers while the MFMAs of the current chunk run.  After the last chunk the 16 products of
+// while the MFMAs of earlier chunks run.  After the last chunk the 16 products of
 // a tile are spread over the four waves; they are combined through LDS (A^T . A), one tile group per pass, and stored
 // with the fused epilogue (bias, ReLU, ReLU mask, skip / gradient add).  Workgroups are persistent; blocks are
 // numbered with the slice index fastest, so the workgroups of an XCD work on neighbouring slices of the same
@@ -23,18 +23,7 @@ namespace gleam {
 
 namespace {
 
-constexpr int kRawSlots = 704;     // 10 rows x 34 columns x 2 channel quads = 680 quads, rounded up to whole wave loads
-constexpr int kRawLoads = kRawSlots / 64;
 constexpr int kUSlots = 1024;      // 16 positions x 2 channel quads x 32 output channels
-constexpr int kExFloats = 4 * 2 * 32 * 8 * 4;   // per pass: 4 waves x 2 output columns x 32 tiles x 8 channel quads
-constexpr int kBufFloats = (kRawSlots + kUSlots) * 4 > kExFloats ? (kRawSlots + kUSlots) * 4 : kExFloats;
-
-// Exchange element (wave, column jj, tile, quad cq): the quad index is XOR-ed with bits of the tile index so that both
-// the writers (16 lanes = 16 tiles, one quad) and the readers (16 lanes = 2 tiles x 8 quads) touch 16 different
-// 16-byte bank groups.
-__device__ __forceinline__ int ex_off(int wave, int jj, int tile, int cq) {
-    return ((((wave * 2 + jj) * 32 + tile) * 8) + (cq ^ ((tile >> 1) & 7))) * 4;
-}
 
 __device__ __forceinline__ void dma16(const float* g, float* l) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
@@ -57,12 +46,29 @@ __device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(
 
 }  // namespace
 
+// Staging.  The raw regions are staged 16 input channels at a time (64 contiguous bytes per pixel and request; with 8
+// channels, i.e. 32 bytes, the same bytes took twice the memory requests and the kernel 5 % longer) while the
+// transformed weights come in 8-channel chunks: a raw half serves two chunks and is requested two chunks ahead, a
+// weight chunk one chunk ahead.  Four LDS objects (two raw halves, two weight chunks) and the chunk loop written out
+// over its period of four, so that the compiler knows which buffer a read touches and does not make it wait for
+// loads in flight into another.  Inside a pixel the four channel quads are XOR-ed with bits 2..3 of the half-column
+// index, so that the 16 lanes a 128-bit read serves together (16 neighbouring tiles, one quad) fall on 16 different
+// bank groups.  K must be a multiple of 32 (an even number of halves per depth tap keeps the rotation aligned).
+constexpr int kRHSlots = 1408;     // 10 rows x 2 column parities x 17 half-columns x 4 quads = 1360, rounded up to whole wave loads
+constexpr int kRHLoads = kRHSlots / 64;
+constexpr int kExHalfFloats = 4 * 32 * 8 * 4;   // per output column: 4 waves x 32 tiles x 8 channel quads
+static_assert(kExHalfFloats <= kUSlots * 4 && kExHalfFloats <= kRHSlots * 4, "the exchange reuses a weight and a raw buffer");
+// Exchange element (wave, tile, quad cq) of an output column: the quad index is XOR-ed with bits of the tile index so
+// that both the writers (16 lanes = 16 tiles, one quad) and the readers (16 lanes = 2 tiles x 8 quads) touch 16
+// different 16-byte bank groups.
+__device__ __forceinline__ int exh_off(int wave, int tile, int cq) { return (((wave * 32 + tile) * 8) + (cq ^ ((tile >> 1) & 7))) * 4; }
+
 template <bool RELU>
 __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
-    // Separate LDS objects: reads of one chunk buffer then do not wait for direct loads into the other.
-    __shared__ __attribute__((aligned(16))) float bufA[kBufFloats];
-    __shared__ __attribute__((aligned(16))) float bufB[kBufFloats];
-    float* const ex = bufB;   // the exchange of the output transform reuses the second chunk buffer
+    __shared__ __attribute__((aligned(16))) float R0[kRHSlots * 4];
+    __shared__ __attribute__((aligned(16))) float R1[kRHSlots * 4];
+    __shared__ __attribute__((aligned(16))) float U0[kUSlots * 4];
+    __shared__ __attribute__((aligned(16))) float U1[kUSlots * 4];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 31, h = lane >> 5, xi = wave;
@@ -70,27 +76,26 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
 
     const XcdRange xr = xcd_range(a.n_blocks);
     const int ny = blockIdx.y, n0 = ny * 32;
-    const int n_kc = a.K / 8;          // even (K is a multiple of 16)
-    const int n_ch = 3 * n_kc;         // chunks per block
+    const int n_kc = a.K / 8, n_hf = a.K / 16;   // chunks and raw halves per depth tap
+    const int n_ch = 3 * n_kc;                   // chunks per block: a multiple of 4
     const long long plane = (long long)a.H * a.W * a.K;   // floats per slice
 
-    // Direct-load sources of this lane: three quads of the raw region (a zero quad outside the slice).
-    int s_row[3], s_col[3], s_quad[3];
+    // Direct loads of the raw halves: slot s = tid + 256*i holds (row*2 + column parity, half-column, position) =
+    // (s / 68, (s % 68) / 4, s % 4); the channel quad at a position is position ^ ((half-column >> 2) & 3).
+    unsigned r_off[6];     // byte offset of the slot's quad from the region origin (pixel (y0-1, x0-1), first channel of the half)
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        const int s = tid + i * 256;
-        // slot = ((row*2 + column parity)*17 + column/2)*2 + quad: the two quads of a pixel are neighbouring lanes
-        // (one 32-byte request), even columns before odd ones
-        const int rp = s / 34, rem = s - rp * 34;
-        s_col[i] = 2 * (rem >> 1) + (rp & 1);
-        s_row[i] = s < 680 ? (rp >> 1) : -100000;            // slots past the region always read the zero quad
-        s_quad[i] = rem & 1;
+    for (int i = 0; i < 6; ++i) {
+        const int s = tid + 256 * i;
+        const int rp = s / 68, rem = s - rp * 68;
+        const int colh = rem >> 2, quad = (rem & 3) ^ ((colh >> 2) & 3);
+        const int row = rp >> 1, col = 2 * colh + (rp & 1);
+        r_off[i] = s < 1360 ? 4u * (unsigned)((row * a.W + col) * a.K + 4 * quad) : 0u;
     }
     struct Block {
         int x0, y0, d;
         long long img;
-        const float* gp[3];   // this lane's quads in the block's own slice, channel 0 (the zero quad when outside)
-        int in_img;           // bit i: quad i lies inside the slice
+        unsigned in_img;      // bit i: slot i lies inside the slice
+        bool interior;        // the whole region lies inside the slice (uniform)
     };
     auto setup = [&](long long item) {
         Block b;
@@ -102,39 +107,56 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
         b.img = (rest / a.by_n) * a.D + b.d;
         b.x0 = bx * 32;
         b.y0 = by * 8;
-        b.in_img = 0;
+        b.interior = b.y0 >= 1 && b.y0 + 8 < a.H && b.x0 >= 1 && b.x0 + 32 < a.W;
+        b.in_img = 0u;
+        if (!b.interior) {   // the slots' pixels again (once per border block; not worth six registers)
+            int t = tid;
+            asm volatile("" : "+v"(t));
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const int yy = b.y0 - 1 + s_row[i], xx = b.x0 - 1 + s_col[i];
-            const bool ok = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
-            b.gp[i] = ok ? a.in + ((b.img * a.H + yy) * a.W + xx) * a.K + s_quad[i] * 4 : a.zero;
-            b.in_img |= ok ? (1 << i) : 0;
+            for (int i = 0; i < 6; ++i) {
+                const int s = t + 256 * i;
+                const int rp = s / 68, rem = s - rp * 68;
+                const int yy = b.y0 - 1 + (rp >> 1), xx = b.x0 - 1 + 2 * (rem >> 2) + (rp & 1);
+                const bool ok = s < 1360 && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
+                b.in_img |= ok ? (1u << i) : 0u;
+            }
         }
         return b;
     };
-    const float* ubase = a.u + (size_t)ny * n_ch * (kUSlots * 4);   // uniform; lanes add a 32-bit offset
-    const unsigned uoff = 16u * (unsigned)tid;   // bytes
-
-    // chunk c = kd * n_kc + kc
-    auto issue = [&](const Block& b, int c, float* dst) {
-        const int kd = c >= 2 * n_kc ? 2 : (c >= n_kc ? 1 : 0);
-        const int kc = c - kd * n_kc;
+    // raw half hidx = kd * n_hf + hf of block b
+    auto issue_raw = [&](const Block& b, int hidx, float* dst) {
+        const int kd = hidx >= 2 * n_hf ? 2 : (hidx >= n_hf ? 1 : 0);
+        const int hf = hidx - kd * n_hf;
         const int dz = b.d + kd - 1;
         const bool slice_ok = dz >= 0 && dz < a.D;          // uniform
-        const long long shift = (long long)(kd - 1) * plane + kc * 8;
+        // region origin; only dereferenced through lanes whose pixel lies inside the slice
+        const float* base = a.in + (b.img + kd - 1) * plane + ((long long)(b.y0 - 1) * a.W + (b.x0 - 1)) * a.K + 16 * hf;
+        if (slice_ok && b.interior) {
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const int o = wave + i * 4;
-            if (o < kRawLoads) {
-                const float* p = (slice_ok && ((b.in_img >> i) & 1)) ? b.gp[i] + shift : a.zero;
-                dma16(p, dst + o * 256);
+            for (int i = 0; i < 6; ++i) {
+                const int o = wave + 4 * i;
+                if (o < kRHLoads) dma16_off(base, r_off[i], dst + o * 256);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                const int o = wave + 4 * i;
+                if (o < kRHLoads) {
+                    const bool ok = slice_ok && ((b.in_img >> i) & 1u);
+                    const float* p = ok ? reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + r_off[i]) : a.zero;
+                    dma16(p, dst + o * 256);
+                }
             }
         }
+    };
+    const float* ubase = a.u + (size_t)ny * n_ch * (kUSlots * 4);   // uniform; lanes add a 32-bit offset
+    const unsigned uoff = 16u * (unsigned)tid;   // bytes
+    auto issue_u = [&](int c, float* dst) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int o = wave + i * 4;
             const float* ub = ubase + ((size_t)c * (kUSlots * 4) + 1024 * i);   // scalar address
-            dma16_off(ub, uoff, dst + kRawSlots * 4 + o * 256);
+            dma16_off(ub, uoff, dst + o * 256);
         }
     };
 
@@ -142,17 +164,26 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
     const int ra = xi == 0 ? 0 : (xi == 2 ? 2 : 1);
     const int rb = xi == 3 ? 3 : (xi == 2 ? 1 : 2);
     const float sg = xi == 1 ? 1.f : -1.f;
-    // Region quad (row, column, quad) sits at slot ((row*2 + (column & 1))*17 + column/2)*2 + quad; tile group g
-    // starts four region rows further down.
-    const int offA = (((2 * trl + ra) * 2) * 17 + tc) * 8 + 4 * h;
-    const int offB = (((2 * trl + rb) * 2) * 17 + tc) * 8 + 4 * h;
-    constexpr int kGroupFloats = 4 * 2 * 17 * 8;
+    // float offset of this lane's quad: region row r, column 2*tc + c, channel quad 2*sub + h of the half ->
+    // ((r*2 + (c & 1))*17 + tc + (c >> 1))*16 + 4*((2*sub + h) ^ (((tc + (c >> 1)) >> 2) & 3)); tile group g starts four rows down
+    int pa[2][2], pb[2][2];   // [c >> 1][sub]
+#pragma unroll
+    for (int cs = 0; cs < 2; ++cs)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int colh = tc + cs;
+            const int lanepart = colh * 16 + 4 * ((2 * sub + h) ^ ((colh >> 2) & 3));
+            pa[cs][sub] = (2 * trl + ra) * 2 * 17 * 16 + lanepart;
+            pb[cs][sub] = (2 * trl + rb) * 2 * 17 * 16 + lanepart;
+        }
+    constexpr int kParFloats = 17 * 16, kGroupFloats = 4 * 2 * 17 * 16;
     // U quad (position, channel quad hq, output channel n) at slot ((pos*2 + hq)*32 + n)
-    const int offU = kRawSlots * 4 + (((xi * 4) * 2 + h) * 32 + m) * 4;
+    const int offU = (((xi * 4) * 2 + h) * 32 + m) * 4;
 
     floatx16 acc[4][2];
 
-    auto compute = [&](const float* buf, auto first_c) {
+    auto compute = [&](const float* raw, const float* u_, auto sub_c, auto first_c) __attribute__((always_inline)) {
+        constexpr int SUB = decltype(sub_c)::value;
         constexpr bool FIRST = decltype(first_c)::value;   // first chunk of a block: accumulators start from zero
         float4 v[2][4];
 #pragma unroll
@@ -160,8 +191,8 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
             float4 t[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                float4 da = *reinterpret_cast<const float4*>(buf + offA + g * kGroupFloats + ((c & 1) * 17 + (c >> 1)) * 8);
-                float4 db = *reinterpret_cast<const float4*>(buf + offB + g * kGroupFloats + ((c & 1) * 17 + (c >> 1)) * 8);
+                float4 da = *reinterpret_cast<const float4*>(raw + pa[c >> 1][SUB] + g * kGroupFloats + (c & 1) * kParFloats);
+                float4 db = *reinterpret_cast<const float4*>(raw + pb[c >> 1][SUB] + g * kGroupFloats + (c & 1) * kParFloats);
                 if (RELU) {
                     da = relu4(da);
                     db = relu4(db);
@@ -175,7 +206,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
         }
 #pragma unroll
         for (int nu = 0; nu < 4; ++nu) {
-            const float4 u = *reinterpret_cast<const float4*>(buf + offU + (nu * 2 * 32) * 4);
+            const float4 u = *reinterpret_cast<const float4*>(u_ + offU + (nu * 2 * 32) * 4);
             if (FIRST) {
                 floatx16 z;
 #pragma unroll
@@ -194,46 +225,58 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
             acc[nu][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(u.w, v[1][nu].w, acc[nu][1], 0, 0, 0);
         }
     };
+    auto sync = [&]() {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
 
     if (xr.first >= xr.end) return;   // uniform for the workgroup
     Block cur = setup(xr.first);
-    issue(cur, 0, bufA);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    const float4 bias_r = a.bias ? *reinterpret_cast<const float4*>(a.bias + n0 + 4 * (tid & 7)) : make_float4(0.f, 0.f, 0.f, 0.f);
+    issue_raw(cur, 0, R0);
+    issue_u(0, U0);
+    sync();
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
     for (long long item = xr.first; item < xr.end; item += xr.stride) {
         const bool has_next = item + xr.stride < xr.end;
         const Block nxt = setup(has_next ? item + xr.stride : item);
         const int x0 = cur.x0, y0 = cur.y0;
         const long long img = cur.img;
-        // n_ch is even: chunks alternate between the two buffers
-        issue(cur, 1, bufB);
-        __builtin_amdgcn_sched_barrier(0);   // keep the direct loads ahead of the MFMAs they overlap with
-        compute(bufA, std::true_type{});
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        for (int c = 1; c < n_ch; c += 2) {
-            // the first chunk of the next block is fetched under the last MFMAs of this one
-            if (c + 1 < n_ch) issue(cur, c + 1, bufA);
-            else if (has_next) issue(nxt, 0, bufA);
+        // chunk c reads raw half c / 2 (R0, R0, R1, R1, ...) and weight chunk c (U0, U1, U0, U1, ...); a raw half is
+        // requested two chunks before its first use, a weight chunk one chunk before
+        for (int c = 0; c < n_ch; c += 4) {
+            const bool last4 = c + 4 >= n_ch;
+            issue_u(c + 1, U1);
+            issue_raw(cur, c / 2 + 1, R1);
+            __builtin_amdgcn_sched_barrier(0);   // keep the direct loads ahead of the MFMAs they overlap with
+            if (c == 0) compute(R0, U0, I0{}, std::true_type{});
+            else compute(R0, U0, I0{}, std::false_type{});
+            sync();
+            issue_u(c + 2, U0);
             __builtin_amdgcn_sched_barrier(0);
-            compute(bufB, std::false_type{});
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            if (c + 1 >= n_ch) break;
-            issue(cur, c + 2, bufB);
+            compute(R0, U1, I1{}, std::false_type{});
+            sync();
+            issue_u(c + 3, U1);
+            if (!last4) issue_raw(cur, c / 2 + 2, R0);
+            else if (has_next) issue_raw(nxt, 0, R0);
             __builtin_amdgcn_sched_barrier(0);
-            compute(bufA, std::false_type{});
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
+            compute(R1, U0, I0{}, std::false_type{});
+            sync();
+            if (!last4) issue_u(c + 4, U0);
+            else if (has_next) issue_u(0, U0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(R1, U1, I1{}, std::false_type{});
+            sync();
         }
 
         // Output transform.  In registers over nu: R_0 = M_0 + M_1 + M_2, R_1 = M_1 - M_2 - M_3; across the four waves
-        // through LDS: Y_0 = R[xi=0] + R[1] + R[2], Y_1 = R[1] - R[2] - R[3].  One pass per tile group.  A thread
-        // finishes the 2x2 pixels of one tile for one channel quad; what the fused epilogue reads from memory (ReLU
-        // mask source, tensor to add) is requested for all four pixels before the exchange, from a clamped address
-        // where the pixel is outside the slice.
+        // through LDS: Y_0 = R[xi=0] + R[1] + R[2], Y_1 = R[1] - R[2] - R[3].  One pass per tile group; the exchange goes
+        // through the weight and the raw buffer that the loads of the next block do not use, one output column each.
+        // A thread finishes the 2x2 pixels of one tile for one channel quad; what the fused epilogue reads from memory
+        // (ReLU mask source, tensor to add) is requested for all four pixels before the exchange, from a clamped
+        // address where the pixel is outside the slice.
         const int e_cq = tid & 7, e_tile = (tid >> 3) & 31;
+        const float4 bias_r = a.bias ? *reinterpret_cast<const float4*>(a.bias + n0 + 4 * e_cq) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
             if (g) __syncthreads();
@@ -263,15 +306,16 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
                     r1[i] = m1 - m2 - m3;
                 }
                 const int cq = 2 * rg + h;
-                *reinterpret_cast<float4*>(ex + ex_off(wave, 0, m, cq)) = make_float4(r0[0], r0[1], r0[2], r0[3]);
-                *reinterpret_cast<float4*>(ex + ex_off(wave, 1, m, cq)) = make_float4(r1[0], r1[1], r1[2], r1[3]);
+                *reinterpret_cast<float4*>(U1 + exh_off(wave, m, cq)) = make_float4(r0[0], r0[1], r0[2], r0[3]);
+                *reinterpret_cast<float4*>(R1 + exh_off(wave, m, cq)) = make_float4(r1[0], r1[1], r1[2], r1[3]);
             }
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < 2; ++i) {          // output row inside the tile
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj) {   // output column inside the tile
-                    auto rd = [&](int x_i) { return *reinterpret_cast<const float4*>(ex + ex_off(x_i, jj, e_tile, e_cq)); };
+                    const float* exj = jj ? R1 : U1;
+                    auto rd = [&](int x_i) { return *reinterpret_cast<const float4*>(exj + exh_off(x_i, e_tile, e_cq)); };
                     float4 yv;
                     if (i == 0) yv = add4(add4(rd(0), rd(1)), rd(2));
                     else yv = sub4(sub4(rd(1), rd(2)), rd(3));
@@ -292,7 +336,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
                 }
             }
         }
-        __syncthreads();   // the exchange lived in the second chunk buffer, which the next block loads into first
+        __syncthreads();   // the exchange lived in buffers that the first chunk of the next block loads into
         cur = nxt;
     }
 }
@@ -661,8 +705,8 @@ hipError_t wgrad_wino3_finish(const float* psum, int Co, int Ci, float* grad_w, 
 }
 
 bool conv_wino3_applies(const PixDims& d, int K, int Nn) {
-    return d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3 && K % 16 == 0 && Nn % 32 == 0 &&
-           (long long)d.H * d.W * K < (1LL << 30);
+    return d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3 && K % 32 == 0 && Nn % 32 == 0 &&
+           40.0 * d.W * K < 2.0e9;   // 32-bit lane byte offsets within the ten rows of a region
 }
 
 size_t conv_wino3_weight_floats(int K, int Nn) { return (size_t)48 * K * Nn + 4; }
