@@ -288,6 +288,170 @@ __global__ __launch_bounds__(256) void conv_thin_out_time_mfma_kernel(ThinOutTim
     }
 }
 
+// 3x3x3 layers with 32 input channels: a walk along the depth.  conv_thin_out_mfma_kernel<K, BF, 3, 3> visits every
+// input slice three times (once per output slice it contributes to) and was bound by those re-reads (2.7 times the
+// input left the L2 on the 3D volume).  Here a workgroup owns an 8 x 32-pixel column of the volume and walks a run of
+// slices: input slice z is read once, multiplied with the weight rows of all three depth taps (54 rows = 27 taps x 2
+// outputs, packed into two 32-row MFMA blocks instead of three) and its shifted sums go to the outputs of slices
+// z + 1, z and z - 1, which a thread keeps in registers for its pixel until slice z + 1 has added the last of them.
+// The next slice's pixels are requested before the MFMAs of the current one.
+struct ThinOutWalkArgs {
+    const float* in;      // [volumes][D][H][W][K]
+    const float* wts;     // [2][27][K]
+    const float* bias;    // [2] or null
+    const float* add;     // [volumes][D][H][W][2] or null
+    float* out;
+    int relu_in, relu_out, D, H, W, bx_n, by_n;
+    int seg_len, segs_per_col;   // output slices per run, runs per column
+    long long n_items;
+};
+
+constexpr int kTWStride = 56;   // floats per pixel slot in LDS: 54 tap contributions + 2
+
+template <int K>
+__global__ __launch_bounds__(256, 2) void conv_thin_out_walk_kernel(ThinOutWalkArgs a) {
+    constexpr int NM = K / 2, NV = NM / 4;   // MFMAs per 32-pixel block and row set; float4 loads per lane and block
+    constexpr int RW = 34, RPX = 10 * RW, NBLK = (RPX + 31) / 32;   // 340 region pixels in 11 blocks: three per wave, the last wave two
+    __shared__ __attribute__((aligned(16))) float c[NBLK * 32 * kTWStride];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    const int H = a.H, W = a.W, D = a.D;
+
+    // A operands: row m of set s is (tap 16*s + m/2, output m & 1); taps past the 27th are zero rows
+    float wf[2][NM];
+#pragma unroll
+    for (int s_ = 0; s_ < 2; ++s_) {
+        const int tap = 16 * s_ + (m >> 1);
+        const float* wrow = a.wts + (size_t)((m & 1) * 27 + (tap < 27 ? tap : 0)) * K + NM * h;
+#pragma unroll
+        for (int i = 0; i < NM; ++i) wf[s_][i] = tap < 27 ? wrow[i] : 0.f;
+    }
+    const float bias0 = a.bias ? a.bias[0] : 0.f, bias1 = a.bias ? a.bias[1] : 0.f;
+    const int oy = tid >> 5, ox = tid & 31;
+
+    const XcdRange xr = xcd_range(a.n_items);
+    for (long long item = xr.first; item < xr.end; item += xr.stride) {
+        const int by = (int)(item % a.by_n);
+        long long rest = item / a.by_n;
+        const int bx = (int)(rest % a.bx_n);
+        rest /= a.bx_n;
+        const int seg = (int)(rest % a.segs_per_col);
+        const long long vol = rest / a.segs_per_col;
+        const int x0 = bx * 32, y0 = by * 8;
+        const int z0 = seg * a.seg_len, z1 = z0 + a.seg_len < D ? z0 + a.seg_len : D;
+
+        // this lane's pixel slots (blocks wave, wave + 4, wave + 8): offset inside a slice, or -1 outside the image
+        int pix_off[3];
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            const int s_ = 32 * (wave + 4 * j) + m;
+            const int ry = s_ / RW, rx = s_ - ry * RW;
+            const int y = y0 - 1 + ry, x = x0 - 1 + rx;
+            pix_off[j] = (wave + 4 * j < NBLK && s_ < RPX && y >= 0 && y < H && x >= 0 && x < W) ? y * W + x : -1;
+        }
+        const bool third = wave + 8 < NBLK;   // uniform per wave
+        auto load = [&](int z, float4 (*v)[NV]) {
+            const float* plane = a.in + ((vol * D + z) * H) * (long long)W * K + NM * h;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                if (j == 2 && !third) continue;
+                const float* p = plane + (long long)(pix_off[j] >= 0 ? pix_off[j] : 0) * K;   // clamped: the loads are unconditional
+#pragma unroll
+                for (int q = 0; q < NV; ++q) v[j][q] = *reinterpret_cast<const float4*>(p + 4 * q);
+            }
+        };
+        auto compute = [&](int j, const float4* v) {
+            const bool ok = pix_off[j] >= 0;
+            float* cs = c + (32 * (wave + 4 * j) + m) * kTWStride;
+#pragma unroll
+            for (int s_ = 0; s_ < 2; ++s_) {
+                floatx16 acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+                    const float e[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        float xv = a.relu_in ? fmaxf(e[t], 0.f) : e[t];
+                        xv = ok ? xv : 0.f;
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[s_][4 * q + t], xv, acc, 0, 0, 0);
+                    }
+                }
+                // accumulator r holds row 8*(r/4) + 4*h + r%4 of this lane's pixel; set 1 keeps rows 0..21
+#pragma unroll
+                for (int rg = 0; rg < (s_ == 0 ? 4 : 3); ++rg)
+                    *reinterpret_cast<float4*>(cs + 32 * s_ + 8 * rg + 4 * h) =
+                        make_float4(acc[4 * rg], acc[4 * rg + 1], acc[4 * rg + 2], acc[4 * rg + 3]);
+            }
+        };
+
+        // o[k]: sums of this thread's pixel in slices zi - 1, zi, zi + 1 while input slice zi is worked on
+        float o[3][2] = {{bias0, bias1}, {bias0, bias1}, {bias0, bias1}};
+        float4 cur[3][NV], nxt[3][NV];
+        const int zi_first = z0 - 1 >= 0 ? z0 - 1 : 0, zi_last = z1 < D ? z1 : D - 1;
+        load(zi_first, cur);
+        for (int zi = zi_first; zi <= zi_last; ++zi) {
+            if (zi + 1 <= zi_last) load(zi + 1, nxt);
+            __builtin_amdgcn_sched_barrier(0);   // the next slice's loads are in flight before the first MFMA
+            compute(0, cur[0]);
+            compute(1, cur[1]);
+            if (third) compute(2, cur[2]);
+            __syncthreads();
+#pragma unroll
+            for (int ko = 0; ko < 3; ++ko)
+#pragma unroll
+                for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                    for (int dx = 0; dx < 3; ++dx) {
+                        const float2 v = *reinterpret_cast<const float2*>(c + ((oy + dy) * RW + ox + dx) * kTWStride + 2 * (ko * 9 + dy * 3 + dx));
+                        o[2 - ko][0] += v.x;
+                        o[2 - ko][1] += v.y;
+                    }
+            // slice zi - 1 has received its last contribution (slice zi - 1 = z0 - 1 or earlier is not this run's)
+            {
+                const int zo = zi - 1, y = y0 + oy, x = x0 + ox;
+                if (zo >= z0 && zo < z1 && y < H && x < W) {
+                    const long long q = ((vol * D + zo) * H + y) * W + x;
+                    float r0 = o[0][0], r1 = o[0][1];
+                    if (a.relu_out) { r0 = fmaxf(r0, 0.f); r1 = fmaxf(r1, 0.f); }
+                    if (a.add) {
+                        const float2 av = *reinterpret_cast<const float2*>(a.add + 2 * q);
+                        r0 += av.x;
+                        r1 += av.y;
+                    }
+                    *reinterpret_cast<float2*>(a.out + 2 * q) = make_float2(r0, r1);
+                }
+            }
+            o[0][0] = o[1][0]; o[0][1] = o[1][1];
+            o[1][0] = o[2][0]; o[1][1] = o[2][1];
+            o[2][0] = bias0; o[2][1] = bias1;
+#pragma unroll
+            for (int j = 0; j < 3; ++j)
+#pragma unroll
+                for (int q = 0; q < NV; ++q) cur[j][q] = nxt[j][q];
+            __syncthreads();   // the next slice overwrites c
+        }
+        // the last slices of the run: when the volume ends at z1 no input slice z1 exists to push them out
+        for (int zo = zi_last; zo < z1; ++zo) {
+            const int y = y0 + oy, x = x0 + ox;
+            if (zo >= z0 && y < H && x < W) {
+                const long long q = ((vol * D + zo) * H + y) * W + x;
+                float r0 = o[0][0], r1 = o[0][1];
+                if (a.relu_out) { r0 = fmaxf(r0, 0.f); r1 = fmaxf(r1, 0.f); }
+                if (a.add) {
+                    const float2 av = *reinterpret_cast<const float2*>(a.add + 2 * q);
+                    r0 += av.x;
+                    r1 += av.y;
+                }
+                *reinterpret_cast<float2*>(a.out + 2 * q) = make_float2(r0, r1);
+            }
+            o[0][0] = o[1][0]; o[0][1] = o[1][1];
+        }
+    }
+}
+
 // 0: not covered; 1: 3x3 in the plane; 2: 3x3x3 (outer axis = depth); 3: 3x1x1 on tiles that span all frames (as a
 // loop over three planes of an 8 x 32 tile it re-read every input three times and was slower than the lane-per-pixel
 // kernel, 125 against 97 us).
@@ -347,9 +511,27 @@ hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const flo
             else if (K == 64) launch_thin_out_mfma_t<64, false, 3, 1>(a, st);
             else launch_thin_out_mfma_t<128, false, 3, 1>(a, st);
         }
+    } else if (K == 32) {   // walk along the depth: every input slice read once
+        ThinOutWalkArgs w{};
+        w.in = reinterpret_cast<const float*>(in); w.wts = wts; w.bias = bias; w.add = add; w.out = out;
+        w.relu_in = relu_in; w.relu_out = relu_out; w.D = d.D; w.H = d.H; w.W = d.W;
+        w.bx_n = a.bx_n; w.by_n = a.by_n;
+        const long long cols = d.Q / ((long long)d.D * d.H * d.W) * a.bx_n * a.by_n;
+        const long long cap = 512;   // two workgroups per CU
+        // runs per column: the split that minimises (runs per workgroup) x (run length + the two extra slices a run reads)
+        double best = 1e300;
+        w.seg_len = d.D; w.segs_per_col = 1;
+        for (int n = 1; n <= 64 && n <= d.D; ++n) {
+            const int len = (d.D + n - 1) / n, nseg = (d.D + len - 1) / len;
+            const long long items = cols * nseg, wgs = items < cap ? items : cap;
+            const double cost = (double)((items + wgs - 1) / wgs) * (len + 2.0);
+            if (cost < best) { best = cost; w.seg_len = len; w.segs_per_col = nseg; }
+        }
+        w.n_items = cols * w.segs_per_col;
+        const long long gx = ((w.n_items < cap ? w.n_items : cap) + 7) / 8 * 8;
+        hipLaunchKernelGGL((conv_thin_out_walk_kernel<32>), dim3((unsigned)gx), dim3(256), 0, st, w);
     } else {
-        if (K == 32) launch_thin_out_mfma_t<32, false, 3, 3>(a, st);
-        else launch_thin_out_mfma_t<64, false, 3, 3>(a, st);
+        launch_thin_out_mfma_t<64, false, 3, 3>(a, st);
     }
     return hipGetLastError();
 }

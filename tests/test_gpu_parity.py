@@ -103,7 +103,7 @@ def module_cases():
     yield "thin_vol128_flat", synth.Geom(3, 1, 2, 1, 4, 6, 46), synth.chain_prox([2, 128, 32, 2], [K3, (1, 1, 1, 1), K3], has_bias=0), 1
     # 3x3x3 layers with 32-multiples of channels (Winograd inside the slices, runs along the depth): volumes that the
     # 8 x 32 and 2 x 32 pixel blocks do not divide, one and two slices, two samples, two channel blocks, no bias
-    yield "vol_wino_ragged", synth.Geom(3, 2, 2, 1, 6, 6, 46), synth.chain_prox([2, 32, 64, 2], [K3] * 3), 0
+    yield "vol_wino_ragged", synth.Geom(3, 2, 2, 1, 6, 6, 46), synth.chain_prox([2, 32, 64, 32, 2], [K3] * 4), 0
     yield "vol_16_to_32_direct", synth.Geom(3, 1, 2, 1, 4, 6, 12), synth.chain_prox([2, 16, 32, 2], [K3] * 3), 0
     yield "vol_wino_two_slices_l1", synth.Geom(2, 1, 2, 1, 2, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3, has_bias=0), 1
     # temporal 3x1x1 layers between 64-multiples of channels (weight gradient walks the frames): frames whose pixel
