@@ -428,27 +428,37 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
     }
 
     // Direct loads.  Slot s of a region (16 bytes at float offset 4*s) holds channel quad s & 7 of pixel
-    // 2*(s >> 4) + (((s >> 3) ^ (s >> 4)) & 1).  The slot tables are recomputed per chunk (a few dozen vector
-    // instructions against ~100 MFMAs): registers are what this kernel is short of.
-    auto fill = [&](const float* origin, bool plane_ok, bool interior, int y_first, int x_first, int cols, int loads, int C,
-                    float* dst) {
-        int t = tid;
-        asm volatile("" : "+v"(t));   // keeps the tables from being hoisted out of the chunk loop into registers
+    // 2*(s >> 4) + (((s >> 3) ^ (s >> 4)) & 1).  A thread's seven slots (five of the input region, two of the gradient
+    // region) are described by one word each - offset from the region origin in quads | row << 24 | column << 26 - kept
+    // in a thread-private column of an LDS table: registers are what this kernel is short of, and recomputing the
+    // words per chunk cost 14 % of its time.
+    __shared__ unsigned slot_tab[7 * 256];
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+        const bool is_x = i < 5;
+        const int s = tid + 256 * (is_x ? i : i - 5);
+        const int pp = s >> 4, qd = s & 7;
+        const int px = 2 * pp + (((s >> 3) ^ pp) & 1);
+        const int cols = is_x ? 34 : 32, C = is_x ? a.Ci : a.Co;
+        const int row = px / cols, col = px - row * cols;
+        slot_tab[i * 256 + tid] = (unsigned)((row * a.W + col) * (C / 4) + qd) | ((unsigned)row << 24) | ((unsigned)col << 26);
+    }
+    // FIRST / LOADS: first table row and wave-wide loads of the region (17 for the input, 8 for the gradient)
+    auto fill = [&](const float* origin, bool plane_ok, bool interior, int y_first, int x_first, auto first_c, auto loads_c, float* dst) {
+        constexpr int FIRST = decltype(first_c)::value, LOADS = decltype(loads_c)::value, N = (LOADS + 3) / 4;
         // Lanes whose pixel lies outside the volume store zeros themselves (a direct load writes lane l's 16 bytes at
         // the wave's base + 16*l, masked-off lanes write nothing).  All zero stores of a region come before its
         // direct loads: a store into a buffer waits for the loads already in flight into it.
+        unsigned e[N];
         unsigned valid = 0u;
 #pragma unroll
-        for (int i = 0; i < 5; ++i) {
+        for (int i = 0; i < N; ++i) {
             const int o = wave + 4 * i;
-            if (o < loads) {
+            if (o < LOADS) {
+                e[i] = slot_tab[(FIRST + i) * 256 + tid];
                 bool ok = plane_ok;
                 if (!interior) {
-                    const int s = t + 256 * i;
-                    const int pp = s >> 4;
-                    const int px = 2 * pp + (((s >> 3) ^ pp) & 1);
-                    const int row = px / cols, col = px - row * cols;
-                    const int yy = y_first + row, xx = x_first + col;
+                    const int yy = y_first + (int)((e[i] >> 24) & 3u), xx = x_first + (int)(e[i] >> 26);
                     ok = ok && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
                 }
                 if (ok) valid |= 1u << i;
@@ -456,15 +466,9 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
             }
         }
 #pragma unroll
-        for (int i = 0; i < 5; ++i) {
+        for (int i = 0; i < N; ++i) {
             const int o = wave + 4 * i;
-            if (o < loads && ((valid >> i) & 1u)) {
-                const int s = t + 256 * i;
-                const int pp = s >> 4, qd = s & 7;
-                const int px = 2 * pp + (((s >> 3) ^ pp) & 1);
-                const int row = px / cols, col = px - row * cols;
-                dma16_off(origin, 4u * (unsigned)((row * a.W + col) * C + 4 * qd), dst + o * 256);
-            }
+            if (o < LOADS && ((valid >> i) & 1u)) dma16_off(origin, (e[i] & 0xffffffu) << 4, dst + o * 256);
         }
     };
 
@@ -567,10 +571,12 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
         const float* const og = a.g + (((vol * a.D) * a.H + y0) * a.W + x0) * a.Co + co0;
         const long long px_plane = (long long)a.H * a.W;
         auto load_x = [&](int tau, float* dst) {
-            fill(ox + tau * px_plane * a.Ci, tau >= 0 && tau < a.D, interior, y0 - 1, x0 - 1, 34, k3XLoads, a.Ci, dst);
+            fill(ox + tau * px_plane * a.Ci, tau >= 0 && tau < a.D, interior, y0 - 1, x0 - 1, std::integral_constant<int, 0>{},
+                 std::integral_constant<int, k3XLoads>{}, dst);
         };
         auto load_g = [&](int tau, float* dst) {
-            fill(og + tau * px_plane * a.Co, tau >= 0 && tau < a.D, interior, y0, x0, 32, k3GLoads, a.Co, dst);
+            fill(og + tau * px_plane * a.Co, tau >= 0 && tau < a.D, interior, y0, x0, std::integral_constant<int, 5>{},
+                 std::integral_constant<int, k3GLoads>{}, dst);
         };
         // the previous chunk ended with a barrier: all buffers are free
         load_x(tau0, X0);
