@@ -660,7 +660,7 @@ __global__ __launch_bounds__(256) void wgrad_wino3_finish_kernel(const float* __
 
 bool wgrad_wino3_applies(const PixDims& d, int Ci, int Co) {
     return d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3 && Ci % 32 == 0 && Co % 32 == 0 &&
-           16.0 * d.W * (Ci > Co ? Ci : Co) < 2.0e9;   // 32-bit lane byte offsets within four image rows
+           (3LL * d.W + 40) * (Ci > Co ? Ci : Co) / 4 < (1LL << 24);   // slot offsets within four image rows: 24 bits of quads
 }
 
 // Workgroups along x and the run of slices one of them walks per column: the choice that minimises
