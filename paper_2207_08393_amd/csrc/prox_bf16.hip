@@ -594,6 +594,282 @@ __global__ __launch_bounds__(256, 2) void conv_bf16_2d_kernel(ConvBf16Args a, in
     }
 }
 
+// ------------------------------------------------------------------ 3x3 layers: weights resident in registers
+// Forward / data gradient of 3x3 layers with up to 128 input channels and a multiple of 128 output channels.  The
+// kernels above re-stage the nine taps' weights for every tile (two thirds of what they pull through L2) and are bound
+// by that traffic and by LDS operand reads.  Here one workgroup of 4 waves owns a CU (one wave per SIMD, the whole
+// 512-register file each): wave w keeps the weights of its 32 output channels - 9 taps x K input channels, 72 MFMA
+// A operands = 288 registers for K = 128 - for the life of the kernel, and only pixels stream: the raw 6 x 34-pixel
+// region of a 4 x 32-pixel tile with all K channels goes global -> LDS by direct loads into one of two buffers (separate
+// LDS objects, tile loop written out for both) while the MFMAs of the previous tile run; all four waves read the
+// same pixel operands.  A wave works on two image rows at a time (two independent accumulator chains; a pixel
+// operand read from LDS feeds up to two MFMAs).  A pixel takes one 16-byte slot more than its channel quads in LDS, so
+// that the 16 lanes a 128-bit read serves together (16 neighbouring pixels, one quad) fall on 16 different bank groups
+// while every operand address is one lane register plus a constant (an XOR swizzle needs a register per operand:
+// 96 of them, which the compiler spills).  Out-of-image quads and the padding slots are loaded from a zero quad.  Epilogue straight from the accumulators: a lane holds 16 channels
+// of its pixel in groups of four, 8-byte stores.
+constexpr int kRwStageStride = 36;   // floats per staged output pixel: 32 channels + 4 (bank spread)
+template <int NKC> struct RwGeom {
+    static constexpr int PIXQ = 2 * NKC;                 // 16-byte quads per pixel (K = 16 * NKC channels)
+    static constexpr int PIXS = PIXQ + 1;                // LDS slots per pixel: one unused slot of padding
+    static constexpr int ROWS = 6, COLS = 34;            // region of a 4 x 32 tile
+    static constexpr int QUADS = ROWS * COLS * PIXS;
+    static constexpr int LOADS = (QUADS + 63) / 64;      // wave-wide direct loads per region
+    static constexpr int PER_LANE = (LOADS + 3) / 4;
+};
+
+// weights as A operands: wt[((((ny*4 + wave)*9 + tap)*NKC + kc)*64 + lane)*8 + s] = W[n = 128*ny + 32*wave + (lane & 31)]
+// [tap][k = 16*kc + 8*(lane >> 5) + s]; one zero quad follows.  Source (n, tap, k) at w[n*sn + tapidx*st + k*sk].
+__global__ __launch_bounds__(256) void weights_image_bf16_rw_kernel(const float* __restrict__ w, long long sn, long long st_, long long sk,
+                                                                    int flip, int K, int Nn, unsigned short* __restrict__ wt) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long total = 9LL * K * Nn;
+    if (i < 8) wt[total + i] = 0;
+    if (i >= total) return;
+    const int nkc = K / 16;
+    const int s = (int)(i & 7), lane = (int)((i >> 3) & 63);
+    long long rest = i >> 9;
+    const int kc = (int)(rest % nkc);
+    rest /= nkc;
+    const int tap = (int)(rest % 9);
+    rest /= 9;
+    const int wave = (int)(rest & 3), ny = (int)(rest >> 2);
+    const int n = 128 * ny + 32 * wave + (lane & 31), k = 16 * kc + 8 * (lane >> 5) + s;
+    wt[i] = f32_to_bf16(w[n * sn + (flip ? 8 - tap : tap) * st_ + k * sk]);
+}
+
+template <bool RELU, int NKC>
+__global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, int bx_n, int by_n, long long n_blocks) {
+    using G = RwGeom<NKC>;
+    constexpr int PIXQ = G::PIXQ, K = 16 * NKC;
+    __shared__ uint4 bufA[G::LOADS * 64];
+    __shared__ uint4 bufB[G::LOADS * 64];
+    __shared__ __attribute__((aligned(16))) float stage_all[4 * 32 * kRwStageStride];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    const int H = a.d.H, W = a.d.W;
+    const XcdRange xr = xcd_range(n_blocks);
+    if (xr.first >= xr.end) return;   // uniform for the workgroup
+    const int ny = blockIdx.y, n0 = 128 * ny + 32 * wave;
+
+    // this wave's weights, for the life of the kernel
+    bf16x8 wr[9][NKC];
+    {
+        const uint4* wp = reinterpret_cast<const uint4*>(a.wt) + ((size_t)(ny * 4 + wave) * 9 * NKC) * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) wr[t][kc] = __builtin_bit_cast(bf16x8, wp[(t * NKC + kc) * 64]);
+    }
+    const unsigned short* zero = a.wt + 9LL * K * a.Nn;
+
+    // direct-load slots of this lane: slot s = tid + 256*i is channel quad s % PIXS (the last one: padding) of region
+    // pixel s / PIXS; element offset from the region origin (pixel (y0-1, x0-1))
+    constexpr int PIXS = G::PIXS;
+    unsigned s_off[G::PER_LANE];
+#pragma unroll
+    for (int i = 0; i < G::PER_LANE; ++i) {
+        const int s = tid + 256 * i;
+        const int px = s / PIXS, pos = s - px * PIXS;
+        const int row = px / G::COLS, col = px - row * G::COLS;
+        s_off[i] = (s < G::QUADS && pos < PIXQ) ? (unsigned)((row * W + col) * K + 8 * pos) : ~0u;
+    }
+    struct Block {
+        int x0, y0;
+        long long img;
+    };
+    auto setup = [&](long long item) {
+        Block b;
+        const int bx = (int)(item % bx_n);
+        const long long rest = item / bx_n;
+        const int by = (int)(rest % by_n);
+        b.img = rest / by_n;
+        b.x0 = bx * 32;
+        b.y0 = by * 4;
+        return b;
+    };
+    auto issue = [&](const Block& b, uint4* dst) {
+        const bool interior = b.y0 >= 1 && b.y0 + 4 < H && b.x0 >= 1 && b.x0 + 32 < W;   // uniform
+        const unsigned short* base = a.in + ((b.img * H + b.y0 - 1) * W + b.x0 - 1) * K;   // only dereferenced inside the image
+        int t = tid;
+        asm volatile("" : "+v"(t));   // the slots' pixels are recomputed per tile rather than kept in registers
+#pragma unroll
+        for (int i = 0; i < G::PER_LANE; ++i) {
+            const int o = wave + 4 * i;
+            if (o < G::LOADS) {
+                const unsigned short* p = s_off[i] != ~0u ? base + s_off[i] : zero;
+                if (!interior) {
+                    const int s = t + 256 * i;
+                    const int px = s / PIXS;
+                    const int row = px / G::COLS, col = px - row * G::COLS;
+                    const int yy = b.y0 - 1 + row, xx = b.x0 - 1 + col;
+                    const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
+                    p = ok ? p : zero;
+                }
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                                 (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
+            }
+        }
+    };
+
+    floatx16 acc[4];   // the tile's four image rows
+    const int lane_q = m * PIXS + h;   // this lane's pixel column and half of a 16-channel block, in 16-byte slots
+    // rows 2p and 2p + 1 of the tile: pixel operand (region row 2p + rho, column m + dx, channels 16 kc + 8 h ..) feeds
+    // tap (rho, dx) of the upper row and tap (rho - 1, dx) of the lower one
+    auto compute = [&](const uint4* buf, int p) __attribute__((always_inline)) {
+        // groups of four operands (one tap column dx of one 16-channel block kc, the pair's four region rows): the reads of
+        // a group are issued before the six MFMAs of the group ahead of it
+        uint4 bq[2][4];
+        auto read_group = [&](int g, uint4* b) {
+            const int kc = g / 3, dx = g - 3 * kc;
+#pragma unroll
+            for (int rho = 0; rho < 4; ++rho) {
+                b[rho] = buf[lane_q + ((2 * p + rho) * G::COLS + dx) * PIXS + 2 * kc];
+                if (RELU) {
+                    b[rho].x = relu_bf16x2(b[rho].x); b[rho].y = relu_bf16x2(b[rho].y);
+                    b[rho].z = relu_bf16x2(b[rho].z); b[rho].w = relu_bf16x2(b[rho].w);
+                }
+            }
+        };
+        read_group(0, bq[0]);
+#pragma unroll
+        for (int g = 0; g < 3 * NKC; ++g) {
+            const int kc = g / 3, dx = g - 3 * kc;
+            if (g + 1 < 3 * NKC) read_group(g + 1, bq[(g + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int rho = 0; rho < 4; ++rho) {
+                const bf16x8 bv = __builtin_bit_cast(bf16x8, bq[g & 1][rho]);
+                if (rho <= 2) acc[2 * p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[rho * 3 + dx][kc], bv, acc[2 * p], 0, 0, 0);
+                if (rho >= 1) acc[2 * p + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[(rho - 1) * 3 + dx][kc], bv, acc[2 * p + 1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // Accumulator r of lane (m, h): output channel n0 + 8*(r/4) + 4*h + r%4 of pixel (row, x0 + m).  Stored from there a
+    // wave store would touch 32 separate 16-byte pieces, and the L2 takes as long over those as the MFMAs over the tile;
+    // so the wave turns its 32 pixels x 32 channels around in its own LDS rows (LDS operations of one wave execute in
+    // order: no barrier) and a lane finishes 8 channels of a pixel: 16-byte stores, 64 contiguous bytes per pixel.
+    float* stage = stage_all + wave * 32 * kRwStageStride;
+    const int e_px = lane >> 2, e_c8 = lane & 3;
+    auto epilogue = [&](const Block& b, int j) {
+        const int y = b.y0 + j;
+        if (y >= H) return;   // uniform
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<float4*>(stage + m * kRwStageStride + 8 * g + 4 * h) =
+                make_float4(acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]);
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int px = e_px + 16 * it, x = b.x0 + px;
+            const float4 v0 = *reinterpret_cast<const float4*>(stage + px * kRwStageStride + 8 * e_c8);
+            const float4 v1 = *reinterpret_cast<const float4*>(stage + px * kRwStageStride + 8 * e_c8 + 4);
+            if (x < W) {
+                const int co = n0 + 8 * e_c8;
+                const long long o = ((b.img * H + y) * W + x) * a.Nn + co;
+                float xv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                if (a.bias) {
+                    const float4 b0 = *reinterpret_cast<const float4*>(a.bias + co), b1 = *reinterpret_cast<const float4*>(a.bias + co + 4);
+                    xv[0] += b0.x; xv[1] += b0.y; xv[2] += b0.z; xv[3] += b0.w;
+                    xv[4] += b1.x; xv[5] += b1.y; xv[6] += b1.z; xv[7] += b1.w;
+                }
+                if (a.relu_out) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) xv[e] = fmaxf(xv[e], 0.f);
+                }
+                uint4 rf = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);   // 1.0 in every half
+                if (a.mask_ref) rf = *reinterpret_cast<const uint4*>(a.mask_ref + o);
+                const unsigned rw[4] = {rf.x, rf.y, rf.z, rf.w};
+                bool pos[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pos[e] = bf16_to_f32((unsigned short)(rw[e >> 1] >> (16 * (e & 1)))) > 0.f;
+                if (a.mask_acc) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) xv[e] = pos[e] ? xv[e] : 0.f;
+                }
+                if (a.add) {
+                    const uint4 av = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned short*>(a.add) + o);
+                    const unsigned aw[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        xv[e] += (a.mask_add && !pos[e]) ? 0.f : bf16_to_f32((unsigned short)(aw[e >> 1] >> (16 * (e & 1))));
+                }
+                *reinterpret_cast<uint4*>(reinterpret_cast<unsigned short*>(a.out) + o) =
+                    make_uint4(pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]), pack_bf16x2(xv[4], xv[5]), pack_bf16x2(xv[6], xv[7]));
+            }
+        }
+    };
+    auto tile = [&](const Block& cur, const Block& nxt, bool has_next, const uint4* buf, uint4* other) __attribute__((always_inline)) {
+        if (has_next) issue(nxt, other);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+        compute(buf, 0);
+        compute(buf, 1);
+        // The wait for the next tile's direct loads comes before the epilogue: the counter it waits on also counts
+        // stores, and with one wave per SIMD nothing else would run while this tile's stores drain.  They drain under
+        // the next tile's MFMAs instead.
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) epilogue(cur, j);
+    };
+
+    Block cur = setup(xr.first);
+    issue(cur, bufA);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (long long item = xr.first; item < xr.end; item += 2 * xr.stride) {
+        const bool n1 = item + xr.stride < xr.end;
+        const Block b1 = setup(n1 ? item + xr.stride : item);
+        tile(cur, b1, n1, bufA, bufB);
+        if (!n1) break;
+        const bool n2 = item + 2 * xr.stride < xr.end;
+        const Block b2 = setup(n2 ? item + 2 * xr.stride : item);
+        tile(b1, b2, n2, bufB, bufA);
+        cur = b2;
+    }
+}
+
+static bool conv_bf16_rw_applies(const ConvBf16Args& a) {
+    // byte offsets inside a region are 32 bits in the kernel
+    return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && (a.K == 128 || a.K == 64) && a.Nn % 128 == 0 && !a.out_f32 &&
+           12.0 * a.d.W * a.K < 2.0e9;
+}
+
+static hipError_t launch_conv_bf16_rw(ConvBf16Args a, const float* w, long long sn, long long st_, long long sk, int flip,
+                                      unsigned short* wt_scratch, hipStream_t st) {
+    {
+        const long long total = 9LL * a.K * a.Nn;
+        KernelScope ks("weights_image_bf16", 0.0, 6.0 * (double)total, st);
+        hipLaunchKernelGGL(weights_image_bf16_rw_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w, sn, st_, sk, flip,
+                           a.K, a.Nn, wt_scratch);
+    }
+    a.wt = wt_scratch;
+    a.bits_in = nullptr;
+    a.bits_out = nullptr;
+    const int bx_n = (a.d.W + 31) / 32, by_n = (a.d.H + 3) / 4;
+    const long long n_img = a.d.Q / ((long long)a.d.H * a.d.W);
+    const long long n_blocks = n_img * bx_n * by_n;
+    const long long cap = 256;   // one workgroup per CU
+    const long long gx = ((n_blocks < cap ? n_blocks : cap) + 7) / 8 * 8;
+    dim3 grid((unsigned)gx, (unsigned)(a.Nn / 128));
+    char name[56];
+    snprintf(name, sizeof(name), "conv_bf16_%s_%dto%d_t9", flip ? "dgrad" : "fwd", a.K, a.Nn);
+    KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * 9, 2.0 * (double)a.d.Q * (a.K + a.Nn), st);
+    if (a.K == 128) {
+        if (a.relu_in) hipLaunchKernelGGL((conv_bf16_rw_kernel<true, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+        else hipLaunchKernelGGL((conv_bf16_rw_kernel<false, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+    } else {
+        if (a.relu_in) hipLaunchKernelGGL((conv_bf16_rw_kernel<true, 4>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+        else hipLaunchKernelGGL((conv_bf16_rw_kernel<false, 4>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+    }
+    return hipGetLastError();
+}
+
 static bool conv_bf16_2d_applies(const ConvBf16Args& a) {
     // an even number of 16-channel chunks; byte offsets into the input tensor are 32 bits in the kernel
     return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && a.K % 32 == 0 && a.Nn % 64 == 0 && !a.out_f32 &&
@@ -606,7 +882,7 @@ static bool bf16_2d_enabled() { return !(kernel_policy() & GLEAM_POLICY_NO_BF16_
 bool conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn) {
     ConvBf16Args a{};
     a.d = d; a.K = K; a.Nn = Nn;
-    return bf16_2d_enabled() && conv_bf16_2d_applies(a);
+    return bf16_2d_enabled() && conv_bf16_2d_applies(a) && !conv_bf16_rw_applies(a);
 }
 
 size_t conv_bf16_sign_words(const PixDims& d, int Nn) {   // four words per thread, block and group of 64 channels
@@ -640,6 +916,7 @@ static hipError_t launch_conv_bf16_2d(ConvBf16Args a, const float* w, long long 
 hipError_t launch_conv_bf16(const ConvBf16Args& a_in, const float* w, long long sn, long long st_, long long sk, int flip,
                             unsigned short* wt_scratch, hipStream_t stream) {
     ConvBf16Args a = a_in;
+    if (bf16_2d_enabled() && conv_bf16_rw_applies(a)) return launch_conv_bf16_rw(a, w, sn, st_, sk, flip, wt_scratch, stream);
     if (bf16_2d_enabled() && conv_bf16_2d_applies(a)) return launch_conv_bf16_2d(a, w, sn, st_, sk, flip, wt_scratch, stream);
     const int taps = a.d.kt * a.d.kd * a.d.kh * a.d.kw;
     const int nb = bf_nb(a.Nn);

@@ -104,8 +104,12 @@ __device__ __forceinline__ unsigned short f32_to_bf16(float f) {   // round to n
     return (unsigned short)(u >> 16);
 }
 __device__ __forceinline__ float bf16_to_f32(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
+// two values at once: gfx950's packed conversion (v_cvt_pk_bf16_f32, round to nearest even like f32_to_bf16)
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
-    return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+    const float2v f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2v));
 }
 // max(x, 0) on two packed bf16 values: a negative bf16 has the sign bit of its 16-bit pattern set, so a
 // packed signed 16-bit max with 0 is ReLU (one instruction)
