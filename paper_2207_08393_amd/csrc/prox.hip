@@ -1864,9 +1864,11 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
             db.Q = da.Q = plan.Q;
             db.kt = below.kt; db.kd = below.kd; db.kh = below.kh; db.kw = below.kw;
             da.kt = above.kt; da.kd = above.kd; da.kh = above.kh; da.kw = above.kw;
-            if (!conv_bf16_takes_sign_words(db, below.cin, below.cout) || !conv_bf16_takes_sign_words(da, above.cout, above.cin)) continue;
+            // the launch that writes the words and the one that reads them must be the same kernel (same tile geometry)
+            const int variant = conv_bf16_takes_sign_words(db, below.cin, below.cout);
+            if (variant == 0 || variant != conv_bf16_takes_sign_words(da, above.cout, above.cin)) continue;
             plan.sign_off[l] = off;
-            off += align256(conv_bf16_sign_words(db, below.cout) * sizeof(unsigned));
+            off += align256(conv_bf16_sign_words(db, below.cout, variant) * sizeof(unsigned));
         }
     if (p.dtype == 0)
         for (int l = 1; l < L; ++l) {

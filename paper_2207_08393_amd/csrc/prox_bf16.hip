@@ -677,10 +677,11 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
     }
     struct Block {
         int x0, y0;
-        long long img;
+        long long img, item;
     };
     auto setup = [&](long long item) {
         Block b;
+        b.item = item;
         const int bx = (int)(item % bx_n);
         const long long rest = item / bx_n;
         const int by = (int)(rest % by_n);
@@ -715,11 +716,122 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
 
     floatx16 acc[4];   // the tile's four image rows
     const int lane_q = m * PIXS + h;   // this lane's pixel column and half of a 16-channel block, in 16-byte slots
-    // rows 2p and 2p + 1 of the tile: pixel operand (region row 2p + rho, column m + dx, channels 16 kc + 8 h ..) feeds
-    // tap (rho, dx) of the upper row and tap (rho - 1, dx) of the lower one
-    auto compute = [&](const uint4* buf, int p) __attribute__((always_inline)) {
-        // groups of four operands (one tap column dx of one 16-channel block kc, the pair's four region rows): the reads of
-        // a group are issued before the six MFMAs of the group ahead of it
+
+    // ---- epilogue, cut into parts that are interleaved with the MFMAs of the next image-row pair.  With one wave per
+    // SIMD nothing else hides its instructions: run after the MFMAs it took a third of the kernel's time.  It is free of
+    // branches, so that the compiler can schedule its parts between the MFMAs: pixels outside the image (and a tile that
+    // does not exist) get a buffer offset past the end, which the hardware drops on stores and answers with zeros on
+    // loads, and operands the call does not have are read through an empty buffer.
+    // Accumulator r of lane (m, h): output channel n0 + 8*(r/4) + 4*h + r%4 of pixel (row, x0 + m).  Stored from there a
+    // wave store would touch 32 separate 16-byte pieces (the L2 takes as long over those as the MFMAs over the tile), so
+    // the wave turns its 32 pixels x 32 channels around in its own LDS rows (LDS operations of one wave execute in
+    // order: no barrier) and a lane finishes 8 channels of a pixel: 16-byte stores, 64 contiguous bytes per pixel.
+    // ReLU mask as sign bits: bit 16*(j & 1) + 8*it + e of word j / 2 of a thread says whether the value of image row
+    // j, pass it, channel e of its piece is positive.  The forward launch that produces an activation writes the words,
+    // the data-gradient launch into the same tensor (same geometry, so the same thread holds the same values) reads
+    // them instead of the activation.
+    float* stage = stage_all + wave * 32 * kRwStageStride;
+    const int e_px = lane >> 2, e_c8 = lane & 3;
+    const unsigned out_bytes = (unsigned)(2 * a.d.Q * a.Nn);   // the launcher checks that this fits 32 bits
+    const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, out_bytes, 0x00020000);
+    const bool use_bits = a.bits_in != nullptr;
+    const __amdgpu_buffer_rsrc_t r_mask =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(a.mask_ref ? (const void*)a.mask_ref : (const void*)a.out), 0,
+                                          (a.mask_ref && !use_bits) ? out_bytes : 0u, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_add =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(a.add ? a.add : (const void*)a.out), 0, a.add ? out_bytes : 0u, 0x00020000);
+    const unsigned word_bytes = (unsigned)(n_blocks * (a.Nn / 128) * 256 * 8);
+    const __amdgpu_buffer_rsrc_t r_bin =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(use_bits ? (const void*)a.bits_in : (const void*)a.out), 0, use_bits ? word_bytes : 0u, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_bout =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(a.bits_out ? (void*)a.bits_out : a.out), 0, a.bits_out ? word_bytes : 0u, 0x00020000);
+    float bias_r[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bias_r[e] = a.bias ? a.bias[n0 + 8 * e_c8 + e] : 0.f;
+    const float relu_floor = a.relu_out ? 0.f : -__builtin_huge_valf();
+    const bool has_mask = a.mask_ref != nullptr;   // with or without sign words
+    const bool mask_acc = a.mask_acc != 0, mask_add = a.mask_add != 0;
+
+    typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+    typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+    struct Slice {   // one piece (image row j, pass it) on its way out
+        unsigned off;
+        float xv[8];
+        uint4v rf, av;
+        unsigned posbits;
+    };
+    Slice sl;
+    unsigned sign_in_w = 0u, sign_out_w = 0u;
+    // part 0..5 of piece (j, it) of block b
+    auto epi_part = [&](const Block& b, int j, int it, int part) __attribute__((always_inline)) {
+        if (part == 0) {
+            if (it == 0) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4*>(stage + m * kRwStageStride + 8 * g + 4 * h) =
+                        make_float4(acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]);
+            }
+            const int px = e_px + 16 * it, x = b.x0 + px, y = b.y0 + j;
+            const bool ok = b.item >= 0 && y < H && x < W;
+            sl.off = ok ? ((unsigned)(b.img * H + y) * (unsigned)W + (unsigned)x) * (unsigned)(2 * a.Nn) + 2u * (unsigned)(n0 + 8 * e_c8) : ~0u;
+            sl.rf = __builtin_amdgcn_raw_buffer_load_b128(r_mask, sl.off, 0, 0);
+            sl.av = __builtin_amdgcn_raw_buffer_load_b128(r_add, sl.off, 0, 0);
+        } else if (part == 1) {
+            const int px = e_px + 16 * it;
+            const float4 v0 = *reinterpret_cast<const float4*>(stage + px * kRwStageStride + 8 * e_c8);
+            const float4 v1 = *reinterpret_cast<const float4*>(stage + px * kRwStageStride + 8 * e_c8 + 4);
+            const float t[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sl.xv[e] = fmaxf(t[e] + bias_r[e], relu_floor);
+        } else if (part == 2) {
+            // which values pass the ReLU mask: all (no mask), the sign words, or the mask tensor's own signs
+            unsigned bits = 0u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned hv = (sl.rf[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                bits |= (hv - 1u < 0x7fffu ? 1u : 0u) << e;
+            }
+            const unsigned from_words = (sign_in_w >> (16 * (j & 1) + 8 * it)) & 0xffu;
+            sl.posbits = !has_mask ? 0xffu : (use_bits ? from_words : bits);
+        } else if (part == 3) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool pos = (sl.posbits >> e) & 1u;
+                float x = sl.xv[e];
+                x = (mask_acc && !pos) ? 0.f : x;
+                const float ad = __uint_as_float((sl.av[e >> 1] >> (16 * (e & 1))) << 16);
+                x += (mask_add && !pos) ? 0.f : ad;
+                sl.xv[e] = x;
+            }
+        } else if (part == 4) {
+            uint4v packed;
+            packed[0] = pack_bf16x2(sl.xv[0], sl.xv[1]); packed[1] = pack_bf16x2(sl.xv[2], sl.xv[3]);
+            packed[2] = pack_bf16x2(sl.xv[4], sl.xv[5]); packed[3] = pack_bf16x2(sl.xv[6], sl.xv[7]);
+            __builtin_amdgcn_raw_buffer_store_b128(packed, r_out, sl.off, 0, 0);
+            sl.rf = packed;   // kept for the sign bits
+        } else {
+            // the sign of what was stored, i.e. of the rounded value: 0x0001 .. 0x7fff; nothing for a dropped store
+            unsigned bits = 0u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned hv = (sl.rf[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                bits |= (hv - 1u < 0x7fffu ? 1u : 0u) << e;
+            }
+            bits = sl.off != ~0u ? bits : 0u;
+            sign_out_w |= bits << (16 * (j & 1) + 8 * it);
+        }
+    };
+    // the sign words of pair q (image rows 2q, 2q + 1) of block b
+    auto word_off = [&](const Block& b, int q) -> unsigned {
+        return b.item >= 0 ? (unsigned)((((long long)ny * n_blocks + b.item) * 256 + tid) * 8 + 4 * q) : ~0u;
+    };
+
+    // MFMAs of image rows 2p and 2p + 1 of the tile in `buf`, with the epilogue of rows 2q, 2q + 1 of block eb between them.
+    // Pixel operand (region row 2p + rho, column m + dx, channels 16 kc + 8 h ..) feeds tap (rho, dx) of the upper row and
+    // tap (rho - 1, dx) of the lower one; operands come in groups of four (one dx of one 16-channel block), the reads of
+    // a group are issued before the six MFMAs of the group ahead of it, and every group carries one part of the epilogue
+    // (4 pieces x 6 parts = 24 groups).
+    auto compute = [&](const uint4* buf, int p, const Block& eb, int q) __attribute__((always_inline)) {
         uint4 bq[2][4];
         auto read_group = [&](int g, uint4* b) {
             const int kc = g / 3, dx = g - 3 * kc;
@@ -732,112 +844,89 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
                 }
             }
         };
+        sign_in_w = __builtin_amdgcn_raw_buffer_load_b32(r_bin, word_off(eb, q), 0, 0);
+        sign_out_w = 0u;
         read_group(0, bq[0]);
 #pragma unroll
         for (int g = 0; g < 3 * NKC; ++g) {
             const int kc = g / 3, dx = g - 3 * kc;
             if (g + 1 < 3 * NKC) read_group(g + 1, bq[(g + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
+            epi_part(eb, 2 * q + g / 12, (g / 6) & 1, g % 6);
 #pragma unroll
             for (int rho = 0; rho < 4; ++rho) {
                 const bf16x8 bv = __builtin_bit_cast(bf16x8, bq[g & 1][rho]);
-                if (rho <= 2) acc[2 * p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[rho * 3 + dx][kc], bv, acc[2 * p], 0, 0, 0);
-                if (rho >= 1) acc[2 * p + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[(rho - 1) * 3 + dx][kc], bv, acc[2 * p + 1], 0, 0, 0);
+                if (rho <= 2) {
+                    if (g == 0 && rho == 0) {
+                        floatx16 z;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                        acc[2 * p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[rho * 3 + dx][kc], bv, z, 0, 0, 0);
+                    } else {
+                        acc[2 * p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[rho * 3 + dx][kc], bv, acc[2 * p], 0, 0, 0);
+                    }
+                }
+                if (rho >= 1) {
+                    if (g == 0 && rho == 1) {
+                        floatx16 z;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                        acc[2 * p + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[(rho - 1) * 3 + dx][kc], bv, z, 0, 0, 0);
+                    } else {
+                        acc[2 * p + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[(rho - 1) * 3 + dx][kc], bv, acc[2 * p + 1], 0, 0, 0);
+                    }
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        __builtin_amdgcn_raw_buffer_store_b32(sign_out_w, r_bout, word_off(eb, q), 0, 0);
     };
-    // Accumulator r of lane (m, h): output channel n0 + 8*(r/4) + 4*h + r%4 of pixel (row, x0 + m).  Stored from there a
-    // wave store would touch 32 separate 16-byte pieces, and the L2 takes as long over those as the MFMAs over the tile;
-    // so the wave turns its 32 pixels x 32 channels around in its own LDS rows (LDS operations of one wave execute in
-    // order: no barrier) and a lane finishes 8 channels of a pixel: 16-byte stores, 64 contiguous bytes per pixel.
-    float* stage = stage_all + wave * 32 * kRwStageStride;
-    const int e_px = lane >> 2, e_c8 = lane & 3;
-    auto epilogue = [&](const Block& b, int j) {
-        const int y = b.y0 + j;
-        if (y >= H) return;   // uniform
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-            *reinterpret_cast<float4*>(stage + m * kRwStageStride + 8 * g + 4 * h) =
-                make_float4(acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]);
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int px = e_px + 16 * it, x = b.x0 + px;
-            const float4 v0 = *reinterpret_cast<const float4*>(stage + px * kRwStageStride + 8 * e_c8);
-            const float4 v1 = *reinterpret_cast<const float4*>(stage + px * kRwStageStride + 8 * e_c8 + 4);
-            if (x < W) {
-                const int co = n0 + 8 * e_c8;
-                const long long o = ((b.img * H + y) * W + x) * a.Nn + co;
-                float xv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-                if (a.bias) {
-                    const float4 b0 = *reinterpret_cast<const float4*>(a.bias + co), b1 = *reinterpret_cast<const float4*>(a.bias + co + 4);
-                    xv[0] += b0.x; xv[1] += b0.y; xv[2] += b0.z; xv[3] += b0.w;
-                    xv[4] += b1.x; xv[5] += b1.y; xv[6] += b1.z; xv[7] += b1.w;
-                }
-                if (a.relu_out) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) xv[e] = fmaxf(xv[e], 0.f);
-                }
-                uint4 rf = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);   // 1.0 in every half
-                if (a.mask_ref) rf = *reinterpret_cast<const uint4*>(a.mask_ref + o);
-                const unsigned rw[4] = {rf.x, rf.y, rf.z, rf.w};
-                bool pos[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pos[e] = bf16_to_f32((unsigned short)(rw[e >> 1] >> (16 * (e & 1)))) > 0.f;
-                if (a.mask_acc) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) xv[e] = pos[e] ? xv[e] : 0.f;
-                }
-                if (a.add) {
-                    const uint4 av = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned short*>(a.add) + o);
-                    const unsigned aw[4] = {av.x, av.y, av.z, av.w};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        xv[e] += (a.mask_add && !pos[e]) ? 0.f : bf16_to_f32((unsigned short)(aw[e >> 1] >> (16 * (e & 1))));
-                }
-                *reinterpret_cast<uint4*>(reinterpret_cast<unsigned short*>(a.out) + o) =
-                    make_uint4(pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]), pack_bf16x2(xv[4], xv[5]), pack_bf16x2(xv[6], xv[7]));
-            }
-        }
-    };
-    auto tile = [&](const Block& cur, const Block& nxt, bool has_next, const uint4* buf, uint4* other) __attribute__((always_inline)) {
+    static_assert(NKC == 8, "24 operand groups per row pair carry the 24 epilogue parts");
+
+    // One tile: rows 0, 1 are computed while rows 2, 3 of the previous tile leave, then rows 2, 3 while rows 0, 1 leave.
+    auto tile = [&](const Block& cur, const Block& prev, const Block& nxt, bool has_next, const uint4* buf, uint4* other)
+                    __attribute__((always_inline)) {
         if (has_next) issue(nxt, other);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-        compute(buf, 0);
-        compute(buf, 1);
-        // The wait for the next tile's direct loads comes before the epilogue: the counter it waits on also counts
-        // stores, and with one wave per SIMD nothing else would run while this tile's stores drain.  They drain under
-        // the next tile's MFMAs instead.
+        compute(buf, 0, prev, 1);
+        compute(buf, 1, cur, 0);
+        // (the counter waited on also counts this tile's stores; they have had the tile to drain)
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 4; ++j) epilogue(cur, j);
     };
 
-    Block cur = setup(xr.first);
+    Block none;
+    none.x0 = none.y0 = 0; none.img = 0; none.item = -1;
+    Block cur = setup(xr.first), prev = none;
     issue(cur, bufA);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     for (long long item = xr.first; item < xr.end; item += 2 * xr.stride) {
         const bool n1 = item + xr.stride < xr.end;
         const Block b1 = setup(n1 ? item + xr.stride : item);
-        tile(cur, b1, n1, bufA, bufB);
+        tile(cur, prev, b1, n1, bufA, bufB);
+        prev = cur;
         if (!n1) break;
         const bool n2 = item + 2 * xr.stride < xr.end;
         const Block b2 = setup(n2 ? item + 2 * xr.stride : item);
-        tile(b1, b2, n2, bufB, bufA);
+        tile(b1, prev, b2, n2, bufB, bufA);
+        prev = b1;
         cur = b2;
     }
+    // rows 2, 3 of the last tile
+    sign_in_w = __builtin_amdgcn_raw_buffer_load_b32(r_bin, word_off(prev, 1), 0, 0);
+    sign_out_w = 0u;
+#pragma unroll
+    for (int s_ = 0; s_ < 4; ++s_)
+#pragma unroll
+        for (int part = 0; part < 6; ++part) epi_part(prev, 2 + s_ / 2, s_ & 1, part);
+    __builtin_amdgcn_raw_buffer_store_b32(sign_out_w, r_bout, word_off(prev, 1), 0, 0);
 }
 
 static bool conv_bf16_rw_applies(const ConvBf16Args& a) {
     // byte offsets inside a region are 32 bits in the kernel
-    return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && (a.K == 128 || a.K == 64) && a.Nn % 128 == 0 && !a.out_f32 &&
-           12.0 * a.d.W * a.K < 2.0e9;
+    return a.d.kt == 1 && a.d.kd == 1 && a.d.kh == 3 && a.d.kw == 3 && a.K == 128 && a.Nn % 128 == 0 && !a.out_f32 &&
+           12.0 * a.d.W * a.K < 2.0e9 && 2.0 * (double)a.d.Q * a.Nn < 4.0e9;
 }
 
 static hipError_t launch_conv_bf16_rw(ConvBf16Args a, const float* w, long long sn, long long st_, long long sk, int flip,
@@ -849,8 +938,6 @@ static hipError_t launch_conv_bf16_rw(ConvBf16Args a, const float* w, long long 
                            a.K, a.Nn, wt_scratch);
     }
     a.wt = wt_scratch;
-    a.bits_in = nullptr;
-    a.bits_out = nullptr;
     const int bx_n = (a.d.W + 31) / 32, by_n = (a.d.H + 3) / 4;
     const long long n_img = a.d.Q / ((long long)a.d.H * a.d.W);
     const long long n_blocks = n_img * bx_n * by_n;
@@ -860,13 +947,8 @@ static hipError_t launch_conv_bf16_rw(ConvBf16Args a, const float* w, long long 
     char name[56];
     snprintf(name, sizeof(name), "conv_bf16_%s_%dto%d_t9", flip ? "dgrad" : "fwd", a.K, a.Nn);
     KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * 9, 2.0 * (double)a.d.Q * (a.K + a.Nn), st);
-    if (a.K == 128) {
-        if (a.relu_in) hipLaunchKernelGGL((conv_bf16_rw_kernel<true, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
-        else hipLaunchKernelGGL((conv_bf16_rw_kernel<false, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
-    } else {
-        if (a.relu_in) hipLaunchKernelGGL((conv_bf16_rw_kernel<true, 4>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
-        else hipLaunchKernelGGL((conv_bf16_rw_kernel<false, 4>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
-    }
+    if (a.relu_in) hipLaunchKernelGGL((conv_bf16_rw_kernel<true, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+    else hipLaunchKernelGGL((conv_bf16_rw_kernel<false, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
     return hipGetLastError();
 }
 
@@ -879,14 +961,19 @@ static bool conv_bf16_2d_applies(const ConvBf16Args& a) {
 // GLEAM_POLICY_NO_BF16_2D keeps the flattened-pixel kernel
 static bool bf16_2d_enabled() { return !(kernel_policy() & GLEAM_POLICY_NO_BF16_2D); }
 
-bool conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn) {
+int conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn) {
     ConvBf16Args a{};
     a.d = d; a.K = K; a.Nn = Nn;
-    return bf16_2d_enabled() && conv_bf16_2d_applies(a) && !conv_bf16_rw_applies(a);
+    if (!bf16_2d_enabled()) return 0;
+    if (conv_bf16_rw_applies(a)) return 2;
+    return conv_bf16_2d_applies(a) ? 1 : 0;
 }
 
-size_t conv_bf16_sign_words(const PixDims& d, int Nn) {   // four words per thread, block and group of 64 channels
+size_t conv_bf16_sign_words(const PixDims& d, int Nn, int variant) {
     const size_t n_img = (size_t)d.Q / ((size_t)d.H * d.W);
+    if (variant == 2)   // two words per thread, 4 x 32 tile and group of 128 channels
+        return n_img * ((d.W + 31) / 32) * ((d.H + 3) / 4) * 256 * 2 * (size_t)(Nn / 128);
+    // four words per thread, block and group of 64 channels
     return n_img * ((d.W + 31) / 32) * ((d.H + kB2TileRows - 1) / kB2TileRows) * 256 * 4 * (size_t)(Nn / 64);
 }
 

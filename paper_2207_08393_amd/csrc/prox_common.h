@@ -287,8 +287,9 @@ struct ConvBf16Args {
 };
 // Whether a (K -> Nn) layer with bfloat16 output runs on the two-dimensional-tile kernel, whose launches can leave
 // and take ReLU masks as sign words, and how many 32-bit words those are for a [pixels][Nn] tensor.
-bool conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn);
-size_t conv_bf16_sign_words(const PixDims& d, int Nn);
+// 0: neither; 1: the two-dimensional-tile kernel; 2: the kernel with register-resident weights.
+int conv_bf16_takes_sign_words(const PixDims& d, int K, int Nn);
+size_t conv_bf16_sign_words(const PixDims& d, int Nn, int variant);
 hipError_t launch_conv_bf16(const ConvBf16Args& a, const float* w, long long sn, long long st, long long sk, int flip,
                             unsigned short* wt_scratch, hipStream_t stream);
 size_t conv_bf16_wimg_elems(int K, int Nn, int taps);

@@ -24,10 +24,10 @@ def elementwise_factor(n):
     return max(1.0, float(np.sqrt(2.0 * np.log(2.0 * max(int(n), 1)))))
 
 
-def assert_close(got, ref, tol, what):
+def assert_close(got, ref, tol, what, sup=None):
     """Relative L2 <= tol (the stated tolerance), and every element within elementwise_factor(n) * tol * max|ref| of
-    its reference, so that a wrong value cannot hide behind the norm of the rest.  A reference that is exactly zero
-    must be matched exactly."""
+    its reference, so that a wrong value cannot hide behind the norm of the rest (`sup`, when given, replaces that
+    element-wise bound, as a fraction of max|ref|).  A reference that is exactly zero must be matched exactly."""
     got = np.asarray(got)
     ref = np.asarray(ref)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
@@ -39,7 +39,7 @@ def assert_close(got, ref, tol, what):
     err = rel_l2(got, ref)
     worst = float(np.abs(got.astype(ref.dtype if np.iscomplexobj(ref) else np.float64) - ref).max()) / scale
     assert err <= tol, (what, "rel-L2", err, "tol", tol)
-    bound = elementwise_factor(ref.size) * tol
+    bound = elementwise_factor(ref.size) * tol if sup is None else sup
     assert worst <= bound, (what, "max |d| / max |ref|", worst, "bound", bound)
     return err
 
@@ -77,6 +77,6 @@ def assert_grad_close(prox, got, ref, tol, what="grad_theta", exact=None, share=
     return errs
 
 
-def assert_image_close(got, ref, tol, what="x_out"):
+def assert_image_close(got, ref, tol, what="x_out", sup=None):
     """Per batch sample (axis 0)."""
-    return [assert_close(got[b], ref[b], tol, f"{what} sample {b}") for b in range(ref.shape[0])]
+    return [assert_close(got[b], ref[b], tol, f"{what} sample {b}", sup) for b in range(ref.shape[0])]
