@@ -638,7 +638,9 @@ __global__ __launch_bounds__(256) void weights_image_bf16_rw_kernel(const float*
     wt[i] = f32_to_bf16(w[n * sn + (flip ? 8 - tap : tap) * st_ + k * sk]);
 }
 
-template <bool RELU, int NKC>
+// VAR: 0 forward; 1 forward that leaves the ReLU mask of its output as lane masks; 2 data gradient with the ReLU mask
+// taken from the activation; 3 data gradient with the mask taken from lane masks.
+template <bool RELU, int NKC, int VAR>
 __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, int bx_n, int by_n, long long n_blocks) {
     using G = RwGeom<NKC>;
     constexpr int PIXQ = G::PIXQ, K = 16 * NKC;
@@ -673,7 +675,7 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
         const int s = tid + 256 * i;
         const int px = s / PIXS, pos = s - px * PIXS;
         const int row = px / G::COLS, col = px - row * G::COLS;
-        s_off[i] = (s < G::QUADS && pos < PIXQ) ? (unsigned)((row * W + col) * K + 8 * pos) : ~0u;
+        s_off[i] = (s < G::QUADS && pos < PIXQ) ? (unsigned)((row * W + col) * K + 8 * pos) : 0u;
     }
     struct Block {
         int x0, y0;
@@ -693,23 +695,31 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
     auto issue = [&](const Block& b, uint4* dst) {
         const bool interior = b.y0 >= 1 && b.y0 + 4 < H && b.x0 >= 1 && b.x0 + 32 < W;   // uniform
         const unsigned short* base = a.in + ((b.img * H + b.y0 - 1) * W + b.x0 - 1) * K;   // only dereferenced inside the image
-        int t = tid;
-        asm volatile("" : "+v"(t));   // the slots' pixels are recomputed per tile rather than kept in registers
+        if (interior) {
+            // uniform base + 32-bit lane offset; the padding slots (never read) fetch the region's first quad
 #pragma unroll
-        for (int i = 0; i < G::PER_LANE; ++i) {
-            const int o = wave + 4 * i;
-            if (o < G::LOADS) {
-                const unsigned short* p = s_off[i] != ~0u ? base + s_off[i] : zero;
-                if (!interior) {
+            for (int i = 0; i < G::PER_LANE; ++i) {
+                const int o = wave + 4 * i;
+                if (o < G::LOADS)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + s_off[i]),
+                                                     (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
+            }
+        } else {
+            int t = tid;
+            asm volatile("" : "+v"(t));   // the slots' pixels are recomputed per border tile rather than kept in registers
+#pragma unroll
+            for (int i = 0; i < G::PER_LANE; ++i) {
+                const int o = wave + 4 * i;
+                if (o < G::LOADS) {
                     const int s = t + 256 * i;
                     const int px = s / PIXS;
                     const int row = px / G::COLS, col = px - row * G::COLS;
                     const int yy = b.y0 - 1 + row, xx = b.x0 - 1 + col;
-                    const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
-                    p = ok ? p : zero;
+                    const bool ok = s < G::QUADS && yy >= 0 && yy < H && xx >= 0 && xx < W;
+                    const unsigned short* p = ok ? base + s_off[i] : zero;
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                                     (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
                 }
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                                 (__attribute__((address_space(3))) void*)(dst + o * 64), 16, 0, 0);
             }
         }
     };
@@ -718,39 +728,37 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
     const int lane_q = m * PIXS + h;   // this lane's pixel column and half of a 16-channel block, in 16-byte slots
 
     // ---- epilogue, cut into parts that are interleaved with the MFMAs of the next image-row pair.  With one wave per
-    // SIMD nothing else hides its instructions: run after the MFMAs it took a third of the kernel's time.  It is free of
-    // branches, so that the compiler can schedule its parts between the MFMAs: pixels outside the image (and a tile that
-    // does not exist) get a buffer offset past the end, which the hardware drops on stores and answers with zeros on
-    // loads, and operands the call does not have are read through an empty buffer.
+    // SIMD nothing else hides its instructions (run after the MFMAs it took a third of the kernel's time), and every
+    // vector instruction takes an issue slot from the MFMAs, so it is kept short.  It is free of branches, so that the
+    // compiler can schedule its parts between the MFMAs: pixels outside the image (and a tile that does not exist) get
+    // a buffer offset past the end, which the hardware drops on stores and answers with zeros on loads, and a tensor to
+    // add that the call does not have is read through an empty buffer.
     // Accumulator r of lane (m, h): output channel n0 + 8*(r/4) + 4*h + r%4 of pixel (row, x0 + m).  Stored from there a
     // wave store would touch 32 separate 16-byte pieces (the L2 takes as long over those as the MFMAs over the tile), so
     // the wave turns its 32 pixels x 32 channels around in its own LDS rows (LDS operations of one wave execute in
     // order: no barrier) and a lane finishes 8 channels of a pixel: 16-byte stores, 64 contiguous bytes per pixel.
-    // ReLU mask as sign bits: bit 16*(j & 1) + 8*it + e of word j / 2 of a thread says whether the value of image row
-    // j, pass it, channel e of its piece is positive.  The forward launch that produces an activation writes the words,
-    // the data-gradient launch into the same tensor (same geometry, so the same thread holds the same values) reads
-    // them instead of the activation.
+    // ReLU mask as sign bits, in the form the hardware compares and selects with: one 64-bit lane mask per (wave, image
+    // row, pass, channel e of a lane's piece), bit l = the value lane l holds is positive.  The forward launch that
+    // produces an activation writes the masks (VAR 1), the data-gradient launch into the same tensor (same geometry,
+    // so the same lane holds the same values) reads them (VAR 3) instead of the activation (VAR 2); VAR 0: no mask.
+    constexpr bool kMasked = VAR >= 2, kWriteBits = VAR == 1, kReadBits = VAR == 3;
     float* stage = stage_all + wave * 32 * kRwStageStride;
     const int e_px = lane >> 2, e_c8 = lane & 3;
     const unsigned out_bytes = (unsigned)(2 * a.d.Q * a.Nn);   // the launcher checks that this fits 32 bits
     const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, out_bytes, 0x00020000);
-    const bool use_bits = a.bits_in != nullptr;
     const __amdgpu_buffer_rsrc_t r_mask =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(a.mask_ref ? (const void*)a.mask_ref : (const void*)a.out), 0,
-                                          (a.mask_ref && !use_bits) ? out_bytes : 0u, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(VAR == 2 ? (const void*)a.mask_ref : (const void*)a.out), 0, VAR == 2 ? out_bytes : 0u, 0x00020000);
     const __amdgpu_buffer_rsrc_t r_add =
         __builtin_amdgcn_make_buffer_rsrc((void*)(a.add ? a.add : (const void*)a.out), 0, a.add ? out_bytes : 0u, 0x00020000);
     const unsigned word_bytes = (unsigned)(n_blocks * (a.Nn / 128) * 256 * 8);
-    const __amdgpu_buffer_rsrc_t r_bin =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(use_bits ? (const void*)a.bits_in : (const void*)a.out), 0, use_bits ? word_bytes : 0u, 0x00020000);
-    const __amdgpu_buffer_rsrc_t r_bout =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(a.bits_out ? (void*)a.bits_out : a.out), 0, a.bits_out ? word_bytes : 0u, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_bits = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(kReadBits ? (const void*)a.bits_in : (kWriteBits ? (const void*)a.bits_out : (const void*)a.out)), 0,
+        (kReadBits || kWriteBits) ? word_bytes : 0u, 0x00020000);
     float bias_r[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) bias_r[e] = a.bias ? a.bias[n0 + 8 * e_c8 + e] : 0.f;
     const float relu_floor = a.relu_out ? 0.f : -__builtin_huge_valf();
-    const bool has_mask = a.mask_ref != nullptr;   // with or without sign words
-    const bool mask_acc = a.mask_acc != 0, mask_add = a.mask_add != 0;
+    const unsigned long long acc_all = a.mask_acc ? 0ull : ~0ull, add_all = a.mask_add ? 0ull : ~0ull;   // uniform
 
     typedef unsigned uint4v __attribute__((ext_vector_type(4)));
     typedef unsigned uint2v __attribute__((ext_vector_type(2)));
@@ -758,12 +766,21 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
         unsigned off;
         float xv[8];
         uint4v rf, av;
-        unsigned posbits;
+        uint2v mk;
+        unsigned long long pos[8];   // uniform: lane masks of the ReLU mask
     };
     Slice sl;
-    unsigned sign_in_w = 0u, sign_out_w = 0u;
-    // part 0..5 of piece (j, it) of block b
+    // byte offset of the eight lane masks of piece (pair q, s = row parity * 2 + pass) of block b: lane e < 8 of a wave holds mask e
+    auto mask_off = [&](const Block& b, int q, int s_, bool all_lanes) -> unsigned {
+        const bool ok = b.item >= 0 && (all_lanes || lane < 8);
+        return ok ? (unsigned)(((((((long long)ny * n_blocks + b.item) * 4 + wave) * 2 + q) * 4 + s_) * 8 + (lane & 7)) * 8) : ~0u;
+    };
+    // a 16-bit half of w is a positive bfloat16 (0x0001 .. 0x7fff), as a lane mask
+    auto positive_lo = [&](unsigned w) { return __builtin_amdgcn_ballot_w64((int)(w << 16) > 0); };
+    auto positive_hi = [&](unsigned w) { return __builtin_amdgcn_ballot_w64((int)w > 0xffff); };
+    // part 0..5 of piece (j, it) of block b; q = j / 2
     auto epi_part = [&](const Block& b, int j, int it, int part) __attribute__((always_inline)) {
+        const int q = j >> 1, s_ = 2 * (j & 1) + it;
         if (part == 0) {
             if (it == 0) {
 #pragma unroll
@@ -774,7 +791,8 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
             const int px = e_px + 16 * it, x = b.x0 + px, y = b.y0 + j;
             const bool ok = b.item >= 0 && y < H && x < W;
             sl.off = ok ? ((unsigned)(b.img * H + y) * (unsigned)W + (unsigned)x) * (unsigned)(2 * a.Nn) + 2u * (unsigned)(n0 + 8 * e_c8) : ~0u;
-            sl.rf = __builtin_amdgcn_raw_buffer_load_b128(r_mask, sl.off, 0, 0);
+            if (VAR == 2) sl.rf = __builtin_amdgcn_raw_buffer_load_b128(r_mask, sl.off, 0, 0);
+            if (kReadBits) sl.mk = __builtin_amdgcn_raw_buffer_load_b64(r_bits, mask_off(b, q, s_, true), 0, 0);
             sl.av = __builtin_amdgcn_raw_buffer_load_b128(r_add, sl.off, 0, 0);
         } else if (part == 1) {
             const int px = e_px + 16 * it;
@@ -784,23 +802,27 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
 #pragma unroll
             for (int e = 0; e < 8; ++e) sl.xv[e] = fmaxf(t[e] + bias_r[e], relu_floor);
         } else if (part == 2) {
-            // which values pass the ReLU mask: all (no mask), the sign words, or the mask tensor's own signs
-            unsigned bits = 0u;
+            if (kMasked) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const unsigned hv = (sl.rf[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                bits |= (hv - 1u < 0x7fffu ? 1u : 0u) << e;
+                for (int e = 0; e < 8; ++e) {
+                    if (kReadBits)
+                        sl.pos[e] = (unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)sl.mk[0], e) |   // (the builtin returns int)
+                                    ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)sl.mk[1], e) << 32);
+                    else
+                        sl.pos[e] = (e & 1) ? positive_hi(sl.rf[e >> 1]) : positive_lo(sl.rf[e >> 1]);
+                }
             }
-            const unsigned from_words = (sign_in_w >> (16 * (j & 1) + 8 * it)) & 0xffu;
-            sl.posbits = !has_mask ? 0xffu : (use_bits ? from_words : bits);
         } else if (part == 3) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const bool pos = (sl.posbits >> e) & 1u;
                 float x = sl.xv[e];
-                x = (mask_acc && !pos) ? 0.f : x;
-                const float ad = __uint_as_float((sl.av[e >> 1] >> (16 * (e & 1))) << 16);
-                x += (mask_add && !pos) ? 0.f : ad;
+                const float ad = __uint_as_float((e & 1) ? (sl.av[e >> 1] & 0xffff0000u) : (sl.av[e >> 1] << 16));
+                if (kMasked) {
+                    x = __builtin_amdgcn_inverse_ballot_w64(sl.pos[e] | acc_all) ? x : 0.f;
+                    x += __builtin_amdgcn_inverse_ballot_w64(sl.pos[e] | add_all) ? ad : 0.f;
+                } else {
+                    x += ad;
+                }
                 sl.xv[e] = x;
             }
         } else if (part == 4) {
@@ -808,22 +830,22 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
             packed[0] = pack_bf16x2(sl.xv[0], sl.xv[1]); packed[1] = pack_bf16x2(sl.xv[2], sl.xv[3]);
             packed[2] = pack_bf16x2(sl.xv[4], sl.xv[5]); packed[3] = pack_bf16x2(sl.xv[6], sl.xv[7]);
             __builtin_amdgcn_raw_buffer_store_b128(packed, r_out, sl.off, 0, 0);
-            sl.rf = packed;   // kept for the sign bits
+            sl.rf = packed;   // kept for the sign masks
         } else {
-            // the sign of what was stored, i.e. of the rounded value: 0x0001 .. 0x7fff; nothing for a dropped store
-            unsigned bits = 0u;
+            if (kWriteBits) {
+                // the sign of what was stored, i.e. of the rounded value; lanes whose store was dropped report "not positive"
+                const unsigned keep = sl.off != ~0u ? 0xffffffffu : 0u;
+                uint2v out_m = {0u, 0u};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const unsigned hv = (sl.rf[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                bits |= (hv - 1u < 0x7fffu ? 1u : 0u) << e;
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned w = sl.rf[e >> 1] & keep;
+                    const unsigned long long pm = (e & 1) ? positive_hi(w) : positive_lo(w);
+                    out_m[0] = lane == e ? (unsigned)pm : out_m[0];
+                    out_m[1] = lane == e ? (unsigned)(pm >> 32) : out_m[1];
+                }
+                __builtin_amdgcn_raw_buffer_store_b64(out_m, r_bits, mask_off(b, q, s_, false), 0, 0);
             }
-            bits = sl.off != ~0u ? bits : 0u;
-            sign_out_w |= bits << (16 * (j & 1) + 8 * it);
         }
-    };
-    // the sign words of pair q (image rows 2q, 2q + 1) of block b
-    auto word_off = [&](const Block& b, int q) -> unsigned {
-        return b.item >= 0 ? (unsigned)((((long long)ny * n_blocks + b.item) * 256 + tid) * 8 + 4 * q) : ~0u;
     };
 
     // MFMAs of image rows 2p and 2p + 1 of the tile in `buf`, with the epilogue of rows 2q, 2q + 1 of block eb between them.
@@ -844,8 +866,6 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
                 }
             }
         };
-        sign_in_w = __builtin_amdgcn_raw_buffer_load_b32(r_bin, word_off(eb, q), 0, 0);
-        sign_out_w = 0u;
         read_group(0, bq[0]);
 #pragma unroll
         for (int g = 0; g < 3 * NKC; ++g) {
@@ -879,7 +899,6 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_raw_buffer_store_b32(sign_out_w, r_bout, word_off(eb, q), 0, 0);
     };
     static_assert(NKC == 8, "24 operand groups per row pair carry the 24 epilogue parts");
 
@@ -914,13 +933,10 @@ __global__ __launch_bounds__(256, 1) void conv_bf16_rw_kernel(ConvBf16Args a, in
         cur = b2;
     }
     // rows 2, 3 of the last tile
-    sign_in_w = __builtin_amdgcn_raw_buffer_load_b32(r_bin, word_off(prev, 1), 0, 0);
-    sign_out_w = 0u;
 #pragma unroll
     for (int s_ = 0; s_ < 4; ++s_)
 #pragma unroll
         for (int part = 0; part < 6; ++part) epi_part(prev, 2 + s_ / 2, s_ & 1, part);
-    __builtin_amdgcn_raw_buffer_store_b32(sign_out_w, r_bout, word_off(prev, 1), 0, 0);
 }
 
 static bool conv_bf16_rw_applies(const ConvBf16Args& a) {
@@ -947,8 +963,19 @@ static hipError_t launch_conv_bf16_rw(ConvBf16Args a, const float* w, long long 
     char name[56];
     snprintf(name, sizeof(name), "conv_bf16_%s_%dto%d_t9", flip ? "dgrad" : "fwd", a.K, a.Nn);
     KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * 9, 2.0 * (double)a.d.Q * (a.K + a.Nn), st);
-    if (a.relu_in) hipLaunchKernelGGL((conv_bf16_rw_kernel<true, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
-    else hipLaunchKernelGGL((conv_bf16_rw_kernel<false, 8>), grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks);
+    const int var = a.mask_ref ? (a.bits_in ? 3 : 2) : (a.bits_out ? 1 : 0);
+    auto go = [&](auto kern) { hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, a, bx_n, by_n, n_blocks); };
+    if (a.relu_in) {
+        if (var == 0) go(conv_bf16_rw_kernel<true, 8, 0>);
+        else if (var == 1) go(conv_bf16_rw_kernel<true, 8, 1>);
+        else if (var == 2) go(conv_bf16_rw_kernel<true, 8, 2>);
+        else go(conv_bf16_rw_kernel<true, 8, 3>);
+    } else {
+        if (var == 0) go(conv_bf16_rw_kernel<false, 8, 0>);
+        else if (var == 1) go(conv_bf16_rw_kernel<false, 8, 1>);
+        else if (var == 2) go(conv_bf16_rw_kernel<false, 8, 2>);
+        else go(conv_bf16_rw_kernel<false, 8, 3>);
+    }
     return hipGetLastError();
 }
 
