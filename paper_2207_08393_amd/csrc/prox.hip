@@ -1918,6 +1918,11 @@ void plan_prox(const gleam_geom& g, const gleam_prox_desc& p, ProxPlan& plan) {
             const size_t need = align256(wgrad_wino3_partial_floats(dd, c.cin, c.cout) * sizeof(float));
             if (need > plan.partial_bytes) plan.partial_bytes = need;
         }
+        if (p.dtype == 1 && wgrad_bf16_walk_applies(dd, c.cin, c.cout)) {
+            dd.Q = plan.Q;
+            const size_t need = align256(wgrad_bf16_walk_partial_floats(dd, c.cin, c.cout) * sizeof(float));
+            if (need > plan.partial_bytes) plan.partial_bytes = need;
+        }
     }
     w += plan.partial_bytes;
     plan.bias_partial_off = w;
@@ -2265,7 +2270,12 @@ hipError_t prox_backward(const gleam_geom& g, const gleam_prox_desc& p, const Pr
                 wb.partial = partial;
                 wb.bias_partial = c.has_bias ? bpart : nullptr;
                 wb.Co = c.cout; wb.Ci = c.cin; wb.relu_in = wa.relu_in; wb.d = d;
-                e = launch_wgrad_bf16(wb, plan.n_split, st);
+                if (!(kernel_policy() & GLEAM_POLICY_NO_FRAME_WALK) && wgrad_bf16_walk_applies(d, c.cin, c.cout)) {
+                    e = launch_wgrad_bf16_walk(wb, st);   // down the rows, every input row segment staged once
+                    used_split = wgrad_bf16_walk_splits(d, c.cout);
+                } else {
+                    e = launch_wgrad_bf16(wb, plan.n_split, st);
+                }
                 bias_done = c.has_bias;
             }
         } else if (wino_enabled() && wgrad_wino_applies(d, c.cin, c.cout)) {

@@ -306,5 +306,11 @@ struct WgradBf16Args {
 };
 hipError_t launch_wgrad_bf16(const WgradBf16Args& a, int n_split, hipStream_t stream);
 size_t wgrad_bf16_lds_bytes(int Co, int Ci, int kt, int kd, int kh, int kw);
+// 3x3 layers with 128 input channels: walk down strips of 64 columns (prox_bf16w.hip); writes
+// wgrad_bf16_walk_splits partial blocks (two_buf is not used)
+bool wgrad_bf16_walk_applies(const PixDims& d, int Ci, int Co);
+int wgrad_bf16_walk_splits(const PixDims& d, int Co);
+size_t wgrad_bf16_walk_partial_floats(const PixDims& d, int Ci, int Co);
+hipError_t launch_wgrad_bf16_walk(const WgradBf16Args& a, hipStream_t stream);
 
 }  // namespace gleam
