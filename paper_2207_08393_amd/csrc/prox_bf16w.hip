@@ -5,11 +5,11 @@
 // row reads each input three times and pays the staging instructions three times).  Nothing is staged through
 // registers: row segments go from memory to LDS by direct loads, one image row ahead of the matrix cores; pixels
 // outside the image are loaded from a 16-byte block of zeros, so the loop has no masks and no LDS stores.
-// A workgroup of 4 waves (one per SIMD, the whole register file each) owns 64 output channels x 128 input channels:
-// wave w holds the nine taps of input channels 32 w .. 32 w + 31 against both 32-channel halves of the output
-// channels (18 accumulators).  Per 16 pixels it reads its input window (3 transposing LDS reads per input row,
-// the kx shifts are register shifts of that window) and the gradient operands (shared by the waves), 13 LDS reads
-// for 18 MFMAs.  v_mfma_f32_32x32x16_bf16: contraction index = pixel; A = gradient (rows = output channels),
+// A workgroup of 8 waves (two per SIMD) owns 64 output channels x 128 input channels: wave (wi, wc) holds the nine taps
+// of input channels 32 wi .. + 31 against output channels 32 wc .. + 31 (9 accumulators; 18 per wave would be 288
+// registers, more than the 256 accumulation registers an MFMA can address, and the compiler then moves accumulators
+// to and fro all the time).  Per 16 pixels it reads its input window (3 transposing LDS reads per input row, the kx
+// shifts are register shifts of that window) and its gradient operand, 11 LDS reads for 9 MFMAs.  v_mfma_f32_32x32x16_bf16: contraction index = pixel; A = gradient (rows = output channels),
 // B = input window (columns = input channels), so a lane's accumulators are one input channel and lanes are
 // contiguous in the [Co][tap][Ci] partial block every workgroup writes once.
 // The four input buffers and the two gradient buffers are separate LDS objects and the walk is written out over
@@ -59,7 +59,7 @@ struct WalkWgradBf16Args {
 };
 
 template <bool RELU>
-__global__ __launch_bounds__(256, 1) void wgrad_bf16_walk_kernel(WalkWgradBf16Args a) {
+__global__ __launch_bounds__(512) void wgrad_bf16_walk_kernel(WalkWgradBf16Args a) {
     __shared__ __attribute__((aligned(16))) unsigned short X0[kWXQuads * 8];
     __shared__ __attribute__((aligned(16))) unsigned short X1[kWXQuads * 8];
     __shared__ __attribute__((aligned(16))) unsigned short X2[kWXQuads * 8];
@@ -69,24 +69,25 @@ __global__ __launch_bounds__(256, 1) void wgrad_bf16_walk_kernel(WalkWgradBf16Ar
     __shared__ float bred[4][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wi = wave >> 1, wc = wave & 1;
     const int m = lane & 31, h = lane >> 5;
     const int co0 = 64 * (int)blockIdx.y;
     constexpr int Ci = 128;
 
-    // Direct loads.  Input buffer: slot s = 64 (wave + 4 i) + lane holds channel quad s % 18 (16, 17: padding) of segment
+    // Direct loads.  Input buffer: slot s = 64 (wave + 8 i) + lane holds channel quad s % 18 (16, 17: padding) of segment
     // pixel s / 18 = image column x0 - 1 + s / 18.  Gradient buffer: slot s holds quad s % 10 (8, 9: padding) of pixel
     // s / 10 = column x0 + s / 10.  Padding slots and pixels that are not loaded fetch the zeros as well.
-    int x_off[5], x_col[5], g_off[3], g_col[3];   // element offset from (row, x0), column offset; column 1 << 20: never valid
+    int x_off[3], x_col[3], g_off[2], g_col[2];   // element offset from (row, x0), column offset; column 1 << 20: never valid
 #pragma unroll
-    for (int i = 0; i < 5; ++i) {
-        const int s = 64 * (wave + 4 * i) + lane, pp = s / 18, c8 = s % 18;
+    for (int i = 0; i < 3; ++i) {
+        const int s = 64 * (wave + 8 * i) + lane, pp = s / 18, c8 = s % 18;
         const bool data = c8 < 16 && pp < kWXPix;
         x_col[i] = data ? pp - 1 : (1 << 20);
         x_off[i] = data ? (pp - 1) * Ci + 8 * c8 : 0;
     }
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        const int s = 64 * (wave + 4 * i) + lane, p = s / 10, c8 = s % 10;
+    for (int i = 0; i < 2; ++i) {
+        const int s = 64 * (wave + 8 * i) + lane, p = s / 10, c8 = s % 10;
         const bool data = c8 < 8;
         g_col[i] = data ? p : (1 << 20);
         g_off[i] = data ? p * a.Co + 8 * c8 : 0;
@@ -96,34 +97,28 @@ __global__ __launch_bounds__(256, 1) void wgrad_bf16_walk_kernel(WalkWgradBf16Ar
     // per-lane element offsets of the transposing reads: pixel 8h + (lane % 16) / 4 of the 16-pixel block, channels
     // 16 ((lane / 16) % 2) + 4 (lane % 4) .. + 3 of the wave's 32-channel block
     const int tr_row = 8 * h + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    const int g_rd = tr_row * kWGRow + tr_col;
-    const int x_rd = tr_row * kWXRow + wave * 32 + tr_col;
+    const int g_rd = tr_row * kWGRow + wc * 32 + tr_col;
+    const int x_rd = tr_row * kWXRow + wi * 32 + tr_col;
 
-    floatx16 acc[2][9];
+    floatx16 acc[9];
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int j = 0; j < 9; ++j)
 #pragma unroll
-        for (int j = 0; j < 9; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[c][j][r] = 0.f;
-    float bsum[2] = {0.f, 0.f};
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    float bsum = 0.f;
 
     // one image row of the strip: input rows y - 1, y, y + 1 in xm, xz, xp, gradient row y in gc
     auto run = [&](const unsigned short* xm, const unsigned short* xz, const unsigned short* xp, const unsigned short* gc)
                    __attribute__((always_inline)) {
 #pragma unroll
         for (int kb = 0; kb < kWW / 16; ++kb) {
-            bf16x8 gv[2];
+            const unsigned short* gp = gc + g_rd + 16 * kb * kWGRow;
+            const uint2 g0 = w_read_tr16(gp), g1 = w_read_tr16(gp + 4 * kWGRow);
+            const bf16x8 gv = __builtin_bit_cast(bf16x8, make_uint4(g0.x, g0.y, g1.x, g1.y));
+            if (kb == wi) {   // bias gradient: of the four waves with these output channels, each sums one of the four pixel blocks
+                const unsigned w4[4] = {g0.x, g0.y, g1.x, g1.y};
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const unsigned short* gp = gc + g_rd + 32 * c + 16 * kb * kWGRow;
-                const uint2 g0 = w_read_tr16(gp), g1 = w_read_tr16(gp + 4 * kWGRow);
-                gv[c] = __builtin_bit_cast(bf16x8, make_uint4(g0.x, g0.y, g1.x, g1.y));
-                if (kb == wave) {   // bias gradient: each wave sums the gradient operands of one of the four pixel blocks
-                    const unsigned w4[4] = {g0.x, g0.y, g1.x, g1.y};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) bsum[c] += __uint_as_float(w4[e] << 16) + __uint_as_float(w4[e] & 0xffff0000u);
-                }
+                for (int e = 0; e < 4; ++e) bsum += __uint_as_float(w4[e] << 16) + __uint_as_float(w4[e] & 0xffff0000u);
             }
 #pragma unroll
             for (int rt = 0; rt < 3; ++rt) {
@@ -146,10 +141,7 @@ __global__ __launch_bounds__(256, 1) void wgrad_bf16_walk_kernel(WalkWgradBf16Ar
                     } else {
                         b = make_uint4(dws[dw / 2], dws[dw / 2 + 1], dws[dw / 2 + 2], dws[dw / 2 + 3]);
                     }
-                    const bf16x8 bv = __builtin_bit_cast(bf16x8, b);
-#pragma unroll
-                    for (int c = 0; c < 2; ++c)
-                        acc[c][3 * rt + dw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv[c], bv, acc[c][3 * rt + dw], 0, 0, 0);
+                    acc[3 * rt + dw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b), acc[3 * rt + dw], 0, 0, 0);
                 }
             }
         }
@@ -162,25 +154,25 @@ __global__ __launch_bounds__(256, 1) void wgrad_bf16_walk_kernel(WalkWgradBf16Ar
         const int x0 = strip * kWW;
         const int y0 = rn * a.run_len, y1 = y0 + a.run_len < a.H ? y0 + a.run_len : a.H;
         // which of this thread's slots hold pixels inside the image row
-        bool x_in[5], g_in[3];
+        bool x_in[3], g_in[2];
 #pragma unroll
-        for (int i = 0; i < 5; ++i) x_in[i] = (unsigned)(x0 + x_col[i]) < (unsigned)a.W;
+        for (int i = 0; i < 3; ++i) x_in[i] = (unsigned)(x0 + x_col[i]) < (unsigned)a.W;
 #pragma unroll
-        for (int i = 0; i < 3; ++i) g_in[i] = (unsigned)(x0 + g_col[i]) < (unsigned)a.W;
+        for (int i = 0; i < 2; ++i) g_in[i] = (unsigned)(x0 + g_col[i]) < (unsigned)a.W;
         const unsigned short* const xa = a.a + ((img * a.H) * a.W + x0) * Ci;          // (row 0, x0) of the image
         const unsigned short* const ga = a.g + ((img * a.H) * a.W + x0) * a.Co + co0;
         auto load_x = [&](int y, unsigned short* dst) __attribute__((always_inline)) {
             const bool row_ok = y >= 0 && y < a.H;
             const unsigned short* const base = xa + (long long)(row_ok ? y : 0) * a.W * Ci;
 #pragma unroll
-            for (int i = 0; i < 5; ++i)
-                if (wave + 4 * i < kWXLoads) w_dma16(row_ok && x_in[i] ? base + x_off[i] : zero, dst + (wave + 4 * i) * 512);
+            for (int i = 0; i < 3; ++i)
+                if (wave + 8 * i < kWXLoads) w_dma16(row_ok && x_in[i] ? base + x_off[i] : zero, dst + (wave + 8 * i) * 512);
         };
         auto load_g = [&](int y, unsigned short* dst) __attribute__((always_inline)) {
             const unsigned short* const base = ga + (long long)y * a.W * a.Co;   // rows y0 .. y1 - 1 only
 #pragma unroll
-            for (int i = 0; i < 3; ++i)
-                if (wave + 4 * i < kWGLoads) w_dma16(g_in[i] ? base + g_off[i] : zero, dst + (wave + 4 * i) * 512);
+            for (int i = 0; i < 2; ++i)
+                if (wave + 8 * i < kWGLoads) w_dma16(g_in[i] ? base + g_off[i] : zero, dst + (wave + 8 * i) * 512);
         };
         // the previous item ended with a barrier: all buffers are free
         load_x(y0 - 1, X0);
@@ -217,20 +209,15 @@ __global__ __launch_bounds__(256, 1) void wgrad_bf16_walk_kernel(WalkWgradBf16Ar
 
     float* const pout = a.partial + (size_t)blockIdx.x * a.Co * 9 * Ci;
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int j = 0; j < 9; ++j)
 #pragma unroll
-        for (int j = 0; j < 9; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int co = co0 + 32 * c + 8 * (r >> 2) + 4 * h + (r & 3), ci = 32 * wave + m;
-                pout[((size_t)co * 9 + j) * Ci + ci] = acc[c][j][r];
-            }
-    if (a.bias_partial) {
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const float tot = bsum[c] + __shfl_xor(bsum[c], 32);
-            if (h == 0) bred[wave][32 * c + m] = tot;
+        for (int r = 0; r < 16; ++r) {
+            const int co = co0 + 32 * wc + 8 * (r >> 2) + 4 * h + (r & 3), ci = 32 * wi + m;
+            pout[((size_t)co * 9 + j) * Ci + ci] = acc[j][r];
         }
+    if (a.bias_partial) {
+        const float tot = bsum + __shfl_xor(bsum, 32);
+        if (h == 0) bred[wi][32 * wc + m] = tot;
         __syncthreads();
         if (tid < 64) a.bias_partial[(size_t)blockIdx.x * a.Co + co0 + tid] = (bred[0][tid] + bred[1][tid]) + (bred[2][tid] + bred[3][tid]);
     }
@@ -285,8 +272,8 @@ hipError_t launch_wgrad_bf16_walk(const WgradBf16Args& w, hipStream_t st) {
     snprintf(name, sizeof(name), "conv_bf16_wgrad_%dto%d_t9", w.Ci, w.Co);
     KernelScope ks(name, 2.0 * (double)d.Q * w.Ci * w.Co * 9, 2.0 * (double)d.Q * (w.Ci + w.Co), st);
     dim3 grid((unsigned)splits, (unsigned)(w.Co / 64));
-    if (w.relu_in) hipLaunchKernelGGL((wgrad_bf16_walk_kernel<true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((wgrad_bf16_walk_kernel<false>), grid, dim3(256), 0, st, a);
+    if (w.relu_in) hipLaunchKernelGGL((wgrad_bf16_walk_kernel<true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_bf16_walk_kernel<false>), grid, dim3(512), 0, st, a);
     return hipGetLastError();
 }
 
