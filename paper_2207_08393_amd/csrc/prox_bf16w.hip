@@ -4,14 +4,16 @@
 // columns and every input row segment is brought into LDS once (a kernel that stages the three rows per gradient
 // row reads each input three times and pays the staging instructions three times).  Nothing is staged through
 // registers: row segments go from memory to LDS by direct loads, one image row ahead of the matrix cores; pixels
-// outside the image are loaded from a 16-byte block of zeros, so the loop has no masks and no LDS stores.
+// outside the image fall outside the buffer resource of their image row and arrive as zeros, so the loop has no
+// masks, no selects and no LDS stores.
 // A workgroup of 8 waves (two per SIMD) owns 64 output channels x 128 input channels: wave (wi, wc) holds the nine taps
 // of input channels 32 wi .. + 31 against output channels 32 wc .. + 31 (9 accumulators; 18 per wave would be 288
 // registers, more than the 256 accumulation registers an MFMA can address, and the compiler then moves accumulators
-// to and fro all the time).  Per 16 pixels it reads its input window (3 transposing LDS reads per input row, the kx
-// shifts are register shifts of that window) and its gradient operand, 11 LDS reads for 9 MFMAs.  v_mfma_f32_32x32x16_bf16: contraction index = pixel; A = gradient (rows = output channels),
-// B = input window (columns = input channels), so a lane's accumulators are one input channel and lanes are
-// contiguous in the [Co][tap][Ci] partial block every workgroup writes once.
+// to and fro all the time).  Per 16 pixels and input row it reads its input window with 4 transposing LDS reads (the
+// taps kx = 0 and kx = 2 as they lie, kx = 1 by register shifts of the two) and per 16 pixels its gradient operand with 2;
+// the bias sums are packed dot products with ones.  v_mfma_f32_32x32x16_bf16: contraction index = pixel; A = gradient
+// (rows = output channels), B = input window (columns = input channels), so a lane's accumulators are one input
+// channel and lanes are contiguous in the [Co][tap][Ci] partial block every workgroup writes once.
 // The four input buffers and the two gradient buffers are separate LDS objects and the walk is written out over
 // its four rotations: the compiler then knows which buffer a read touches and does not make operand reads wait for
 // the direct loads in flight.
@@ -22,21 +24,19 @@ namespace gleam {
 namespace {
 
 constexpr int kWW = 64;                  // columns of a strip
-constexpr int kWXRow = 128 + 16;         // elements per pixel of an input segment: 128 channels + 32 bytes (bank spread)
-constexpr int kWGRow = 64 + 16;          // elements per pixel of a gradient segment
+// LDS layout of a segment: pixel p, channel c at element p * row + 16 * ((p / 8) % 2) + c, with rows of 320 bytes
+// (input, 128 channels) and 192 bytes (gradient, 64 channels).  A transposing read touches, per group of 16 lanes,
+// 32 bytes of each of 4 consecutive pixels, the lane halves of a wave are 8 pixels apart and the two groups of a
+// half 32 bytes: with row = 64 (mod 256) bytes the four pixels of a half fill the 64 banks exactly, and the extra 32
+// bytes of every other block of 8 pixels keep the halves apart whichever lanes the hardware serves together.
+// (With 288-byte rows the counters showed two conflict cycles per cycle of LDS work.)
+constexpr int kWXRow = 160;              // elements per pixel of an input segment
+constexpr int kWGRow = 96;               // elements per pixel of a gradient segment
 constexpr int kWXPix = kWW + 2;          // pixels of an input segment that are loaded (one halo column each side)
-constexpr int kWXQuads = 20 * 64;        // 16-byte slots of an input buffer: 68 pixels (the windows of the last lanes
-                                         // reach two pixels past the loaded ones; what they read there is not used)
-constexpr int kWXLoads = 19;             // wave-wide direct loads that cover the 66 loaded pixels (18 slots each)
-constexpr int kWGQuads = 10 * 64;        // 64 pixels x 10 slots
-constexpr int kWGLoads = 10;
-
-__device__ __attribute__((aligned(16))) unsigned w_zero_quad[4];   // zero-initialised: the source of every out-of-image pixel
-
-__device__ __forceinline__ void w_dma16(const unsigned short* g, unsigned short* l) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)l, 16, 0, 0);
-}
+constexpr int kWXQuads = 21 * 64;        // 16-byte slots of an input buffer: 66 pixels of 20 slots and the shift
+constexpr int kWXLoads = 21;             // wave-wide direct loads that cover the 66 loaded pixels
+constexpr int kWGQuads = 12 * 64;        // 64 pixels x 12 slots
+constexpr int kWGLoads = 12;
 
 typedef short w_short4 __attribute__((ext_vector_type(4)));
 // ds_read_b64_tr_b16: within each group of 16 lanes, lane s passes the address of 4 consecutive 16-bit values of
@@ -66,7 +66,6 @@ __global__ __launch_bounds__(512) void wgrad_bf16_walk_kernel(WalkWgradBf16Args 
     __shared__ __attribute__((aligned(16))) unsigned short X3[kWXQuads * 8];
     __shared__ __attribute__((aligned(16))) unsigned short G0[kWGQuads * 8];
     __shared__ __attribute__((aligned(16))) unsigned short G1[kWGQuads * 8];
-    __shared__ float bred[4][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wi = wave >> 1, wc = wave & 1;
@@ -74,31 +73,33 @@ __global__ __launch_bounds__(512) void wgrad_bf16_walk_kernel(WalkWgradBf16Args 
     const int co0 = 64 * (int)blockIdx.y;
     constexpr int Ci = 128;
 
-    // Direct loads.  Input buffer: slot s = 64 (wave + 8 i) + lane holds channel quad s % 18 (16, 17: padding) of segment
-    // pixel s / 18 = image column x0 - 1 + s / 18.  Gradient buffer: slot s holds quad s % 10 (8, 9: padding) of pixel
-    // s / 10 = column x0 + s / 10.  Padding slots and pixels that are not loaded fetch the zeros as well.
-    int x_off[3], x_col[3], g_off[2], g_col[2];   // element offset from (row, x0), column offset; column 1 << 20: never valid
+    // Direct loads through a buffer resource that spans one image row: a slot whose byte offset falls outside the row
+    // (columns left of 0 come out as huge unsigned offsets, columns right of W - 1 exceed the size) is filled with zeros
+    // by the hardware, a row outside the image gets a resource of size 0, and padding slots an offset that is always
+    // outside; no selects, no LDS stores.  Input buffer: slot s = 64 (wave + 8 i) + lane belongs to segment pixel
+    // pp = s / 20 = image column x0 - 1 + pp and holds its channel quad s % 20 - 2 ((pp / 8) % 2) if that is one of
+    // 0 .. 15.  Gradient buffer: pixel p = s / 12 = column x0 + p, quad s % 12 - 2 ((p / 8) % 2) of 0 .. 7.
+    constexpr unsigned kOutside = 0x80000000u;   // (row sizes are below 2^31 bytes: checked by the launcher)
+    unsigned x_slot[3], g_slot[2];               // byte offset from column x0 of the row
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
-        const int s = 64 * (wave + 8 * i) + lane, pp = s / 18, c8 = s % 18;
-        const bool data = c8 < 16 && pp < kWXPix;
-        x_col[i] = data ? pp - 1 : (1 << 20);
-        x_off[i] = data ? (pp - 1) * Ci + 8 * c8 : 0;
+        const int s = 64 * (wave + 8 * i) + lane, pp = s / 20, c8 = s % 20 - 2 * ((pp >> 3) & 1);
+        x_slot[i] = (c8 >= 0 && c8 < 16 && pp < kWXPix) ? (unsigned)((pp - 1) * Ci * 2 + 16 * c8) : kOutside;
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const int s = 64 * (wave + 8 * i) + lane, p = s / 10, c8 = s % 10;
-        const bool data = c8 < 8;
-        g_col[i] = data ? p : (1 << 20);
-        g_off[i] = data ? p * a.Co + 8 * c8 : 0;
+        const int s = 64 * (wave + 8 * i) + lane, p = s / 12, c8 = s % 12 - 2 * ((p >> 3) & 1);
+        g_slot[i] = (c8 >= 0 && c8 < 8) ? (unsigned)(p * a.Co * 2 + 2 * co0 + 16 * c8) : kOutside;
     }
-    const unsigned short* const zero = reinterpret_cast<const unsigned short*>(w_zero_quad);
+    const unsigned x_row_bytes = (unsigned)a.W * Ci * 2, g_row_bytes = (unsigned)a.W * (unsigned)a.Co * 2;
 
-    // per-lane element offsets of the transposing reads: pixel 8h + (lane % 16) / 4 of the 16-pixel block, channels
-    // 16 ((lane / 16) % 2) + 4 (lane % 4) .. + 3 of the wave's 32-channel block
+    // per-lane element offsets of the transposing reads: pixel 8h + (lane % 16) / 4 (+ 2, 4, 6) of the 16-pixel block,
+    // channels 16 ((lane / 16) % 2) + 4 (lane % 4) .. + 3 of the wave's 32-channel block
     const int tr_row = 8 * h + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    const int g_rd = tr_row * kWGRow + wc * 32 + tr_col;
-    const int x_rd = tr_row * kWXRow + wi * 32 + tr_col;
+    auto px_off = [](int p, int row) { return p * row + 16 * ((p >> 3) & 1); };
+    const int g_rd = px_off(tr_row, kWGRow) + wc * 32 + tr_col;        // (+ 4 pixels: the same block of 8)
+    const int x_rd = px_off(tr_row, kWXRow) + wi * 32 + tr_col;        // (+ 2, + 4 pixels: the same block of 8)
+    const int x_rd6 = px_off(tr_row + 6, kWXRow) + wi * 32 + tr_col;
 
     floatx16 acc[9];
 #pragma unroll
@@ -106,44 +107,59 @@ __global__ __launch_bounds__(512) void wgrad_bf16_walk_kernel(WalkWgradBf16Args 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
     float bsum = 0.f;
+    const bf16x2v ones = {(__bf16)1.0f, (__bf16)1.0f};
 
     // one image row of the strip: input rows y - 1, y, y + 1 in xm, xz, xp, gradient row y in gc
     auto run = [&](const unsigned short* xm, const unsigned short* xz, const unsigned short* xp, const unsigned short* gc)
                    __attribute__((always_inline)) {
+        // 12 operand groups (16-pixel block kb, input row rt): 4 window reads (+ 2 gradient reads when rt = 0) and 3 MFMAs
+        // each; the reads of a group are issued two groups ahead of its MFMAs.  Of this lane's input channel a group
+        // reads segment pixels 16 kb + 8 h + 0 .. 7 (tap kx = 0) and + 2 .. 9 (kx = 2) as they are (four registers that
+        // start at an odd one are no MFMA operand, and the copies would cost more than the second pair of reads);
+        // kx = 1 is shifted out of the two.
+        uint2 wq[3][4], gq[2][2];
+        auto read_group = [&](int g) __attribute__((always_inline)) {
+            const int kb = g / 3, rt = g - 3 * kb;
+            if (rt == 0) {
+                const unsigned short* gp = gc + g_rd + 16 * kb * kWGRow;
+                gq[kb & 1][0] = w_read_tr16(gp);
+                gq[kb & 1][1] = w_read_tr16(gp + 4 * kWGRow);
+            }
+            const unsigned short* row = (rt == 0 ? xm : rt == 1 ? xz : xp) + 16 * kb * kWXRow;
+            wq[g % 3][0] = w_read_tr16(row + x_rd);
+            wq[g % 3][1] = w_read_tr16(row + x_rd + 4 * kWXRow);
+            wq[g % 3][2] = w_read_tr16(row + x_rd + 2 * kWXRow);
+            wq[g % 3][3] = w_read_tr16(row + x_rd6);
+        };
+        read_group(0);
+        read_group(1);
 #pragma unroll
-        for (int kb = 0; kb < kWW / 16; ++kb) {
-            const unsigned short* gp = gc + g_rd + 16 * kb * kWGRow;
-            const uint2 g0 = w_read_tr16(gp), g1 = w_read_tr16(gp + 4 * kWGRow);
+        for (int g = 0; g < 12; ++g) {
+            const int kb = g / 3, rt = g - 3 * kb;
+            if (g + 2 < 12) read_group(g + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            const uint2 g0 = gq[kb & 1][0], g1 = gq[kb & 1][1];
             const bf16x8 gv = __builtin_bit_cast(bf16x8, make_uint4(g0.x, g0.y, g1.x, g1.y));
-            if (kb == wi) {   // bias gradient: of the four waves with these output channels, each sums one of the four pixel blocks
+            if (rt == 0) {   // bias gradient (the four waves with these output channels all form it; one of them writes it)
                 const unsigned w4[4] = {g0.x, g0.y, g1.x, g1.y};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) bsum += __uint_as_float(w4[e] << 16) + __uint_as_float(w4[e] & 0xffff0000u);
+                for (int e = 0; e < 4; ++e) bsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, w4[e]), ones, bsum, false);
             }
+            uint2* w = wq[g % 3];
+            if (RELU) {
 #pragma unroll
-            for (int rt = 0; rt < 3; ++rt) {
-                // window of segment pixels 16 kb + 8 h .. + 11 of this lane's input channel, six 32-bit words
-                const unsigned short* row = (rt == 0 ? xm : rt == 1 ? xz : xp) + x_rd + 16 * kb * kWXRow;
-                const uint2 w0 = w_read_tr16(row), w1 = w_read_tr16(row + 4 * kWXRow), w2 = w_read_tr16(row + 8 * kWXRow);
-                unsigned dws[5] = {w0.x, w0.y, w1.x, w1.y, w2.x};
-                if (RELU) {
-#pragma unroll
-                    for (int e = 0; e < 5; ++e) dws[e] = relu_bf16x2(dws[e]);
-                }
-#pragma unroll
-                for (int dw = 0; dw < 3; ++dw) {
-                    uint4 b;
-                    if (dw == 1) {
-                        b.x = __builtin_amdgcn_alignbit(dws[1], dws[0], 16);
-                        b.y = __builtin_amdgcn_alignbit(dws[2], dws[1], 16);
-                        b.z = __builtin_amdgcn_alignbit(dws[3], dws[2], 16);
-                        b.w = __builtin_amdgcn_alignbit(dws[4], dws[3], 16);
-                    } else {
-                        b = make_uint4(dws[dw / 2], dws[dw / 2 + 1], dws[dw / 2 + 2], dws[dw / 2 + 3]);
-                    }
-                    acc[3 * rt + dw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b), acc[3 * rt + dw], 0, 0, 0);
-                }
+                for (int e = 0; e < 4; ++e) { w[e].x = relu_bf16x2(w[e].x); w[e].y = relu_bf16x2(w[e].y); }
             }
+            uint4 b1;   // pixels 1 .. 8 of the window
+            b1.x = __builtin_amdgcn_alignbit(w[0].y, w[0].x, 16);
+            b1.y = __builtin_amdgcn_alignbit(w[1].x, w[0].y, 16);
+            b1.z = __builtin_amdgcn_alignbit(w[1].y, w[1].x, 16);
+            b1.w = __builtin_amdgcn_alignbit(w[3].y, w[1].y, 16);
+            const uint4 b0 = make_uint4(w[0].x, w[0].y, w[1].x, w[1].y), b2 = make_uint4(w[2].x, w[2].y, w[3].x, w[3].y);
+            acc[3 * rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b0), acc[3 * rt], 0, 0, 0);
+            acc[3 * rt + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b1), acc[3 * rt + 1], 0, 0, 0);
+            acc[3 * rt + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gv, __builtin_bit_cast(bf16x8, b2), acc[3 * rt + 2], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -153,26 +169,31 @@ __global__ __launch_bounds__(512) void wgrad_bf16_walk_kernel(WalkWgradBf16Args 
         const long long img = item / ((long long)a.runs * a.strips);
         const int x0 = strip * kWW;
         const int y0 = rn * a.run_len, y1 = y0 + a.run_len < a.H ? y0 + a.run_len : a.H;
-        // which of this thread's slots hold pixels inside the image row
-        bool x_in[3], g_in[2];
+        unsigned x_at[3], g_at[2];   // byte offsets of this thread's slots inside an image row
 #pragma unroll
-        for (int i = 0; i < 3; ++i) x_in[i] = (unsigned)(x0 + x_col[i]) < (unsigned)a.W;
+        for (int i = 0; i < 3; ++i) x_at[i] = x_slot[i] + (unsigned)(x0 * Ci * 2);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) g_in[i] = (unsigned)(x0 + g_col[i]) < (unsigned)a.W;
-        const unsigned short* const xa = a.a + ((img * a.H) * a.W + x0) * Ci;          // (row 0, x0) of the image
-        const unsigned short* const ga = a.g + ((img * a.H) * a.W + x0) * a.Co + co0;
+        for (int i = 0; i < 2; ++i) g_at[i] = g_slot[i] + (unsigned)(x0 * a.Co * 2);
+        const unsigned short* const xa = a.a + (img * a.H) * a.W * Ci;     // row 0 of the image
+        const unsigned short* const ga = a.g + (img * a.H) * a.W * a.Co;
         auto load_x = [&](int y, unsigned short* dst) __attribute__((always_inline)) {
             const bool row_ok = y >= 0 && y < a.H;
-            const unsigned short* const base = xa + (long long)(row_ok ? y : 0) * a.W * Ci;
+            const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(xa + (long long)(row_ok ? y : 0) * a.W * Ci), 0, row_ok ? x_row_bytes : 0u, 0x00020000);
 #pragma unroll
             for (int i = 0; i < 3; ++i)
-                if (wave + 8 * i < kWXLoads) w_dma16(row_ok && x_in[i] ? base + x_off[i] : zero, dst + (wave + 8 * i) * 512);
+                if (wave + 8 * i < kWXLoads)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(dst + (wave + 8 * i) * 512), 16,
+                                                             x_at[i], 0, 0, 0);
         };
-        auto load_g = [&](int y, unsigned short* dst) __attribute__((always_inline)) {
-            const unsigned short* const base = ga + (long long)y * a.W * a.Co;   // rows y0 .. y1 - 1 only
+        auto load_g = [&](int y, unsigned short* dst) __attribute__((always_inline)) {   // rows y0 .. y1 - 1 only
+            const __amdgpu_buffer_rsrc_t r =
+                __builtin_amdgcn_make_buffer_rsrc((void*)(ga + (long long)y * a.W * a.Co), 0, g_row_bytes, 0x00020000);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                if (wave + 8 * i < kWGLoads) w_dma16(g_in[i] ? base + g_off[i] : zero, dst + (wave + 8 * i) * 512);
+                if (wave + 8 * i < kWGLoads)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(dst + (wave + 8 * i) * 512), 16,
+                                                             g_at[i], 0, 0, 0);
         };
         // the previous item ended with a barrier: all buffers are free
         load_x(y0 - 1, X0);
@@ -215,18 +236,16 @@ __global__ __launch_bounds__(512) void wgrad_bf16_walk_kernel(WalkWgradBf16Args 
             const int co = co0 + 32 * wc + 8 * (r >> 2) + 4 * h + (r & 3), ci = 32 * wi + m;
             pout[((size_t)co * 9 + j) * Ci + ci] = acc[j][r];
         }
-    if (a.bias_partial) {
+    if (a.bias_partial && wi == 0) {
         const float tot = bsum + __shfl_xor(bsum, 32);
-        if (h == 0) bred[wi][32 * wc + m] = tot;
-        __syncthreads();
-        if (tid < 64) a.bias_partial[(size_t)blockIdx.x * a.Co + co0 + tid] = (bred[0][tid] + bred[1][tid]) + (bred[2][tid] + bred[3][tid]);
+        if (h == 0) a.bias_partial[(size_t)blockIdx.x * a.Co + co0 + 32 * wc + m] = tot;
     }
 }
 
 bool wgrad_bf16_walk_applies(const PixDims& d, int Ci, int Co) {
     // element offsets inside a row of strips are 32 bits in the kernel
     return d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3 && Ci == 128 && Co % 64 == 0 && Co >= 64 &&
-           d.W < (1 << 20) && (double)(d.W + 2 * kWW) * (Ci > Co ? Ci : Co) < 2.0e9;
+           (double)(d.W + 2 * kWW) * 2.0 * (Ci > Co ? Ci : Co) < 2.0e9;   // byte offsets inside an image row: 31 bits
 }
 
 // Runs per strip.  In units of the time of one image row of a strip: a run of n rows costs n + 3 (its first rows), the
