@@ -547,10 +547,11 @@ hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const flo
 // (float32) or 8-byte (bfloat16) stores after a turn through the wave's own LDS rows.  No barriers: every wave
 // walks 32-pixel row segments on its own.  The kernel it replaces for these shapes computes on the vector ALUs, 2*taps multiply-adds per output.
 
-template <int KD, int NB, int NH, bool BF>
-__global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a) {
+template <int KD, int NB, int NH, bool BF, bool EPI>   // EPI: the call has a ReLU mask source or an add operand
+__global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a, int runs, int run_len) {
     // NH passes of NB blocks of 32 output channels each: Nn = 32 * NB * NH
-    constexpr int TAPS = KD * 9, NP = 32 * NB, NN = NP * NH, SS = NP + 4;   // SS: floats per pixel row of the wave's LDS rows
+    static_assert(KD == 3, "the walk keeps three slices of three rows");
+    constexpr int TAPS = 27, NP = 32 * NB, NN = NP * NH, SS = NP + 4;   // SS: floats per pixel row of the wave's LDS rows
     __shared__ __attribute__((aligned(16))) float stage_all[4 * 32 * SS];
     const PixDims d = a.d;
     const int lane = threadIdx.x & 63;
@@ -565,121 +566,241 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
 #pragma unroll
             for (int t = 0; t < TAPS; ++t)
                 wreg[hb][nb][t] = a.w[(NP * hb + 32 * nb + m) * a.sn + (a.flip ? TAPS - 1 - t : t) * a.st + h * a.sk];
+    // A wave walks down the rows of one 32-pixel column segment of one slice: of the 27 input values a row needs (three
+    // slices x three rows x three columns) the 18 of the two upper rows are the previous row's, so a row costs 9 loads,
+    // and all of its addresses are a wave-uniform row pointer plus a lane constant.  Item = (slice of an image, segment,
+    // run of run_len rows).
     const int segs = (d.W + 31) / 32;
-    const long long n_items = d.Q / d.W * segs;
+    const long long planes = d.Q / ((long long)d.H * d.W);   // images x slices
+    const long long n_items = planes * segs * runs;
     const long long first = (long long)blockIdx.x * 4 + wave, step = (long long)gridDim.x * 4;
-    const float* in = a.in;
-    for (long long item = first; item < n_items; item += step) {
-        const long long row = item / segs;
-        const int x = (int)(item - row * segs) * 32 + m;
-        const int y = (int)(row % d.H);
-        const int z = (int)((row / d.H) % d.D);
-        const long long q = row * d.W + x;
-        const bool px_ok = x < d.W;
-        float v[TAPS];
-#pragma unroll
-        for (int t = 0; t < TAPS; ++t) {
-            const int iz = KD == 1 ? 0 : t / 9 - 1, iy = (t / 3) % 3 - 1, ix = t % 3 - 1;
-            const bool ok = px_ok && (unsigned)(x + ix) < (unsigned)d.W && (unsigned)(y + iy) < (unsigned)d.H &&
-                            (KD == 1 || (unsigned)(z + iz) < (unsigned)d.D);
-            const long long off = ((long long)iz * d.H + iy) * d.W + ix;
-            const float f = in[ok ? 2 * (q + off) + h : h];   // clamped: the loads are unconditional
-            v[t] = ok ? (a.relu_in ? fmaxf(f, 0.f) : f) : 0.f;
+    // epilogue pieces: pass u of a 32-pixel x NP-channel block covers pixel (64 u + lane) / (NP / 4), channels 4 ((64 u + lane) % (NP / 4)) ..
+    constexpr int PASSES = NB * 4;
+    // loads and stores go through buffer resources: a wave-uniform row offset in a scalar register plus a 32-bit lane
+    // offset, so that no lane forms a 64-bit address (the launcher checks that both tensors are below 4 GB)
+    const __amdgpu_buffer_rsrc_t r_in = __builtin_amdgcn_make_buffer_rsrc((void*)a.in, 0, (unsigned)(d.Q * 8), 0x00020000);
+    constexpr unsigned ES = BF ? 2u : 4u;   // bytes per output element
+    const unsigned out_bytes = (unsigned)(d.Q * NN * ES);
+    const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, out_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_ref =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(a.mask_ref ? a.mask_ref : (const void*)a.out), 0, a.mask_ref ? out_bytes : 0u, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_add =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(a.add ? a.add : (const void*)a.out), 0, a.add ? out_bytes : 0u, 0x00020000);
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    constexpr bool PRE = NB * NH == 1;
+    // four output-sized values (16 bytes of float32, 8 of bfloat16) at lane offset off of the row at byte offset row
+    auto load_piece = [&](__amdgpu_buffer_rsrc_t r, unsigned off, unsigned row) -> u32x4 {
+        if constexpr (BF) {
+            const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(r, off, row, 0);
+            return u32x4{w[0], w[1], 0u, 0u};
+        } else {
+            return __builtin_amdgcn_raw_buffer_load_b128(r, off, row, 0);
         }
-        __builtin_amdgcn_sched_barrier(0);   // all tap loads are in flight before the first MFMA
-        const long long q0 = q - m;   // first pixel of the segment
-        const int x_seg = x - m;
+    };
+    auto piece_values = [&](u32x4 w) -> float4 {
+        if constexpr (BF)
+            return make_float4(bf16_to_f32((unsigned short)w[0]), bf16_to_f32((unsigned short)(w[0] >> 16)),
+                               bf16_to_f32((unsigned short)w[1]), bf16_to_f32((unsigned short)(w[1] >> 16)));
+        else
+            return make_float4(__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3]));
+    };
+    const int in_floor_i = a.relu_in ? 0 : (int)0x80000000;
+    const float out_floor = a.relu_out ? 0.f : -__builtin_huge_valf();
+    __shared__ __attribute__((aligned(16))) float bias_s[NN];
+    if ((int)threadIdx.x < NN) bias_s[threadIdx.x] = a.bias ? a.bias[threadIdx.x] : 0.f;
+    __syncthreads();
+    for (long long item = first; item < n_items; item += step) {
+        const int rn = (int)(item % runs);
+        const int seg = (int)((item / runs) % segs);
+        const long long plane = item / ((long long)runs * segs);
+        const int z = (int)(plane % d.D);
+        const int x_seg = 32 * seg, x = x_seg + m;
+        const int y0 = rn * run_len, y1 = y0 + run_len < d.H ? y0 + run_len : d.H;
+        // byte offset of this lane's value for column tap ix inside a row, clamped into the row (the value is dropped when
+        // the column is outside), and whether it counts
+        unsigned col_off[3], col_ok[3];   // (col_ok: all ones or zero)
 #pragma unroll
-        for (int hb = 0; hb < NH; ++hb) {
-            floatx16 acc[NB];
+        for (int ix = 0; ix < 3; ++ix) {
+            const int xc = x + ix - 1;
+            col_ok[ix] = (x < d.W && xc >= 0 && xc < d.W) ? 0xffffffffu : 0u;
+            const int xcl = xc < 0 ? 0 : (xc >= d.W ? d.W - 1 : xc);
+            col_off[ix] = (unsigned)(2 * xcl + h) * 4u;
+        }
+        const bool z_ok[3] = {z >= 1, true, z + 1 < d.D};
+        // epilogue piece u of this lane: inside the row?  byte offset from the segment's first piece (0 if not: the loads
+        // are unconditional)
+        bool okk_item[PASSES];
+        unsigned oo_item[PASSES];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+        for (int u = 0; u < PASSES; ++u) {
+            const int j = u * 64 + lane;
+            const int px = j / (NP / 4), cq = j - px * (NP / 4);
+            okk_item[u] = x_seg + px < d.W;
+            oo_item[u] = okk_item[u] ? (unsigned)(px * NN + 4 * cq) * ES : 0u;
+        }
+        float v[3][3][3];   // [slice tap][row slot][column tap]; row y + iy - 1 sits in slot (y + iy - 1 - (y0 - 1)) % 3
+        auto load_row = [&](int yy, int slot) __attribute__((always_inline)) {
+            const bool y_ok = yy >= 0 && yy < d.H;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+            for (int iz = 0; iz < 3; ++iz) {
+                // a row outside the image is read at row 0 of the tensor and masked away: the nine loads of a row are
+                // unconditional, so that they are all in flight together (a uniform branch around each made them wait
+                // for one another)
+                const bool ok = y_ok && z_ok[iz];   // uniform
+                const unsigned row = ok ? (unsigned)((((plane + iz - 1) * d.H + yy) * d.W) * 8) : 0u;   // byte offset of the row
+                const unsigned row_mask = ok ? 0xffffffffu : 0u;
 #pragma unroll
-            for (int t = 0; t < TAPS; ++t)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[hb][nb][t], v[t], acc[nb], 0, 0, 0);
-            // accumulator r of block nb: output channel NP*hb + 32*nb + 8*(r/4) + 4*h + r%4 of this lane's pixel.  The
-            // wave turns its 32 pixels x NP channels around in its own LDS rows, so that the epilogue's loads and stores
-            // cover whole runs of NP channels per pixel; LDS accesses of one wave complete in order, no barrier.
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    *reinterpret_cast<float4*>(stage + m * SS + 32 * nb + 8 * g + 4 * h) =
-                        make_float4(acc[nb][4 * g], acc[nb][4 * g + 1], acc[nb][4 * g + 2], acc[nb][4 * g + 3]);
-            __builtin_amdgcn_wave_barrier();
-            constexpr int PASSES = NB * 4, UN = 4;   // 64 pieces of four channels per pass
-#pragma unroll
-            for (int p0 = 0; p0 < PASSES; p0 += UN) {
-                float4 accv[UN], refv[UN], addv[UN];
-                long long oo[UN];
-                bool okk[UN];
-#pragma unroll
-                for (int u = 0; u < UN; ++u) {
-                    const int j = (p0 + u) * 64 + lane;
-                    const int px = j / (NP / 4), cq = j - px * (NP / 4);
-                    okk[u] = x_seg + px < d.W;
-                    oo[u] = okk[u] ? (q0 + px) * NN + NP * hb + 4 * cq : 0;   // clamped for the loads
-                    accv[u] = *reinterpret_cast<const float4*>(stage + px * SS + 4 * cq);
-                    refv[u] = make_float4(1.f, 1.f, 1.f, 1.f);
-                    addv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if constexpr (BF) {
-                        if (a.mask_ref) {
-                            const uint2 w2 = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned short*>(a.mask_ref) + oo[u]);
-                            refv[u] = make_float4(bf16_to_f32((unsigned short)w2.x), bf16_to_f32((unsigned short)(w2.x >> 16)),
-                                                  bf16_to_f32((unsigned short)w2.y), bf16_to_f32((unsigned short)(w2.y >> 16)));
-                        }
-                        if (a.add) {
-                            const uint2 w2 = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned short*>(a.add) + oo[u]);
-                            addv[u] = make_float4(bf16_to_f32((unsigned short)w2.x), bf16_to_f32((unsigned short)(w2.x >> 16)),
-                                                  bf16_to_f32((unsigned short)w2.y), bf16_to_f32((unsigned short)(w2.y >> 16)));
-                        }
-                    } else {
-                        if (a.mask_ref) refv[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.mask_ref) + oo[u]);
-                        if (a.add) addv[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.add) + oo[u]);
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < UN; ++u) {
-                    const int j = (p0 + u) * 64 + lane;
-                    const int co = NP * hb + 4 * (j % (NP / 4));
-                    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (a.bias) bv = make_float4(a.bias[co], a.bias[co + 1], a.bias[co + 2], a.bias[co + 3]);
-                    float xv[4] = {accv[u].x + bv.x, accv[u].y + bv.y, accv[u].z + bv.z, accv[u].w + bv.w};
-                    const float rr[4] = {refv[u].x, refv[u].y, refv[u].z, refv[u].w};
-                    const float aa[4] = {addv[u].x, addv[u].y, addv[u].z, addv[u].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (a.relu_out) xv[e] = fmaxf(xv[e], 0.f);
-                        if (a.mask_acc) xv[e] = rr[e] > 0.f ? xv[e] : 0.f;
-                        xv[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
-                    }
-                    if (okk[u]) {
-                        if constexpr (BF)
-                            *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.out) + oo[u]) =
-                                make_uint2(pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]));
-                        else
-                            *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + oo[u]) = make_float4(xv[0], xv[1], xv[2], xv[3]);
-                    }
+                for (int ix = 0; ix < 3; ++ix) {
+                    const unsigned f = __builtin_amdgcn_raw_buffer_load_b32(r_in, col_off[ix], row, 0);
+                    // (ReLU as a signed-integer maximum: negative floats are negative integers)
+                    const int fi = (int)(f & (row_mask & col_ok[ix]));
+                    v[iz][slot][ix] = __int_as_float(fi > in_floor_i ? fi : in_floor_i);
                 }
             }
-            __builtin_amdgcn_wave_barrier();
+        };
+        load_row(y0 - 1, 0);
+        load_row(y0, 1);
+        int y = y0;
+        // ROT: slot of row y - 1
+        auto row_step = [&](auto rot_c) __attribute__((always_inline)) {
+            constexpr int ROT = decltype(rot_c)::value;
+            load_row(y + 1, (ROT + 2) % 3);
+            const long long q0 = (plane * d.H + y) * d.W + x_seg;   // first pixel of the segment
+            // mask source and add operand of the row's pieces: requested here, used after the MFMAs (32-channel layers;
+            // the wider ones do not have the registers and load them in the epilogue)
+            u32x4 refq[PRE ? PASSES : 1], addq[PRE ? PASSES : 1];
+            if constexpr (EPI && PRE) {
+                const unsigned rb = (unsigned)((q0 * NN) * ES);
+#pragma unroll
+                for (int u = 0; u < PASSES; ++u) {
+                    refq[u] = load_piece(r_ref, oo_item[u], rb);
+                    addq[u] = load_piece(r_add, oo_item[u], rb);
+                }
+            }
+#pragma unroll
+            for (int hb = 0; hb < NH; ++hb) {
+                floatx16 acc[NB];
+                // row taps in the order upper, middle, lower: the lower row's values are the ones just requested
+#pragma unroll
+                for (int k = 0; k < TAPS; ++k) {
+                    const int iy = k / 9, iz = (k / 3) % 3, ix = k % 3, t = 9 * iz + 3 * iy + ix;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        floatx16 c;
+                        if (k == 0) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) c[r] = 0.f;
+                        } else {
+                            c = acc[nb];
+                        }
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[hb][nb][t], v[iz][(ROT + iy) % 3][ix], c, 0, 0, 0);
+                    }
+                }
+                // accumulator r of block nb: output channel NP*hb + 32*nb + 8*(r/4) + 4*h + r%4 of this lane's pixel.  The
+                // wave turns its 32 pixels x NP channels around in its own LDS rows, so that the epilogue's loads and stores
+                // cover whole runs of NP channels per pixel; LDS accesses of one wave complete in order, no barrier.
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        *reinterpret_cast<float4*>(stage + m * SS + 32 * nb + 8 * g + 4 * h) =
+                            make_float4(acc[nb][4 * g], acc[nb][4 * g + 1], acc[nb][4 * g + 2], acc[nb][4 * g + 3]);
+                __builtin_amdgcn_wave_barrier();
+                constexpr int UN = 4;   // 64 pieces of four channels per pass
+                const unsigned row_byte = (unsigned)((q0 * NN + NP * hb) * ES);   // uniform: byte offset of the segment's first piece
+#pragma unroll
+                for (int p0 = 0; p0 < PASSES; p0 += UN) {
+                    float4 accv[UN], refv[UN], addv[UN];
+                    unsigned oo[UN];
+                    bool okk[UN];
+#pragma unroll
+                    for (int u = 0; u < UN; ++u) {
+                        const int j = (p0 + u) * 64 + lane;
+                        const int px = j / (NP / 4), cq = j - px * (NP / 4);
+                        okk[u] = okk_item[p0 + u];
+                        oo[u] = oo_item[p0 + u];
+                        accv[u] = *reinterpret_cast<const float4*>(stage + px * SS + 4 * cq);
+                        refv[u] = make_float4(1.f, 1.f, 1.f, 1.f);
+                        addv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if constexpr (EPI) {   // (an absent operand reads zeros through its empty resource and is not used)
+                            const u32x4 w2 = PRE ? refq[PRE ? p0 + u : 0] : load_piece(r_ref, oo[u], row_byte);
+                            const u32x4 w3 = PRE ? addq[PRE ? p0 + u : 0] : load_piece(r_add, oo[u], row_byte);
+                            if (a.mask_ref) refv[u] = piece_values(w2);
+                            addv[u] = piece_values(w3);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < UN; ++u) {
+                        const int j = (p0 + u) * 64 + lane;
+                        const int co = NP * hb + 4 * (j % (NP / 4));
+                        const float4 bv = *reinterpret_cast<const float4*>(bias_s + co);
+                        float xv[4] = {accv[u].x + bv.x, accv[u].y + bv.y, accv[u].z + bv.z, accv[u].w + bv.w};
+                        const float rr[4] = {refv[u].x, refv[u].y, refv[u].z, refv[u].w};
+                        const float aa[4] = {addv[u].x, addv[u].y, addv[u].z, addv[u].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            xv[e] = fmaxf(xv[e], out_floor);
+                            if constexpr (EPI) {
+                                if (a.mask_acc) xv[e] = rr[e] > 0.f ? xv[e] : 0.f;
+                                xv[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
+                            }
+                        }
+                        if (okk[u]) {
+                            if constexpr (BF) {
+                                const u32x2 pk = {pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3])};
+                                __builtin_amdgcn_raw_buffer_store_b64(pk, r_out, oo[u], row_byte, 0);
+                            } else {
+                                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                                const f32x4 pk = {xv[0], xv[1], xv[2], xv[3]};
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((ext_vector_type(4))) unsigned, pk), r_out, oo[u], row_byte, 0);
+                            }
+                        }
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+            ++y;
+        };
+        while (true) {
+            row_step(std::integral_constant<int, 0>{});
+            if (y >= y1) break;
+            row_step(std::integral_constant<int, 1>{});
+            if (y >= y1) break;
+            row_step(std::integral_constant<int, 2>{});
+            if (y >= y1) break;
         }
     }
 }
 
-template <int KD, int NB, int NH, bool BF>
-static void launch_thin_in_mfma_t(const ThinInMfmaArgs& a, hipStream_t st) {
+template <int KD, int NB, int NH, bool BF, bool EPI>
+static void launch_thin_in_mfma_e(const ThinInMfmaArgs& a, hipStream_t st) {
     static const int per_cu = [] {   // persistent waves: what the instantiation's registers allow, at most four workgroups
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, conv_thin_in_mfma_kernel<KD, NB, NH, BF>, 256, 0) != hipSuccess) n = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, conv_thin_in_mfma_kernel<KD, NB, NH, BF, EPI>, 256, 0) != hipSuccess) n = 1;
         return n < 1 ? 1 : (n > 4 ? 4 : n);
     }();
-    const long long n_items = a.d.Q / a.d.W * ((a.d.W + 31) / 32);
+    // runs of rows per (slice, segment) column: the split that minimises (columns per wave) x (run length + the two rows a
+    // run loads before its first)
+    const long long cols = a.d.Q / ((long long)a.d.H * a.d.W) * ((a.d.W + 31) / 32), waves = 4LL * 256 * per_cu;
+    int runs = 1, run_len = a.d.H;
+    double best = 1e300;
+    for (int n = 1; n <= a.d.H; ++n) {
+        const int len = (a.d.H + n - 1) / n;
+        if ((a.d.H + len - 1) / len != n) continue;
+        const long long items = cols * n;
+        const double cost = (double)((items + waves - 1) / waves) * (len + 2.0);
+        if (cost < best) { best = cost; runs = n; run_len = len; }
+    }
+    const long long n_items = cols * runs;
     const long long want = (n_items + 3) / 4, cap = 256LL * per_cu;
-    hipLaunchKernelGGL((conv_thin_in_mfma_kernel<KD, NB, NH, BF>), dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((conv_thin_in_mfma_kernel<KD, NB, NH, BF, EPI>), dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, st, a, runs, run_len);
+}
+
+template <int KD, int NB, int NH, bool BF>
+static void launch_thin_in_mfma_t(const ThinInMfmaArgs& a, hipStream_t st) {
+    if (a.mask_ref || a.add) launch_thin_in_mfma_e<KD, NB, NH, BF, true>(a, st);
+    else launch_thin_in_mfma_e<KD, NB, NH, BF, false>(a, st);
 }
 
 template <int KD, bool BF>
@@ -697,6 +818,8 @@ bool conv_thin_in_mfma_applies(const PixDims& d, int Nn) {
     // speed of its stores (knee: 38 against 40 us forward, 54 against 54 us data gradient; brain, bfloat16 output:
     // 116 against 96 us forward, 231 against 265 us data gradient); with 54 it does not
     if (!on || !(d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3)) return false;
+    // byte offsets into the input and the output are 32 bits in the kernel
+    if ((double)d.Q * 8.0 >= 4.0e9 || (double)d.Q * Nn * 4.0 >= 4.0e9) return false;
     return Nn == 32 || Nn == 64 || Nn == 128;
 }
 

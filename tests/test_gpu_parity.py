@@ -654,8 +654,9 @@ def test_direct_kernels_still_cover_the_winograd_shapes(kernel_policy):
 def test_fallback_kernels_of_the_two_channel_layers_and_the_27_tap_gradient(kernel_policy):
     """GLEAM_POLICY_NO_THIN_MFMA, _NO_BF16_2D, _NO_WGRAD_BALANCE (with _NO_WINOGRAD, which otherwise takes the 27-tap
     layer) and _NO_FRAME_WALK route the shapes that normally take the matrix-core two-channel kernels, the
-    two-dimensional-tile bf16 kernel, the balanced 27-tap weight gradient and the frame walk of the temporal weight
-    gradient through the kernels they replaced: 2D fp32, 2D bf16, 3D and 2D+t module steps on those against the oracle."""
+    two-dimensional-tile and register-resident-weights bf16 kernels, the balanced 27-tap weight gradient and the walking
+    weight gradients (along the frames of a temporal layer, down the rows of a 128-channel bf16 layer) through the
+    kernels they replaced: 2D fp32, 2D bf16, 3D and 2D+t module steps on those against the oracle."""
     kernel_policy(gb.POLICY_NO_THIN_MFMA | gb.POLICY_NO_BF16_2D | gb.POLICY_NO_WGRAD_BALANCE | gb.POLICY_NO_WINOGRAD |
                   gb.POLICY_NO_FRAME_WALK)
     cases = [(synth.Geom(2, 1, 2, 1, 1, 10, 46), synth.chain_prox([2, 64, 64, 2], [K2] * 3), TOL),
