@@ -537,21 +537,23 @@ hipError_t launch_conv_thin_out_mfma(const void* in, const float* wts, const flo
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Two-channel-INPUT 3x3x3 convolution (first layer of the prox; data gradient of the last layer) on the matrix cores.
+// Two-channel-INPUT 3x3 (KD = 1) or 3x3x3 (KD = 3) convolution (first layer of the prox; data gradient of the last
+// layer) on the matrix cores.
 //
 // out[p][n] = b[n] + sum_{tap,e} W[n][tap][e] * in[p + off(tap)][e] with e = 0, 1: one v_mfma_f32_32x32x2_f32 per
 // tap and block of 32 output channels, its depth of two being exactly the two input channels.  Lane (m, h) of a
-// wave supplies W[32*nb + m][tap][h] (registers, for the life of the wave) and in[p_m + off(tap)][h] (one 4-byte
-// load per tap, 256 contiguous bytes per wave, zero outside the grid), and ends up with 16 output channels of its
-// pixel in groups of four, which go through the usual fused epilogue (bias, ReLU, ReLU mask, add) into 16-byte
-// (float32) or 8-byte (bfloat16) stores after a turn through the wave's own LDS rows.  No barriers: every wave
-// walks 32-pixel row segments on its own.  The kernel it replaces for these shapes computes on the vector ALUs, 2*taps multiply-adds per output.
+// wave supplies W[32*nb + m][tap][h] (registers, for the life of the wave) and in[p_m + off(tap)][h] (4-byte loads,
+// 256 contiguous bytes per wave, zero outside the grid), and ends up with 16 output channels of its pixel in groups
+// of four, which go through the usual fused epilogue (bias, ReLU, ReLU mask, add) into 16-byte (float32) or 8-byte
+// (bfloat16) stores after a turn through the wave's own LDS rows.  No barriers in the loop: every wave walks down
+// 32-pixel column segments on its own.  The kernel it replaces for these shapes computes on the vector ALUs,
+// 2*taps multiply-adds per output.
 
 template <int KD, int NB, int NH, bool BF, bool EPI>   // EPI: the call has a ReLU mask source or an add operand
 __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a, int runs, int run_len) {
     // NH passes of NB blocks of 32 output channels each: Nn = 32 * NB * NH
-    static_assert(KD == 3, "the walk keeps three slices of three rows");
-    constexpr int TAPS = 27, NP = 32 * NB, NN = NP * NH, SS = NP + 4;   // SS: floats per pixel row of the wave's LDS rows
+    static_assert(KD == 1 || KD == 3, "the walk keeps KD slices of three rows");
+    constexpr int TAPS = 9 * KD, NP = 32 * NB, NN = NP * NH, SS = NP + 4;   // SS: floats per pixel row of the wave's LDS rows
     __shared__ __attribute__((aligned(16))) float stage_all[4 * 32 * SS];
     const PixDims d = a.d;
     const int lane = threadIdx.x & 63;
@@ -566,8 +568,8 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
 #pragma unroll
             for (int t = 0; t < TAPS; ++t)
                 wreg[hb][nb][t] = a.w[(NP * hb + 32 * nb + m) * a.sn + (a.flip ? TAPS - 1 - t : t) * a.st + h * a.sk];
-    // A wave walks down the rows of one 32-pixel column segment of one slice: of the 27 input values a row needs (three
-    // slices x three rows x three columns) the 18 of the two upper rows are the previous row's, so a row costs 9 loads,
+    // A wave walks down the rows of one 32-pixel column segment of one slice: of the 9 KD input values a row needs (KD
+    // slices x three rows x three columns) those of the two upper rows are the previous row's, so a row costs 3 KD loads,
     // and all of its addresses are a wave-uniform row pointer plus a lane constant.  Item = (slice of an image, segment,
     // run of run_len rows).
     const int segs = (d.W + 31) / 32;
@@ -627,7 +629,7 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
             const int xcl = xc < 0 ? 0 : (xc >= d.W ? d.W - 1 : xc);
             col_off[ix] = (unsigned)(2 * xcl + h) * 4u;
         }
-        const bool z_ok[3] = {z >= 1, true, z + 1 < d.D};
+        const bool z_ok[3] = {KD == 1 || z >= 1, true, KD == 1 || z + 1 < d.D};   // (KD = 1: only [0] is used)
         // epilogue piece u of this lane: inside the row?  byte offset from the segment's first piece (0 if not: the loads
         // are unconditional)
         bool okk_item[PASSES];
@@ -639,16 +641,16 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
             okk_item[u] = x_seg + px < d.W;
             oo_item[u] = okk_item[u] ? (unsigned)(px * NN + 4 * cq) * ES : 0u;
         }
-        float v[3][3][3];   // [slice tap][row slot][column tap]; row y + iy - 1 sits in slot (y + iy - 1 - (y0 - 1)) % 3
+        float v[KD][3][3];   // [slice tap][row slot][column tap]; row y + iy - 1 sits in slot (y + iy - 1 - (y0 - 1)) % 3
         auto load_row = [&](int yy, int slot) __attribute__((always_inline)) {
             const bool y_ok = yy >= 0 && yy < d.H;
 #pragma unroll
-            for (int iz = 0; iz < 3; ++iz) {
+            for (int iz = 0; iz < KD; ++iz) {
                 // a row outside the image is read at row 0 of the tensor and masked away: the nine loads of a row are
                 // unconditional, so that they are all in flight together (a uniform branch around each made them wait
                 // for one another)
                 const bool ok = y_ok && z_ok[iz];   // uniform
-                const unsigned row = ok ? (unsigned)((((plane + iz - 1) * d.H + yy) * d.W) * 8) : 0u;   // byte offset of the row
+                const unsigned row = ok ? (unsigned)((((plane + iz - KD / 2) * d.H + yy) * d.W) * 8) : 0u;   // byte offset of the row
                 const unsigned row_mask = ok ? 0xffffffffu : 0u;
 #pragma unroll
                 for (int ix = 0; ix < 3; ++ix) {
@@ -684,7 +686,7 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
                 // row taps in the order upper, middle, lower: the lower row's values are the ones just requested
 #pragma unroll
                 for (int k = 0; k < TAPS; ++k) {
-                    const int iy = k / 9, iz = (k / 3) % 3, ix = k % 3, t = 9 * iz + 3 * iy + ix;
+                    const int iy = k / (3 * KD), iz = (k / 3) % KD, ix = k % 3, t = 9 * iz + 3 * iy + ix;
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
                         floatx16 c;
@@ -814,10 +816,7 @@ static void launch_thin_in_mfma_n(const ThinInMfmaArgs& a, hipStream_t st) {
 
 bool conv_thin_in_mfma_applies(const PixDims& d, int Nn) {
     const bool on = !(kernel_policy() & GLEAM_POLICY_NO_THIN_MFMA);   // else the vector-ALU kernel
-    // 3x3 layers in the plane stay on the vector-ALU kernel: with 18 multiply-adds per output it already runs at the
-    // speed of its stores (knee: 38 against 40 us forward, 54 against 54 us data gradient; brain, bfloat16 output:
-    // 116 against 96 us forward, 231 against 265 us data gradient); with 54 it does not
-    if (!on || !(d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3)) return false;
+    if (!on || !(d.kt == 1 && (d.kd == 3 || d.kd == 1) && d.kh == 3 && d.kw == 3)) return false;
     // byte offsets into the input and the output are 32 bits in the kernel
     if ((double)d.Q * 8.0 >= 4.0e9 || (double)d.Q * Nn * 4.0 >= 4.0e9) return false;
     return Nn == 32 || Nn == 64 || Nn == 128;
@@ -825,8 +824,13 @@ bool conv_thin_in_mfma_applies(const PixDims& d, int Nn) {
 
 hipError_t launch_conv_thin_in_mfma(const ThinInMfmaArgs& a, bool bf, hipStream_t st) {
     if (!conv_thin_in_mfma_applies(a.d, a.Nn)) return hipErrorInvalidValue;
-    if (bf) launch_thin_in_mfma_n<3, true>(a, st);
-    else launch_thin_in_mfma_n<3, false>(a, st);
+    if (a.d.kd == 3) {
+        if (bf) launch_thin_in_mfma_n<3, true>(a, st);
+        else launch_thin_in_mfma_n<3, false>(a, st);
+    } else {
+        if (bf) launch_thin_in_mfma_n<1, true>(a, st);
+        else launch_thin_in_mfma_n<1, false>(a, st);
+    }
     return hipGetLastError();
 }
 
