@@ -2088,6 +2088,14 @@ static hipError_t launch_wgrad_thin(const WgradArgs& a, float* bias_partial, boo
     const bool k2 = d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3, k3 = d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3;
     const bool kt3 = d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1;
     if (!k2 && !k3 && !kt3) return hipSuccess;
+    if (wgrad_thin_walk_applies(d, wide, bf)) {   // 3x3 / 3x3x3 with 32, 64 or 128 wide channels: matrix cores
+        WgradThinWalkArgs t{};
+        t.partial = a.partial; t.bias_partial = bias_partial; t.relu_in = a.relu_in; t.d = d; t.WC = wide; t.bf = bf ? 1 : 0;
+        if (a.Ci == 2) { t.wide = a.g; t.thin = a.a; t.thin_in = 1; }
+        else { t.wide = a.a; t.thin = a.g; t.thin_in = 0; }
+        *hit = true;
+        return launch_wgrad_thin_walk(t, partial_floats, used_split, st);
+    }
     // HBM-bound: one workgroup per image row up to kThinSplit partials (as many as the scratch holds)
     long long ts = d.Q / d.W;
     if (ts > kThinSplit) ts = kThinSplit;

@@ -269,6 +269,19 @@ struct ThinInMfmaArgs {
     PixDims d;
 };
 bool conv_thin_in_mfma_applies(const PixDims& d, int Nn);
+
+// Weight gradient of a layer with the 2-channel image on one side, 3x3 or 3x3x3 taps, on the matrix cores (prox_thin.hip)
+struct WgradThinWalkArgs {
+    const void* wide;      // [Q][WC] float32 or bfloat16 (bf)
+    const float* thin;     // [Q][2]
+    float* partial;        // [workgroups][Co][taps][Ci]
+    float* bias_partial;   // [workgroups][Co] or null
+    int WC, relu_in, thin_in, bf;   // thin_in: the layer's input is the thin side (wide = output gradient)
+    PixDims d;
+};
+constexpr int kThinWalkSplit = 1024;   // most partial blocks the kernel writes
+bool wgrad_thin_walk_applies(const PixDims& d, int WC, bool bf);
+hipError_t launch_wgrad_thin_walk(const WgradThinWalkArgs& a, size_t partial_floats, int* used_split, hipStream_t stream);
 hipError_t launch_conv_thin_in_mfma(const ThinInMfmaArgs& a, bool bf, hipStream_t stream);
 
 struct ConvBf16Args {

@@ -834,4 +834,254 @@ hipError_t launch_conv_thin_in_mfma(const ThinInMfmaArgs& a, bool bf, hipStream_
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Weight gradient of a layer with the 2-channel image on one side, 3x3 (KD = 1) or 3x3x3 (KD = 3) taps, on the matrix
+// cores:
+//   THIN_IN  (first layer):  dw[c][tap][e] = sum_q wide[q][c] * thin[q + off(tap)][e]      wide = output gradient
+//   !THIN_IN (last layer):   dw[e][tap][c] = sum_q wide[q][c] * thin[q - off(tap)][e]      wide = input activation
+// One v_mfma_f32_32x32x2_f32 takes two pixels as its depth: A = the wide tensor (rows = 32 channels, lane (m, h) loads
+// channel m of pixel h: 256 contiguous bytes per wave), B = the thin tensor seen through the taps (columns = (tap, e)
+// pairs, 18 or 54 of them in one or two blocks of 32; lane (n, h) loads the value its pair needs for pixel h).  A wave
+// walks down the rows of a 32-pixel column segment; all loads go through buffer resources: the wide one spans one image
+// row (pixels past the row's end arrive as zeros), the thin one the tensor, and a lane whose tap row lies outside the
+// volume gets an offset outside of it (zeros, no select per load).  Only in the first and last segment of a row the
+// columns next to the image edge need a per-load check.  The vector-ALU kernel this replaces for these shapes spends
+// 2 * taps multiply-adds per wide value and is bound by them.
+struct WgradThinWalkKArgs {
+    WgradThinWalkArgs a;
+    int runs, run_len;
+};
+
+template <int KD, int NCB, bool THIN_IN, bool BF>
+__global__ __launch_bounds__(256) void wgrad_thin_walk_kernel(WgradThinWalkKArgs ka) {
+    constexpr int TAPS = 9 * KD, NCOL = 2 * TAPS, NBLK = (NCOL + 31) / 32, WC = 32 * NCB;
+    constexpr int ES = BF ? 2 : 4;
+    constexpr unsigned kOutside = 0x80000000u;
+    __shared__ float red[4][NCB * NBLK * 16 * 64 > 64 * NCB ? NCB * NBLK * 16 * 64 : 64 * NCB];
+    const WgradThinWalkArgs& a = ka.a;
+    const PixDims d = a.d;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    constexpr int sgn = THIN_IN ? 1 : -1;
+    // this lane's (tap, e) pair per column block
+    int dz[NBLK], dy[NBLK], dx[NBLK], ee[NBLK];
+    bool col_used[NBLK];
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int n = 32 * b + m, tap = n >> 1;
+        col_used[b] = n < NCOL;
+        ee[b] = n & 1;
+        dz[b] = KD == 1 ? 0 : sgn * (tap / 9 - 1);
+        dy[b] = sgn * ((tap / 3) % 3 - 1);
+        dx[b] = sgn * (tap % 3 - 1);
+    }
+    floatx16 acc[NCB][NBLK];
+#pragma unroll
+    for (int c = 0; c < NCB; ++c)
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[c][b][r] = 0.f;
+    float bs[THIN_IN ? NCB : 1];
+#pragma unroll
+    for (int c = 0; c < (THIN_IN ? NCB : 1); ++c) bs[c] = 0.f;
+
+    const int segs = (d.W + 31) / 32;
+    const long long planes = d.Q / ((long long)d.H * d.W);
+    const long long n_items = planes * segs * ka.runs;
+    const __amdgpu_buffer_rsrc_t r_thin = __builtin_amdgcn_make_buffer_rsrc((void*)a.thin, 0, (unsigned)(d.Q * 8), 0x00020000);
+    const unsigned wide_row_bytes = (unsigned)d.W * WC * ES;
+    const int relu_floor = a.relu_in ? 0 : (int)0x80000000;   // ReLU as a signed-integer maximum on the bit pattern
+
+    for (long long item = (long long)blockIdx.x * 4 + wave; item < n_items; item += (long long)gridDim.x * 4) {
+        const int rn = (int)(item % ka.runs);
+        const int seg = (int)((item / ka.runs) % segs);
+        const long long plane = item / ((long long)ka.runs * segs);
+        const int z = (int)(plane % d.D);
+        const int x_seg = 32 * seg;
+        const int y0 = rn * ka.run_len, y1 = y0 + ka.run_len < d.H ? y0 + ka.run_len : d.H;
+        const bool interior = x_seg >= 1 && x_seg + 33 <= d.W;   // uniform: every tap column of every pixel is inside the row
+        // thin side: byte offset of this lane's value for pixel pair 0 of row y0, and which pairs are inside the row
+        unsigned vo[NBLK], xbad[NBLK];
+        bool z_ok[NBLK];
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            z_ok[b] = col_used[b] && (KD == 1 || (unsigned)(z + dz[b]) < (unsigned)d.D);
+            const int xl = x_seg + h + dx[b];
+            vo[b] = (unsigned)(((((plane + dz[b]) * d.H + (y0 + dy[b])) * d.W + xl) * 2 + ee[b]) * 4);
+            unsigned bad = 0u;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) bad |= ((unsigned)(xl + 2 * j) < (unsigned)d.W ? 0u : 1u) << j;
+            xbad[b] = bad;
+        }
+        const unsigned wide_lane = (unsigned)((h * WC + m) * ES);
+        for (int y = y0; y < y1; ++y) {
+            const __amdgpu_buffer_rsrc_t r_wide = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)((const char*)a.wide + ((plane * d.H + y) * d.W) * (long long)(WC * ES)), 0, wide_row_bytes, 0x00020000);
+            unsigned vrow[NBLK];
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const bool ok = z_ok[b] && (unsigned)(y + dy[b]) < (unsigned)d.H;
+                vrow[b] = ok ? vo[b] : kOutside;
+                vo[b] += (unsigned)d.W * 8u;
+            }
+            float av[NCB][16], bv[NBLK][16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+#pragma unroll
+                for (int c = 0; c < NCB; ++c) {
+                    const unsigned off = wide_lane + (unsigned)(((x_seg + 2 * j) * WC + 32 * c) * ES);
+                    int bits;
+                    if constexpr (BF) bits = (int)((unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_wide, off, 0, 0) << 16);
+                    else bits = (int)__builtin_amdgcn_raw_buffer_load_b32(r_wide, off, 0, 0);
+                    if (!THIN_IN) bits = bits > relu_floor ? bits : relu_floor;
+                    av[c][j] = __int_as_float(bits);
+                }
+            }
+            if (interior) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+#pragma unroll
+                    for (int b = 0; b < NBLK; ++b) {
+                        int bits = (int)__builtin_amdgcn_raw_buffer_load_b32(r_thin, vrow[b] + 16u * j, 0, 0);
+                        if (THIN_IN) bits = bits > relu_floor ? bits : relu_floor;
+                        bv[b][j] = __int_as_float(bits);
+                    }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+#pragma unroll
+                    for (int b = 0; b < NBLK; ++b) {
+                        const unsigned o = ((xbad[b] >> j) & 1u) ? kOutside : vrow[b];
+                        int bits = (int)__builtin_amdgcn_raw_buffer_load_b32(r_thin, o + 16u * j, 0, 0);
+                        if (THIN_IN) bits = bits > relu_floor ? bits : relu_floor;
+                        bv[b][j] = __int_as_float(bits);
+                    }
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+#pragma unroll
+                for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                    for (int b = 0; b < NBLK; ++b) acc[c][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c][j], bv[b][j], acc[c][b], 0, 0, 0);
+                // bias gradient: column sums of the output gradient, which is the wide tensor (THIN_IN) or the thin one
+                // (there the centre tap's columns hold the pixel itself)
+                if (THIN_IN) {
+#pragma unroll
+                    for (int c = 0; c < NCB; ++c) bs[c] += av[c][j];
+                } else {
+                    bs[0] += bv[0][j];
+                }
+            }
+        }
+    }
+
+    // fold the four waves of the workgroup, then write its partial block in dw layout
+    constexpr int NACC = NCB * NBLK * 16;
+    const int Co = THIN_IN ? WC : 2, Ci = THIN_IN ? 2 : WC;
+    float* dst = a.partial + (size_t)blockIdx.x * Co * TAPS * Ci;
+#pragma unroll
+    for (int c = 0; c < NCB; ++c)
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) red[wave][((c * NBLK + b) * 16 + r) * 64 + lane] = acc[c][b][r];
+    __syncthreads();
+    for (int i = threadIdx.x; i < NACC * 64; i += 256) {
+        const float sum = (red[0][i] + red[1][i]) + (red[2][i] + red[3][i]);
+        const int l = i & 63, r = (i >> 6) & 15, cbk = i >> 10, b = cbk % NBLK, c = cbk / NBLK;
+        const int n = 32 * b + (l & 31), ch = 32 * c + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        if (n < NCOL) {
+            const int tap = n >> 1, e = n & 1;
+            dst[THIN_IN ? ((size_t)ch * TAPS + tap) * 2 + e : ((size_t)e * TAPS + tap) * WC + ch] = sum;
+        }
+    }
+    if (a.bias_partial != nullptr) {
+        __syncthreads();
+        if (THIN_IN) {
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) {
+                const float tot = bs[c] + __shfl_xor(bs[c], 32);
+                if (h == 0) red[wave][32 * c + m] = tot;
+            }
+            __syncthreads();
+            if ((int)threadIdx.x < WC)
+                a.bias_partial[(size_t)blockIdx.x * Co + threadIdx.x] =
+                    (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+        } else {
+            const float tot = bs[0] + __shfl_xor(bs[0], 32);
+            if (h == 0) red[wave][m] = tot;
+            __syncthreads();
+            if (threadIdx.x < 2) {
+                const int col = 2 * (TAPS / 2) + threadIdx.x;   // centre tap
+                a.bias_partial[(size_t)blockIdx.x * Co + threadIdx.x] = (red[0][col] + red[1][col]) + (red[2][col] + red[3][col]);
+            }
+        }
+    }
+}
+
+bool wgrad_thin_walk_applies(const PixDims& d, int WC, bool bf) {
+    if (kernel_policy() & GLEAM_POLICY_NO_THIN_MFMA) return false;
+    if (!(d.kt == 1 && (d.kd == 1 || d.kd == 3) && d.kh == 3 && d.kw == 3)) return false;
+    // byte offsets into the thin tensor and into an image row of the wide one are 32 bits in the kernel
+    if ((double)d.Q * 8.0 >= 2.0e9 || (double)d.W * WC * 4.0 >= 2.0e9) return false;
+    (void)bf;
+    return WC == 32 || WC == 64 || WC == 128;
+}
+
+template <int KD, int NCB, bool THIN_IN, bool BF>
+static hipError_t launch_wgrad_thin_walk_t(const WgradThinWalkArgs& a, size_t partial_floats, int* used_split, hipStream_t st) {
+    static const int per_cu = [] {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, wgrad_thin_walk_kernel<KD, NCB, THIN_IN, BF>, 256, 0) != hipSuccess) n = 1;
+        return n < 1 ? 1 : (n > 4 ? 4 : n);
+    }();
+    const PixDims& d = a.d;
+    const long long cols = d.Q / ((long long)d.H * d.W) * ((d.W + 31) / 32);
+    const size_t block = (size_t)(32 * NCB) * 9 * KD * 2;
+    long long wgs = 256LL * per_cu;
+    const long long fit = (long long)(partial_floats / block);
+    if (wgs > fit) wgs = fit;
+    if (wgs > kThinWalkSplit) wgs = kThinWalkSplit;
+    if (wgs < 1) return hipErrorInvalidValue;
+    WgradThinWalkKArgs ka{a, 1, d.H};
+    double best = 1e300;
+    for (int n = 1; n <= d.H; ++n) {
+        const int len = (d.H + n - 1) / n;
+        if ((d.H + len - 1) / len != n) continue;
+        const long long items = cols * n;
+        const double cost = (double)((items + 4 * wgs - 1) / (4 * wgs)) * (len + 0.5);
+        if (cost < best) { best = cost; ka.runs = n; ka.run_len = len; }
+    }
+    const long long want = (cols * ka.runs + 3) / 4;
+    const long long gx = want < wgs ? want : wgs;
+    hipLaunchKernelGGL((wgrad_thin_walk_kernel<KD, NCB, THIN_IN, BF>), dim3((unsigned)gx), dim3(256), 0, st, ka);
+    *used_split = (int)gx;
+    return hipGetLastError();
+}
+
+template <int KD, bool THIN_IN, bool BF>
+static hipError_t launch_wgrad_thin_walk_c(const WgradThinWalkArgs& a, size_t partial_floats, int* used_split, hipStream_t st) {
+    switch (a.WC / 32) {
+        case 1: return launch_wgrad_thin_walk_t<KD, 1, THIN_IN, BF>(a, partial_floats, used_split, st);
+        case 2: return launch_wgrad_thin_walk_t<KD, 2, THIN_IN, BF>(a, partial_floats, used_split, st);
+        default: return launch_wgrad_thin_walk_t<KD, 4, THIN_IN, BF>(a, partial_floats, used_split, st);
+    }
+}
+
+hipError_t launch_wgrad_thin_walk(const WgradThinWalkArgs& a, size_t partial_floats, int* used_split, hipStream_t st) {
+    if (!wgrad_thin_walk_applies(a.d, a.WC, a.bf != 0)) return hipErrorInvalidValue;
+#define GLEAM_TW(KD_)                                                                                       \
+    if (a.thin_in) {                                                                                        \
+        if (a.bf) return launch_wgrad_thin_walk_c<KD_, true, true>(a, partial_floats, used_split, st);     \
+        return launch_wgrad_thin_walk_c<KD_, true, false>(a, partial_floats, used_split, st);              \
+    } else {                                                                                                \
+        if (a.bf) return launch_wgrad_thin_walk_c<KD_, false, true>(a, partial_floats, used_split, st);    \
+        return launch_wgrad_thin_walk_c<KD_, false, false>(a, partial_floats, used_split, st);             \
+    }
+    if (a.d.kd == 3) { GLEAM_TW(3) } else { GLEAM_TW(1) }
+#undef GLEAM_TW
+}
+
 }  // namespace gleam
