@@ -842,11 +842,12 @@ hipError_t launch_conv_thin_in_mfma(const ThinInMfmaArgs& a, bool bf, hipStream_
 // One v_mfma_f32_32x32x2_f32 takes two pixels as its depth: A = the wide tensor (rows = 32 channels, lane (m, h) loads
 // channel m of pixel h: 256 contiguous bytes per wave), B = the thin tensor seen through the taps (columns = (tap, e)
 // pairs, 18 or 54 of them in one or two blocks of 32; lane (n, h) loads the value its pair needs for pixel h).  A wave
-// walks down the rows of a 32-pixel column segment; all loads go through buffer resources: the wide one spans one image
-// row (pixels past the row's end arrive as zeros), the thin one the tensor, and a lane whose tap row lies outside the
-// volume gets an offset outside of it (zeros, no select per load).  Only in the first and last segment of a row the
-// columns next to the image edge need a per-load check.  The vector-ALU kernel this replaces for these shapes spends
-// 2 * taps multiply-adds per wide value and is bound by them.
+// walks down the rows of a 32-pixel column segment and keeps the thin rows around the current row in its own LDS rows
+// (one new row per slice tap and image row, fetched a row ahead), from where the B operands are 4-byte LDS reads at
+// lane-constant offsets (read straight from memory, a wave-wide load gathered from up to 27 rows and took as long as
+// the MFMAs).  All global loads go through buffer resources that span one image row: pixels outside the row arrive
+// as zeros and a row outside the volume gets a resource of size 0, so nothing is masked.  The vector-ALU kernel this
+// replaces for these shapes spends 2 * taps multiply-adds per wide value and is bound by them.
 struct WgradThinWalkKArgs {
     WgradThinWalkArgs a;
     int runs, run_len;
@@ -857,12 +858,22 @@ __global__ __launch_bounds__(256) void wgrad_thin_walk_kernel(WgradThinWalkKArgs
     constexpr int TAPS = 9 * KD, NCOL = 2 * TAPS, NBLK = (NCOL + 31) / 32, WC = 32 * NCB;
     constexpr int ES = BF ? 2 : 4;
     constexpr unsigned kOutside = 0x80000000u;
-    __shared__ float red[4][NCB * NBLK * 16 * 64 > 64 * NCB ? NCB * NBLK * 16 * 64 : 64 * NCB];
+    __shared__ float red[2][NCB * NBLK * 16 * 64];
+    // bfloat16 wide tensors with 64 channels or more are loaded as channel pairs (4 bytes per lane): row i of block c is
+    // channel 64 (c / 2) + 2 i + c % 2 then, else channel 32 c + i
+    constexpr bool PAIRS = BF && NCB >= 2;
+    auto chan = [](int c, int i) { return PAIRS ? 64 * (c / 2) + 2 * i + (c & 1) : 32 * c + i; };
+    // the thin rows around the current row, per wave: [slice tap][ring of 4 rows][36 pixels][2]; pixel pp = image column
+    // x_seg - 1 + pp.  Rows and columns outside the volume hold zeros (they are loaded through a resource that spans one
+    // image row, of size 0 for a row outside), so the B operand reads need no masks.
+    constexpr int kSlabPx = 36;
+    __shared__ __attribute__((aligned(8))) float slab_all[4][KD * 4 * kSlabPx * 2];
     const WgradThinWalkArgs& a = ka.a;
     const PixDims d = a.d;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int m = lane & 31, h = lane >> 5;
+    float* const slab = slab_all[wave];
     constexpr int sgn = THIN_IN ? 1 : -1;
     // this lane's (tap, e) pair per column block
     int dz[NBLK], dy[NBLK], dx[NBLK], ee[NBLK];
@@ -890,7 +901,6 @@ __global__ __launch_bounds__(256) void wgrad_thin_walk_kernel(WgradThinWalkKArgs
     const int segs = (d.W + 31) / 32;
     const long long planes = d.Q / ((long long)d.H * d.W);
     const long long n_items = planes * segs * ka.runs;
-    const __amdgpu_buffer_rsrc_t r_thin = __builtin_amdgcn_make_buffer_rsrc((void*)a.thin, 0, (unsigned)(d.Q * 8), 0x00020000);
     const unsigned wide_row_bytes = (unsigned)d.W * WC * ES;
     const int relu_floor = a.relu_in ? 0 : (int)0x80000000;   // ReLU as a signed-integer maximum on the bit pattern
 
@@ -901,64 +911,72 @@ __global__ __launch_bounds__(256) void wgrad_thin_walk_kernel(WgradThinWalkKArgs
         const int z = (int)(plane % d.D);
         const int x_seg = 32 * seg;
         const int y0 = rn * ka.run_len, y1 = y0 + ka.run_len < d.H ? y0 + ka.run_len : d.H;
-        const bool interior = x_seg >= 1 && x_seg + 33 <= d.W;   // uniform: every tap column of every pixel is inside the row
-        // thin side: byte offset of this lane's value for pixel pair 0 of row y0, and which pairs are inside the row
-        unsigned vo[NBLK], xbad[NBLK];
-        bool z_ok[NBLK];
+        // thin side: lanes 0 .. 35 fetch pixel pp = lane of a row segment (8 bytes); float offset of this lane's B value
+        // inside a slab row
+        const unsigned thin_lane = lane < kSlabPx ? (unsigned)((x_seg - 1 + lane) * 8) : kOutside;
+        int b_in_row[NBLK];
 #pragma unroll
-        for (int b = 0; b < NBLK; ++b) {
-            z_ok[b] = col_used[b] && (KD == 1 || (unsigned)(z + dz[b]) < (unsigned)d.D);
-            const int xl = x_seg + h + dx[b];
-            vo[b] = (unsigned)(((((plane + dz[b]) * d.H + (y0 + dy[b])) * d.W + xl) * 2 + ee[b]) * 4);
-            unsigned bad = 0u;
+        for (int b = 0; b < NBLK; ++b) b_in_row[b] = ((KD == 1 ? 0 : dz[b] + 1) * 4 * kSlabPx + h + dx[b] + 1) * 2 + ee[b];
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 tq[KD];
+        auto fetch_thin = [&](int ys) __attribute__((always_inline)) {   // row ys of the KD slices
 #pragma unroll
-            for (int j = 0; j < 16; ++j) bad |= ((unsigned)(xl + 2 * j) < (unsigned)d.W ? 0u : 1u) << j;
-            xbad[b] = bad;
-        }
-        const unsigned wide_lane = (unsigned)((h * WC + m) * ES);
+            for (int iz = 0; iz < KD; ++iz) {
+                const int zz = z + iz - KD / 2;
+                const bool ok = ys >= 0 && ys < d.H && (KD == 1 || (zz >= 0 && zz < d.D));   // uniform
+                const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+                    (void*)(a.thin + (ok ? ((plane + iz - KD / 2) * d.H + ys) * d.W * 2 : 0)), 0, ok ? (unsigned)d.W * 8u : 0u, 0x00020000);
+                tq[iz] = __builtin_amdgcn_raw_buffer_load_b64(r, thin_lane, 0, 0);
+            }
+        };
+        auto store_thin = [&](int ys) __attribute__((always_inline)) {
+            const int slot = (ys - y0 + 1) & 3;
+            if (lane < kSlabPx) {
+#pragma unroll
+                for (int iz = 0; iz < KD; ++iz) {
+                    int v0 = (int)tq[iz][0], v1 = (int)tq[iz][1];
+                    if (THIN_IN) { v0 = v0 > relu_floor ? v0 : relu_floor; v1 = v1 > relu_floor ? v1 : relu_floor; }
+                    *reinterpret_cast<float2*>(slab + ((iz * 4 + slot) * kSlabPx + lane) * 2) = make_float2(__int_as_float(v0), __int_as_float(v1));
+                }
+            }
+        };
+        // (LDS operations of one wave execute in order: no barrier between this wave's stores and its reads)
+        fetch_thin(y0 - 1); store_thin(y0 - 1);
+        fetch_thin(y0); store_thin(y0);
+        fetch_thin(y0 + 1); store_thin(y0 + 1);
+        const unsigned wide_lane = (unsigned)((h * WC + (PAIRS ? 2 * m : m)) * ES);
         for (int y = y0; y < y1; ++y) {
+            fetch_thin(y + 2);   // stored after this row's reads, into the slot of row y - 2
             const __amdgpu_buffer_rsrc_t r_wide = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)((const char*)a.wide + ((plane * d.H + y) * d.W) * (long long)(WC * ES)), 0, wide_row_bytes, 0x00020000);
-            unsigned vrow[NBLK];
+            const float* brow[NBLK];
 #pragma unroll
-            for (int b = 0; b < NBLK; ++b) {
-                const bool ok = z_ok[b] && (unsigned)(y + dy[b]) < (unsigned)d.H;
-                vrow[b] = ok ? vo[b] : kOutside;
-                vo[b] += (unsigned)d.W * 8u;
-            }
+            for (int b = 0; b < NBLK; ++b) brow[b] = slab + b_in_row[b] + ((y + dy[b] - y0 + 1) & 3) * (kSlabPx * 2);
             float av[NCB][16], bv[NBLK][16];
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
 #pragma unroll
-                for (int c = 0; c < NCB; ++c) {
+                for (int c = 0; c < NCB; c += PAIRS ? 2 : 1) {
                     const unsigned off = wide_lane + (unsigned)(((x_seg + 2 * j) * WC + 32 * c) * ES);
-                    int bits;
-                    if constexpr (BF) bits = (int)((unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_wide, off, 0, 0) << 16);
-                    else bits = (int)__builtin_amdgcn_raw_buffer_load_b32(r_wide, off, 0, 0);
-                    if (!THIN_IN) bits = bits > relu_floor ? bits : relu_floor;
-                    av[c][j] = __int_as_float(bits);
+                    if constexpr (PAIRS) {
+                        const unsigned w2 = __builtin_amdgcn_raw_buffer_load_b32(r_wide, off, 0, 0);
+                        int lo = (int)(w2 << 16), hi = (int)(w2 & 0xffff0000u);
+                        if (!THIN_IN) { lo = lo > relu_floor ? lo : relu_floor; hi = hi > relu_floor ? hi : relu_floor; }
+                        av[c][j] = __int_as_float(lo);
+                        av[c + 1][j] = __int_as_float(hi);
+                    } else {
+                        int bits;
+                        if constexpr (BF) bits = (int)((unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_wide, off, 0, 0) << 16);
+                        else bits = (int)__builtin_amdgcn_raw_buffer_load_b32(r_wide, off, 0, 0);
+                        if (!THIN_IN) bits = bits > relu_floor ? bits : relu_floor;
+                        av[c][j] = __int_as_float(bits);
+                    }
                 }
             }
-            if (interior) {
 #pragma unroll
-                for (int j = 0; j < 16; ++j)
+            for (int j = 0; j < 16; ++j)
 #pragma unroll
-                    for (int b = 0; b < NBLK; ++b) {
-                        int bits = (int)__builtin_amdgcn_raw_buffer_load_b32(r_thin, vrow[b] + 16u * j, 0, 0);
-                        if (THIN_IN) bits = bits > relu_floor ? bits : relu_floor;
-                        bv[b][j] = __int_as_float(bits);
-                    }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-#pragma unroll
-                    for (int b = 0; b < NBLK; ++b) {
-                        const unsigned o = ((xbad[b] >> j) & 1u) ? kOutside : vrow[b];
-                        int bits = (int)__builtin_amdgcn_raw_buffer_load_b32(r_thin, o + 16u * j, 0, 0);
-                        if (THIN_IN) bits = bits > relu_floor ? bits : relu_floor;
-                        bv[b][j] = __int_as_float(bits);
-                    }
-            }
+                for (int b = 0; b < NBLK; ++b) bv[b][j] = brow[b][4 * j];
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
 #pragma unroll
@@ -974,49 +992,70 @@ __global__ __launch_bounds__(256) void wgrad_thin_walk_kernel(WgradThinWalkKArgs
                     bs[0] += bv[0][j];
                 }
             }
+            store_thin(y + 2);
         }
     }
 
-    // fold the four waves of the workgroup, then write its partial block in dw layout
-    constexpr int NACC = NCB * NBLK * 16;
+    // fold the four waves of the workgroup (waves 2, 3 into 0, 1, then 1 into 0), then wave 0 writes the partial block in
+    // dw layout
     const int Co = THIN_IN ? WC : 2, Ci = THIN_IN ? 2 : WC;
     float* dst = a.partial + (size_t)blockIdx.x * Co * TAPS * Ci;
+    float bsum[THIN_IN ? NCB : 1];
 #pragma unroll
-    for (int c = 0; c < NCB; ++c)
+    for (int c = 0; c < (THIN_IN ? NCB : 1); ++c) bsum[c] = bs[c] + __shfl_xor(bs[c], 32);
+    auto put = [&](int slot) {
 #pragma unroll
-        for (int b = 0; b < NBLK; ++b)
+        for (int c = 0; c < NCB; ++c)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) red[wave][((c * NBLK + b) * 16 + r) * 64 + lane] = acc[c][b][r];
+            for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) red[slot][((c * NBLK + b) * 16 + r) * 64 + lane] = acc[c][b][r];
+    };
+    auto take = [&](int slot) {
+#pragma unroll
+        for (int c = 0; c < NCB; ++c)
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[c][b][r] += red[slot][((c * NBLK + b) * 16 + r) * 64 + lane];
+    };
+    __shared__ float bred[4][THIN_IN ? 32 * NCB : 64];
+#pragma unroll
+    for (int c = 0; c < (THIN_IN ? NCB : 1); ++c)
+        if (h == 0) bred[wave][32 * c + m] = bsum[c];
+    if (wave >= 2) put(wave - 2);
     __syncthreads();
-    for (int i = threadIdx.x; i < NACC * 64; i += 256) {
-        const float sum = (red[0][i] + red[1][i]) + (red[2][i] + red[3][i]);
-        const int l = i & 63, r = (i >> 6) & 15, cbk = i >> 10, b = cbk % NBLK, c = cbk / NBLK;
-        const int n = 32 * b + (l & 31), ch = 32 * c + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-        if (n < NCOL) {
-            const int tap = n >> 1, e = n & 1;
-            dst[THIN_IN ? ((size_t)ch * TAPS + tap) * 2 + e : ((size_t)e * TAPS + tap) * WC + ch] = sum;
-        }
+    if (wave < 2) take(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        take(0);
+#pragma unroll
+        for (int c = 0; c < NCB; ++c)
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int n = 32 * b + m;
+                if (n < NCOL) {
+                    const int tap = n >> 1, e = n & 1;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int ch = chan(c, 8 * (r >> 2) + 4 * h + (r & 3));
+                        dst[THIN_IN ? ((size_t)ch * TAPS + tap) * 2 + e : ((size_t)e * TAPS + tap) * WC + ch] = acc[c][b][r];
+                    }
+                }
+            }
     }
     if (a.bias_partial != nullptr) {
-        __syncthreads();
         if (THIN_IN) {
-#pragma unroll
-            for (int c = 0; c < NCB; ++c) {
-                const float tot = bs[c] + __shfl_xor(bs[c], 32);
-                if (h == 0) red[wave][32 * c + m] = tot;
+            if ((int)threadIdx.x < WC) {
+                const int c = threadIdx.x >> 5, i = threadIdx.x & 31;
+                a.bias_partial[(size_t)blockIdx.x * Co + chan(c, i)] =
+                    (bred[0][threadIdx.x] + bred[1][threadIdx.x]) + (bred[2][threadIdx.x] + bred[3][threadIdx.x]);
             }
-            __syncthreads();
-            if ((int)threadIdx.x < WC)
-                a.bias_partial[(size_t)blockIdx.x * Co + threadIdx.x] =
-                    (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
-        } else {
-            const float tot = bs[0] + __shfl_xor(bs[0], 32);
-            if (h == 0) red[wave][m] = tot;
-            __syncthreads();
-            if (threadIdx.x < 2) {
-                const int col = 2 * (TAPS / 2) + threadIdx.x;   // centre tap
-                a.bias_partial[(size_t)blockIdx.x * Co + threadIdx.x] = (red[0][col] + red[1][col]) + (red[2][col] + red[3][col]);
-            }
+        } else if (threadIdx.x < 2) {
+            const int col = 2 * (TAPS / 2) + threadIdx.x;   // centre tap
+            a.bias_partial[(size_t)blockIdx.x * Co + threadIdx.x] = (bred[0][col] + bred[1][col]) + (bred[2][col] + bred[3][col]);
         }
     }
 }
