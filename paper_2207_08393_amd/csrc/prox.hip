@@ -1123,6 +1123,16 @@ static hipError_t launch_conv(ConvArgs a, const ConvWeights& cw, float* wt_scrat
         snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
         return launch_conv_wino3(wa, cw.w, cw.sn, cw.st, cw.sk, a.flip, a.relu_in, wt_scratch, name, st);
     }
+    if (!(kernel_policy() & GLEAM_POLICY_NO_FRAME_WALK) && conv_time_applies(a.d, a.K, a.Nn)) {   // temporal 3x1x1: walk along the frames
+        TimeConvArgs t{};
+        t.in = a.in; t.out = a.out; t.bias = a.bias; t.mask_ref = a.mask_ref; t.add = a.add;
+        t.w = cw.w; t.sn = cw.sn; t.st = cw.st; t.sk = cw.sk; t.flip = a.flip;
+        t.Nn = a.Nn; t.relu_in = a.relu_in; t.relu_out = a.relu_out; t.mask_acc = a.mask_acc; t.mask_add = a.mask_add;
+        char name[56];
+        snprintf(name, sizeof(name), "conv_%s_%dto%d_t%d", a.flip ? "dgrad" : "fwd", a.K, a.Nn, taps_);
+        KernelScope ks(name, 2.0 * (double)a.d.Q * a.K * a.Nn * taps_, 4.0 * (double)a.d.Q * (a.K + a.Nn), st);
+        return launch_conv_time(t, a.d, st);
+    }
     const int ck = conv_ck(a.K), nb = conv_nb(a.Nn);
     {
         WimgArgs t{};

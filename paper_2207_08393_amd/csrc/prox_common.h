@@ -216,6 +216,21 @@ bool wgrad_time_applies(const PixDims& d, int Ci, int Co);
 int wgrad_time_splits(const PixDims& d);
 size_t wgrad_time_partial_floats(const PixDims& d, int Ci, int Co);
 hipError_t launch_wgrad_time(TimeWgradArgs a, const PixDims& d, int relu_in, hipStream_t stream);
+// Forward / data gradient of a temporal 3x1x1 layer with 64 input channels by a walk along the frames (prox_time.hip).
+struct TimeConvArgs {
+    const float* in;        // [samples][T][P][64]
+    float* out;             // [samples][T][P][Nn]
+    const float* bias;      // [Nn] or null
+    const float* mask_ref;  // [..][Nn] or null: ReLU mask source (value > 0 passes)
+    const float* add;       // [..][Nn] or null
+    const float* w;         // element (output n, tap t, input k) at w[n*sn + t*st + k*sk]; flip: taps mirrored
+    long long sn, st, sk;
+    int flip, Nn, relu_in, relu_out, mask_acc, mask_add;
+    int T;                  // set by the launcher: frames, pixels per frame, 64-pixel segments per frame, segments in total
+    long long P, segs, n_items;
+};
+bool conv_time_applies(const PixDims& d, int K, int Nn);
+hipError_t launch_conv_time(TimeConvArgs a, const PixDims& d, hipStream_t stream);
 // Transformed weights of several layers in one launch (a launch costs more than the transform of one layer).
 struct WinoWeightJob {
     const float* w;

@@ -184,4 +184,189 @@ hipError_t launch_wgrad_time(TimeWgradArgs a, const PixDims& d, int relu_in, hip
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Forward / data gradient of a temporal 3x1x1 layer with 64 input channels, float32:
+//     out[t][p][n] = b[n] + sum over kt and k of W[n][kt][k] * in[t + kt - 1][p][k]
+// Output frame t needs input frames t - 1, t, t + 1, so a workgroup walks the frames of a 64-pixel segment in order
+// and every input segment is read from memory once (as three independent taps of a flattened-pixel kernel each is
+// staged three times).  The weights stay in registers: wave (cb, pb) of 4 owns 32 output channels x 32 pixels and
+// keeps W[32 cb + m][kt][32 h + i] for the whole kernel (96 registers: the A operands).  Contraction step i of
+// v_mfma_f32_32x32x2_f32 pairs input channels i and 32 + i (any pairing is a sum over all 64), so that a lane's B
+// operands of a tap are 32 consecutive floats of its pixel: eight 16-byte LDS reads.  Input segments go from memory
+// to LDS by direct loads through a buffer resource that spans one frame (pixels past the frame's end arrive as
+// zeros, a frame outside 0 .. T - 1 gets a resource of size 0), one frame ahead, into a ring of four buffers that are
+// separate LDS objects; the walk is written out over the four rotations.  The epilogue is branch-free through buffer
+// resources (a pixel past the frame's end has its stores dropped) and its mask source / add operand are requested
+// before the MFMAs of the frame.
+namespace {
+constexpr int kCPix = 64;                 // pixels per segment
+constexpr int kCRow = 68;                 // floats per pixel in LDS: 64 channels + 16 bytes (bank spread of the 16-byte reads)
+constexpr int kCLoads = 17;               // wave-wide direct loads per segment: 64 pixels x 17 slots of 16 bytes
+}  // namespace
+
+template <bool RELU, bool EPI>
+__global__ __launch_bounds__(256, 2) void conv_time_kernel(TimeConvArgs a) {
+    __shared__ __attribute__((aligned(16))) float F0[kCLoads * 256];
+    __shared__ __attribute__((aligned(16))) float F1[kCLoads * 256];
+    __shared__ __attribute__((aligned(16))) float F2[kCLoads * 256];
+    __shared__ __attribute__((aligned(16))) float F3[kCLoads * 256];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cb = wave & 1, pb = wave >> 1;
+    const int m = lane & 31, h = lane >> 5;
+    const int co0 = 64 * (int)blockIdx.y + 32 * cb;
+    constexpr unsigned kOutside = 0x80000000u;
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+    float wreg[3][32];
+#pragma unroll
+    for (int kt = 0; kt < 3; ++kt)
+#pragma unroll
+        for (int i = 0; i < 32; ++i) wreg[kt][i] = a.w[(co0 + m) * a.sn + (a.flip ? 2 - kt : kt) * a.st + (32 * h + i) * a.sk];
+
+    // direct loads: slot s = 64 (wave + 4 i) + lane holds channel quad s % 17 (16: padding) of segment pixel s / 17
+    unsigned slot_off[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) {
+        const int s = 64 * (wave + 4 * i) + lane, px = s / 17, q = s % 17;
+        slot_off[i] = q < 16 ? (unsigned)((px * 64 + 4 * q) * 4) : kOutside;
+    }
+    const unsigned in_frame_bytes = (unsigned)(a.P * 256);
+    const unsigned out_frame_bytes = (unsigned)(a.P * a.Nn * 4);
+    const int b_rd = (32 * pb + m) * kCRow + 32 * h;   // this lane's pixel and channel half
+    // epilogue: accumulators 4 g .. 4 g + 3 are output channels co0 + 8 g + 4 h .. + 3 of pixel 32 pb + m
+    const unsigned out_lane = (unsigned)(((32 * pb + m) * a.Nn + co0 + 4 * h) * 4);
+    __shared__ __attribute__((aligned(16))) float bias_s[64];   // of the workgroup's 64 output channels
+    if (tid < 64) bias_s[tid] = a.bias ? a.bias[64 * (int)blockIdx.y + tid] : 0.f;
+    __syncthreads();
+    const float out_floor = a.relu_out ? 0.f : -__builtin_huge_valf();
+
+    for (long long item = blockIdx.x; item < a.n_items; item += gridDim.x) {
+        const long long seg = item % a.segs, vol = item / a.segs;
+        const unsigned p_off_in = (unsigned)(seg * kCPix * 256), p_off_out = (unsigned)(seg * kCPix * a.Nn * 4);
+        auto load = [&](int tau, float* dst) __attribute__((always_inline)) {
+            const bool ok = tau >= 0 && tau < a.T;
+            const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(a.in + ((vol * a.T + (ok ? tau : 0)) * a.P) * 64), 0, ok ? in_frame_bytes : 0u, 0x00020000);
+#pragma unroll
+            for (int i = 0; i < 5; ++i)
+                if (wave + 4 * i < kCLoads)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(dst + (wave + 4 * i) * 256), 16,
+                                                             slot_off[i] + p_off_in, 0, 0, 0);
+        };
+        // the previous item ended with a barrier: all buffers are free
+        load(-1, F0);
+        load(0, F1);
+        load(1, F2);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        int t = 0;
+        auto step = [&](const float* fm, const float* fz, const float* fp, float* fn) __attribute__((always_inline)) {
+            if (t + 1 < a.T) load(t + 2, fn);
+            const long long frame = vol * a.T + t;
+            const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)(a.out + frame * a.P * a.Nn), 0, out_frame_bytes, 0x00020000);
+            u32x4 refq[4], addq[4];
+            if constexpr (EPI) {
+                const __amdgpu_buffer_rsrc_t r_ref = __builtin_amdgcn_make_buffer_rsrc(
+                    (void*)(a.mask_ref ? a.mask_ref + frame * a.P * a.Nn : a.out), 0, a.mask_ref ? out_frame_bytes : 0u, 0x00020000);
+                const __amdgpu_buffer_rsrc_t r_add = __builtin_amdgcn_make_buffer_rsrc(
+                    (void*)(a.add ? a.add + frame * a.P * a.Nn : a.out), 0, a.add ? out_frame_bytes : 0u, 0x00020000);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    refq[g] = __builtin_amdgcn_raw_buffer_load_b128(r_ref, out_lane + p_off_out + 32u * g, 0, 0);
+                    addq[g] = __builtin_amdgcn_raw_buffer_load_b128(r_add, out_lane + p_off_out + 32u * g, 0, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // the 32 B operands of a tap are read while the MFMAs of the tap before it run
+            floatx16 acc;
+            float4 vq[2][8];
+            auto read_tap = [&](int kt) __attribute__((always_inline)) {
+                const float* fb = (kt == 0 ? fm : kt == 1 ? fz : fp) + b_rd;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) vq[kt & 1][q] = *reinterpret_cast<const float4*>(fb + 4 * q);
+            };
+            read_tap(0);
+#pragma unroll
+            for (int kt = 0; kt < 3; ++kt) {
+                if (kt + 1 < 3) read_tap(kt + 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const float4 v4 = vq[kt & 1][q];
+                    float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (RELU) v[e] = __int_as_float(__float_as_int(v[e]) > 0 ? __float_as_int(v[e]) : 0);
+                        floatx16 c;
+                        if (kt == 0 && q == 0 && e == 0) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) c[r] = 0.f;
+                        } else {
+                            c = acc;
+                        }
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[kt][4 * q + e], v[e], c, 0, 0, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 b4 = *reinterpret_cast<const float4*>(bias_s + 32 * cb + 8 * g + 4 * h);
+                const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
+                u32x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float x = fmaxf(acc[4 * g + e] + bb[e], out_floor);
+                    if constexpr (EPI) {
+                        const bool pos = a.mask_ref ? __uint_as_float(refq[g][e]) > 0.f : true;
+                        if (a.mask_acc) x = pos ? x : 0.f;
+                        x += (a.mask_add && !pos) ? 0.f : __uint_as_float(addq[g][e]);
+                    }
+                    pk[e] = __float_as_uint(x);
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(pk, r_out, out_lane + p_off_out + 32u * g, 0, 0);
+            }
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            ++t;
+        };
+        while (true) {
+            step(F0, F1, F2, F3);
+            if (t >= a.T) break;
+            step(F1, F2, F3, F0);
+            if (t >= a.T) break;
+            step(F2, F3, F0, F1);
+            if (t >= a.T) break;
+            step(F3, F0, F1, F2);
+            if (t >= a.T) break;
+        }
+    }
+}
+
+bool conv_time_applies(const PixDims& d, int K, int Nn) {
+    const long long P = (long long)d.D * d.H * d.W;
+    // byte offsets inside a frame are 32 bits in the kernel (and below the offset that marks padding slots)
+    return d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1 && K == 64 && Nn % 64 == 0 && Nn >= 64 &&
+           (double)(P + kCPix) * (Nn > 64 ? Nn : 64) * 4.0 < 2.0e9;
+}
+
+hipError_t launch_conv_time(TimeConvArgs a, const PixDims& d, hipStream_t st) {
+    a.T = d.T;
+    a.P = (long long)d.D * d.H * d.W;
+    a.segs = (a.P + kCPix - 1) / kCPix;
+    a.n_items = d.Q / ((long long)d.T * a.P) * a.segs;
+    const long long cap = 512 / (a.Nn / 64) > 8 ? 512 / (a.Nn / 64) : 8;   // two workgroups per CU in total
+    dim3 grid((unsigned)(a.n_items < cap ? a.n_items : cap), (unsigned)(a.Nn / 64));
+    const bool epi = a.mask_ref || a.add;
+    if (a.relu_in) {
+        if (epi) hipLaunchKernelGGL((conv_time_kernel<true, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((conv_time_kernel<true, false>), grid, dim3(256), 0, st, a);
+    } else {
+        if (epi) hipLaunchKernelGGL((conv_time_kernel<false, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((conv_time_kernel<false, false>), grid, dim3(256), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace gleam
