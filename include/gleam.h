@@ -109,8 +109,9 @@ int gleam_theta_count(const gleam_prox_desc* prox, size_t* n_floats);
 #define GLEAM_POLICY_NO_BF16_2D       2u  /* 3x3 bf16 layers: flattened-pixel kernel instead of the 2D-tile one        */
 #define GLEAM_POLICY_NO_THIN_MFMA     4u  /* 2-channel first / last layers: vector-ALU kernels instead of matrix-core   */
 #define GLEAM_POLICY_NO_WGRAD_BALANCE 8u  /* 27-tap weight gradient: nine 3-tap jobs instead of the balanced 8-wave split */
-#define GLEAM_POLICY_NO_FRAME_WALK    16u /* weight gradients that walk an axis (3x1x1 fp32 along the frames, 3x3 bf16 with
-                                          * 128 input channels down the rows): the kernels that stage every tap row instead */
+#define GLEAM_POLICY_NO_FRAME_WALK    16u /* kernels that walk an axis (3x1x1 fp32 layers along the frames: forward, data and
+                                          * weight gradient; 3x3 bf16 weight gradient with 128 input channels down the
+                                          * rows): the kernels that stage every tap row instead */
 #define GLEAM_POLICY_ALL              31u
 int gleam_set_kernel_policy(uint32_t policy);
 uint32_t gleam_get_kernel_policy(void);
