@@ -292,6 +292,9 @@ def bf16_cases():
     # 128 input channels: the weight gradient walks down strips of 64 columns (two full strips and one of 32, two
     # images, runs of 10 rows with a last one of 6)
     yield "chain128_strips", synth.Geom(2, 2, 2, 1, 1, 46, 160), synth.chain_prox([2, 128, 128, 64, 2], [K2] * 4, dtype=1), 0
+    # 256 output channels: two channel groups of the register-resident-weights kernel (forward 128->256, data gradient
+    # 256->128 seen from its output) and four of the walking weight gradient
+    yield "chain128_256", synth.Geom(2, 1, 2, 1, 1, 12, 46), synth.chain_prox([2, 128, 256, 128, 2], [K2] * 4, dtype=1), 0
     yield "vol32", synth.Geom(3, 1, 2, 1, 8, 10, 12), synth.chain_prox([2, 32, 32, 2], [K3] * 3, dtype=1), 0
     yield "cine64", synth.Geom(2, 1, 2, 6, 1, 12, 16), synth.chain_prox([2, 64, 64, 64, 2], [KS, KT, KS, KT], dtype=1), 0
     # 96 channels x 27 taps: the weight gradient's two staging buffers exceed LDS, so it runs single-buffered
