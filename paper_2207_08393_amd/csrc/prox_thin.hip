@@ -613,8 +613,9 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
     if ((int)threadIdx.x < NN) bias_s[threadIdx.x] = a.bias ? a.bias[threadIdx.x] : 0.f;
     __syncthreads();
     for (long long item = first; item < n_items; item += step) {
-        const int rn = (int)(item % runs);
-        const int seg = (int)((item / runs) % segs);
+        // segments fastest: the four waves of a workgroup walk down neighbouring segments of the same rows
+        const int seg = (int)(item % segs);
+        const int rn = (int)((item / segs) % runs);
         const long long plane = item / ((long long)runs * segs);
         const int z = (int)(plane % d.D);
         const int x_seg = 32 * seg, x = x_seg + m;
@@ -905,8 +906,9 @@ __global__ __launch_bounds__(256) void wgrad_thin_walk_kernel(WgradThinWalkKArgs
     const int relu_floor = a.relu_in ? 0 : (int)0x80000000;   // ReLU as a signed-integer maximum on the bit pattern
 
     for (long long item = (long long)blockIdx.x * 4 + wave; item < n_items; item += (long long)gridDim.x * 4) {
-        const int rn = (int)(item % ka.runs);
-        const int seg = (int)((item / ka.runs) % segs);
+        // segments fastest: the four waves of a workgroup walk down neighbouring segments of the same rows
+        const int seg = (int)(item % segs);
+        const int rn = (int)((item / segs) % ka.runs);
         const long long plane = item / ((long long)ka.runs * segs);
         const int z = (int)(plane % d.D);
         const int x_seg = 32 * seg;
