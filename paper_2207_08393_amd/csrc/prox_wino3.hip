@@ -63,7 +63,7 @@ static_assert(kExHalfFloats <= kUSlots * 4 && kExHalfFloats <= kRHSlots * 4, "th
 // different 16-byte bank groups.
 __device__ __forceinline__ int exh_off(int wave, int tile, int cq) { return (((wave * 32 + tile) * 8) + (cq ^ ((tile >> 1) & 7))) * 4; }
 
-template <bool RELU>
+template <bool RELU, bool EPI>   // EPI: the call has a ReLU mask source or a tensor to add
 __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
     __shared__ __attribute__((aligned(16))) float R0[kRHSlots * 4];
     __shared__ __attribute__((aligned(16))) float R1[kRHSlots * 4];
@@ -292,8 +292,10 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
                     op[i][jj] = okp[i][jj] ? ((img * a.H + ey + i) * a.W + ex_ + jj) * a.Nn + n0 + 4 * e_cq : (long long)(n0 + 4 * e_cq);
                     refv[i][jj] = make_float4(1.f, 1.f, 1.f, 1.f);
                     addv[i][jj] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (a.mask_ref) refv[i][jj] = *reinterpret_cast<const float4*>(a.mask_ref + op[i][jj]);
-                    if (a.add) addv[i][jj] = *reinterpret_cast<const float4*>(a.add + op[i][jj]);
+                    if constexpr (EPI) {
+                        if (a.mask_ref) refv[i][jj] = *reinterpret_cast<const float4*>(a.mask_ref + op[i][jj]);
+                        if (a.add) addv[i][jj] = *reinterpret_cast<const float4*>(a.add + op[i][jj]);
+                    }
                 }
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
@@ -326,12 +328,14 @@ __global__ __launch_bounds__(256, 2) void conv_wino3_kernel(WinoArgs a) {
                     }
                     const float rr[4] = {refv[i][jj].x, refv[i][jj].y, refv[i][jj].z, refv[i][jj].w};
                     const float aa[4] = {addv[i][jj].x, addv[i][jj].y, addv[i][jj].z, addv[i][jj].w};
-                    if (a.mask_acc) {
+                    if constexpr (EPI) {
+                        if (a.mask_acc) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = rr[e] > 0.f ? v[e] : 0.f;
+                            for (int e = 0; e < 4; ++e) v[e] = rr[e] > 0.f ? v[e] : 0.f;
+                        }
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
                     }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !(rr[e] > 0.f)) ? 0.f : aa[e];
                     if (okp[i][jj]) *reinterpret_cast<float4*>(a.out + op[i][jj]) = make_float4(v[0], v[1], v[2], v[3]);
                 }
             }
@@ -737,8 +741,14 @@ hipError_t launch_conv_wino3(WinoArgs a, const float* w, long long sn, long long
     const double Q = (double)a.NI * a.H * a.W;
     // 16 multiplications per 2x2 outputs, depth tap and channel pair on the matrix cores instead of the 36 of the definition
     KernelScope ks(name, 2.0 * Q * a.K * a.Nn * 27, 4.0 * Q * (a.K + a.Nn), st, 2.0 * Q * a.K * a.Nn * 12);
-    if (relu_in) hipLaunchKernelGGL((conv_wino3_kernel<true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((conv_wino3_kernel<false>), grid, dim3(256), 0, st, a);
+    const bool epi = a.mask_ref || a.add;
+    if (relu_in) {
+        if (epi) hipLaunchKernelGGL((conv_wino3_kernel<true, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((conv_wino3_kernel<true, false>), grid, dim3(256), 0, st, a);
+    } else {
+        if (epi) hipLaunchKernelGGL((conv_wino3_kernel<false, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((conv_wino3_kernel<false, false>), grid, dim3(256), 0, st, a);
+    }
     return hipGetLastError();
 }
 
