@@ -62,7 +62,7 @@ __device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(
 
 }  // namespace
 
-template <bool RELU>
+template <bool RELU, bool EPI>   // EPI: the call has a ReLU mask (source tensor or sign words) or a tensor to add
 __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
     // Separate LDS objects: reads of one chunk buffer then do not wait for direct loads into the other.
     __shared__ __attribute__((aligned(16))) float bufA[kWBufFloats];
@@ -245,7 +245,9 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
     // the same values) reads them instead of the activation itself.
     const long long word_idx = ((long long)ny * a.n_blocks + item) * 256 + tid_b;
     unsigned sign_in = 0u, sign_out = 0u;
-    if (a.bits_in) sign_in = a.bits_in[word_idx];
+    if constexpr (EPI) {
+        if (a.bits_in) sign_in = a.bits_in[word_idx];
+    }
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) {
         if (jp) __syncthreads();
@@ -256,8 +258,10 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
             for (int jj = 0; jj < 2; ++jj) {
                 refv[i][jj] = make_float4(1.f, 1.f, 1.f, 1.f);
                 addv[i][jj] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (a.mask_ref && !a.bits_in) refv[i][jj] = *reinterpret_cast<const float4*>(a.mask_ref + op[i][jj] + 32 * jp);
-                if (a.add) addv[i][jj] = *reinterpret_cast<const float4*>(a.add + op[i][jj] + 32 * jp);
+                if constexpr (EPI) {
+                    if (a.mask_ref && !a.bits_in) refv[i][jj] = *reinterpret_cast<const float4*>(a.mask_ref + op[i][jj] + 32 * jp);
+                    if (a.add) addv[i][jj] = *reinterpret_cast<const float4*>(a.add + op[i][jj] + 32 * jp);
+                }
             }
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
@@ -290,15 +294,17 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(WinoArgs a) {
                 const float rr[4] = {refv[i][jj].x, refv[i][jj].y, refv[i][jj].z, refv[i][jj].w};
                 const float aa[4] = {addv[i][jj].x, addv[i][jj].y, addv[i][jj].z, addv[i][jj].w};
                 const int bit0 = 16 * jp + 4 * (2 * i + jj);
-                bool pos[4];
+                if constexpr (EPI) {
+                    bool pos[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) pos[e] = a.bits_in ? ((sign_in >> (bit0 + e)) & 1u) != 0u : rr[e] > 0.f;
-                if (a.mask_acc) {
+                    for (int e = 0; e < 4; ++e) pos[e] = a.bits_in ? ((sign_in >> (bit0 + e)) & 1u) != 0u : rr[e] > 0.f;
+                    if (a.mask_acc) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = pos[e] ? v[e] : 0.f;
+                        for (int e = 0; e < 4; ++e) v[e] = pos[e] ? v[e] : 0.f;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !pos[e]) ? 0.f : aa[e];
                 }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] += (a.mask_add && !pos[e]) ? 0.f : aa[e];
                 if (a.bits_out) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) sign_out |= (v[e] > 0.f ? 1u : 0u) << (bit0 + e);
@@ -660,8 +666,14 @@ hipError_t launch_conv_wino(WinoArgs a, const float* w, long long sn, long long 
     const double Q = (double)a.NI * a.H * a.W;
     // F(2x2, 3x3): 16 multiplications per 2x2 outputs and channel pair on the matrix cores instead of the 36 of the definition
     KernelScope ks(name, 2.0 * Q * a.K * a.Nn * 9, 4.0 * Q * (a.K + a.Nn), st, 2.0 * Q * a.K * a.Nn * 4);
-    if (relu_in) hipLaunchKernelGGL((conv_wino_kernel<true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((conv_wino_kernel<false>), grid, dim3(256), 0, st, a);
+    const bool epi = a.mask_ref || a.add || a.bits_in;
+    if (relu_in) {
+        if (epi) hipLaunchKernelGGL((conv_wino_kernel<true, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((conv_wino_kernel<true, false>), grid, dim3(256), 0, st, a);
+    } else {
+        if (epi) hipLaunchKernelGGL((conv_wino_kernel<false, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((conv_wino_kernel<false, false>), grid, dim3(256), 0, st, a);
+    }
     return hipGetLastError();
 }
 
