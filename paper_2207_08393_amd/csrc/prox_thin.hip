@@ -590,7 +590,9 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
         __builtin_amdgcn_make_buffer_rsrc((void*)(a.add ? a.add : (const void*)a.out), 0, a.add ? out_bytes : 0u, 0x00020000);
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-    constexpr bool PRE = NB * NH == 1;
+    // the mask source and the add operand of a pass over the channels are requested before its MFMAs where the registers
+    // allow (32 channels per pass, or bfloat16 pieces of 8 bytes); else they are loaded in the epilogue
+    constexpr bool PRE = NB == 1 || BF;
     // four output-sized values (16 bytes of float32, 8 of bfloat16) at lane offset off of the row at byte offset row
     auto load_piece = [&](__amdgpu_buffer_rsrc_t r, unsigned off, unsigned row) -> u32x4 {
         if constexpr (BF) {
@@ -670,20 +672,18 @@ __global__ __launch_bounds__(256) void conv_thin_in_mfma_kernel(ThinInMfmaArgs a
             constexpr int ROT = decltype(rot_c)::value;
             load_row(y + 1, (ROT + 2) % 3);
             const long long q0 = (plane * d.H + y) * d.W + x_seg;   // first pixel of the segment
-            // mask source and add operand of the row's pieces: requested here, used after the MFMAs (32-channel layers;
-            // the wider ones do not have the registers and load them in the epilogue)
-            u32x4 refq[PRE ? PASSES : 1], addq[PRE ? PASSES : 1];
-            if constexpr (EPI && PRE) {
-                const unsigned rb = (unsigned)((q0 * NN) * ES);
-#pragma unroll
-                for (int u = 0; u < PASSES; ++u) {
-                    refq[u] = load_piece(r_ref, oo_item[u], rb);
-                    addq[u] = load_piece(r_add, oo_item[u], rb);
-                }
-            }
 #pragma unroll
             for (int hb = 0; hb < NH; ++hb) {
                 floatx16 acc[NB];
+                u32x4 refq[PRE ? PASSES : 1], addq[PRE ? PASSES : 1];
+                if constexpr (EPI && PRE) {
+                    const unsigned rb = (unsigned)((q0 * NN + NP * hb) * ES);
+#pragma unroll
+                    for (int u = 0; u < PASSES; ++u) {
+                        refq[u] = load_piece(r_ref, oo_item[u], rb);
+                        addq[u] = load_piece(r_add, oo_item[u], rb);
+                    }
+                }
                 // row taps in the order upper, middle, lower: the lower row's values are the ones just requested
 #pragma unroll
                 for (int k = 0; k < TAPS; ++k) {
