@@ -433,46 +433,39 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
 
     // Direct loads.  Slot s of a region (16 bytes at float offset 4*s) holds channel quad s & 7 of pixel
     // 2*(s >> 4) + (((s >> 3) ^ (s >> 4)) & 1).  A thread's seven slots (five of the input region, two of the gradient
-    // region) are described by one word each - offset from the region origin in quads | row << 24 | column << 26 - kept
-    // in a thread-private column of an LDS table: registers are what this kernel is short of, and recomputing the
-    // words per chunk cost 14 % of its time.
+    // region) do not change along a run of slices, so their byte offsets inside a slice - or an offset outside every
+    // slice when the pixel lies outside the image - are worked out once per run and kept in a thread-private column
+    // of an LDS table (registers are what this kernel is short of).  A chunk's loads then go through a buffer
+    // resource that spans the slice (of size 0 for a slice outside the volume): out-of-image pixels arrive as zeros
+    // with the data, without bounds checks, selects or zero stores in the loop.
     __shared__ unsigned slot_tab[7 * 256];
+    constexpr unsigned kOutside = 0x80000000u;   // (a slice is below 2^31 bytes: checked by wgrad_wino3_applies)
+    auto slots_of_run = [&](int y0, int x0) {
 #pragma unroll
-    for (int i = 0; i < 7; ++i) {
-        const bool is_x = i < 5;
-        const int s = tid + 256 * (is_x ? i : i - 5);
-        const int pp = s >> 4, qd = s & 7;
-        const int px = 2 * pp + (((s >> 3) ^ pp) & 1);
-        const int cols = is_x ? 34 : 32, C = is_x ? a.Ci : a.Co;
-        const int row = px / cols, col = px - row * cols;
-        slot_tab[i * 256 + tid] = (unsigned)((row * a.W + col) * (C / 4) + qd) | ((unsigned)row << 24) | ((unsigned)col << 26);
-    }
-    // FIRST / LOADS: first table row and wave-wide loads of the region (17 for the input, 8 for the gradient)
-    auto fill = [&](const float* origin, bool plane_ok, bool interior, int y_first, int x_first, auto first_c, auto loads_c, float* dst) {
-        constexpr int FIRST = decltype(first_c)::value, LOADS = decltype(loads_c)::value, N = (LOADS + 3) / 4;
-        // Lanes whose pixel lies outside the volume store zeros themselves (a direct load writes lane l's 16 bytes at
-        // the wave's base + 16*l, masked-off lanes write nothing).  All zero stores of a region come before its
-        // direct loads: a store into a buffer waits for the loads already in flight into it.
-        unsigned e[N];
-        unsigned valid = 0u;
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int o = wave + 4 * i;
-            if (o < LOADS) {
-                e[i] = slot_tab[(FIRST + i) * 256 + tid];
-                bool ok = plane_ok;
-                if (!interior) {
-                    const int yy = y_first + (int)((e[i] >> 24) & 3u), xx = x_first + (int)(e[i] >> 26);
-                    ok = ok && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
-                }
-                if (ok) valid |= 1u << i;
-                else *reinterpret_cast<float4*>(dst + o * 256 + lane * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
-            }
+        for (int i = 0; i < 7; ++i) {
+            const bool is_x = i < 5;
+            const int s = tid + 256 * (is_x ? i : i - 5);
+            const int pp = s >> 4, qd = s & 7;
+            const int px = 2 * pp + (((s >> 3) ^ pp) & 1);
+            const int cols = is_x ? 34 : 32, C = is_x ? a.Ci : a.Co, c0 = is_x ? ci0 : co0;
+            const int row = px / cols, col = px - row * cols;
+            const int yy = (is_x ? y0 - 1 : y0) + row, xx = (is_x ? x0 - 1 : x0) + col;
+            const bool ok = row < (is_x ? 4 : 2) && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
+            slot_tab[i * 256 + tid] = ok ? (unsigned)(((yy * a.W + xx) * C + c0 + 4 * qd) * 4) : kOutside;
         }
+    };
+    // FIRST / LOADS: first table row and wave-wide loads of the region (17 for the input, 8 for the gradient);
+    // plane: the slice of the tensor (C channels per pixel), or null if it lies outside the volume
+    auto fill = [&](const float* plane, int C, auto first_c, auto loads_c, float* dst) {
+        constexpr int FIRST = decltype(first_c)::value, LOADS = decltype(loads_c)::value, N = (LOADS + 3) / 4;
+        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(plane ? plane : a.a), 0, plane ? (unsigned)(a.H * a.W * C * 4) : 0u, 0x00020000);
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int o = wave + 4 * i;
-            if (o < LOADS && ((valid >> i) & 1u)) dma16_off(origin, (e[i] & 0xffffffu) << 4, dst + o * 256);
+            if (o < LOADS)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(dst + o * 256), 16,
+                                                         slot_tab[(FIRST + i) * 256 + tid], 0, 0, 0);
         }
     };
 
@@ -569,17 +562,16 @@ __global__ __launch_bounds__(256, 2) void wgrad_wino3_kernel(Wino3WgradArgs a) {
         const long long vol = rest / a.segs_per_col;
         const int y0 = 2 * by, x0 = 32 * bx;
         const int tau0 = seg * a.seg_len, tau1 = tau0 + a.seg_len < a.D ? tau0 + a.seg_len : a.D;
-        const bool interior = y0 >= 1 && y0 + 2 < a.H && x0 >= 1 && x0 + 32 < a.W;   // uniform
-        // origins of the regions in slice 0 of this volume; never dereferenced outside the tensors
-        const float* const ox = a.a + (((vol * a.D) * a.H + y0 - 1) * a.W + x0 - 1) * a.Ci + ci0;
-        const float* const og = a.g + (((vol * a.D) * a.H + y0) * a.W + x0) * a.Co + co0;
+        slots_of_run(y0, x0);
         const long long px_plane = (long long)a.H * a.W;
+        const float* const vx = a.a + (vol * a.D) * px_plane * a.Ci;   // slice 0 of this volume
+        const float* const vg = a.g + (vol * a.D) * px_plane * a.Co;
         auto load_x = [&](int tau, float* dst) {
-            fill(ox + tau * px_plane * a.Ci, tau >= 0 && tau < a.D, interior, y0 - 1, x0 - 1, std::integral_constant<int, 0>{},
+            fill(tau >= 0 && tau < a.D ? vx + tau * px_plane * a.Ci : nullptr, a.Ci, std::integral_constant<int, 0>{},
                  std::integral_constant<int, k3XLoads>{}, dst);
         };
         auto load_g = [&](int tau, float* dst) {
-            fill(og + tau * px_plane * a.Co, tau >= 0 && tau < a.D, interior, y0, x0, std::integral_constant<int, 5>{},
+            fill(tau >= 0 && tau < a.D ? vg + tau * px_plane * a.Co : nullptr, a.Co, std::integral_constant<int, 5>{},
                  std::integral_constant<int, k3GLoads>{}, dst);
         };
         // the previous chunk ended with a barrier: all buffers are free
@@ -664,7 +656,7 @@ __global__ __launch_bounds__(256) void wgrad_wino3_finish_kernel(const float* __
 
 bool wgrad_wino3_applies(const PixDims& d, int Ci, int Co) {
     return d.kt == 1 && d.kd == 3 && d.kh == 3 && d.kw == 3 && Ci % 32 == 0 && Co % 32 == 0 &&
-           (3LL * d.W + 40) * (Ci > Co ? Ci : Co) / 4 < (1LL << 24);   // slot offsets within four image rows: 24 bits of quads
+           (double)d.H * d.W * (Ci > Co ? Ci : Co) * 4.0 < 2.0e9;   // byte offsets inside a slice: 31 bits
 }
 
 // Workgroups along x and the run of slices one of them walks per column: the choice that minimises
