@@ -432,16 +432,23 @@ __global__ __launch_bounds__(512) void wgrad_wino_kernel(WinoWgradArgs a) {
                 }
             }
         } else {
+            // a chunk at the image border: through buffer resources that span the image, with an offset outside of it for
+            // the lanes whose pixel lies outside - those arrive as zeros with the data (LDS stores of zeros into the
+            // buffer would have to wait for the direct loads in flight into it)
+            const long long img_px = (long long)a.H * a.W;
+            const __amdgpu_buffer_rsrc_t r_d = __builtin_amdgcn_make_buffer_rsrc((void*)(a.a + img * img_px * a.Ci), 0, (unsigned)(img_px * a.Ci * 4), 0x00020000);
+            const __amdgpu_buffer_rsrc_t r_g = __builtin_amdgcn_make_buffer_rsrc((void*)(a.g + img * img_px * a.Co), 0, (unsigned)(img_px * a.Co * 4), 0x00020000);
+            const unsigned od_off = (unsigned)((((y0 - 1) * a.W + x0 - 1) * a.Ci + ci0) * 4);   // (wraps for the row above the image)
+            const unsigned og_off = (unsigned)(((y0 * a.W + x0) * a.Co + co0) * 4);
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
                 const int o = wave + 8 * i;
                 if (o < kGWaveLoads) {
                     const int yy = y0 - 1 + (s_rc[i] >> 8), xx = x0 - 1 + (s_rc[i] & 255);
                     const bool ok = yy >= 0 && yy < a.H && xx >= 0 && xx < a.W;
-                    // lanes whose pixel lies outside the image store zeros themselves (a direct load writes lane l's
-                    // 16 bytes at the wave's base + 16*l, masked-off lanes write nothing)
-                    if (ok) dma16(reinterpret_cast<const float*>(reinterpret_cast<const char*>(is_g(i) ? og : od) + s_off[i]), dst + o * 256);
-                    else *reinterpret_cast<float4*>(dst + o * 256 + lane * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                    const bool g = i > 4 || (i == 4 && wave >= 2);   // uniform: slot 4 is an input slot for tid < 128
+                    const unsigned voff = ok ? (g ? og_off : od_off) + s_off[i] : 0x80000000u;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(g ? r_g : r_d, (__attribute__((address_space(3))) void*)(dst + o * 256), 16, voff, 0, 0, 0);
                 }
             }
         }
@@ -600,7 +607,8 @@ __global__ __launch_bounds__(256) void wgrad_wino_finish_kernel(const float* __r
 
 bool wgrad_wino_applies(const PixDims& d, int Ci, int Co) {
     return d.kt == 1 && d.kd == 1 && d.kh == 3 && d.kw == 3 && Ci % 64 == 0 && Co % 64 == 0 &&
-           4.0 * d.W * (Ci > Co ? Ci : Co) < 5.0e8;   // 32-bit lane byte offsets within four image rows
+           4.0 * d.W * (Ci > Co ? Ci : Co) < 5.0e8 &&   // 32-bit lane byte offsets within four image rows
+           4.0 * d.H * d.W * (Ci > Co ? Ci : Co) < 2.0e9;   // ... and within an image (chunks at the border)
 }
 
 size_t wgrad_wino_partial_floats(int Ci, int Co, int n_split) { return (size_t)(n_split + 1) * 16 * Ci * Co; }
