@@ -56,27 +56,24 @@ __global__ __launch_bounds__(256, 3) void wgrad_time_kernel(TimeWgradArgs a) {
     }
 
     // Direct loads: slot s = tid + 256*i (16 bytes at float offset 4*s) holds channel quad (s & 15) ^ 8*(p & 1) of
-    // pixel p = s >> 4.  Lanes past the end of the frame, and every lane when the frame does not exist, store zeros
-    // themselves (a direct load writes lane l's 16 bytes at the wave's base + 16*l; masked-off lanes write nothing);
-    // the zero stores come before the loads, because a store into a buffer waits for loads in flight into it.
-    int s_px[2];
-    unsigned s_qd[2];
+    // pixel p = s >> 4.  They go through a buffer resource that spans one frame of the tensor: pixels past the end of
+    // the frame arrive as zeros with the data, and a frame that does not exist gets a resource of size 0 (no bounds
+    // checks, no LDS stores of zeros, which would have to wait for the direct loads in flight into the buffer).
+    unsigned s_slot[2];   // pixel and channel quad of the slot
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int s = tid + 256 * i;
-        s_px[i] = s >> 4;
-        s_qd[i] = (unsigned)((s & 15) ^ (8 * ((s >> 4) & 1)));
+        s_slot[i] = (unsigned)(((s >> 4) << 4) | ((s & 15) ^ (8 * ((s >> 4) & 1))));
     }
-    auto fill = [&](const float* origin, bool frame_ok, int n_px, int C, float* dst) {
-        bool ok[2];
+    // frame: first element of the frame's channel block (or null), C channels per pixel, p0 first pixel of the segment
+    auto fill = [&](const float* frame, long long p0, int C, float* dst) {
+        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)(frame ? frame : a.a), 0,
+                                                                           frame ? (unsigned)(a.P * C * 4) : 0u, 0x00020000);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            ok[i] = frame_ok && s_px[i] < n_px;
-            if (!ok[i]) *reinterpret_cast<float4*>(dst + (wave + 4 * i) * 256 + lane * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            const unsigned voff = (((unsigned)p0 + (s_slot[i] >> 4)) * (unsigned)C + 4u * (s_slot[i] & 15u)) * 4u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(dst + (wave + 4 * i) * 256), 16, voff, 0, 0, 0);
         }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            if (ok[i]) dma16(origin + (size_t)s_px[i] * C + 4 * s_qd[i], dst + (wave + 4 * i) * 256);
     };
 
     // LDS float offsets of this lane's operands at contraction step k (pixels 2k, 2k + 1): + 128*k
@@ -107,12 +104,11 @@ __global__ __launch_bounds__(256, 3) void wgrad_time_kernel(TimeWgradArgs a) {
     for (long long item = xr.first; item < xr.end; item += xr.stride) {
         const long long seg = item % a.segs, vol = item / a.segs;   // segment of the frame, sample
         const long long p0 = seg * kTPix;
-        const int n_px = a.P - p0 < kTPix ? (int)(a.P - p0) : kTPix;
-        // origins of the segment in frame 0 of this sample; only ever dereferenced for frames 0 .. T-1
-        const float* const ox = a.a + ((vol * a.T) * a.P + p0) * a.Ci + ci0;
-        const float* const og = a.g + ((vol * a.T) * a.P + p0) * a.Co + co0;
-        auto load_x = [&](int tau, float* dst) { fill(ox + (long long)tau * a.P * a.Ci, tau >= 0 && tau < a.T, n_px, a.Ci, dst); };
-        auto load_g = [&](int tau, float* dst) { fill(og + (long long)tau * a.P * a.Co, tau >= 0 && tau < a.T, n_px, a.Co, dst); };
+        // frame 0 of this sample, at the workgroup's channel block
+        const float* const ox = a.a + ((vol * a.T) * a.P) * a.Ci + ci0;
+        const float* const og = a.g + ((vol * a.T) * a.P) * a.Co + co0;
+        auto load_x = [&](int tau, float* dst) { fill(tau >= 0 && tau < a.T ? ox + (long long)tau * a.P * a.Ci : nullptr, p0, a.Ci, dst); };
+        auto load_g = [&](int tau, float* dst) { fill(tau >= 0 && tau < a.T ? og + (long long)tau * a.P * a.Co : nullptr, p0, a.Co, dst); };
         // the previous chunk ended with a barrier: all buffers are free
         load_x(0, X0);
         load_g(1, G0);
@@ -161,7 +157,9 @@ __global__ __launch_bounds__(256, 3) void wgrad_time_kernel(TimeWgradArgs a) {
 }
 
 bool wgrad_time_applies(const PixDims& d, int Ci, int Co) {
-    return d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1 && Ci % 64 == 0 && Co % 64 == 0;
+    const double P = (double)d.D * d.H * d.W;
+    // byte offsets inside a frame are 32 bits in the kernel
+    return d.kt == 3 && d.kd == 1 && d.kh == 1 && d.kw == 1 && Ci % 64 == 0 && Co % 64 == 0 && (P + kTPix) * (Ci > Co ? Ci : Co) * 4.0 < 4.0e9;
 }
 
 int wgrad_time_splits(const PixDims& d) {
